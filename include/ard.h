@@ -1,0 +1,247 @@
+/*
+ * libard -- training matrix multiplications under Approximate Random Dropout,
+ * hand-written HIP for AMD MI355X (gfx950), behind a plain C ABI.
+ *
+ * Conventions shared by every entry point
+ *  - Pointers named d_* and every tensor argument (X, W, Y, dY, ...) are DEVICE
+ *    pointers owned by the caller; the library never frees or keeps them.
+ *    Pointers without that prefix (pattern structs, host tables, out scalars) are
+ *    HOST pointers read or written before the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *    entry points only enqueue work on it and return; they never synchronise.
+ *  - `ws` is a caller-provided device workspace of `ws_bytes` bytes, at least what
+ *    the matching *_workspace_bytes() call returns (may be NULL when that is 0).
+ *    The library allocates no device memory.
+ *  - Matrices are row-major and dense (leading dimension = number of columns).
+ *    X[B x I] activations, W[O x I] weights (row o = output neuron o of the layer),
+ *    Y[B x O] = X . W^T.  dtype ARD_F32 = float, ARD_BF16 = bfloat16 bit patterns;
+ *    products always accumulate in fp32; outputs have the input dtype unless stated.
+ *  - Every element of an output tensor is written: kept positions get the value,
+ *    dropped positions get exactly +0.0 (or beta * old value where beta is given).
+ *  - Return value: ARD_OK or a negative ard_status.  All argument checks happen on
+ *    the host before anything is enqueued; ard_last_error() gives the message.
+ *    Nothing throws or aborts across this boundary.
+ *  - Same inputs give bit-identical outputs (no floating-point atomics).
+ */
+#ifndef ARD_H
+#define ARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ARD_OK = 0,
+  ARD_EINVAL = -1,       /* bad pattern parameters, null pointer, bad flag        */
+  ARD_ESHAPE = -2,       /* non-positive or inconsistent sizes                    */
+  ARD_EDTYPE = -3,       /* unknown dtype                                         */
+  ARD_EWORKSPACE = -4,   /* workspace missing or too small                        */
+  ARD_EHIP = -5,         /* the HIP runtime reported an error on launch           */
+  ARD_EUNSUPPORTED = -6  /* valid request this build does not implement           */
+} ard_status;
+
+typedef enum { ARD_F32 = 0, ARD_BF16 = 1 } ard_dtype;
+
+typedef enum {
+  ARD_PAT_NONE = 0,  /* nothing dropped                                              */
+  ARD_PAT_ROW = 1,   /* row-based pattern (Section 3.1, Eq. 1): parameters dp, b     */
+  ARD_PAT_TILE = 2,  /* tile-based pattern (Section 3.2): dp, b, tile_r x tile_c     */
+  ARD_PAT_LIST = 3   /* explicit ascending device list of kept units (d_keep, count) */
+} ard_pat_kind;
+
+/*
+ * A dropout pattern.  dp is the period and b the bias in the paper's 1-based
+ * convention, b in {1..dp}: the unit with 1-based index i is dropped iff
+ * (i - b) mod dp != 0, so dp=3, b=1 keeps units 1, 4, 7, ... (Section 3.1).
+ * ROW: units are the neurons of one layer (rows of W for an output pattern,
+ * columns of W for an input pattern); dp <= number of units.
+ * TILE: units are the tile_r x tile_c tiles of W[O x I] numbered row-major over
+ * the tile grid ceil(O/tile_r) x ceil(I/tile_c), edge tiles clipped (Section 3.2);
+ * dp <= number of tiles.
+ * LIST: d_keep holds `count` strictly ascending unit indices (device memory).
+ * The d_* fields below d_keep are optional for TILE: the outputs of a previous
+ * ard_pattern_gen() call for the same pattern; when NULL the GEMM entry points
+ * regenerate them in their workspace.
+ */
+typedef struct {
+  int32_t kind;            /* ard_pat_kind                                   */
+  int32_t dp, b;           /* ROW, TILE                                      */
+  int32_t tile_r, tile_c;  /* TILE                                           */
+  int32_t count;           /* LIST: number of kept units                     */
+  const int32_t* d_keep;   /* LIST: kept units; TILE (optional): kept tiles  */
+  const uint8_t* d_mask;   /* TILE (optional): tile mask, 1 = kept           */
+  const int32_t* d_rowptr; /* TILE (optional): CSR offsets into d_keep       */
+  const int32_t* d_colptr; /* TILE (optional): CSC offsets into d_csc_rows   */
+  const int32_t* d_csc_rows; /* TILE (optional): kept tile rows per column   */
+} ard_pattern;
+
+/* ---- pattern distribution and sampling (host only) ---------------------- */
+
+/*
+ * Search for the pattern distribution K (Section 3.3): v in R^n, d = softmax(v),
+ * loss = (d . p_u - p)^2 + 1e-3 * sum d ln d with p_u[i] = (i-1)/i, descent on v
+ * from v = 0 (perturbed deterministically when seed != 0) until the loss stops
+ * moving.  Writes k_out[n] (doubles summing to 1) and cdf_out[n], the 2^32
+ * fixed-point cumulative table round(2^32 * sum_{j<=i} k_j) with cdf_out[n-1] = 2^32.
+ * Both are host arrays.  Needs 0 <= p < 1, 1 <= n <= 4096.
+ */
+int32_t ard_search_k(double p, int32_t n, uint64_t seed, double* k_out, uint64_t* cdf_out);
+
+/*
+ * Pattern of one iteration (Section 3.4): dp drawn from K, then b uniform in
+ * {1..dp}.  Stateless and integer-only: two 32-bit words r1, r2 come from the
+ * SplitMix64 finaliser chained over (seed, iter, stream_id);
+ * dp = 1 + min{i : r1 < cdf[i]}, b = 1 + ((r2 * dp) >> 32).  cdf is the host table
+ * from ard_search_k.  Writes the two host ints.
+ */
+int32_t ard_pattern_sample(const uint64_t* cdf, int32_t n, uint64_t seed, uint64_t iter,
+                           uint32_t stream_id, int32_t* dp_out, int32_t* b_out);
+
+/* ---- pattern generation on the device (Sections 3.1, 3.2, 6) ------------ */
+
+/*
+ * Binary mask (uint8, 1 = kept, Section 6) and compacted ascending list of the
+ * kept units of a ROW or TILE pattern.
+ * ROW : units = `rows` neurons (`cols` ignored).  d_mask[rows], d_keep[>= kept],
+ *       d_count[1].  d_rowptr, d_colptr, d_csc_rows must be NULL.
+ * TILE: W is rows x cols (= O x I); TR = ceil(rows/tile_r), TC = ceil(cols/tile_c).
+ *       d_mask[TR*TC] row-major, d_keep[>= kept] linear tile ids (ascending, which
+ *       is also CSR order: tile column = id - tile_row*TC), d_count[1],
+ *       d_rowptr[TR+1], d_colptr[TC+1], d_csc_rows[>= kept] (tile rows, grouped by
+ *       tile column, ascending inside each column).  Any output pointer may be NULL
+ *       to skip it, except that d_csc_rows needs d_colptr.
+ * Kept count is ceil((units - (b-1)) / dp) (0 if b-1 >= units).
+ */
+int32_t ard_pattern_gen(const ard_pattern* pat, int32_t rows, int32_t cols,
+                        uint8_t* d_mask, int32_t* d_keep, int32_t* d_count,
+                        int32_t* d_rowptr, int32_t* d_colptr, int32_t* d_csc_rows,
+                        void* stream);
+
+/* ---- fully connected layer under a pattern (Sections 3.1, 3.2) ---------- */
+
+/*
+ * pat_out / pat_in select what is dropped (either may be NULL = NONE):
+ *   pat_out ROW/LIST over the O output neurons, pat_in ROW/LIST over the I input
+ *   neurons (the previous layer's pattern): synapse (o,i) survives iff both do.
+ *   pat_out TILE: tile pattern on W; pat_in must then be NULL/NONE.
+ * Workspace for any of the three calls below with the same arguments.
+ */
+size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, int32_t O,
+                                const ard_pattern* pat_out, const ard_pattern* pat_in);
+
+/*
+ * Forward: Y[:, kept o] = alpha * X[:, kept i] . W[kept o, kept i]^T, optional
+ * ReLU (fuse_relu != 0); Y[:, dropped o] = 0 (Section 3.1: only the kept rows of
+ * W and the kept part of the input are fetched and multiplied, the rest of the
+ * output is zero).  TILE: Y[:, block J] = alpha * sum over kept tiles (J,k) of
+ * X[:, block k] . W[J,k]^T (Section 3.2).
+ */
+int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_t O,
+                          const void* X, const void* W, void* Y,
+                          const ard_pattern* pat_out, const ard_pattern* pat_in,
+                          float alpha, int32_t fuse_relu,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward w.r.t. the input: dX[:, kept i] = alpha * dY[:, kept o] . W[kept o, kept i];
+ * dX[:, dropped i] = 0.  If relu_src != NULL (same shape and dtype as dX: the
+ * stored activation this layer consumed), dX is additionally zeroed wherever
+ * relu_src <= 0 (ReLU backward fused).  The paper does not write the backward
+ * pass; this is the derivative of the masked forward above.
+ */
+int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O,
+                               const void* dY, const void* W, void* dX,
+                               const ard_pattern* pat_out, const ard_pattern* pat_in,
+                               float alpha, const void* relu_src,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward w.r.t. the weight: dW[kept o, kept i] = alpha * dY[:, kept o]^T . X[:, kept i]
+ * + beta * dW_old; every dropped synapse gets beta * dW_old (exactly 0 for beta = 0).
+ */
+int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O,
+                                 const void* dY, const void* X, void* dW,
+                                 const ard_pattern* pat_out, const ard_pattern* pat_in,
+                                 float alpha, float beta,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/* Standalone ReLU backward: dX = dY where Y > 0 else 0; n elements of `dtype`. */
+int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const void* Y, void* dX, void* stream);
+
+/* ---- LSTM layer under a row pattern on its hidden units (Section 7.2.3) -- */
+
+/*
+ * Fused weight W[4H x (I+H)], gate blocks of H rows in the order i, f, g, o,
+ * columns [x | h]; no bias; zero initial state.  `pat` (ROW/LIST/NONE over the H
+ * hidden units) holds for the whole sequence: a dropped unit has h = c = 0 at
+ * every step, its four gate rows and its recurrent column are never loaded.
+ * x[T,B,I] dtype; outputs h[T,B,H] dtype, c[T,B,H] fp32, gates[T,B,4H] fp32
+ * (activated i,f,g,o; entries of dropped units are 0), all fully written.
+ */
+size_t ard_lstm_workspace_bytes(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
+                                const ard_pattern* pat);
+int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
+                     const void* x, const void* W, const ard_pattern* pat,
+                     void* h, float* c, float* gates,
+                     void* ws, size_t ws_bytes, void* stream);
+/*
+ * Back-propagation through time with the same pattern.  dh[T,B,H] (dtype) is the
+ * gradient arriving on every h_t; h, c, gates are ard_lstm_fwd's outputs.
+ * Writes dx[T,B,I] (dtype) and dW[4H x (I+H)] (dtype; zero outside kept gate rows
+ * x ([x] + kept recurrent columns)).
+ */
+int32_t ard_lstm_bwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
+                     const void* x, const void* W, const ard_pattern* pat,
+                     const void* h, const float* c, const float* gates, const void* dh,
+                     void* dx, void* dW,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---- convolution with dropped input feature maps (Sections 5, 6) -------- */
+
+typedef enum {
+  ARD_CONV_SELECT = 0,    /* sensitivity score + selection -> d_mask, d_keep, d_count, d_score */
+  ARD_CONV_FWD = 1,       /* out = Y[N,Cout,Ho,Wo]                                        */
+  ARD_CONV_BWD_DATA = 2,  /* out = dA[N,C,H,W], dropped channels exactly 0               */
+  ARD_CONV_BWD_WEIGHT = 3 /* out = dWt[Cout,C,KH,KW], dropped channels exactly 0         */
+} ard_conv_mode;
+
+size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd,
+                                int32_t Cout, int32_t kh, int32_t kw, int32_t stride, int32_t pad);
+
+/*
+ * NCHW activations A[N,C,H,Wd], OIHW weights Wt[Cout,C,kh,kw], output spatial
+ * size Ho = (H + 2 pad - kh)/stride + 1 (same for Wo).
+ * SELECT (channel-level reading of the sensitivity-aware drop of Section 5):
+ *   score[c] = sum over (n,h,w) of floor(min(|A|, 2^15) * 2^24) as an exact int64
+ *   (order-independent; mean |A| = score / 2^24 / (N*H*Wd)); the floor(rate*C)
+ *   channels that come first in ascending (score, channel) order are dropped.
+ *   Writes d_mask[C] (1 = kept), d_keep[C - floor(rate*C)] ascending, d_count[1]
+ *   and, if non-NULL, d_score[C] (int64).  Needs N*H*Wd <= 2^24.
+ * FWD / BWD_DATA / BWD_WEIGHT read the kept channels from d_keep (n_keep entries,
+ *   n_keep given on the host) and never load a dropped channel:
+ *   FWD        Y  = conv(A restricted to kept channels, Wt)       needs A, Wt
+ *   BWD_DATA   dA[:, kept] = conv^T(dY, Wt), others 0              needs dYin, Wt
+ *   BWD_WEIGHT dWt[:, kept] = corr(dY, A), others 0                needs dYin, A
+ */
+int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype,
+                           int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
+                           int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                           double rate, int32_t n_keep,
+                           const void* A, const void* Wt, const void* dYin, void* out,
+                           uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* ---- misc ---------------------------------------------------------------- */
+
+/* Message of the last failing call on this thread (static storage, never NULL). */
+const char* ard_last_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t ard_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARD_H */

@@ -1,0 +1,250 @@
+"""ctypes binding of libard.so: argument marshalling only.
+
+Function names follow the C ABI (``include/ard.h``) without the ``ard_`` prefix.
+Tensors are torch CUDA tensors used purely as device memory; every computation
+runs in the library's HIP kernels.  If the library has not been built the first
+call raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libard.so")
+
+F32, BF16 = 0, 1
+PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
+CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT = 0, 1, 2, 3
+
+
+class ArdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libard error {code}: {msg}")
+        self.code = code
+
+
+class CPattern(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("dp", C.c_int32), ("b", C.c_int32),
+                ("tile_r", C.c_int32), ("tile_c", C.c_int32), ("count", C.c_int32),
+                ("d_keep", C.c_void_p), ("d_mask", C.c_void_p), ("d_rowptr", C.c_void_p),
+                ("d_colptr", C.c_void_p), ("d_csc_rows", C.c_void_p)]
+
+
+class Pattern:
+    """Host description of a dropout pattern (keeps the tensors it points to alive)."""
+
+    def __init__(self, kind=PAT_NONE, dp=1, b=1, tile_r=0, tile_c=0, keep: Optional[torch.Tensor] = None,
+                 count: Optional[int] = None, lists: Optional[dict] = None):
+        self.kind, self.dp, self.b, self.tile_r, self.tile_c = kind, dp, b, tile_r, tile_c
+        self.keep = keep
+        self.count = (0 if keep is None else int(keep.numel())) if count is None else count
+        self.lists = lists
+
+    @staticmethod
+    def row(dp, b):
+        return Pattern(PAT_ROW, dp, b)
+
+    @staticmethod
+    def tile(dp, b, tile_r, tile_c, lists=None):
+        return Pattern(PAT_TILE, dp, b, tile_r, tile_c, lists=lists)
+
+    @staticmethod
+    def list(keep: torch.Tensor, count=None):
+        assert keep.dtype == torch.int32 and keep.is_cuda
+        return Pattern(PAT_LIST, keep=keep, count=count)
+
+    def c(self) -> CPattern:
+        p = CPattern(self.kind, self.dp, self.b, self.tile_r, self.tile_c, self.count,
+                     None, None, None, None, None)
+        if self.kind == PAT_LIST and self.keep is not None:
+            p.d_keep = self.keep.data_ptr()
+        if self.kind == PAT_TILE and self.lists:
+            p.d_keep = self.lists["keep"].data_ptr()
+            p.d_mask = self.lists["mask"].data_ptr()
+            p.d_rowptr = self.lists["rowptr"].data_ptr()
+            p.d_colptr = self.lists["colptr"].data_ptr()
+            p.d_csc_rows = self.lists["csc_rows"].data_ptr()
+        return p
+
+
+_lib = None
+
+_SIGS = {
+    "ard_search_k": (C.c_int32, [C.c_double, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p]),
+    "ard_pattern_sample": (C.c_int32, [C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
+    "ard_pattern_gen": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 7),
+    "ard_gemm_workspace_bytes": (C.c_size_t, [C.c_int32] * 4 + [C.c_void_p] * 2),
+    "ard_drop_gemm_fwd": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_drop_gemm_bwd_data": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_drop_gemm_bwd_weight": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_relu_bwd": (C.c_int32, [C.c_int32, C.c_int64] + [C.c_void_p] * 4),
+    "ard_lstm_workspace_bytes": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
+    "ard_lstm_fwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
+    "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
+    "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
+    "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
+    "ard_last_error": (C.c_char_p, []),
+    "ard_version": (C.c_int32, []),
+}
+
+
+def exported_symbols():
+    """Names every build of the library must export (mirrors include/ard.h)."""
+    return sorted(_SIGS)
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2203_05705_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise ArdError(code, lib().ard_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream):
+    return (torch.cuda.current_stream() if stream is None else stream).cuda_stream
+
+
+def _pref(p: Optional[Pattern]):
+    if p is None:
+        return None, None
+    cp = p.c()
+    return cp, C.byref(cp)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor):
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t
+
+
+# ---- host-side pattern distribution and sampling -----------------------------
+
+def search_k(p: float, n: int, seed: int = 0):
+    """Returns (k: list[float], cdf: list[int]) from the library's host search."""
+    k = (C.c_double * n)()
+    cdf = (C.c_uint64 * n)()
+    _check(lib().ard_search_k(p, n, seed, k, cdf))
+    return list(k), list(cdf)
+
+
+def pattern_sample(cdf, seed: int, it: int, stream_id: int):
+    arr = (C.c_uint64 * len(cdf))(*[int(c) for c in cdf])
+    dp, b = C.c_int32(), C.c_int32()
+    _check(lib().ard_pattern_sample(arr, len(cdf), seed, it, stream_id, C.byref(dp), C.byref(b)))
+    return dp.value, b.value
+
+
+# ---- device entry points ---------------------------------------------------------
+
+def pattern_gen(pat: Pattern, rows: int, cols: int = 0, device="cuda", stream=None) -> dict:
+    """Mask, kept list, count (and tile offsets) as device tensors."""
+    cp, ref = _pref(pat)
+    if pat.kind == PAT_TILE:
+        TR, TC = -(-rows // max(pat.tile_r, 1)), -(-cols // max(pat.tile_c, 1))
+        n = max(TR * TC, 1)
+        out = dict(mask=torch.empty(n, dtype=torch.uint8, device=device),
+                   keep=torch.full((n,), -1, dtype=torch.int32, device=device),
+                   count=torch.zeros(1, dtype=torch.int32, device=device),
+                   rowptr=torch.empty(TR + 1, dtype=torch.int32, device=device),
+                   colptr=torch.empty(TC + 1, dtype=torch.int32, device=device),
+                   csc_rows=torch.full((n,), -1, dtype=torch.int32, device=device))
+        _check(lib().ard_pattern_gen(ref, rows, cols, out["mask"].data_ptr(), out["keep"].data_ptr(),
+                                     out["count"].data_ptr(), out["rowptr"].data_ptr(), out["colptr"].data_ptr(),
+                                     out["csc_rows"].data_ptr(), _stream(stream)))
+        return out
+    n = max(rows, 1)
+    out = dict(mask=torch.empty(n, dtype=torch.uint8, device=device),
+               keep=torch.full((n,), -1, dtype=torch.int32, device=device),
+               count=torch.zeros(1, dtype=torch.int32, device=device))
+    _check(lib().ard_pattern_gen(ref, rows, cols, out["mask"].data_ptr(), out["keep"].data_ptr(),
+                                 out["count"].data_ptr(), None, None, None, _stream(stream)))
+    return out
+
+
+def gemm_workspace_bytes(dtype_code, B, I, O, pat_out=None, pat_in=None) -> int:
+    _, ro = _pref(pat_out)
+    _, ri = _pref(pat_in)
+    return int(lib().ard_gemm_workspace_bytes(dtype_code, B, I, O, ro, ri))
+
+
+def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
+    if ws is not None:
+        return ws
+    return torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device)
+
+
+def drop_gemm_fwd(X, W, pat_out=None, pat_in=None, alpha=1.0, relu=False, out=None, ws=None, stream=None):
+    _dev(X), _dev(W)
+    B, I = X.shape
+    O = W.shape[0]
+    dt = _dtype_code(X)
+    Y = torch.empty((B, O), dtype=X.dtype, device=X.device) if out is None else out
+    co, ro = _pref(pat_out)
+    ci, ri = _pref(pat_in)
+    ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), X.device, ws)
+    _check(lib().ard_drop_gemm_fwd(dt, B, I, O, X.data_ptr(), W.data_ptr(), Y.data_ptr(), ro, ri,
+                                   float(alpha), int(bool(relu)), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return Y
+
+
+def drop_gemm_bwd_data(dY, W, pat_out=None, pat_in=None, alpha=1.0, relu_src=None, out=None, ws=None, stream=None):
+    _dev(dY), _dev(W)
+    B, O = dY.shape
+    I = W.shape[1]
+    dt = _dtype_code(dY)
+    dX = torch.empty((B, I), dtype=dY.dtype, device=dY.device) if out is None else out
+    co, ro = _pref(pat_out)
+    ci, ri = _pref(pat_in)
+    ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
+    _check(lib().ard_drop_gemm_bwd_data(dt, B, I, O, dY.data_ptr(), W.data_ptr(), dX.data_ptr(), ro, ri,
+                                        float(alpha), _ptr(relu_src), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return dX
+
+
+def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, out=None, ws=None, stream=None):
+    _dev(dY), _dev(X)
+    B, O = dY.shape
+    I = X.shape[1]
+    dt = _dtype_code(dY)
+    dW = torch.empty((O, I), dtype=dY.dtype, device=dY.device) if out is None else out
+    co, ro = _pref(pat_out)
+    ci, ri = _pref(pat_in)
+    ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
+    _check(lib().ard_drop_gemm_bwd_weight(dt, B, I, O, dY.data_ptr(), X.data_ptr(), dW.data_ptr(), ro, ri,
+                                          float(alpha), float(beta), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return dW
+
+
+def relu_bwd(dY, Y, out=None, stream=None):
+    _dev(dY), _dev(Y)
+    dX = torch.empty_like(dY) if out is None else out
+    _check(lib().ard_relu_bwd(_dtype_code(dY), dY.numel(), dY.data_ptr(), Y.data_ptr(), dX.data_ptr(), _stream(stream)))
+    return dX

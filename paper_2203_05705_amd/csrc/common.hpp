@@ -1,0 +1,98 @@
+// Shared host/device helpers of libard: index maps, bf16 conversion, error plumbing.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+
+#include "../../include/ard.h"
+
+namespace ard {
+
+// ---- error plumbing -------------------------------------------------------
+void set_error(const char* fmt, ...);
+int32_t fail(int32_t code, const char* fmt, ...);
+#define ARD_HIP_CHECK(expr)                                                        \
+  do {                                                                             \
+    hipError_t e__ = (expr);                                                       \
+    if (e__ != hipSuccess)                                                         \
+      return ard::fail(ARD_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+#define ARD_LAUNCH_CHECK(name)                                                     \
+  do {                                                                             \
+    hipError_t e__ = hipGetLastError();                                            \
+    if (e__ != hipSuccess)                                                         \
+      return ard::fail(ARD_EHIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
+  } while (0)
+
+// ---- index maps -------------------------------------------------------------
+// A logical (compact) index j in [0, n) maps to a physical index in [0, nphys):
+//   AFFINE  off + j*step          (row pattern: off = b-1, step = dp; identity: 0, 1)
+//   LIST    list[j]               (explicit kept-unit list)
+//   BLOCK   list[j / bs]*bs + j%bs (kept tiles: list of block ids, block size bs)
+enum { AX_AFFINE = 0, AX_LIST = 1, AX_BLOCK = 2 };
+
+struct Axis {
+  const int* list;
+  int kind;
+  int off, step;
+  int bs;
+  int n;      // logical length
+  int nphys;  // physical extent
+};
+
+static inline Axis axis_identity(int n) { return Axis{nullptr, AX_AFFINE, 0, 1, 1, n, n}; }
+static inline Axis axis_affine(int off, int step, int n, int nphys) {
+  return Axis{nullptr, AX_AFFINE, off, step, 1, n, nphys};
+}
+static inline Axis axis_list(const int* l, int n, int nphys) { return Axis{l, AX_LIST, 0, 1, 1, n, nphys}; }
+static inline Axis axis_block(const int* l, int bs, int nblocks, int nphys) {
+  return Axis{l, AX_BLOCK, 0, 1, bs, nblocks * bs, nphys};
+}
+// A run of `ce` logical elements starting at a multiple of `ce` is physically
+// contiguous and starts at a multiple of `ce`.
+static inline bool axis_chunk_contiguous(const Axis& a, int ce) {
+  if (a.kind == AX_AFFINE) return a.step == 1 && (a.off % ce) == 0;
+  if (a.kind == AX_BLOCK) return (a.bs % ce) == 0;
+  return false;
+}
+
+__device__ __forceinline__ int ax_phys(const Axis& a, int j) {
+  if (a.kind == AX_AFFINE) return a.off + j * a.step;
+  if (a.kind == AX_LIST) return a.list[j];
+  int q = j / a.bs;
+  return a.list[q] * a.bs + (j - q * a.bs);
+}
+
+// ---- bf16 -------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+  static constexpr int CE = 4;  // elements per 16-byte chunk
+  __device__ static __forceinline__ float to_f32(float v) { return v; }
+  __device__ static __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct ElemTraits<uint16_t> {
+  static constexpr int CE = 8;
+  __device__ static __forceinline__ float to_f32(uint16_t v) { return bf16_bits_to_f32(v); }
+  __device__ static __forceinline__ uint16_t from_f32(float v) { return f32_to_bf16_bits(v); }
+};
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- pattern helpers (host) ---------------------------------------------------
+int32_t check_pattern(const ard_pattern* p, int units, const char* what);
+// number of kept units of a ROW pattern (or NONE/LIST) over `units`
+int kept_count(const ard_pattern* p, int units);
+// logical->physical map of a ROW / LIST / NONE pattern over `units`
+Axis axis_of_pattern(const ard_pattern* p, int units);
+
+}  // namespace ard

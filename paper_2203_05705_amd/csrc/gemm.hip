@@ -1,0 +1,301 @@
+// Fully connected layer under a dropout pattern: forward, backward-data and
+// backward-weight entry points (Sections 3.1, 3.2), all mapped onto the gathered
+// MFMA engine.
+#include "engine.hpp"
+#include "pattern.hpp"
+
+namespace ard {
+
+template <typename T, int BM, int BN, int WGM, int WGN>
+static int32_t launch_cfg(bool a_kc, bool b_kc, GemmParams& P, hipStream_t stream) {
+  P.tiles_m = ceil_div(P.M, BM);
+  P.tiles_n = ceil_div(P.N, BN);
+  long blocks = (long)P.tiles_m * P.tiles_n;
+  if (blocks <= 0) return ARD_OK;
+  if (blocks > 0x7fffffffL) return fail(ARD_ESHAPE, "too many workgroups");
+  dim3 grid((unsigned)blocks), block(256);
+  if (a_kc && b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, true, true>), grid, block, 0, stream, P);
+  else if (a_kc && !b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, true, false>), grid, block, 0, stream, P);
+  else if (!a_kc && !b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, false, false>), grid, block, 0, stream, P);
+  else
+    return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
+  ARD_LAUNCH_CHECK("gemm_kernel");
+  return ARD_OK;
+}
+
+template <typename T>
+static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipStream_t stream) {
+  if (max_bn == 32) return launch_cfg<T, 128, 32, 4, 1>(a_kc, b_kc, P, stream);
+  if (max_bn == 64) return launch_cfg<T, 128, 64, 2, 2>(a_kc, b_kc, P, stream);
+  long t128 = (long)ceil_div(P.M, 128) * ceil_div(P.N, 128);
+  if (t128 >= 192) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
+  return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
+}
+
+int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int /*max_bm*/, hipStream_t stream) {
+  if (dtype == ARD_BF16) return run_gemm_t<uint16_t>(a_kc, b_kc, P, max_bn, stream);
+  if (dtype == ARD_F32) return run_gemm_t<float>(a_kc, b_kc, P, max_bn, stream);
+  return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+}
+
+static int elem_size(int32_t dtype) { return dtype == ARD_BF16 ? 2 : 4; }
+static int chunk_elems(int32_t dtype) { return 16 / elem_size(dtype); }
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+int32_t fill_matrix(int32_t dtype, void* p, long n, float beta, hipStream_t stream) {
+  if (n <= 0 || beta == 1.0f) return ARD_OK;
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == ARD_BF16)
+    hipLaunchKernelGGL(scale_fill_kernel<uint16_t>, grid, block, 0, stream, (uint16_t*)p, n, beta);
+  else
+    hipLaunchKernelGGL(scale_fill_kernel<float>, grid, block, 0, stream, (float*)p, n, beta);
+  ARD_LAUNCH_CHECK("scale_fill_kernel");
+  return ARD_OK;
+}
+
+struct LayerArgs {
+  int32_t dtype, B, I, O;
+  const ard_pattern *po, *pi;
+  bool tile;
+  int TR, TC;
+};
+
+static int32_t check_layer(LayerArgs& a, const void* p0, const void* p1, const void* p2) {
+  if (a.dtype != ARD_F32 && a.dtype != ARD_BF16) return fail(ARD_EDTYPE, "unknown dtype %d", a.dtype);
+  if (a.B <= 0 || a.I <= 0 || a.O <= 0) return fail(ARD_ESHAPE, "B, I, O must be positive (got %d, %d, %d)", a.B, a.I, a.O);
+  if (!p0 || !p1 || !p2) return fail(ARD_EINVAL, "null tensor pointer");
+  a.tile = a.po && a.po->kind == ARD_PAT_TILE;
+  if (a.pi && a.pi->kind == ARD_PAT_TILE) return fail(ARD_EINVAL, "a tile pattern goes in pat_out");
+  if (a.tile) {
+    if (a.pi && a.pi->kind != ARD_PAT_NONE) return fail(ARD_EINVAL, "tile pattern cannot be combined with pat_in");
+    if (a.po->tile_r <= 0 || a.po->tile_c <= 0) return fail(ARD_EINVAL, "tile size must be positive");
+    a.TR = ceil_div(a.O, a.po->tile_r);
+    a.TC = ceil_div(a.I, a.po->tile_c);
+    int32_t st = check_pattern(a.po, a.TR * a.TC, "pat_out");
+    if (st) return st;
+    if (a.po->tile_r % 32 || a.po->tile_c % 32)
+      return fail(ARD_EUNSUPPORTED, "tile sizes must be multiples of 32 (got %d x %d)", a.po->tile_r, a.po->tile_c);
+  } else {
+    int32_t st = check_pattern(a.po, a.O, "pat_out");
+    if (st) return st;
+    st = check_pattern(a.pi, a.I, "pat_in");
+    if (st) return st;
+  }
+  return ARD_OK;
+}
+
+// Workspace layout for a tile pattern: mask | keep | count | rowptr | colptr | csc_rows
+struct TileLists {
+  const uint8_t* mask;
+  const int32_t *keep, *rowptr, *colptr, *csc_rows;
+};
+
+static size_t tile_ws_bytes(int TR, int TC) {
+  size_t n = (size_t)TR * TC;
+  return align_up(n, 256) + align_up(n * 4, 256) + 256 + align_up((size_t)(TR + 1) * 4, 256) +
+         align_up((size_t)(TC + 1) * 4, 256) + align_up(n * 4, 256);
+}
+
+static int32_t tile_lists(const LayerArgs& a, void* ws, size_t ws_bytes, hipStream_t stream, TileLists& L) {
+  const ard_pattern* p = a.po;
+  if (p->d_keep && p->d_mask && p->d_rowptr && p->d_colptr && p->d_csc_rows) {
+    L = TileLists{p->d_mask, p->d_keep, p->d_rowptr, p->d_colptr, p->d_csc_rows};
+    return ARD_OK;
+  }
+  size_t need = tile_ws_bytes(a.TR, a.TC);
+  if (!ws || ws_bytes < need) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
+  size_t n = (size_t)a.TR * a.TC;
+  char* w = (char*)ws;
+  uint8_t* mask = (uint8_t*)w;
+  w += align_up(n, 256);
+  int32_t* keep = (int32_t*)w;
+  w += align_up(n * 4, 256);
+  int32_t* count = (int32_t*)w;
+  w += 256;
+  int32_t* rowptr = (int32_t*)w;
+  w += align_up((size_t)(a.TR + 1) * 4, 256);
+  int32_t* colptr = (int32_t*)w;
+  w += align_up((size_t)(a.TC + 1) * 4, 256);
+  int32_t* csc = (int32_t*)w;
+  int32_t st = pattern_gen_launch(p, a.O, a.I, mask, keep, count, rowptr, colptr, csc, stream);
+  if (st) return st;
+  L = TileLists{mask, keep, rowptr, colptr, csc};
+  return ARD_OK;
+}
+
+static int pick_bn(int t) { return t % 128 == 0 ? 128 : (t % 64 == 0 ? 64 : 32); }
+
+}  // namespace ard
+
+using namespace ard;
+
+extern "C" size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, int32_t O, const ard_pattern* pat_out,
+                                           const ard_pattern* pat_in) {
+  (void)dtype;
+  (void)B;
+  (void)pat_in;
+  if (pat_out && pat_out->kind == ARD_PAT_TILE && pat_out->tile_r > 0 && pat_out->tile_c > 0 && I > 0 && O > 0)
+    return tile_ws_bytes(ceil_div(O, pat_out->tile_r), ceil_div(I, pat_out->tile_c));
+  return 0;
+}
+
+extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* X, const void* W,
+                                     void* Y, const ard_pattern* pat_out, const ard_pattern* pat_in, float alpha,
+                                     int32_t fuse_relu, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
+  int32_t st = check_layer(a, X, W, Y);
+  if (st) return st;
+  const int ce = chunk_elems(dtype);
+  GemmParams P{};
+  P.A.p = X;
+  P.A.ld = I;
+  P.A.r = axis_identity(B);
+  P.B.p = W;
+  P.B.ld = I;
+  int max_bn = 0;
+  if (a.tile) {
+    TileLists L;
+    st = tile_lists(a, ws, ws_bytes, stream, L);
+    if (st) return st;
+    P.B.r = axis_identity(O);
+    P.k = axis_block(L.keep, pat_out->tile_c, 0, I);
+    P.kb_ptr = L.rowptr;
+    P.kb_ncols = pat_out->tile_r;
+    P.kb_bias = -a.TC;
+    P.C.cn = axis_identity(O);
+    max_bn = pick_bn(pat_out->tile_r);
+  } else {
+    P.B.r = axis_of_pattern(pat_out, O);
+    P.k = axis_of_pattern(pat_in, I);
+    P.C.cn = P.B.r;
+  }
+  bool kvec = axis_chunk_contiguous(P.k, ce) && (I % ce) == 0;
+  P.A.vec = kvec && aligned16(X);
+  P.B.vec = kvec && aligned16(W);
+  P.C.p = Y;
+  P.C.ld = O;
+  P.C.rm = axis_identity(B);
+  P.C.fill = 1;
+  P.C.relu = fuse_relu != 0;
+  P.C.alpha = alpha;
+  P.C.beta = 0.0f;
+  P.M = B;
+  P.N = P.B.r.n;
+  if (P.N == 0) return fill_matrix(dtype, Y, (long)B * O, 0.0f, stream);
+  return run_gemm(dtype, true, true, P, max_bn, 0, stream);
+}
+
+extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY, const void* W,
+                                          void* dX, const ard_pattern* pat_out, const ard_pattern* pat_in, float alpha,
+                                          const void* relu_src, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
+  int32_t st = check_layer(a, dY, W, dX);
+  if (st) return st;
+  const int ce = chunk_elems(dtype);
+  GemmParams P{};
+  P.A.p = dY;
+  P.A.ld = O;
+  P.A.r = axis_identity(B);
+  P.B.p = W;  // element (n = input neuron, k = output neuron) at W[k*I + n]
+  P.B.ld = I;
+  int max_bn = 0;
+  if (a.tile) {
+    TileLists L;
+    st = tile_lists(a, ws, ws_bytes, stream, L);
+    if (st) return st;
+    P.B.r = axis_identity(I);
+    P.k = axis_block(L.csc_rows, pat_out->tile_r, 0, O);
+    P.kb_ptr = L.colptr;
+    P.kb_ncols = pat_out->tile_c;
+    P.kb_bias = 0;
+    max_bn = pick_bn(pat_out->tile_c);
+  } else {
+    P.B.r = axis_of_pattern(pat_in, I);
+    P.k = axis_of_pattern(pat_out, O);
+  }
+  P.A.vec = axis_chunk_contiguous(P.k, ce) && (O % ce) == 0 && aligned16(dY);
+  P.B.vec = 0;
+  P.C.p = dX;
+  P.C.relu_src = relu_src;
+  P.C.ld = I;
+  P.C.rm = axis_identity(B);
+  P.C.cn = P.B.r;
+  P.C.fill = 1;
+  P.C.alpha = alpha;
+  P.M = B;
+  P.N = P.B.r.n;
+  if (P.N == 0) return fill_matrix(dtype, dX, (long)B * I, 0.0f, stream);
+  return run_gemm(dtype, true, false, P, max_bn, 0, stream);
+}
+
+extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY,
+                                            const void* X, void* dW, const ard_pattern* pat_out,
+                                            const ard_pattern* pat_in, float alpha, float beta, void* ws,
+                                            size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
+  int32_t st = check_layer(a, dY, X, dW);
+  if (st) return st;
+  GemmParams P{};
+  P.A.p = dY;  // element (m = output neuron, k = batch row) at dY[k*O + m]
+  P.A.ld = O;
+  P.B.p = X;   // element (n = input neuron, k = batch row) at X[k*I + n]
+  P.B.ld = I;
+  P.k = axis_identity(B);
+  if (a.tile) {
+    TileLists L;
+    st = tile_lists(a, ws, ws_bytes, stream, L);
+    if (st) return st;
+    P.A.r = axis_identity(O);
+    P.B.r = axis_identity(I);
+    P.tmask = L.mask;
+    P.tm_r = pat_out->tile_r;
+    P.tm_c = pat_out->tile_c;
+    P.tm_tc = a.TC;
+  } else {
+    P.A.r = axis_of_pattern(pat_out, O);
+    P.B.r = axis_of_pattern(pat_in, I);
+  }
+  P.C.p = dW;
+  P.C.ld = I;
+  P.C.rm = P.A.r;
+  P.C.cn = P.B.r;
+  P.C.fill = 1;
+  P.C.alpha = alpha;
+  P.C.beta = beta;
+  P.M = P.A.r.n;
+  P.N = P.B.r.n;
+  if (P.M == 0 || P.N == 0) return fill_matrix(dtype, dW, (long)O * I, beta, stream);
+  return run_gemm(dtype, false, false, P, 0, 0, stream);
+}
+
+namespace ard {
+template <typename T>
+__global__ void relu_bwd_kernel(const T* dY, const T* Y, T* dX, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dX[i] = ElemTraits<T>::to_f32(Y[i]) > 0.0f ? dY[i] : ElemTraits<T>::from_f32(0.0f);
+}
+}  // namespace ard
+
+extern "C" int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const void* Y, void* dX, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (n < 0) return fail(ARD_ESHAPE, "negative length");
+  if (n == 0) return ARD_OK;
+  if (!dY || !Y || !dX) return fail(ARD_EINVAL, "null tensor pointer");
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == ARD_BF16)
+    hipLaunchKernelGGL(relu_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)dY, (const uint16_t*)Y,
+                       (uint16_t*)dX, (long)n);
+  else if (dtype == ARD_F32)
+    hipLaunchKernelGGL(relu_bwd_kernel<float>, grid, block, 0, stream, (const float*)dY, (const float*)Y, (float*)dX,
+                       (long)n);
+  else
+    return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+  ARD_LAUNCH_CHECK("relu_bwd_kernel");
+  return ARD_OK;
+}
