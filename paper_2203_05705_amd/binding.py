@@ -145,6 +145,16 @@ def _dev(t: torch.Tensor):
     return t
 
 
+def to_device(a, device="cuda") -> torch.Tensor:
+    """Host array -> device tensor with the bytes unchanged: uint16 arrays are bf16 bit
+    patterns, float32 stays float32, integer arrays keep their type."""
+    import numpy as np
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a.copy()).to(device)
+
+
 # ---- host-side pattern distribution and sampling -----------------------------
 
 def search_k(p: float, n: int, seed: int = 0):
