@@ -258,3 +258,110 @@ def relu_bwd(dY, Y, out=None, stream=None):
     dX = torch.empty_like(dY) if out is None else out
     _check(lib().ard_relu_bwd(_dtype_code(dY), dY.numel(), dY.data_ptr(), Y.data_ptr(), dX.data_ptr(), _stream(stream)))
     return dX
+
+
+# ---- LSTM -------------------------------------------------------------------------------
+
+def lstm_workspace_bytes(dtype_code, T, B, I, H, pat=None) -> int:
+    _, r = _pref(pat)
+    return int(lib().ard_lstm_workspace_bytes(dtype_code, T, B, I, H, r))
+
+
+def lstm_fwd(x, W, pat=None, ws=None, stream=None):
+    """x[T,B,I], W[4H, I+H] -> (h[T,B,H] dtype, c[T,B,H] fp32, gates[T,B,4H] fp32)."""
+    _dev(x), _dev(W)
+    T, B, I = x.shape
+    H = W.shape[0] // 4
+    assert W.shape == (4 * H, I + H)
+    dt = _dtype_code(x)
+    h = torch.empty((T, B, H), dtype=x.dtype, device=x.device)
+    c = torch.empty((T, B, H), dtype=torch.float32, device=x.device)
+    gates = torch.empty((T, B, 4 * H), dtype=torch.float32, device=x.device)
+    cp, r = _pref(pat)
+    ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
+    _check(lib().ard_lstm_fwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
+                              gates.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return h, c, gates
+
+
+def lstm_bwd(x, W, pat, h, c, gates, dh, ws=None, stream=None):
+    """Returns (dx[T,B,I], dW[4H, I+H]) in the storage dtype."""
+    for t in (x, W, h, c, gates, dh):
+        _dev(t)
+    T, B, I = x.shape
+    H = W.shape[0] // 4
+    dt = _dtype_code(x)
+    dx = torch.empty_like(x)
+    dW = torch.empty_like(W)
+    cp, r = _pref(pat)
+    ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
+    _check(lib().ard_lstm_bwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
+                              gates.data_ptr(), dh.data_ptr(), dx.data_ptr(), dW.data_ptr(), ws.data_ptr(),
+                              ws.numel(), _stream(stream)))
+    return dx, dW
+
+
+# ---- convolution with dropped input feature maps ---------------------------------------------
+
+def conv_workspace_bytes(dtype_code, N, C, H, W, Cout, kh, kw, stride, pad) -> int:
+    return int(lib().ard_conv_workspace_bytes(dtype_code, N, C, H, W, Cout, kh, kw, stride, pad))
+
+
+def fmap_drop_conv(mode, shape, dtype_code, Cout, ksize, stride, pad, rate=0.0, n_keep=0, A=None, Wt=None, dY=None,
+                   out=None, mask=None, keep=None, count=None, score=None, ws=None, stream=None):
+    """Raw call of ard_fmap_drop_conv; `shape` = (N, C, H, W) of the activations."""
+    N, Cc, H, W = shape
+    kh, kw = ksize
+    dev = next(t.device for t in (A, Wt, dY, out, keep) if t is not None)
+    ws = _workspace(conv_workspace_bytes(dtype_code, N, Cc, H, W, Cout, kh, kw, stride, pad), dev, ws)
+    _check(lib().ard_fmap_drop_conv(mode, dtype_code, N, Cc, H, W, Cout, kh, kw, stride, pad, float(rate), int(n_keep),
+                                    _ptr(A), _ptr(Wt), _ptr(dY), _ptr(out), _ptr(mask), _ptr(keep), _ptr(count),
+                                    _ptr(score), ws.data_ptr(), ws.numel(), _stream(stream)))
+
+
+def conv_select(A, rate, Cout=1, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None):
+    """Sensitivity scores and channel selection: dict(mask, keep, count, score)."""
+    _dev(A)
+    N, Cc, H, W = A.shape
+    out = dict(mask=torch.empty(Cc, dtype=torch.uint8, device=A.device),
+               keep=torch.full((Cc,), -1, dtype=torch.int32, device=A.device),
+               count=torch.zeros(1, dtype=torch.int32, device=A.device),
+               score=torch.empty(Cc, dtype=torch.int64, device=A.device))
+    fmap_drop_conv(CONV_SELECT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, rate=rate, A=A, mask=out["mask"],
+                   keep=out["keep"], count=out["count"], score=out["score"], ws=ws, stream=stream)
+    return out
+
+
+def _out_hw(H, W, ksize, stride, pad):
+    return (H + 2 * pad - ksize[0]) // stride + 1, (W + 2 * pad - ksize[1]) // stride + 1
+
+
+def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None):
+    _dev(A), _dev(Wt)
+    N, Cc, H, W = A.shape
+    Cout, _, kh, kw = Wt.shape
+    Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
+    Y = torch.empty((N, Cout, Ho, Wo), dtype=A.dtype, device=A.device)
+    fmap_drop_conv(CONV_FWD, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
+                   keep=keep, ws=ws, stream=stream)
+    return Y
+
+
+def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=None):
+    _dev(dY), _dev(Wt)
+    N = dY.shape[0]
+    Cout, Cc, kh, kw = Wt.shape
+    dA = torch.empty((N, Cc, in_hw[0], in_hw[1]), dtype=dY.dtype, device=dY.device)
+    fmap_drop_conv(CONV_BWD_DATA, dA.shape, _dtype_code(dY), Cout, (kh, kw), stride, pad, n_keep=n_keep, Wt=Wt, dY=dY,
+                   out=dA, keep=keep, ws=ws, stream=stream)
+    return dA
+
+
+def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None):
+    _dev(dY), _dev(A)
+    N, Cc, H, W = A.shape
+    Cout = dY.shape[1]
+    dW = torch.empty((Cout, Cc, ksize[0], ksize[1]), dtype=A.dtype, device=A.device)
+    fmap_drop_conv(CONV_BWD_WEIGHT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, n_keep=n_keep, A=A, dY=dY,
+                   out=dW, keep=keep, ws=ws, stream=stream)
+    return dW

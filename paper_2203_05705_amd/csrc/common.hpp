@@ -41,7 +41,7 @@ struct Axis {
   int nphys;  // physical extent
 };
 
-static inline Axis axis_identity(int n) { return Axis{nullptr, AX_AFFINE, 0, 1, 1, n, n}; }
+__host__ __device__ static inline Axis axis_identity(int n) { return Axis{nullptr, AX_AFFINE, 0, 1, 1, n, n}; }
 static inline Axis axis_affine(int off, int step, int n, int nphys) {
   return Axis{nullptr, AX_AFFINE, off, step, 1, n, nphys};
 }

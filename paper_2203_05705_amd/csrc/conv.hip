@@ -1,16 +1,634 @@
-// Convolution with dropped input feature maps (Sections 5, 6).
+// Convolution with dropped input feature maps (Sections 5, 6), channel-level reading:
+// one sensitivity score per input feature map, the lowest-scoring maps are dropped and
+// their activations, weights and gradients are never loaded.
+//
+// All three passes are implicit GEMMs on the MFMA engine (im2col is never materialised):
+//   FWD        Y[co, (n,oh,ow)]  = sum_{tap, c kept}  Wp[co, (tap,c)]  * A[n, c, oh*s+kh-p, ow*s+kw-p]
+//   BWD_DATA   dA[c kept, (n,y,x)] = sum_{tap, co}    Wq[c, (tap,co)]  * dY[n, co, y-kh+p, x-kw+p]
+//   BWD_WEIGHT dW[co, (c kept,tap)] = sum_{(n,oh,ow)} dY[n, co, oh, ow] * A[n, c, oh*s+kh-p, ow*s+kw-p]
+// Wp / Wq are compact repacked copies of the kept-channel weights (tiny, built per call).
 #include "engine.hpp"
 #include "pattern.hpp"
 
-using namespace ard;
+namespace ard {
 
-extern "C" size_t ard_conv_workspace_bytes(int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t,
-                                           int32_t, int32_t) {
-  return 0;
+// ---- sensitivity score and selection -------------------------------------------------------
+
+// score[c] += sum over this block's share of (n, h, w) of floor(min(|a|, 2^15) * 2^24):
+// exact integers, so the result does not depend on the order of summation.
+template <typename T>
+__global__ __launch_bounds__(256) void channel_score_kernel(const T* A, int N, int C, int HW, int n_per_block,
+                                                           unsigned long long* score) {
+  const int c = blockIdx.x;
+  const int n_begin = blockIdx.y * n_per_block;
+  const int n_end = min(N, n_begin + n_per_block);
+  unsigned long long acc = 0;
+  for (int n = n_begin; n < n_end; ++n) {
+    const T* p = A + ((long)n * C + c) * HW;
+    for (int i = threadIdx.x; i < HW; i += 256) {
+      float a = fminf(fabsf(ElemTraits<T>::to_f32(p[i])), 32768.0f);
+      acc += (unsigned long long)(a * 16777216.0f);
+    }
+  }
+  // wavefront reduction, then one integer atomic per wavefront
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+  if ((threadIdx.x & 63) == 0 && acc) atomicAdd(score + c, acc);
 }
 
-extern "C" int32_t ard_fmap_drop_conv(int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t,
-                                      int32_t, int32_t, double, int32_t, const void*, const void*, const void*, void*,
-                                      uint8_t*, int32_t*, int32_t*, int64_t*, void*, size_t, void*) {
-  return fail(ARD_EUNSUPPORTED, "ard_fmap_drop_conv is not built yet");
+__global__ void zero_u64_kernel(unsigned long long* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// Drop the n_drop channels that come first in ascending (score, index) order; write the
+// mask (1 = kept) and the ascending kept list (ballot + mbcnt compaction, one workgroup).
+__global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned long long* score, int C, int n_drop,
+                                                             uint8_t* mask, int* keep, int* count) {
+  __shared__ int wave_tot[16];
+  __shared__ int running_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) running_s = 0;
+  __syncthreads();
+  for (int base = 0; base < C; base += 1024) {
+    const int c = base + tid;
+    bool kept = false;
+    if (c < C) {
+      const unsigned long long s = score[c];
+      int rank = 0;
+      for (int o = 0; o < C; ++o) {
+        const unsigned long long so = score[o];
+        rank += (so < s || (so == s && o < c)) ? 1 : 0;
+      }
+      kept = rank >= n_drop;
+      mask[c] = kept ? 1 : 0;
+    }
+    const unsigned long long bal = __ballot(kept);
+    const int r = __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0));
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int before = running_s, total = 0;
+    for (int w = 0; w < 16; ++w) {
+      int t = wave_tot[w];
+      if (w < wave) before += t;
+      total += t;
+    }
+    if (kept) keep[before + r] = c;
+    __syncthreads();
+    if (tid == 0) running_s += total;
+    __syncthreads();
+  }
+  if (tid == 0 && count) *count = running_s;
+}
+
+// ---- weight repacking ------------------------------------------------------------------------
+
+// flip == 0: out[r = co][tap][q = kept c] = Wt[co][keep[q]][tap]            (rows = Cout, inner = Ck)
+// flip == 1: out[r = kept c][tap][q = co] = Wt[co][keep[r]][taps-1-tap]    (rows = Ck, inner = Cout)
+template <typename T>
+__global__ void pack_weights_kernel(const T* Wt, const int* keep, int C, int taps, int rows, int inner, int flip,
+                                    T* out) {
+  const long total = (long)rows * taps * inner;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int q = (int)(idx % inner);
+  const int tap = (int)((idx / inner) % taps);
+  const int r = (int)(idx / ((long)inner * taps));
+  long src = flip ? ((long)q * C + keep[r]) * taps + (taps - 1 - tap) : ((long)r * C + keep[q]) * taps + tap;
+  out[idx] = Wt[src];
+}
+
+// ---- implicit-GEMM operand loaders ---------------------------------------------------------------
+
+struct ConvGeom {
+  int N, Cin, Hin, Win;      // tensor the patches are cut from
+  int Hout, Wout;            // position grid (one GEMM column per (n, oh, ow))
+  int KH, KW, stride, pad_h, pad_w;
+  int Ck;                    // gathered channels per tap
+  const int* chan;           // channel list (NULL = identity)
+};
+
+// B operand of FWD / BWD_DATA: row = position (n, oh, ow), contraction index k = tap*Ck + cc.
+template <typename T, int ROWS>
+struct PatchLoader {
+  static constexpr int CE = ElemTraits<T>::CE;
+  static constexpr int PASSES = ROWS / 32;
+  const T* src;
+  ConvGeom g;
+  int K;
+  long ibase[PASSES];
+  int ih0[PASSES], iw0[PASSES];
+  bool rvalid[PASSES];
+  int lr[PASSES], lc[PASSES];
+
+  __device__ __forceinline__ void init(const void* p, const ConvGeom& geom, int row0, int tid) {
+    src = (const T*)p;
+    g = geom;
+    K = g.KH * g.KW * g.Ck;
+    const int hw = g.Hout * g.Wout;
+    const long ntot = (long)g.N * hw;
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      int r, c;
+      if (ROWS >= 64) {
+        constexpr int RP = ROWS >= 64 ? ROWS / 64 : 1;
+        r = (tid & 63) + 64 * (ps % RP);
+        c = (tid >> 6) + 4 * (ps / RP);
+      } else {
+        r = tid & 31;
+        c = tid >> 5;
+      }
+      lr[ps] = r;
+      lc[ps] = c;
+      const long j = (long)row0 + r;
+      rvalid[ps] = j < ntot;
+      const int n = rvalid[ps] ? (int)(j / hw) : 0;
+      const int rem = rvalid[ps] ? (int)(j - (long)n * hw) : 0;
+      const int oh = rem / g.Wout, ow = rem - oh * g.Wout;
+      ibase[ps] = (long)n * g.Cin * g.Hin * g.Win;
+      ih0[ps] = oh * g.stride - g.pad_h;
+      iw0[ps] = ow * g.stride - g.pad_w;
+    }
+  }
+
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      const int kc = k0 + lc[ps] * CE;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (rvalid[ps] && kc < K) {
+        T tmp[CE];
+        int tap = kc / g.Ck, cc = kc - tap * g.Ck;
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+          while (cc >= g.Ck) {
+            cc -= g.Ck;
+            ++tap;
+          }
+          T x = 0;
+          if (kc + e < K) {
+            const int kh = tap / g.KW, kw = tap - kh * g.KW;
+            const int ih = ih0[ps] + kh, iw = iw0[ps] + kw;
+            if (ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win) {
+              const int ch = g.chan ? g.chan[cc] : cc;
+              x = src[ibase[ps] + ((long)ch * g.Hin + ih) * g.Win + iw];
+            }
+          }
+          tmp[e] = x;
+          ++cc;
+        }
+        v = *reinterpret_cast<const uint4*>(tmp);
+      }
+      regs[ps] = v;
+    }
+  }
+
+  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc[ps]] = regs[ps];
+  }
+};
+
+struct ConvGemmParams {
+  Operand Wp;       // packed weights [M x K], contraction-contiguous
+  const void* src;  // activations (FWD) or output gradient (BWD_DATA)
+  ConvGeom g;
+  OutMat C;
+  int M, K;
+  long Ncols;
+  int tiles_n;
+};
+
+template <typename T, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void conv_gemm_kernel(const ConvGemmParams P) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+  const int tid = threadIdx.x;
+  const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
+  const int m0 = mb * BM, n0 = nb * BN;
+  bool act[TM][TN];
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int im = 0; im < TM; ++im)
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      act[im][in] = true;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
+    }
+  if (P.K > 0) {
+    TileLoader<T, BM, true> la;
+    PatchLoader<T, BN> lb;
+    la.init(P.Wp, axis_identity(P.K), m0, tid);
+    lb.init(P.src, P.g, n0, tid);
+    gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, 0, P.K, lds, acc, act);
+  }
+  gemm_epilogue<T, BM, BN, WGM, WGN>(P.C, acc, m0, n0, P.M, (int)P.Ncols);
+}
+
+// A operand of BWD_WEIGHT: row = co, contraction index k = (n, oh, ow) over dY[N, Cout, Ho, Wo].
+template <typename T, int ROWS>
+struct GradRowLoader {
+  static constexpr int CE = ElemTraits<T>::CE;
+  static constexpr int PASSES = ROWS / 32;
+  const T* src;
+  int Cout, HW, vec;
+  long K;
+  int row[PASSES];
+  bool rvalid[PASSES];
+  int lr[PASSES], lc;
+
+  __device__ __forceinline__ void init(const void* p, int cout, int hw, long k, int v, int row0, int tid) {
+    src = (const T*)p;
+    Cout = cout;
+    HW = hw;
+    K = k;
+    vec = v;
+    lc = tid & 7;
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      lr[ps] = (tid >> 3) + 32 * ps;
+      row[ps] = row0 + lr[ps];
+      rvalid[ps] = row[ps] < Cout;
+    }
+  }
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
+    const long kc = (long)k0 + lc * CE;
+    const int n = (int)(kc / HW);
+    const int p = (int)(kc - (long)n * HW);
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (rvalid[ps] && kc < K) {
+        const T* base = src + ((long)n * Cout + row[ps]) * HW;
+        if (vec && p + CE <= HW) {
+          v = *reinterpret_cast<const uint4*>(base + p);
+        } else {
+          T tmp[CE];
+          int nn = 0, pp = p;
+#pragma unroll
+          for (int e = 0; e < CE; ++e) {
+            if (pp >= HW) {
+              pp -= HW;
+              ++nn;
+            }
+            tmp[e] = (kc + e < K) ? base[(long)nn * Cout * HW + pp] : (T)0;
+            ++pp;
+          }
+          v = *reinterpret_cast<const uint4*>(tmp);
+        }
+      }
+      regs[ps] = v;
+    }
+  }
+  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc] = regs[ps];
+  }
+};
+
+// B operand of BWD_WEIGHT: row j = (kept channel, tap), contraction index k = (n, oh, ow).
+template <typename T, int ROWS>
+struct PatchColLoader {
+  static constexpr int CE = ElemTraits<T>::CE;
+  static constexpr int PASSES = ROWS / 32;
+  const T* src;
+  ConvGeom g;
+  long K;
+  long rbase[PASSES];
+  int kh[PASSES], kw[PASSES];
+  bool rvalid[PASSES];
+  int lr[PASSES], lc;
+
+  __device__ __forceinline__ void init(const void* p, const ConvGeom& geom, int row0, int tid) {
+    src = (const T*)p;
+    g = geom;
+    const int taps = g.KH * g.KW;
+    K = (long)g.N * g.Hout * g.Wout;
+    lc = tid & 7;
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      lr[ps] = (tid >> 3) + 32 * ps;
+      const int j = row0 + lr[ps];
+      rvalid[ps] = j < g.Ck * taps;
+      const int cc = rvalid[ps] ? j / taps : 0;
+      const int tap = rvalid[ps] ? j - cc * taps : 0;
+      const int ch = g.chan ? g.chan[cc] : cc;
+      rbase[ps] = (long)ch * g.Hin * g.Win;
+      kh[ps] = tap / g.KW;
+      kw[ps] = tap - kh[ps] * g.KW;
+    }
+  }
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
+    const long kc = (long)k0 + lc * CE;
+    const int hw = g.Hout * g.Wout;
+    const int n0 = (int)(kc / hw);
+    const int p0 = (int)(kc - (long)n0 * hw);
+    const int oh0 = p0 / g.Wout, ow0 = p0 - oh0 * g.Wout;
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (rvalid[ps] && kc < K) {
+        T tmp[CE];
+        int n = n0, oh = oh0, ow = ow0;
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+          if (ow >= g.Wout) {
+            ow = 0;
+            if (++oh >= g.Hout) {
+              oh = 0;
+              ++n;
+            }
+          }
+          T x = 0;
+          if (kc + e < K) {
+            const int ih = oh * g.stride - g.pad_h + kh[ps], iw = ow * g.stride - g.pad_w + kw[ps];
+            if (ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win)
+              x = src[(long)n * g.Cin * g.Hin * g.Win + rbase[ps] + (long)ih * g.Win + iw];
+          }
+          tmp[e] = x;
+          ++ow;
+        }
+        v = *reinterpret_cast<const uint4*>(tmp);
+      }
+      regs[ps] = v;
+    }
+  }
+  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc] = regs[ps];
+  }
+};
+
+struct ConvWgradParams {
+  const void* dY;
+  const void* A;
+  ConvGeom g;
+  float* part;   // [splits][Cout][Nn] fp32 partial sums
+  int Cout, Nn, dy_vec;
+  long K;
+  int k_per_split;
+  int tiles_n;
+};
+
+template <typename T, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void conv_wgrad_kernel(const ConvWgradParams P) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+  const int tid = threadIdx.x;
+  const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
+  const int m0 = mb * BM, n0 = nb * BN;
+  const int split = blockIdx.y;
+  const long kb = (long)split * P.k_per_split;
+  const long ke = kb + P.k_per_split < P.K ? kb + P.k_per_split : P.K;
+  bool act[TM][TN];
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int im = 0; im < TM; ++im)
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      act[im][in] = true;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
+    }
+  if (kb < ke) {
+    GradRowLoader<T, BM> la;
+    PatchColLoader<T, BN> lb;
+    la.init(P.dY, P.Cout, P.g.Hout * P.g.Wout, P.K, P.dy_vec, m0, tid);
+    lb.init(P.A, P.g, n0, tid);
+    gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, (int)kb, (int)ke, lds, acc, act);
+  }
+  OutMat C{};
+  C.p = P.part + (long)split * P.Cout * P.Nn;
+  C.ld = P.Nn;
+  C.rm = axis_identity(P.Cout);
+  C.cn = axis_identity(P.Nn);
+  C.out_f32 = 1;
+  C.alpha = 1.0f;
+  gemm_epilogue<T, BM, BN, WGM, WGN>(C, acc, m0, n0, P.Cout, P.Nn);
+}
+
+// dWt[co][c][tap] = rank[c] >= 0 ? sum over splits of part[s][co][rank[c]*taps + tap] : 0
+template <typename T>
+__global__ void conv_wgrad_reduce_kernel(const float* part, const int* rank, int splits, int Cout, int C, int taps,
+                                         int Nn, T* dWt) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long total = (long)Cout * C * taps;
+  if (idx >= total) return;
+  const int tap = (int)(idx % taps);
+  const int c = (int)((idx / taps) % C);
+  const int co = (int)(idx / ((long)taps * C));
+  float s = 0.0f;
+  const int r = rank[c];
+  if (r >= 0)
+    for (int sp = 0; sp < splits; ++sp) s += part[((long)sp * Cout + co) * Nn + (long)r * taps + tap];
+  dWt[idx] = ElemTraits<T>::from_f32(s);
+}
+
+__global__ void rank_from_keep_kernel(const int* keep, int n_keep, int C, int* rank) {
+  for (int c = threadIdx.x; c < C; c += blockDim.x) rank[c] = -1;
+  __syncthreads();
+  for (int j = threadIdx.x; j < n_keep; j += blockDim.x) rank[keep[j]] = j;
+}
+
+struct ConvArgs {
+  int32_t mode, dtype, N, C, H, W, Cout, kh, kw, stride, pad, n_keep, Ho, Wo, es;
+};
+
+struct ConvWs {
+  unsigned long long* score;
+  int* rank;
+  char* wp;
+  float* part;
+  size_t total;
+  int splits;
+};
+
+static int wgrad_splits(const ConvArgs& a) {
+  long tiles = (long)ceil_div(a.Cout, 128) * ceil_div(a.C * a.kh * a.kw, 128);
+  long K = (long)a.N * a.Ho * a.Wo;
+  long want = (1024 + tiles - 1) / tiles;
+  long maxs = (K + 255) / 256;
+  long s = want < maxs ? want : maxs;
+  return (int)(s < 1 ? 1 : (s > 64 ? 64 : s));
+}
+
+static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
+  ConvWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes ? bytes : 1, 256);
+    return p;
+  };
+  const size_t taps = (size_t)a.kh * a.kw;
+  w.splits = wgrad_splits(a);
+  w.score = (unsigned long long*)take((size_t)a.C * 8);
+  w.rank = (int*)take((size_t)a.C * 4);
+  w.wp = take((size_t)a.Cout * a.C * taps * a.es);
+  w.part = (float*)take((size_t)w.splits * a.Cout * a.C * taps * 4);
+  w.total = off;
+  return w;
+}
+
+static int32_t conv_check(ConvArgs& a) {
+  if (a.dtype != ARD_F32 && a.dtype != ARD_BF16) return fail(ARD_EDTYPE, "unknown dtype %d", a.dtype);
+  if (a.N <= 0 || a.C <= 0 || a.H <= 0 || a.W <= 0 || a.Cout <= 0 || a.kh <= 0 || a.kw <= 0 || a.stride <= 0 || a.pad < 0)
+    return fail(ARD_ESHAPE, "non-positive convolution size");
+  if (a.H + 2 * a.pad < a.kh || a.W + 2 * a.pad < a.kw) return fail(ARD_ESHAPE, "kernel larger than the padded input");
+  a.Ho = (a.H + 2 * a.pad - a.kh) / a.stride + 1;
+  a.Wo = (a.W + 2 * a.pad - a.kw) / a.stride + 1;
+  a.es = a.dtype == ARD_BF16 ? 2 : 4;
+  if ((long)a.N * a.H * a.W > 0x7fffff00L || (long)a.N * a.Ho * a.Wo > 0x7fffff00L || (long)a.C * a.kh * a.kw > 0x7fffff00L)
+    return fail(ARD_ESHAPE, "tensor too large for 32-bit position indices");
+  return ARD_OK;
+}
+
+static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <typename T>
+static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const void* Wt, const void* dYin, void* out,
+                        uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score, const ConvWs& w,
+                        hipStream_t stream) {
+  const int taps = a.kh * a.kw, ce = 16 / a.es;
+  if (a.mode == ARD_CONV_SELECT) {
+    if (!(rate >= 0.0 && rate <= 1.0)) return fail(ARD_EINVAL, "rate must be in [0,1] (got %g)", rate);
+    if (!A || !d_mask || !d_keep) return fail(ARD_EINVAL, "SELECT needs A, d_mask and d_keep");
+    if ((long)a.N * a.H * a.W > (1L << 24)) return fail(ARD_ESHAPE, "SELECT needs N*H*W <= 2^24");
+    unsigned long long* score = d_score ? (unsigned long long*)d_score : w.score;
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, score, a.C);
+    ARD_LAUNCH_CHECK("zero_u64_kernel");
+    int ysplit = ceil_div(2048, a.C);
+    if (ysplit > a.N) ysplit = a.N;
+    if (ysplit < 1) ysplit = 1;
+    const int n_per_block = ceil_div(a.N, ysplit);
+    hipLaunchKernelGGL(channel_score_kernel<T>, dim3(a.C, ceil_div(a.N, n_per_block)), dim3(256), 0, stream,
+                       (const T*)A, a.N, a.C, a.H * a.W, n_per_block, score);
+    ARD_LAUNCH_CHECK("channel_score_kernel");
+    const int n_drop = (int)floor(rate * (double)a.C);
+    hipLaunchKernelGGL(channel_select_kernel, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)score, a.C,
+                       n_drop, d_mask, d_keep, d_count);
+    ARD_LAUNCH_CHECK("channel_select_kernel");
+    return ARD_OK;
+  }
+  if (a.n_keep < 0 || a.n_keep > a.C) return fail(ARD_EINVAL, "n_keep=%d outside 0..%d", a.n_keep, a.C);
+  if (a.n_keep > 0 && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
+  if (!out) return fail(ARD_EINVAL, "null output pointer");
+  const int Ck = a.n_keep;
+
+  if (a.mode == ARD_CONV_FWD) {
+    if (!A || !Wt) return fail(ARD_EINVAL, "FWD needs A and Wt");
+    if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.N * a.Cout * a.Ho * a.Wo, 0.0f, stream);
+    const long total = (long)a.Cout * taps * Ck;
+    hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const T*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, 0, (T*)w.wp);
+    ARD_LAUNCH_CHECK("pack_weights_kernel");
+    ConvGemmParams P{};
+    P.K = taps * Ck;
+    P.Wp = Operand{w.wp, P.K, axis_identity(a.Cout), (P.K % ce) == 0};
+    P.src = A;
+    P.g = ConvGeom{a.N, a.C, a.H, a.W, a.Ho, a.Wo, a.kh, a.kw, a.stride, a.pad, a.pad, Ck, d_keep};
+    P.M = a.Cout;
+    P.Ncols = (long)a.N * a.Ho * a.Wo;
+    P.C.p = out;
+    P.C.rm = axis_identity(a.Cout);
+    P.C.cn = axis_identity((int)P.Ncols);
+    P.C.plane = a.Ho * a.Wo;
+    P.C.img_stride = (long)a.Cout * a.Ho * a.Wo;
+    P.C.alpha = 1.0f;
+    P.tiles_n = ceil_div((int)P.Ncols, 128);
+    long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
+    hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
+    ARD_LAUNCH_CHECK("conv_gemm_kernel");
+    return ARD_OK;
+  }
+
+  if (a.mode == ARD_CONV_BWD_DATA) {
+    if (!dYin || !Wt) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
+    if (a.stride != 1) return fail(ARD_EUNSUPPORTED, "BWD_DATA is built for stride 1 only (got %d)", a.stride);
+    if (a.kh - 1 - a.pad < 0 || a.kw - 1 - a.pad < 0) return fail(ARD_EUNSUPPORTED, "BWD_DATA needs pad <= k-1");
+    if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.N * a.C * a.H * a.W, 0.0f, stream);
+    const long total = (long)Ck * taps * a.Cout;
+    hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const T*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, 1, (T*)w.wp);
+    ARD_LAUNCH_CHECK("pack_weights_kernel");
+    ConvGemmParams P{};
+    P.K = taps * a.Cout;
+    P.Wp = Operand{w.wp, P.K, axis_identity(Ck), (P.K % ce) == 0};
+    P.src = dYin;
+    P.g = ConvGeom{a.N, a.Cout, a.Ho, a.Wo, a.H, a.W, a.kh, a.kw, 1, a.kh - 1 - a.pad, a.kw - 1 - a.pad, a.Cout, nullptr};
+    P.M = Ck;
+    P.Ncols = (long)a.N * a.H * a.W;
+    P.C.p = out;
+    P.C.rm = axis_list(d_keep, Ck, a.C);
+    P.C.cn = axis_identity((int)P.Ncols);
+    P.C.plane = a.H * a.W;
+    P.C.img_stride = (long)a.C * a.H * a.W;
+    P.C.fill = 1;
+    P.C.alpha = 1.0f;
+    P.tiles_n = ceil_div((int)P.Ncols, 128);
+    long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
+    hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
+    ARD_LAUNCH_CHECK("conv_gemm_kernel");
+    return ARD_OK;
+  }
+
+  if (a.mode == ARD_CONV_BWD_WEIGHT) {
+    if (!dYin || !A) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
+    if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.Cout * a.C * taps, 0.0f, stream);
+    hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+    ARD_LAUNCH_CHECK("rank_from_keep_kernel");
+    ConvWgradParams P{};
+    P.dY = dYin;
+    P.A = A;
+    P.g = ConvGeom{a.N, a.C, a.H, a.W, a.Ho, a.Wo, a.kh, a.kw, a.stride, a.pad, a.pad, Ck, d_keep};
+    P.part = w.part;
+    P.Cout = a.Cout;
+    P.Nn = Ck * taps;
+    P.K = (long)a.N * a.Ho * a.Wo;
+    const int hw = a.Ho * a.Wo;
+    P.dy_vec = (hw % ce) == 0 && al16c(dYin);
+    const int bk = 8 * ce;
+    int splits = w.splits;
+    long per = (P.K + splits - 1) / splits;
+    per = (per + bk - 1) / bk * bk;
+    splits = (int)((P.K + per - 1) / per);
+    P.k_per_split = (int)per;
+    P.tiles_n = ceil_div(P.Nn, 128);
+    dim3 grid((unsigned)(ceil_div(P.Cout, 128) * P.tiles_n), (unsigned)splits);
+    hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 128, 2, 2>), grid, dim3(256), 0, stream, P);
+    ARD_LAUNCH_CHECK("conv_wgrad_kernel");
+    const long total = (long)a.Cout * a.C * taps;
+    hipLaunchKernelGGL(conv_wgrad_reduce_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const float*)w.part, (const int*)w.rank, splits, a.Cout, a.C, taps, P.Nn, (T*)out);
+    ARD_LAUNCH_CHECK("conv_wgrad_reduce_kernel");
+    return ARD_OK;
+  }
+  return fail(ARD_EINVAL, "unknown conv mode %d", a.mode);
+}
+
+}  // namespace ard
+
+using namespace ard;
+
+extern "C" size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
+                                           int32_t kh, int32_t kw, int32_t stride, int32_t pad) {
+  ConvArgs a{0, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, 0, 0, 0, 0};
+  if (conv_check(a)) return 0;
+  return conv_ws_layout(nullptr, a).total;
+}
+
+extern "C" int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd,
+                                      int32_t Cout, int32_t kh, int32_t kw, int32_t stride, int32_t pad, double rate,
+                                      int32_t n_keep, const void* A, const void* Wt, const void* dYin, void* out,
+                                      uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  ConvArgs a{mode, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, n_keep, 0, 0, 0};
+  int32_t st = conv_check(a);
+  if (st) return st;
+  ConvWs w = conv_ws_layout((char*)ws, a);
+  if (!ws || ws_bytes < w.total)
+    return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
+  if (dtype == ARD_BF16)
+    return conv_run<uint16_t>(a, rate, A, Wt, dYin, out, d_mask, d_keep, d_count, d_score, w, (hipStream_t)stream);
+  return conv_run<float>(a, rate, A, Wt, dYin, out, d_mask, d_keep, d_count, d_score, w, (hipStream_t)stream);
 }

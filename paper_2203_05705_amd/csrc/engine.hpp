@@ -27,6 +27,7 @@ struct Operand {
   long ld;   // elements between consecutive physical rows of the stored matrix
   Axis r;    // map of the non-contracted axis (M for A, N for B)
   int vec;   // 16-byte chunk loads are legal (contiguity and alignment checked on the host)
+  int kdense;  // this operand is already compact along the contraction: it ignores the K map
 };
 
 struct OutMat {
@@ -34,6 +35,11 @@ struct OutMat {
   const void* relu_src;  // optional: zero the result where relu_src <= 0 (same layout/dtype as the output)
   long ld;
   Axis rm, cn;           // compact -> physical row / column of the output
+  // optional batched-plane addressing (NCHW tensors): physical column c = (image, position)
+  // with `plane` positions per image; element (r, c) lives at
+  // (c / plane) * img_stride + r * plane + c % plane.  plane == 0: plain r * ld + c.
+  int plane;
+  long img_stride;
   int out_f32;           // output is fp32 regardless of the input dtype
   int fill;              // write zeros (or beta*old) into dropped rows/columns
   int relu;
@@ -90,14 +96,16 @@ struct TileLoader {
   const T* base;
   long ld;
   int vec;
+  Axis kax;
   long roff[PASSES];
   bool rvalid[PASSES];
   int lr[PASSES], lc[PASSES];
 
-  __device__ __forceinline__ void init(const Operand& op, int row0, int tid) {
+  __device__ __forceinline__ void init(const Operand& op, const Axis& k, int row0, int tid) {
     base = (const T*)op.p;
     ld = op.ld;
     vec = op.vec;
+    kax = op.kdense ? axis_identity(k.n) : k;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       int r, c;
@@ -121,7 +129,7 @@ struct TileLoader {
     }
   }
 
-  __device__ __forceinline__ void load(const Axis& kax, int k0, uint4 (&regs)[PASSES]) const {
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int kc = k0 + lc[p] * CE;
@@ -189,21 +197,101 @@ __device__ __forceinline__ void store_out(const OutMat& C, long idx, float x, bo
     ((T*)C.p)[idx] = ElemTraits<T>::from_f32(v);
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
-  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+// Contraction loop of one workgroup tile.  LA / LB stage the A (BM rows) and B (BN rows)
+// operand tiles: load(k0, regs) fetches the 128-byte-per-row slab starting at compact
+// contraction index k0 into registers, store(tile, regs) writes it to LDS.
+template <typename T, int BM, int BN, int WGM, int WGN, class LA, class LB>
+__device__ __forceinline__ void gemm_mainloop(const LA& la, const LB& lb, int k_begin, int k_end, uint4* lds,
+                                              f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                              const bool (&act)[BM / WGM / 32][BN / WGN / 32]) {
   constexpr int CE = ElemTraits<T>::CE;
   constexpr int BK = 8 * CE;  // contraction elements per step (128 bytes per row)
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
   constexpr int PA = BM / 32, PB = BN / 32;
-
-  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
   uint4* As = lds;
   uint4* Bs = lds + BM * LDS_ROW_U4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  uint4 ra[PA], rb[PB];
+  la.load(k_begin, ra);
+  lb.load(k_begin, rb);
+  const uint4* Arow = As + (wm * WTM + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
+  const uint4* Brow = Bs + (wn * WTN + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+    la.store(As, ra);
+    lb.store(Bs, rb);
+    __syncthreads();
+    if (k0 + BK < k_end) {
+      la.load(k0 + BK, ra);
+      lb.load(k0 + BK, rb);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint4 a[TM], b[TN];
+#pragma unroll
+      for (int im = 0; im < TM; ++im) a[im] = Arow[im * 32 * LDS_ROW_U4 + 2 * q];
+#pragma unroll
+      for (int in = 0; in < TN; ++in) b[in] = Brow[in * 32 * LDS_ROW_U4 + 2 * q];
+#pragma unroll
+      for (int im = 0; im < TM; ++im)
+#pragma unroll
+        for (int in = 0; in < TN; ++in)
+          if (act[im][in]) Mma<T>::run(a[im], b[in], acc[im][in]);
+    }
+    __syncthreads();
+  }
+}
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Scatter of the accumulators: lane holds column (lane & 31) of each 32x32 tile, rows
+// 8*(v/4) + 4*(lane>>5) + v%4.  Each compact row / column also owns the dropped physical
+// rows / columns that follow it (the first one also those before it) and writes their zeros.
+template <typename T, int BM, int BN, int WGM, int WGN>
+__device__ __forceinline__ void gemm_epilogue(const OutMat& C, const f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                              int m0, int n0, int M, int N) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+#pragma unroll
+  for (int in = 0; in < TN; ++in) {
+    const int j = n0 + wn * WTN + in * 32 + (lane & 31);
+    if (j >= N) continue;
+    int clo, chi, cp;
+    own_range(C.cn, j, C.fill, clo, chi, cp);
+#pragma unroll
+    for (int im = 0; im < TM; ++im) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = m0 + wm * WTM + im * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (i >= M) continue;
+        int rlo, rhi, rp;
+        own_range(C.rm, i, C.fill, rlo, rhi, rp);
+        const float x = C.alpha * acc[im][in][v];
+        for (int c = clo; c < chi; ++c) {
+          long cbase = c, rmul = C.ld;
+          if (C.plane) {
+            int img = c / C.plane;
+            cbase = (long)img * C.img_stride + (c - img * C.plane);
+            rmul = C.plane;
+          }
+          for (int r = rlo; r < rhi; ++r) store_out<T>(C, (long)r * rmul + cbase, x, r == rp && c == cp);
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
+  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
+
+  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+
+  const int tid = threadIdx.x, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
   const int m0 = mb * BM, n0 = nb * BN;
@@ -253,60 +341,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   if (any && kax.n > 0) {
     TileLoader<T, BM, A_KC> la;
     TileLoader<T, BN, B_KC> lb;
-    la.init(P.A, m0, tid);
-    lb.init(P.B, n0, tid);
-    uint4 ra[PA], rb[PB];
-    la.load(kax, 0, ra);
-    lb.load(kax, 0, rb);
-    const uint4* Arow = As + (wm * WTM + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
-    const uint4* Brow = Bs + (wn * WTN + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
-    for (int k0 = 0; k0 < kax.n; k0 += BK) {
-      la.store(As, ra);
-      lb.store(Bs, rb);
-      __syncthreads();
-      if (k0 + BK < kax.n) {
-        la.load(kax, k0 + BK, ra);
-        lb.load(kax, k0 + BK, rb);
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        uint4 a[TM], b[TN];
-#pragma unroll
-        for (int im = 0; im < TM; ++im) a[im] = Arow[im * 32 * LDS_ROW_U4 + 2 * q];
-#pragma unroll
-        for (int in = 0; in < TN; ++in) b[in] = Brow[in * 32 * LDS_ROW_U4 + 2 * q];
-#pragma unroll
-        for (int im = 0; im < TM; ++im)
-#pragma unroll
-          for (int in = 0; in < TN; ++in)
-            if (act[im][in]) Mma<T>::run(a[im], b[in], acc[im][in]);
-      }
-      __syncthreads();
-    }
+    la.init(P.A, kax, m0, tid);
+    lb.init(P.B, kax, n0, tid);
+    gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, 0, kax.n, lds, acc, act);
   }
-
-  // epilogue: lane holds column (lane & 31) of each 32x32 tile, rows 8*(v/4) + 4*(lane>>5) + v%4
-  const OutMat& C = P.C;
-#pragma unroll
-  for (int in = 0; in < TN; ++in) {
-    const int j = n0 + wn * WTN + in * 32 + (lane & 31);
-    if (j >= P.N) continue;
-    int clo, chi, cp;
-    own_range(C.cn, j, C.fill, clo, chi, cp);
-#pragma unroll
-    for (int im = 0; im < TM; ++im) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = m0 + wm * WTM + im * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (i >= P.M) continue;
-        int rlo, rhi, rp;
-        own_range(C.rm, i, C.fill, rlo, rhi, rp);
-        const float x = C.alpha * acc[im][in][v];
-        for (int r = rlo; r < rhi; ++r)
-          for (int c = clo; c < chi; ++c) store_out<T>(C, (long)r * C.ld + c, x, r == rp && c == cp);
-      }
-    }
-  }
+  gemm_epilogue<T, BM, BN, WGM, WGN>(P.C, acc, m0, n0, P.M, P.N);
 }
 
 // Fill a dense matrix region with zeros (or scale by beta): used when a pattern keeps nothing.

@@ -1,0 +1,94 @@
+"""GPU parity: sensitivity scoring/selection and the channel-compacted convolution."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv as OC
+from paper_2203_05705_amd import binding as ard
+from paper_2203_05705_amd import workloads as WL
+from util import assert_parity, from_vals, stored, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _select_and_check(Av, Ad, rate):
+    sel = ard.conv_select(Ad, rate)
+    torch.cuda.synchronize()
+    score = OC.channel_score_fixed(Av)
+    m = OC.select_channels(score, rate)
+    assert np.array_equal(sel["score"].cpu().numpy(), score)            # exact integers
+    assert np.array_equal(sel["mask"].cpu().numpy(), m)
+    keep = np.flatnonzero(m).astype(np.int32)
+    cnt = int(sel["count"].item())
+    assert cnt == len(keep)
+    assert np.array_equal(sel["keep"].cpu().numpy()[:cnt], keep)
+    return sel, m, cnt
+
+
+def _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed, check_bwd_data=True):
+    print(f"conv case dtype={dtype} N={N} C={C} Cout={Cout} H={H} W={W} k={k} stride={stride} pad={pad} rate={rate}",
+          flush=True)
+    rng = np.random.default_rng(seed)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Wv = stored(rng.standard_normal((Cout, C, k, k)) * 0.2, dtype)
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    dYv = stored(rng.standard_normal((N, Cout, Ho, Wo)), dtype)
+    Ad, Wd, dYd = from_vals(Av, dtype), from_vals(Wv, dtype), from_vals(dYv, dtype)
+    sel, m, cnt = _select_and_check(Av, Ad, rate)
+    Y = ard.conv_fwd(Ad, Wd, sel["keep"], cnt, stride, pad)
+    assert_parity(Y, OC.conv_fwd(Av, Wv, m, stride, pad), dtype, None, "conv Y")
+    dW = ard.conv_bwd_weight(dYd, Ad, sel["keep"], cnt, (k, k), stride, pad)
+    zero_w = np.broadcast_to((m == 0)[None, :, None, None], (Cout, C, k, k))
+    assert_parity(dW, OC.conv_bwd_weight(dYv, Av, m, (k, k), stride, pad), dtype, zero_w, "conv dW")
+    if check_bwd_data:
+        dA = ard.conv_bwd_data(dYd, Wd, sel["keep"], cnt, (H, W), stride, pad)
+        zero_a = np.broadcast_to((m == 0)[None, :, None, None], (N, C, H, W))
+        assert_parity(dA, OC.conv_bwd_data(dYv, Wv, m, (H, W), stride, pad), dtype, zero_a, "conv dA")
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,rate", [
+    (2, 8, 16, 7, 7, 3, 1, 1, 0.5),
+    (3, 12, 20, 9, 6, 3, 1, 1, 0.34),       # ragged, floor(rate*C) = 4
+    (2, 16, 8, 8, 8, 1, 1, 0, 0.25),        # 1x1
+    (2, 6, 10, 11, 10, 5, 1, 2, 0.5),       # 5x5
+    (4, 32, 40, 14, 14, 3, 1, 1, 0.0),      # nothing dropped
+    (5, 24, 130, 10, 12, 3, 1, 1, 0.75),    # more than one row tile
+])
+def test_conv_parity(dtype, N, C, Cout, H, W, k, stride, pad, rate):
+    _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed=N * 1000 + C)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_conv_strided_forward_and_weight_gradient(dtype):
+    _conv_case(dtype, 2, 8, 12, 9, 9, 3, 2, 1, 0.5, seed=31, check_bwd_data=False)
+
+
+def test_select_ties_and_extremes():
+    A = torch.zeros((2, 6, 4, 4), dtype=torch.bfloat16, device="cuda")
+    A[:, 0] = 2.0
+    A[:, 2] = 1.0
+    A[:, 5] = 1.0
+    Av = A.float().cpu().numpy().astype(np.float64)
+    for rate in (0.0, 0.5, 0.67, 1.0):
+        _select_and_check(Av, A, rate)
+
+
+def test_config5_conv_layer_full_size():
+    """BASELINE config 5: N=128, C=Cout=256, 28x28, 3x3 s1 p1, bf16, drop the 50% lowest-sensitivity channels."""
+    wl = WL.conv_layer(seed=5)
+    Av, Wv, dYv = wl.values("A"), wl.values("Wt"), wl.values("dY")
+    Ad, Wd, dYd = (to_dev(wl.arrays[k], "bf16") for k in ("A", "Wt", "dY"))
+    sel, m, cnt = _select_and_check(Av, Ad, 0.5)
+    assert cnt == 128
+    print("config 5: running oracle convolutions (fp64) ...", flush=True)
+    e1 = assert_parity(ard.conv_fwd(Ad, Wd, sel["keep"], cnt), OC.conv_fwd(Av, Wv, m), "bf16", None, "Y")
+    print("config 5 fwd done", flush=True)
+    zero_a = np.broadcast_to((m == 0)[None, :, None, None], Av.shape)
+    e2 = assert_parity(ard.conv_bwd_data(dYd, Wd, sel["keep"], cnt, (28, 28)), OC.conv_bwd_data(dYv, Wv, m, (28, 28)),
+                       "bf16", zero_a, "dA")
+    print("config 5 bwd_data done", flush=True)
+    zero_w = np.broadcast_to((m == 0)[None, :, None, None], Wv.shape)
+    e3 = assert_parity(ard.conv_bwd_weight(dYd, Ad, sel["keep"], cnt), OC.conv_bwd_weight(dYv, Av, m), "bf16", zero_w, "dW")
+    print(f"config 5 max rel err: Y {e1:.2e} dA {e2:.2e} dW {e3:.2e}", flush=True)
