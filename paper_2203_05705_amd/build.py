@@ -17,7 +17,7 @@ HIPCC_FLAGS = [
     # keep hipcc from forming packed fp32 instructions (gfx950 guidance for the test machines)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
-]
+] + os.environ.get("ARD_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _hipcc() -> str:

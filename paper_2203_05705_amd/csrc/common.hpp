@@ -30,7 +30,8 @@ int32_t fail(int32_t code, const char* fmt, ...);
 //   AFFINE  off + j*step          (row pattern: off = b-1, step = dp; identity: 0, 1)
 //   LIST    list[j]               (explicit kept-unit list)
 //   BLOCK   list[j / bs]*bs + j%bs (kept tiles: list of block ids, block size bs)
-enum { AX_AFFINE = 0, AX_LIST = 1, AX_BLOCK = 2 };
+//   BAFF    (off + (j / bs)*step)*bs + j%bs   (every step-th block starting at block off)
+enum { AX_AFFINE = 0, AX_LIST = 1, AX_BLOCK = 2, AX_BAFF = 3 };
 
 struct Axis {
   const int* list;
@@ -49,11 +50,14 @@ static inline Axis axis_list(const int* l, int n, int nphys) { return Axis{l, AX
 static inline Axis axis_block(const int* l, int bs, int nblocks, int nphys) {
   return Axis{l, AX_BLOCK, 0, 1, bs, nblocks * bs, nphys};
 }
+__host__ __device__ static inline Axis axis_baff(int off, int step, int bs, int nblocks, int nphys) {
+  return Axis{nullptr, AX_BAFF, off, step, bs, nblocks * bs, nphys};
+}
 // A run of `ce` logical elements starting at a multiple of `ce` is physically
 // contiguous and starts at a multiple of `ce`.
 static inline bool axis_chunk_contiguous(const Axis& a, int ce) {
   if (a.kind == AX_AFFINE) return a.step == 1 && (a.off % ce) == 0;
-  if (a.kind == AX_BLOCK) return (a.bs % ce) == 0;
+  if (a.kind == AX_BLOCK || a.kind == AX_BAFF) return (a.bs % ce) == 0;
   return false;
 }
 
@@ -61,6 +65,7 @@ __device__ __forceinline__ int ax_phys(const Axis& a, int j) {
   if (a.kind == AX_AFFINE) return a.off + j * a.step;
   if (a.kind == AX_LIST) return a.list[j];
   int q = j / a.bs;
+  if (a.kind == AX_BAFF) return (a.off + q * a.step) * a.bs + (j - q * a.bs);
   return a.list[q] * a.bs + (j - q * a.bs);
 }
 

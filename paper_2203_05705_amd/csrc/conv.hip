@@ -112,6 +112,7 @@ template <typename T, int ROWS>
 struct PatchLoader {
   static constexpr int CE = ElemTraits<T>::CE;
   static constexpr int PASSES = ROWS / 32;
+  static constexpr int NREG = PASSES;
   const T* src;
   ConvGeom g;
   int K;
@@ -184,7 +185,7 @@ struct PatchLoader {
 
   __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc[ps]] = regs[ps];
+    for (int ps = 0; ps < PASSES; ++ps) tile[swz(lr[ps], lc[ps])] = regs[ps];
   }
 };
 
@@ -201,7 +202,7 @@ struct ConvGemmParams {
 template <typename T, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(const ConvGemmParams P) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+  __shared__ uint4 lds[2 * (BM + BN) * LDS_ROW_U4];
   const int tid = threadIdx.x;
   const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
   const int m0 = mb * BM, n0 = nb * BN;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const ConvGemmParams P) 
       for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
     }
   if (P.K > 0) {
-    TileLoader<T, BM, true> la;
+    LoaderKC<T, BM, 256> la;
     PatchLoader<T, BN> lb;
     la.init(P.Wp, axis_identity(P.K), m0, tid);
     lb.init(P.src, P.g, n0, tid);
@@ -230,6 +231,7 @@ template <typename T, int ROWS>
 struct GradRowLoader {
   static constexpr int CE = ElemTraits<T>::CE;
   static constexpr int PASSES = ROWS / 32;
+  static constexpr int NREG = PASSES;
   const T* src;
   int Cout, HW, vec;
   long K;
@@ -282,7 +284,7 @@ struct GradRowLoader {
   }
   __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc] = regs[ps];
+    for (int ps = 0; ps < PASSES; ++ps) tile[swz(lr[ps], lc)] = regs[ps];
   }
 };
 
@@ -291,6 +293,7 @@ template <typename T, int ROWS>
 struct PatchColLoader {
   static constexpr int CE = ElemTraits<T>::CE;
   static constexpr int PASSES = ROWS / 32;
+  static constexpr int NREG = PASSES;
   const T* src;
   ConvGeom g;
   long K;
@@ -355,7 +358,7 @@ struct PatchColLoader {
   }
   __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) tile[lr[ps] * LDS_ROW_U4 + lc] = regs[ps];
+    for (int ps = 0; ps < PASSES; ++ps) tile[swz(lr[ps], lc)] = regs[ps];
   }
 };
 
@@ -373,7 +376,7 @@ struct ConvWgradParams {
 template <typename T, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(256) void conv_wgrad_kernel(const ConvWgradParams P) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+  __shared__ uint4 lds[2 * (BM + BN) * LDS_ROW_U4];
   const int tid = threadIdx.x;
   const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
   const int m0 = mb * BM, n0 = nb * BN;

@@ -9,10 +9,9 @@
 // epilogue scatters results to their physical positions and writes zeros into
 // the dropped positions it owns.
 //
-// One workgroup = 256 threads = 4 wavefronts computes a BM x BN tile with
+// One workgroup of 4 or 8 wavefronts computes a BM x BN tile with
 // 32x32 MFMA tiles (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32),
-// operands staged through LDS in rows of 128 bytes (+16 bytes of padding, which
-// makes the 16-byte fragment reads bank-conflict free).
+// operands staged through double-buffered LDS in XOR-swizzled rows of 128 bytes.
 #pragma once
 #include "common.hpp"
 
@@ -61,6 +60,14 @@ struct GemmParams {
   int tiles_m, tiles_n;
 };
 
+// Host: may this operand be fetched with 16-byte loads?  KC operands need contiguous,
+// aligned runs along the contraction axis; MC operands along their row axis.
+static inline bool operand_vec_ok(const Operand& op, bool kc, const Axis& k, int ce) {
+  if (((uintptr_t)op.p & 15) != 0 || (op.ld % ce) != 0) return false;
+  if (kc) return op.kdense ? true : axis_chunk_contiguous(k, ce);
+  return axis_chunk_contiguous(op.r, ce);
+}
+
 template <typename T> struct Mma;
 template <> struct Mma<uint16_t> {
   __device__ static __forceinline__ void run(const uint4& a, const uint4& b, f32x16_t& c) {
@@ -76,82 +83,77 @@ template <> struct Mma<float> {
   }
 };
 
-constexpr int LDS_ROW_U4 = 9;  // 128 data bytes + 16 pad bytes, in uint4 units
+// LDS operand tiles: rows of 128 bytes = 8 chunks of 16 bytes, no padding.  Chunk c of
+// row r sits at slot c ^ (r & 7) ^ ((r >> 3) & 7): the 16-byte fragment reads of 8 (and 16)
+// consecutive rows, the row-major chunk writes and the transposed 8-byte writes below all
+// spread over every bank.
+constexpr int LDS_ROW_U4 = 8;
+__device__ __forceinline__ int swz(int row, int c) { return row * 8 + (c ^ (row & 7) ^ ((row >> 3) & 7)); }
 
 __device__ __forceinline__ int ax_phys_k(const Axis& a, int j) {
   // contraction axis: BLOCK lists carry a bias in `off`
   if (a.kind == AX_AFFINE) return a.off + j * a.step;
   if (a.kind == AX_LIST) return a.list[j];
   int q = j / a.bs;
+  if (a.kind == AX_BAFF) return (a.off + q * a.step) * a.bs + (j - q * a.bs);
   return (a.list[q] + a.off) * a.bs + (j - q * a.bs);
 }
 
-// Global -> register -> LDS staging of a ROWS x 128-byte operand tile.
-// KC: the stored matrix is contraction-contiguous (element (row, k) at p[row*ld + k]).
-// otherwise the contraction index selects the stored row (element at p[k*ld + row]).
-template <typename T, int ROWS, bool KC>
-struct TileLoader {
+// Global -> register -> LDS staging of a ROWS x 128-byte operand tile by NT threads.
+// KC: the stored matrix is contraction-contiguous (element (row, k) at p[row*ld + k]); each
+// thread moves 16-byte chunks (one global_load_dwordx4 when the chunk is contiguous and
+// aligned, element loads through the index map otherwise).
+template <typename T, int ROWS, int NT>
+struct LoaderKC {
   static constexpr int CE = ElemTraits<T>::CE;
-  static constexpr int PASSES = ROWS / 32;
+  static constexpr int PASSES = ROWS * 8 / NT;
+  static constexpr int NREG = PASSES;
+  static_assert(PASSES >= 1, "tile too small for the workgroup");
   const T* base;
-  long ld;
-  int vec;
+  int vec, lc, lr0;
   Axis kax;
   long roff[PASSES];
   bool rvalid[PASSES];
-  int lr[PASSES], lc[PASSES];
 
   __device__ __forceinline__ void init(const Operand& op, const Axis& k, int row0, int tid) {
     base = (const T*)op.p;
-    ld = op.ld;
     vec = op.vec;
     kax = op.kdense ? axis_identity(k.n) : k;
+    lc = tid & 7;
+    lr0 = tid >> 3;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
-      int r, c;
-      if (KC) {
-        c = tid & 7;
-        r = (tid >> 3) + 32 * p;
-      } else if (ROWS >= 64) {
-        constexpr int RP = ROWS >= 64 ? ROWS / 64 : 1;
-        r = (tid & 63) + 64 * (p % RP);
-        c = (tid >> 6) + 4 * (p / RP);
-      } else {
-        r = tid & 31;
-        c = tid >> 5;
-      }
-      lr[p] = r;
-      lc[p] = c;
-      int j = row0 + r;
+      int j = row0 + lr0 + (NT / 8) * p;
       rvalid[p] = j < op.r.n;
       int ph = rvalid[p] ? ax_phys(op.r, j) : 0;
-      roff[p] = KC ? (long)ph * ld : (long)ph;
+      roff[p] = (long)ph * op.ld;
     }
   }
 
-  __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[NREG]) const {
+    const int kc = k0 + lc * CE;
+    const bool kin = kc < kax.n;
+    int kp = 0;
+    bool kvec = false;
+    if (kin && vec && kc + CE <= kax.n) {
+      kp = ax_phys_k(kax, kc);
+      kvec = kp + CE <= kax.nphys;
+    }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
-      const int kc = k0 + lc[p] * CE;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (rvalid[p] && kc < kax.n) {
-        bool done = false;
-        if (KC && vec && kc + CE <= kax.n) {
-          int kp = ax_phys_k(kax, kc);
-          if (kp + CE <= kax.nphys) {
-            v = *reinterpret_cast<const uint4*>(base + roff[p] + kp);
-            done = true;
-          }
-        }
-        if (!done) {
+      if (rvalid[p] && kin) {
+        if (kvec) {
+          v = *reinterpret_cast<const uint4*>(base + roff[p] + kp);
+        } else {
           T tmp[CE];
 #pragma unroll
           for (int e = 0; e < CE; ++e) {
             int k = kc + e;
             T x = 0;
             if (k < kax.n) {
-              int kp = ax_phys_k(kax, k);
-              if (kp < kax.nphys) x = KC ? base[roff[p] + kp] : base[(long)kp * ld + roff[p]];
+              int kq = ax_phys_k(kax, k);
+              if (kq < kax.nphys) x = base[roff[p] + kq];
             }
             tmp[e] = x;
           }
@@ -162,9 +164,117 @@ struct TileLoader {
     }
   }
 
-  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[PASSES]) const {
+  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[NREG]) const {
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) tile[lr[p] * LDS_ROW_U4 + lc[p]] = regs[p];
+    for (int p = 0; p < PASSES; ++p) tile[swz(lr0 + (NT / 8) * p, lc)] = regs[p];
+  }
+};
+
+// MC: the contraction index selects the stored row (element (row, k) at p[k*ld + row]).
+// A thread fetches a unit of 4 contraction rows x one 16-byte run along the tile rows,
+// transposes it in registers and writes, per tile row, the 4 contraction values (8 bytes
+// for bf16, one full chunk for fp32).  Lanes of a wavefront cover 8 adjacent runs (one
+// 128-byte line) x 8 contraction quads.
+template <typename T, int ROWS, int NT>
+struct LoaderMC {
+  static constexpr int CE = ElemTraits<T>::CE;
+  static constexpr int KU = 4;
+  static constexpr int KQ = 8 * CE / KU;          // contraction quads per step
+  static constexpr int NBT = ROWS / CE;           // 16-byte runs per tile
+  static constexpr int UNITS = KQ * NBT;
+  static constexpr int PASSES = (UNITS + NT - 1) / NT;
+  static constexpr int NREG = PASSES * KU;
+  static constexpr int NB_L = NBT < 8 ? NBT : 8;
+  static constexpr int KQ_L = 64 / NB_L;
+  static constexpr int NBG = NBT / NB_L;
+  const T* base;
+  long ld;
+  int vec;
+  Axis kax, rax;
+  int nb[PASSES], kq[PASSES], jrow[PASSES];
+  long roff[PASSES];
+  bool uvalid[PASSES], rfull[PASSES];
+
+  __device__ __forceinline__ void init(const Operand& op, const Axis& k, int row0, int tid) {
+    base = (const T*)op.p;
+    ld = op.ld;
+    vec = op.vec;
+    kax = op.kdense ? axis_identity(k.n) : k;
+    rax = op.r;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int u = tid + NT * p;
+      const int ul = u & 63, g = u >> 6;
+      nb[p] = (g % NBG) * NB_L + (ul % NB_L);
+      kq[p] = (g / NBG) * KQ_L + (ul / NB_L);
+      uvalid[p] = u < UNITS;
+      jrow[p] = row0 + nb[p] * CE;
+      rfull[p] = jrow[p] + CE <= rax.n;
+      roff[p] = (uvalid[p] && jrow[p] < rax.n) ? (long)ax_phys(rax, jrow[p]) : 0;
+    }
+  }
+
+  __device__ __forceinline__ void load(int k0, uint4 (&regs)[NREG]) const {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+#pragma unroll
+      for (int e = 0; e < KU; ++e) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        const int k = k0 + kq[p] * KU + e;
+        if (uvalid[p] && k < kax.n && jrow[p] < rax.n) {
+          const int kp = ax_phys_k(kax, k);
+          if (kp < kax.nphys) {
+            const T* rowp = base + (long)kp * ld;
+            if (vec && rfull[p]) {
+              v = *reinterpret_cast<const uint4*>(rowp + roff[p]);
+            } else {
+              T tmp[CE];
+#pragma unroll
+              for (int i = 0; i < CE; ++i) {
+                int j = jrow[p] + i;
+                tmp[i] = j < rax.n ? rowp[ax_phys(rax, j)] : (T)0;
+              }
+              v = *reinterpret_cast<const uint4*>(tmp);
+            }
+          }
+        }
+        regs[p * KU + e] = v;
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(uint4* tile, const uint4 (&regs)[NREG]) const {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      if (!uvalid[p]) continue;
+      const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&regs[p * KU + 0]);
+      const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&regs[p * KU + 1]);
+      const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&regs[p * KU + 2]);
+      const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&regs[p * KU + 3]);
+      if (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int d = i >> 1;
+          uint2 o;
+          if (i & 1) {
+            o.x = (w0[d] >> 16) | (w1[d] & 0xffff0000u);
+            o.y = (w2[d] >> 16) | (w3[d] & 0xffff0000u);
+          } else {
+            o.x = (w0[d] & 0xffffu) | (w1[d] << 16);
+            o.y = (w2[d] & 0xffffu) | (w3[d] << 16);
+          }
+          const int row = nb[p] * 8 + i;
+          uint2* dst = reinterpret_cast<uint2*>(tile + swz(row, kq[p] >> 1)) + (kq[p] & 1);
+          *dst = o;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = nb[p] * 4 + i;
+          tile[swz(row, kq[p])] = make_uint4(w0[i], w1[i], w2[i], w3[i]);
+        }
+      }
+    }
   }
 };
 
@@ -198,8 +308,10 @@ __device__ __forceinline__ void store_out(const OutMat& C, long idx, float x, bo
 }
 
 // Contraction loop of one workgroup tile.  LA / LB stage the A (BM rows) and B (BN rows)
-// operand tiles: load(k0, regs) fetches the 128-byte-per-row slab starting at compact
-// contraction index k0 into registers, store(tile, regs) writes it to LDS.
+// operand tiles: load(k0, regs) fetches the 128-byte-per-row slab that starts at compact
+// contraction index k0 into registers, store(tile, regs) writes it to LDS.  Two LDS
+// buffers: the slab of step s+1 is fetched before and written after the MFMAs of step s,
+// one barrier per step.
 template <typename T, int BM, int BN, int WGM, int WGN, class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(const LA& la, const LB& lb, int k_begin, int k_end, uint4* lds,
                                               f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
@@ -208,38 +320,57 @@ __device__ __forceinline__ void gemm_mainloop(const LA& la, const LB& lb, int k_
   constexpr int BK = 8 * CE;  // contraction elements per step (128 bytes per row)
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int PA = BM / 32, PB = BN / 32;
-  uint4* As = lds;
-  uint4* Bs = lds + BM * LDS_ROW_U4;
+  constexpr int STAGE = (BM + BN) * LDS_ROW_U4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  uint4 ra[PA], rb[PB];
+  uint4 ra[LA::NREG], rb[LB::NREG];
+  int aidx[TM], axr[TM], bidx[TN], bxr[TN];
+#pragma unroll
+  for (int im = 0; im < TM; ++im) {
+    const int row = wm * WTM + im * 32 + (lane & 31);
+    aidx[im] = row * 8;
+    axr[im] = (row & 7) ^ ((row >> 3) & 7);
+  }
+#pragma unroll
+  for (int in = 0; in < TN; ++in) {
+    const int row = wn * WTN + in * 32 + (lane & 31);
+    bidx[in] = BM * LDS_ROW_U4 + row * 8;
+    bxr[in] = (row & 7) ^ ((row >> 3) & 7);
+  }
   la.load(k_begin, ra);
   lb.load(k_begin, rb);
-  const uint4* Arow = As + (wm * WTM + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
-  const uint4* Brow = Bs + (wn * WTN + (lane & 31)) * LDS_ROW_U4 + (lane >> 5);
+  la.store(lds, ra);
+  lb.store(lds + BM * LDS_ROW_U4, rb);
+  __syncthreads();
+  int buf = 0;
   for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-    la.store(As, ra);
-    lb.store(Bs, rb);
-    __syncthreads();
-    if (k0 + BK < k_end) {
+    const bool more = k0 + BK < k_end;
+    if (more) {
       la.load(k0 + BK, ra);
       lb.load(k0 + BK, rb);
     }
+    const uint4* cur = lds + buf * STAGE;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+      const int c = 2 * q + (lane >> 5);
       uint4 a[TM], b[TN];
 #pragma unroll
-      for (int im = 0; im < TM; ++im) a[im] = Arow[im * 32 * LDS_ROW_U4 + 2 * q];
+      for (int im = 0; im < TM; ++im) a[im] = cur[aidx[im] + (c ^ axr[im])];
 #pragma unroll
-      for (int in = 0; in < TN; ++in) b[in] = Brow[in * 32 * LDS_ROW_U4 + 2 * q];
+      for (int in = 0; in < TN; ++in) b[in] = cur[bidx[in] + (c ^ bxr[in])];
 #pragma unroll
       for (int im = 0; im < TM; ++im)
 #pragma unroll
         for (int in = 0; in < TN; ++in)
           if (act[im][in]) Mma<T>::run(a[im], b[in], acc[im][in]);
     }
+    if (more) {
+      uint4* nxt = lds + (buf ^ 1) * STAGE;
+      la.store(nxt, ra);
+      lb.store(nxt + BM * LDS_ROW_U4, rb);
+    }
     __syncthreads();
+    buf ^= 1;
   }
 }
 
@@ -282,14 +413,17 @@ __device__ __forceinline__ void gemm_epilogue(const OutMat& C, const f32x16_t (&
   }
 }
 
+template <bool KC, typename T, int ROWS, int NT> struct PickLoader { typedef LoaderKC<T, ROWS, NT> type; };
+template <typename T, int ROWS, int NT> struct PickLoader<false, T, ROWS, NT> { typedef LoaderMC<T, ROWS, NT> type; };
+
 template <typename T, int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
-  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmParams P) {
+  constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
 
-  __shared__ uint4 lds[(BM + BN) * LDS_ROW_U4];
+  extern __shared__ uint4 lds[];  // 2 * (BM + BN) * LDS_ROW_U4 entries, sized at launch
 
   const int tid = threadIdx.x, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -339,8 +473,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
       for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
 
   if (any && kax.n > 0) {
-    TileLoader<T, BM, A_KC> la;
-    TileLoader<T, BN, B_KC> lb;
+    typename PickLoader<A_KC, T, BM, NT>::type la;
+    typename PickLoader<B_KC, T, BN, NT>::type lb;
     la.init(P.A, kax, m0, tid);
     lb.init(P.B, kax, n0, tid);
     gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, 0, kax.n, lds, acc, act);

@@ -1,10 +1,31 @@
 // Fully connected layer under a dropout pattern: forward, backward-data and
 // backward-weight entry points (Sections 3.1, 3.2), all mapped onto the gathered
 // MFMA engine.
+#include <stdlib.h>
+
 #include "engine.hpp"
+#include "fast.hpp"
 #include "pattern.hpp"
 
 namespace ard {
+
+// Launch with dynamic LDS; kernels above the 64 KiB default get their limit raised once.
+template <typename K>
+static int32_t launch_one(K kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const GemmParams& P) {
+  if (lds_bytes > 65536) {
+    static thread_local const void* raised[64];
+    static thread_local int n_raised = 0;
+    bool seen = false;
+    for (int i = 0; i < n_raised; ++i) seen = seen || raised[i] == (const void*)kernel;
+    if (!seen) {
+      ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+      if (n_raised < 64) raised[n_raised++] = (const void*)kernel;
+    }
+  }
+  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, P);
+  ARD_LAUNCH_CHECK("gemm_kernel");
+  return ARD_OK;
+}
 
 template <typename T, int BM, int BN, int WGM, int WGN>
 static int32_t launch_cfg(bool a_kc, bool b_kc, GemmParams& P, hipStream_t stream) {
@@ -13,21 +34,25 @@ static int32_t launch_cfg(bool a_kc, bool b_kc, GemmParams& P, hipStream_t strea
   long blocks = (long)P.tiles_m * P.tiles_n;
   if (blocks <= 0) return ARD_OK;
   if (blocks > 0x7fffffffL) return fail(ARD_ESHAPE, "too many workgroups");
-  dim3 grid((unsigned)blocks), block(256);
+  dim3 grid((unsigned)blocks), block(64 * WGM * WGN);
+  constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   if (a_kc && b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, true, true>), grid, block, 0, stream, P);
-  else if (a_kc && !b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, true, false>), grid, block, 0, stream, P);
-  else if (!a_kc && !b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, false, false>), grid, block, 0, stream, P);
-  else
-    return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
-  ARD_LAUNCH_CHECK("gemm_kernel");
-  return ARD_OK;
+    return launch_one(gemm_kernel<T, BM, BN, WGM, WGN, true, true>, grid, block, lds_bytes, stream, P);
+  if (a_kc && !b_kc)
+    return launch_one(gemm_kernel<T, BM, BN, WGM, WGN, true, false>, grid, block, lds_bytes, stream, P);
+  if (!a_kc && !b_kc)
+    return launch_one(gemm_kernel<T, BM, BN, WGM, WGN, false, false>, grid, block, lds_bytes, stream, P);
+  return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
 }
 
 template <typename T>
 static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipStream_t stream) {
+  if (const char* f = getenv("ARD_FORCE_TILE")) {  // development knob: force a workgroup tile
+    int v = atoi(f);
+    if (v == 256) return launch_cfg<T, 256, 256, 2, 4>(a_kc, b_kc, P, stream);
+    if (v == 128) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
+    if (v == 64) return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
+  }
   if (max_bn == 32) return launch_cfg<T, 128, 32, 4, 1>(a_kc, b_kc, P, stream);
   if (max_bn == 64) return launch_cfg<T, 128, 64, 2, 2>(a_kc, b_kc, P, stream);
   long t128 = (long)ceil_div(P.M, 128) * ceil_div(P.N, 128);
@@ -35,10 +60,88 @@ static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipSt
   return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
 }
 
+static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, int32_t& st);
+
 int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int /*max_bm*/, hipStream_t stream) {
+  int32_t st_fast = ARD_OK;
+  if (try_fast_plain(dtype, a_kc, b_kc, P, stream, st_fast)) return st_fast;
   if (dtype == ARD_BF16) return run_gemm_t<uint16_t>(a_kc, b_kc, P, max_bn, stream);
   if (dtype == ARD_F32) return run_gemm_t<float>(a_kc, b_kc, P, max_bn, stream);
   return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+}
+
+// ---- large-tile path -------------------------------------------------------------------
+
+static int gcd_int(int a, int b) {
+  while (b) {
+    int t = a % b;
+    a = b;
+    b = t;
+  }
+  return a;
+}
+
+static int32_t launch_fast(bool a_kc, bool b_kc, FastParams& F, hipStream_t stream) {
+  if (F.total_tiles <= 0) return ARD_OK;
+  F.tiles_per_xcd = ceil_div(F.total_tiles, 8);
+  // an XCD's share should be about square in tiles: bands of group_m tile rows
+  int gm = 1;
+  while (gm * gm * 2 <= F.tiles_per_xcd && gm < 8) gm *= 2;
+  F.group_m = gm;
+  dim3 grid((unsigned)(F.tiles_per_xcd * 8)), block(F_NT);
+  const size_t lds_bytes = (size_t)2 * (F_BM + F_BN) * LDS_ROW_U4 * sizeof(uint4);
+  auto go = [&](auto kernel) -> int32_t {
+    static thread_local bool raised = false;
+    if (!raised) {
+      ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+      raised = true;
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, F);
+    ARD_LAUNCH_CHECK("gemm256_kernel");
+    return ARD_OK;
+  };
+  if (a_kc && b_kc) return go(gemm256_kernel<true, true>);
+  if (a_kc && !b_kc) return go(gemm256_kernel<true, false>);
+  if (!a_kc && !b_kc) return go(gemm256_kernel<false, false>);
+  return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
+}
+
+static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0 && ld < (1L << 30); }
+
+// Large dense-like products: identity output maps, 16-byte loads on both operands.
+static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, int32_t& st) {
+  if (dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
+  if (!P.A.vec || !P.B.vec || P.A.kdense || P.B.kdense || P.kb_ptr || P.tmask) return false;
+  if (P.k.kind != AX_AFFINE || P.k.step != 1 || (P.k.off % 8) || (P.k.n % 8) || (P.k.nphys % 8)) return false;
+  const OutMat& C = P.C;
+  if (C.out_f32 || C.beta != 0.0f || C.relu_src || C.plane || C.fill) return false;
+  auto ident = [](const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; };
+  if (!ident(C.rm) || !ident(C.cn)) return false;
+  if (!fast_ptr_ok(P.A.p, P.A.ld) || !fast_ptr_ok(P.B.p, P.B.ld) || (C.ld % 8)) return false;
+  if (!a_kc && (P.A.r.n % 8)) return false;
+  if (!b_kc && (P.B.r.n % 8)) return false;
+  if ((long)P.A.r.nphys * P.A.ld >= (1L << 31) || (long)P.B.r.nphys * P.B.ld >= (1L << 31)) return false;
+  const long tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, F_BN);
+  if (tiles < 96) return false;
+  FastParams F{};
+  F.A = (const uint16_t*)P.A.p;
+  F.B = (const uint16_t*)P.B.p;
+  F.C = (uint16_t*)C.p;
+  F.lda = (int)P.A.ld;
+  F.ldb = (int)P.B.ld;
+  F.ldc = (int)C.ld;
+  F.am = P.A.r;
+  F.bn = P.B.r;
+  F.k = P.k;
+  F.alpha = C.alpha;
+  F.relu = C.relu;
+  F.M = P.M;
+  F.N = P.N;
+  F.tiles_m = ceil_div(P.M, F_BM);
+  F.tiles_n = ceil_div(P.N, F_BN);
+  F.total_tiles = (int)tiles;
+  st = launch_fast(a_kc, b_kc, F, stream);
+  return true;
 }
 
 static int elem_size(int32_t dtype) { return dtype == ARD_BF16 ? 2 : 4; }
@@ -126,6 +229,107 @@ static int32_t tile_lists(const LayerArgs& a, void* ws, size_t ws_bytes, hipStre
   return ARD_OK;
 }
 
+// Tile pattern on the large-tile path: classes of tile rows / columns (see fast.hpp).
+// op 0: Y = X . W^T   1: dX = dY . W   2: dW = dY^T . X
+static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void* Bp, void* Cp, float alpha, int relu,
+                          hipStream_t stream, int32_t& st) {
+  if (a.dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
+  const int x = a.po->tile_r, y = a.po->tile_c, dp = a.po->dp, o = a.po->b - 1, TR = a.TR, TC = a.TC;
+  const int B = a.B, I = a.I, O = a.O;
+  if ((I % 8) || (O % 8) || (long)B * O >= (1L << 31) || (long)B * I >= (1L << 31) || (long)O * I >= (1L << 31)) return false;
+  if (((uintptr_t)Ap & 15) || ((uintptr_t)Bp & 15)) return false;
+  const int g = gcd_int(TC, dp), Pp = dp / g;
+  FastParams F{};
+  ClassTab& t = F.tab;
+  const int tiles_b = ceil_div(B, F_BM);
+  auto cnt = [](int total, int first, int step) { return first < total ? (total - first + step - 1) / step : 0; };
+  if (op == 0) {
+    if ((256 % x) || (y % 64) || Pp > F_MAXCLS) return false;
+    t.ncls = Pp;
+    t.n_step = Pp, t.n_bs = x, t.n_phys = O;
+    t.k_step = dp, t.k_bs = y, t.k_phys = I;
+    for (int c = 0; c < Pp; ++c) {
+      t.n_off[c] = c;
+      t.n_cnt[c] = cnt(TR, c, Pp);
+      const int t0 = (int)((((long)o - (long)c * TC) % dp + dp) % dp);
+      t.k_off[c] = t0;
+      t.k_cnt[c] = cnt(TC, t0, dp);
+      t.mblk[c] = tiles_b;
+    }
+    F.A = (const uint16_t*)Ap, F.lda = I, F.am = axis_identity(B);
+    F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.C = (uint16_t*)Cp, F.ldc = O;
+    F.c_cols_mapped = 1;
+    F.M = B, F.N = O;
+  } else if (op == 1) {
+    if ((256 % y) || (x % 64) || dp > F_MAXCLS) return false;
+    t.ncls = dp;
+    t.n_step = dp, t.n_bs = y, t.n_phys = I;
+    t.k_step = Pp, t.k_bs = x, t.k_phys = O;
+    for (int c = 0; c < dp; ++c) {
+      t.n_off[c] = c;
+      t.n_cnt[c] = cnt(TC, c, dp);
+      int J0 = -1;
+      for (int J = 0; J < Pp; ++J)
+        if ((((long)J * TC + c - o) % dp + dp) % dp == 0) {
+          J0 = J;
+          break;
+        }
+      t.k_off[c] = J0 < 0 ? 0 : J0;
+      t.k_cnt[c] = J0 < 0 ? 0 : cnt(TR, J0, Pp);
+      t.mblk[c] = tiles_b;
+    }
+    F.A = (const uint16_t*)Ap, F.lda = O, F.am = axis_identity(B);
+    F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.C = (uint16_t*)Cp, F.ldc = I;
+    F.c_cols_mapped = 1;
+    F.M = B, F.N = I;
+  } else {
+    if ((256 % x) || (256 % y) || (x % 8) || (y % 8) || Pp > F_MAXCLS) return false;
+    t.ncls = Pp;
+    t.m_step = Pp, t.m_bs = x, t.m_phys = O;
+    t.n_step = dp, t.n_bs = y, t.n_phys = I;
+    t.k_bs = 0;
+    for (int c = 0; c < Pp; ++c) {
+      t.m_off[c] = c;
+      t.m_cnt[c] = cnt(TR, c, Pp);
+      const int t0 = (int)((((long)o - (long)c * TC) % dp + dp) % dp);
+      t.n_off[c] = t0;
+      t.n_cnt[c] = cnt(TC, t0, dp);
+      t.mblk[c] = ceil_div(t.m_cnt[c], F_BM / x);
+    }
+    F.A = (const uint16_t*)Ap, F.lda = O;
+    F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.k = axis_identity(B);
+    F.C = (uint16_t*)Cp, F.ldc = I;
+    F.c_rows_mapped = F.c_cols_mapped = 1;
+    F.M = O, F.N = I;
+  }
+  int total = 0;
+  for (int c = 0; c < t.ncls; ++c) {
+    t.prefix[c] = total;
+    const int nblk = ceil_div(t.n_cnt[c], F_BN / t.n_bs);
+    if (t.mblk[c] <= 0 || nblk <= 0) t.mblk[c] = t.mblk[c] > 0 ? t.mblk[c] : 1;
+    total += (t.n_cnt[c] > 0 && (op != 2 || t.m_cnt[c] > 0)) ? t.mblk[c] * nblk : 0;
+  }
+  t.prefix[t.ncls] = total;
+  if (total < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
+  F.alpha = alpha;
+  F.relu = relu;
+  F.total_tiles = total;
+  if (op == 2) {
+    hipLaunchKernelGGL(zero_dropped_tiles_kernel, dim3((unsigned)(TR * TC)), dim3(256), 0, stream, (uint16_t*)Cp, I, O, I,
+                       x, y, TC, dp, o);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+      st = fail(ARD_EHIP, "launch of zero_dropped_tiles_kernel failed: %s", hipGetErrorString(e));
+      return true;
+    }
+  }
+  st = launch_fast(op != 2, op == 0, F, stream);
+  return true;
+}
+
 static int pick_bn(int t) { return t % 128 == 0 ? 128 : (t % 64 == 0 ? 64 : 32); }
 
 }  // namespace ard
@@ -157,6 +361,7 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
   P.B.p = W;
   P.B.ld = I;
   int max_bn = 0;
+  if (a.tile && try_fast_tile(0, a, X, W, Y, alpha, fuse_relu, stream, st)) return st;
   if (a.tile) {
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
@@ -173,9 +378,8 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
     P.k = axis_of_pattern(pat_in, I);
     P.C.cn = P.B.r;
   }
-  bool kvec = axis_chunk_contiguous(P.k, ce) && (I % ce) == 0;
-  P.A.vec = kvec && aligned16(X);
-  P.B.vec = kvec && aligned16(W);
+  P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
+  P.B.vec = operand_vec_ok(P.B, true, P.k, ce);
   P.C.p = Y;
   P.C.ld = O;
   P.C.rm = axis_identity(B);
@@ -204,6 +408,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
   P.B.p = W;  // element (n = input neuron, k = output neuron) at W[k*I + n]
   P.B.ld = I;
   int max_bn = 0;
+  if (a.tile && !relu_src && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st)) return st;
   if (a.tile) {
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
@@ -218,8 +423,8 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
     P.B.r = axis_of_pattern(pat_in, I);
     P.k = axis_of_pattern(pat_out, O);
   }
-  P.A.vec = axis_chunk_contiguous(P.k, ce) && (O % ce) == 0 && aligned16(dY);
-  P.B.vec = 0;
+  P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
+  P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
   P.C.p = dX;
   P.C.relu_src = relu_src;
   P.C.ld = I;
@@ -247,6 +452,7 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   P.B.p = X;   // element (n = input neuron, k = batch row) at X[k*I + n]
   P.B.ld = I;
   P.k = axis_identity(B);
+  if (a.tile && beta == 0.0f && try_fast_tile(2, a, dY, X, dW, alpha, 0, stream, st)) return st;
   if (a.tile) {
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
@@ -261,6 +467,8 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
     P.A.r = axis_of_pattern(pat_out, O);
     P.B.r = axis_of_pattern(pat_in, I);
   }
+  P.A.vec = operand_vec_ok(P.A, false, P.k, chunk_elems(dtype));
+  P.B.vec = operand_vec_ok(P.B, false, P.k, chunk_elems(dtype));
   P.C.p = dW;
   P.C.ld = I;
   P.C.rm = P.A.r;

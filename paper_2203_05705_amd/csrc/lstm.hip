@@ -259,6 +259,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
       P.C.alpha = 1.0f;
       P.M = B;
       P.N = Hk;
+      P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
       st = run_gemm(a.dtype, true, false, P, 0, 0, stream);
       if (st) return st;
     }
@@ -276,6 +277,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     P.C.alpha = 1.0f;
     P.M = T_ * B;
     P.N = I;
+    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
     st = run_gemm(a.dtype, true, false, P, 0, 0, stream);
     if (st) return st;
   }
@@ -293,6 +295,8 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     P.C.alpha = 1.0f;
     P.M = 4 * Hk;
     P.N = I;
+    P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
+    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
     st = run_gemm(a.dtype, false, false, P, 0, 0, stream);
     if (st) return st;
   }
@@ -310,6 +314,8 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     P.C.alpha = 1.0f;
     P.M = 4 * Hk;
     P.N = Hk;
+    P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
+    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
     st = run_gemm(a.dtype, false, false, P, 0, 0, stream);
     if (st) return st;
   }
