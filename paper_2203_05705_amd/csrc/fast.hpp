@@ -1,19 +1,33 @@
-// Large-tile bf16 path of the gathered GEMM: 256 x 256 x 64 workgroup tiles, 8 wavefronts
-// (2 x 4, each 128 x 64 = 4 x 2 MFMA 32x32x16 tiles), two wavefronts per SIMD so one
-// wavefront's LDS/global waits hide behind the other's MFMAs, double-buffered swizzled LDS
-// (128 KiB of the 160 KiB per CU), XCD-aware tile order.
+// Large-tile bf16 path of the gathered GEMM for gfx950.
+//
+// Workgroup: 8 wavefronts (two per SIMD), tile 256 x BN x 64 with BN = 256 (waves 2 x 4, each
+// 128 x 64) or BN = 128 (waves 4 x 2, each 64 x 64), MFMA 32x32x16 bf16.
+//
+// Operand staging uses LDS-direct loads (global_load_lds_dwordx4): a wavefront instruction
+// moves 64 x 16 bytes from per-lane global addresses into 1 KiB of consecutive LDS with no
+// register in between, so a whole stage stays in flight behind the MFMAs of the previous one.
+// The LDS layout is therefore fixed by lane order, and each lane picks WHICH chunk it fetches
+// so that the layout comes out swizzled (bank-conflict free for the fragment reads):
+//   KC operand (contraction-contiguous in memory): LDS tile [rows][8 chunks of 16 B]; an
+//     instruction fills 8 rows; lane = (row, slot) fetches logical chunk slot ^ xr(row).
+//     Fragments: ds_read_b128.
+//   MC operand (contraction-strided in memory): LDS tile [64 k][rows] exactly as in memory; lane
+//     = (k, pos) fetches chunk pos ^ 4*(k & 3).  Fragments: two ds_read_b64_tr_b16 (the
+//     transposing LDS read of gfx950) per MFMA operand, no register transpose anywhere.
+// LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1]; the stage is an immediate offset of
+// the fragment reads, so every read address is a loop invariant.
 //
 // Tile patterns (Section 3.2) are period patterns over the linear tile index, so the tile
 // rows (or columns) fall into a few CLASSES that share one kept-column (kept-row) set:
 // class members, and the kept set of a class, are both arithmetic progressions.  A
-// workgroup takes 256/tile consecutive members of ONE class as its rows or columns and
-// walks that class's kept set along the contraction, so dropped tiles cost nothing and
-// the macro tile stays 256 wide.  ClassTab carries the progressions.
+// workgroup takes consecutive members of ONE class as its rows or columns and walks that
+// class's kept set along the contraction, so dropped tiles cost nothing and the macro
+// tile stays wide.  ClassTab carries the progressions.
 //
-// Restrictions checked on the host (anything else goes through gemm_kernel):
-//   bf16 operands fetched with 16-byte loads only; contraction map identity or block
-//   progression with block size a multiple of 64; every extent along a 16-byte run is a
-//   multiple of 8.
+// Restrictions checked on the host (anything else goes through gemm_kernel): bf16, 16-byte
+// aligned operands, every extent along a 16-byte run a multiple of 8, contraction map =
+// identity or a block progression with block size a multiple of 64, outputs not scattered
+// below 32-wide blocks.
 #pragma once
 #include <type_traits>
 
@@ -25,7 +39,7 @@ constexpr int F_MAXCLS = 16;
 
 struct ClassTab {
   int ncls;                       // 0: plain tiles_m x tiles_n grid over P.am / P.bn / P.k
-  int prefix[F_MAXCLS + 1];       // workgroups before class c
+  int nblk[F_MAXCLS];             // workgroups of class c
   int mblk[F_MAXCLS];             // workgroup rows of class c
   // row side (M): block progression off + i*step, `cnt` blocks of size bs (bs == 0: identity rows)
   int m_off[F_MAXCLS], m_cnt[F_MAXCLS], m_step, m_bs, m_phys;
@@ -45,12 +59,11 @@ struct FastParams {
   int c_rows_mapped, c_cols_mapped;  // output rows / columns go through the M / N map (else identity)
   float alpha;
   int relu;
-  int M, N, tiles_m, tiles_n, group_m, tiles_per_xcd, total_tiles;
+  int M, N, tiles_m, tiles_n, group_m, total_tiles;
 };
 
-constexpr int F_BM = 256, F_BN = 256, F_NT = 512;
+constexpr int F_BM = 256, F_NT = 512;
 
-typedef short v4i16_t __attribute__((ext_vector_type(4)));
 #define ARD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 #define ARD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 
@@ -65,64 +78,55 @@ __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
   return (k.list[q] + k.off) * k.bs + (ks - q * k.bs);
 }
 
-// Operand staging with LDS-direct loads (global_load_lds_dwordx4): a wavefront instruction
-// moves 64 x 16 bytes from per-lane global addresses into 1 KiB of consecutive LDS, with no
-// register in between, so a whole 64 KiB stage stays in flight behind the MFMAs.  The LDS
-// layout is therefore fixed by lane order, and each lane picks WHICH chunk it fetches so
-// that the layout comes out swizzled:
-//   KC operand (contraction-contiguous): LDS tile [256 rows][8 chunks]; an instruction fills
-//     8 rows; lane = (row, slot) fetches logical chunk slot ^ xr(row).  Fragments: ds_read_b128.
-//   MC operand (contraction-strided): LDS tile [64 k][32 chunks of 8 rows] exactly as in
-//     memory; an instruction fills 2 k-rows; lane = (k, pos) fetches chunk pos ^ 4*(k & 3).
-//     Fragments: two ds_read_b64_tr_b16 (transposing reads) per MFMA operand.
-template <bool KC> struct DirectLoader;
+template <bool KC, int ROWS> struct DirectLoader;
 
-template <> struct DirectLoader<true> {
+template <int ROWS> struct DirectLoader<true, ROWS> {
+  static constexpr int NI = ROWS / 64;  // instructions per wavefront and stage (8 rows each)
   const uint16_t* base;
-  int goff[4];   // element offset of this lane's chunk for instruction j, without the slab start
-  int kc;        // first contraction element of the chunk inside the slab
+  int goff[NI];  // element offset of this lane's chunk for instruction j, without the slab start
+  __device__ static __forceinline__ int chunk_k(int lane, int wave, int j) {
+    const int row = (wave * NI + j) * 8 + (lane >> 3);
+    return ((lane & 7) ^ (row & 7) ^ ((row >> 3) & 7)) * 8;
+  }
   __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave) {
     base = p;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = (wave * 4 + j) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ (row & 7) ^ ((row >> 3) & 7);
+    for (int j = 0; j < NI; ++j) {
+      const int row = (wave * NI + j) * 8 + (lane >> 3);
       int ph = row0 + row < r.n ? ax_phys(r, row0 + row) : 0;
       ph = ph < r.nphys ? ph : 0;  // rows outside the matrix: fetch row 0, the result is never stored
-      goff[j] = ph * ld + c * 8;
-      if (j == 0) kc = c * 8;      // (row & 7) and ((row >> 3) & 7) differ per j: kc is per j below
+      goff[j] = ph * ld + chunk_k(lane, wave, j);
     }
-  }
-  // chunk index of instruction j (recomputed: cheaper than four more registers)
-  __device__ __forceinline__ int chunk_k(int lane, int wave, int j) const {
-    const int row = (wave * 4 + j) * 8 + (lane >> 3);
-    return ((lane & 7) ^ (row & 7) ^ ((row >> 3) & 7)) * 8;
   }
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
                                         int wave) const {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NI; ++j) {
       const uint16_t* src = base + (long)goff[j] + kslab;
       if (tail) {
         const int k = chunk_k(lane, wave, j);
         if (!(k < krem && kslab + k + 8 <= kphys_end)) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
       }
-      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * 4 + j) * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
 };
 
-template <> struct DirectLoader<false> {
+template <int ROWS> struct DirectLoader<false, ROWS> {
+  static constexpr int CPR = ROWS / 8;   // 16-byte chunks per contraction row
+  static constexpr int KPI = 64 / CPR;   // contraction rows per instruction
+  static constexpr int NI = 8 / KPI;     // instructions per wavefront and stage
+  static constexpr int NCO = KPI == 2 ? 2 : 1;
   const uint16_t* base;
   int ld;
-  int coff[2];  // physical column of this lane's chunk for even / odd instructions
+  int coff[NCO];  // physical column of this lane's chunk (per instruction parity when KPI == 2)
   __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave) {
     base = p;
     ld = ld_;
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int kloc = 2 * par + (lane >> 5);               // k & 3 of the row this lane fills
-      const int c = (lane & 31) ^ (4 * (kloc & 3));
+    for (int par = 0; par < NCO; ++par) {
+      const int k3 = (KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR) & 3;  // (k & 3) of the row this lane fills
+      const int c = (lane % CPR) ^ (4 * k3);
       const int j = row0 + c * 8;
       int ph = j + 8 <= r.n ? ax_phys(r, j) : 0;
       coff[par] = ph + 8 <= r.nphys ? ph : 0;
@@ -131,37 +135,33 @@ template <> struct DirectLoader<false> {
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
                                         int wave) const {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int kloc = 2 * (wave * 4 + j) + (lane >> 5);
-      const uint16_t* src = base + (long)(kslab + kloc) * ld + coff[j & 1];
+    for (int j = 0; j < NI; ++j) {
+      const int kloc = KPI * (wave * NI + j) + lane / CPR;
+      const uint16_t* src = base + (long)(kslab + kloc) * ld + coff[NCO == 2 ? (j & 1) : 0];
       if (tail && !(kloc < krem && kslab + kloc < kphys_end)) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
-      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * 4 + j) * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
 };
 
-// Fragment addressing.  KC: u4 index of (row, chunk 2q+g).  MC: byte address of the lane's
-// source position for the transposing read of MFMA tile `t` (k offset q*16 + h*4 added as
-// an immediate by the caller).
+// Byte offset, inside an MC operand tile of `ROWS` rows, of this lane's source position for the
+// transposing reads of the 32-wide MFMA tile that starts at tile row `tile_col0`.  The reads
+// of slice q, half h add the immediate (q*16 + h*4) * ROWS*2.
+// ds_read_b64_tr_b16 works on groups of 16 lanes: result lane i, element e comes from source
+// lane 4e + i/4, element i%4.  With source lane s at (k = s/4, column 4*(s%4)) of a 4 x 16
+// block, result lane i holds column i for k = 0..3: the MFMA operand order.
+template <int ROWS>
 __device__ __forceinline__ int mc_frag_base(int tile_col0, int lane) {
   const int s = lane & 15, G = lane >> 4;
   const int g = G >> 1, jhalf = G & 1;
   const int c = (tile_col0 >> 3) + 2 * jhalf + ((s & 3) >> 1);
   const int pc = c ^ (4 * ((s >> 2) & 3));
-  return (g * 8 + (s >> 2)) * 512 + pc * 16 + 8 * (s & 1);
+  return (g * 8 + (s >> 2)) * (ROWS * 2) + pc * 16 + 8 * (s & 1);
 }
 
-__device__ __forceinline__ uint4 mc_frag_read(const char* op_bytes, int base, int q) {
-  typedef v4i16_t __attribute__((address_space(3))) * lds_v4;
-  const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(op_bytes + base + q * 8192));
-  const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(op_bytes + base + q * 8192 + 2048));
-  uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
-  return make_uint4(l.x, l.y, h.x, h.y);
-}
-
-// LDS fragment reads are issued as volatile asm: the compiler then cannot move a read next to
-// its consumer, and the single wait below (tied to the fragment registers) is the only place
-// where a slice's MFMAs meet their operands.  One slice ahead is always in flight.
+// LDS fragment reads are issued as volatile asm with ONE explicit wait per 16-wide slice: the
+// compiler cannot sink a read next to its consumer, so a slice's reads are in flight while
+// the previous slice's MFMAs run (left to itself the scheduler waits right after each read).
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 struct Frag {  // one MFMA operand: a full 16-byte read (KC) or two transposing 8-byte reads (MC)
@@ -189,35 +189,46 @@ __device__ __forceinline__ bf16x8_t frag_value(const Frag& f) {
   return __builtin_bit_cast(bf16x8_t, t);
 }
 
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, int BN>
 __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
-  constexpr int TM = 4, TN = 2, WTM = 128, WTN = 64;
-  constexpr int STAGE = (F_BM + F_BN) * LDS_ROW_U4;  // 64 KiB
+  constexpr int WGN = BN == 256 ? 4 : 2, WGM = 8 / WGN;
+  constexpr int WTM = F_BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int OPA = F_BM * LDS_ROW_U4, OPB = BN * LDS_ROW_U4;  // u4 entries of one operand stage
   extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / WGN, wn = wave % WGN;
 
-  // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so XCD x = id % 8 gets the
-  // contiguous range [x * tiles_per_xcd, ...) of the logical order.
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int L = xcd * P.tiles_per_xcd + local;
-  if (local >= P.tiles_per_xcd || L >= P.total_tiles) return;
-
+  // Workgroup ids go round-robin over the 8 XCDs.  XCD x = id % 8 takes, of every class, the
+  // contiguous share [x*n/8, (x+1)*n/8) of its n workgroups: the shares are compact rectangles
+  // (operand panels stay in that XCD's L2) and heavy and light classes are spread evenly.
+  const int xcd = blockIdx.x & 7;
+  int local = blockIdx.x >> 3;
   Axis am = P.am, bn = P.bn, kax = P.k;
   int m0 = 0, n0 = 0;
   if (P.tab.ncls == 0) {
-    // bands of group_m tile rows, walked column by column: an XCD's share is a compact rectangle
+    const int lo = (int)((long)xcd * P.total_tiles / 8), hi = (int)((long)(xcd + 1) * P.total_tiles / 8);
+    if (local >= hi - lo) return;
+    const int L = lo + local;
+    // bands of group_m tile rows, walked column by column
     const int band_sz = P.group_m * P.tiles_n;
     const int band = L / band_sz, inb = L - band * band_sz;
     const int rows_in_band = min(P.group_m, P.tiles_m - band * P.group_m);
     m0 = (band * P.group_m + inb % rows_in_band) * F_BM;
-    n0 = (inb / rows_in_band) * F_BN;
+    n0 = (inb / rows_in_band) * BN;
   } else {
     const ClassTab& t = P.tab;
-    int c = 0;
-    while (c + 1 < t.ncls && L >= t.prefix[c + 1]) ++c;
-    const int l = L - t.prefix[c];
+    int c = 0, l = -1;
+    for (; c < t.ncls; ++c) {
+      const int lo = (int)((long)xcd * t.nblk[c] / 8), hi = (int)((long)(xcd + 1) * t.nblk[c] / 8);
+      if (local < hi - lo) {
+        l = lo + local;
+        break;
+      }
+      local -= hi - lo;
+    }
+    if (l < 0) return;
     const int mi = l % t.mblk[c], ni = l / t.mblk[c];
     if (t.m_bs) {
       const int g = F_BM / t.m_bs;
@@ -227,7 +238,7 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
       m0 = mi * F_BM;
     }
     {
-      const int g = F_BN / t.n_bs;
+      const int g = BN / t.n_bs;
       const int left = t.n_cnt[c] - ni * g;
       bn = axis_baff(t.n_off[c] + ni * g * t.n_step, t.n_step, t.n_bs, left < g ? left : g, t.n_phys);
     }
@@ -244,13 +255,10 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
       for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
 
   if (Kn > 0) {
-    DirectLoader<A_KC> la;
-    DirectLoader<B_KC> lb;
+    DirectLoader<A_KC, F_BM> la;
+    DirectLoader<B_KC, BN> lb;
     la.init(P.A, P.lda, am, m0, lane, wave);
     lb.init(P.B, P.ldb, bn, n0, lane, wave);
-    // LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KiB each, so the stage is an
-    // immediate offset of the fragment reads and every read address is a loop invariant.
-    constexpr int OPT = F_BM * LDS_ROW_U4;  // u4 entries of one operand tile
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
     unsigned aaddr[TM][A_KC ? 4 : 1], baddr[TN][B_KC ? 4 : 1];
 #pragma unroll
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) aaddr[im][q] = lds_base + (unsigned)(row * 8 + ((2 * q + (lane >> 5)) ^ xr)) * 16u;
       } else {
-        aaddr[im][0] = lds_base + (unsigned)mc_frag_base(wm * WTM + im * 32, lane);
+        aaddr[im][0] = lds_base + (unsigned)mc_frag_base<F_BM>(wm * WTM + im * 32, lane);
       }
     }
 #pragma unroll
@@ -271,90 +279,107 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
         const int xr = (row & 7) ^ ((row >> 3) & 7);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          baddr[in][q] = lds_base + (unsigned)(2 * OPT + row * 8 + ((2 * q + (lane >> 5)) ^ xr)) * 16u;
+          baddr[in][q] = lds_base + (unsigned)(2 * OPA + row * 8 + ((2 * q + (lane >> 5)) ^ xr)) * 16u;
       } else {
-        baddr[in][0] = lds_base + (unsigned)(2 * OPT) * 16u + (unsigned)mc_frag_base(wn * WTN + in * 32, lane);
+        baddr[in][0] = lds_base + (unsigned)(2 * OPA) * 16u + (unsigned)mc_frag_base<BN>(wn * WTN + in * 32, lane);
       }
     }
     const int S = (Kn + 63) >> 6;
     auto load_stage = [&](int it, int buf) {
+#if defined(ARD_ABL) && (ARD_ABL & 1)
+      if (it > 1) return;
+#endif
       const int krem = Kn - it * 64;
       const int ks = fast_kslab(kax, it * 64);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
-      la.issue(lds + buf * OPT, ks, krem, kax.nphys, tail, lane, wave);
-      lb.issue(lds + (2 + buf) * OPT, ks, krem, kax.nphys, tail, lane, wave);
+      la.issue(lds + buf * OPA, ks, krem, kax.nphys, tail, lane, wave);
+      lb.issue(lds + 2 * OPA + buf * OPB, ks, krem, kax.nphys, tail, lane, wave);
     };
-    // One contraction step from stage BUF (compile-time, so its offset is an immediate).
-    // LDS fragment reads are volatile asm with one explicit wait per 16-wide slice: a slice's
-    // reads are issued while the previous slice's MFMAs run and meet their consumers only at
-    // that wait.
-    auto step = [&](auto bufc) {
+    constexpr int QA = 16 * F_BM * 2, QB = 16 * BN * 2;  // bytes per 16-wide slice of an MC tile
+    Frag fa[2][TM], fb[2][TN];
+    // issue the fragment reads of slice Q of stage BUF (both compile-time: immediates) into `set`
+    auto issue = [&](auto bufc, auto qc, int set) {
+#if defined(ARD_ABL) && (ARD_ABL & 4)
+      return;
+#endif
+      constexpr int BUF = decltype(bufc)::value, Q = decltype(qc)::value;
+      constexpr int SA = BUF * OPA * 16, SB = BUF * OPB * 16;  // byte offsets of the stage
+#pragma unroll
+      for (int im = 0; im < TM; ++im) {
+        if (A_KC) {
+          lds_read_b128<SA>(fa[set][im].v, aaddr[im][A_KC ? Q : 0]);
+        } else {
+          lds_read_tr16_b64<SA + Q * QA>(fa[set][im].lo, aaddr[im][0]);
+          lds_read_tr16_b64<SA + Q * QA + QA / 4>(fa[set][im].hi, aaddr[im][0]);
+        }
+      }
+#pragma unroll
+      for (int in = 0; in < TN; ++in) {
+        if (B_KC) {
+          lds_read_b128<SB>(fb[set][in].v, baddr[in][B_KC ? Q : 0]);
+        } else {
+          lds_read_tr16_b64<SB + Q * QB>(fb[set][in].lo, baddr[in][0]);
+          lds_read_tr16_b64<SB + Q * QB + QB / 4>(fb[set][in].hi, baddr[in][0]);
+        }
+      }
+    };
+    auto wait = [&](int set) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int im = 0; im < TM; ++im) frag_wait<A_KC>(fa[set][im]);
+#pragma unroll
+      for (int in = 0; in < TN; ++in) frag_wait<B_KC>(fb[set][in]);
+    };
+    auto mma = [&](int set) {
+#if defined(ARD_ABL) && (ARD_ABL & 2)
+      return;
+#endif
+#pragma unroll
+      for (int im = 0; im < TM; ++im)
+#pragma unroll
+        for (int in = 0; in < TN; ++in)
+          acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_value<A_KC>(fa[set][im]),
+                                                                frag_value<B_KC>(fb[set][in]), acc[im][in], 0, 0, 0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    // One contraction step from stage BUF.  Slice q+1's reads are in flight behind slice q's
+    // MFMAs; the stage hand-over (wait for the next stage's loads, barrier, start the loads of
+    // the stage after it into the buffer just released, read the next stage's first slice)
+    // sits in front of the LAST slice's MFMAs, so neither the barrier nor the first LDS
+    // latency of a stage leaves the matrix cores idle.
+    auto step = [&](auto bufc, int it) {
       constexpr int BUF = decltype(bufc)::value;
-      constexpr int SOFF = BUF * OPT * 16;  // byte offset of the stage inside its operand pair
-      Frag fa[2][TM], fb[2][TN];
-      auto issue = [&](auto qc, int set) {
-        constexpr int Q = decltype(qc)::value;
-#pragma unroll
-        for (int im = 0; im < TM; ++im) {
-          if (A_KC) {
-            lds_read_b128<SOFF>(fa[set][im].v, aaddr[im][A_KC ? Q : 0]);
-          } else {
-            lds_read_tr16_b64<SOFF + Q * 8192>(fa[set][im].lo, aaddr[im][0]);
-            lds_read_tr16_b64<SOFF + Q * 8192 + 2048>(fa[set][im].hi, aaddr[im][0]);
-          }
-        }
-#pragma unroll
-        for (int in = 0; in < TN; ++in) {
-          if (B_KC) {
-            lds_read_b128<SOFF>(fb[set][in].v, baddr[in][B_KC ? Q : 0]);
-          } else {
-            lds_read_tr16_b64<SOFF + Q * 8192>(fb[set][in].lo, baddr[in][0]);
-            lds_read_tr16_b64<SOFF + Q * 8192 + 2048>(fb[set][in].hi, baddr[in][0]);
-          }
-        }
-      };
-      auto wait = [&](int set) {
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int im = 0; im < TM; ++im) frag_wait<A_KC>(fa[set][im]);
-#pragma unroll
-        for (int in = 0; in < TN; ++in) frag_wait<B_KC>(fb[set][in]);
-      };
-      auto mma = [&](int set) {
-#pragma unroll
-        for (int im = 0; im < TM; ++im)
-#pragma unroll
-          for (int in = 0; in < TN; ++in)
-            acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_value<A_KC>(fa[set][im]),
-                                                                  frag_value<B_KC>(fb[set][in]), acc[im][in], 0, 0, 0);
-      };
-      issue(std::integral_constant<int, 0>{}, 0);
+      using B = std::integral_constant<int, BUF>;
+      using NB = std::integral_constant<int, BUF ^ 1>;
       wait(0);
-      issue(std::integral_constant<int, 1>{}, 1);
+      issue(B{}, I1{}, 1);
       mma(0);
       wait(1);
-      issue(std::integral_constant<int, 2>{}, 0);
+      issue(B{}, I2{}, 0);
       mma(1);
       wait(0);
-      issue(std::integral_constant<int, 3>{}, 1);
+      issue(B{}, I3{}, 1);
       mma(0);
       wait(1);
+      if (it + 1 < S) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // stage it+1 is complete and visible; nobody reads stage it any more
+        if (it + 2 < S) load_stage(it + 2, BUF);
+        issue(NB{}, I0{}, 0);
+      }
       mma(1);
     };
     load_stage(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (S > 1) load_stage(1, 1);
+    issue(I0{}, I0{}, 0);
     for (int it = 0; it < S; it += 2) {
-      // stage `it` has landed once every wavefront's loads are done; the barrier also tells us
-      // that everybody finished reading the other buffer, which the next loads overwrite
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (it + 1 < S) load_stage(it + 1, 1);
-      step(std::integral_constant<int, 0>{});
-      if (it + 1 < S) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (it + 2 < S) load_stage(it + 2, 0);
-        step(std::integral_constant<int, 1>{});
-      }
+      step(I0{}, it);
+      if (it + 1 < S) step(I1{}, it + 1);
     }
   }
 
@@ -377,15 +402,33 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
     if (pc >= nphys) continue;
 #pragma unroll
     for (int im = 0; im < TM; ++im) {
-      uint16_t* dst = P.C + (long)(prow[im] + 4 * (lane >> 5)) * P.ldc + pc;
+      // Adjacent lanes hold adjacent columns of the same row.  Rows come in pairs (v, v+1):
+      // the even lane takes the odd lane's value of row v, the odd lane the even lane's value
+      // of row v+1 (one DPP swap), and each stores one packed 32-bit word.
       const int rbase = prow[im] + 4 * (lane >> 5);
+      const bool odd = lane & 1;
+      uint16_t* dst = P.C + (long)rbase * P.ldc + (pc & ~1);
+      const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int dr = 8 * (v >> 2) + (v & 3);
-        if (rbase + dr >= mphys) continue;
-        float x = P.alpha * acc[im][in][v];
-        if (P.relu) x = fmaxf(x, 0.0f);
-        dst[(long)dr * P.ldc] = f32_to_bf16_bits(x);
+      for (int v = 0; v < 16; v += 2) {
+        float x0 = P.alpha * acc[im][in][v], x1 = P.alpha * acc[im][in][v + 1];
+        if (P.relu) {
+          x0 = fmaxf(x0, 0.0f);
+          x1 = fmaxf(x1, 0.0f);
+        }
+        const uint32_t b0 = f32_to_bf16_bits(x0), b1 = f32_to_bf16_bits(x1);
+        const int dr0 = 8 * (v >> 2) + (v & 3);  // row of v; v+1 is the next row
+        if (pair_ok) {
+          const uint32_t send = odd ? b0 : b1;
+          const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, true);  // swap with lane^1
+          const uint32_t word = odd ? (got | (b1 << 16)) : (b0 | (got << 16));
+          const int dr = odd ? dr0 + 1 : dr0;
+          if (rbase + dr < mphys) *reinterpret_cast<uint32_t*>(dst + (long)dr * P.ldc) = word;
+        } else {
+          uint16_t* d1 = P.C + (long)rbase * P.ldc + pc;
+          if (rbase + dr0 < mphys) d1[(long)dr0 * P.ldc] = (uint16_t)b0;
+          if (rbase + dr0 + 1 < mphys) d1[(long)(dr0 + 1) * P.ldc] = (uint16_t)b1;
+        }
       }
     }
   }

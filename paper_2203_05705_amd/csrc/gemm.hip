@@ -81,15 +81,10 @@ static int gcd_int(int a, int b) {
   return a;
 }
 
-static int32_t launch_fast(bool a_kc, bool b_kc, FastParams& F, hipStream_t stream) {
-  if (F.total_tiles <= 0) return ARD_OK;
-  F.tiles_per_xcd = ceil_div(F.total_tiles, 8);
-  // an XCD's share should be about square in tiles: bands of group_m tile rows
-  int gm = 1;
-  while (gm * gm * 2 <= F.tiles_per_xcd && gm < 8) gm *= 2;
-  F.group_m = gm;
-  dim3 grid((unsigned)(F.tiles_per_xcd * 8)), block(F_NT);
-  const size_t lds_bytes = (size_t)2 * (F_BM + F_BN) * LDS_ROW_U4 * sizeof(uint4);
+template <int BN>
+static int32_t launch_fast_bn(bool a_kc, bool b_kc, FastParams& F, int grid_blocks, hipStream_t stream) {
+  dim3 grid((unsigned)grid_blocks), block(F_NT);
+  const size_t lds_bytes = (size_t)2 * (F_BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   auto go = [&](auto kernel) -> int32_t {
     static thread_local bool raised = false;
     if (!raised) {
@@ -100,10 +95,38 @@ static int32_t launch_fast(bool a_kc, bool b_kc, FastParams& F, hipStream_t stre
     ARD_LAUNCH_CHECK("gemm256_kernel");
     return ARD_OK;
   };
-  if (a_kc && b_kc) return go(gemm256_kernel<true, true>);
-  if (a_kc && !b_kc) return go(gemm256_kernel<true, false>);
-  if (!a_kc && !b_kc) return go(gemm256_kernel<false, false>);
+  if (a_kc && b_kc) return go(gemm256_kernel<true, true, BN>);
+  if (a_kc && !b_kc) return go(gemm256_kernel<true, false, BN>);
+  if (!a_kc && !b_kc) return go(gemm256_kernel<false, false, BN>);
   return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
+}
+
+// Grid of the large-tile kernel: every XCD takes the share [x*n/8, (x+1)*n/8) of each class.
+static int fast_grid(const FastParams& F) {
+  int worst = 0;
+  for (int x = 0; x < 8; ++x) {
+    int sum = 0;
+    if (F.tab.ncls == 0) {
+      sum = (int)((long)(x + 1) * F.total_tiles / 8) - (int)((long)x * F.total_tiles / 8);
+    } else {
+      for (int c = 0; c < F.tab.ncls; ++c)
+        sum += (int)((long)(x + 1) * F.tab.nblk[c] / 8) - (int)((long)x * F.tab.nblk[c] / 8);
+    }
+    worst = sum > worst ? sum : worst;
+  }
+  return worst * 8;
+}
+
+static int32_t launch_fast(bool a_kc, bool b_kc, FastParams& F, int bn, hipStream_t stream) {
+  if (F.total_tiles <= 0) return ARD_OK;
+  // an XCD's share should be about square in tiles: bands of group_m tile rows
+  const int per_xcd = ceil_div(F.total_tiles, 8);
+  int gm = 1;
+  while (gm * gm * 2 <= per_xcd && gm < 8) gm *= 2;
+  F.group_m = gm;
+  const int grid = fast_grid(F);
+  if (bn == 128) return launch_fast_bn<128>(a_kc, b_kc, F, grid, stream);
+  return launch_fast_bn<256>(a_kc, b_kc, F, grid, stream);
 }
 
 static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0 && ld < (1L << 30); }
@@ -121,7 +144,12 @@ static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams
   if (!a_kc && (P.A.r.n % 8)) return false;
   if (!b_kc && (P.B.r.n % 8)) return false;
   if ((long)P.A.r.nphys * P.A.ld >= (1L << 31) || (long)P.B.r.nphys * P.B.ld >= (1L << 31)) return false;
-  const long tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, F_BN);
+  int bn = 256;
+  long tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, 256);
+  if (tiles < 200) {
+    bn = 128;
+    tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, 128);
+  }
   if (tiles < 96) return false;
   FastParams F{};
   F.A = (const uint16_t*)P.A.p;
@@ -138,9 +166,9 @@ static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams
   F.M = P.M;
   F.N = P.N;
   F.tiles_m = ceil_div(P.M, F_BM);
-  F.tiles_n = ceil_div(P.N, F_BN);
+  F.tiles_n = ceil_div(P.N, bn);
   F.total_tiles = (int)tiles;
-  st = launch_fast(a_kc, b_kc, F, stream);
+  st = launch_fast(a_kc, b_kc, F, bn, stream);
   return true;
 }
 
@@ -305,15 +333,27 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     F.c_rows_mapped = F.c_cols_mapped = 1;
     F.M = O, F.N = I;
   }
-  int total = 0;
-  for (int c = 0; c < t.ncls; ++c) {
-    t.prefix[c] = total;
-    const int nblk = ceil_div(t.n_cnt[c], F_BN / t.n_bs);
-    if (t.mblk[c] <= 0 || nblk <= 0) t.mblk[c] = t.mblk[c] > 0 ? t.mblk[c] : 1;
-    total += (t.n_cnt[c] > 0 && (op != 2 || t.m_cnt[c] > 0)) ? t.mblk[c] * nblk : 0;
+  // workgroups per class for a column tile of BN; "heavy" ones have something to contract
+  auto count = [&](int bn, int& heavy) {
+    int total = 0;
+    heavy = 0;
+    for (int c = 0; c < t.ncls; ++c) {
+      const int mb = op == 2 ? ceil_div(t.m_cnt[c], F_BM / x) : tiles_b;
+      const int nb = ceil_div(t.n_cnt[c], bn / t.n_bs);
+      t.mblk[c] = mb > 0 ? mb : 1;
+      t.nblk[c] = (t.n_cnt[c] > 0 && mb > 0) ? mb * nb : 0;
+      total += t.nblk[c];
+      if (op == 2 || t.k_cnt[c] > 0) heavy += t.nblk[c];
+    }
+    return total;
+  };
+  int heavy = 0, bn = 256;
+  int total = count(256, heavy);
+  if (heavy < 200 && (128 % t.n_bs) == 0) {  // not enough wide tiles to fill 256 CUs: halve the tile
+    bn = 128;
+    total = count(128, heavy);
   }
-  t.prefix[t.ncls] = total;
-  if (total < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
+  if (heavy < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
   F.alpha = alpha;
   F.relu = relu;
   F.total_tiles = total;
@@ -326,7 +366,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
       return true;
     }
   }
-  st = launch_fast(op != 2, op == 0, F, stream);
+  st = launch_fast(op != 2, op == 0, F, bn, stream);
   return true;
 }
 
