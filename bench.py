@@ -55,7 +55,8 @@ class MlpChain:
         self.Y = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2, 3)]
         self.dYh = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2)]   # gradient at hidden outputs
         self.dW = [torch.empty_like(w) for w in self.W]
-        self.ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+        self.Wc = [torch.empty_like(self.W[1]), torch.empty_like(self.W[2])]   # kept blocks of W2, W3
+        self.ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
         self.stream = torch.cuda.current_stream().cuda_stream
         self._keep = []
 
@@ -65,24 +66,33 @@ class MlpChain:
         return C.byref(p)
 
     def plan(self, pats):
-        """pats = ((dp1,b1),(dp2,b2)) -> list of (fn, args, name, kept_flops)."""
+        """pats = ((dp1,b1),(dp2,b2)) -> list of (fn, args, name, kept_flops).
+
+        Hidden activations and their gradients stay compact between the calls (only kept
+        neurons are stored); W2's kept block is gathered once per iteration and shared by the
+        forward and the data-gradient product; weight gradients are written in full."""
         lib, B, s, ws = self.lib, BATCH, self.stream, self.ws
         p1, p2 = self._pat(*pats[0]), self._pat(*pats[1])
         k1 = -(-(SIZES[1] - (pats[0][1] - 1)) // pats[0][0])
         k2 = -(-(SIZES[2] - (pats[1][1] - 1)) // pats[1][0])
         X0, (W1, W2, W3), (Y1, Y2, Y3), (dY1, dY2), (dW1, dW2, dW3) = self.X0, self.W, self.Y, self.dYh, self.dW
+        W2c, W3c = self.Wc
         bf = self.ard.BF16
+        IN, OUT, WC = self.ard.IN_COMPACT, self.ard.OUT_COMPACT, self.ard.W_COMPACT
         P = lambda t: t.data_ptr()
         f = 2.0 * B
+        n = ws.numel()
         calls = [
-            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, P(ws), ws.numel(), s), "L1.fwd", f * SIZES[0] * k1),
-            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2), P(Y2), p2, p1, 1.0, 1, P(ws), ws.numel(), s), "L2.fwd", f * k1 * k2),
-            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, p2, 1.0, 0, P(ws), ws.numel(), s), "L3.fwd", f * k2 * SIZES[3]),
-            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, P(ws), ws.numel(), s), "L3.bwd_weight", f * k2 * SIZES[3]),
-            (lib.ard_drop_gemm_bwd_data, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(W3), P(dY2), None, p2, 1.0, P(Y2), P(ws), ws.numel(), s), "L3.bwd_data", f * k2 * SIZES[3]),
-            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, P(ws), ws.numel(), s), "L2.bwd_weight", f * k1 * k2),
-            (lib.ard_drop_gemm_bwd_data, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2), P(dY1), p2, p1, 1.0, P(Y1), P(ws), ws.numel(), s), "L2.bwd_data", f * k1 * k2),
-            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, P(ws), ws.numel(), s), "L1.bwd_weight", f * SIZES[0] * k1),
+            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, OUT, P(ws), n, s), "L1.fwd", f * SIZES[0] * k1),
+            (lib.ard_compact_weight, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1, s), "L2.compact_w", 0.0),
+            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2c), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC, P(ws), n, s), "L2.fwd", f * k1 * k2),
+            (lib.ard_compact_weight, (bf, SIZES[2], SIZES[3], P(W3), P(W3c), None, p2, s), "L3.compact_w", 0.0),
+            (lib.ard_drop_gemm_fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3c), P(Y3), None, p2, 1.0, 0, IN | WC, P(ws), n, s), "L3.fwd", f * k2 * SIZES[3]),
+            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN, P(ws), n, s), "L3.bwd_weight", f * k2 * SIZES[3]),
+            (lib.ard_drop_gemm_bwd_data, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(W3c), P(dY2), None, p2, 1.0, P(Y2), IN | WC, P(ws), n, s), "L3.bwd_data", f * k2 * SIZES[3]),
+            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT, P(ws), n, s), "L2.bwd_weight", f * k1 * k2),
+            (lib.ard_drop_gemm_bwd_data, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2c), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC, P(ws), n, s), "L2.bwd_data", f * k1 * k2),
+            (lib.ard_drop_gemm_bwd_weight, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT, P(ws), n, s), "L1.bwd_weight", f * SIZES[0] * k1),
         ]
         return calls
 

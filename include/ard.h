@@ -123,6 +123,25 @@ int32_t ard_pattern_gen(const ard_pattern* pat, int32_t rows, int32_t cols,
 /* ---- fully connected layer under a pattern (Sections 3.1, 3.2) ---------- */
 
 /*
+ * Layout flags of the three layer calls below (OR them into `flags`).  The method multiplies
+ * compacted operands and scatters the result (Section 3.1); these flags let a chain of
+ * layers keep its activations compact between calls instead of scattering and re-gathering:
+ *   ARD_IN_COMPACT   the input-side activation (X, dX, relu_src) is [B x I'] and holds only the
+ *                    kept input neurons of pat_in, in ascending order;
+ *   ARD_OUT_COMPACT  the output-side activation (Y, dY) is [B x O'] and holds only the kept
+ *                    output neurons of pat_out (nothing is zero-filled then);
+ *   ARD_W_COMPACT    W is the compact [O' x I'] matrix written by ard_compact_weight().
+ * dW is always the full [O x I] matrix.  Without ARD_W_COMPACT, a forward or backward-data
+ * call whose pat_in is not NONE first gathers W[kept o, kept i] into its workspace.
+ * Tile patterns take no flags.
+ */
+enum { ARD_IN_COMPACT = 1, ARD_OUT_COMPACT = 2, ARD_W_COMPACT = 4 };
+
+/* Wc[O' x I'] = W[kept o, kept i] (ROW/LIST/NONE patterns). One gather kernel, no workspace. */
+int32_t ard_compact_weight(int32_t dtype, int32_t I, int32_t O, const void* W, void* Wc,
+                           const ard_pattern* pat_out, const ard_pattern* pat_in, void* stream);
+
+/*
  * pat_out / pat_in select what is dropped (either may be NULL = NONE):
  *   pat_out ROW/LIST over the O output neurons, pat_in ROW/LIST over the I input
  *   neurons (the previous layer's pattern): synapse (o,i) survives iff both do.
@@ -142,7 +161,7 @@ size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, int32_t O,
 int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_t O,
                           const void* X, const void* W, void* Y,
                           const ard_pattern* pat_out, const ard_pattern* pat_in,
-                          float alpha, int32_t fuse_relu,
+                          float alpha, int32_t fuse_relu, int32_t flags,
                           void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -155,7 +174,7 @@ int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_t O,
 int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O,
                                const void* dY, const void* W, void* dX,
                                const ard_pattern* pat_out, const ard_pattern* pat_in,
-                               float alpha, const void* relu_src,
+                               float alpha, const void* relu_src, int32_t flags,
                                void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -165,7 +184,7 @@ int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O,
 int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O,
                                  const void* dY, const void* X, void* dW,
                                  const ard_pattern* pat_out, const ard_pattern* pat_in,
-                                 float alpha, float beta,
+                                 float alpha, float beta, int32_t flags,
                                  void* ws, size_t ws_bytes, void* stream);
 
 /* Standalone ReLU backward: dX = dY where Y > 0 else 0; n elements of `dtype`. */

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(HERE, "libard.so")
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
 CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT = 0, 1, 2, 3
+IN_COMPACT, OUT_COMPACT, W_COMPACT = 1, 2, 4
 
 
 class ArdError(RuntimeError):
@@ -78,9 +79,10 @@ _SIGS = {
     "ard_pattern_sample": (C.c_int32, [C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "ard_pattern_gen": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 7),
     "ard_gemm_workspace_bytes": (C.c_size_t, [C.c_int32] * 4 + [C.c_void_p] * 2),
-    "ard_drop_gemm_fwd": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
-    "ard_drop_gemm_bwd_data": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
-    "ard_drop_gemm_bwd_weight": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_compact_weight": (C.c_int32, [C.c_int32] * 3 + [C.c_void_p] * 5),
+    "ard_drop_gemm_fwd": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_drop_gemm_bwd_data": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_drop_gemm_bwd_weight": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ard_relu_bwd": (C.c_int32, [C.c_int32, C.c_int64] + [C.c_void_p] * 4),
     "ard_lstm_workspace_bytes": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
     "ard_lstm_fwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
@@ -211,45 +213,80 @@ def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
     return torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device)
 
 
-def drop_gemm_fwd(X, W, pat_out=None, pat_in=None, alpha=1.0, relu=False, out=None, ws=None, stream=None):
+def kept_count(pat: Optional[Pattern], units: int) -> int:
+    """Number of kept units of a ROW / LIST / NONE pattern over `units`."""
+    if pat is None or pat.kind == PAT_NONE:
+        return units
+    if pat.kind == PAT_LIST:
+        return pat.count
+    o = pat.b - 1
+    return -(-(units - o) // pat.dp) if units > o else 0
+
+
+def compact_weight(W, pat_out=None, pat_in=None, out=None, stream=None):
+    """Wc[O' x I'] = W[kept o, kept i]."""
+    _dev(W)
+    O, I = W.shape
+    Ok, Ik = kept_count(pat_out, O), kept_count(pat_in, I)
+    Wc = torch.empty((Ok, Ik), dtype=W.dtype, device=W.device) if out is None else out
+    co, ro = _pref(pat_out)
+    ci, ri = _pref(pat_in)
+    _check(lib().ard_compact_weight(_dtype_code(W), I, O, W.data_ptr(), Wc.data_ptr(), ro, ri, _stream(stream)))
+    return Wc
+
+
+def drop_gemm_fwd(X, W, pat_out=None, pat_in=None, alpha=1.0, relu=False, flags=0, out=None, ws=None, stream=None,
+                  I=None, O=None):
+    """Y = X . W^T under the patterns.  With layout flags pass the full sizes I / O explicitly."""
     _dev(X), _dev(W)
-    B, I = X.shape
-    O = W.shape[0]
+    B = X.shape[0]
+    I = (W.shape[1] if not flags & W_COMPACT else None) if I is None else I
+    O = (W.shape[0] if not flags & W_COMPACT else None) if O is None else O
+    assert I is not None and O is not None, "pass I and O with ARD_W_COMPACT"
     dt = _dtype_code(X)
-    Y = torch.empty((B, O), dtype=X.dtype, device=X.device) if out is None else out
+    Oc = kept_count(pat_out, O) if flags & OUT_COMPACT else O
+    Y = torch.empty((B, Oc), dtype=X.dtype, device=X.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), X.device, ws)
     _check(lib().ard_drop_gemm_fwd(dt, B, I, O, X.data_ptr(), W.data_ptr(), Y.data_ptr(), ro, ri,
-                                   float(alpha), int(bool(relu)), ws.data_ptr(), ws.numel(), _stream(stream)))
+                                   float(alpha), int(bool(relu)), int(flags), ws.data_ptr(), ws.numel(), _stream(stream)))
     return Y
 
 
-def drop_gemm_bwd_data(dY, W, pat_out=None, pat_in=None, alpha=1.0, relu_src=None, out=None, ws=None, stream=None):
+def drop_gemm_bwd_data(dY, W, pat_out=None, pat_in=None, alpha=1.0, relu_src=None, flags=0, out=None, ws=None,
+                       stream=None, I=None, O=None):
     _dev(dY), _dev(W)
-    B, O = dY.shape
-    I = W.shape[1]
+    B = dY.shape[0]
+    I = (W.shape[1] if not flags & W_COMPACT else None) if I is None else I
+    O = (W.shape[0] if not flags & W_COMPACT else None) if O is None else O
+    assert I is not None and O is not None, "pass I and O with ARD_W_COMPACT"
     dt = _dtype_code(dY)
-    dX = torch.empty((B, I), dtype=dY.dtype, device=dY.device) if out is None else out
+    Ic = kept_count(pat_in, I) if flags & IN_COMPACT else I
+    dX = torch.empty((B, Ic), dtype=dY.dtype, device=dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
     _check(lib().ard_drop_gemm_bwd_data(dt, B, I, O, dY.data_ptr(), W.data_ptr(), dX.data_ptr(), ro, ri,
-                                        float(alpha), _ptr(relu_src), ws.data_ptr(), ws.numel(), _stream(stream)))
+                                        float(alpha), _ptr(relu_src), int(flags), ws.data_ptr(), ws.numel(),
+                                        _stream(stream)))
     return dX
 
 
-def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, out=None, ws=None, stream=None):
+def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, flags=0, out=None, ws=None,
+                         stream=None, I=None, O=None):
     _dev(dY), _dev(X)
-    B, O = dY.shape
-    I = X.shape[1]
+    B = dY.shape[0]
+    O = dY.shape[1] if O is None else O
+    I = X.shape[1] if I is None else I
     dt = _dtype_code(dY)
     dW = torch.empty((O, I), dtype=dY.dtype, device=dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
     _check(lib().ard_drop_gemm_bwd_weight(dt, B, I, O, dY.data_ptr(), X.data_ptr(), dW.data_ptr(), ro, ri,
-                                          float(alpha), float(beta), ws.data_ptr(), ws.numel(), _stream(stream)))
+                                          float(alpha), float(beta), int(flags), ws.data_ptr(), ws.numel(),
+                                          _stream(stream)))
     return dW
 
 

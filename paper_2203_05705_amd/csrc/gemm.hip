@@ -376,143 +376,241 @@ static int pick_bn(int t) { return t % 128 == 0 ? 128 : (t % 64 == 0 ? 64 : 32);
 
 using namespace ard;
 
+namespace ard {
+
+// Wc[r][c] = W[out(r)][in(c)]
+template <typename T>
+__global__ void compact_weight_kernel(const T* W, long ld, Axis ao, Axis ai, T* Wc) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  const int r = blockIdx.y;
+  if (c < ai.n && r < ao.n) Wc[(long)r * ai.n + c] = W[(long)ax_phys(ao, r) * ld + ax_phys(ai, c)];
+}
+
+static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, const Axis& ao, const Axis& ai,
+                              hipStream_t stream) {
+  if (ao.n <= 0 || ai.n <= 0) return ARD_OK;
+  if (ao.n > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
+  dim3 grid(ceil_div(ai.n, 256), ao.n), block(256);
+  if (dtype == ARD_BF16)
+    hipLaunchKernelGGL(compact_weight_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)W, (long)I, ao, ai,
+                       (uint16_t*)Wc);
+  else
+    hipLaunchKernelGGL(compact_weight_kernel<float>, grid, block, 0, stream, (const float*)W, (long)I, ao, ai,
+                       (float*)Wc);
+  ARD_LAUNCH_CHECK("compact_weight_kernel");
+  return ARD_OK;
+}
+
+static bool is_identity(const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; }
+
+// Row / list pattern layer: resolves the layout flags into operand descriptions.
+struct RowLayer {
+  Axis ao, ai;      // kept output / input neurons
+  bool in_c, out_c; // activations compact on the input / output side
+  const void* Wp;   // weight operand actually multiplied
+  long w_ld;
+  Axis w_rows, w_cols;  // maps into Wp (identity when Wp is compact)
+  bool w_compact;
+};
+
+static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* W, bool need_w, void* ws, size_t ws_bytes,
+                                 hipStream_t stream, RowLayer& L) {
+  if (flags & ~(ARD_IN_COMPACT | ARD_OUT_COMPACT | ARD_W_COMPACT)) return fail(ARD_EINVAL, "unknown flag bits 0x%x", flags);
+  L.ao = axis_of_pattern(a.po, a.O);
+  L.ai = axis_of_pattern(a.pi, a.I);
+  L.in_c = (flags & ARD_IN_COMPACT) != 0;
+  L.out_c = (flags & ARD_OUT_COMPACT) != 0;
+  L.Wp = W;
+  L.w_ld = a.I;
+  L.w_rows = L.ao;
+  L.w_cols = L.ai;
+  L.w_compact = false;
+  if (!need_w) return ARD_OK;
+  const int es = a.dtype == ARD_BF16 ? 2 : 4;
+  if (flags & ARD_W_COMPACT) {
+    L.w_compact = true;
+  } else if (!is_identity(L.ai) && L.ai.n > 0 && L.ao.n > 0) {
+    // the kept input neurons are strided along the contiguous axis of W: gather the kept block once
+    const size_t need = (size_t)L.ao.n * L.ai.n * es;
+    if (!ws || ws_bytes < need) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
+    int32_t st = compact_weight(a.dtype, a.I, W, ws, L.ao, L.ai, stream);
+    if (st) return st;
+    L.Wp = ws;
+    L.w_compact = true;
+  }
+  if (L.w_compact) {
+    L.w_ld = L.ai.n;
+    L.w_rows = axis_identity(L.ao.n);
+    L.w_cols = axis_identity(L.ai.n);
+  }
+  return ARD_OK;
+}
+
+}  // namespace ard
+
 extern "C" size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, int32_t O, const ard_pattern* pat_out,
                                            const ard_pattern* pat_in) {
-  (void)dtype;
   (void)B;
-  (void)pat_in;
-  if (pat_out && pat_out->kind == ARD_PAT_TILE && pat_out->tile_r > 0 && pat_out->tile_c > 0 && I > 0 && O > 0)
+  if (I <= 0 || O <= 0) return 0;
+  if (pat_out && pat_out->kind == ARD_PAT_TILE && pat_out->tile_r > 0 && pat_out->tile_c > 0)
     return tile_ws_bytes(ceil_div(O, pat_out->tile_r), ceil_div(I, pat_out->tile_c));
+  if (pat_in && pat_in->kind != ARD_PAT_NONE && pat_in->kind != ARD_PAT_TILE)
+    return align_up((size_t)kept_count(pat_out, O) * kept_count(pat_in, I) * (dtype == ARD_BF16 ? 2 : 4), 256);
   return 0;
+}
+
+extern "C" int32_t ard_compact_weight(int32_t dtype, int32_t I, int32_t O, const void* W, void* Wc,
+                                      const ard_pattern* pat_out, const ard_pattern* pat_in, void* stream) {
+  LayerArgs a{dtype, 1, I, O, pat_out, pat_in, false, 0, 0};
+  int32_t st = check_layer(a, W, Wc, W);
+  if (st) return st;
+  if (a.tile) return fail(ARD_EINVAL, "ard_compact_weight takes row or list patterns");
+  return compact_weight(dtype, I, W, Wc, axis_of_pattern(pat_out, O), axis_of_pattern(pat_in, I), (hipStream_t)stream);
 }
 
 extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* X, const void* W,
                                      void* Y, const ard_pattern* pat_out, const ard_pattern* pat_in, float alpha,
-                                     int32_t fuse_relu, void* ws, size_t ws_bytes, void* stream_) {
+                                     int32_t fuse_relu, int32_t flags, void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
   int32_t st = check_layer(a, X, W, Y);
   if (st) return st;
   const int ce = chunk_elems(dtype);
   GemmParams P{};
-  P.A.p = X;
-  P.A.ld = I;
-  P.A.r = axis_identity(B);
-  P.B.p = W;
-  P.B.ld = I;
   int max_bn = 0;
-  if (a.tile && try_fast_tile(0, a, X, W, Y, alpha, fuse_relu, stream, st)) return st;
   if (a.tile) {
+    if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
+    if (try_fast_tile(0, a, X, W, Y, alpha, fuse_relu != 0, stream, st)) return st;
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
     if (st) return st;
-    P.B.r = axis_identity(O);
+    P.A = Operand{X, I, axis_identity(B), 0, 0};
+    P.B = Operand{W, I, axis_identity(O), 0, 0};
     P.k = axis_block(L.keep, pat_out->tile_c, 0, I);
     P.kb_ptr = L.rowptr;
     P.kb_ncols = pat_out->tile_r;
     P.kb_bias = -a.TC;
     P.C.cn = axis_identity(O);
+    P.C.ld = O;
+    P.C.fill = 1;
     max_bn = pick_bn(pat_out->tile_r);
   } else {
-    P.B.r = axis_of_pattern(pat_out, O);
-    P.k = axis_of_pattern(pat_in, I);
-    P.C.cn = P.B.r;
+    RowLayer L;
+    st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
+    if (st) return st;
+    // contraction over the kept input neurons; an operand that is already compact ignores the map
+    P.k = L.ai;
+    P.A = Operand{X, L.in_c ? L.ai.n : I, axis_identity(B), 0, L.in_c ? 1 : 0};
+    P.B = Operand{L.Wp, L.w_ld, L.w_rows, 0, L.w_compact ? 1 : 0};
+    if (L.in_c && L.w_compact) P.k = axis_identity(L.ai.n);
+    P.C.cn = L.out_c ? axis_identity(L.ao.n) : L.ao;
+    P.C.ld = L.out_c ? L.ao.n : O;
+    P.C.fill = L.out_c ? 0 : 1;
   }
   P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, true, P.k, ce);
   P.C.p = Y;
-  P.C.ld = O;
   P.C.rm = axis_identity(B);
-  P.C.fill = 1;
   P.C.relu = fuse_relu != 0;
   P.C.alpha = alpha;
   P.C.beta = 0.0f;
   P.M = B;
   P.N = P.B.r.n;
-  if (P.N == 0) return fill_matrix(dtype, Y, (long)B * O, 0.0f, stream);
+  if (P.N == 0) return (flags & ARD_OUT_COMPACT) ? ARD_OK : fill_matrix(dtype, Y, (long)B * O, 0.0f, stream);
   return run_gemm(dtype, true, true, P, max_bn, 0, stream);
 }
 
 extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY, const void* W,
                                           void* dX, const ard_pattern* pat_out, const ard_pattern* pat_in, float alpha,
-                                          const void* relu_src, void* ws, size_t ws_bytes, void* stream_) {
+                                          const void* relu_src, int32_t flags, void* ws, size_t ws_bytes,
+                                          void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
   int32_t st = check_layer(a, dY, W, dX);
   if (st) return st;
   const int ce = chunk_elems(dtype);
   GemmParams P{};
-  P.A.p = dY;
-  P.A.ld = O;
-  P.A.r = axis_identity(B);
-  P.B.p = W;  // element (n = input neuron, k = output neuron) at W[k*I + n]
-  P.B.ld = I;
   int max_bn = 0;
-  if (a.tile && !relu_src && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st)) return st;
   if (a.tile) {
+    if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
+    if (!relu_src && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st)) return st;
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
     if (st) return st;
-    P.B.r = axis_identity(I);
+    P.A = Operand{dY, O, axis_identity(B), 0, 0};
+    P.B = Operand{W, I, axis_identity(I), 0, 0};  // element (n = input neuron, k = output neuron) at W[k*I + n]
     P.k = axis_block(L.csc_rows, pat_out->tile_r, 0, O);
     P.kb_ptr = L.colptr;
     P.kb_ncols = pat_out->tile_c;
     P.kb_bias = 0;
+    P.C.cn = axis_identity(I);
+    P.C.ld = I;
+    P.C.fill = 1;
     max_bn = pick_bn(pat_out->tile_c);
   } else {
-    P.B.r = axis_of_pattern(pat_in, I);
-    P.k = axis_of_pattern(pat_out, O);
+    RowLayer L;
+    st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
+    if (st) return st;
+    // contraction over the kept output neurons
+    P.k = L.ao;
+    P.A = Operand{dY, L.out_c ? L.ao.n : O, axis_identity(B), 0, L.out_c ? 1 : 0};
+    P.B = Operand{L.Wp, L.w_ld, L.w_cols, 0, L.w_compact ? 1 : 0};
+    if (L.out_c && L.w_compact) P.k = axis_identity(L.ao.n);
+    P.C.cn = L.in_c ? axis_identity(L.ai.n) : L.ai;
+    P.C.ld = L.in_c ? L.ai.n : I;
+    P.C.fill = L.in_c ? 0 : 1;
   }
   P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
   P.C.p = dX;
   P.C.relu_src = relu_src;
-  P.C.ld = I;
   P.C.rm = axis_identity(B);
-  P.C.cn = P.B.r;
-  P.C.fill = 1;
   P.C.alpha = alpha;
   P.M = B;
   P.N = P.B.r.n;
-  if (P.N == 0) return fill_matrix(dtype, dX, (long)B * I, 0.0f, stream);
+  if (P.N == 0) return (flags & ARD_IN_COMPACT) ? ARD_OK : fill_matrix(dtype, dX, (long)B * I, 0.0f, stream);
   return run_gemm(dtype, true, false, P, max_bn, 0, stream);
 }
 
 extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY,
                                             const void* X, void* dW, const ard_pattern* pat_out,
-                                            const ard_pattern* pat_in, float alpha, float beta, void* ws,
-                                            size_t ws_bytes, void* stream_) {
+                                            const ard_pattern* pat_in, float alpha, float beta, int32_t flags,
+                                            void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
   int32_t st = check_layer(a, dY, X, dW);
   if (st) return st;
+  const int ce = chunk_elems(dtype);
   GemmParams P{};
-  P.A.p = dY;  // element (m = output neuron, k = batch row) at dY[k*O + m]
-  P.A.ld = O;
-  P.B.p = X;   // element (n = input neuron, k = batch row) at X[k*I + n]
-  P.B.ld = I;
   P.k = axis_identity(B);
-  if (a.tile && beta == 0.0f && try_fast_tile(2, a, dY, X, dW, alpha, 0, stream, st)) return st;
   if (a.tile) {
+    if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
+    if (beta == 0.0f && try_fast_tile(2, a, dY, X, dW, alpha, 0, stream, st)) return st;
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
     if (st) return st;
-    P.A.r = axis_identity(O);
-    P.B.r = axis_identity(I);
+    P.A = Operand{dY, O, axis_identity(O), 0, 0};  // element (m = output neuron, k = batch row) at dY[k*O + m]
+    P.B = Operand{X, I, axis_identity(I), 0, 0};   // element (n = input neuron, k = batch row) at X[k*I + n]
+    P.C.rm = axis_identity(O);
+    P.C.cn = axis_identity(I);
     P.tmask = L.mask;
     P.tm_r = pat_out->tile_r;
     P.tm_c = pat_out->tile_c;
     P.tm_tc = a.TC;
   } else {
-    P.A.r = axis_of_pattern(pat_out, O);
-    P.B.r = axis_of_pattern(pat_in, I);
+    if (flags & ARD_W_COMPACT) return fail(ARD_EINVAL, "ARD_W_COMPACT has no meaning for the weight gradient");
+    RowLayer L;
+    st = resolve_row_layer(a, flags, nullptr, false, ws, ws_bytes, stream, L);
+    if (st) return st;
+    P.A = Operand{dY, L.out_c ? L.ao.n : O, L.out_c ? axis_identity(L.ao.n) : L.ao, 0, 0};
+    P.B = Operand{X, L.in_c ? L.ai.n : I, L.in_c ? axis_identity(L.ai.n) : L.ai, 0, 0};
+    P.C.rm = L.ao;
+    P.C.cn = L.ai;
   }
-  P.A.vec = operand_vec_ok(P.A, false, P.k, chunk_elems(dtype));
-  P.B.vec = operand_vec_ok(P.B, false, P.k, chunk_elems(dtype));
+  P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
+  P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
   P.C.p = dW;
   P.C.ld = I;
-  P.C.rm = P.A.r;
-  P.C.cn = P.B.r;
   P.C.fill = 1;
   P.C.alpha = alpha;
   P.C.beta = beta;

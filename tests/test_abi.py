@@ -64,17 +64,17 @@ def test_host_side_argument_errors():
     # argument checks run before anything touches the device: fake non-null pointers are never dereferenced
     fake = ctypes.c_void_p(0x1000)
     bad = ard.CPattern(ard.PAT_ROW, 3, 4, 0, 0, 0, None, None, None, None, None)      # b > dp
-    code = lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, fake, fake, fake, ctypes.byref(bad), None, 1.0, 0, None, 0, None)
+    code = lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, fake, fake, fake, ctypes.byref(bad), None, 1.0, 0, 0, None, 0, None)
     assert code == -1 and b"b=4" in lib.ard_last_error()
     bad = ard.CPattern(ard.PAT_ROW, 9, 1, 0, 0, 0, None, None, None, None, None)      # dp > number of rows
-    code = lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, fake, fake, fake, ctypes.byref(bad), None, 1.0, 0, None, 0, None)
+    code = lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, fake, fake, fake, ctypes.byref(bad), None, 1.0, 0, 0, None, 0, None)
     assert code == -1
     ok = ard.CPattern(ard.PAT_ROW, 2, 1, 0, 0, 0, None, None, None, None, None)
-    assert lib.ard_drop_gemm_fwd(ard.F32, 0, 8, 8, fake, fake, fake, ctypes.byref(ok), None, 1.0, 0, None, 0, None) == -2
-    assert lib.ard_drop_gemm_fwd(7, 4, 8, 8, fake, fake, fake, ctypes.byref(ok), None, 1.0, 0, None, 0, None) == -3
-    assert lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, None, fake, fake, ctypes.byref(ok), None, 1.0, 0, None, 0, None) == -1
+    assert lib.ard_drop_gemm_fwd(ard.F32, 0, 8, 8, fake, fake, fake, ctypes.byref(ok), None, 1.0, 0, 0, None, 0, None) == -2
+    assert lib.ard_drop_gemm_fwd(7, 4, 8, 8, fake, fake, fake, ctypes.byref(ok), None, 1.0, 0, 0, None, 0, None) == -3
+    assert lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, None, fake, fake, ctypes.byref(ok), None, 1.0, 0, 0, None, 0, None) == -1
     tile = ard.CPattern(ard.PAT_TILE, 2, 1, 64, 64, 0, None, None, None, None, None)
-    assert lib.ard_drop_gemm_fwd(ard.BF16, 4, 128, 128, fake, fake, fake, ctypes.byref(tile), None, 1.0, 0, None, 0, None) == -4
+    assert lib.ard_drop_gemm_fwd(ard.BF16, 4, 128, 128, fake, fake, fake, ctypes.byref(tile), None, 1.0, 0, 0, None, 0, None) == -4
     assert lib.ard_gemm_workspace_bytes(ard.BF16, 4, 128, 128, ctypes.byref(tile), None) > 0
     assert lib.ard_pattern_gen(ctypes.byref(ok), 0, 0, None, None, None, None, None, None, None) == -2
     assert lib.ard_pattern_gen(None, 8, 0, None, None, None, None, None, None, None) == -1

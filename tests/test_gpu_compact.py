@@ -1,0 +1,105 @@
+"""GPU parity of the compact-activation layout: a chain of layers keeps only the kept neurons
+between calls; results must equal the oracle's masked-dense chain gathered on the kept units."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gemm as G
+from oracle import patterns as P
+from oracle import rounding as R
+from paper_2203_05705_amd import binding as ard
+from paper_2203_05705_amd import workloads as WL
+from util import assert_parity, from_vals, stored, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,I,O,po,pi", [(70, 136, 90, (2, 2), (3, 1)), (130, 264, 200, (4, 2), (2, 2)),
+                                          (64, 100, 83, (3, 3), None), (33, 96, 64, None, (5, 2))])
+def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
+    print(f"compact layer dtype={dtype} B={B} I={I} O={O} pat_out={po} pat_in={pi}", flush=True)
+    rng = np.random.default_rng(B + I + O)
+    Xv, Wv, dYv = (stored(rng.standard_normal(s), dtype) for s in ((B, I), (O, I), (B, O)))
+    mo = P.row_mask(O, *po) if po else np.ones(O, np.uint8)
+    mi = P.row_mask(I, *pi) if pi else np.ones(I, np.uint8)
+    ko, ki = P.keep_list(mo), P.keep_list(mi)
+    MW = G.weight_mask_rows(mo, mi)
+    pat_o = ard.Pattern.row(*po) if po else None
+    pat_i = ard.Pattern.row(*pi) if pi else None
+    Xc, dYc = from_vals(Xv[:, ki], dtype), from_vals(dYv[:, ko], dtype)
+    W = from_vals(Wv, dtype)
+    IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
+    refY = G.drop_gemm_fwd(Xv, Wv, MW, mo, 1.5, relu=True)
+    refdX = G.drop_gemm_bwd_data(dYv, Wv, MW, mo, 0.5)
+    refdW = G.drop_gemm_bwd_weight(dYv, Xv, MW, mo)
+    # weight gathered inside the call
+    Y = ard.drop_gemm_fwd(Xc, W, pat_o, pat_i, alpha=1.5, relu=True, flags=IN | OUT)
+    assert Y.shape == (B, len(ko))
+    assert_parity(Y, refY[:, ko], dtype, what="Y compact")
+    dX = ard.drop_gemm_bwd_data(dYc, W, pat_o, pat_i, alpha=0.5, flags=IN | OUT)
+    assert_parity(dX, refdX[:, ki], dtype, what="dX compact")
+    # weight compacted once and shared
+    Wc = ard.compact_weight(W, pat_o, pat_i)
+    assert np.array_equal(to_host(Wc), Wv[np.ix_(ko, ki)])
+    Y2 = ard.drop_gemm_fwd(Xc, Wc, pat_o, pat_i, alpha=1.5, relu=True, flags=IN | OUT | WC, I=I, O=O)
+    assert torch.equal(Y2, Y)
+    dX2 = ard.drop_gemm_bwd_data(dYc, Wc, pat_o, pat_i, alpha=0.5, flags=IN | OUT | WC, I=I, O=O)
+    assert torch.equal(dX2, dX)
+    # mixed: compact in, expanded out (zero-filled)
+    Y3 = ard.drop_gemm_fwd(Xc, W, pat_o, pat_i, alpha=1.5, relu=True, flags=IN)
+    assert_parity(Y3, refY, dtype, zero_mask=(mo == 0)[None, :], what="Y expanded")
+    # weight gradient: compact activations in, full matrix out
+    dW = torch.full((O, I), float("nan"), dtype=W.dtype, device="cuda")
+    ard.drop_gemm_bwd_weight(dYc, Xc, pat_o, pat_i, flags=IN | OUT, out=dW, I=I, O=O)
+    assert_parity(dW, refdW, dtype, zero_mask=(MW == 0), what="dW")
+
+
+def test_config2_mlp_chain_iterations():
+    """BASELINE config 2: MLP 784-2048-2048-10, batch 1024, bf16; patterns of iterations 0..4 from the
+    searched distribution (rate 0.5), every GEMM of the compact chain against the oracle chain."""
+    from oracle import sampler as S
+    from oracle import search as K
+    wl = WL.mlp_chain(seed=2)
+    sizes, B = wl.params["sizes"], wl.params["B"]
+    X0v, dYLv = wl.values("X0"), wl.values("dY")
+    Wv = [wl.values(f"W{l}") for l in (1, 2, 3)]
+    X0, dYL = to_dev(wl.arrays["X0"], "bf16"), to_dev(wl.arrays["dY"], "bf16")
+    W = [to_dev(wl.arrays[f"W{l}"], "bf16") for l in (1, 2, 3)]
+    d, _ = K.search_k(0.5, 8)
+    cdf = [int(c) for c in K.fixed_point_cdf(d)]
+    IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
+    for it in range(5):
+        pats = [S.sample_pattern(cdf, 2, it, layer) for layer in (1, 2)]
+        assert pats == [ard.pattern_sample(cdf, 2, it, layer) for layer in (1, 2)]
+        print(f"iteration {it}: patterns {pats}", flush=True)
+        masks = [P.row_mask(sizes[l + 1], *pats[l]) for l in range(2)]
+        keep = [P.keep_list(m) for m in masks]
+        ref = G.mlp_iteration(X0v, Wv, dYLv, masks, R.to_bf16_values)
+        p1, p2 = ard.Pattern.row(*pats[0]), ard.Pattern.row(*pats[1])
+        # forward, fed with the oracle's stored activations so each product is checked on its own
+        Y1 = ard.drop_gemm_fwd(X0, W[0], p1, None, relu=True, flags=OUT)
+        assert_parity(Y1, ref["Y"][0][:, keep[0]], "bf16", what="Y1")
+        W2c = ard.compact_weight(W[1], p2, p1)
+        Y1o = from_vals(ref["Y"][0][:, keep[0]], "bf16")
+        Y2 = ard.drop_gemm_fwd(Y1o, W2c, p2, p1, relu=True, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
+        assert_parity(Y2, ref["Y"][1][:, keep[1]], "bf16", what="Y2")
+        W3c = ard.compact_weight(W[2], None, p2)
+        Y2o = from_vals(ref["Y"][1][:, keep[1]], "bf16")
+        Y3 = ard.drop_gemm_fwd(Y2o, W3c, None, p2, flags=IN | WC, I=sizes[2], O=sizes[3])
+        assert_parity(Y3, ref["Y"][2], "bf16", what="Y3")
+        # backward
+        dW3 = ard.drop_gemm_bwd_weight(dYL, Y2o, None, p2, flags=IN, I=sizes[2], O=sizes[3])
+        assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3")
+        dY2 = ard.drop_gemm_bwd_data(dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
+        assert_parity(dY2, ref["dY"][1][:, keep[1]], "bf16", what="dY2")
+        dY2o = from_vals(ref["dY"][1][:, keep[1]], "bf16")
+        dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
+        MW2 = G.weight_mask_rows(masks[1], masks[0])
+        assert_parity(dW2, ref["dW"][1], "bf16", zero_mask=(MW2 == 0), what="dW2")
+        dY1 = ard.drop_gemm_bwd_data(dY2o, W2c, p2, p1, relu_src=Y1o, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
+        assert_parity(dY1, ref["dY"][0][:, keep[0]], "bf16", what="dY1")
+        dY1o = from_vals(ref["dY"][0][:, keep[0]], "bf16")
+        dW1 = ard.drop_gemm_bwd_weight(dY1o, X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
+        assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape), what="dW1")
+    torch.cuda.synchronize()
