@@ -491,6 +491,7 @@ __global__ void scale_fill_kernel(T* p, long n, float beta) {
 
 // Host-side dispatch: picks the workgroup tile for the problem and launches.
 // max_bn: the widest column tile the contraction lists allow (tile pattern), or 0.
-int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int max_bm, hipStream_t stream);
+int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int max_bm, hipStream_t stream,
+                 void* ws = nullptr, size_t ws_bytes = 0);
 
 }  // namespace ard

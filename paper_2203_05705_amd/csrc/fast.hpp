@@ -1,7 +1,9 @@
 // Large-tile bf16 path of the gathered GEMM for gfx950.
 //
-// Workgroup: 8 wavefronts (two per SIMD), tile 256 x BN x 64 with BN = 256 (waves 2 x 4, each
-// 128 x 64) or BN = 128 (waves 4 x 2, each 64 x 64), MFMA 32x32x16 bf16.
+// Workgroup tiles BM x BN x 64 of 32x32x16 bf16 MFMA tiles: 256x256 and 256x128 with 8
+// wavefronts (two per SIMD), 128x128, 128x64 and 64x64 with 4 wavefronts for products too small
+// to fill 256 CUs with large tiles; optional split of the contraction over blockIdx.y with
+// fp32 partial sums that a finishing kernel reduces (fixed split: deterministic).
 //
 // Operand staging uses LDS-direct loads (global_load_lds_dwordx4): a wavefront instruction
 // moves 64 x 16 bytes from per-lane global addresses into 1 KiB of consecutive LDS with no
@@ -57,12 +59,13 @@ struct FastParams {
   Axis am, bn, k;  // plain mode: compact -> physical rows of A (M), rows of B (N), contraction
   ClassTab tab;
   int c_rows_mapped, c_cols_mapped;  // output rows / columns go through the M / N map (else identity)
-  float alpha;
-  int relu;
+  float alpha, beta;
+  int relu, out_f32;
+  const uint16_t* relu_src;  // optional, same layout as C
+  float* part;               // != NULL: write fp32 partial sums part[split][M][N] instead of C
+  int splits;
   int M, N, tiles_m, tiles_n, group_m, total_tiles;
 };
-
-constexpr int F_BM = 256, F_NT = 512;
 
 #define ARD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 #define ARD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
@@ -78,10 +81,11 @@ __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
   return (k.list[q] + k.off) * k.bs + (ks - q * k.bs);
 }
 
-template <bool KC, int ROWS> struct DirectLoader;
+template <bool KC, int ROWS, int NW> struct DirectLoader;
 
-template <int ROWS> struct DirectLoader<true, ROWS> {
-  static constexpr int NI = ROWS / 64;  // instructions per wavefront and stage (8 rows each)
+template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
+  static constexpr int NI = ROWS / 8 / NW;  // instructions per wavefront and stage (8 rows each)
+  static_assert(NI >= 1, "tile too small for the workgroup");
   const uint16_t* base;
   int goff[NI];  // element offset of this lane's chunk for instruction j, without the slab start
   __device__ static __forceinline__ int chunk_k(int lane, int wave, int j) {
@@ -112,11 +116,20 @@ template <int ROWS> struct DirectLoader<true, ROWS> {
   }
 };
 
-template <int ROWS> struct DirectLoader<false, ROWS> {
-  static constexpr int CPR = ROWS / 8;   // 16-byte chunks per contraction row
-  static constexpr int KPI = 64 / CPR;   // contraction rows per instruction
-  static constexpr int NI = 8 / KPI;     // instructions per wavefront and stage
+// swizzle of an MC tile: chunk c of contraction row k sits at position c ^ mc_swz(k).  Rows are
+// ROWS*2 bytes apart; the XOR makes the four rows a transposing read touches land in different
+// banks (rows of 256+ bytes all start at the same bank, rows of 128 bytes alternate).
+template <int ROWS>
+__device__ __forceinline__ int mc_swz(int k) {
+  return ROWS >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1);
+}
+
+template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
+  static constexpr int CPR = ROWS / 8;         // 16-byte chunks per contraction row
+  static constexpr int KPI = 64 / CPR;         // contraction rows per instruction
+  static constexpr int NI = 64 / KPI / NW;     // instructions per wavefront and stage
   static constexpr int NCO = KPI == 2 ? 2 : 1;
+  static_assert(NI >= 1, "tile too small for the workgroup");
   const uint16_t* base;
   int ld;
   int coff[NCO];  // physical column of this lane's chunk (per instruction parity when KPI == 2)
@@ -125,8 +138,8 @@ template <int ROWS> struct DirectLoader<false, ROWS> {
     ld = ld_;
 #pragma unroll
     for (int par = 0; par < NCO; ++par) {
-      const int k3 = (KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR) & 3;  // (k & 3) of the row this lane fills
-      const int c = (lane % CPR) ^ (4 * k3);
+      const int kl = KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR;  // low bits of the row this lane fills
+      const int c = (lane % CPR) ^ mc_swz<ROWS>(kl);
       const int j = row0 + c * 8;
       int ph = j + 8 <= r.n ? ax_phys(r, j) : 0;
       coff[par] = ph + 8 <= r.nphys ? ph : 0;
@@ -155,7 +168,7 @@ __device__ __forceinline__ int mc_frag_base(int tile_col0, int lane) {
   const int s = lane & 15, G = lane >> 4;
   const int g = G >> 1, jhalf = G & 1;
   const int c = (tile_col0 >> 3) + 2 * jhalf + ((s & 3) >> 1);
-  const int pc = c ^ (4 * ((s >> 2) & 3));
+  const int pc = c ^ mc_swz<ROWS>(s >> 2);
   return (g * 8 + (s >> 2)) * (ROWS * 2) + pc * 16 + 8 * (s & 1);
 }
 
@@ -189,10 +202,11 @@ __device__ __forceinline__ bf16x8_t frag_value(const Frag& f) {
   return __builtin_bit_cast(bf16x8_t, t);
 }
 
-template <bool A_KC, bool B_KC, int BN>
-__global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
-  constexpr int WGN = BN == 256 ? 4 : 2, WGM = 8 / WGN;
+template <bool A_KC, bool B_KC, int F_BM, int BN, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P) {
+  constexpr int WGN = (NW == 8 && BN == 256) ? 4 : 2, WGM = NW / WGN;
   constexpr int WTM = F_BM / WGM, WTN = BN / WGN;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must hold whole MFMA tiles");
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int OPA = F_BM * LDS_ROW_U4, OPB = BN * LDS_ROW_U4;  // u4 entries of one operand stage
   extern __shared__ uint4 lds[];
@@ -255,8 +269,8 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
       for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
 
   if (Kn > 0) {
-    DirectLoader<A_KC, F_BM> la;
-    DirectLoader<B_KC, BN> lb;
+    DirectLoader<A_KC, F_BM, NW> la;
+    DirectLoader<B_KC, BN, NW> lb;
     la.init(P.A, P.lda, am, m0, lane, wave);
     lb.init(P.B, P.ldb, bn, n0, lane, wave);
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
@@ -284,13 +298,13 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
         baddr[in][0] = lds_base + (unsigned)(2 * OPA) * 16u + (unsigned)mc_frag_base<BN>(wn * WTN + in * 32, lane);
       }
     }
-    const int S = (Kn + 63) >> 6;
+    // contraction steps of this workgroup (a share of them when the contraction is split)
+    const int S_all = (Kn + 63) >> 6;
+    const int s_lo = (int)((long)blockIdx.y * S_all / P.splits), s_hi = (int)((long)(blockIdx.y + 1) * S_all / P.splits);
+    const int S = s_hi - s_lo;
     auto load_stage = [&](int it, int buf) {
-#if defined(ARD_ABL) && (ARD_ABL & 1)
-      if (it > 1) return;
-#endif
-      const int krem = Kn - it * 64;
-      const int ks = fast_kslab(kax, it * 64);
+      const int krem = Kn - (s_lo + it) * 64;
+      const int ks = fast_kslab(kax, (s_lo + it) * 64);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
       la.issue(lds + buf * OPA, ks, krem, kax.nphys, tail, lane, wave);
       lb.issue(lds + 2 * OPA + buf * OPB, ks, krem, kax.nphys, tail, lane, wave);
@@ -299,9 +313,6 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
     Frag fa[2][TM], fb[2][TN];
     // issue the fragment reads of slice Q of stage BUF (both compile-time: immediates) into `set`
     auto issue = [&](auto bufc, auto qc, int set) {
-#if defined(ARD_ABL) && (ARD_ABL & 4)
-      return;
-#endif
       constexpr int BUF = decltype(bufc)::value, Q = decltype(qc)::value;
       constexpr int SA = BUF * OPA * 16, SB = BUF * OPB * 16;  // byte offsets of the stage
 #pragma unroll
@@ -331,9 +342,6 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
       for (int in = 0; in < TN; ++in) frag_wait<B_KC>(fb[set][in]);
     };
     auto mma = [&](int set) {
-#if defined(ARD_ABL) && (ARD_ABL & 2)
-      return;
-#endif
 #pragma unroll
       for (int im = 0; im < TM; ++im)
 #pragma unroll
@@ -372,14 +380,16 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
       }
       mma(1);
     };
-    load_stage(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (S > 1) load_stage(1, 1);
-    issue(I0{}, I0{}, 0);
-    for (int it = 0; it < S; it += 2) {
-      step(I0{}, it);
-      if (it + 1 < S) step(I1{}, it + 1);
+    if (S > 0) {
+      load_stage(0, 0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (S > 1) load_stage(1, 1);
+      issue(I0{}, I0{}, 0);
+      for (int it = 0; it < S; it += 2) {
+        step(I0{}, it);
+        if (it + 1 < S) step(I1{}, it + 1);
+      }
     }
   }
 
@@ -388,12 +398,34 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
   // 32x32 tile places all of its rows (columns).
   const int nlim = P.c_cols_mapped ? bn.n : P.N, mlim = P.c_rows_mapped ? am.n : P.M;
   const int nphys = P.c_cols_mapped ? bn.nphys : P.N, mphys = P.c_rows_mapped ? am.nphys : P.M;
+  // (the 256 x 256 tile has no registers to spare: it only stores plain bf16 results)
+  constexpr bool GENERAL_OUT = !(F_BM == 256 && BN == 256);
+  if (GENERAL_OUT && P.part) {
+    // fp32 partial sums of this share of the contraction, compact [M x N]
+    float* part = P.part + (long)blockIdx.y * P.M * P.N;
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      const int j = n0 + wn * WTN + in * 32 + (lane & 31);
+      if (j >= P.N) continue;
+#pragma unroll
+      for (int im = 0; im < TM; ++im) {
+        const int i0 = m0 + wm * WTM + im * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = i0 + 8 * (v >> 2) + (v & 3);
+          if (i < P.M) part[(long)i * P.N + j] = acc[im][in][v];
+        }
+      }
+    }
+    return;
+  }
   int prow[TM];
 #pragma unroll
   for (int im = 0; im < TM; ++im) {
     const int i0 = m0 + wm * WTM + im * 32;
     prow[im] = i0 < mlim ? (P.c_rows_mapped ? ax_phys(am, i0) : i0) : mphys;
   }
+  const bool plain_bf16 = !GENERAL_OUT || (!P.out_f32 && P.beta == 0.0f && !P.relu_src);
 #pragma unroll
   for (int in = 0; in < TN; ++in) {
     const int j0 = n0 + wn * WTN + in * 32;
@@ -402,10 +434,25 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
     if (pc >= nphys) continue;
 #pragma unroll
     for (int im = 0; im < TM; ++im) {
+      const int rbase = prow[im] + 4 * (lane >> 5);
+      if (!plain_bf16) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = rbase + 8 * (v >> 2) + (v & 3);
+          if (r >= mphys) continue;
+          const long idx = (long)r * P.ldc + pc;
+          float x = P.alpha * acc[im][in][v];
+          if (P.beta != 0.0f) x += P.beta * (P.out_f32 ? reinterpret_cast<const float*>(P.C)[idx] : bf16_bits_to_f32(P.C[idx]));
+          if (P.relu) x = fmaxf(x, 0.0f);
+          if (P.relu_src) x = bf16_bits_to_f32(P.relu_src[idx]) > 0.0f ? x : 0.0f;
+          if (P.out_f32) reinterpret_cast<float*>(P.C)[idx] = x;
+          else P.C[idx] = f32_to_bf16_bits(x);
+        }
+        continue;
+      }
       // Adjacent lanes hold adjacent columns of the same row.  Rows come in pairs (v, v+1):
       // the even lane takes the odd lane's value of row v, the odd lane the even lane's value
       // of row v+1 (one DPP swap), and each stores one packed 32-bit word.
-      const int rbase = prow[im] + 4 * (lane >> 5);
       const bool odd = lane & 1;
       uint16_t* dst = P.C + (long)rbase * P.ldc + (pc & ~1);
       const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0);
@@ -431,6 +478,57 @@ __global__ __launch_bounds__(F_NT) void gemm256_kernel(const FastParams P) {
         }
       }
     }
+  }
+}
+
+// Finishing pass of a product whose result could not be stored by the GEMM itself (split
+// contraction, or an output scattered at element granularity with dropped positions to zero):
+// sums the fp32 partials part[split][M][N] and writes the output through its maps, walking the
+// PHYSICAL output when dropped positions have to be written.
+__device__ __forceinline__ int ax_inverse(const Axis& a, int p) {
+  // compact index of physical index p, or -1
+  if (a.kind == AX_AFFINE) {
+    const int d = p - a.off;
+    if (d < 0 || d % a.step) return -1;
+    const int j = d / a.step;
+    return j < a.n ? j : -1;
+  }
+  if (a.kind == AX_LIST) {
+    int lo = 0, hi = a.n - 1;
+    while (lo <= hi) {
+      const int mid = (lo + hi) >> 1, v = a.list[mid];
+      if (v == p) return mid;
+      if (v < p) lo = mid + 1;
+      else hi = mid - 1;
+    }
+    return -1;
+  }
+  return -1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int splits, int M, int N, OutMat C) {
+  const int rows = C.fill ? C.rm.nphys : M, cols = C.fill ? C.cn.nphys : N;
+  const long total = (long)rows * cols;
+  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+    const int r = (int)(e / cols), c = (int)(e - (long)r * cols);
+    int i, j, pr, pc;
+    if (C.fill) {
+      pr = r, pc = c;
+      i = ax_inverse(C.rm, r);
+      j = ax_inverse(C.cn, c);
+    } else {
+      i = r, j = c;
+      pr = ax_phys(C.rm, r);
+      pc = ax_phys(C.cn, c);
+    }
+    float x = 0.0f;
+    if (i >= 0 && j >= 0) {
+      const float* p = part + (long)i * N + j;
+      for (int s = 0; s < splits; ++s) x += p[(long)s * M * N];
+      x *= C.alpha;
+    }
+    store_out<T>(C, (long)pr * C.ld + pc, x, true);
   }
 }
 

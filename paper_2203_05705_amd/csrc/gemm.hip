@@ -49,7 +49,7 @@ template <typename T>
 static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipStream_t stream) {
   if (const char* f = getenv("ARD_FORCE_TILE")) {  // development knob: force a workgroup tile
     int v = atoi(f);
-    if (v == 256) return launch_cfg<T, 256, 256, 2, 4>(a_kc, b_kc, P, stream);
+    if (v == 256) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
     if (v == 128) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
     if (v == 64) return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
   }
@@ -60,11 +60,13 @@ static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipSt
   return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
 }
 
-static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, int32_t& st);
+static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, void* ws, size_t ws_bytes,
+                       hipStream_t stream, int32_t& st);
 
-int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int /*max_bm*/, hipStream_t stream) {
+int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int /*max_bm*/, hipStream_t stream,
+                 void* ws, size_t ws_bytes) {
   int32_t st_fast = ARD_OK;
-  if (try_fast_plain(dtype, a_kc, b_kc, P, stream, st_fast)) return st_fast;
+  if (try_direct(dtype, a_kc, b_kc, P, ws, ws_bytes, stream, st_fast)) return st_fast;
   if (dtype == ARD_BF16) return run_gemm_t<uint16_t>(a_kc, b_kc, P, max_bn, stream);
   if (dtype == ARD_F32) return run_gemm_t<float>(a_kc, b_kc, P, max_bn, stream);
   return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
@@ -81,23 +83,23 @@ static int gcd_int(int a, int b) {
   return a;
 }
 
-template <int BN>
-static int32_t launch_fast_bn(bool a_kc, bool b_kc, FastParams& F, int grid_blocks, hipStream_t stream) {
-  dim3 grid((unsigned)grid_blocks), block(F_NT);
-  const size_t lds_bytes = (size_t)2 * (F_BM + BN) * LDS_ROW_U4 * sizeof(uint4);
+template <int BM, int BN, int NW>
+static int32_t launch_direct_cfg(bool a_kc, bool b_kc, FastParams& F, int grid_x, hipStream_t stream) {
+  dim3 grid((unsigned)grid_x, (unsigned)F.splits), block(64 * NW);
+  const size_t lds_bytes = (size_t)2 * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   auto go = [&](auto kernel) -> int32_t {
     static thread_local bool raised = false;
-    if (!raised) {
+    if (!raised && lds_bytes >= 65536) {
       ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
       raised = true;
     }
     hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, F);
-    ARD_LAUNCH_CHECK("gemm256_kernel");
+    ARD_LAUNCH_CHECK("gemm_direct_kernel");
     return ARD_OK;
   };
-  if (a_kc && b_kc) return go(gemm256_kernel<true, true, BN>);
-  if (a_kc && !b_kc) return go(gemm256_kernel<true, false, BN>);
-  if (!a_kc && !b_kc) return go(gemm256_kernel<false, false, BN>);
+  if (a_kc && b_kc) return go(gemm_direct_kernel<true, true, BM, BN, NW>);
+  if (a_kc && !b_kc) return go(gemm_direct_kernel<true, false, BM, BN, NW>);
+  if (!a_kc && !b_kc) return go(gemm_direct_kernel<false, false, BM, BN, NW>);
   return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
 }
 
@@ -117,40 +119,81 @@ static int fast_grid(const FastParams& F) {
   return worst * 8;
 }
 
-static int32_t launch_fast(bool a_kc, bool b_kc, FastParams& F, int bn, hipStream_t stream) {
+struct TileCfg {
+  int bm, bn;
+};
+static const TileCfg kTileCfgs[] = {{256, 256}, {256, 128}, {128, 128}, {128, 64}, {64, 64}};
+
+static int32_t launch_direct(bool a_kc, bool b_kc, FastParams& F, int bm, int bn, hipStream_t stream) {
   if (F.total_tiles <= 0) return ARD_OK;
+  if (F.splits < 1) F.splits = 1;
   // an XCD's share should be about square in tiles: bands of group_m tile rows
   const int per_xcd = ceil_div(F.total_tiles, 8);
   int gm = 1;
   while (gm * gm * 2 <= per_xcd && gm < 8) gm *= 2;
   F.group_m = gm;
   const int grid = fast_grid(F);
-  if (bn == 128) return launch_fast_bn<128>(a_kc, b_kc, F, grid, stream);
-  return launch_fast_bn<256>(a_kc, b_kc, F, grid, stream);
+  if (bm == 256 && bn == 256) return launch_direct_cfg<256, 256, 8>(a_kc, b_kc, F, grid, stream);
+  if (bm == 256 && bn == 128) return launch_direct_cfg<256, 128, 8>(a_kc, b_kc, F, grid, stream);
+  if (bm == 128 && bn == 128) return launch_direct_cfg<128, 128, 4>(a_kc, b_kc, F, grid, stream);
+  if (bm == 128 && bn == 64) return launch_direct_cfg<128, 64, 4>(a_kc, b_kc, F, grid, stream);
+  if (bm == 64 && bn == 64) return launch_direct_cfg<64, 64, 4>(a_kc, b_kc, F, grid, stream);
+  return fail(ARD_EUNSUPPORTED, "tile configuration not built");
 }
 
 static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0 && ld < (1L << 30); }
 
-// Large dense-like products: identity output maps, 16-byte loads on both operands.
-static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, int32_t& st) {
+// bf16 products whose operands can be fetched with 16-byte loads go through the LDS-direct
+// kernels; results that the kernel cannot store itself (split contraction, element-level
+// scatter with zero fill) pass through fp32 partials in the workspace and a finishing kernel.
+static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, void* ws, size_t ws_bytes,
+                       hipStream_t stream, int32_t& st) {
   if (dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
-  if (!P.A.vec || !P.B.vec || P.A.kdense || P.B.kdense || P.kb_ptr || P.tmask) return false;
-  if (P.k.kind != AX_AFFINE || P.k.step != 1 || (P.k.off % 8) || (P.k.n % 8) || (P.k.nphys % 8)) return false;
-  const OutMat& C = P.C;
-  if (C.out_f32 || C.beta != 0.0f || C.relu_src || C.plane || C.fill) return false;
+  if (!P.A.vec || !P.B.vec || P.kb_ptr || P.tmask) return false;
+  Axis k = P.k;
   auto ident = [](const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; };
-  if (!ident(C.rm) || !ident(C.cn)) return false;
-  if (!fast_ptr_ok(P.A.p, P.A.ld) || !fast_ptr_ok(P.B.p, P.B.ld) || (C.ld % 8)) return false;
+  if (P.A.kdense && P.B.kdense) k = axis_identity(P.k.n);
+  else if ((P.A.kdense || P.B.kdense) && !ident(P.k)) return false;
+  if (k.kind != AX_AFFINE || k.step != 1 || (k.off % 8) || (k.n % 8)) return false;
+  const OutMat& C = P.C;
+  if (C.plane) return false;
+  if (!fast_ptr_ok(P.A.p, P.A.ld) || !fast_ptr_ok(P.B.p, P.B.ld)) return false;
   if (!a_kc && (P.A.r.n % 8)) return false;
   if (!b_kc && (P.B.r.n % 8)) return false;
   if ((long)P.A.r.nphys * P.A.ld >= (1L << 31) || (long)P.B.r.nphys * P.B.ld >= (1L << 31)) return false;
-  int bn = 256;
-  long tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, 256);
-  if (tiles < 200) {
-    bn = 128;
-    tiles = (long)ceil_div(P.M, F_BM) * ceil_div(P.N, 128);
+  if ((long)P.M * P.N >= (1L << 31)) return false;
+  const bool direct_out = ident(C.rm) && ident(C.cn);
+  if (!direct_out) {
+    auto inv_ok = [](const Axis& a) { return a.kind == AX_AFFINE || a.kind == AX_LIST; };
+    if (!inv_ok(C.rm) || !inv_ok(C.cn)) return false;
   }
-  if (tiles < 96) return false;
+  // workgroup tile: the largest one that still fills the chip; then split the contraction of
+  // products with too few tiles
+  const int steps = ceil_div(k.n, 64);
+  int bm = 64, bn = 64;
+  long tiles = 0;
+  const bool plain_out = direct_out && !C.out_f32 && C.beta == 0.0f && !C.relu_src;
+  for (const TileCfg& c : kTileCfgs) {
+    if (c.bm == 256 && c.bn == 256 && !plain_out) continue;  // that tile only stores plain bf16
+    tiles = (long)ceil_div(P.M, c.bm) * ceil_div(P.N, c.bn);
+    bm = c.bm, bn = c.bn;
+    if (tiles >= 220) break;
+  }
+  if (tiles >= (1L << 24)) return false;
+  int splits = 1;
+  if (tiles < 160 && steps >= 4) {
+    splits = (int)(320 / tiles);
+    if (splits > steps / 2) splits = steps / 2;
+    if (splits > 8) splits = 8;
+    if (splits < 1) splits = 1;
+  }
+  if (bm == 256 && bn == 256) splits = 1;
+  size_t need = (splits > 1 || !direct_out) ? (size_t)splits * P.M * P.N * 4 : 0;
+  if (need > ws_bytes || (need && !ws)) {
+    if (!direct_out) return false;  // no room for the partials: the general kernel scatters itself
+    splits = 1;
+    need = 0;
+  }
   FastParams F{};
   F.A = (const uint16_t*)P.A.p;
   F.B = (const uint16_t*)P.B.p;
@@ -160,15 +203,28 @@ static bool try_fast_plain(int32_t dtype, bool a_kc, bool b_kc, const GemmParams
   F.ldc = (int)C.ld;
   F.am = P.A.r;
   F.bn = P.B.r;
-  F.k = P.k;
+  F.k = k;
   F.alpha = C.alpha;
+  F.beta = C.beta;
   F.relu = C.relu;
+  F.out_f32 = C.out_f32;
+  F.relu_src = (const uint16_t*)C.relu_src;
+  F.part = need ? (float*)ws : nullptr;
+  F.splits = splits;
   F.M = P.M;
   F.N = P.N;
-  F.tiles_m = ceil_div(P.M, F_BM);
+  F.tiles_m = ceil_div(P.M, bm);
   F.tiles_n = ceil_div(P.N, bn);
   F.total_tiles = (int)tiles;
-  st = launch_fast(a_kc, b_kc, F, bn, stream);
+  st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  if (st || !need) return true;
+  const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
+  long blocks = (total + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws, splits,
+                     P.M, P.N, C);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) st = fail(ARD_EHIP, "launch of gemm_finish_kernel failed: %s", hipGetErrorString(e));
   return true;
 }
 
@@ -269,7 +325,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   const int g = gcd_int(TC, dp), Pp = dp / g;
   FastParams F{};
   ClassTab& t = F.tab;
-  const int tiles_b = ceil_div(B, F_BM);
+  const int tiles_b = ceil_div(B, 256);
   auto cnt = [](int total, int first, int step) { return first < total ? (total - first + step - 1) / step : 0; };
   if (op == 0) {
     if ((256 % x) || (y % 64) || Pp > F_MAXCLS) return false;
@@ -324,7 +380,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
       const int t0 = (int)((((long)o - (long)c * TC) % dp + dp) % dp);
       t.n_off[c] = t0;
       t.n_cnt[c] = cnt(TC, t0, dp);
-      t.mblk[c] = ceil_div(t.m_cnt[c], F_BM / x);
+      t.mblk[c] = ceil_div(t.m_cnt[c], 256 / x);
     }
     F.A = (const uint16_t*)Ap, F.lda = O;
     F.B = (const uint16_t*)Bp, F.ldb = I;
@@ -338,7 +394,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     int total = 0;
     heavy = 0;
     for (int c = 0; c < t.ncls; ++c) {
-      const int mb = op == 2 ? ceil_div(t.m_cnt[c], F_BM / x) : tiles_b;
+      const int mb = op == 2 ? ceil_div(t.m_cnt[c], 256 / x) : tiles_b;
       const int nb = ceil_div(t.n_cnt[c], bn / t.n_bs);
       t.mblk[c] = mb > 0 ? mb : 1;
       t.nblk[c] = (t.n_cnt[c] > 0 && mb > 0) ? mb * nb : 0;
@@ -366,7 +422,8 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
       return true;
     }
   }
-  st = launch_fast(op != 2, op == 0, F, bn, stream);
+  F.splits = 1;
+  st = launch_direct(op != 2, op == 0, F, 256, bn, stream);
   return true;
 }
 
@@ -411,6 +468,7 @@ struct RowLayer {
   long w_ld;
   Axis w_rows, w_cols;  // maps into Wp (identity when Wp is compact)
   bool w_compact;
+  size_t ws_used;  // bytes of the workspace taken by the gathered weight
 };
 
 static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* W, bool need_w, void* ws, size_t ws_bytes,
@@ -425,6 +483,7 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
   L.w_rows = L.ao;
   L.w_cols = L.ai;
   L.w_compact = false;
+  L.ws_used = 0;
   if (!need_w) return ARD_OK;
   const int es = a.dtype == ARD_BF16 ? 2 : 4;
   if (flags & ARD_W_COMPACT) {
@@ -437,6 +496,7 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
     if (st) return st;
     L.Wp = ws;
     L.w_compact = true;
+    L.ws_used = align_up(need, 256);
   }
   if (L.w_compact) {
     L.w_ld = L.ai.n;
@@ -454,9 +514,16 @@ extern "C" size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, 
   if (I <= 0 || O <= 0) return 0;
   if (pat_out && pat_out->kind == ARD_PAT_TILE && pat_out->tile_r > 0 && pat_out->tile_c > 0)
     return tile_ws_bytes(ceil_div(O, pat_out->tile_r), ceil_div(I, pat_out->tile_c));
-  if (pat_in && pat_in->kind != ARD_PAT_NONE && pat_in->kind != ARD_PAT_TILE)
-    return align_up((size_t)kept_count(pat_out, O) * kept_count(pat_in, I) * (dtype == ARD_BF16 ? 2 : 4), 256);
-  return 0;
+  // gathered kept block of W, then room for fp32 partial results of up to 8 contraction splits
+  const size_t Ok = (size_t)kept_count(pat_out, O), Ik = (size_t)kept_count(pat_in, I), Bn = B > 0 ? (size_t)B : 0;
+  size_t bytes = 0;
+  if (pat_in && pat_in->kind != ARD_PAT_NONE) bytes += align_up(Ok * Ik * (dtype == ARD_BF16 ? 2 : 4), 256);
+  size_t big = Bn * Ok;
+  if (Bn * Ik > big) big = Bn * Ik;
+  if (Ok * Ik > big) big = Ok * Ik;
+  size_t part = big * 4 * 8;
+  if (part > ((size_t)256 << 20)) part = (size_t)256 << 20;
+  return bytes + part;
 }
 
 extern "C" int32_t ard_compact_weight(int32_t dtype, int32_t I, int32_t O, const void* W, void* Wc,
@@ -478,6 +545,7 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
   const int ce = chunk_elems(dtype);
   GemmParams P{};
   int max_bn = 0;
+  size_t ws_used = 0;
   if (a.tile) {
     if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
     if (try_fast_tile(0, a, X, W, Y, alpha, fuse_relu != 0, stream, st)) return st;
@@ -503,6 +571,7 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
     P.A = Operand{X, L.in_c ? L.ai.n : I, axis_identity(B), 0, L.in_c ? 1 : 0};
     P.B = Operand{L.Wp, L.w_ld, L.w_rows, 0, L.w_compact ? 1 : 0};
     if (L.in_c && L.w_compact) P.k = axis_identity(L.ai.n);
+    ws_used = L.ws_used;
     P.C.cn = L.out_c ? axis_identity(L.ao.n) : L.ao;
     P.C.ld = L.out_c ? L.ao.n : O;
     P.C.fill = L.out_c ? 0 : 1;
@@ -517,7 +586,8 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
   P.M = B;
   P.N = P.B.r.n;
   if (P.N == 0) return (flags & ARD_OUT_COMPACT) ? ARD_OK : fill_matrix(dtype, Y, (long)B * O, 0.0f, stream);
-  return run_gemm(dtype, true, true, P, max_bn, 0, stream);
+  return run_gemm(dtype, true, true, P, max_bn, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
+                  a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
 }
 
 extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY, const void* W,
@@ -531,6 +601,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
   const int ce = chunk_elems(dtype);
   GemmParams P{};
   int max_bn = 0;
+  size_t ws_used = 0;
   if (a.tile) {
     if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
     if (!relu_src && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st)) return st;
@@ -556,6 +627,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
     P.A = Operand{dY, L.out_c ? L.ao.n : O, axis_identity(B), 0, L.out_c ? 1 : 0};
     P.B = Operand{L.Wp, L.w_ld, L.w_cols, 0, L.w_compact ? 1 : 0};
     if (L.out_c && L.w_compact) P.k = axis_identity(L.ao.n);
+    ws_used = L.ws_used;
     P.C.cn = L.in_c ? axis_identity(L.ai.n) : L.ai;
     P.C.ld = L.in_c ? L.ai.n : I;
     P.C.fill = L.in_c ? 0 : 1;
@@ -569,7 +641,8 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
   P.M = B;
   P.N = P.B.r.n;
   if (P.N == 0) return (flags & ARD_IN_COMPACT) ? ARD_OK : fill_matrix(dtype, dX, (long)B * I, 0.0f, stream);
-  return run_gemm(dtype, true, false, P, max_bn, 0, stream);
+  return run_gemm(dtype, true, false, P, max_bn, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
+                  a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
 }
 
 extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY,
@@ -617,7 +690,7 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   P.M = P.A.r.n;
   P.N = P.B.r.n;
   if (P.M == 0 || P.N == 0) return fill_matrix(dtype, dW, (long)O * I, beta, stream);
-  return run_gemm(dtype, false, false, P, 0, 0, stream);
+  return run_gemm(dtype, false, false, P, 0, 0, stream, a.tile ? nullptr : ws, a.tile ? 0 : ws_bytes);
 }
 
 namespace ard {
