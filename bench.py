@@ -55,7 +55,8 @@ class MlpChain:
         self.Y = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2, 3)]
         self.dYh = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2)]   # gradient at hidden outputs
         self.dW = [torch.empty_like(w) for w in self.W]
-        self.Wc = [torch.empty_like(self.W[1]), torch.empty_like(self.W[2])]   # kept blocks of W2, W3
+        self.Wc = [torch.empty(((w.shape[0] + 7) & ~7, (w.shape[1] + 7) & ~7), dtype=dt, device="cuda")
+                   for w in self.W[1:]]   # kept blocks of W2, W3 (axes padded to multiples of 8)
         self.ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
         self.stream = torch.cuda.current_stream().cuda_stream
         self._keep = []

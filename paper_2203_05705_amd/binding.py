@@ -223,12 +223,30 @@ def kept_count(pat: Optional[Pattern], units: int) -> int:
     return -(-(units - o) // pat.dp) if units > o else 0
 
 
+def pad8(n: int) -> int:
+    """Compact matrices store their kept-unit axes rounded up to a multiple of 8 (zero filled)."""
+    return (n + 7) & ~7
+
+
+def pad_compact(t: torch.Tensor) -> torch.Tensor:
+    """[B, count] -> [B, pad8(count)] with zero padding: the compact activation layout."""
+    B, n = t.shape
+    out = torch.zeros((B, pad8(n)), dtype=t.dtype, device=t.device)
+    out[:, :n] = t
+    return out
+
+
+def _check_compact(t, count, what):
+    if t.shape[1] != pad8(count) or not t.is_contiguous():
+        raise ValueError(f"{what}: a compact activation has pad8(kept)={pad8(count)} contiguous columns, got {tuple(t.shape)}")
+
+
 def compact_weight(W, pat_out=None, pat_in=None, out=None, stream=None):
-    """Wc[O' x I'] = W[kept o, kept i]."""
+    """Wc[pad8(O') x pad8(I')]: W[kept o, kept i] in the top-left corner, zeros elsewhere."""
     _dev(W)
     O, I = W.shape
     Ok, Ik = kept_count(pat_out, O), kept_count(pat_in, I)
-    Wc = torch.empty((Ok, Ik), dtype=W.dtype, device=W.device) if out is None else out
+    Wc = torch.empty((pad8(Ok), pad8(Ik)), dtype=W.dtype, device=W.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     _check(lib().ard_compact_weight(_dtype_code(W), I, O, W.data_ptr(), Wc.data_ptr(), ro, ri, _stream(stream)))
@@ -244,7 +262,9 @@ def drop_gemm_fwd(X, W, pat_out=None, pat_in=None, alpha=1.0, relu=False, flags=
     O = (W.shape[0] if not flags & W_COMPACT else None) if O is None else O
     assert I is not None and O is not None, "pass I and O with ARD_W_COMPACT"
     dt = _dtype_code(X)
-    Oc = kept_count(pat_out, O) if flags & OUT_COMPACT else O
+    Oc = pad8(kept_count(pat_out, O)) if flags & OUT_COMPACT else O
+    if flags & IN_COMPACT:
+        _check_compact(X, kept_count(pat_in, I), "X")
     Y = torch.empty((B, Oc), dtype=X.dtype, device=X.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
@@ -262,7 +282,9 @@ def drop_gemm_bwd_data(dY, W, pat_out=None, pat_in=None, alpha=1.0, relu_src=Non
     O = (W.shape[0] if not flags & W_COMPACT else None) if O is None else O
     assert I is not None and O is not None, "pass I and O with ARD_W_COMPACT"
     dt = _dtype_code(dY)
-    Ic = kept_count(pat_in, I) if flags & IN_COMPACT else I
+    Ic = pad8(kept_count(pat_in, I)) if flags & IN_COMPACT else I
+    if flags & OUT_COMPACT:
+        _check_compact(dY, kept_count(pat_out, O), "dY")
     dX = torch.empty((B, Ic), dtype=dY.dtype, device=dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
@@ -280,6 +302,10 @@ def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, 
     O = dY.shape[1] if O is None else O
     I = X.shape[1] if I is None else I
     dt = _dtype_code(dY)
+    if flags & OUT_COMPACT:
+        _check_compact(dY, kept_count(pat_out, O), "dY")
+    if flags & IN_COMPACT:
+        _check_compact(X, kept_count(pat_in, I), "X")
     dW = torch.empty((O, I), dtype=dY.dtype, device=dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)

@@ -91,6 +91,8 @@ template <> struct ElemTraits<uint16_t> {
 };
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+// column count of a compact matrix: kept count rounded up to a whole 16-byte chunk of bf16
+__host__ __device__ static inline int pad8(int n) { return (n + 7) & ~7; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- pattern helpers (host) ---------------------------------------------------

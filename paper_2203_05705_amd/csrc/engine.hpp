@@ -27,6 +27,8 @@ struct Operand {
   Axis r;    // map of the non-contracted axis (M for A, N for B)
   int vec;   // 16-byte chunk loads are legal (contiguity and alignment checked on the host)
   int kdense;  // this operand is already compact along the contraction: it ignores the K map
+  int kpad;    // storage along the contraction is zero padded up to the next multiple of 8
+  int rpad;    // storage along the non-contracted axis is readable up to the next multiple of 8
 };
 
 struct OutMat {

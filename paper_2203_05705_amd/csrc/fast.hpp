@@ -97,9 +97,9 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int row = (wave * NI + j) * 8 + (lane >> 3);
-      int ph = row0 + row < r.n ? ax_phys(r, row0 + row) : 0;
-      ph = ph < r.nphys ? ph : 0;  // rows outside the matrix: fetch row 0, the result is never stored
-      goff[j] = ph * ld + chunk_k(lane, wave, j);
+      const int ph = row0 + row < r.n ? ax_phys(r, row0 + row) : r.nphys;
+      // rows beyond the axis contribute zeros (their outputs, if stored at all, are padding)
+      goff[j] = ph < r.nphys ? ph * ld + chunk_k(lane, wave, j) : -1;
     }
   }
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
@@ -107,6 +107,7 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const uint16_t* src = base + (long)goff[j] + kslab;
+      if (goff[j] < 0) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
       if (tail) {
         const int k = chunk_k(lane, wave, j);
         if (!(k < krem && kslab + k + 8 <= kphys_end)) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
@@ -141,8 +142,8 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
       const int kl = KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR;  // low bits of the row this lane fills
       const int c = (lane % CPR) ^ mc_swz<ROWS>(kl);
       const int j = row0 + c * 8;
-      int ph = j + 8 <= r.n ? ax_phys(r, j) : 0;
-      coff[par] = ph + 8 <= r.nphys ? ph : 0;
+      const int ph = j + 8 <= r.n ? ax_phys(r, j) : r.nphys;
+      coff[par] = ph + 8 <= r.nphys ? ph : -1;  // runs beyond the axis contribute zeros
     }
   }
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
@@ -150,8 +151,9 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int kloc = KPI * (wave * NI + j) + lane / CPR;
-      const uint16_t* src = base + (long)(kslab + kloc) * ld + coff[NCO == 2 ? (j & 1) : 0];
-      if (tail && !(kloc < krem && kslab + kloc < kphys_end)) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
+      const int co = coff[NCO == 2 ? (j & 1) : 0];
+      const uint16_t* src = base + (long)(kslab + kloc) * ld + co;
+      if (co < 0 || (tail && !(kloc < krem && kslab + kloc < kphys_end))) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -455,7 +457,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       // of row v+1 (one DPP swap), and each stores one packed 32-bit word.
       const bool odd = lane & 1;
       uint16_t* dst = P.C + (long)rbase * P.ldc + (pc & ~1);
-      const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0);
+      const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0) && (((uintptr_t)P.C & 3) == 0);
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
         float x0 = P.alpha * acc[im][in][v], x1 = P.alpha * acc[im][in][v + 1];

@@ -154,12 +154,24 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   auto ident = [](const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; };
   if (P.A.kdense && P.B.kdense) k = axis_identity(P.k.n);
   else if ((P.A.kdense || P.B.kdense) && !ident(P.k)) return false;
-  if (k.kind != AX_AFFINE || k.step != 1 || (k.off % 8) || (k.n % 8)) return false;
+  if (k.kind != AX_AFFINE || k.step != 1 || (k.off % 8)) return false;
+  if (k.n % 8) {
+    // both operands carry zero padding along the contraction: run it to the padded length
+    if (!P.A.kpad || !P.B.kpad || !ident(k)) return false;
+    k = axis_identity(pad8(k.n));
+  }
+  Axis ax_m = P.A.r, ax_n = P.B.r;
+  if (!a_kc && (ax_m.n % 8)) {
+    if (!P.A.rpad || !ident(ax_m)) return false;
+    ax_m = axis_identity(pad8(ax_m.n));
+  }
+  if (!b_kc && (ax_n.n % 8)) {
+    if (!P.B.rpad || !ident(ax_n)) return false;
+    ax_n = axis_identity(pad8(ax_n.n));
+  }
   const OutMat& C = P.C;
   if (C.plane) return false;
   if (!fast_ptr_ok(P.A.p, P.A.ld) || !fast_ptr_ok(P.B.p, P.B.ld)) return false;
-  if (!a_kc && (P.A.r.n % 8)) return false;
-  if (!b_kc && (P.B.r.n % 8)) return false;
   if ((long)P.A.r.nphys * P.A.ld >= (1L << 31) || (long)P.B.r.nphys * P.B.ld >= (1L << 31)) return false;
   if ((long)P.M * P.N >= (1L << 31)) return false;
   const bool direct_out = ident(C.rm) && ident(C.cn);
@@ -201,8 +213,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   F.lda = (int)P.A.ld;
   F.ldb = (int)P.B.ld;
   F.ldc = (int)C.ld;
-  F.am = P.A.r;
-  F.bn = P.B.r;
+  F.am = ax_m;
+  F.bn = ax_n;
   F.k = k;
   F.alpha = C.alpha;
   F.beta = C.beta;
@@ -435,19 +447,30 @@ using namespace ard;
 
 namespace ard {
 
-// Wc[r][c] = W[out(r)][in(c)]
+// Wc[r][c] = W[out(r)][in(c)]; rows and columns up to the next multiple of 8 are zero
 template <typename T>
 __global__ void compact_weight_kernel(const T* W, long ld, Axis ao, Axis ai, T* Wc) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   const int r = blockIdx.y;
-  if (c < ai.n && r < ao.n) Wc[(long)r * ai.n + c] = W[(long)ax_phys(ao, r) * ld + ax_phys(ai, c)];
+  const int cols = pad8(ai.n);
+  if (c < cols) Wc[(long)r * cols + c] = (c < ai.n && r < ao.n) ? W[(long)ax_phys(ao, r) * ld + ax_phys(ai, c)] : (T)0;
+}
+
+// out[r][c] = c < cols ? in[r*cols + c] : 0 for c < pad8(cols): aligned copy of a narrow activation
+template <typename T>
+__global__ void pad_cols_kernel(const T* in, int rows, int cols, T* out) {
+  const int pc = pad8(cols);
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)rows * pc) return;
+  const int r = (int)(idx / pc), c = (int)(idx - (long)r * pc);
+  out[idx] = c < cols ? in[(long)r * cols + c] : (T)0;
 }
 
 static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, const Axis& ao, const Axis& ai,
                               hipStream_t stream) {
   if (ao.n <= 0 || ai.n <= 0) return ARD_OK;
-  if (ao.n > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
-  dim3 grid(ceil_div(ai.n, 256), ao.n), block(256);
+  if (pad8(ao.n) > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
+  dim3 grid(ceil_div(pad8(ai.n), 256), pad8(ao.n)), block(256);
   if (dtype == ARD_BF16)
     hipLaunchKernelGGL(compact_weight_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)W, (long)I, ao, ai,
                        (uint16_t*)Wc);
@@ -455,6 +478,27 @@ static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, con
     hipLaunchKernelGGL(compact_weight_kernel<float>, grid, block, 0, stream, (const float*)W, (long)I, ao, ai,
                        (float*)Wc);
   ARD_LAUNCH_CHECK("compact_weight_kernel");
+  return ARD_OK;
+}
+
+// A [rows x cols] activation whose rows are not 16-byte aligned (cols % 8 != 0, bf16) is
+// copied once into the workspace with zero-padded rows, so the product can use 16-byte loads.
+// Returns the pointer to use and its leading dimension; advances ws_off.
+static int32_t aligned_activation(int32_t dtype, const void* p, int rows, int cols, void* ws, size_t ws_bytes,
+                                  size_t& ws_off, hipStream_t stream, const void*& out, int& ld) {
+  out = p;
+  ld = cols;
+  if (dtype != ARD_BF16 || (cols % 8) == 0 || cols > 256) return ARD_OK;
+  const size_t need = align_up((size_t)rows * pad8(cols) * 2, 256);
+  if (!ws || ws_off + need > ws_bytes) return ARD_OK;  // no room: the general kernel copes with the original
+  uint16_t* dst = (uint16_t*)((char*)ws + ws_off);
+  const long total = (long)rows * pad8(cols);
+  hipLaunchKernelGGL(pad_cols_kernel<uint16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                     (const uint16_t*)p, rows, cols, dst);
+  ARD_LAUNCH_CHECK("pad_cols_kernel");
+  ws_off += need;
+  out = dst;
+  ld = pad8(cols);
   return ARD_OK;
 }
 
@@ -490,7 +534,7 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
     L.w_compact = true;
   } else if (!is_identity(L.ai) && L.ai.n > 0 && L.ao.n > 0) {
     // the kept input neurons are strided along the contiguous axis of W: gather the kept block once
-    const size_t need = (size_t)L.ao.n * L.ai.n * es;
+    const size_t need = (size_t)pad8(L.ao.n) * pad8(L.ai.n) * es;
     if (!ws || ws_bytes < need) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
     int32_t st = compact_weight(a.dtype, a.I, W, ws, L.ao, L.ai, stream);
     if (st) return st;
@@ -499,9 +543,9 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
     L.ws_used = align_up(need, 256);
   }
   if (L.w_compact) {
-    L.w_ld = L.ai.n;
-    L.w_rows = axis_identity(L.ao.n);
-    L.w_cols = axis_identity(L.ai.n);
+    L.w_ld = pad8(L.ai.n);
+    L.w_rows = axis_identity(pad8(L.ao.n));
+    L.w_cols = axis_identity(pad8(L.ai.n));
   }
   return ARD_OK;
 }
@@ -517,10 +561,14 @@ extern "C" size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, 
   // gathered kept block of W, then room for fp32 partial results of up to 8 contraction splits
   const size_t Ok = (size_t)kept_count(pat_out, O), Ik = (size_t)kept_count(pat_in, I), Bn = B > 0 ? (size_t)B : 0;
   size_t bytes = 0;
-  if (pat_in && pat_in->kind != ARD_PAT_NONE) bytes += align_up(Ok * Ik * (dtype == ARD_BF16 ? 2 : 4), 256);
-  size_t big = Bn * Ok;
-  if (Bn * Ik > big) big = Bn * Ik;
-  if (Ok * Ik > big) big = Ok * Ik;
+  const size_t es = dtype == ARD_BF16 ? 2 : 4;
+  if (pat_in && pat_in->kind != ARD_PAT_NONE) bytes += align_up((size_t)pad8((int)Ok) * pad8((int)Ik) * es, 256);
+  if (O % 8) bytes += align_up(Bn * pad8(O) * es, 256);
+  if (I % 8) bytes += align_up(Bn * pad8(I) * es, 256);
+  const size_t Okp = pad8((int)Ok), Ikp = pad8((int)Ik);
+  size_t big = Bn * Okp;
+  if (Bn * Ikp > big) big = Bn * Ikp;
+  if (Okp * Ikp > big) big = Okp * Ikp;
   size_t part = big * 4 * 8;
   if (part > ((size_t)256 << 20)) part = (size_t)256 << 20;
   return bytes + part;
@@ -566,15 +614,24 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
     RowLayer L;
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
-    // contraction over the kept input neurons; an operand that is already compact ignores the map
-    P.k = L.ai;
-    P.A = Operand{X, L.in_c ? L.ai.n : I, axis_identity(B), 0, L.in_c ? 1 : 0};
-    P.B = Operand{L.Wp, L.w_ld, L.w_rows, 0, L.w_compact ? 1 : 0};
-    if (L.in_c && L.w_compact) P.k = axis_identity(L.ai.n);
+    // contraction over the kept input neurons; an operand that is already compact ignores the map.
+    // Compact matrices have pad8(count) columns, a compact W also pad8(count) rows, zero filled.
     ws_used = L.ws_used;
-    P.C.cn = L.out_c ? axis_identity(L.ao.n) : L.ao;
-    P.C.ld = L.out_c ? L.ao.n : O;
-    P.C.fill = L.out_c ? 0 : 1;
+    P.k = L.ai;
+    P.A = Operand{X, L.in_c ? pad8(L.ai.n) : I, axis_identity(B), 0, L.in_c, L.in_c, 0};
+    P.B = Operand{L.Wp, L.w_ld, L.w_rows, 0, L.w_compact, L.w_compact, 0};
+    if (L.out_c) {
+      // the padding columns are written too (as zeros: W has no rows there)
+      P.N = pad8(L.ao.n);
+      P.C.cn = axis_identity(P.N);
+      P.C.ld = P.N;
+      P.C.fill = 0;
+    } else {
+      P.N = L.ao.n;
+      P.C.cn = L.ao;
+      P.C.ld = O;
+      P.C.fill = 1;
+    }
   }
   P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, true, P.k, ce);
@@ -584,7 +641,7 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
   P.C.alpha = alpha;
   P.C.beta = 0.0f;
   P.M = B;
-  P.N = P.B.r.n;
+  if (a.tile) P.N = O;
   if (P.N == 0) return (flags & ARD_OUT_COMPACT) ? ARD_OK : fill_matrix(dtype, Y, (long)B * O, 0.0f, stream);
   return run_gemm(dtype, true, true, P, max_bn, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
                   a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
@@ -623,14 +680,29 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
     // contraction over the kept output neurons
-    P.k = L.ao;
-    P.A = Operand{dY, L.out_c ? L.ao.n : O, axis_identity(B), 0, L.out_c ? 1 : 0};
-    P.B = Operand{L.Wp, L.w_ld, L.w_cols, 0, L.w_compact ? 1 : 0};
-    if (L.out_c && L.w_compact) P.k = axis_identity(L.ao.n);
     ws_used = L.ws_used;
-    P.C.cn = L.in_c ? axis_identity(L.ai.n) : L.ai;
-    P.C.ld = L.in_c ? L.ai.n : I;
-    P.C.fill = L.in_c ? 0 : 1;
+    P.k = L.ao;
+    P.A = Operand{dY, L.out_c ? pad8(L.ao.n) : O, axis_identity(B), 0, L.out_c, L.out_c, 0};
+    P.B = Operand{L.Wp, L.w_ld, L.w_cols, 0, L.w_compact, L.w_compact, L.w_compact};
+    if (!L.out_c && L.w_compact && is_identity(L.ao)) {
+      // narrow dY (last layer): a zero-padded copy lets the contraction run over whole chunks
+      const void* dYp;
+      int dy_ld;
+      st = aligned_activation(dtype, dY, B, O, ws, ws_bytes, ws_used, stream, dYp, dy_ld);
+      if (st) return st;
+      if (dYp != dY) P.A = Operand{dYp, dy_ld, axis_identity(B), 0, 0, 1, 0};
+    }
+    if (L.in_c) {
+      P.N = pad8(L.ai.n);
+      P.C.cn = axis_identity(P.N);
+      P.C.ld = P.N;
+      P.C.fill = 0;
+    } else {
+      P.N = L.ai.n;
+      P.C.cn = L.ai;
+      P.C.ld = I;
+      P.C.fill = 1;
+    }
   }
   P.A.vec = operand_vec_ok(P.A, true, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
@@ -639,7 +711,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
   P.C.rm = axis_identity(B);
   P.C.alpha = alpha;
   P.M = B;
-  P.N = P.B.r.n;
+  if (a.tile) P.N = I;
   if (P.N == 0) return (flags & ARD_IN_COMPACT) ? ARD_OK : fill_matrix(dtype, dX, (long)B * I, 0.0f, stream);
   return run_gemm(dtype, true, false, P, max_bn, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
                   a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
@@ -656,6 +728,7 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   const int ce = chunk_elems(dtype);
   GemmParams P{};
   P.k = axis_identity(B);
+  size_t ws_used = 0;
   if (a.tile) {
     if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
     if (beta == 0.0f && try_fast_tile(2, a, dY, X, dW, alpha, 0, stream, st)) return st;
@@ -675,8 +748,22 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
     RowLayer L;
     st = resolve_row_layer(a, flags, nullptr, false, ws, ws_bytes, stream, L);
     if (st) return st;
-    P.A = Operand{dY, L.out_c ? L.ao.n : O, L.out_c ? axis_identity(L.ao.n) : L.ao, 0, 0};
-    P.B = Operand{X, L.in_c ? L.ai.n : I, L.in_c ? axis_identity(L.ai.n) : L.ai, 0, 0};
+    P.A = Operand{dY, L.out_c ? pad8(L.ao.n) : O, L.out_c ? axis_identity(L.ao.n) : L.ao, 0, 0, 0, L.out_c};
+    P.B = Operand{X, L.in_c ? pad8(L.ai.n) : I, L.in_c ? axis_identity(L.ai.n) : L.ai, 0, 0, 0, L.in_c};
+    if (!L.out_c && is_identity(L.ao)) {
+      const void* q;
+      int q_ld;
+      st = aligned_activation(dtype, dY, B, O, ws, ws_bytes, ws_used, stream, q, q_ld);
+      if (st) return st;
+      if (q != dY) P.A = Operand{q, q_ld, L.ao, 0, 0, 0, 1};
+    }
+    if (!L.in_c && is_identity(L.ai)) {
+      const void* q;
+      int q_ld;
+      st = aligned_activation(dtype, X, B, I, ws, ws_bytes, ws_used, stream, q, q_ld);
+      if (st) return st;
+      if (q != X) P.B = Operand{q, q_ld, L.ai, 0, 0, 0, 1};
+    }
     P.C.rm = L.ao;
     P.C.cn = L.ai;
   }
@@ -690,7 +777,8 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   P.M = P.A.r.n;
   P.N = P.B.r.n;
   if (P.M == 0 || P.N == 0) return fill_matrix(dtype, dW, (long)O * I, beta, stream);
-  return run_gemm(dtype, false, false, P, 0, 0, stream, a.tile ? nullptr : ws, a.tile ? 0 : ws_bytes);
+  return run_gemm(dtype, false, false, P, 0, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
+                  a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
 }
 
 namespace ard {

@@ -14,6 +14,19 @@ from util import assert_parity, from_vals, stored, to_dev, to_host
 pytestmark = pytest.mark.gpu
 
 
+def compact_in(vals, dtype):
+    """[B, count] values -> device tensor in the compact layout (pad8(count) columns, zero padded)."""
+    return ard.pad_compact(from_vals(vals, dtype))
+
+
+def check_compact(t, ref, dtype, what):
+    """Kept columns against the oracle; padding columns exactly +0.0."""
+    n = ref.shape[1]
+    assert t.shape == (ref.shape[0], ard.pad8(n)), (what, t.shape)
+    assert_parity(t[:, :n].contiguous(), ref, dtype, what=what)
+    assert not t[:, n:].contiguous().view(torch.int16 if dtype == "bf16" else torch.int32).any(), what + ": padding not +0.0"
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,I,O,po,pi", [(70, 136, 90, (2, 2), (3, 1)), (130, 264, 200, (4, 2), (2, 2)),
                                           (64, 100, 83, (3, 3), None), (33, 96, 64, None, (5, 2))])
@@ -27,7 +40,7 @@ def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
     MW = G.weight_mask_rows(mo, mi)
     pat_o = ard.Pattern.row(*po) if po else None
     pat_i = ard.Pattern.row(*pi) if pi else None
-    Xc, dYc = from_vals(Xv[:, ki], dtype), from_vals(dYv[:, ko], dtype)
+    Xc, dYc = compact_in(Xv[:, ki], dtype), compact_in(dYv[:, ko], dtype)
     W = from_vals(Wv, dtype)
     IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
     refY = G.drop_gemm_fwd(Xv, Wv, MW, mo, 1.5, relu=True)
@@ -35,13 +48,14 @@ def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
     refdW = G.drop_gemm_bwd_weight(dYv, Xv, MW, mo)
     # weight gathered inside the call
     Y = ard.drop_gemm_fwd(Xc, W, pat_o, pat_i, alpha=1.5, relu=True, flags=IN | OUT)
-    assert Y.shape == (B, len(ko))
-    assert_parity(Y, refY[:, ko], dtype, what="Y compact")
+    check_compact(Y, refY[:, ko], dtype, "Y compact")
     dX = ard.drop_gemm_bwd_data(dYc, W, pat_o, pat_i, alpha=0.5, flags=IN | OUT)
-    assert_parity(dX, refdX[:, ki], dtype, what="dX compact")
+    check_compact(dX, refdX[:, ki], dtype, "dX compact")
     # weight compacted once and shared
     Wc = ard.compact_weight(W, pat_o, pat_i)
-    assert np.array_equal(to_host(Wc), Wv[np.ix_(ko, ki)])
+    Wc_ref = np.zeros((ard.pad8(len(ko)), ard.pad8(len(ki))))
+    Wc_ref[:len(ko), :len(ki)] = Wv[np.ix_(ko, ki)]
+    assert np.array_equal(to_host(Wc), Wc_ref)
     Y2 = ard.drop_gemm_fwd(Xc, Wc, pat_o, pat_i, alpha=1.5, relu=True, flags=IN | OUT | WC, I=I, O=O)
     assert torch.equal(Y2, Y)
     dX2 = ard.drop_gemm_bwd_data(dYc, Wc, pat_o, pat_i, alpha=0.5, flags=IN | OUT | WC, I=I, O=O)
@@ -79,27 +93,27 @@ def test_config2_mlp_chain_iterations():
         p1, p2 = ard.Pattern.row(*pats[0]), ard.Pattern.row(*pats[1])
         # forward, fed with the oracle's stored activations so each product is checked on its own
         Y1 = ard.drop_gemm_fwd(X0, W[0], p1, None, relu=True, flags=OUT)
-        assert_parity(Y1, ref["Y"][0][:, keep[0]], "bf16", what="Y1")
+        check_compact(Y1, ref["Y"][0][:, keep[0]], "bf16", "Y1")
         W2c = ard.compact_weight(W[1], p2, p1)
-        Y1o = from_vals(ref["Y"][0][:, keep[0]], "bf16")
+        Y1o = compact_in(ref["Y"][0][:, keep[0]], "bf16")
         Y2 = ard.drop_gemm_fwd(Y1o, W2c, p2, p1, relu=True, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
-        assert_parity(Y2, ref["Y"][1][:, keep[1]], "bf16", what="Y2")
+        check_compact(Y2, ref["Y"][1][:, keep[1]], "bf16", "Y2")
         W3c = ard.compact_weight(W[2], None, p2)
-        Y2o = from_vals(ref["Y"][1][:, keep[1]], "bf16")
+        Y2o = compact_in(ref["Y"][1][:, keep[1]], "bf16")
         Y3 = ard.drop_gemm_fwd(Y2o, W3c, None, p2, flags=IN | WC, I=sizes[2], O=sizes[3])
         assert_parity(Y3, ref["Y"][2], "bf16", what="Y3")
         # backward
         dW3 = ard.drop_gemm_bwd_weight(dYL, Y2o, None, p2, flags=IN, I=sizes[2], O=sizes[3])
         assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3")
         dY2 = ard.drop_gemm_bwd_data(dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
-        assert_parity(dY2, ref["dY"][1][:, keep[1]], "bf16", what="dY2")
-        dY2o = from_vals(ref["dY"][1][:, keep[1]], "bf16")
+        check_compact(dY2, ref["dY"][1][:, keep[1]], "bf16", "dY2")
+        dY2o = compact_in(ref["dY"][1][:, keep[1]], "bf16")
         dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
         MW2 = G.weight_mask_rows(masks[1], masks[0])
         assert_parity(dW2, ref["dW"][1], "bf16", zero_mask=(MW2 == 0), what="dW2")
         dY1 = ard.drop_gemm_bwd_data(dY2o, W2c, p2, p1, relu_src=Y1o, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
-        assert_parity(dY1, ref["dY"][0][:, keep[0]], "bf16", what="dY1")
-        dY1o = from_vals(ref["dY"][0][:, keep[0]], "bf16")
+        check_compact(dY1, ref["dY"][0][:, keep[0]], "bf16", "dY1")
+        dY1o = compact_in(ref["dY"][0][:, keep[0]], "bf16")
         dW1 = ard.drop_gemm_bwd_weight(dY1o, X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
         assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape), what="dW1")
     torch.cuda.synchronize()
