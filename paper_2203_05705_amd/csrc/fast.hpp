@@ -204,8 +204,31 @@ __device__ __forceinline__ bf16x8_t frag_value(const Frag& f) {
   return __builtin_bit_cast(bf16x8_t, t);
 }
 
+// LDS stages of a tile configuration: the loads of NST - 1 contraction steps are in flight
+// while one step is multiplied.  Small tiles finish a step long before a load returns, so they
+// run deeper pipelines; the 256-wide tiles fill the LDS with two stages.
+#ifndef ARD_NST_SMALL
+#define ARD_NST_SMALL 4
+#endif
+#ifndef ARD_NST_MID
+#define ARD_NST_MID 2
+#endif
+constexpr int direct_stages(int bm, int bn) { return bm + bn >= 512 ? 2 : (bm + bn >= 384 ? ARD_NST_MID : ARD_NST_SMALL); }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Plain barrier.  The LDS stages are filled by LDS-direct loads (each wave waits for its own
+// with wait_vmcnt before the barrier) and read by volatile asm, so no fence is wanted: a fence
+// would also wait for the younger stages still in flight.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
 template <bool A_KC, bool B_KC, int F_BM, int BN, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P) {
+  constexpr int NST = direct_stages(F_BM, BN);
   constexpr int WGN = (NW == 8 && BN == 256) ? 4 : 2, WGM = NW / WGN;
   constexpr int WTM = F_BM / WGM, WTN = BN / WGN;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must hold whole MFMA tiles");
@@ -295,9 +318,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
         const int xr = (row & 7) ^ ((row >> 3) & 7);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          baddr[in][q] = lds_base + (unsigned)(2 * OPA + row * 8 + ((2 * q + (lane >> 5)) ^ xr)) * 16u;
+          baddr[in][q] = lds_base + (unsigned)(NST * OPA + row * 8 + ((2 * q + (lane >> 5)) ^ xr)) * 16u;
       } else {
-        baddr[in][0] = lds_base + (unsigned)(2 * OPA) * 16u + (unsigned)mc_frag_base<BN>(wn * WTN + in * 32, lane);
+        baddr[in][0] = lds_base + (unsigned)(NST * OPA) * 16u + (unsigned)mc_frag_base<BN>(wn * WTN + in * 32, lane);
       }
     }
     // contraction steps of this workgroup (a share of them when the contraction is split)
@@ -309,7 +332,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       const int ks = fast_kslab(kax, (s_lo + it) * 64);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
       la.issue(lds + buf * OPA, ks, krem, kax.nphys, tail, lane, wave);
-      lb.issue(lds + 2 * OPA + buf * OPB, ks, krem, kax.nphys, tail, lane, wave);
+      lb.issue(lds + NST * OPA + buf * OPB, ks, krem, kax.nphys, tail, lane, wave);
     };
     constexpr int QA = 16 * F_BM * 2, QB = 16 * BN * 2;  // bytes per 16-wide slice of an MC tile
     Frag fa[2][TM], fb[2][TN];
@@ -357,13 +380,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
     using I3 = std::integral_constant<int, 3>;
     // One contraction step from stage BUF.  Slice q+1's reads are in flight behind slice q's
     // MFMAs; the stage hand-over (wait for the next stage's loads, barrier, start the loads of
-    // the stage after it into the buffer just released, read the next stage's first slice)
-    // sits in front of the LAST slice's MFMAs, so neither the barrier nor the first LDS
-    // latency of a stage leaves the matrix cores idle.
+    // stage it+NST into the buffer just released, read the next stage's first slice) sits in
+    // front of the LAST slice's MFMAs, so neither the barrier nor the first LDS latency of a
+    // stage leaves the matrix cores idle.  Loads complete in order: with NST - 2 younger
+    // stages allowed in flight, stage it+1 has landed.
+    constexpr int LPS = decltype(la)::NI + decltype(lb)::NI;  // loads of one thread per stage
     auto step = [&](auto bufc, int it) {
       constexpr int BUF = decltype(bufc)::value;
       using B = std::integral_constant<int, BUF>;
-      using NB = std::integral_constant<int, BUF ^ 1>;
+      using NB = std::integral_constant<int, (BUF + 1) % NST>;
       wait(0);
       issue(B{}, I1{}, 1);
       mma(0);
@@ -375,22 +400,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       mma(0);
       wait(1);
       if (it + 1 < S) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();  // stage it+1 is complete and visible; nobody reads stage it any more
-        if (it + 2 < S) load_stage(it + 2, BUF);
+        if (it + NST - 1 < S) wait_vmcnt<(NST - 2) * LPS>();
+        else wait_vmcnt<0>();
+        wg_barrier();  // stage it+1 is complete and visible; nobody reads stage it any more
+        if (it + NST < S) load_stage(it + NST, BUF);
         issue(NB{}, I0{}, 0);
       }
       mma(1);
     };
     if (S > 0) {
-      load_stage(0, 0);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (S > 1) load_stage(1, 1);
+#pragma unroll
+      for (int st = 0; st < NST; ++st)
+        if (st < S) load_stage(st, st);
+      if (S >= NST) wait_vmcnt<(NST - 1) * LPS>();
+      else wait_vmcnt<0>();
+      wg_barrier();
       issue(I0{}, I0{}, 0);
-      for (int it = 0; it < S; it += 2) {
+      for (int it = 0; it < S; it += NST) {
         step(I0{}, it);
-        if (it + 1 < S) step(I1{}, it + 1);
+        if (NST > 1 && it + 1 < S) step(std::integral_constant<int, 1 % NST>{}, it + 1);
+        if (NST > 2 && it + 2 < S) step(std::integral_constant<int, 2 % NST>{}, it + 2);
+        if (NST > 3 && it + 3 < S) step(std::integral_constant<int, 3 % NST>{}, it + 3);
+        static_assert(NST >= 2 && NST <= 4, "pipeline depth");
       }
     }
   }
@@ -531,6 +562,75 @@ __global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int
       x *= C.alpha;
     }
     store_out<T>(C, (long)pr * C.ld + pc, x, true);
+  }
+}
+
+// The same pass for bf16 outputs whose rows can be written in 16-byte pieces (host checks:
+// bf16 result, beta == 0, 16-byte aligned rows, column count a multiple of 8; without zero
+// fill the column map is the identity).  A thread produces 8 adjacent physical columns.
+__global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float* part, int splits, int M, int N, OutMat C) {
+  // grid: x over the 8-column pieces of a row, y over rows (uniform per workgroup, so the row
+  // lookup is scalar work)
+  const int rows = C.fill ? C.rm.nphys : M, cols8 = (C.fill ? C.cn.nphys : N) >> 3;
+  const long MN = (long)M * N;
+  const int piece = blockIdx.x * 256 + threadIdx.x;
+  if (piece >= cols8) return;
+  const int c0 = piece * 8;
+  for (int r = blockIdx.y; r < rows; r += gridDim.y) {
+    const int i = C.fill ? ax_inverse(C.rm, r) : r;
+    const int pr = C.fill ? r : ax_phys(C.rm, r);
+    const long idx = (long)pr * C.ld + c0;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (i >= 0) {
+      uint4 gate = make_uint4(0, 0, 0, 0);
+      if (C.relu_src) gate = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(C.relu_src) + idx);
+      const uint32_t* gw = reinterpret_cast<const uint32_t*>(&gate);
+      int j = C.fill ? -1 : c0;
+      if (C.fill && C.cn.kind == AX_AFFINE) {
+        // first kept column at or after c0 (exact for the 24-bit operands of this division)
+        const int d = c0 - C.cn.off + C.cn.step - 1;
+        j = 0;
+        if (d >= C.cn.step) {
+          j = (int)((float)d / (float)C.cn.step);
+          j += ((j + 1) * C.cn.step <= d) - (j * C.cn.step > d);
+        }
+      }
+      int jj[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        if (!C.fill) jj[t] = j + t;
+        else if (C.cn.kind == AX_AFFINE) jj[t] = (j < C.cn.n && C.cn.off + j * C.cn.step == c0 + t) ? j++ : -1;
+        else jj[t] = ax_inverse(C.cn, c0 + t);
+      }
+      // all loads of the (at most 8) splits are independent: issue them together
+      float x[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      const float* prow = part + (long)i * N;
+      float ldv[8][8];
+#pragma unroll
+      for (int sp = 0; sp < 8; ++sp)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) ldv[sp][t] = (sp < splits && jj[t] >= 0) ? prow[sp * MN + jj[t]] : 0.0f;
+#pragma unroll
+      for (int sp = 0; sp < 8; ++sp)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] += ldv[sp][t];
+      for (int sp = 8; sp < splits; ++sp)
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          if (jj[t] >= 0) x[t] += prow[sp * MN + jj[t]];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        if (jj[t] < 0) continue;
+        float v = x[t] * C.alpha;
+        if (C.relu) v = fmaxf(v, 0.0f);
+        if (C.relu_src) {
+          const uint32_t g = (gw[t >> 1] >> (16 * (t & 1))) & 0xffffu;
+          v = bf16_bits_to_f32((uint16_t)g) > 0.0f ? v : 0.0f;
+        }
+        w[t >> 1] |= (uint32_t)f32_to_bf16_bits(v) << (16 * (t & 1));
+      }
+    }
+    *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(C.p) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 

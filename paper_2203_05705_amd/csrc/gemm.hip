@@ -86,7 +86,7 @@ static int gcd_int(int a, int b) {
 template <int BM, int BN, int NW>
 static int32_t launch_direct_cfg(bool a_kc, bool b_kc, FastParams& F, int grid_x, hipStream_t stream) {
   dim3 grid((unsigned)grid_x, (unsigned)F.splits), block(64 * NW);
-  const size_t lds_bytes = (size_t)2 * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
+  const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   auto go = [&](auto kernel) -> int32_t {
     static thread_local bool raised = false;
     if (!raised && lds_bytes >= 65536) {
@@ -231,10 +231,21 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
   if (st || !need) return true;
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
+  const int out_cols = C.fill ? C.cn.nphys : P.N;
+  const bool vec_out = !C.out_f32 && C.beta == 0.0f && (out_cols % 8) == 0 && (C.ld % 8) == 0 &&
+                       ((uintptr_t)C.p & 15) == 0 && (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) &&
+                       (C.fill || ident(C.cn)) && out_cols < (1 << 23);
   long blocks = (total + 255) / 256;
   if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws, splits,
-                     P.M, P.N, C);
+  if (blocks < 1) blocks = 1;
+  if (vec_out) {
+    const int out_rows = C.fill ? C.rm.nphys : P.M;
+    dim3 grid((unsigned)ceil_div(out_cols / 8, 256), (unsigned)(out_rows < 32768 ? out_rows : 32768));
+    hipLaunchKernelGGL(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, (const float*)ws, splits, P.M, P.N, C);
+  }
+  else
+    hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
+                       splits, P.M, P.N, C);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) st = fail(ARD_EHIP, "launch of gemm_finish_kernel failed: %s", hipGetErrorString(e));
   return true;

@@ -107,6 +107,12 @@ def test_config2_mlp_chain_iterations():
         assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3")
         dY2 = ard.drop_gemm_bwd_data(dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
         check_compact(dY2, ref["dY"][1][:, keep[1]], "bf16", "dY2")
+        # the same two products fed with the loss gradient in the compact (padded) layout
+        dYLc = ard.pad_compact(dYL)
+        dW3c = ard.drop_gemm_bwd_weight(dYLc, Y2o, None, p2, flags=IN | OUT, I=sizes[2], O=sizes[3])
+        assert_parity(dW3c, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3 (padded dY)")
+        dY2c = ard.drop_gemm_bwd_data(dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
+        check_compact(dY2c, ref["dY"][1][:, keep[1]], "bf16", "dY2 (padded dY)")
         dY2o = compact_in(ref["dY"][1][:, keep[1]], "bf16")
         dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
         MW2 = G.weight_mask_rows(masks[1], masks[0])
