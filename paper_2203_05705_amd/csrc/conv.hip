@@ -7,7 +7,10 @@
 //   BWD_DATA   dA[c kept, (n,y,x)] = sum_{tap, co}    Wq[c, (tap,co)]  * dY[n, co, y-kh+p, x-kw+p]
 //   BWD_WEIGHT dW[co, (c kept,tap)] = sum_{(n,oh,ow)} dY[n, co, oh, ow] * A[n, c, oh*s+kh-p, ow*s+kw-p]
 // Wp / Wq are compact repacked copies of the kept-channel weights (tiny, built per call).
+#include <stdlib.h>
+
 #include "engine.hpp"
+#include "fast.hpp"
 #include "pattern.hpp"
 
 namespace ard {
@@ -433,6 +436,95 @@ __global__ void rank_from_keep_kernel(const int* keep, int n_keep, int C, int* r
   for (int j = threadIdx.x; j < n_keep; j += blockDim.x) rank[keep[j]] = j;
 }
 
+
+// ---- bf16, stride 1: channels-last grid + LDS-direct implicit GEMM ----------------------------------
+//
+// The kept feature maps are copied once into a zero-bordered channels-last grid
+// T[(n*Hg + h + oh)*Wg + w + ow][Cp] (compaction of the kept maps and layout change in one pass;
+// Cp = kept channels rounded up to 64, extra channels zero).  On that grid the patch of an
+// output pixel is, per filter tap, one contiguous Cp-run at a pixel offset that depends on the
+// tap only, so the im2col operand streams through 16-byte LDS-direct loads like a plain matrix.
+
+__host__ __device__ static inline int pad64(int n) { return (n + 63) & ~63; }
+
+// dst tile of 64 grid pixels x 64 channels per workgroup: read along pixels, write along channels
+__global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
+                                                      int Ws, int Hg, int Wg, int oh, int ow, int Cp, long n_pix_valid,
+                                                      long n_pix_total, uint16_t* dst) {
+  __shared__ uint16_t tile[64][66];
+  const long p0 = (long)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  const int t = threadIdx.x;
+  {
+    const int pl = t & 63;
+    const long p = p0 + pl;
+    long off = -1;
+    if (p < n_pix_valid) {
+      const int n = (int)(p / ((long)Hg * Wg)), rem = (int)(p - (long)n * Hg * Wg);
+      const int h = rem / Wg - oh, w = rem % Wg - ow;
+      if (h >= 0 && h < Hs && w >= 0 && w < Ws) off = ((long)n * Cs * Hs + h) * Ws + w;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int cl = (t >> 6) + 4 * i, c = c0 + cl;
+      uint16_t v = 0;
+      if (off >= 0 && c < n_chan) v = src[off + (long)(chan ? chan[c] : c) * Hs * Ws];
+      tile[cl][pl] = v;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int pl = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
+    const long p = p0 + pl;
+    if (p >= n_pix_total) continue;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[c8 + 2 * e][pl] | ((uint32_t)tile[c8 + 2 * e + 1][pl] << 16);
+    *reinterpret_cast<uint4*>(dst + p * Cp + c0 + c8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+// Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
+// data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
+__global__ void pack_weights_grid_kernel(const uint16_t* Wt, const int* keep, int C, int taps, int rows, int inner, int Cp,
+                                         int flip, uint16_t* out) {
+  const long total = (long)rows * taps * Cp;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int q = (int)(idx % Cp);
+  const int tap = (int)((idx / Cp) % taps);
+  const int r = (int)(idx / ((long)Cp * taps));
+  uint16_t v = 0;
+  if (q < inner) v = flip ? Wt[((long)q * C + keep[r]) * taps + (taps - 1 - tap)] : Wt[((long)r * C + keep[q]) * taps + tap];
+  out[idx] = v;
+}
+
+// planes of dropped channels of an NCHW tensor to +0.0 (the GEMM writes the kept ones)
+__global__ __launch_bounds__(256) void zero_dropped_planes_kernel(uint16_t* dst, const int* rank, int C, int HW) {
+  const int c = blockIdx.x, n = blockIdx.y;
+  if (rank[c] >= 0) return;
+  uint16_t* p = dst + ((long)n * C + c) * HW;
+  for (int i = threadIdx.x; i < HW; i += 256) p[i] = 0;
+}
+
+// dW[co][c][tap] = sum over splits of part[sp][co][tap*Cp + rank(c)] (dropped channels: +0.0)
+__global__ void wgrad_grid_reduce_kernel(const float* part, const int* rank, int splits, int Cout, int C, int taps, int Cp,
+                                         uint16_t* dWt) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long total = (long)Cout * C * taps;
+  if (idx >= total) return;
+  const int tap = (int)(idx % taps);
+  const int c = (int)((idx / taps) % C);
+  const int co = (int)(idx / ((long)taps * C));
+  const int Nn = taps * Cp;
+  float s = 0.0f;
+  const int r = rank[c];
+  if (r >= 0)
+    for (int sp = 0; sp < splits; ++sp) s += part[((long)sp * Cout + co) * Nn + tap * Cp + r];
+  dWt[idx] = f32_to_bf16_bits(s);
+}
+
 struct ConvArgs {
   int32_t mode, dtype, N, C, H, W, Cout, kh, kw, stride, pad, n_keep, Ho, Wo, es;
 };
@@ -442,9 +534,19 @@ struct ConvWs {
   int* rank;
   char* wp;
   float* part;
+  uint16_t *grid_a, *grid_y;  // channels-last grids of the fast path (NULL when it does not apply)
+  uint16_t* gwp;              // its packed weights
+  float* gpart;               // its weight-gradient partial sums
   size_t total;
   int splits;
+  int gsplits;  // contraction splits of the fast weight-gradient product
 };
+
+// The LDS-direct path: bf16, stride 1, padding no larger than the filter allows for the data
+// gradient, and grids small enough for 32-bit element offsets.
+static bool conv_fast_ok(const ConvArgs& a);
+static long conv_grid_pixels(const ConvArgs& a, int* hg, int* wg);
+static int conv_grid_splits(const ConvArgs& a);
 
 static int wgrad_splits(const ConvArgs& a) {
   long tiles = (long)ceil_div(a.Cout, 128) * ceil_div(a.C * a.kh * a.kw, 128);
@@ -469,8 +571,175 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
   w.rank = (int*)take((size_t)a.C * 4);
   w.wp = take((size_t)a.Cout * a.C * taps * a.es);
   w.part = (float*)take((size_t)w.splits * a.Cout * a.C * taps * 4);
+  w.grid_a = w.grid_y = w.gwp = nullptr;
+  w.gpart = nullptr;
+  w.gsplits = 1;
+  if (conv_fast_ok(a)) {
+    int hg, wg;
+    const long pix = conv_grid_pixels(a, &hg, &wg);
+    w.gsplits = conv_grid_splits(a);
+    const size_t cpa = pad64(a.C), cpy = pad64(a.Cout);
+    w.grid_a = (uint16_t*)take((size_t)pix * cpa * 2);
+    w.grid_y = (uint16_t*)take((size_t)pix * cpy * 2);
+    w.gwp = (uint16_t*)take((size_t)(a.Cout > a.C ? a.Cout : a.C) * taps * (cpa > cpy ? cpa : cpy) * 2);
+    w.gpart = (float*)take((size_t)w.gsplits * a.Cout * taps * cpa * 4);
+  }
   w.total = off;
   return w;
+}
+
+
+static bool conv_fast_ok(const ConvArgs& a) {
+  if (a.dtype != ARD_BF16 || a.stride != 1) return false;
+  if (a.pad > a.kh - 1 || a.pad > a.kw - 1) return false;
+  int hg, wg;
+  const long pix = conv_grid_pixels(a, &hg, &wg);
+  const long cmax = pad64(a.C > a.Cout ? a.C : a.Cout);
+  return pix * cmax < (1L << 31) && (long)a.kh * a.kw * cmax < (1L << 24);
+}
+
+// Pixels of the largest grid any mode builds (input grid with its border, or the output grid
+// bordered for the data gradient), plus the margin the shifted reads of the weight gradient
+// and the 64-pixel tiles of the copy kernel may touch.
+static long conv_grid_pixels(const ConvArgs& a, int* hg, int* wg) {
+  const int ho = a.H + 2 * a.pad - a.kh + 1, wo = a.W + 2 * a.pad - a.kw + 1;
+  const int h1 = a.H + 2 * a.pad, w1 = a.W + 2 * a.pad;
+  const int h2 = ho + 2 * (a.kh - 1 - a.pad), w2 = wo + 2 * (a.kw - 1 - a.pad);
+  *hg = h1 > h2 ? h1 : h2;
+  *wg = w1 > w2 ? w1 : w2;
+  const long margin = (long)a.kh * *wg + a.kw + 128;
+  return (long)a.N * *hg * *wg + margin;
+}
+
+static int conv_grid_splits(const ConvArgs& a) {
+  const long tiles = (long)ceil_div(a.Cout, 128) * ceil_div(a.kh * a.kw * pad64(a.C), 128);
+  long s = 256 / tiles;  // about one 128 x 128 workgroup (its LDS fills a CU) per CU
+  return (int)(s < 1 ? 1 : (s > 64 ? 64 : s));
+}
+
+static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
+                       int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream) {
+  const long valid = (long)N * Hg * Wg, total = valid + margin;
+  dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
+  hipLaunchKernelGGL(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
+                     ow, Cp, valid, total, dst);
+  ARD_LAUNCH_CHECK("to_grid_kernel");
+  return ARD_OK;
+}
+
+// Y[row][pixel] = sum_k Wp[row][k] * im2col[pixel][k] on the grid; NCHW output
+static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_t* grid_t, const ConvMap& cv, void* out,
+                              hipStream_t stream) {
+  FastParams F{};
+  F.A = Wp;
+  F.B = grid_t;
+  F.C = (uint16_t*)out;
+  F.lda = K;
+  F.ldb = cv.Cp;
+  F.am = axis_identity(rows);
+  F.bn = axis_identity(cv.npix);
+  F.k = axis_identity(K);
+  F.alpha = 1.0f;
+  F.splits = 1;
+  F.M = rows;
+  F.N = cv.npix;
+  F.cv = cv;
+  int bm, bn;
+  if (rows > 128) {
+    bm = 256;
+    bn = (long)ceil_div(rows, 256) * ceil_div(cv.npix, 256) >= 220 ? 256 : 128;
+  } else if (rows > 64) {
+    bm = bn = 128;
+  } else {
+    bm = bn = 64;
+  }
+  F.tiles_m = ceil_div(rows, bm);
+  F.tiles_n = ceil_div(cv.npix, bn);
+  const long tiles = (long)F.tiles_m * F.tiles_n;
+  if (tiles >= (1L << 24)) return fail(ARD_ESHAPE, "convolution too large for one launch");
+  F.total_tiles = (int)tiles;
+  F.group_m = direct_group_m(F.total_tiles);
+  const int grid = direct_plain_grid(F.total_tiles);
+  if (bm == 256 && bn == 256) return launch_direct_kernel<true, true, 256, 256, 8, 1>(F, grid, stream);
+  if (bm == 256) return launch_direct_kernel<true, true, 256, 128, 8, 1>(F, grid, stream);
+  if (bm == 128) return launch_direct_kernel<true, true, 128, 128, 4, 1>(F, grid, stream);
+  return launch_direct_kernel<true, true, 64, 64, 4, 1>(F, grid, stream);
+}
+
+static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, const void* dYin, void* out,
+                             const int32_t* d_keep, const ConvWs& w, hipStream_t stream) {
+  const int taps = a.kh * a.kw, Ck = a.n_keep;
+  int hgm, wgm;
+  const long pix_cap = conv_grid_pixels(a, &hgm, &wgm);
+  (void)pix_cap;
+  if (a.mode == ARD_CONV_FWD) {
+    const int Cp = pad64(Ck), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
+    int32_t st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, 64, w.grid_a, stream);
+    if (st) return st;
+    const long total = (long)a.Cout * K;
+    hipLaunchKernelGGL(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
+    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout};
+    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, cv, out, stream);
+  }
+  if (a.mode == ARD_CONV_BWD_DATA) {
+    // dA = dY (bordered by k-1-pad) convolved with the reversed filter, contraction over (tap, co)
+    const int ph = a.kh - 1 - a.pad, pw = a.kw - 1 - a.pad;
+    const int Cp = pad64(a.Cout), Hg = a.Ho + 2 * ph, Wg = a.Wo + 2 * pw, K = taps * Cp;
+    int32_t st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, 64, w.grid_y, stream);
+    if (st) return st;
+    const long total = (long)Ck * K;
+    hipLaunchKernelGGL(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
+    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+    ARD_LAUNCH_CHECK("rank_from_keep_kernel");
+    hipLaunchKernelGGL(zero_dropped_planes_kernel, dim3(a.C, a.N), dim3(256), 0, stream, (uint16_t*)out, (const int*)w.rank,
+                       a.C, a.H * a.W);
+    ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
+    ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck};
+    return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, cv, out, stream);
+  }
+  // BWD_WEIGHT: contraction over the pixels of the input grid; dY sits on the same grid (top-left
+  // aligned, zero elsewhere), the tap shifts the activation grid by (r*Wg + s) pixels.
+  const int Cpa = pad64(Ck), Cpy = pad64(a.Cout), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad;
+  const long margin = (long)a.kh * Wg + a.kw + 128;
+  int32_t st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cpa, margin, w.grid_a, stream);
+  if (st) return st;
+  st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, 0, 0, Cpy, 64, w.grid_y, stream);
+  if (st) return st;
+  hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+  ARD_LAUNCH_CHECK("rank_from_keep_kernel");
+  const int Kq = a.N * Hg * Wg, Nn = taps * Cpa;
+  FastParams F{};
+  F.A = w.grid_y;
+  F.B = w.grid_a;
+  F.lda = Cpy;
+  F.ldb = Cpa;
+  F.am = axis_identity(Cpy);
+  F.bn = axis_identity(Nn);
+  F.k = axis_identity(Kq);
+  F.alpha = 1.0f;
+  F.part = w.gpart;
+  int splits = w.gsplits;
+  const int steps = ceil_div(Kq, 64);
+  if (splits > steps) splits = steps;
+  F.splits = splits;
+  F.M = a.Cout;
+  F.N = Nn;
+  F.cv = ConvMap{0, 0, Hg * Wg, Wg, Cpa, a.kw, 0, 0, nullptr, 0};
+  F.tiles_m = ceil_div(a.Cout, 128);
+  F.tiles_n = ceil_div(Nn, 128);
+  F.total_tiles = F.tiles_m * F.tiles_n;
+  F.group_m = direct_group_m(F.total_tiles);
+  st = launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
+  if (st) return st;
+  const long total = (long)a.Cout * a.C * taps;
+  hipLaunchKernelGGL(wgrad_grid_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                     (const float*)w.gpart, (const int*)w.rank, splits, a.Cout, a.C, taps, Cpa, (uint16_t*)out);
+  ARD_LAUNCH_CHECK("wgrad_grid_reduce_kernel");
+  return ARD_OK;
 }
 
 static int32_t conv_check(ConvArgs& a) {
@@ -517,6 +786,12 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
   if (a.n_keep > 0 && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
   if (!out) return fail(ARD_EINVAL, "null output pointer");
   const int Ck = a.n_keep;
+  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !getenv("ARD_NO_FAST")) {
+    if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
+    if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
+    if (a.mode == ARD_CONV_BWD_WEIGHT && (!dYin || !A)) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
+    return conv_run_grid(a, A, Wt, dYin, out, d_keep, w, stream);
+  }
 
   if (a.mode == ARD_CONV_FWD) {
     if (!A || !Wt) return fail(ARD_EINVAL, "FWD needs A and Wt");

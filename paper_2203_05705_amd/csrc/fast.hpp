@@ -51,6 +51,21 @@ struct ClassTab {
   int k_off[F_MAXCLS], k_cnt[F_MAXCLS], k_step, k_bs, k_phys;
 };
 
+// Implicit-GEMM convolution on a channels-last, zero-bordered copy of the activations
+// T[(n*Hg + h)*Wg + w][Cp] (Cp channels per pixel, a multiple of 64): the patch of output pixel
+// (n, ho, wo) and tap (r, s) is the Cp-run that starts at pixel (n*Hg + ho + r)*Wg + wo + s, so
+// along the contraction k = (tap, c) every row of the im2col matrix is its base pixel plus an
+// offset that depends on k only.
+struct ConvMap {
+  int HoWo, Wo;     // output pixels per image / per row
+  int HgWg, Wg;     // pixels per image / per row of the bordered grid
+  int Cp, kw;       // channels per pixel of the grid, taps per filter row
+  int npix;         // output pixels over the batch (rows of the im2col matrix)
+  int out_chan;     // channels per image of the output tensor (NCHW)
+  const int* chan;  // optional: output channel of compact row i (kept-channel list), else i
+  int n_rows;       // valid compact output rows (channels)
+};
+
 struct FastParams {
   const uint16_t* A;
   const uint16_t* B;
@@ -65,13 +80,14 @@ struct FastParams {
   float* part;               // != NULL: write fp32 partial sums part[split][M][N] instead of C
   int splits;
   int M, N, tiles_m, tiles_n, group_m, total_tiles;
+  ConvMap cv;  // MODE 1 / 2 of the kernel only
 };
 
 #define ARD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 #define ARD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 
 // 64 zero bytes: source of the chunks that lie beyond the end of the contraction
-__device__ uint4 g_zero_chunk[4];
+static __device__ uint4 g_zero_chunk[4];
 
 // physical start of the 64-wide contraction slab that begins at compact index ks (uniform)
 __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
@@ -100,6 +116,20 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
       const int ph = row0 + row < r.n ? ax_phys(r, row0 + row) : r.nphys;
       // rows beyond the axis contribute zeros (their outputs, if stored at all, are padding)
       goff[j] = ph < r.nphys ? ph * ld + chunk_k(lane, wave, j) : -1;
+    }
+  }
+  // rows = output pixels of a convolution: base pixel of the patch in the bordered grid
+  __device__ __forceinline__ void init_pixels(const uint16_t* p, const ConvMap& cv, int row0, int lane, int wave) {
+    base = p;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int row = row0 + (wave * NI + j) * 8 + (lane >> 3);
+      goff[j] = -1;
+      if (row < cv.npix) {
+        const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
+        const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
+        goff[j] = (n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j);
+      }
     }
   }
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
@@ -144,6 +174,23 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
       const int j = row0 + c * 8;
       const int ph = j + 8 <= r.n ? ax_phys(r, j) : r.nphys;
       coff[par] = ph + 8 <= r.nphys ? ph : -1;  // runs beyond the axis contribute zeros
+    }
+  }
+  // columns = (tap, channel) of the weight gradient: pixel offset of the tap plus the channel
+  __device__ __forceinline__ void init_tap_columns(const uint16_t* p, const ConvMap& cv, int ncols, int row0, int lane,
+                                                   int wave) {
+    base = p;
+    ld = cv.Cp;
+#pragma unroll
+    for (int par = 0; par < NCO; ++par) {
+      const int kl = KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR;
+      const int c = (lane % CPR) ^ mc_swz<ROWS>(kl);
+      const int j = row0 + c * 8;
+      coff[par] = -1;
+      if (j + 8 <= ncols) {
+        const int t = j / cv.Cp;
+        coff[par] = ((t / cv.kw) * cv.Wg + t % cv.kw) * cv.Cp + (j - t * cv.Cp);
+      }
     }
   }
   __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
@@ -226,7 +273,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // would also wait for the younger stages still in flight.
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <bool A_KC, bool B_KC, int F_BM, int BN, int NW>
+// MODE 0: plain product.  MODE 1: convolution, B rows are output pixels gathered from the
+// bordered channels-last grid (contraction = (tap, channel)), output NCHW.  MODE 2: weight
+// gradient of the convolution, contraction over the grid's pixels, B columns = (tap, channel).
+template <bool A_KC, bool B_KC, int F_BM, int BN, int NW, int MODE = 0>
 __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P) {
   constexpr int NST = direct_stages(F_BM, BN);
   constexpr int WGN = (NW == 8 && BN == 256) ? 4 : 2, WGM = NW / WGN;
@@ -297,7 +347,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
     DirectLoader<A_KC, F_BM, NW> la;
     DirectLoader<B_KC, BN, NW> lb;
     la.init(P.A, P.lda, am, m0, lane, wave);
-    lb.init(P.B, P.ldb, bn, n0, lane, wave);
+    if constexpr (MODE == 1) lb.init_pixels(P.B, P.cv, n0, lane, wave);
+    else if constexpr (MODE == 2) lb.init_tap_columns(P.B, P.cv, P.N, n0, lane, wave);
+    else lb.init(P.B, P.ldb, bn, n0, lane, wave);
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
     unsigned aaddr[TM][A_KC ? 4 : 1], baddr[TN][B_KC ? 4 : 1];
 #pragma unroll
@@ -332,7 +384,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       const int ks = fast_kslab(kax, (s_lo + it) * 64);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
       la.issue(lds + buf * OPA, ks, krem, kax.nphys, tail, lane, wave);
-      lb.issue(lds + NST * OPA + buf * OPB, ks, krem, kax.nphys, tail, lane, wave);
+      int ksb = ks;
+      if constexpr (MODE == 1) {
+        // slab (tap, c0) of the im2col row: offset of the tap's pixel plus the channel
+        const int t = ks / P.cv.Cp;
+        ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
+      }
+      lb.issue(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, tail, lane, wave);
     };
     constexpr int QA = 16 * F_BM * 2, QB = 16 * BN * 2;  // bytes per 16-wide slice of an MC tile
     Frag fa[2][TM], fb[2][TN];
@@ -447,6 +505,50 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
         for (int v = 0; v < 16; ++v) {
           const int i = i0 + 8 * (v >> 2) + (v & 3);
           if (i < P.M) part[(long)i * P.N + j] = acc[im][in][v];
+        }
+      }
+    }
+    return;
+  }
+  if constexpr (MODE == 1) {
+    // NCHW output: compact row i -> channel (through the kept-channel list when there is one),
+    // column j -> pixel (n, hw) at n*out_chan*HW + hw.  Pairs of adjacent pixels are packed
+    // into 32-bit stores as below when the plane size is even.
+    const ConvMap& cv = P.cv;
+    const int HW = cv.HoWo;
+    const bool odd = lane & 1;
+    const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0);
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      const int j = n0 + wn * WTN + in * 32 + (lane & 31);
+      if (j >= cv.npix) continue;  // npix is even whenever pair_ok, so a pair is in or out together
+      const int n = j / HW;
+      uint16_t* col = P.C + (long)n * cv.out_chan * HW + (j - n * HW);
+#pragma unroll
+      for (int im = 0; im < TM; ++im) {
+        const int i0 = m0 + wm * WTM + im * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+          const int ia = i0 + 8 * (v >> 2) + (v & 3);  // row of v; v+1 is the next row
+          float x0 = P.alpha * acc[im][in][v], x1 = P.alpha * acc[im][in][v + 1];
+          if (P.relu) {
+            x0 = fmaxf(x0, 0.0f);
+            x1 = fmaxf(x1, 0.0f);
+          }
+          const uint32_t b0 = f32_to_bf16_bits(x0), b1 = f32_to_bf16_bits(x1);
+          if (pair_ok) {
+            const uint32_t send = odd ? b0 : b1;
+            const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, true);
+            const uint32_t word = odd ? (got | (b1 << 16)) : (b0 | (got << 16));
+            const int i = odd ? ia + 1 : ia;
+            if (i < cv.n_rows) {
+              const int ch = cv.chan ? cv.chan[i] : i;
+              *reinterpret_cast<uint32_t*>(col - (odd ? 1 : 0) + (long)ch * HW) = word;
+            }
+          } else {
+            if (ia < cv.n_rows) col[(long)(cv.chan ? cv.chan[ia] : ia) * HW] = (uint16_t)b0;
+            if (ia + 1 < cv.n_rows) col[(long)(cv.chan ? cv.chan[ia + 1] : ia + 1) * HW] = (uint16_t)b1;
+          }
         }
       }
     }
@@ -568,7 +670,7 @@ __global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int
 // The same pass for bf16 outputs whose rows can be written in 16-byte pieces (host checks:
 // bf16 result, beta == 0, 16-byte aligned rows, column count a multiple of 8; without zero
 // fill the column map is the identity).  A thread produces 8 adjacent physical columns.
-__global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float* part, int splits, int M, int N, OutMat C) {
+static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float* part, int splits, int M, int N, OutMat C) {
   // grid: x over the 8-column pieces of a row, y over rows (uniform per workgroup, so the row
   // lookup is scalar work)
   const int rows = C.fill ? C.rm.nphys : M, cols8 = (C.fill ? C.cn.nphys : N) >> 3;
@@ -635,7 +737,7 @@ __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float* part,
 }
 
 // Zero the dropped tiles of a tile-masked matrix (weight gradient): one workgroup per tile.
-__global__ __launch_bounds__(256) void zero_dropped_tiles_kernel(uint16_t* C, int ld, int rows, int cols, int tr, int tc,
+static __global__ __launch_bounds__(256) void zero_dropped_tiles_kernel(uint16_t* C, int ld, int rows, int cols, int tr, int tc,
                                                                  int TC, int dp, int o) {
   const int t = blockIdx.x;
   if (((t + dp - o) % dp) == 0) return;  // kept tile: written by the GEMM
@@ -653,6 +755,41 @@ __global__ __launch_bounds__(256) void zero_dropped_tiles_kernel(uint16_t* C, in
       C[(long)(r0 + r) * ld + c0 + c] = 0;
     }
   }
+}
+
+// Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
+// kernels above the 64 KiB default get their limit raised once.
+template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
+static int32_t launch_direct_kernel(const FastParams& F, int grid_x, hipStream_t stream) {
+  auto kernel = gemm_direct_kernel<A_KC, B_KC, BM, BN, NW, MODE>;
+  const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
+  static thread_local bool raised = false;
+  if (!raised && lds_bytes >= 65536) {
+    ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    raised = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid_x, (unsigned)(F.splits < 1 ? 1 : F.splits)), dim3(64 * NW), lds_bytes,
+                     stream, F);
+  ARD_LAUNCH_CHECK("gemm_direct_kernel");
+  return ARD_OK;
+}
+
+// Grid of a plain (class-free) launch: every XCD takes the share [x*n/8, (x+1)*n/8) of the tiles.
+static inline int direct_plain_grid(int total_tiles) {
+  int worst = 0;
+  for (int x = 0; x < 8; ++x) {
+    const int sum = (int)((long)(x + 1) * total_tiles / 8) - (int)((long)x * total_tiles / 8);
+    worst = sum > worst ? sum : worst;
+  }
+  return worst * 8;
+}
+
+// an XCD's share should be about square in tiles: bands of group_m tile rows
+static inline int direct_group_m(int total_tiles) {
+  const int per_xcd = ceil_div(total_tiles, 8);
+  int gm = 1;
+  while (gm * gm * 2 <= per_xcd && gm < 8) gm *= 2;
+  return gm;
 }
 
 }  // namespace ard

@@ -85,21 +85,9 @@ static int gcd_int(int a, int b) {
 
 template <int BM, int BN, int NW>
 static int32_t launch_direct_cfg(bool a_kc, bool b_kc, FastParams& F, int grid_x, hipStream_t stream) {
-  dim3 grid((unsigned)grid_x, (unsigned)F.splits), block(64 * NW);
-  const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
-  auto go = [&](auto kernel) -> int32_t {
-    static thread_local bool raised = false;
-    if (!raised && lds_bytes >= 65536) {
-      ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-      raised = true;
-    }
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, F);
-    ARD_LAUNCH_CHECK("gemm_direct_kernel");
-    return ARD_OK;
-  };
-  if (a_kc && b_kc) return go(gemm_direct_kernel<true, true, BM, BN, NW>);
-  if (a_kc && !b_kc) return go(gemm_direct_kernel<true, false, BM, BN, NW>);
-  if (!a_kc && !b_kc) return go(gemm_direct_kernel<false, false, BM, BN, NW>);
+  if (a_kc && b_kc) return launch_direct_kernel<true, true, BM, BN, NW, 0>(F, grid_x, stream);
+  if (a_kc && !b_kc) return launch_direct_kernel<true, false, BM, BN, NW, 0>(F, grid_x, stream);
+  if (!a_kc && !b_kc) return launch_direct_kernel<false, false, BM, BN, NW, 0>(F, grid_x, stream);
   return fail(ARD_EUNSUPPORTED, "operand layout combination not built");
 }
 
