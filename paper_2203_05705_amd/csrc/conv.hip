@@ -613,7 +613,7 @@ static long conv_grid_pixels(const ConvArgs& a, int* hg, int* wg) {
 
 static int conv_grid_splits(const ConvArgs& a) {
   const long tiles = (long)ceil_div(a.Cout, 128) * ceil_div(a.kh * a.kw * pad64(a.C), 128);
-  long s = 256 / tiles;  // about one 128 x 128 workgroup (its LDS fills a CU) per CU
+  long s = 512 / tiles;  // about two 128 x 128 workgroups per CU
   return (int)(s < 1 ? 1 : (s > 64 ? 64 : s));
 }
 
@@ -649,7 +649,8 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
     bm = 256;
     bn = (long)ceil_div(rows, 256) * ceil_div(cv.npix, 256) >= 220 ? 256 : 128;
   } else if (rows > 64) {
-    bm = bn = 128;
+    bm = 128;
+    bn = 256;
   } else {
     bm = bn = 64;
   }
@@ -662,7 +663,7 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
   const int grid = direct_plain_grid(F.total_tiles);
   if (bm == 256 && bn == 256) return launch_direct_kernel<true, true, 256, 256, 8, 1>(F, grid, stream);
   if (bm == 256) return launch_direct_kernel<true, true, 256, 128, 8, 1>(F, grid, stream);
-  if (bm == 128) return launch_direct_kernel<true, true, 128, 128, 4, 1>(F, grid, stream);
+  if (bm == 128) return launch_direct_kernel<true, true, 128, 256, 8, 1>(F, grid, stream);
   return launch_direct_kernel<true, true, 64, 64, 4, 1>(F, grid, stream);
 }
 
@@ -722,18 +723,27 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   F.k = axis_identity(Kq);
   F.alpha = 1.0f;
   F.part = w.gpart;
-  int splits = w.gsplits;
+  // tile 256 x 128 (8 wavefronts) when there are enough output channels, else 128 x 128; the
+  // contraction is split until every CU has a workgroup (two of the small ones), within the
+  // room the workspace has for partial sums
+  const bool big = a.Cout > 128;
+  const int bm = big ? 256 : 128;
+  const long cap = (long)w.gsplits * taps * pad64(a.C) / Nn;
+  F.tiles_m = ceil_div(a.Cout, bm);
+  F.tiles_n = ceil_div(Nn, 128);
+  F.total_tiles = F.tiles_m * F.tiles_n;
+  int splits = (big ? 256 : 512) / F.total_tiles;
+  if (splits > cap) splits = (int)cap;
   const int steps = ceil_div(Kq, 64);
   if (splits > steps) splits = steps;
+  if (splits < 1) splits = 1;
   F.splits = splits;
   F.M = a.Cout;
   F.N = Nn;
   F.cv = ConvMap{0, 0, Hg * Wg, Wg, Cpa, a.kw, 0, 0, nullptr, 0};
-  F.tiles_m = ceil_div(a.Cout, 128);
-  F.tiles_n = ceil_div(Nn, 128);
-  F.total_tiles = F.tiles_m * F.tiles_n;
   F.group_m = direct_group_m(F.total_tiles);
-  st = launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
+  st = big ? launch_direct_kernel<false, false, 256, 128, 8, 2>(F, direct_plain_grid(F.total_tiles), stream)
+           : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
   if (st) return st;
   const long total = (long)a.Cout * a.C * taps;
   hipLaunchKernelGGL(wgrad_grid_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,

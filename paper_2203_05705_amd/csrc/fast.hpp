@@ -252,15 +252,13 @@ __device__ __forceinline__ bf16x8_t frag_value(const Frag& f) {
 }
 
 // LDS stages of a tile configuration: the loads of NST - 1 contraction steps are in flight
-// while one step is multiplied.  Small tiles finish a step long before a load returns, so they
-// run deeper pipelines; the 256-wide tiles fill the LDS with two stages.
+// while one step is multiplied.  A 4-wavefront workgroup wants a second workgroup on its CU
+// (8 wavefronts hide the LDS and MFMA latencies), so its stages must fit twice into the 160 KiB
+// LDS; only the smallest tile has room for a third stage.
 #ifndef ARD_NST_SMALL
-#define ARD_NST_SMALL 4
+#define ARD_NST_SMALL 3
 #endif
-#ifndef ARD_NST_MID
-#define ARD_NST_MID 2
-#endif
-constexpr int direct_stages(int bm, int bn) { return bm + bn >= 512 ? 2 : (bm + bn >= 384 ? ARD_NST_MID : ARD_NST_SMALL); }
+constexpr int direct_stages(int bm, int bn) { return bm + bn <= 128 ? ARD_NST_SMALL : 2; }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
