@@ -2,63 +2,83 @@
 // matrix multiplications, so the same patterns apply).
 //
 // Fused weight W[4H x (I+H)], gate blocks i, f, g, o of H rows, columns [x | h].
-// A dropped unit has no gate rows and no recurrent column in any product:
-//   - the input projection of all T steps is one gathered GEMM over the kept gate rows,
-//   - the recurrent weight of the kept units is compacted once per sequence
-//     (W_h'[4H' x H']), and each step multiplies the compact hidden state by it,
-//   - the pointwise cell kernels run over physical units and write zeros for dropped ones.
+// A dropped unit has no gate rows and no recurrent column in any product.  Everything between
+// the products lives in a COMPACT layout: Hk kept units stored with stride Hp = Hk rounded up
+// to 8 (padding entries are zeros), gate g of kept unit j at index g*Hp + j.  All compact
+// extents are then multiples of 8 and every product is a plain matrix product with 16-byte
+// rows:
+//   - the kept rows of the input and recurrent weights are gathered once per call
+//     (Wx'[4Hp x I], Wh'[4Hp x Hp], zero rows / columns at the padding),
+//   - the input projection of all T steps is one product, each step multiplies the compact
+//     hidden state by Wh',
+//   - the pointwise cell kernels run over physical units and write zeros for dropped ones,
+//   - the weight gradient is computed compact and scattered into dW (zeros elsewhere) by one pass.
 #include "engine.hpp"
 #include "pattern.hpp"
 
 namespace ard {
 
-// rank[u] = compact index of unit u or -1; grows[g*Hk + j] = g*H + unit(j)
-__global__ __launch_bounds__(1024) void lstm_setup_kernel(Axis ax, int H, int* rank, int* grows) {
+// rank[u] = compact index of unit u or -1
+__global__ __launch_bounds__(1024) void lstm_setup_kernel(Axis ax, int H, int* rank) {
   for (int u = threadIdx.x; u < H; u += 1024) rank[u] = -1;
   __syncthreads();
-  const int Hk = ax.n;
-  for (int j = threadIdx.x; j < Hk; j += 1024) {
-    int u = ax_phys(ax, j);
-    rank[u] = j;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) grows[g * Hk + j] = g * H + u;
-  }
+  for (int j = threadIdx.x; j < ax.n; j += 1024) rank[ax_phys(ax, j)] = j;
 }
 
-// out[r][j] = src[rowlist ? rowlist[r] : r][col0 + unit(j)]
+// out[g*Hp + j][q] = W[(g*H + unit(j)) * ldw + col(q)] for kept j, 0 at the padding.
+// cols == 0: the input columns, q < ncol identity; cols == 1: the recurrent columns,
+// q < Hp -> I + unit(q) (0 at the padding); out has `ldo` columns.
 template <typename T>
-__global__ void gather_cols_kernel(const T* src, long ld, const int* rowlist, int col0, Axis ax, T* out, int rows) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const int r = blockIdx.y;
-  if (j < ax.n && r < rows) {
-    long pr = rowlist ? rowlist[r] : r;
-    out[(long)r * ax.n + j] = src[pr * ld + col0 + ax_phys(ax, j)];
+__global__ void lstm_gather_w_kernel(const T* W, long ldw, Axis ax, int H, int I, int Hp, int recurrent, int ldo, T* out) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  const int r = blockIdx.y;  // compact gate row
+  if (q >= ldo) return;
+  const int g = r / Hp, j = r - g * Hp;
+  T v = (T)0;
+  if (j < ax.n) {
+    const long row = (long)(g * H + ax_phys(ax, j)) * ldw;
+    if (!recurrent) v = W[row + q];
+    else if (q < ax.n) v = W[row + I + ax_phys(ax, q)];
   }
+  out[(long)r * ldo + q] = v;
+}
+
+// out[r][j] = j < Hk ? src[r*H + unit(j)] : 0 (compact copy of stored hidden states)
+template <typename T>
+__global__ void lstm_gather_h_kernel(const T* src, int H, Axis ax, int Hp, T* out) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const long r = blockIdx.y;
+  if (j < Hp) out[r * Hp + j] = j < ax.n ? src[r * H + ax_phys(ax, j)] : (T)0;
 }
 
 __device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
-// One time step, forward.  G: compact pre-activations [B x 4Hk] (fp32).  Writes the
+// One time step, forward.  G: compact pre-activations [B x 4Hp] (fp32).  Writes the
 // activated gates [B x 4H], c [B x H] (fp32), h [B x H] (dtype) with zeros for dropped
-// units, and the compact h [B x Hk] that feeds the next step's product.
+// units, and the compact h [B x Hp] (zeros at the padding) that feeds the next step's product.
+// Threads u >= H take the padding entries.
 template <typename T>
-__global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const float* c_prev, int B, int H, int Hk,
+__global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const float* c_prev, int B, int H, int Hk, int Hp,
                                      float* gates, float* c, T* h, T* hc) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
-  if (u >= H) return;
+  if (u >= H) {
+    const int j = Hk + (u - H);
+    if (j < Hp) hc[(long)b * Hp + j] = (T)0;
+    return;
+  }
   const int j = rank[u];
   float gi = 0, gf = 0, gg = 0, go = 0, cv = 0, hv = 0;
   if (j >= 0) {
-    const float* g = G + (long)b * 4 * Hk;
+    const float* g = G + (long)b * 4 * Hp;
     gi = sigmoidf_(g[j]);
-    gf = sigmoidf_(g[Hk + j]);
-    gg = tanhf(g[2 * Hk + j]);
-    go = sigmoidf_(g[3 * Hk + j]);
+    gf = sigmoidf_(g[Hp + j]);
+    gg = tanhf(g[2 * Hp + j]);
+    go = sigmoidf_(g[3 * Hp + j]);
     const float cp = c_prev ? c_prev[(long)b * H + u] : 0.0f;
     cv = gf * cp + gi * gg;
     hv = go * tanhf(cv);
-    hc[(long)b * Hk + j] = ElemTraits<T>::from_f32(hv);
+    hc[(long)b * Hp + j] = ElemTraits<T>::from_f32(hv);
   }
   float* ga = gates + (long)b * 4 * H;
   ga[u] = gi;
@@ -69,16 +89,21 @@ __global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const floa
   h[(long)b * H + u] = ElemTraits<T>::from_f32(hv);
 }
 
-// One time step, backward.  dh_next: compact [B x Hk] fp32 (NULL at the last step);
+// One time step, backward.  dh_next: compact [B x Hp] fp32 (NULL at the last step);
 // dc_next: [B x H] fp32, read unless `first`, then overwritten.  Writes the compact gate
-// gradient dG [B x 4Hk] in the storage dtype.
+// gradient dG [B x 4Hp] in the storage dtype (zeros at the padding).
 template <typename T>
 __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const float* c_prev, const T* dh_ext,
-                                     const float* dh_next, float* dc_next, const int* rank, int B, int H, int Hk,
+                                     const float* dh_next, float* dc_next, const int* rank, int B, int H, int Hk, int Hp,
                                      int first, T* dG) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
-  if (u >= H) return;
+  T* d = dG + (long)b * 4 * Hp;
+  if (u >= H) {
+    const int j = Hk + (u - H);
+    if (j < Hp) d[j] = d[Hp + j] = d[2 * Hp + j] = d[3 * Hp + j] = (T)0;
+    return;
+  }
   const int j = rank[u];
   if (j < 0) return;
   const float* ga = gates + (long)b * 4 * H;
@@ -86,31 +111,56 @@ __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const f
   const float tc = tanhf(c[(long)b * H + u]);
   const float cp = c_prev ? c_prev[(long)b * H + u] : 0.0f;
   float dh = ElemTraits<T>::to_f32(dh_ext[(long)b * H + u]);
-  if (dh_next) dh += dh_next[(long)b * Hk + j];
+  if (dh_next) dh += dh_next[(long)b * Hp + j];
   float dc = dh * go * (1.0f - tc * tc);
   if (!first) dc += dc_next[(long)b * H + u];
-  T* d = dG + (long)b * 4 * Hk;
   d[j] = ElemTraits<T>::from_f32(dc * gg * gi * (1.0f - gi));
-  d[Hk + j] = ElemTraits<T>::from_f32(dc * cp * gf * (1.0f - gf));
-  d[2 * Hk + j] = ElemTraits<T>::from_f32(dc * gi * (1.0f - gg * gg));
-  d[3 * Hk + j] = ElemTraits<T>::from_f32(dh * tc * go * (1.0f - go));
+  d[Hp + j] = ElemTraits<T>::from_f32(dc * cp * gf * (1.0f - gf));
+  d[2 * Hp + j] = ElemTraits<T>::from_f32(dc * gi * (1.0f - gg * gg));
+  d[3 * Hp + j] = ElemTraits<T>::from_f32(dh * tc * go * (1.0f - go));
   dc_next[(long)b * H + u] = dc * gf;
+}
+
+// dW[(g*H + u)][q] from the compact gradients dwx[4Hp x I] and dwh[4Hp x Hp]; +0.0 for every
+// row of a dropped unit and every recurrent column of a dropped unit.
+template <typename T>
+__global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* rank, int H, int I, int Hp, T* dW) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  const int p = blockIdx.y;  // physical gate row
+  if (q >= I + H) return;
+  const int g = p / H, u = p - g * H;
+  const int j = rank[u];
+  T v = (T)0;
+  if (j >= 0) {
+    const long r = (long)g * Hp + j;
+    if (q < I) {
+      v = dwx[r * I + q];
+    } else {
+      const int jv = rank[q - I];
+      if (jv >= 0) v = dwh[r * Hp + jv];
+    }
+  }
+  dW[(long)p * (I + H) + q] = v;
 }
 
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 struct LstmWs {
   int* rank;
-  int* grows;
-  char* whc;     // [4Hk x Hk] dtype
-  char* hc;      // [T*B x Hk] dtype
-  char* big;     // fwd: Gx [T*B x 4Hk] fp32; bwd: dG [T*B x 4Hk] dtype
-  float* dh_next;  // [B x Hk]
+  char* wxc;     // [4Hp x I] dtype
+  char* whc;     // [4Hp x Hp] dtype
+  char* hc;      // [T*B x Hp] dtype
+  char* big;     // fwd: Gx [T*B x 4Hp] fp32; bwd: dG [T*B x 4Hp] dtype
+  float* dh_next;  // [B x Hp]
   float* dc_next;  // [B x H]
+  char* dwx;     // [4Hp x I] dtype
+  char* dwh;     // [4Hp x Hp] dtype
+  char* part;    // fp32 partial sums of split products
+  size_t part_bytes;
   size_t total;
 };
 
-static LstmWs lstm_ws_layout(char* base, int es, int T, int B, int H, int Hk) {
+static LstmWs lstm_ws_layout(char* base, int es, int T, int B, int I, int H, int Hk) {
   LstmWs w;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -118,13 +168,22 @@ static LstmWs lstm_ws_layout(char* base, int es, int T, int B, int H, int Hk) {
     off += align_up(bytes ? bytes : 1, 256);
     return p;
   };
+  const size_t Hp = pad8(Hk);
   w.rank = (int*)take((size_t)H * 4);
-  w.grows = (int*)take((size_t)4 * Hk * 4);
-  w.whc = take((size_t)4 * Hk * Hk * es);
-  w.hc = take((size_t)T * B * Hk * es);
-  w.big = take((size_t)T * B * 4 * Hk * 4);
-  w.dh_next = (float*)take((size_t)B * Hk * 4);
+  w.wxc = take(4 * Hp * I * es);
+  w.whc = take(4 * Hp * Hp * es);
+  w.hc = take((size_t)T * B * Hp * es);
+  w.big = take((size_t)T * B * 4 * Hp * 4);
+  w.dh_next = (float*)take((size_t)B * Hp * 4);
   w.dc_next = (float*)take((size_t)B * H * 4);
+  w.dwx = take(4 * Hp * I * es);
+  w.dwh = take(4 * Hp * Hp * es);
+  // room for the partial sums of any product here split 8 ways, capped at 256 MiB
+  size_t big = 4 * Hp * (size_t)(I > (int)Hp ? I : (int)Hp);
+  if ((size_t)B * 4 * Hp > big) big = (size_t)B * 4 * Hp;
+  w.part_bytes = big * 4 * 8;
+  if (w.part_bytes > ((size_t)256 << 20)) w.part_bytes = (size_t)256 << 20;
+  w.part = take(w.part_bytes);
   w.total = off;
   return w;
 }
@@ -144,19 +203,45 @@ static int32_t lstm_check(LstmArgs& a, const ard_pattern* pat) {
   a.ax = axis_of_pattern(pat, a.H);
   a.Hk = a.ax.n;
   a.es = a.dtype == ARD_BF16 ? 2 : 4;
-  if ((long)a.T * a.B > 0x7fffffffL / 4 || (long)a.B > 65535) return fail(ARD_ESHAPE, "T*B or B too large");
+  if ((long)a.T * a.B > 0x7fffffffL / 4 || (long)a.B > 65535 || (long)a.T * a.B > 65535 * 64L)
+    return fail(ARD_ESHAPE, "T*B or B too large");
+  if (4L * a.H > 65535) return fail(ARD_ESHAPE, "more than 16383 hidden units");
   return ARD_OK;
+}
+
+// plain product C[M x N] (+)= A . B with identity maps on every side
+static GemmParams plain_gemm(const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K,
+                             bool a_kc, bool b_kc, int ce, bool out_f32, float beta) {
+  GemmParams P{};
+  P.k = axis_identity(K);
+  P.A = Operand{A, lda, axis_identity(M), 0, 0, 0, 0};
+  P.B = Operand{B, ldb, axis_identity(N), 0, 0, 0, 0};
+  P.A.vec = operand_vec_ok(P.A, a_kc, P.k, ce);
+  P.B.vec = operand_vec_ok(P.B, b_kc, P.k, ce);
+  P.C.p = C;
+  P.C.ld = ldc;
+  P.C.rm = axis_identity(M);
+  P.C.cn = axis_identity(N);
+  P.C.out_f32 = out_f32 ? 1 : 0;
+  P.C.alpha = 1.0f;
+  P.C.beta = beta;
+  P.M = M;
+  P.N = N;
+  return P;
 }
 
 template <typename T>
 static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, hipStream_t stream) {
-  hipLaunchKernelGGL(lstm_setup_kernel, dim3(1), dim3(1024), 0, stream, a.ax, a.H, w.rank, w.grows);
+  hipLaunchKernelGGL(lstm_setup_kernel, dim3(1), dim3(1024), 0, stream, a.ax, a.H, w.rank);
   ARD_LAUNCH_CHECK("lstm_setup_kernel");
+  const int Hp = pad8(a.Hk);
   if (a.Hk > 0) {
-    dim3 grid(ceil_div(a.Hk, 256), 4 * a.Hk);
-    hipLaunchKernelGGL(gather_cols_kernel<T>, grid, dim3(256), 0, stream, (const T*)W, (long)(a.I + a.H),
-                       (const int*)w.grows, a.I, a.ax, (T*)w.whc, 4 * a.Hk);
-    ARD_LAUNCH_CHECK("gather_cols_kernel");
+    hipLaunchKernelGGL(lstm_gather_w_kernel<T>, dim3(ceil_div(a.I, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
+                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, a.I, (T*)w.wxc);
+    ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
+    hipLaunchKernelGGL(lstm_gather_w_kernel<T>, dim3(ceil_div(Hp, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
+                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 1, Hp, (T*)w.whc);
+    ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
   }
   return ARD_OK;
 }
@@ -164,52 +249,29 @@ static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, h
 template <typename T>
 static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void* h, float* c, float* gates,
                           const LstmWs& w, hipStream_t stream) {
-  const int T_ = a.T, B = a.B, I = a.I, H = a.H, Hk = a.Hk, ce = 16 / a.es;
+  const int T_ = a.T, B = a.B, I = a.I, H = a.H, Hk = a.Hk, Hp = pad8(Hk), ce = 16 / a.es;
   int32_t st = lstm_prepare<T>(a, W, w, stream);
   if (st) return st;
   float* Gx = (float*)w.big;
   if (Hk > 0) {
-    // input projection of every step: Gx[T*B x 4Hk] = x . W[kept gate rows, 0:I]^T
-    GemmParams P{};
-    P.A = Operand{x, I, axis_identity(T_ * B), (I % ce) == 0 && al16(x)};
-    P.B = Operand{W, I + H, axis_list(w.grows, 4 * Hk, 4 * H), (I % ce) == 0 && ((I + H) % ce) == 0 && al16(W)};
-    P.k = axis_identity(I);
-    P.C.p = Gx;
-    P.C.ld = 4 * Hk;
-    P.C.rm = axis_identity(T_ * B);
-    P.C.cn = axis_identity(4 * Hk);
-    P.C.out_f32 = 1;
-    P.C.alpha = 1.0f;
-    P.M = T_ * B;
-    P.N = 4 * Hk;
-    st = run_gemm(a.dtype, true, true, P, 0, 0, stream);
+    // input projection of every step: Gx[T*B x 4Hp] = x . Wx'^T
+    GemmParams P = plain_gemm(x, I, w.wxc, I, Gx, 4 * Hp, T_ * B, 4 * Hp, I, true, true, ce, true, 0.0f);
+    st = run_gemm(a.dtype, true, true, P, 0, 0, stream, w.part, w.part_bytes);
     if (st) return st;
   }
-  dim3 cgrid(ceil_div(H, 256), B);
+  dim3 cgrid(ceil_div(H + (Hp - Hk), 256), B);
   for (int t = 0; t < T_; ++t) {
-    float* Gt = Gx + (long)t * B * 4 * Hk;
-    T* hc_t = (T*)w.hc + (long)t * B * Hk;
+    float* Gt = Gx + (long)t * B * 4 * Hp;
+    T* hc_t = (T*)w.hc + (long)t * B * Hp;
     if (t > 0 && Hk > 0) {
-      // recurrent part: G_t += h_{t-1}[kept] . W_h'^T
-      const T* hc_prev = (const T*)w.hc + (long)(t - 1) * B * Hk;
-      GemmParams P{};
-      P.A = Operand{hc_prev, Hk, axis_identity(B), (Hk % ce) == 0 && al16(hc_prev)};
-      P.B = Operand{w.whc, Hk, axis_identity(4 * Hk), (Hk % ce) == 0};
-      P.k = axis_identity(Hk);
-      P.C.p = Gt;
-      P.C.ld = 4 * Hk;
-      P.C.rm = axis_identity(B);
-      P.C.cn = axis_identity(4 * Hk);
-      P.C.out_f32 = 1;
-      P.C.alpha = 1.0f;
-      P.C.beta = 1.0f;
-      P.M = B;
-      P.N = 4 * Hk;
-      st = run_gemm(a.dtype, true, true, P, 0, 0, stream);
+      // recurrent part: G_t += h_{t-1}[kept] . Wh'^T
+      const T* hc_prev = (const T*)w.hc + (long)(t - 1) * B * Hp;
+      GemmParams P = plain_gemm(hc_prev, Hp, w.whc, Hp, Gt, 4 * Hp, B, 4 * Hp, Hp, true, true, ce, true, 1.0f);
+      st = run_gemm(a.dtype, true, true, P, 0, 0, stream, w.part, w.part_bytes);
       if (st) return st;
     }
     hipLaunchKernelGGL(lstm_cell_fwd_kernel<T>, cgrid, dim3(256), 0, stream, (const float*)Gt, (const int*)w.rank,
-                       t > 0 ? (const float*)(c + (long)(t - 1) * B * H) : (const float*)nullptr, B, H, Hk,
+                       t > 0 ? (const float*)(c + (long)(t - 1) * B * H) : (const float*)nullptr, B, H, Hk, Hp,
                        gates + (long)t * B * 4 * H, c + (long)t * B * H, (T*)h + (long)t * B * H, hc_t);
     ARD_LAUNCH_CHECK("lstm_cell_fwd_kernel");
   }
@@ -220,7 +282,7 @@ template <typename T>
 static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const void* h, const float* c,
                           const float* gates, const void* dh, void* dx, void* dW, const LstmWs& w,
                           hipStream_t stream) {
-  const int T_ = a.T, B = a.B, I = a.I, H = a.H, Hk = a.Hk, ce = 16 / a.es;
+  const int T_ = a.T, B = a.B, I = a.I, H = a.H, Hk = a.Hk, Hp = pad8(Hk), ce = 16 / a.es;
   int32_t st = lstm_prepare<T>(a, W, w, stream);
   if (st) return st;
   if (Hk == 0) {
@@ -228,97 +290,52 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     if (st) return st;
     return fill_matrix(a.dtype, dW, (long)4 * H * (I + H), 0.0f, stream);
   }
-  // compact copy of the stored hidden states: hc[T*B x Hk] = h[:, kept]
-  {
-    dim3 grid(ceil_div(Hk, 256), T_ * B);
-    if ((long)T_ * B > 65535) return fail(ARD_ESHAPE, "T*B above 65535 is not supported by the LSTM backward");
-    hipLaunchKernelGGL(gather_cols_kernel<T>, grid, dim3(256), 0, stream, (const T*)h, (long)H, (const int*)nullptr, 0,
-                       a.ax, (T*)w.hc, T_ * B);
-    ARD_LAUNCH_CHECK("gather_cols_kernel");
+  // compact copy of the stored hidden states: hc[T*B x Hp] = h[:, kept]
+  for (long r0 = 0; r0 < (long)T_ * B; r0 += 65535) {
+    const long rows = (long)T_ * B - r0 < 65535 ? (long)T_ * B - r0 : 65535;
+    hipLaunchKernelGGL(lstm_gather_h_kernel<T>, dim3(ceil_div(Hp, 256), (unsigned)rows), dim3(256), 0, stream,
+                       (const T*)h + r0 * H, H, a.ax, Hp, (T*)w.hc + r0 * Hp);
+    ARD_LAUNCH_CHECK("lstm_gather_h_kernel");
   }
   T* dG = (T*)w.big;
-  dim3 cgrid(ceil_div(H, 256), B);
+  dim3 cgrid(ceil_div(H + (Hp - Hk), 256), B);
   for (int t = T_ - 1; t >= 0; --t) {
-    T* dGt = dG + (long)t * B * 4 * Hk;
+    T* dGt = dG + (long)t * B * 4 * Hp;
     hipLaunchKernelGGL(lstm_cell_bwd_kernel<T>, cgrid, dim3(256), 0, stream, gates + (long)t * B * 4 * H,
                        c + (long)t * B * H, t > 0 ? c + (long)(t - 1) * B * H : (const float*)nullptr,
                        (const T*)dh + (long)t * B * H, t < T_ - 1 ? (const float*)w.dh_next : (const float*)nullptr,
-                       w.dc_next, (const int*)w.rank, B, H, Hk, t == T_ - 1 ? 1 : 0, dGt);
+                       w.dc_next, (const int*)w.rank, B, H, Hk, Hp, t == T_ - 1 ? 1 : 0, dGt);
     ARD_LAUNCH_CHECK("lstm_cell_bwd_kernel");
     if (t > 0) {
-      // dh_{t-1}[kept] = dG_t . W_h'
-      GemmParams P{};
-      P.A = Operand{dGt, 4 * Hk, axis_identity(B), ((4 * Hk) % ce) == 0 && al16(dGt)};
-      P.B = Operand{w.whc, Hk, axis_identity(Hk), 0};
-      P.k = axis_identity(4 * Hk);
-      P.C.p = w.dh_next;
-      P.C.ld = Hk;
-      P.C.rm = axis_identity(B);
-      P.C.cn = axis_identity(Hk);
-      P.C.out_f32 = 1;
-      P.C.alpha = 1.0f;
-      P.M = B;
-      P.N = Hk;
-      P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
-      st = run_gemm(a.dtype, true, false, P, 0, 0, stream);
+      // dh_{t-1}[kept] = dG_t . Wh'
+      GemmParams P = plain_gemm(dGt, 4 * Hp, w.whc, Hp, w.dh_next, Hp, B, Hp, 4 * Hp, true, false, ce, true, 0.0f);
+      st = run_gemm(a.dtype, true, false, P, 0, 0, stream, w.part, w.part_bytes);
       if (st) return st;
     }
   }
-  // dx[T*B x I] = dG . W[kept gate rows, 0:I]
   {
-    GemmParams P{};
-    P.A = Operand{dG, 4 * Hk, axis_identity(T_ * B), ((4 * Hk) % ce) == 0 && al16(dG), 1};
-    P.B = Operand{W, I + H, axis_identity(I), 0};
-    P.k = axis_list(w.grows, 4 * Hk, 4 * H);
-    P.C.p = dx;
-    P.C.ld = I;
-    P.C.rm = axis_identity(T_ * B);
-    P.C.cn = axis_identity(I);
-    P.C.alpha = 1.0f;
-    P.M = T_ * B;
-    P.N = I;
-    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
-    st = run_gemm(a.dtype, true, false, P, 0, 0, stream);
+    // dx[T*B x I] = dG . Wx'
+    GemmParams P = plain_gemm(dG, 4 * Hp, w.wxc, I, dx, I, T_ * B, I, 4 * Hp, true, false, ce, false, 0.0f);
+    st = run_gemm(a.dtype, true, false, P, 0, 0, stream, w.part, w.part_bytes);
     if (st) return st;
   }
-  // dW[kept gate rows, 0:I] = dG^T . x ; the other rows of these columns get zeros
   {
-    GemmParams P{};
-    P.A = Operand{dG, 4 * Hk, axis_identity(4 * Hk), 0};
-    P.B = Operand{x, I, axis_identity(I), 0};
-    P.k = axis_identity(T_ * B);
-    P.C.p = dW;
-    P.C.ld = I + H;
-    P.C.rm = axis_list(w.grows, 4 * Hk, 4 * H);
-    P.C.cn = axis_identity(I);
-    P.C.fill = 1;
-    P.C.alpha = 1.0f;
-    P.M = 4 * Hk;
-    P.N = I;
-    P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
-    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
-    st = run_gemm(a.dtype, false, false, P, 0, 0, stream);
+    // compact weight gradients: dwx[4Hp x I] = dG^T . x, dwh[4Hp x Hp] = dG[1:]^T . h[kept][:-1]
+    GemmParams P = plain_gemm(dG, 4 * Hp, x, I, w.dwx, I, 4 * Hp, I, T_ * B, false, false, ce, false, 0.0f);
+    st = run_gemm(a.dtype, false, false, P, 0, 0, stream, w.part, w.part_bytes);
+    if (st) return st;
+    if (T_ > 1) {
+      P = plain_gemm(dG + (long)B * 4 * Hp, 4 * Hp, w.hc, Hp, w.dwh, Hp, 4 * Hp, Hp, (T_ - 1) * B, false, false, ce, false,
+                     0.0f);
+      st = run_gemm(a.dtype, false, false, P, 0, 0, stream, w.part, w.part_bytes);
+    } else {
+      st = fill_matrix(a.dtype, w.dwh, (long)4 * Hp * Hp, 0.0f, stream);
+    }
     if (st) return st;
   }
-  // dW[kept gate rows, I + kept units] = dG[1:]^T . h[kept][:-1] ; zeros elsewhere in columns I..I+H
-  {
-    GemmParams P{};
-    P.A = Operand{dG + (long)B * 4 * Hk, 4 * Hk, axis_identity(4 * Hk), 0};
-    P.B = Operand{w.hc, Hk, axis_identity(Hk), 0};
-    P.k = axis_identity((T_ - 1) * B);
-    P.C.p = (T*)dW + I;
-    P.C.ld = I + H;
-    P.C.rm = axis_list(w.grows, 4 * Hk, 4 * H);
-    P.C.cn = a.ax;
-    P.C.fill = 1;
-    P.C.alpha = 1.0f;
-    P.M = 4 * Hk;
-    P.N = Hk;
-    P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
-    P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
-    st = run_gemm(a.dtype, false, false, P, 0, 0, stream);
-    if (st) return st;
-  }
+  hipLaunchKernelGGL(lstm_scatter_dw_kernel<T>, dim3(ceil_div(I + H, 256), 4 * H), dim3(256), 0, stream, (const T*)w.dwx,
+                     (const T*)w.dwh, (const int*)w.rank, H, I, Hp, (T*)dW);
+  ARD_LAUNCH_CHECK("lstm_scatter_dw_kernel");
   return ARD_OK;
 }
 
@@ -330,7 +347,7 @@ extern "C" size_t ard_lstm_workspace_bytes(int32_t dtype, int32_t T, int32_t B, 
                                            const ard_pattern* pat) {
   LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
   if (lstm_check(a, pat)) return 0;
-  return lstm_ws_layout(nullptr, a.es, T, B, H, a.Hk).total;
+  return lstm_ws_layout(nullptr, a.es, T, B, I, H, a.Hk).total;
 }
 
 extern "C" int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const void* x,
@@ -340,7 +357,7 @@ extern "C" int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, 
   int32_t st = lstm_check(a, pat);
   if (st) return st;
   if (!x || !W || !h || !c || !gates) return fail(ARD_EINVAL, "null tensor pointer");
-  LstmWs w = lstm_ws_layout((char*)ws, a.es, T, B, H, a.Hk);
+  LstmWs w = lstm_ws_layout((char*)ws, a.es, T, B, I, H, a.Hk);
   if (!ws || ws_bytes < w.total) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
   if (dtype == ARD_BF16) return lstm_fwd_t<uint16_t>(a, x, W, h, c, gates, w, (hipStream_t)stream);
   return lstm_fwd_t<float>(a, x, W, h, c, gates, w, (hipStream_t)stream);
@@ -354,7 +371,7 @@ extern "C" int32_t ard_lstm_bwd(int32_t dtype, int32_t T, int32_t B, int32_t I, 
   int32_t st = lstm_check(a, pat);
   if (st) return st;
   if (!x || !W || !h || !c || !gates || !dh || !dx || !dW) return fail(ARD_EINVAL, "null tensor pointer");
-  LstmWs w = lstm_ws_layout((char*)ws, a.es, T, B, H, a.Hk);
+  LstmWs w = lstm_ws_layout((char*)ws, a.es, T, B, I, H, a.Hk);
   if (!ws || ws_bytes < w.total) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
   if (dtype == ARD_BF16) return lstm_bwd_t<uint16_t>(a, x, W, h, c, gates, dh, dx, dW, w, (hipStream_t)stream);
   return lstm_bwd_t<float>(a, x, W, h, c, gates, dh, dx, dW, w, (hipStream_t)stream);
