@@ -37,7 +37,8 @@ def _check(dtype, x, W, dh, m, pat, xd, Wd, dhd, what):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("T,B,I,H,dp,b", [(5, 6, 24, 32, 2, 1), (4, 3, 10, 37, 3, 3), (3, 70, 40, 64, 1, 1),
-                                           (6, 33, 72, 136, 4, 2), (1, 4, 8, 8, 2, 2)])
+                                           (6, 33, 72, 136, 4, 2), (1, 4, 8, 8, 2, 2),
+                                           (3, 64, 128, 200, 3, 1)])  # 67 kept units: padded compact layout
 def test_lstm_row_pattern_parity(dtype, T, B, I, H, dp, b):
     print(f"lstm case dtype={dtype} T={T} B={B} I={I} H={H} dp={dp} b={b}", flush=True)
     rng = np.random.default_rng(T * 100 + H)
