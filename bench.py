@@ -36,7 +36,7 @@ N_PATTERNS = 8           # dp_max of the searched distribution
 SEED = 2
 # HBM bytes per launch of the dominant call's GEMM kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --exec eager` (summaries under profiles/); None until measured
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {"L2.bwd_weight": 15998662}   # 11243 KiB fetched + 4380 KiB written per launch
 
 
 def parse():
@@ -49,6 +49,9 @@ def parse():
                          "machine); graph: every iteration is one replay of a captured two-lane HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (reference for the HBM traffic counters)")
+    ap.add_argument("--only-call", default=None, metavar="NAME",
+                    help="profiling aid: after one full warm-up pass, issue only this call of the rate-0.5 plans "
+                         "(e.g. L2.bwd_weight) for --steps iterations, print its average time and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     return ap.parse_args()
@@ -248,14 +251,19 @@ def time_torch_dense(torch, chain, steps, warmup, mode):
         return time.perf_counter() - t0
 
 
-def per_call_times(torch, chain, plans, reps=3):
+def per_call_times(torch, chain, plans, reps=3, only=None):
     """Per-call HIP-event durations (events on the stream the kernels run on), summed per call name
-    over the plans; every call is issued `reps` times back to back inside its bracket."""
+    over the plans; every call is issued once untimed and then `reps` times back to back inside its
+    bracket.  `only`: issue just that call (one full iteration runs first so every buffer holds finite
+    values; after that only the shapes of a plan matter for the time and the traffic of its calls)."""
     tot, cnt, flops = {}, {}, {}
     with torch.cuda.stream(chain.main):
-        for plan in plans:
-            chain.run(plan, lanes=1)   # inputs of every call hold this plan's values
+        for i, plan in enumerate(plans):
+            if only is None or i == 0:
+                chain.run(plan, lanes=1)   # inputs of every call hold this plan's values (only: shapes suffice)
             for _, lane, fn, args, name, fl in chain.calls(plan):
+                if only is not None and name != only:
+                    continue
                 if lane == 1:
                     args = args[:-1] + (chain.main.cuda_stream,)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -425,6 +433,17 @@ def main():
     dense_f = dense_flops_per_iter()
     n_plan = max(100, args.steps + args.warmup)
     spin_up(torch)
+
+    if args.only_call:
+        _, cdf = ard.search_k(0.5, N_PATTERNS)
+        pats = [tuple(ard.pattern_sample(cdf, SEED, it, layer) for layer in (1, 2)) for it in range(n_plan)]
+        plans = [chain.plan(pp) for pp in pats]
+        used = [plans[(args.warmup + it) % len(plans)] for it in range(args.steps)]
+        tot, cnt, fl = per_call_times(torch, chain, used, only=args.only_call)
+        name = args.only_call
+        print(json.dumps({"call": name, "launches": cnt[name] * 4, "avg_us": tot[name] / cnt[name] * 1e3,
+                          "kept_tflops": fl[name] / (tot[name] / 1e3) / 1e12}))
+        return
 
     # dense chains: this library at dp=1, and the vendor GEMM, run the same way as the dropout chain
     dense_plan = [chain.plan(((1, 1), (1, 1)))]

@@ -126,18 +126,24 @@ int32_t ard_pattern_gen(const ard_pattern* pat, int32_t rows, int32_t cols,
  * Layout flags of the three layer calls below (OR them into `flags`).  The method multiplies
  * compacted operands and scatters the result (Section 3.1); these flags let a chain of
  * layers keep its activations compact between calls instead of scattering and re-gathering:
- *   ARD_IN_COMPACT   the input-side activation (X, dX, relu_src) is [B x I'] and holds only the
- *                    kept input neurons of pat_in, in ascending order;
- *   ARD_OUT_COMPACT  the output-side activation (Y, dY) is [B x O'] and holds only the kept
+ *   ARD_IN_COMPACT   the input-side activation (X, dX, relu_src) is [B x pad8(I')] and holds only
+ *                    the kept input neurons of pat_in, in ascending order;
+ *   ARD_OUT_COMPACT  the output-side activation (Y, dY) is [B x pad8(O')] and holds only the kept
  *                    output neurons of pat_out (nothing is zero-filled then);
- *   ARD_W_COMPACT    W is the compact [O' x I'] matrix written by ard_compact_weight().
+ *   ARD_W_COMPACT    W is the compact matrix written by ard_compact_weight().
+ * pad8(n) = n rounded up to a multiple of 8.  Every compact matrix stores its kept-unit axes
+ * padded to pad8 with ZEROS (rows of 16-byte pieces whatever the kept count is): compact inputs
+ * must carry zero padding, compact outputs are written with it.  With a NONE pattern a compact
+ * activation is simply the dense one with its rows padded to pad8 columns (useful for narrow
+ * matrices such as a 10-column loss gradient).
  * dW is always the full [O x I] matrix.  Without ARD_W_COMPACT, a forward or backward-data
  * call whose pat_in is not NONE first gathers W[kept o, kept i] into its workspace.
  * Tile patterns take no flags.
  */
 enum { ARD_IN_COMPACT = 1, ARD_OUT_COMPACT = 2, ARD_W_COMPACT = 4 };
 
-/* Wc[O' x I'] = W[kept o, kept i] (ROW/LIST/NONE patterns). One gather kernel, no workspace. */
+/* Wc[pad8(O') x pad8(I')]: W[kept o, kept i] in the top-left corner, zeros in the padding
+ * (ROW/LIST/NONE patterns). One gather kernel, no workspace. */
 int32_t ard_compact_weight(int32_t dtype, int32_t I, int32_t O, const void* W, void* Wc,
                            const ard_pattern* pat_out, const ard_pattern* pat_in, void* stream);
 
