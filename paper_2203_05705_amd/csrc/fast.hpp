@@ -81,6 +81,10 @@ struct FastParams {
   int splits;
   int M, N, tiles_m, tiles_n, group_m, total_tiles;
   ConvMap cv;  // MODE 1 / 2 of the kernel only
+  // Scattering epilogue (row patterns without compact outputs): the tile's results go through
+  // LDS and are written, with the dropped positions it owns as +0.0, through these affine maps.
+  int scatter, scatter_vec;
+  Axis srm, scn;
 };
 
 #define ARD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
@@ -270,6 +274,78 @@ __device__ __forceinline__ void wait_vmcnt() {
 // with wait_vmcnt before the barrier) and read by volatile asm, so no fence is wanted: a fence
 // would also wait for the younger stages still in flight.
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Scattering store of one workgroup tile.  `tile` holds the final bf16 values of compact rows
+// [m0, m1) x columns [n0, n1) ([.][ldt] in LDS).  Output maps are affine with off < step: compact
+// index i owns the physical group [i*step, (i+1)*step) that contains its kept position, the last
+// index also the tail up to nphys; everything in the owned region that is not a kept position is
+// written as +0.0.  VEC: 16-byte pieces (host checks extents, leading dimension and alignment).
+template <bool VEC>
+__device__ __forceinline__ void direct_scatter_tile(const uint16_t* tile, int ldt, const FastParams& P, int m0, int m1,
+                                                    int n0, int n1, int tid, int nthreads) {
+  const Axis& rm = P.srm;
+  const Axis& cn = P.scn;
+  const int sr = rm.step, sc = cn.step;
+  const int c_lo = n0 * sc, c_hi = n1 == P.N ? cn.nphys : n1 * sc;
+  constexpr int W = VEC ? 8 : 1;
+  const int CW = (c_hi - c_lo + W - 1) / W;
+  // threads = (row slot, piece slot): a power-of-two number of lanes walks the pieces of a row
+  int sh = 0;
+  while ((1 << sh) < CW && sh < 6) ++sh;
+  const int LPR = 1 << sh, RPP = nthreads >> sh;
+  const int rsub = tid >> sh, cl = tid & (LPR - 1);
+  auto write_row = [&](int r, int li) {
+    uint16_t* rowp = P.C + (long)r * P.ldc;
+    if (li < 0) {
+      for (int cq = cl; cq < CW; cq += LPR) {
+        if (VEC) *reinterpret_cast<uint4*>(rowp + c_lo + cq * W) = make_uint4(0, 0, 0, 0);
+        else rowp[c_lo + cq] = 0;
+      }
+      return;
+    }
+    const uint16_t* trow = tile + li * ldt - n0;
+    for (int cq = cl; cq < CW; cq += LPR) {
+      const int c0 = c_lo + cq * W;
+      int j = 0;
+      const int d = c0 - cn.off + sc - 1;
+      if (d >= sc) {
+        j = (int)((float)d / (float)sc);
+        j += ((j + 1) * sc <= d) - (j * sc > d);
+      }
+      uint4 gate = make_uint4(0, 0, 0, 0);
+      if (P.relu_src) {
+        const uint16_t* g = P.relu_src + (long)r * P.ldc + c0;
+        if (VEC) gate = *reinterpret_cast<const uint4*>(g);
+        else gate.x = *g;
+      }
+      const uint32_t* gw = reinterpret_cast<const uint32_t*>(&gate);
+      uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int t = 0; t < W; ++t) {
+        if (!(j < n1 && cn.off + j * sc == c0 + t)) continue;
+        uint32_t v = trow[j];
+        ++j;
+        if (P.relu_src) {
+          const uint32_t g = (gw[t >> 1] >> (16 * (t & 1))) & 0xffffu;
+          if (!(bf16_bits_to_f32((uint16_t)g) > 0.0f)) v = 0;
+        }
+        w[t >> 1] |= v << (16 * (t & 1));
+      }
+      if (VEC) *reinterpret_cast<uint4*>(rowp + c0) = make_uint4(w[0], w[1], w[2], w[3]);
+      else rowp[c0] = (uint16_t)w[0];
+    }
+  };
+  // the groups of this tile's compact rows: one kept row and step - 1 dropped ones each
+  for (int i = m0 + rsub; i < m1; i += RPP)
+    for (int g = 0; g < sr; ++g) {
+      const int r = i * sr + g;
+      if (r >= rm.nphys) break;
+      write_row(r, g == rm.off ? i - m0 : -1);
+    }
+  // the last tile also owns the rows behind the last group
+  if (m1 == P.M)
+    for (int r = P.M * sr + rsub; r < rm.nphys; r += RPP) write_row(r, -1);
+}
 
 // MODE 0: plain product.  MODE 1: convolution, B rows are output pixels gathered from the
 // bordered channels-last grid (contraction = (tap, channel)), output NCHW.  MODE 2: weight
@@ -550,6 +626,30 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
         }
       }
     }
+    return;
+  }
+  if (GENERAL_OUT && MODE == 0 && P.scatter) {
+    // final bf16 values -> LDS (the operand stages are dead once every wave is past its last read)
+    constexpr int LDT = BN + 2;
+    uint16_t* tile = reinterpret_cast<uint16_t*>(lds);
+    __syncthreads();
+#pragma unroll
+    for (int im = 0; im < TM; ++im)
+#pragma unroll
+      for (int in = 0; in < TN; ++in) {
+        const int lj = wn * WTN + in * 32 + (lane & 31);
+        const int li0 = wm * WTM + im * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float x = P.alpha * acc[im][in][v];
+          if (P.relu) x = fmaxf(x, 0.0f);
+          tile[(li0 + 8 * (v >> 2) + (v & 3)) * LDT + lj] = f32_to_bf16_bits(x);
+        }
+      }
+    __syncthreads();
+    const int m1 = min(m0 + F_BM, P.M), n1 = min(n0 + BN, P.N);
+    if (P.scatter_vec) direct_scatter_tile<true>(tile, LDT, P, m0, m1, n0, n1, tid, 64 * NW);
+    else direct_scatter_tile<false>(tile, LDT, P, m0, m1, n0, n1, tid, 64 * NW);
     return;
   }
   int prow[TM];

@@ -180,15 +180,38 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     if (tiles >= 220) break;
   }
   if (tiles >= (1L << 24)) return false;
+  // A scattered bf16 output with zero fill through affine maps is stored by the product's own
+  // epilogue (no partial sums, no finishing pass) unless the product is so small that it has to
+  // be split to occupy the chip at all.
+  auto owns_groups = [](const Axis& a) { return a.kind == AX_AFFINE && a.step >= 1 && a.off < a.step; };
+  bool scatter = !direct_out && C.fill && !C.out_f32 && C.beta == 0.0f && owns_groups(C.rm) && owns_groups(C.cn) &&
+                 (long)C.rm.nphys * C.ld < (1L << 31) && !getenv("ARD_NO_SCATTER");
+  if (scatter) {
+    // tile: as large as still gives every CU a workgroup; at least 64 workgroups or no scatter
+    bm = bn = 64;
+    for (const TileCfg& c : kTileCfgs) {
+      if (c.bm == 256 && c.bn == 256) continue;
+      const long t = (long)ceil_div(P.M, c.bm) * ceil_div(P.N, c.bn);
+      if (t >= 220) {
+        bm = c.bm, bn = c.bn;
+        break;
+      }
+    }
+    tiles = (long)ceil_div(P.M, bm) * ceil_div(P.N, bn);
+    // With few workgroups the zero fill of large owned regions is better spread over the whole
+    // chip by the finishing pass (measured: regions above 16K elements lose below 160 tiles).
+    const long region = (long)bm * C.rm.step * bn * C.cn.step;
+    if (tiles < 64 || (tiles < 160 && region > 16384)) scatter = false;
+  }
   int splits = 1;
-  if (tiles < 160 && steps >= 4) {
+  if (!scatter && tiles < 160 && steps >= 4) {
     splits = (int)(320 / tiles);
     if (splits > steps / 2) splits = steps / 2;
     if (splits > 8) splits = 8;
     if (splits < 1) splits = 1;
   }
   if (bm == 256 && bn == 256) splits = 1;
-  size_t need = (splits > 1 || !direct_out) ? (size_t)splits * P.M * P.N * 4 : 0;
+  size_t need = (splits > 1 || (!direct_out && !scatter)) ? (size_t)splits * P.M * P.N * 4 : 0;
   if (need > ws_bytes || (need && !ws)) {
     if (!direct_out) return false;  // no room for the partials: the general kernel scatters itself
     splits = 1;
@@ -216,6 +239,13 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   F.tiles_m = ceil_div(P.M, bm);
   F.tiles_n = ceil_div(P.N, bn);
   F.total_tiles = (int)tiles;
+  if (scatter && !need) {
+    F.scatter = 1;
+    F.srm = C.rm;
+    F.scn = C.cn;
+    F.scatter_vec = (C.cn.nphys % 8) == 0 && (C.ld % 8) == 0 && ((uintptr_t)C.p & 15) == 0 &&
+                    (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) && C.cn.nphys < (1 << 23);
+  }
   st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
   if (st || !need) return true;
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
