@@ -658,7 +658,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
     const int i0 = m0 + wm * WTM + im * 32;
     prow[im] = i0 < mlim ? (P.c_rows_mapped ? ax_phys(am, i0) : i0) : mphys;
   }
-  const bool plain_bf16 = !GENERAL_OUT || (!P.out_f32 && P.beta == 0.0f && !P.relu_src);
+  const bool plain_bf16 = !GENERAL_OUT || (!P.out_f32 && P.beta == 0.0f);
 #pragma unroll
   for (int in = 0; in < TN; ++in) {
     const int j0 = n0 + wn * WTN + in * 32;
@@ -688,7 +688,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       // of row v+1 (one DPP swap), and each stores one packed 32-bit word.
       const bool odd = lane & 1;
       uint16_t* dst = P.C + (long)rbase * P.ldc + (pc & ~1);
-      const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0) && (((uintptr_t)P.C & 3) == 0);
+      const bool pair_ok = ((pc | 1) < nphys) && ((P.ldc & 1) == 0) && ((nphys & 1) == 0) && (((uintptr_t)P.C & 3) == 0) &&
+                           (((uintptr_t)P.relu_src & 3) == 0);
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
         float x0 = P.alpha * acc[im][in][v], x1 = P.alpha * acc[im][in][v + 1];
@@ -703,11 +704,26 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
           const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, true);  // swap with lane^1
           const uint32_t word = odd ? (got | (b1 << 16)) : (b0 | (got << 16));
           const int dr = odd ? dr0 + 1 : dr0;
-          if (rbase + dr < mphys) *reinterpret_cast<uint32_t*>(dst + (long)dr * P.ldc) = word;
+          if (rbase + dr < mphys) {
+            uint32_t out = word;
+            if (GENERAL_OUT && P.relu_src) {
+              // ReLU mask of the same two positions (same layout as the output)
+              const uint32_t g = *reinterpret_cast<const uint32_t*>(P.relu_src + (long)(rbase + dr) * P.ldc + (pc & ~1));
+              if (!(bf16_bits_to_f32((uint16_t)(g & 0xffffu)) > 0.0f)) out &= 0xffff0000u;
+              if (!(bf16_bits_to_f32((uint16_t)(g >> 16)) > 0.0f)) out &= 0x0000ffffu;
+            }
+            *reinterpret_cast<uint32_t*>(dst + (long)dr * P.ldc) = out;
+          }
         } else {
           uint16_t* d1 = P.C + (long)rbase * P.ldc + pc;
-          if (rbase + dr0 < mphys) d1[(long)dr0 * P.ldc] = (uint16_t)b0;
-          if (rbase + dr0 + 1 < mphys) d1[(long)(dr0 + 1) * P.ldc] = (uint16_t)b1;
+          const uint16_t* g1 = P.relu_src + (long)rbase * P.ldc + pc;
+          uint16_t o0 = (uint16_t)b0, o1 = (uint16_t)b1;
+          if (GENERAL_OUT && P.relu_src) {
+            if (rbase + dr0 < mphys && !(bf16_bits_to_f32(g1[(long)dr0 * P.ldc]) > 0.0f)) o0 = 0;
+            if (rbase + dr0 + 1 < mphys && !(bf16_bits_to_f32(g1[(long)(dr0 + 1) * P.ldc]) > 0.0f)) o1 = 0;
+          }
+          if (rbase + dr0 < mphys) d1[(long)dr0 * P.ldc] = o0;
+          if (rbase + dr0 + 1 < mphys) d1[(long)(dr0 + 1) * P.ldc] = o1;
         }
       }
     }
