@@ -69,6 +69,34 @@ def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
     assert_parity(dW, refdW, dtype, zero_mask=(MW == 0), what="dW")
 
 
+@pytest.mark.parametrize("I", [1024, 1030])
+def test_expanded_outputs_from_compact_inputs_large(I):
+    """Compact operands in, full-size outputs out, at sizes where the product stores its scattered
+    tile and the zeros of the dropped positions itself (16-byte rows for I = 1024, odd tail for 1030)."""
+    B, O, po, pi, dtype = 1024, 768, (2, 1), (3, 2), "bf16"
+    print(f"expanded outputs B={B} I={I} O={O} pat_out={po} pat_in={pi}", flush=True)
+    rng = np.random.default_rng(I)
+    Xv, Wv, dYv = (stored(rng.standard_normal(s) * sc, dtype) for s, sc in (((B, I), 1.0), ((O, I), 0.1), ((B, O), 1.0)))
+    srcv = stored(rng.standard_normal((B, I)), dtype)
+    mo, mi = P.row_mask(O, *po), P.row_mask(I, *pi)
+    ko, ki = P.keep_list(mo), P.keep_list(mi)
+    MW = G.weight_mask_rows(mo, mi)
+    pat_o, pat_i = ard.Pattern.row(*po), ard.Pattern.row(*pi)
+    Xc, dYc = compact_in(Xv[:, ki], dtype), compact_in(dYv[:, ko], dtype)
+    W, src = from_vals(Wv, dtype), from_vals(srcv, dtype)
+    Y = torch.full((B, O), float("nan"), dtype=W.dtype, device="cuda")
+    ard.drop_gemm_fwd(Xc, W, pat_o, pat_i, alpha=0.5, relu=True, flags=ard.IN_COMPACT, out=Y)
+    assert_parity(Y, G.drop_gemm_fwd(Xv, Wv, MW, mo, 0.5, relu=True), dtype, zero_mask=(mo == 0)[None, :], what="Y")
+    dX = torch.full((B, I), float("nan"), dtype=W.dtype, device="cuda")
+    ard.drop_gemm_bwd_data(dYc, W, pat_o, pat_i, relu_src=src, flags=ard.OUT_COMPACT, out=dX)
+    ref = G.relu_bwd(G.drop_gemm_bwd_data(dYv, Wv, MW, mo, 1.0), srcv)
+    assert_parity(dX, ref, dtype, zero_mask=(mi == 0)[None, :], what="dX")
+    dW = torch.full((O, I), float("nan"), dtype=W.dtype, device="cuda")
+    ard.drop_gemm_bwd_weight(dYc, Xc, pat_o, pat_i, flags=ard.IN_COMPACT | ard.OUT_COMPACT, out=dW, I=I, O=O)
+    assert_parity(dW, G.drop_gemm_bwd_weight(dYv, Xv, MW, mo), dtype, zero_mask=(MW == 0), what="dW")
+    torch.cuda.synchronize()
+
+
 def test_config2_mlp_chain_iterations():
     """BASELINE config 2: MLP 784-2048-2048-10, batch 1024, bf16; patterns of iterations 0..4 from the
     searched distribution (rate 0.5), every GEMM of the compact chain against the oracle chain."""
