@@ -495,5 +495,7 @@ __global__ void scale_fill_kernel(T* p, long n, float beta) {
 // max_bn: the widest column tile the contraction lists allow (tile pattern), or 0.
 int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int max_bm, hipStream_t stream,
                  void* ws = nullptr, size_t ws_bytes = 0);
+bool run_gemm_partials(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, void* part,
+                       size_t part_bytes, int* splits, int32_t* status);
 
 }  // namespace ard

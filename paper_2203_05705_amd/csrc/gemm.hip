@@ -61,7 +61,16 @@ static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipSt
 }
 
 static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, void* ws, size_t ws_bytes,
-                       hipStream_t stream, int32_t& st);
+                       hipStream_t stream, int32_t& st, int* raw_splits = nullptr);
+
+// The product as fp32 partial sums part[split][M][N] (compact, alpha not applied) for a caller
+// whose next kernel sums them itself; *splits receives their number.  Returns false (nothing
+// launched) when the product does not qualify for the LDS-direct kernels or the room is too small.
+bool run_gemm_partials(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, hipStream_t stream, void* part,
+                       size_t part_bytes, int* splits, int32_t* status) {
+  *status = ARD_OK;
+  return try_direct(dtype, a_kc, b_kc, P, part, part_bytes, stream, *status, splits);
+}
 
 int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int /*max_bm*/, hipStream_t stream,
                  void* ws, size_t ws_bytes) {
@@ -135,7 +144,7 @@ static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 
 // kernels; results that the kernel cannot store itself (split contraction, element-level
 // scatter with zero fill) pass through fp32 partials in the workspace and a finishing kernel.
 static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, void* ws, size_t ws_bytes,
-                       hipStream_t stream, int32_t& st) {
+                       hipStream_t stream, int32_t& st, int* raw_splits) {
   if (dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
   if (!P.A.vec || !P.B.vec || P.kb_ptr || P.tmask) return false;
   Axis k = P.k;
@@ -172,7 +181,7 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   const int steps = ceil_div(k.n, 64);
   int bm = 64, bn = 64;
   long tiles = 0;
-  const bool plain_out = direct_out && !C.out_f32 && C.beta == 0.0f && !C.relu_src;
+  const bool plain_out = !raw_splits && direct_out && !C.out_f32 && C.beta == 0.0f && !C.relu_src;
   for (const TileCfg& c : kTileCfgs) {
     if (c.bm == 256 && c.bn == 256 && !plain_out) continue;  // that tile only stores plain bf16
     tiles = (long)ceil_div(P.M, c.bm) * ceil_div(P.N, c.bn);
@@ -184,7 +193,7 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   // epilogue (no partial sums, no finishing pass) unless the product is so small that it has to
   // be split to occupy the chip at all.
   auto owns_groups = [](const Axis& a) { return a.kind == AX_AFFINE && a.step >= 1 && a.off < a.step; };
-  bool scatter = !direct_out && C.fill && !C.out_f32 && C.beta == 0.0f && owns_groups(C.rm) && owns_groups(C.cn) &&
+  bool scatter = !raw_splits && !direct_out && C.fill && !C.out_f32 && C.beta == 0.0f && owns_groups(C.rm) && owns_groups(C.cn) &&
                  (long)C.rm.nphys * C.ld < (1L << 31) && !getenv("ARD_NO_SCATTER");
   if (scatter) {
     // tile: as large as still gives every CU a workgroup; at least 64 workgroups or no scatter
@@ -211,7 +220,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     if (splits < 1) splits = 1;
   }
   if (bm == 256 && bn == 256) splits = 1;
-  size_t need = (splits > 1 || (!direct_out && !scatter)) ? (size_t)splits * P.M * P.N * 4 : 0;
+  size_t need = (splits > 1 || raw_splits || (!direct_out && !scatter)) ? (size_t)splits * P.M * P.N * 4 : 0;
+  if (raw_splits && (need > ws_bytes || !ws)) return false;
   if (need > ws_bytes || (need && !ws)) {
     if (!direct_out) return false;  // no room for the partials: the general kernel scatters itself
     splits = 1;
@@ -247,6 +257,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
                     (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) && C.cn.nphys < (1 << 23);
   }
   st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  if (raw_splits) {
+    *raw_splits = splits;
+    return true;
+  }
   if (st || !need) return true;
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
   const int out_cols = C.fill ? C.cn.nphys : P.N;

@@ -57,9 +57,12 @@ __device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __ex
 // activated gates [B x 4H], c [B x H] (fp32), h [B x H] (dtype) with zeros for dropped
 // units, and the compact h [B x Hp] (zeros at the padding) that feeds the next step's product.
 // Threads u >= H take the padding entries.
+// `part` (optional): `splits` fp32 partial sums [B x 4Hp] of this step's recurrent product, `pstride`
+// floats apart, added to G here (the product then needs no finishing pass).
 template <typename T>
-__global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const float* c_prev, int B, int H, int Hk, int Hp,
-                                     float* gates, float* c, T* h, T* hc) {
+__global__ void lstm_cell_fwd_kernel(const float* G, const float* part, int splits, long pstride, const int* rank,
+                                     const float* c_prev, int B, int H, int Hk, int Hp, float* gates, float* c, T* h,
+                                     T* hc) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
   if (u >= H) {
@@ -71,10 +74,15 @@ __global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const floa
   float gi = 0, gf = 0, gg = 0, go = 0, cv = 0, hv = 0;
   if (j >= 0) {
     const float* g = G + (long)b * 4 * Hp;
-    gi = sigmoidf_(g[j]);
-    gf = sigmoidf_(g[Hp + j]);
-    gg = tanhf(g[2 * Hp + j]);
-    go = sigmoidf_(g[3 * Hp + j]);
+    float zi = g[j], zf = g[Hp + j], zg = g[2 * Hp + j], zo = g[3 * Hp + j];
+    for (int s = 0; s < splits; ++s) {
+      const float* q = part + s * pstride + (long)b * 4 * Hp;
+      zi += q[j], zf += q[Hp + j], zg += q[2 * Hp + j], zo += q[3 * Hp + j];
+    }
+    gi = sigmoidf_(zi);
+    gf = sigmoidf_(zf);
+    gg = tanhf(zg);
+    go = sigmoidf_(zo);
     const float cp = c_prev ? c_prev[(long)b * H + u] : 0.0f;
     cv = gf * cp + gi * gg;
     hv = go * tanhf(cv);
@@ -92,10 +100,11 @@ __global__ void lstm_cell_fwd_kernel(const float* G, const int* rank, const floa
 // One time step, backward.  dh_next: compact [B x Hp] fp32 (NULL at the last step);
 // dc_next: [B x H] fp32, read unless `first`, then overwritten.  Writes the compact gate
 // gradient dG [B x 4Hp] in the storage dtype (zeros at the padding).
+// dh_next may come as `splits` partial sums `pstride` floats apart (summed here).
 template <typename T>
 __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const float* c_prev, const T* dh_ext,
-                                     const float* dh_next, float* dc_next, const int* rank, int B, int H, int Hk, int Hp,
-                                     int first, T* dG) {
+                                     const float* dh_next, int splits, long pstride, float* dc_next, const int* rank, int B,
+                                     int H, int Hk, int Hp, int first, T* dG) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
   T* d = dG + (long)b * 4 * Hp;
@@ -111,7 +120,8 @@ __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const f
   const float tc = tanhf(c[(long)b * H + u]);
   const float cp = c_prev ? c_prev[(long)b * H + u] : 0.0f;
   float dh = ElemTraits<T>::to_f32(dh_ext[(long)b * H + u]);
-  if (dh_next) dh += dh_next[(long)b * Hp + j];
+  if (dh_next)
+    for (int s = 0; s < splits; ++s) dh += dh_next[s * pstride + (long)b * Hp + j];
   float dc = dh * go * (1.0f - tc * tc);
   if (!first) dc += dc_next[(long)b * H + u];
   d[j] = ElemTraits<T>::from_f32(dc * gg * gi * (1.0f - gi));
@@ -263,14 +273,22 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
   for (int t = 0; t < T_; ++t) {
     float* Gt = Gx + (long)t * B * 4 * Hp;
     T* hc_t = (T*)w.hc + (long)t * B * Hp;
+    int splits = 0;
     if (t > 0 && Hk > 0) {
-      // recurrent part: G_t += h_{t-1}[kept] . Wh'^T
+      // recurrent part: G_t += h_{t-1}[kept] . Wh'^T, left as partial sums for the cell kernel when
+      // the product runs on the LDS-direct kernels
       const T* hc_prev = (const T*)w.hc + (long)(t - 1) * B * Hp;
       GemmParams P = plain_gemm(hc_prev, Hp, w.whc, Hp, Gt, 4 * Hp, B, 4 * Hp, Hp, true, true, ce, true, 1.0f);
-      st = run_gemm(a.dtype, true, true, P, 0, 0, stream, w.part, w.part_bytes);
-      if (st) return st;
+      if (run_gemm_partials(a.dtype, true, true, P, stream, w.part, w.part_bytes, &splits, &st)) {
+        if (st) return st;
+      } else {
+        splits = 0;
+        st = run_gemm(a.dtype, true, true, P, 0, 0, stream, w.part, w.part_bytes);
+        if (st) return st;
+      }
     }
-    hipLaunchKernelGGL(lstm_cell_fwd_kernel<T>, cgrid, dim3(256), 0, stream, (const float*)Gt, (const int*)w.rank,
+    hipLaunchKernelGGL(lstm_cell_fwd_kernel<T>, cgrid, dim3(256), 0, stream, (const float*)Gt, (const float*)w.part, splits,
+                       (long)B * 4 * Hp, (const int*)w.rank,
                        t > 0 ? (const float*)(c + (long)(t - 1) * B * H) : (const float*)nullptr, B, H, Hk, Hp,
                        gates + (long)t * B * 4 * H, c + (long)t * B * H, (T*)h + (long)t * B * H, hc_t);
     ARD_LAUNCH_CHECK("lstm_cell_fwd_kernel");
@@ -299,18 +317,27 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
   }
   T* dG = (T*)w.big;
   dim3 cgrid(ceil_div(H + (Hp - Hk), 256), B);
+  const float* dh_src = nullptr;  // dh_t[kept] from the product of step t+1: partial sums or w.dh_next
+  int dh_splits = 0;
   for (int t = T_ - 1; t >= 0; --t) {
     T* dGt = dG + (long)t * B * 4 * Hp;
     hipLaunchKernelGGL(lstm_cell_bwd_kernel<T>, cgrid, dim3(256), 0, stream, gates + (long)t * B * 4 * H,
                        c + (long)t * B * H, t > 0 ? c + (long)(t - 1) * B * H : (const float*)nullptr,
-                       (const T*)dh + (long)t * B * H, t < T_ - 1 ? (const float*)w.dh_next : (const float*)nullptr,
-                       w.dc_next, (const int*)w.rank, B, H, Hk, Hp, t == T_ - 1 ? 1 : 0, dGt);
+                       (const T*)dh + (long)t * B * H, dh_src, dh_splits, (long)B * Hp, w.dc_next, (const int*)w.rank, B, H,
+                       Hk, Hp, t == T_ - 1 ? 1 : 0, dGt);
     ARD_LAUNCH_CHECK("lstm_cell_bwd_kernel");
     if (t > 0) {
       // dh_{t-1}[kept] = dG_t . Wh'
       GemmParams P = plain_gemm(dGt, 4 * Hp, w.whc, Hp, w.dh_next, Hp, B, Hp, 4 * Hp, true, false, ce, true, 0.0f);
-      st = run_gemm(a.dtype, true, false, P, 0, 0, stream, w.part, w.part_bytes);
-      if (st) return st;
+      if (run_gemm_partials(a.dtype, true, false, P, stream, w.part, w.part_bytes, &dh_splits, &st)) {
+        if (st) return st;
+        dh_src = (const float*)w.part;
+      } else {
+        st = run_gemm(a.dtype, true, false, P, 0, 0, stream, w.part, w.part_bytes);
+        if (st) return st;
+        dh_src = w.dh_next;
+        dh_splits = 1;
+      }
     }
   }
   {
