@@ -103,49 +103,55 @@ __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
 
 template <bool KC, int ROWS, int NW> struct DirectLoader;
 
+// Both loaders keep, per lane and instruction, a loop-invariant 32-bit BYTE offset from a base that
+// is uniform over the workgroup; a contraction step only moves the uniform base, so a load costs
+// no vector ALU work.  A lane whose tile row lies beyond the operand reads some valid row instead
+// (clamped at set-up): such rows only feed outputs that are never stored, or that the epilogue
+// overwrites with zeros.  Only the last, partial step of a contraction redirects lanes to a zero chunk.
 template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
   static constexpr int NI = ROWS / 8 / NW;  // instructions per wavefront and stage (8 rows each)
   static_assert(NI >= 1, "tile too small for the workgroup");
-  const uint16_t* base;
-  int goff[NI];  // element offset of this lane's chunk for instruction j, without the slab start
+  const char* base;
+  uint32_t voff[NI];
   __device__ static __forceinline__ int chunk_k(int lane, int wave, int j) {
     const int row = (wave * NI + j) * 8 + (lane >> 3);
     return ((lane & 7) ^ (row & 7) ^ ((row >> 3) & 7)) * 8;
   }
   __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave) {
-    base = p;
+    base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int row = (wave * NI + j) * 8 + (lane >> 3);
-      const int ph = row0 + row < r.n ? ax_phys(r, row0 + row) : r.nphys;
-      // rows beyond the axis contribute zeros (their outputs, if stored at all, are padding)
-      goff[j] = ph < r.nphys ? ph * ld + chunk_k(lane, wave, j) : -1;
+      const int row = min(row0 + (wave * NI + j) * 8 + (lane >> 3), r.n - 1);
+      voff[j] = (uint32_t)(ax_phys(r, row) * ld + chunk_k(lane, wave, j)) * 2u;
     }
   }
   // rows = output pixels of a convolution: base pixel of the patch in the bordered grid
   __device__ __forceinline__ void init_pixels(const uint16_t* p, const ConvMap& cv, int row0, int lane, int wave) {
-    base = p;
+    base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int row = row0 + (wave * NI + j) * 8 + (lane >> 3);
-      goff[j] = -1;
-      if (row < cv.npix) {
-        const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
-        const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
-        goff[j] = (n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j);
-      }
+      const int row = min(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
+      const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
+      const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
+      voff[j] = (uint32_t)((n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j)) * 2u;
     }
   }
-  __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
-                                        int wave) const {
+  // full step: nothing but the loads
+  __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int wave) const {
+    const char* sb = base + (long)kslab * 2;  // uniform
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
+  }
+  // last, partial step of a contraction: chunks beyond its end come from the zero chunk
+  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
+    asm volatile("; partial contraction step" ::: "memory");  // keeps this path out of the full step's code
+    const char* sb = base + (long)kslab * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const uint16_t* src = base + (long)goff[j] + kslab;
-      if (goff[j] < 0) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
-      if (tail) {
-        const int k = chunk_k(lane, wave, j);
-        if (!(k < krem && kslab + k + 8 <= kphys_end)) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
-      }
+      const char* src = sb + voff[j];
+      const int k = chunk_k(lane, wave, j);
+      if (!(k < krem && kslab + k + 8 <= kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -163,48 +169,51 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
   static constexpr int CPR = ROWS / 8;         // 16-byte chunks per contraction row
   static constexpr int KPI = 64 / CPR;         // contraction rows per instruction
   static constexpr int NI = 64 / KPI / NW;     // instructions per wavefront and stage
-  static constexpr int NCO = KPI == 2 ? 2 : 1;
   static_assert(NI >= 1, "tile too small for the workgroup");
-  const uint16_t* base;
+  const char* base;
   int ld;
-  int coff[NCO];  // physical column of this lane's chunk (per instruction parity when KPI == 2)
+  uint32_t voff[NI];  // (contraction row within the step) * ld + column of this lane's chunk, in bytes
+  __device__ __forceinline__ int lane_chunk(int lane, int wave, int j) const {
+    const int kloc = KPI * (wave * NI + j) + lane / CPR;
+    return (lane % CPR) ^ mc_swz<ROWS>(kloc);
+  }
   __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave) {
-    base = p;
+    base = reinterpret_cast<const char*>(p);
     ld = ld_;
 #pragma unroll
-    for (int par = 0; par < NCO; ++par) {
-      const int kl = KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR;  // low bits of the row this lane fills
-      const int c = (lane % CPR) ^ mc_swz<ROWS>(kl);
-      const int j = row0 + c * 8;
-      const int ph = j + 8 <= r.n ? ax_phys(r, j) : r.nphys;
-      coff[par] = ph + 8 <= r.nphys ? ph : -1;  // runs beyond the axis contribute zeros
+    for (int j = 0; j < NI; ++j) {
+      const int kloc = KPI * (wave * NI + j) + lane / CPR;
+      const int col = min(row0 + lane_chunk(lane, wave, j) * 8, r.n - 8);  // runs beyond the axis: clamped
+      voff[j] = (uint32_t)(kloc * ld + ax_phys(r, col)) * 2u;
     }
   }
   // columns = (tap, channel) of the weight gradient: pixel offset of the tap plus the channel
   __device__ __forceinline__ void init_tap_columns(const uint16_t* p, const ConvMap& cv, int ncols, int row0, int lane,
                                                    int wave) {
-    base = p;
+    base = reinterpret_cast<const char*>(p);
     ld = cv.Cp;
-#pragma unroll
-    for (int par = 0; par < NCO; ++par) {
-      const int kl = KPI == 2 ? 2 * par + (lane >> 5) : lane / CPR;
-      const int c = (lane % CPR) ^ mc_swz<ROWS>(kl);
-      const int j = row0 + c * 8;
-      coff[par] = -1;
-      if (j + 8 <= ncols) {
-        const int t = j / cv.Cp;
-        coff[par] = ((t / cv.kw) * cv.Wg + t % cv.kw) * cv.Cp + (j - t * cv.Cp);
-      }
-    }
-  }
-  __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int krem, int kphys_end, bool tail, int lane,
-                                        int wave) const {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int kloc = KPI * (wave * NI + j) + lane / CPR;
-      const int co = coff[NCO == 2 ? (j & 1) : 0];
-      const uint16_t* src = base + (long)(kslab + kloc) * ld + co;
-      if (co < 0 || (tail && !(kloc < krem && kslab + kloc < kphys_end))) src = reinterpret_cast<const uint16_t*>(g_zero_chunk);
+      const int col = min(row0 + lane_chunk(lane, wave, j) * 8, ncols - 8);
+      const int t = col / cv.Cp;
+      voff[j] = (uint32_t)(kloc * ld + ((t / cv.kw) * cv.Wg + t % cv.kw) * cv.Cp + (col - t * cv.Cp)) * 2u;
+    }
+  }
+  __device__ __forceinline__ void issue(uint4* op_tile, int kslab, int wave) const {
+    const char* sb = base + (long)kslab * ld * 2;  // uniform
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
+  }
+  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
+    asm volatile("; partial contraction step" ::: "memory");
+    const char* sb = base + (long)kslab * ld * 2;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const char* src = sb + voff[j];
+      const int kloc = KPI * (wave * NI + j) + lane / CPR;
+      if (!(kloc < krem && kslab + kloc < kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -457,14 +466,19 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       const int krem = Kn - (s_lo + it) * 64;
       const int ks = fast_kslab(kax, (s_lo + it) * 64);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
-      la.issue(lds + buf * OPA, ks, krem, kax.nphys, tail, lane, wave);
       int ksb = ks;
       if constexpr (MODE == 1) {
         // slab (tap, c0) of the im2col row: offset of the tap's pixel plus the channel
         const int t = ks / P.cv.Cp;
         ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
       }
-      lb.issue(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, tail, lane, wave);
+      if (__builtin_expect(tail, 0)) {
+        la.issue_tail(lds + buf * OPA, ks, krem, kax.nphys, lane, wave);
+        lb.issue_tail(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, lane, wave);
+      } else {
+        la.issue(lds + buf * OPA, ks, wave);
+        lb.issue(lds + NST * OPA + buf * OPB, ksb, wave);
+      }
     };
     constexpr int QA = 16 * F_BM * 2, QB = 16 * BN * 2;  // bytes per 16-wide slice of an MC tile
     Frag fa[2][TM], fb[2][TN];
@@ -563,6 +577,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
   // 32x32 tile places all of its rows (columns).
   const int nlim = P.c_cols_mapped ? bn.n : P.N, mlim = P.c_rows_mapped ? am.n : P.M;
   const int nphys = P.c_cols_mapped ? bn.nphys : P.N, mphys = P.c_rows_mapped ? am.nphys : P.M;
+  // Columns at or beyond the B operand's extent (padding of a compact output) are stored as zeros:
+  // the loaders fed them clamped, i.e. arbitrary, rows.
+  const int n_valid = (MODE == 0 && P.tab.ncls == 0) ? bn.n : 0x7fffffff;
   // (the 256 x 256 tile has no registers to spare: it only stores plain bf16 results)
   constexpr bool GENERAL_OUT = !(F_BM == 256 && BN == 256);
   if (GENERAL_OUT && P.part) {
@@ -578,7 +595,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int i = i0 + 8 * (v >> 2) + (v & 3);
-          if (i < P.M) part[(long)i * P.N + j] = acc[im][in][v];
+          if (i < P.M) part[(long)i * P.N + j] = j < n_valid ? acc[im][in][v] : 0.0f;
         }
       }
     }
@@ -641,7 +658,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
         const int li0 = wm * WTM + im * 32 + 4 * (lane >> 5);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float x = P.alpha * acc[im][in][v];
+          float x = n0 + lj < n_valid ? P.alpha * acc[im][in][v] : 0.0f;
           if (P.relu) x = fmaxf(x, 0.0f);
           tile[(li0 + 8 * (v >> 2) + (v & 3)) * LDT + lj] = f32_to_bf16_bits(x);
         }
@@ -674,7 +691,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
           const int r = rbase + 8 * (v >> 2) + (v & 3);
           if (r >= mphys) continue;
           const long idx = (long)r * P.ldc + pc;
-          float x = P.alpha * acc[im][in][v];
+          float x = (j0 + (lane & 31)) < n_valid ? P.alpha * acc[im][in][v] : 0.0f;
           if (P.beta != 0.0f) x += P.beta * (P.out_f32 ? reinterpret_cast<const float*>(P.C)[idx] : bf16_bits_to_f32(P.C[idx]));
           if (P.relu) x = fmaxf(x, 0.0f);
           if (P.relu_src) x = bf16_bits_to_f32(P.relu_src[idx]) > 0.0f ? x : 0.0f;
@@ -697,6 +714,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
           x0 = fmaxf(x0, 0.0f);
           x1 = fmaxf(x1, 0.0f);
         }
+        if ((j0 + (lane & 31)) >= n_valid) x0 = x1 = 0.0f;
         const uint32_t b0 = f32_to_bf16_bits(x0), b1 = f32_to_bf16_bits(x1);
         const int dr0 = 8 * (v >> 2) + (v & 3);  // row of v; v+1 is the next row
         if (pair_ok) {

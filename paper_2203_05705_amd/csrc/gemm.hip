@@ -138,7 +138,7 @@ static int32_t launch_direct(bool a_kc, bool b_kc, FastParams& F, int bm, int bn
   return fail(ARD_EUNSUPPORTED, "tile configuration not built");
 }
 
-static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0 && ld < (1L << 30); }
+static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0 && ld < (1L << 24); }
 
 // bf16 products whose operands can be fetched with 16-byte loads go through the LDS-direct
 // kernels; results that the kernel cannot store itself (split contraction, element-level
@@ -171,6 +171,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   if (!fast_ptr_ok(P.A.p, P.A.ld) || !fast_ptr_ok(P.B.p, P.B.ld)) return false;
   if ((long)P.A.r.nphys * P.A.ld >= (1L << 31) || (long)P.B.r.nphys * P.B.ld >= (1L << 31)) return false;
   if ((long)P.M * P.N >= (1L << 31)) return false;
+  // rows of A beyond its extent would be stored (only columns beyond B's are zeroed by the kernel)
+  if (ax_m.n < P.M || ax_m.n < 1 || ax_n.n < 1 || (!b_kc && ax_n.n < P.N)) return false;
   const bool direct_out = ident(C.rm) && ident(C.cn);
   if (!direct_out) {
     auto inv_ok = [](const Axis& a) { return a.kind == AX_AFFINE || a.kind == AX_LIST; };
