@@ -549,10 +549,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
         if (it + NST - 1 < S) wait_vmcnt<(NST - 2) * LPS>();
         else wait_vmcnt<0>();
         wg_barrier();  // stage it+1 is complete and visible; nobody reads stage it any more
-        if (it + NST < S) load_stage(it + NST, BUF);
         issue(NB{}, I0{}, 0);
       }
       mma(1);
+      // the loads of stage it+NST go into the buffer just released; issued behind the MFMAs so
+      // that nothing but the barrier and one fragment read sits between two slices' MFMAs
+      if (it + NST < S) load_stage(it + NST, BUF);
     };
     if (S > 0) {
 #pragma unroll
