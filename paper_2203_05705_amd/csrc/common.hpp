@@ -92,6 +92,15 @@ template <> struct ElemTraits<uint16_t> {
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // column count of a compact matrix: kept count rounded up to a whole 16-byte chunk of bf16
+// Development switches, read once from the environment: ARD_NO_FAST=1 sends every product
+// through the general engine, ARD_NO_SCATTER=1 disables the scattering epilogue (partial sums +
+// finishing pass instead), ARD_FORCE_TILE=64|128 pins the general engine's workgroup tile.
+struct DevKnobs {
+  bool no_fast, no_scatter;
+  int force_tile;
+};
+const DevKnobs& dev_knobs();
+
 __host__ __device__ static inline int pad8(int n) { return (n + 7) & ~7; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

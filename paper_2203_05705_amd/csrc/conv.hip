@@ -796,7 +796,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
   if (a.n_keep > 0 && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
   if (!out) return fail(ARD_EINVAL, "null output pointer");
   const int Ck = a.n_keep;
-  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !getenv("ARD_NO_FAST")) {
+  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast) {
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
     if (a.mode == ARD_CONV_BWD_WEIGHT && (!dYin || !A)) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");

@@ -47,8 +47,7 @@ static int32_t launch_cfg(bool a_kc, bool b_kc, GemmParams& P, hipStream_t strea
 
 template <typename T>
 static int32_t run_gemm_t(bool a_kc, bool b_kc, GemmParams& P, int max_bn, hipStream_t stream) {
-  if (const char* f = getenv("ARD_FORCE_TILE")) {  // development knob: force a workgroup tile
-    int v = atoi(f);
+  if (const int v = dev_knobs().force_tile) {
     if (v == 256) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
     if (v == 128) return launch_cfg<T, 128, 128, 2, 2>(a_kc, b_kc, P, stream);
     if (v == 64) return launch_cfg<T, 64, 64, 2, 2>(a_kc, b_kc, P, stream);
@@ -145,7 +144,7 @@ static bool fast_ptr_ok(const void* p, long ld) { return ((uintptr_t)p & 15) == 
 // scatter with zero fill) pass through fp32 partials in the workspace and a finishing kernel.
 static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P, void* ws, size_t ws_bytes,
                        hipStream_t stream, int32_t& st, int* raw_splits) {
-  if (dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
+  if (dtype != ARD_BF16 || dev_knobs().no_fast) return false;
   if (!P.A.vec || !P.B.vec || P.kb_ptr || P.tmask) return false;
   Axis k = P.k;
   auto ident = [](const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; };
@@ -196,7 +195,7 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   // be split to occupy the chip at all.
   auto owns_groups = [](const Axis& a) { return a.kind == AX_AFFINE && a.step >= 1 && a.off < a.step; };
   bool scatter = !raw_splits && !direct_out && C.fill && !C.out_f32 && C.beta == 0.0f && owns_groups(C.rm) && owns_groups(C.cn) &&
-                 (long)C.rm.nphys * C.ld < (1L << 31) && !getenv("ARD_NO_SCATTER");
+                 (long)C.rm.nphys * C.ld < (1L << 31) && !dev_knobs().no_scatter;
   if (scatter) {
     // tile: as large as still gives every CU a workgroup; at least 64 workgroups or no scatter
     bm = bn = 64;
@@ -374,7 +373,7 @@ static int32_t tile_lists(const LayerArgs& a, void* ws, size_t ws_bytes, hipStre
 // op 0: Y = X . W^T   1: dX = dY . W   2: dW = dY^T . X
 static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void* Bp, void* Cp, float alpha, int relu,
                           hipStream_t stream, int32_t& st) {
-  if (a.dtype != ARD_BF16 || getenv("ARD_NO_FAST")) return false;
+  if (a.dtype != ARD_BF16 || dev_knobs().no_fast) return false;
   const int x = a.po->tile_r, y = a.po->tile_c, dp = a.po->dp, o = a.po->b - 1, TR = a.TR, TC = a.TC;
   const int B = a.B, I = a.I, O = a.O;
   if ((I % 8) || (O % 8) || (long)B * O >= (1L << 31) || (long)B * I >= (1L << 31) || (long)O * I >= (1L << 31)) return false;

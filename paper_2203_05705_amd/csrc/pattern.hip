@@ -1,6 +1,7 @@
 // Dropout patterns: host-side distribution search and sampling (Sections 3.3, 3.4)
 // and device-side mask + kept-list generation (Sections 3.1, 3.2, 6).
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -8,6 +9,13 @@
 #include "pattern.hpp"
 
 namespace ard {
+
+const DevKnobs& dev_knobs() {
+  static const DevKnobs k = {getenv("ARD_NO_FAST") != nullptr, getenv("ARD_NO_SCATTER") != nullptr,
+                             getenv("ARD_FORCE_TILE") ? atoi(getenv("ARD_FORCE_TILE")) : 0};
+  return k;
+}
+
 
 static thread_local char g_err[512] = "";
 
