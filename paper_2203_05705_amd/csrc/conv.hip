@@ -20,22 +20,39 @@ namespace ard {
 // score[c] += sum over this block's share of (n, h, w) of floor(min(|a|, 2^15) * 2^24):
 // exact integers, so the result does not depend on the order of summation.
 template <typename T>
-__global__ __launch_bounds__(256) void channel_score_kernel(const T* A, int N, int C, int HW, int n_per_block,
+__global__ __launch_bounds__(256) void channel_score_kernel(const T* A, int N, int C, int HW, int n_per_block, int vec,
                                                            unsigned long long* score) {
+  constexpr int CE = ElemTraits<T>::CE;
   const int c = blockIdx.x;
   const int n_begin = blockIdx.y * n_per_block;
   const int n_end = min(N, n_begin + n_per_block);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   unsigned long long acc = 0;
-  for (int n = n_begin; n < n_end; ++n) {
-    const T* p = A + ((long)n * C + c) * HW;
-    for (int i = threadIdx.x; i < HW; i += 256) {
-      float a = fminf(fabsf(ElemTraits<T>::to_f32(p[i])), 32768.0f);
-      acc += (unsigned long long)(a * 16777216.0f);
+  auto add = [&](T v) {
+    const float a = fminf(fabsf(ElemTraits<T>::to_f32(v)), 32768.0f);
+    acc += (unsigned long long)(a * 16777216.0f);
+  };
+  if (vec) {
+    // planes are whole numbers of 16-byte pieces: a wavefront walks one plane at a time
+    const int chunks = HW / CE;
+    for (int n = n_begin + wave; n < n_end; n += 4) {
+      const uint4* p = reinterpret_cast<const uint4*>(A + ((long)n * C + c) * HW);
+      for (int i = lane; i < chunks; i += 64) {
+        const uint4 q = p[i];
+        const T* e = reinterpret_cast<const T*>(&q);
+#pragma unroll
+        for (int t = 0; t < CE; ++t) add(e[t]);
+      }
+    }
+  } else {
+    for (int n = n_begin; n < n_end; ++n) {
+      const T* p = A + ((long)n * C + c) * HW;
+      for (int i = threadIdx.x; i < HW; i += 256) add(p[i]);
     }
   }
   // wavefront reduction, then one integer atomic per wavefront
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-  if ((threadIdx.x & 63) == 0 && acc) atomicAdd(score + c, acc);
+  if (lane == 0 && acc) atomicAdd(score + c, acc);
 }
 
 __global__ void zero_u64_kernel(unsigned long long* p, int n) {
@@ -45,12 +62,18 @@ __global__ void zero_u64_kernel(unsigned long long* p, int n) {
 
 // Drop the n_drop channels that come first in ascending (score, index) order; write the
 // mask (1 = kept) and the ascending kept list (ballot + mbcnt compaction, one workgroup).
-__global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned long long* score, int C, int n_drop,
+__global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned long long* score_g, int C, int n_drop,
                                                              uint8_t* mask, int* keep, int* count) {
+  constexpr int STAGED = 4096;  // scores kept in LDS for the rank loop (larger C reads them from memory)
+  __shared__ unsigned long long staged[STAGED];
   __shared__ int wave_tot[16];
   __shared__ int running_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) running_s = 0;
+  const bool in_lds = C <= STAGED;
+  if (in_lds)
+    for (int i = tid; i < C; i += 1024) staged[i] = score_g[i];
+  const unsigned long long* score = in_lds ? staged : score_g;
   __syncthreads();
   for (int base = 0; base < C; base += 1024) {
     const int c = base + tid;
@@ -58,6 +81,7 @@ __global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned lon
     if (c < C) {
       const unsigned long long s = score[c];
       int rank = 0;
+#pragma unroll 8
       for (int o = 0; o < C; ++o) {
         const unsigned long long so = score[o];
         rank += (so < s || (so == s && o < c)) ? 1 : 0;
@@ -783,8 +807,9 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (ysplit > a.N) ysplit = a.N;
     if (ysplit < 1) ysplit = 1;
     const int n_per_block = ceil_div(a.N, ysplit);
+    const int vec = ((a.H * a.W) % ce) == 0 && al16c(A);
     hipLaunchKernelGGL(channel_score_kernel<T>, dim3(a.C, ceil_div(a.N, n_per_block)), dim3(256), 0, stream,
-                       (const T*)A, a.N, a.C, a.H * a.W, n_per_block, score);
+                       (const T*)A, a.N, a.C, a.H * a.W, n_per_block, vec, score);
     ARD_LAUNCH_CHECK("channel_score_kernel");
     const int n_drop = (int)floor(rate * (double)a.C);
     hipLaunchKernelGGL(channel_select_kernel, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)score, a.C,
