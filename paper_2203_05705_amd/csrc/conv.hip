@@ -509,6 +509,57 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
   }
 }
 
+// The same copy driven from the source side, for planes that are whole numbers of 16-byte pieces:
+// a workgroup reads 64 channels x 64 source pixels with 16-byte loads (8 pixels of one channel
+// each), transposes through LDS and writes each pixel's 64 channels as 128 contiguous bytes.
+// Border pixels, the margin behind the last image and nothing else are left to the zero pass
+// that every workgroup also runs over its share [zb, ze) of the grid's pixels.
+__global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
+                                                          int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
+                                                          long n_pix_total, uint16_t* dst) {
+  __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
+  const int HW = Hs * Ws;
+  const int px_tiles = (HW + 63) / 64;
+  const int n = blockIdx.x / px_tiles, p0 = (blockIdx.x - n * px_tiles) * 64;
+  const int c0 = blockIdx.y * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int u = t + 256 * i;             // 512 pieces: 64 channels x 8 pieces of 8 pixels
+    const int cl = u >> 3, q = u & 7;
+    const int c = c0 + cl, p = p0 + q * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (c < n_chan && p < HW) v = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
+    *reinterpret_cast<uint4*>(&tile[cl][q * 8]) = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int pl = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
+    const int p = p0 + pl;
+    if (p >= HW) continue;
+    const int h = p / Ws, w = p - h * Ws;
+    const long g = ((long)n * Hg + h + oh) * Wg + w + ow;
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (uint32_t)tile[c8 + 2 * e][pl] | ((uint32_t)tile[c8 + 2 * e + 1][pl] << 16);
+    *reinterpret_cast<uint4*>(dst + g * Cp + c0 + c8) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+  // zero pass: this workgroup's share of the grid pixels, for its 64 channels
+  const long nblk = (long)gridDim.x, per = (n_pix_total + nblk - 1) / nblk;
+  const long zb = blockIdx.x * per, ze = zb + per < n_pix_total ? zb + per : n_pix_total;
+  const long valid = (long)N * Hg * Wg;
+  for (long g = zb + (t >> 3); g < ze; g += 32) {
+    bool border = g >= valid;
+    if (!border) {
+      const int rem = (int)(g % ((long)Hg * Wg));
+      const int h = rem / Wg - oh, w = rem % Wg - ow;
+      border = h < 0 || h >= Hs || w < 0 || w >= Ws;
+    }
+    if (border) *reinterpret_cast<uint4*>(dst + g * Cp + c0 + (t & 7) * 8) = make_uint4(0, 0, 0, 0);
+  }
+}
+
 // Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
 // data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
 __global__ void pack_weights_grid_kernel(const uint16_t* Wt, const int* keep, int C, int taps, int rows, int inner, int Cp,
@@ -641,9 +692,18 @@ static int conv_grid_splits(const ConvArgs& a) {
   return (int)(s < 1 ? 1 : (s > 64 ? 64 : s));
 }
 
+static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
                        int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
+  if (((Hs * Ws) % 8) == 0 && al16c(src)) {
+    dim3 grid((unsigned)(N * ceil_div(Hs * Ws, 64)), (unsigned)(Cp / 64));
+    hipLaunchKernelGGL(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
+                       Wg, oh, ow, Cp, N, total, dst);
+    ARD_LAUNCH_CHECK("to_grid_src_kernel");
+    return ARD_OK;
+  }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   hipLaunchKernelGGL(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
                      ow, Cp, valid, total, dst);
@@ -789,7 +849,6 @@ static int32_t conv_check(ConvArgs& a) {
   return ARD_OK;
 }
 
-static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 template <typename T>
 static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const void* Wt, const void* dYin, void* out,
