@@ -87,6 +87,15 @@ struct FastParams {
   Axis srm, scn;
 };
 
+// Two fp32 values to packed bf16 (low half = first) with the conversion instruction of gfx950
+// (round to nearest even, the same rounding as f32_to_bf16_bits for finite values).
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_hw_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
+}
+
 #define ARD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 #define ARD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 
@@ -628,7 +637,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
             x0 = fmaxf(x0, 0.0f);
             x1 = fmaxf(x1, 0.0f);
           }
-          const uint32_t b0 = f32_to_bf16_bits(x0), b1 = f32_to_bf16_bits(x1);
+          const uint32_t b01 = pack_bf16x2(x0, x1);
+          const uint32_t b0 = b01 & 0xffffu, b1 = b01 >> 16;
           if (pair_ok) {
             const uint32_t send = odd ? b0 : b1;
             const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, true);
@@ -717,7 +727,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
           x1 = fmaxf(x1, 0.0f);
         }
         if ((j0 + (lane & 31)) >= n_valid) x0 = x1 = 0.0f;
-        const uint32_t b0 = f32_to_bf16_bits(x0), b1 = f32_to_bf16_bits(x1);
+        const uint32_t b01 = pack_bf16x2(x0, x1);
+        const uint32_t b0 = b01 & 0xffffu, b1 = b01 >> 16;
         const int dr0 = 8 * (v >> 2) + (v & 3);  // row of v; v+1 is the next row
         if (pair_ok) {
           const uint32_t send = odd ? b0 : b1;
