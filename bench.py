@@ -305,8 +305,8 @@ def cpu_baseline(wl, cdf, budget_s):
 
 
 def extra_workloads(ard, torch):
-    """Configs 3 (tile pattern, 4096^3 bf16), 5 (convolution) and 4 (LSTM): per-call times and speedups.
-    Short by design."""
+    """Configs 3 (tile pattern, 4096^3 bf16, dp sweep and rate mixtures), 5 (convolution), 4 (LSTM), 1 and the
+    HBM-bound passes: per-call times and speedups.  Short by design."""
     out = {}
     n = 4096
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -330,7 +330,8 @@ def extra_workloads(ard, torch):
     vendor = dict(fwd=t_us(lambda: torch.matmul(X, W.t(), out=outb)), bwd_data=t_us(lambda: torch.matmul(dY, W, out=outb)),
                   bwd_weight=t_us(lambda: torch.matmul(dY.t(), X, out=outb)))
     res = {"vendor_dense_us": vendor}
-    for dp in (1, 2, 3, 4):
+    ops = ("fwd", "bwd_data", "bwd_weight")
+    for dp in range(1, N_PATTERNS + 1):
         pat = ard.Pattern.tile(dp, 1, 64, 64)
         pat = ard.Pattern.tile(dp, 1, 64, 64, lists=ard.pattern_gen(pat, n, n))
         kept = int(pat.lists["count"].item())
@@ -343,13 +344,48 @@ def extra_workloads(ard, torch):
             row[name] = dict(us=round(us, 1), kept_tflops=round(flops / us / 1e6, 1),
                              frac_mfma_peak=round(flops / us / 1e6 / MFMA_PEAK_BF16, 4))
         res[f"dp{dp}"] = row
-    for name in ("fwd", "bwd_data", "bwd_weight"):
-        dense = min(vendor[name], res["dp1"][name]["us"])
-        res["dp2"][name]["speedup_vs_dense"] = round(dense / res["dp2"][name]["us"], 3)
+    dense = {name: min(vendor[name], res["dp1"][name]["us"]) for name in ops}
+    for name in ops:
+        res["dp2"][name]["speedup_vs_dense"] = round(dense[name] / res["dp2"][name]["us"], 3)
+    # target rates as mixtures over the searched distribution: expected time of the three products
+    # under dp ~ K (per-dp times from the sweep above; the bias b only moves which tiles are kept)
+    for p in (0.3, 0.5, 0.7):
+        k, _ = ard.search_k(p, N_PATTERNS)
+        t_mix = sum(float(k[dp - 1]) * sum(res[f"dp{dp}"][name]["us"] for name in ops) for dp in range(1, N_PATTERNS + 1))
+        kept_frac = sum(float(k[dp - 1]) / dp for dp in range(1, N_PATTERNS + 1))
+        res[f"rate{p}"] = dict(expected_us_fwd_bwd=round(t_mix, 1), speedup_vs_dense=round(sum(dense.values()) / t_mix, 3),
+                               ideal_speedup=round(1.0 / kept_frac, 3))
     out["tile_gemm_4096_bf16_tile64"] = res
     out["conv_fmap_drop_128x256x28x28_bf16"] = extra_conv(ard, torch, t_us)
     out["lstm_1024_1024_b128_t64_bf16"] = extra_lstm(ard, torch, t_us)
+    out["small_and_hbm_bound"] = extra_small(ard, torch, t_us)
     return out
+
+
+def extra_small(ard, torch, t_us):
+    """The latency- and HBM-bound pieces: config 1 (one fp32 layer, 64 x 784 -> 1024), pattern_gen, channel scoring."""
+    from paper_2203_05705_amd import workloads as WL
+    wl = WL.mlp_layer_f32()
+    X, W, dY = (ard.to_device(wl.arrays[k]) for k in ("X", "W", "dY"))
+    pat = ard.Pattern.row(2, 1)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    Y, dX, dW = torch.empty((64, 1024), device="cuda"), torch.empty_like(X), torch.empty_like(W)
+    res = {"config1_fp32_layer_us": dict(
+        fwd=round(t_us(lambda: ard.drop_gemm_fwd(X, W, pat, out=Y, ws=ws)), 2),
+        bwd_data=round(t_us(lambda: ard.drop_gemm_bwd_data(dY, W, pat, out=dX, ws=ws)), 2),
+        bwd_weight=round(t_us(lambda: ard.drop_gemm_bwd_weight(dY, X, pat, out=dW, ws=ws)), 2))}
+    tp = ard.Pattern.tile(3, 2, 64, 64)
+    res["pattern_gen_us"] = dict(rows_2048=round(t_us(lambda: ard.pattern_gen(ard.Pattern.row(3, 2), 2048)), 2),
+                                 tiles_64x64_grid=round(t_us(lambda: ard.pattern_gen(tp, 4096, 4096)), 2),
+                                 note="includes the binding's output allocations; one workgroup, latency-bound")
+    wlc = WL.conv_layer()
+    A = ard.to_device(wlc.arrays["A"])
+    N, C, H, Wd = A.shape
+    wsc = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, C, H, Wd, 256, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
+    us = t_us(lambda: ard.conv_select(A, 0.5, ws=wsc))
+    res["channel_score_select"] = dict(us=round(us, 1), bytes_read=A.numel() * 2,
+                                       gb_per_s=round(A.numel() * 2 / us / 1e3, 1), frac_hbm_peak=round(A.numel() * 2 / us / 1e3 / 8000.0, 4))
+    return res
 
 
 def extra_conv(ard, torch, t_us):
@@ -403,6 +439,8 @@ def extra_lstm(ard, torch, t_us):
     res["vendor_dense_us"] = dict(fwd=round(t_us(lambda: lstm(xx), reps=5, warm=2), 1),
                                   bwd=round(t_us(lambda: torch.autograd.grad(out_, [xx] + list(lstm.parameters()), dh,
                                                                               retain_graph=True), reps=5, warm=2), 1))
+    for dp in (1, 2, 3):
+        res[f"dp{dp}"]["fwd_us_per_step"] = round(res[f"dp{dp}"]["fwd_us"] / T, 2)
     d = min(res["dp1"]["fwd_us"] + res["dp1"]["bwd_us"], res["vendor_dense_us"]["fwd"] + res["vendor_dense_us"]["bwd"])
     res["speedup_vs_dense_dp2"] = round(d / (res["dp2"]["fwd_us"] + res["dp2"]["bwd_us"]), 3)
     return res

@@ -381,7 +381,6 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   const int g = gcd_int(TC, dp), Pp = dp / g;
   FastParams F{};
   ClassTab& t = F.tab;
-  const int tiles_b = ceil_div(B, 256);
   auto cnt = [](int total, int first, int step) { return first < total ? (total - first + step - 1) / step : 0; };
   if (op == 0) {
     if ((256 % x) || (y % 64) || Pp > F_MAXCLS) return false;
@@ -394,7 +393,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
       const int t0 = (int)((((long)o - (long)c * TC) % dp + dp) % dp);
       t.k_off[c] = t0;
       t.k_cnt[c] = cnt(TC, t0, dp);
-      t.mblk[c] = tiles_b;
+      t.mblk[c] = 1;
     }
     F.A = (const uint16_t*)Ap, F.lda = I, F.am = axis_identity(B);
     F.B = (const uint16_t*)Bp, F.ldb = I;
@@ -417,7 +416,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
         }
       t.k_off[c] = J0 < 0 ? 0 : J0;
       t.k_cnt[c] = J0 < 0 ? 0 : cnt(TR, J0, Pp);
-      t.mblk[c] = tiles_b;
+      t.mblk[c] = 1;
     }
     F.A = (const uint16_t*)Ap, F.lda = O, F.am = axis_identity(B);
     F.B = (const uint16_t*)Bp, F.ldb = I;
@@ -445,12 +444,12 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     F.c_rows_mapped = F.c_cols_mapped = 1;
     F.M = O, F.N = I;
   }
-  // workgroups per class for a column tile of BN; "heavy" ones have something to contract
-  auto count = [&](int bn, int& heavy) {
+  // workgroups per class for a BM x BN tile; "heavy" ones have something to contract
+  auto count = [&](int bm, int bn, int& heavy) {
     int total = 0;
     heavy = 0;
     for (int c = 0; c < t.ncls; ++c) {
-      const int mb = op == 2 ? ceil_div(t.m_cnt[c], 256 / x) : tiles_b;
+      const int mb = op == 2 ? ceil_div(t.m_cnt[c], bm / x) : ceil_div(B, bm);
       const int nb = ceil_div(t.n_cnt[c], bn / t.n_bs);
       t.mblk[c] = mb > 0 ? mb : 1;
       t.nblk[c] = (t.n_cnt[c] > 0 && mb > 0) ? mb * nb : 0;
@@ -459,12 +458,15 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
     return total;
   };
-  int heavy = 0, bn = 256;
-  int total = count(256, heavy);
-  if (heavy < 200 && (128 % t.n_bs) == 0) {  // not enough wide tiles to fill 256 CUs: halve the tile
-    bn = 128;
-    total = count(128, heavy);
+  // the largest tile that still gives (about) every CU a workgroup with work
+  int heavy = 0, bm = 256, bn = 256, total = 0;
+  for (const TileCfg& c : kTileCfgs) {
+    if ((c.bn % t.n_bs) || (op == 2 && (c.bm % x))) continue;
+    bm = c.bm, bn = c.bn;
+    total = count(bm, bn, heavy);
+    if (heavy >= 200) break;
   }
+  if (total == 0) return false;
   if (heavy < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
   F.alpha = alpha;
   F.relu = relu;
@@ -479,7 +481,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
   }
   F.splits = 1;
-  st = launch_direct(op != 2, op == 0, F, 256, bn, stream);
+  st = launch_direct(op != 2, op == 0, F, bm, bn, stream);
   return true;
 }
 
