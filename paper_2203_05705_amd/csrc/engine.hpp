@@ -60,6 +60,10 @@ struct GemmParams {
   OutMat C;
   int M, N;
   int tiles_m, tiles_n;
+  // contraction split over blockIdx.y: fp32 partial sums part[split][M][N] (compact, alpha not
+  // applied) that a finishing pass reduces; NULL: the kernel stores the result itself
+  float* part;
+  int splits;
 };
 
 // Host: may this operand be fetched with 16-byte loads?  KC operands need contiguous,
@@ -479,7 +483,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmParams P
     typename PickLoader<B_KC, T, BN, NT>::type lb;
     la.init(P.A, kax, m0, tid);
     lb.init(P.B, kax, n0, tid);
-    gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, 0, kax.n, lds, acc, act);
+    int k_begin = 0, k_end = kax.n;
+    if (P.part) {
+      // whole 128-byte steps per split
+      constexpr int BK = 8 * ElemTraits<T>::CE;
+      const int steps = (kax.n + BK - 1) / BK;
+      k_begin = (int)((long)blockIdx.y * steps / P.splits) * BK;
+      k_end = min(kax.n, (int)((long)(blockIdx.y + 1) * steps / P.splits) * BK);
+    }
+    if (k_begin < k_end) gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, k_begin, k_end, lds, acc, act);
+  }
+  if (P.part) {
+    float* part = P.part + (long)blockIdx.y * P.M * P.N;
+    const int lane = tid & 63;
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      const int j = n0 + wn * WTN + in * 32 + (lane & 31);
+      if (j >= P.N) continue;
+#pragma unroll
+      for (int im = 0; im < TM; ++im) {
+        const int i0 = m0 + wm * WTM + im * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = i0 + 8 * (v >> 2) + (v & 3);
+          if (i < P.M) part[(long)i * P.N + j] = acc[im][in][v];
+        }
+      }
+    }
+    return;
   }
   gemm_epilogue<T, BM, BN, WGM, WGN>(P.C, acc, m0, n0, P.M, P.N);
 }

@@ -34,7 +34,7 @@ static int32_t launch_cfg(bool a_kc, bool b_kc, GemmParams& P, hipStream_t strea
   long blocks = (long)P.tiles_m * P.tiles_n;
   if (blocks <= 0) return ARD_OK;
   if (blocks > 0x7fffffffL) return fail(ARD_ESHAPE, "too many workgroups");
-  dim3 grid((unsigned)blocks), block(64 * WGM * WGN);
+  dim3 grid((unsigned)blocks, (unsigned)(P.part ? P.splits : 1)), block(64 * WGM * WGN);
   constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   if (a_kc && b_kc)
     return launch_one(gemm_kernel<T, BM, BN, WGM, WGN, true, true>, grid, block, lds_bytes, stream, P);
@@ -75,9 +75,38 @@ int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, 
                  void* ws, size_t ws_bytes) {
   int32_t st_fast = ARD_OK;
   if (try_direct(dtype, a_kc, b_kc, P, ws, ws_bytes, stream, st_fast)) return st_fast;
-  if (dtype == ARD_BF16) return run_gemm_t<uint16_t>(a_kc, b_kc, P, max_bn, stream);
-  if (dtype == ARD_F32) return run_gemm_t<float>(a_kc, b_kc, P, max_bn, stream);
-  return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+  if (dtype != ARD_BF16 && dtype != ARD_F32) return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+  // A product with too few tiles for the chip splits its contraction over blockIdx.y into fp32
+  // partial sums (fixed split: deterministic) that the finishing pass reduces and stores.
+  auto inv_ok = [](const Axis& a) { return a.kind == AX_AFFINE || a.kind == AX_LIST; };
+  const long tiles = (long)ceil_div(P.M, 64) * ceil_div(P.N, 64);
+  const int steps = ceil_div(P.k.n, dtype == ARD_BF16 ? 64 : 32);
+  if (ws && !P.kb_ptr && !P.tmask && !P.C.plane && inv_ok(P.C.rm) && inv_ok(P.C.cn) && tiles > 0 && tiles < 128 &&
+      steps >= 4 && (long)P.M * P.N < (1L << 31)) {
+    int splits = (int)(256 / tiles);
+    if (splits > steps / 2) splits = steps / 2;
+    if (splits > 8) splits = 8;
+    if (splits > 1 && (size_t)splits * P.M * P.N * 4 <= ws_bytes) {
+      P.part = (float*)ws;
+      P.splits = splits;
+    }
+  }
+  int32_t st = dtype == ARD_BF16 ? run_gemm_t<uint16_t>(a_kc, b_kc, P, max_bn, stream)
+                                 : run_gemm_t<float>(a_kc, b_kc, P, max_bn, stream);
+  if (st || !P.part) return st;
+  const OutMat& C = P.C;
+  const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
+  long blocks = (total + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  if (dtype == ARD_BF16)
+    hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
+                       P.splits, P.M, P.N, C);
+  else
+    hipLaunchKernelGGL(gemm_finish_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws, P.splits,
+                       P.M, P.N, C);
+  ARD_LAUNCH_CHECK("gemm_finish_kernel");
+  return ARD_OK;
 }
 
 // ---- large-tile path -------------------------------------------------------------------
