@@ -2,11 +2,16 @@
 // one sensitivity score per input feature map, the lowest-scoring maps are dropped and
 // their activations, weights and gradients are never loaded.
 //
-// All three passes are implicit GEMMs on the MFMA engine (im2col is never materialised):
+// All three passes are implicit GEMMs on the matrix cores:
 //   FWD        Y[co, (n,oh,ow)]  = sum_{tap, c kept}  Wp[co, (tap,c)]  * A[n, c, oh*s+kh-p, ow*s+kw-p]
 //   BWD_DATA   dA[c kept, (n,y,x)] = sum_{tap, co}    Wq[c, (tap,co)]  * dY[n, co, y-kh+p, x-kw+p]
 //   BWD_WEIGHT dW[co, (c kept,tap)] = sum_{(n,oh,ow)} dY[n, co, oh, ow] * A[n, c, oh*s+kh-p, ow*s+kw-p]
 // Wp / Wq are compact repacked copies of the kept-channel weights (tiny, built per call).
+//
+// Two paths.  bf16 with stride 1: the kept maps are copied once into a zero-bordered
+// channels-last grid and the products run on the LDS-direct kernel of fast.hpp (second half of
+// this file).  Everything else (fp32, strides): the general engine with loaders that compute
+// the patch addresses on the fly, im2col never materialised (first half).
 #include <stdlib.h>
 
 #include "engine.hpp"

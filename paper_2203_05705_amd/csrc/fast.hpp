@@ -1,6 +1,6 @@
-// Large-tile bf16 path of the gathered GEMM for gfx950.
+// LDS-direct bf16 path of the gathered GEMM for gfx950.
 //
-// Workgroup tiles BM x BN x 64 of 32x32x16 bf16 MFMA tiles: 256x256 and 256x128 with 8
+// Workgroup tiles BM x BN x 64 of 32x32x16 bf16 MFMA tiles: 256x256, 256x128, 128x256 with 8
 // wavefronts (two per SIMD), 128x128, 128x64 and 64x64 with 4 wavefronts for products too small
 // to fill 256 CUs with large tiles; optional split of the contraction over blockIdx.y with
 // fp32 partial sums that a finishing kernel reduces (fixed split: deterministic).
@@ -16,8 +16,8 @@
 //   MC operand (contraction-strided in memory): LDS tile [64 k][rows] exactly as in memory; lane
 //     = (k, pos) fetches chunk pos ^ 4*(k & 3).  Fragments: two ds_read_b64_tr_b16 (the
 //     transposing LDS read of gfx950) per MFMA operand, no register transpose anywhere.
-// LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1]; the stage is an immediate offset of
-// the fragment reads, so every read address is a loop invariant.
+// LDS: [A stages | B stages] (2 stages, 3 for the 64x64 tile); the stage is an immediate offset
+// of the fragment reads, so every read address is a loop invariant.
 //
 // Tile patterns (Section 3.2) are period patterns over the linear tile index, so the tile
 // rows (or columns) fall into a few CLASSES that share one kept-column (kept-row) set:
@@ -26,10 +26,13 @@
 // class's kept set along the contraction, so dropped tiles cost nothing and the macro
 // tile stays wide.  ClassTab carries the progressions.
 //
+// The same kernel runs the convolutions on a channels-last grid of the kept feature maps
+// (MODE 1: rows of B are output pixels, contraction = (tap, channel); MODE 2: weight gradient,
+// contraction over the grid's pixels).
+//
 // Restrictions checked on the host (anything else goes through gemm_kernel): bf16, 16-byte
-// aligned operands, every extent along a 16-byte run a multiple of 8, contraction map =
-// identity or a block progression with block size a multiple of 64, outputs not scattered
-// below 32-wide blocks.
+// aligned operands, every extent along a 16-byte run a multiple of 8 (or zero-padded storage),
+// contraction map = identity or a block progression with block size a multiple of 64.
 #pragma once
 #include <type_traits>
 
