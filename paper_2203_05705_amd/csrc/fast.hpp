@@ -852,22 +852,16 @@ static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float
         else if (C.cn.kind == AX_AFFINE) jj[t] = (j < C.cn.n && C.cn.off + j * C.cn.step == c0 + t) ? j++ : -1;
         else jj[t] = ax_inverse(C.cn, c0 + t);
       }
-      // all loads of the (at most 8) splits are independent: issue them together
+      // the 8 loads of one split are independent; splits are summed in order
       float x[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
       const float* prow = part + (long)i * N;
-      float ldv[8][8];
+      for (int sp = 0; sp < splits; ++sp) {
+        float v[8];
 #pragma unroll
-      for (int sp = 0; sp < 8; ++sp)
+        for (int t = 0; t < 8; ++t) v[t] = jj[t] >= 0 ? prow[sp * MN + jj[t]] : 0.0f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) ldv[sp][t] = (sp < splits && jj[t] >= 0) ? prow[sp * MN + jj[t]] : 0.0f;
-#pragma unroll
-      for (int sp = 0; sp < 8; ++sp)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] += ldv[sp][t];
-      for (int sp = 8; sp < splits; ++sp)
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-          if (jj[t] >= 0) x[t] += prow[sp * MN + jj[t]];
+        for (int t = 0; t < 8; ++t) x[t] += v[t];
+      }
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         if (jj[t] < 0) continue;
