@@ -77,7 +77,8 @@ class MlpChain:
         B = BATCH
         self.Y = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2, 3)]
         self.dYh = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2)]   # gradient at hidden outputs
-        self.dW = [torch.empty_like(w) for w in self.W]
+        # room for the full [O x I] gradient and for the compact one, whose axes are padded to multiples of 8
+        self.dW = [torch.empty(((w.shape[0] + 7) & ~7, (w.shape[1] + 7) & ~7), dtype=dt, device="cuda") for w in self.W]
         self.Wc = [torch.empty(((w.shape[0] + 7) & ~7, (w.shape[1] + 7) & ~7), dtype=dt, device="cuda")
                    for w in self.W[1:]]   # kept blocks of W2, W3 (axes padded to multiples of 8)
         self.ws = [torch.empty(1 << 24, dtype=torch.uint8, device="cuda") for _ in range(2)]  # one per lane
@@ -90,7 +91,7 @@ class MlpChain:
         self._keep.append(p)
         return C.byref(p)
 
-    def plan(self, pats):
+    def plan(self, pats, compact_dw=False):
         """pats = ((dp1,b1),(dp2,b2)) -> list of steps.
 
         A step is ("call", lane, fn, args, name, kept_flops) or ("wait", lane, other_lane): `lane`
@@ -100,7 +101,8 @@ class MlpChain:
 
         Hidden activations and their gradients stay compact between the calls (only kept
         neurons are stored); W2's kept block is gathered once per iteration and shared by the
-        forward and the data-gradient product; weight gradients are written in full."""
+        forward and the data-gradient product; weight gradients are written in full, or, with
+        compact_dw, as the gradient of the kept synapses only (a reported variant, not the headline)."""
         lib, B = self.lib, BATCH
         p1, p2 = self._pat(*pats[0]), self._pat(*pats[1])
         k1 = -(-(SIZES[1] - (pats[0][1] - 1)) // pats[0][0])
@@ -110,6 +112,9 @@ class MlpChain:
         dYL = self.dYLc
         bf = self.ard.BF16
         IN, OUT, WC = self.ard.IN_COMPACT, self.ard.OUT_COMPACT, self.ard.W_COMPACT
+        DW1 = DW = 0
+        if compact_dw:   # the compact gradients fit in the full-size buffers
+            DW, DW1 = self.ard.DW_COMPACT, self.ard.DW_COMPACT | IN   # X0 has 784 = pad8(784) columns
         P = lambda t: t.data_ptr()
         f = 2.0 * B
         n = self.ws[0].numel()
@@ -128,14 +133,14 @@ class MlpChain:
             ("wait", 0, 1),
             call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2c), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC), "L2.fwd", f * k1 * k2),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT), "L3.bwd_weight", f * k2 * SIZES[3]),
+            call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT | DW), "L3.bwd_weight", f * k2 * SIZES[3]),
             call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3c), P(Y3), None, p2, 1.0, 0, IN | WC), "L3.fwd", f * k2 * SIZES[3]),
             call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3c), P(dY2), None, p2, 1.0, P(Y2), IN | OUT | WC), "L3.bwd_data", f * k2 * SIZES[3]),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT), "L2.bwd_weight", f * k1 * k2),
+            call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT | DW), "L2.bwd_weight", f * k1 * k2),
             call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2c), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC), "L2.bwd_data", f * k1 * k2),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT), "L1.bwd_weight", f * SIZES[0] * k1),
+            call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT | DW1), "L1.bwd_weight", f * SIZES[0] * k1),
             ("wait", 0, 1),
         ]
 
@@ -510,6 +515,9 @@ def main():
             other = "eager" if args.mode == "graph" else "graph"
             rates[str(p)][f"{other}_ms_per_step"] = time_steps(torch, chain, plans, args.steps, args.warmup,
                                                                other) / args.steps * 1e3
+            cplans = [chain.plan(pp, compact_dw=True) for pp in pats]
+            rates[str(p)]["compact_dw_ms_per_step"] = time_steps(torch, chain, cplans, args.steps, args.warmup,
+                                                                 args.mode) / args.steps * 1e3
             # roofline of the call that takes the largest share of the iteration, over the timed plans
             tot, cnt, fl = per_call_times(torch, chain, used)
             name = max(tot, key=tot.get)

@@ -130,17 +130,20 @@ int32_t ard_pattern_gen(const ard_pattern* pat, int32_t rows, int32_t cols,
  *                    the kept input neurons of pat_in, in ascending order;
  *   ARD_OUT_COMPACT  the output-side activation (Y, dY) is [B x pad8(O')] and holds only the kept
  *                    output neurons of pat_out (nothing is zero-filled then);
- *   ARD_W_COMPACT    W is the compact matrix written by ard_compact_weight().
+ *   ARD_W_COMPACT    W is the compact matrix written by ard_compact_weight();
+ *   ARD_DW_COMPACT   (weight gradient only, together with the two flags above) dW is the gradient
+ *                    of the kept synapses only, [pad8(O') x pad8(I')] in the layout of a compact
+ *                    weight; the gradient of every dropped synapse is zero and is not stored.
  * pad8(n) = n rounded up to a multiple of 8.  Every compact matrix stores its kept-unit axes
  * padded to pad8 with ZEROS (rows of 16-byte pieces whatever the kept count is): compact inputs
  * must carry zero padding, compact outputs are written with it.  With a NONE pattern a compact
  * activation is simply the dense one with its rows padded to pad8 columns (useful for narrow
  * matrices such as a 10-column loss gradient).
- * dW is always the full [O x I] matrix.  Without ARD_W_COMPACT, a forward or backward-data
+ * Without ARD_DW_COMPACT dW is the full [O x I] matrix.  Without ARD_W_COMPACT, a forward or backward-data
  * call whose pat_in is not NONE first gathers W[kept o, kept i] into its workspace.
  * Tile patterns take no flags.
  */
-enum { ARD_IN_COMPACT = 1, ARD_OUT_COMPACT = 2, ARD_W_COMPACT = 4 };
+enum { ARD_IN_COMPACT = 1, ARD_OUT_COMPACT = 2, ARD_W_COMPACT = 4, ARD_DW_COMPACT = 8 };
 
 /* Wc[pad8(O') x pad8(I')]: W[kept o, kept i] in the top-left corner, zeros in the padding
  * (ROW/LIST/NONE patterns). One gather kernel, no workspace. */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libard.so")
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
 CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT = 0, 1, 2, 3
-IN_COMPACT, OUT_COMPACT, W_COMPACT = 1, 2, 4
+IN_COMPACT, OUT_COMPACT, W_COMPACT, DW_COMPACT = 1, 2, 4, 8
 
 
 class ArdError(RuntimeError):
@@ -306,7 +306,8 @@ def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, 
         _check_compact(dY, kept_count(pat_out, O), "dY")
     if flags & IN_COMPACT:
         _check_compact(X, kept_count(pat_in, I), "X")
-    dW = torch.empty((O, I), dtype=dY.dtype, device=dY.device) if out is None else out
+    shape = (pad8(kept_count(pat_out, O)), pad8(kept_count(pat_in, I))) if flags & DW_COMPACT else (O, I)
+    dW = torch.empty(shape, dtype=dY.dtype, device=dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)

@@ -592,7 +592,8 @@ struct RowLayer {
 
 static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* W, bool need_w, void* ws, size_t ws_bytes,
                                  hipStream_t stream, RowLayer& L) {
-  if (flags & ~(ARD_IN_COMPACT | ARD_OUT_COMPACT | ARD_W_COMPACT)) return fail(ARD_EINVAL, "unknown flag bits 0x%x", flags);
+  if (flags & ~(ARD_IN_COMPACT | ARD_OUT_COMPACT | ARD_W_COMPACT | ARD_DW_COMPACT))
+    return fail(ARD_EINVAL, "unknown flag bits 0x%x", flags);
   L.ao = axis_of_pattern(a.po, a.O);
   L.ai = axis_of_pattern(a.pi, a.I);
   L.in_c = (flags & ARD_IN_COMPACT) != 0;
@@ -686,6 +687,7 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
     P.C.fill = 1;
     max_bn = pick_bn(pat_out->tile_r);
   } else {
+    if (flags & ARD_DW_COMPACT) return fail(ARD_EINVAL, "ARD_DW_COMPACT belongs to the weight gradient");
     RowLayer L;
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
@@ -751,6 +753,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
     P.C.fill = 1;
     max_bn = pick_bn(pat_out->tile_c);
   } else {
+    if (flags & ARD_DW_COMPACT) return fail(ARD_EINVAL, "ARD_DW_COMPACT belongs to the weight gradient");
     RowLayer L;
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
@@ -804,6 +807,7 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   GemmParams P{};
   P.k = axis_identity(B);
   size_t ws_used = 0;
+  bool dw_compact = false;
   if (a.tile) {
     if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
     if (beta == 0.0f && try_fast_tile(2, a, dY, X, dW, alpha, 0, stream, st)) return st;
@@ -841,17 +845,28 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
     }
     P.C.rm = L.ao;
     P.C.cn = L.ai;
+    if (flags & ARD_DW_COMPACT) {
+      // dW of the kept synapses only, [pad8(O') x pad8(I')] like a compact weight: both activations
+      // come compact, so the padding rows and columns are products of zeros
+      if (!L.out_c || !L.in_c) return fail(ARD_EINVAL, "ARD_DW_COMPACT needs ARD_IN_COMPACT and ARD_OUT_COMPACT");
+      const int Mp = pad8(L.ao.n), Np = pad8(L.ai.n);
+      P.A.r = axis_identity(Mp);
+      P.B.r = axis_identity(Np);
+      P.C.rm = axis_identity(Mp);
+      P.C.cn = axis_identity(Np);
+      dw_compact = true;
+    }
   }
   P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
   P.C.p = dW;
-  P.C.ld = I;
-  P.C.fill = 1;
+  P.C.ld = dw_compact ? P.C.cn.n : I;
+  P.C.fill = dw_compact ? 0 : 1;
   P.C.alpha = alpha;
   P.C.beta = beta;
   P.M = P.A.r.n;
   P.N = P.B.r.n;
-  if (P.M == 0 || P.N == 0) return fill_matrix(dtype, dW, (long)O * I, beta, stream);
+  if (P.M == 0 || P.N == 0) return dw_compact ? ARD_OK : fill_matrix(dtype, dW, (long)O * I, beta, stream);
   return run_gemm(dtype, false, false, P, 0, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
                   a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
 }

@@ -67,6 +67,36 @@ def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
     dW = torch.full((O, I), float("nan"), dtype=W.dtype, device="cuda")
     ard.drop_gemm_bwd_weight(dYc, Xc, pat_o, pat_i, flags=IN | OUT, out=dW, I=I, O=O)
     assert_parity(dW, refdW, dtype, zero_mask=(MW == 0), what="dW")
+    # weight gradient of the kept synapses only, in the layout of a compact weight
+    dWc = torch.full((ard.pad8(len(ko)), ard.pad8(len(ki))), float("nan"), dtype=W.dtype, device="cuda")
+    ard.drop_gemm_bwd_weight(dYc, Xc, pat_o, pat_i, flags=IN | OUT | ard.DW_COMPACT, out=dWc, I=I, O=O)
+    check_compact_dw(dWc, refdW, ko, ki, dtype)
+    with pytest.raises(ard.ArdError):
+        ard.drop_gemm_bwd_weight(from_vals(dYv, dtype), Xc, pat_o, pat_i, flags=IN | ard.DW_COMPACT, I=I, O=O)
+
+
+def check_compact_dw(dWc, refdW, ko, ki, dtype):
+    """Kept synapses against the oracle's full gradient; padding rows and columns exactly +0.0."""
+    no, ni = len(ko), len(ki)
+    assert dWc.shape == (ard.pad8(no), ard.pad8(ni))
+    assert_parity(dWc[:no, :ni].contiguous(), refdW[np.ix_(ko, ki)], dtype, what="dW compact")
+    bits = dWc.view(torch.int16 if dtype == "bf16" else torch.int32)
+    assert not bits[no:, :].any() and not bits[:, ni:].any(), "dW compact: padding not +0.0"
+
+
+@pytest.mark.parametrize("O,I,po,pi", [(2048, 2048, (2, 1), (2, 2)), (1000, 1500, (3, 2), (3, 1))])
+def test_compact_weight_gradient_large(O, I, po, pi):
+    """Compact weight gradient at sizes that run the split contraction over several macro tiles."""
+    B, dtype = 128, "bf16"
+    print(f"compact dW B={B} I={I} O={O} pat_out={po} pat_in={pi}", flush=True)
+    rng = np.random.default_rng(O + I)
+    Xv, dYv = (stored(rng.standard_normal(s), dtype) for s in ((B, I), (B, O)))
+    mo, mi = P.row_mask(O, *po), P.row_mask(I, *pi)
+    ko, ki = P.keep_list(mo), P.keep_list(mi)
+    refdW = G.drop_gemm_bwd_weight(dYv, Xv, G.weight_mask_rows(mo, mi), mo)
+    dWc = ard.drop_gemm_bwd_weight(compact_in(dYv[:, ko], dtype), compact_in(Xv[:, ki], dtype), ard.Pattern.row(*po),
+                                   ard.Pattern.row(*pi), flags=ard.IN_COMPACT | ard.OUT_COMPACT | ard.DW_COMPACT, I=I, O=O)
+    check_compact_dw(dWc, refdW, ko, ki, dtype)
 
 
 @pytest.mark.parametrize("I", [1024, 1030])
