@@ -568,6 +568,30 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       // that nothing but the barrier and one fragment read sits between two slices' MFMAs
       if (it + NST < S) load_stage(it + NST, BUF);
     };
+    // The same step where every question is settled: a successor stage exists, the stage to load
+    // exists and is a full one, the contraction axis is affine.  No scalar bookkeeping, no branches.
+    auto steady_step = [&](auto bufc, int it) {
+      constexpr int BUF = decltype(bufc)::value;
+      using B = std::integral_constant<int, BUF>;
+      using NB = std::integral_constant<int, (BUF + 1) % NST>;
+      wait(0);
+      issue(B{}, I1{}, 1);
+      mma(0);
+      wait(1);
+      issue(B{}, I2{}, 0);
+      mma(1);
+      wait(0);
+      issue(B{}, I3{}, 1);
+      mma(0);
+      wait(1);
+      wait_vmcnt<(NST - 2) * LPS>();
+      wg_barrier();
+      issue(NB{}, I0{}, 0);
+      mma(1);
+      const int ks = kax.off + (s_lo + it + NST) * 64;
+      la.issue(lds + BUF * OPA, ks, wave);
+      lb.issue(lds + NST * OPA + BUF * OPB, ks, wave);
+    };
     if (S > 0) {
 #pragma unroll
       for (int st = 0; st < NST; ++st)
@@ -576,7 +600,17 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       else wait_vmcnt<0>();
       wg_barrier();
       issue(I0{}, I0{}, 0);
-      for (int it = 0; it < S; it += NST) {
+      int it0 = 0;
+      if (MODE == 0 && kax.kind == AX_AFFINE) {
+        // steps whose stage it+NST is not the last one (only the last can be partial)
+        for (; it0 + 2 * NST < S; it0 += NST) {
+          steady_step(I0{}, it0);
+          steady_step(I1{}, it0 + 1);
+          if (NST > 2) steady_step(std::integral_constant<int, 2 % NST>{}, it0 + 2);
+          if (NST > 3) steady_step(std::integral_constant<int, 3 % NST>{}, it0 + 3);
+        }
+      }
+      for (int it = it0; it < S; it += NST) {
         step(I0{}, it);
         if (NST > 1 && it + 1 < S) step(std::integral_constant<int, 1 % NST>{}, it + 1);
         if (NST > 2 && it + 2 < S) step(std::integral_constant<int, 2 % NST>{}, it + 2);
