@@ -101,7 +101,7 @@ class MlpChain:
 
         Hidden activations and their gradients stay compact between the calls (only kept
         neurons are stored); W2's kept block is gathered once per iteration and shared by the
-        forward and the data-gradient product; weight gradients are written in full, or, with
+        forward and the data-gradient product (the 10-neuron last layer reads W3 through the map); weight gradients are written in full, or, with
         compact_dw, as the gradient of the kept synapses only (a reported variant, not the headline)."""
         lib, B = self.lib, BATCH
         p1, p2 = self._pat(*pats[0]), self._pat(*pats[1])
@@ -128,14 +128,13 @@ class MlpChain:
             return ("call", lane, fn, args + tail, name, flops)
         return [
             call(1, cw, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1), "L2.compact_w", 0.0),
-            call(1, cw, (bf, SIZES[2], SIZES[3], P(W3), P(W3c), None, p2), "L3.compact_w", 0.0),
             call(0, fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, OUT), "L1.fwd", f * SIZES[0] * k1),
             ("wait", 0, 1),
             call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2c), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC), "L2.fwd", f * k1 * k2),
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT | DW), "L3.bwd_weight", f * k2 * SIZES[3]),
-            call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3c), P(Y3), None, p2, 1.0, 0, IN | WC), "L3.fwd", f * k2 * SIZES[3]),
-            call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3c), P(dY2), None, p2, 1.0, P(Y2), IN | OUT | WC), "L3.bwd_data", f * k2 * SIZES[3]),
+            call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, p2, 1.0, 0, IN), "L3.fwd", f * k2 * SIZES[3]),
+            call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3), P(dY2), None, p2, 1.0, P(Y2), IN | OUT), "L3.bwd_data", f * k2 * SIZES[3]),
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT | DW), "L2.bwd_weight", f * k1 * k2),
             call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2c), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC), "L2.bwd_data", f * k1 * k2),

@@ -577,6 +577,7 @@ static int32_t aligned_activation(int32_t dtype, const void* p, int rows, int co
   return ARD_OK;
 }
 
+constexpr int32_t kLayoutFlags = ARD_IN_COMPACT | ARD_OUT_COMPACT | ARD_W_COMPACT | ARD_DW_COMPACT;
 static bool is_identity(const Axis& a) { return a.kind == AX_AFFINE && a.off == 0 && a.step == 1; }
 
 // Row / list pattern layer: resolves the layout flags into operand descriptions.
@@ -688,6 +689,9 @@ extern "C" int32_t ard_drop_gemm_fwd(int32_t dtype, int32_t B, int32_t I, int32_
     max_bn = pick_bn(pat_out->tile_r);
   } else {
     if (flags & ARD_DW_COMPACT) return fail(ARD_EINVAL, "ARD_DW_COMPACT belongs to the weight gradient");
+    if (!(flags & ~kLayoutFlags) && try_skinny(0, dtype, B, I, O, X, W, Y, axis_of_pattern(pat_out, O), axis_of_pattern(pat_in, I),
+                                               flags, alpha, 0.0f, fuse_relu != 0, nullptr, stream, &st))
+      return st;
     RowLayer L;
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
@@ -754,6 +758,9 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
     max_bn = pick_bn(pat_out->tile_c);
   } else {
     if (flags & ARD_DW_COMPACT) return fail(ARD_EINVAL, "ARD_DW_COMPACT belongs to the weight gradient");
+    if (!(flags & ~kLayoutFlags) && try_skinny(1, dtype, B, I, O, dY, W, dX, axis_of_pattern(pat_out, O), axis_of_pattern(pat_in, I),
+                                               flags, alpha, 0.0f, 0, relu_src, stream, &st))
+      return st;
     RowLayer L;
     st = resolve_row_layer(a, flags, W, true, ws, ws_bytes, stream, L);
     if (st) return st;
@@ -857,6 +864,9 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
       dw_compact = true;
     }
   }
+  if (!a.tile && try_skinny(2, dtype, B, I, O, dY, X, dW, axis_of_pattern(pat_out, O), axis_of_pattern(pat_in, I), flags, alpha,
+                            beta, 0, nullptr, stream, &st))
+    return st;
   P.A.vec = operand_vec_ok(P.A, false, P.k, ce);
   P.B.vec = operand_vec_ok(P.B, false, P.k, ce);
   P.C.p = dW;
