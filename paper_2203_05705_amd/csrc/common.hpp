@@ -94,10 +94,11 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // column count of a compact matrix: kept count rounded up to a whole 16-byte chunk of bf16
 // Development switches, read once from the environment: ARD_NO_FAST=1 sends every product
 // through the general engine, ARD_NO_SCATTER=1 disables the scattering epilogue (partial sums +
-// finishing pass instead), ARD_FORCE_TILE=64|128 pins the general engine's workgroup tile.
+// finishing pass instead), ARD_FORCE_TILE=64|128 pins the general engine's workgroup tile,
+// ARD_CLASS_TILE=1..5 pins the tile of the tile-pattern products (position in their tile list).
 struct DevKnobs {
   bool no_fast, no_scatter;
-  int force_tile;
+  int force_tile, class_tile;
 };
 const DevKnobs& dev_knobs();
 

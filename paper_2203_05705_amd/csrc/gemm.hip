@@ -491,6 +491,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   int heavy = 0, bm = 256, bn = 256, total = 0;
   for (const TileCfg& c : kTileCfgs) {
     if ((c.bn % t.n_bs) || (op == 2 && (c.bm % x))) continue;
+    if (dev_knobs().class_tile && &c != &kTileCfgs[dev_knobs().class_tile - 1]) continue;
     bm = c.bm, bn = c.bn;
     total = count(bm, bn, heavy);
     if (heavy >= 200) break;

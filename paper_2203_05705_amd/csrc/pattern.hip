@@ -12,7 +12,8 @@ namespace ard {
 
 const DevKnobs& dev_knobs() {
   static const DevKnobs k = {getenv("ARD_NO_FAST") != nullptr, getenv("ARD_NO_SCATTER") != nullptr,
-                             getenv("ARD_FORCE_TILE") ? atoi(getenv("ARD_FORCE_TILE")) : 0};
+                             getenv("ARD_FORCE_TILE") ? atoi(getenv("ARD_FORCE_TILE")) : 0,
+                             getenv("ARD_CLASS_TILE") ? atoi(getenv("ARD_CLASS_TILE")) : 0};
   return k;
 }
 
