@@ -413,7 +413,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       local -= hi - lo;
     }
     if (l < 0) return;
-    const int mi = l % t.mblk[c], ni = l / t.mblk[c];
+    // bands of group_m row blocks, walked column by column (as in the plain case): an XCD's share
+    // of a class is about square, so its operand panels are reused out of that XCD's L2
+    const int nbc = t.nblk[c] / t.mblk[c];
+    const int band_sz = P.group_m * nbc;
+    const int band = l / band_sz, inb = l - band * band_sz;
+    const int rows_in_band = min(P.group_m, t.mblk[c] - band * P.group_m);
+    const int mi = band * P.group_m + inb % rows_in_band, ni = inb / rows_in_band;
     if (t.m_bs) {
       const int g = F_BM / t.m_bs;
       const int left = t.m_cnt[c] - mi * g;
