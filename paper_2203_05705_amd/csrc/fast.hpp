@@ -596,8 +596,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       issue(NB{}, I0{}, 0);
       mma(1);
       const int ks = fast_kslab(kax, (s_lo + it + NST) * 64);
+      int ksb = ks;
+      if constexpr (MODE == 1) {
+        const int t = ks / P.cv.Cp;
+        ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
+      }
       la.issue(lds + BUF * OPA, ks, wave);
-      lb.issue(lds + NST * OPA + BUF * OPB, ks, wave);
+      lb.issue(lds + NST * OPA + BUF * OPB, ksb, wave);
     };
     if (S > 0) {
 #pragma unroll
@@ -608,7 +613,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       wg_barrier();
       issue(I0{}, I0{}, 0);
       int it0 = 0;
-      if (MODE == 0 && (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && kax.bs % 64 == 0))) {
+      if (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && kax.bs % 64 == 0)) {
         // steps whose stage it+NST is not the last one (only the last can be partial)
         for (; it0 + 2 * NST < S; it0 += NST) {
           steady_step(I0{}, it0);
