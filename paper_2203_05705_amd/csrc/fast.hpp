@@ -391,10 +391,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
   int local = blockIdx.x >> 3;
   Axis am = P.am, bn = P.bn, kax = P.k;
   int m0 = 0, n0 = 0;
+  int split = 0;  // share of the contraction this workgroup takes
   if (P.tab.ncls == 0) {
-    const int lo = (int)((long)xcd * P.total_tiles / 8), hi = (int)((long)(xcd + 1) * P.total_tiles / 8);
+    // work items = (split, tile), split-major: an XCD's contiguous share holds whole splits (or long
+    // runs of one), so the workgroups in flight on it read the same slab of the contraction
+    const int total = P.total_tiles * P.splits;
+    const int lo = (int)((long)xcd * total / 8), hi = (int)((long)(xcd + 1) * total / 8);
     if (local >= hi - lo) return;
-    const int L = lo + local;
+    int L = lo + local;
+    split = L / P.total_tiles;
+    L -= split * P.total_tiles;
     // bands of group_m tile rows, walked column by column
     const int band_sz = P.group_m * P.tiles_n;
     const int band = L / band_sz, inb = L - band * band_sz;
@@ -478,7 +484,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
     }
     // contraction steps of this workgroup (a share of them when the contraction is split)
     const int S_all = (Kn + 63) >> 6;
-    const int s_lo = (int)((long)blockIdx.y * S_all / P.splits), s_hi = (int)((long)(blockIdx.y + 1) * S_all / P.splits);
+    const int s_lo = (int)((long)split * S_all / P.splits), s_hi = (int)((long)(split + 1) * S_all / P.splits);
     const int S = s_hi - s_lo;
     auto load_stage = [&](int it, int buf) {
       const int krem = Kn - (s_lo + it) * 64;
@@ -644,7 +650,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
   constexpr bool GENERAL_OUT = !(F_BM == 256 && BN == 256);
   if (GENERAL_OUT && P.part) {
     // fp32 partial sums of this share of the contraction, compact [M x N]
-    float* part = P.part + (long)blockIdx.y * P.M * P.N;
+    float* part = P.part + (long)split * P.M * P.N;
 #pragma unroll
     for (int in = 0; in < TN; ++in) {
       const int j = n0 + wn * WTN + in * 32 + (lane & 31);
@@ -945,23 +951,6 @@ static __global__ __launch_bounds__(256) void zero_dropped_tiles_kernel(uint16_t
   }
 }
 
-// Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
-// kernels above the 64 KiB default get their limit raised once.
-template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
-static int32_t launch_direct_kernel(const FastParams& F, int grid_x, hipStream_t stream) {
-  auto kernel = gemm_direct_kernel<A_KC, B_KC, BM, BN, NW, MODE>;
-  const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
-  static thread_local bool raised = false;
-  if (!raised && lds_bytes >= 65536) {
-    ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    raised = true;
-  }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)grid_x, (unsigned)(F.splits < 1 ? 1 : F.splits)), dim3(64 * NW), lds_bytes,
-                     stream, F);
-  ARD_LAUNCH_CHECK("gemm_direct_kernel");
-  return ARD_OK;
-}
-
 // Grid of a plain (class-free) launch: every XCD takes the share [x*n/8, (x+1)*n/8) of the tiles.
 static inline int direct_plain_grid(int total_tiles) {
   int worst = 0;
@@ -970,6 +959,26 @@ static inline int direct_plain_grid(int total_tiles) {
     worst = sum > worst ? sum : worst;
   }
   return worst * 8;
+}
+
+// Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
+// kernels above the 64 KiB default get their limit raised once.
+template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
+static int32_t launch_direct_kernel(const FastParams& F_in, int grid_x, hipStream_t stream) {
+  FastParams F = F_in;
+  if (F.splits < 1) F.splits = 1;
+  auto kernel = gemm_direct_kernel<A_KC, B_KC, BM, BN, NW, MODE>;
+  const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
+  static thread_local bool raised = false;
+  if (!raised && lds_bytes >= 65536) {
+    ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    raised = true;
+  }
+  // class-free launches: the (split, tile) items are dealt to the XCDs inside the kernel
+  if (F.tab.ncls == 0) grid_x = direct_plain_grid(F.total_tiles * (F.splits < 1 ? 1 : F.splits));
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid_x), dim3(64 * NW), lds_bytes, stream, F);
+  ARD_LAUNCH_CHECK("gemm_direct_kernel");
+  return ARD_OK;
 }
 
 // an XCD's share should be about square in tiles: bands of group_m tile rows
