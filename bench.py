@@ -126,18 +126,20 @@ class MlpChain:
             # the trailing arguments of every GEMM entry point are (workspace, bytes, stream)
             tail = (st[lane],) if fn is cw else (wsp[lane], n, st[lane])
             return ("call", lane, fn, args + tail, name, flops)
-        return [
-            call(1, cw, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1), "L2.compact_w", 0.0),
+        # nothing dropped around layer 2 (the dense baseline, a (1, 1) sample): its products read W2 itself
+        gather2 = pats[0][0] != 1 or pats[1][0] != 1
+        W2x, WC2 = (W2c, WC) if gather2 else (W2, 0)
+        return ([call(1, cw, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1), "L2.compact_w", 0.0)] if gather2 else []) + [
             call(0, fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, OUT), "L1.fwd", f * SIZES[0] * k1),
             ("wait", 0, 1),
-            call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2c), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC), "L2.fwd", f * k1 * k2),
+            call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2x), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC2), "L2.fwd", f * k1 * k2),
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT | DW), "L3.bwd_weight", f * k2 * SIZES[3]),
             call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, p2, 1.0, 0, IN), "L3.fwd", f * k2 * SIZES[3]),
             call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3), P(dY2), None, p2, 1.0, P(Y2), IN | OUT), "L3.bwd_data", f * k2 * SIZES[3]),
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT | DW), "L2.bwd_weight", f * k1 * k2),
-            call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2c), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC), "L2.bwd_data", f * k1 * k2),
+            call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2x), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC2), "L2.bwd_data", f * k1 * k2),
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT | DW1), "L1.bwd_weight", f * SIZES[0] * k1),
             ("wait", 0, 1),
