@@ -878,7 +878,13 @@ static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float
   const int piece = blockIdx.x * 256 + threadIdx.x;
   if (piece >= cols8) return;
   const int c0 = piece * 8;
-  for (int r = blockIdx.y; r < rows; r += gridDim.y) {
+  // Workgroup ids go round-robin over the 8 XCDs: XCD x takes the contiguous rows
+  // [x * chunk, (x + 1) * chunk).  (Row r on XCD r % 8 would put every kept row of a step-8
+  // pattern, i.e. all the work, on one XCD.)
+  const int chunk = (rows + 7) >> 3;
+  for (int y = blockIdx.y; y < chunk * 8; y += gridDim.y) {
+    const int r = (y & 7) * chunk + (y >> 3);
+    if (r >= rows) continue;
     const int i = C.fill ? ax_inverse(C.rm, r) : r;
     const int pr = C.fill ? r : ax_phys(C.rm, r);
     const long idx = (long)pr * C.ld + c0;

@@ -240,14 +240,32 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     // With few workgroups the zero fill of large owned regions is better spread over the whole
     // chip by the finishing pass (measured: regions above 16K elements lose below 160 tiles).
     const long region = (long)bm * C.rm.step * bn * C.cn.step;
-    if (tiles < 64 || (tiles < 160 && region > 16384)) scatter = false;
+    // Column groups wider than 4 make the epilogue's rows long and ragged (a 64-column tile owns
+    // 320+ columns): measured 25 us against 16 us through the finishing pass.
+    if (tiles < 64 || (region > 16384 && (tiles < 160 || C.cn.step > 4))) scatter = false;
   }
+  // Splitting the contraction s ways shortens a workgroup's loop by steps * (1 - 1/s) steps of about
+  // 0.19 us (a step takes that long however few tiles there are), and costs about 2.6 us per
+  // additional split in the pass that sums the partial sums (they come back from memory, written
+  // by other XCDs), plus the pass itself (about 6 us) for a product that could have stored its own
+  // result.  Measured on 256 x 784 x 1024: 8.4 + 6.2 us unsplit against 6.6 + 19.8 us in 6 splits.
+  // A caller that sums the partials in a kernel it runs anyway (LSTM cell) keeps the old rule.
   int splits = 1;
   if (!scatter && tiles < 160 && steps >= 4) {
-    splits = (int)(320 / tiles);
-    if (splits > steps / 2) splits = steps / 2;
-    if (splits > 8) splits = 8;
-    if (splits < 1) splits = 1;
+    int cap = (int)(320 / tiles);
+    if (cap > steps / 2) cap = steps / 2;
+    if (cap > 8) cap = 8;
+    if (cap < 1) cap = 1;
+    if (raw_splits) {
+      splits = cap;
+    } else {
+      const bool own_store = direct_out;  // no pass needed without a split
+      float best = 0.0f;
+      for (int sp = 2; sp <= cap; ++sp) {
+        const float gain = steps * 0.19f * (1.0f - 1.0f / sp) - 2.6f * (sp - 1) - (own_store ? 6.0f : 0.0f);
+        if (gain > best) best = gain, splits = sp;
+      }
+    }
   }
   if (bm == 256 && bn == 256) splits = 1;
   size_t need = (splits > 1 || raw_splits || (!direct_out && !scatter)) ? (size_t)splits * P.M * P.N * 4 : 0;
@@ -302,7 +320,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   if (blocks < 1) blocks = 1;
   if (vec_out) {
     const int out_rows = C.fill ? C.rm.nphys : P.M;
-    dim3 grid((unsigned)ceil_div(out_cols / 8, 256), (unsigned)(out_rows < 32768 ? out_rows : 32768));
+    const int grid_rows = ceil_div(out_rows, 8) * 8;  // the pass deals rows to the XCDs in eighths
+    dim3 grid((unsigned)ceil_div(out_cols / 8, 256), (unsigned)(grid_rows < 32768 ? grid_rows : 32768));
     hipLaunchKernelGGL(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, (const float*)ws, splits, P.M, P.N, C);
   }
   else
