@@ -237,12 +237,18 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
       }
     }
     tiles = (long)ceil_div(P.M, bm) * ceil_div(P.N, bn);
-    // With few workgroups the zero fill of large owned regions is better spread over the whole
-    // chip by the finishing pass (measured: regions above 16K elements lose below 160 tiles).
     const long region = (long)bm * C.rm.step * bn * C.cn.step;
-    // Column groups wider than 4 make the epilogue's rows long and ragged (a 64-column tile owns
-    // 320+ columns): measured 25 us against 16 us through the finishing pass.
-    if (tiles < 64 || (region > 16384 && (tiles < 160 || C.cn.step > 4))) scatter = false;
+    // Measured on the weight gradients of the MLP chain, every (row step, column step) in 1..8:
+    // what the epilogue costs grows with the column step (rows of the owned region get long and
+    // ragged).  With identity columns it always beats the finishing pass; with column step 2 up
+    // to row step 4; beyond that only while the region is small or the tiles many, and never for
+    // column groups wider than 4 (25 us against 15 us through the pass).
+    const int cs = C.cn.step;
+    const bool small_or_many = region <= 16384 || tiles >= 160;
+    if (cs == 1) scatter = tiles >= 4;
+    else if (cs == 2) scatter = tiles >= 64 ? (small_or_many || C.rm.step <= 4) : false;
+    else if (cs <= 4) scatter = tiles >= 64 && small_or_many;
+    else scatter = tiles >= 64 && region <= 16384;
   }
   // Splitting the contraction s ways shortens a workgroup's loop by steps * (1 - 1/s) steps of about
   // 0.19 us (a step takes that long however few tiles there are), and costs about 2.6 us per
