@@ -216,7 +216,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     if (c.bm == 256 && c.bn == 256 && !plain_out) continue;  // that tile only stores plain bf16
     tiles = (long)ceil_div(P.M, c.bm) * ceil_div(P.N, c.bn);
     bm = c.bm, bn = c.bn;
-    if (tiles >= 220) break;
+    // An 8-wavefront tile wants a workgroup per CU; a 4-wavefront tile runs one wavefront per SIMD
+    // and wants two workgroups per CU to overlap its waits (measured at batch 1024: 256 tiles of
+    // 128 x 64 take 23.5 us where 512 tiles of 64 x 64 take 15.8 us).
+    if (tiles >= (c.bm * c.bn >= 256 * 128 ? 220 : 440)) break;
   }
   if (tiles >= (1L << 24)) return false;
   // A scattered bf16 output with zero fill through affine maps is stored by the product's own
