@@ -522,7 +522,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     if (dev_knobs().class_tile && &c != &kTileCfgs[dev_knobs().class_tile - 1]) continue;
     bm = c.bm, bn = c.bn;
     total = count(bm, bn, heavy);
-    if (heavy >= 200) break;
+    if (heavy >= (bm * bn >= 256 * 128 ? 200 : 440)) break;  // (two workgroups per CU for the 4-wavefront tiles)
   }
   if (total == 0) return false;
   if (heavy < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
