@@ -36,7 +36,7 @@ N_PATTERNS = 8           # dp_max of the searched distribution
 SEED = 2
 # HBM bytes per launch of the dominant call's GEMM kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --exec eager` (summaries under profiles/); None until measured
-TRAFFIC_BYTES = {"L2.bwd_weight": 16056201}   # 11370 KiB fetched + 4310 KiB written per launch
+TRAFFIC_BYTES = {"L2.bwd_weight": 16677504}   # 11366 KiB fetched + 4921 KiB written per launch
 
 
 def parse():
