@@ -1,10 +1,11 @@
 // Layers with at most 16 output neurons (the classifier at the end of the MLP; Sec. III-B applies
 // the row pattern to its INPUT neurons only, since output units are never dropped): bf16 kernels
-// that read the operands straight from global memory and take the kept-input map themselves, so
-// neither a gathered copy of W nor a split contraction with a finishing pass is needed.
+// without the tile machinery that take the kept-input map themselves (a dense W is copied into LDS
+// with 16-byte loads and read through the map there), so neither a gathered copy of W in memory
+// nor a split contraction with a finishing pass is needed.
 //
 //   forward          Y[B x O]   = alpha * Xc[B x K'] . W[O x kept]^T        (16x16x32 MFMA, K' split over 4 waves)
-//   backward, data   dXc[B x K'] = alpha * dY[B x O] . W[O x kept]           (vector FMAs, W held in registers)
+//   backward, data   dXc[B x K'] = alpha * dY[B x O] . W[O x kept]           (vector FMAs, a thread's 16 x 8 weights in registers)
 //   backward, weight dW[O x kept] = alpha * dY^T . Xc                         (16x16x32 MFMA, batch split over 4 waves)
 //
 // Xc / dXc are activations in the compact layout (pad8(K') columns, zero padded) or, without a
