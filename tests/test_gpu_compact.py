@@ -181,3 +181,23 @@ def test_config2_mlp_chain_iterations():
         dW1 = ard.drop_gemm_bwd_weight(dY1o, X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
         assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape), what="dW1")
     torch.cuda.synchronize()
+
+@pytest.mark.parametrize("B,O,I,po,pi", [(256, 2044, 1024, (8, 3), (3, 2)), (8192, 520, 512, (8, 1), (2, 1)),
+                                          (1024, 2048, 784, (8, 8), None)])
+def test_weight_gradient_through_the_finishing_pass(B, O, I, po, pi):
+    """Full-size dW from compact operands where the product leaves fp32 partial sums to a second pass:
+    few kept rows (every 8th, row count not a multiple of 8), a contraction long enough to be split,
+    and identity columns with 4 row tiles."""
+    dtype = "bf16"
+    print(f"finishing pass B={B} O={O} I={I} pat_out={po} pat_in={pi}", flush=True)
+    rng = np.random.default_rng(B + O)
+    Xv, dYv = (stored(rng.standard_normal(s) * 0.25, dtype) for s in ((B, I), (B, O)))
+    mo = P.row_mask(O, *po)
+    mi = P.row_mask(I, *pi) if pi else np.ones(I, np.uint8)
+    ko, ki = P.keep_list(mo), P.keep_list(mi)
+    MW = G.weight_mask_rows(mo, mi)
+    refdW = G.drop_gemm_bwd_weight(dYv, Xv, MW, mo)
+    dW = torch.full((O, I), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ard.drop_gemm_bwd_weight(compact_in(dYv[:, ko], dtype), compact_in(Xv[:, ki], dtype), ard.Pattern.row(*po),
+                             ard.Pattern.row(*pi) if pi else None, flags=ard.IN_COMPACT | ard.OUT_COMPACT, out=dW, I=I, O=O)
+    assert_parity(dW, refdW, dtype, zero_mask=(MW == 0), what="dW")
