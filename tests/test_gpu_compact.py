@@ -171,6 +171,11 @@ def test_config2_mlp_chain_iterations():
         assert_parity(dW3c, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3 (padded dY)")
         dY2c = ard.drop_gemm_bwd_data(dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
         check_compact(dY2c, ref["dY"][1][:, keep[1]], "bf16", "dY2 (padded dY)")
+        # the last layer as the benchmark issues it: W3 itself, read through the kept-input map
+        Y3d = ard.drop_gemm_fwd(Y2o, W[2], None, p2, flags=IN, I=sizes[2], O=sizes[3])
+        assert_parity(Y3d, ref["Y"][2], "bf16", what="Y3 (dense W3)")
+        dY2d = ard.drop_gemm_bwd_data(dYLc, W[2], None, p2, relu_src=Y2o, flags=IN | OUT, I=sizes[2], O=sizes[3])
+        check_compact(dY2d, ref["dY"][1][:, keep[1]], "bf16", "dY2 (dense W3)")
         dY2o = compact_in(ref["dY"][1][:, keep[1]], "bf16")
         dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
         MW2 = G.weight_mask_rows(masks[1], masks[0])
