@@ -581,8 +581,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       if (it + NST < S) load_stage(it + NST, BUF);
     };
     // The same step where every question is settled: a successor stage exists, the stage to load
-    // exists and is a full one (the axis is affine, or made of blocks that hold whole steps).  No
-    // tail handling, no branches.
+    // exists and is a full one (the axis is affine, or made of whole blocks that hold whole steps:
+    // then only the last stage can be partial).  No tail handling, no branches.
     auto steady_step = [&](auto bufc, int it) {
       constexpr int BUF = decltype(bufc)::value;
       using B = std::integral_constant<int, BUF>;
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       wg_barrier();
       issue(I0{}, I0{}, 0);
       int it0 = 0;
-      if (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && kax.bs % 64 == 0)) {
+      if (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && kax.bs % 64 == 0 && kax.nphys % kax.bs == 0)) {
         // steps whose stage it+NST is not the last one (only the last can be partial)
         for (; it0 + 2 * NST < S; it0 += NST) {
           steady_step(I0{}, it0);

@@ -49,6 +49,8 @@ def test_config3_tile_gemm_full_size(dp, b):
     (2048, 2048, 2048, 32, 64, 3, 2),      # 32-row tiles
     (2050, 2056, 2312, 64, 128, 6, 4),     # gcd(TC, dp) > 1 and ragged batch
     (2048, 4096, 4096, 256, 256, 2, 2),
+    (2048, 5128, 2048, 64, 128, 2, 1),     # long contraction whose last 128-wide block holds 8 columns (kept)
+    (2048, 5128, 2048, 64, 128, 2, 2),     # ... (dropped)
 ])
 def test_large_tile_path_other_shapes(B, I, O, x, y, dp, b):
     print(f"large tile case B={B} I={I} O={O} tile={x}x{y} dp={dp} b={b}", flush=True)
