@@ -134,7 +134,10 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int row = min(row0 + (wave * NI + j) * 8 + (lane >> 3), r.n - 1);
-      voff[j] = (uint32_t)(ax_phys(r, row) * ld + chunk_k(lane, wave, j)) * 2u;
+      // (a block axis counts its last block in full even when the operand ends inside it)
+      int prow = ax_phys(r, row);
+      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) prow = min(prow, r.nphys - 1);
+      voff[j] = (uint32_t)(prow * ld + chunk_k(lane, wave, j)) * 2u;
     }
   }
   // rows = output pixels of a convolution: base pixel of the patch in the bordered grid
@@ -196,7 +199,10 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
     for (int j = 0; j < NI; ++j) {
       const int kloc = KPI * (wave * NI + j) + lane / CPR;
       const int col = min(row0 + lane_chunk(lane, wave, j) * 8, r.n - 8);  // runs beyond the axis: clamped
-      voff[j] = (uint32_t)(kloc * ld + ax_phys(r, col)) * 2u;
+      // (a block axis counts its last block in full even when the operand ends inside it)
+      int pcol = ax_phys(r, col);
+      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) pcol = max(min(pcol, (r.nphys - 8) & ~7), 0);
+      voff[j] = (uint32_t)(kloc * ld + pcol) * 2u;
     }
   }
   // columns = (tap, channel) of the weight gradient: pixel offset of the tap plus the channel

@@ -51,6 +51,8 @@ def test_config3_tile_gemm_full_size(dp, b):
     (2048, 4096, 4096, 256, 256, 2, 2),
     (2048, 5128, 2048, 64, 128, 2, 1),     # long contraction whose last 128-wide block holds 8 columns (kept)
     (2048, 5128, 2048, 64, 128, 2, 2),     # ... (dropped)
+    (1965, 2760, 2480, 256, 64, 7, 1),     # W ends 176 rows into its last 256-row tile row (loaders clamp there)
+    (968, 1864, 3144, 256, 128, 3, 3),     # both axes end inside their last block
 ])
 def test_large_tile_path_other_shapes(B, I, O, x, y, dp, b):
     print(f"large tile case B={B} I={I} O={O} tile={x}x{y} dp={dp} b={b}", flush=True)
