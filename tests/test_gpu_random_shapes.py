@@ -76,3 +76,20 @@ def test_random_layers(seed):
         assert_parity(dWc[:len(ko), :len(ki)].contiguous(), refdW[np.ix_(ko, ki)], "bf16", what="dW compact")
         bits = raw_bits(dWc)
         assert not bits[len(ko):, :].any() and not bits[:, len(ki):].any(), "dW compact padding"
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_tile_patterns(seed):
+    """Tile patterns at sizes that take the class-grouped large-tile kernels: random tile shapes, periods
+    and extents that end inside their last tile row / column."""
+    from test_gpu_fast import _tile_case
+    rng = np.random.default_rng(2000 + seed)
+    B = int(rng.integers(100, 330)) * 8 + (int(rng.integers(0, 8)) if rng.random() < 0.3 else 0)
+    I = int(rng.integers(100, 520)) * 8
+    O = int(rng.integers(100, 330)) * 8
+    x, y = int(rng.choice([32, 64, 128, 256])), int(rng.choice([32, 64, 128, 256]))
+    dp = int(rng.integers(1, 9))
+    b = int(rng.integers(1, dp + 1))
+    print(f"seed {seed}: B={B} I={I} O={O} tile {x}x{y} dp={dp} b={b}", flush=True)
+    Xv, Wv, dYv = (stored(rng.standard_normal(s) * 0.5, "bf16") for s in ((B, I), (O, I), (B, O)))
+    _tile_case(Xv, Wv, dYv, from_vals(Xv, "bf16"), from_vals(Wv, "bf16"), from_vals(dYv, "bf16"), x, y, dp, b, f"seed {seed}")
