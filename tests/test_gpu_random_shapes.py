@@ -31,13 +31,14 @@ def draw_case(rng):
     return B, I, O, po, pi
 
 
+@pytest.mark.parametrize("dtype", [dtype, "f32"])
 @pytest.mark.parametrize("seed", range(6))
-def test_random_layers(seed):
+def test_random_layers(seed, dtype):
     rng = np.random.default_rng(1000 + seed)
     for case in range(5):
         B, I, O, po, pi = draw_case(rng)
-        print(f"seed {seed} case {case}: B={B} I={I} O={O} pat_out={po} pat_in={pi}", flush=True)
-        Xv, Wv, dYv = (stored(rng.standard_normal(s) * 0.5, "bf16") for s in ((B, I), (O, I), (B, O)))
+        print(f"{dtype} seed {seed} case {case}: B={B} I={I} O={O} pat_out={po} pat_in={pi}", flush=True)
+        Xv, Wv, dYv = (stored(rng.standard_normal(s) * 0.5, dtype) for s in ((B, I), (O, I), (B, O)))
         mo = P.row_mask(O, *po) if po else np.ones(O, np.uint8)
         mi = P.row_mask(I, *pi) if pi else np.ones(I, np.uint8)
         ko, ki = P.keep_list(mo), P.keep_list(mi)
@@ -47,33 +48,33 @@ def test_random_layers(seed):
         refY = G.drop_gemm_fwd(Xv, Wv, MW, mo, 1.0, relu=True)
         refdX = G.drop_gemm_bwd_data(dYv, Wv, MW, mo, 1.0)
         refdW = G.drop_gemm_bwd_weight(dYv, Xv, MW, mo)
-        X, W, dY = (from_vals(v, "bf16") for v in (Xv, Wv, dYv))
-        Xc, dYc = ard.pad_compact(from_vals(Xv[:, ki], "bf16")), ard.pad_compact(from_vals(dYv[:, ko], "bf16"))
+        X, W, dY = (from_vals(v, dtype) for v in (Xv, Wv, dYv))
+        Xc, dYc = ard.pad_compact(from_vals(Xv[:, ki], dtype)), ard.pad_compact(from_vals(dYv[:, ko], dtype))
         Wc = ard.compact_weight(W, pat_o, pat_i)
         zo, zi = (mo == 0)[None, :], (mi == 0)[None, :]
-        assert_parity(ard.drop_gemm_fwd(X, W, pat_o, pat_i, relu=True), refY, "bf16", zero_mask=zo, what="Y")
-        assert_parity(ard.drop_gemm_bwd_data(dY, W, pat_o, pat_i), refdX, "bf16", zero_mask=zi, what="dX")
-        assert_parity(ard.drop_gemm_bwd_weight(dY, X, pat_o, pat_i), refdW, "bf16", zero_mask=(MW == 0), what="dW")
+        assert_parity(ard.drop_gemm_fwd(X, W, pat_o, pat_i, relu=True), refY, dtype, zero_mask=zo, what="Y")
+        assert_parity(ard.drop_gemm_bwd_data(dY, W, pat_o, pat_i), refdX, dtype, zero_mask=zi, what="dX")
+        assert_parity(ard.drop_gemm_bwd_weight(dY, X, pat_o, pat_i), refdW, dtype, zero_mask=(MW == 0), what="dW")
         for flags, Wt in ((IN | OUT, W), (IN | OUT | WC, Wc), (IN, W), (OUT, W)):
             Xin, dYin = (Xc if flags & IN else X), (dYc if flags & OUT else dY)
             Y = ard.drop_gemm_fwd(Xin, Wt, pat_o, pat_i, relu=True, flags=flags, I=I, O=O)
             if flags & OUT:
-                assert_parity(Y[:, :len(ko)].contiguous(), refY[:, ko], "bf16", what=f"Y flags={flags}")
+                assert_parity(Y[:, :len(ko)].contiguous(), refY[:, ko], dtype, what=f"Y flags={flags}")
                 assert not raw_bits(Y[:, len(ko):].contiguous()).any(), "Y padding"
             else:
-                assert_parity(Y, refY, "bf16", zero_mask=zo, what=f"Y flags={flags}")
+                assert_parity(Y, refY, dtype, zero_mask=zo, what=f"Y flags={flags}")
             dX = ard.drop_gemm_bwd_data(dYin, Wt, pat_o, pat_i, flags=flags, I=I, O=O)
             if flags & IN:
-                assert_parity(dX[:, :len(ki)].contiguous(), refdX[:, ki], "bf16", what=f"dX flags={flags}")
+                assert_parity(dX[:, :len(ki)].contiguous(), refdX[:, ki], dtype, what=f"dX flags={flags}")
                 assert not raw_bits(dX[:, len(ki):].contiguous()).any(), "dX padding"
             else:
-                assert_parity(dX, refdX, "bf16", zero_mask=zi, what=f"dX flags={flags}")
+                assert_parity(dX, refdX, dtype, zero_mask=zi, what=f"dX flags={flags}")
             if not flags & WC:
-                dW = torch.full((O, I), float("nan"), dtype=torch.bfloat16, device="cuda")
+                dW = torch.full((O, I), float("nan"), dtype=X.dtype, device="cuda")
                 ard.drop_gemm_bwd_weight(dYin, Xin, pat_o, pat_i, flags=flags, out=dW, I=I, O=O)
-                assert_parity(dW, refdW, "bf16", zero_mask=(MW == 0), what=f"dW flags={flags}")
+                assert_parity(dW, refdW, dtype, zero_mask=(MW == 0), what=f"dW flags={flags}")
         dWc = ard.drop_gemm_bwd_weight(dYc, Xc, pat_o, pat_i, flags=IN | OUT | DW, I=I, O=O)
-        assert_parity(dWc[:len(ko), :len(ki)].contiguous(), refdW[np.ix_(ko, ki)], "bf16", what="dW compact")
+        assert_parity(dWc[:len(ko), :len(ki)].contiguous(), refdW[np.ix_(ko, ki)], dtype, what="dW compact")
         bits = raw_bits(dWc)
         assert not bits[len(ko):, :].any() and not bits[:, len(ki):].any(), "dW compact padding"
 
