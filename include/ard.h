@@ -262,6 +262,39 @@ int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype,
                            uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* ---- sizes of compact buffers and grids (host only, nothing is launched) --- */
+
+/* Number of kept units of a ROW / LIST / NONE pattern over `units` units: ceil((units - (b-1)) / dp)
+ * for ROW (Section 3.1; the "(dp-1)/dp dropped" of the text is exact only when dp divides units),
+ * `count` for LIST, `units` for NONE or NULL.  Negative ard_status on a bad pattern. */
+int32_t ard_kept_count(const ard_pattern* pat, int32_t units);
+/* Stored extent of that axis in a compact matrix: the kept count rounded up to a multiple of 8. */
+int32_t ard_compact_dim(const ard_pattern* pat, int32_t units);
+/* Tile grid of a TILE pattern over W[rows x cols]: ceil(rows/tile_r) x ceil(cols/tile_c) (Section 3.2). */
+int32_t ard_tile_grid(const ard_pattern* pat, int32_t rows, int32_t cols, int32_t* tile_rows, int32_t* tile_cols);
+/* Output extent of a convolution along one axis: (in + 2 pad - k) / stride + 1, or a negative status. */
+int32_t ard_conv_out_size(int32_t in, int32_t k, int32_t stride, int32_t pad);
+
+/* ---- debugging aids (host logic without a GPU) ----------------------------- */
+
+/*
+ * Dry-run mode, process-wide.  While on, every entry point runs its argument checks, its dispatch
+ * and the host-side bounds proof of its loaders (every workgroup, wavefront, lane and contraction
+ * step of every launch that fetches operands with unchecked per-lane addresses), but enqueues nothing
+ * and makes no HIP call; device pointers are never dereferenced, so any non-NULL, 16-byte aligned
+ * value will do.  Turning the mode on or off resets the counters below.
+ */
+void ard_debug_set_dry_run(int32_t on);
+/* Launches skipped on this thread since the last call (or mode switch); if names != NULL their kernel
+ * names, comma separated and truncated to cap-1 characters, are copied there. */
+int32_t ard_debug_dry_launches(char* names, size_t cap);
+/* Bounds proofs run on this thread since the last call; six[0..5] = first byte, end byte and size of
+ * operand A, then of operand B, of the most recent one (offsets relative to the operand's pointer). */
+int32_t ard_debug_last_bounds(int64_t* six);
+/* The proofs treat every operand as `elems` elements shorter than stated (0 = normal).  Lets a test
+ * show that a proof rejects a launch whose loads would end past a (pretended) operand end. */
+void ard_debug_set_extent_slack(int64_t elems);
+
 /* ---- misc ---------------------------------------------------------------- */
 
 /* Message of the last failing call on this thread (static storage, never NULL). */

@@ -89,6 +89,14 @@ _SIGS = {
     "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
     "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
+    "ard_kept_count": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "ard_compact_dim": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "ard_tile_grid": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "ard_conv_out_size": (C.c_int32, [C.c_int32] * 4),
+    "ard_debug_set_dry_run": (None, [C.c_int32]),
+    "ard_debug_dry_launches": (C.c_int32, [C.c_char_p, C.c_size_t]),
+    "ard_debug_last_bounds": (C.c_int32, [C.c_void_p]),
+    "ard_debug_set_extent_slack": (None, [C.c_int64]),
     "ard_last_error": (C.c_char_p, []),
     "ard_version": (C.c_int32, []),
 }
@@ -142,6 +150,22 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
+_ALLOC = torch.empty
+
+
+def set_output_allocator(fn=None):
+    """Every output tensor the wrappers below create comes from fn(shape, dtype=..., device=...)
+    (default torch.empty).  Tests install an allocator that poisons outputs and fences them with
+    guard bands; returns the previous allocator."""
+    global _ALLOC
+    prev, _ALLOC = _ALLOC, (torch.empty if fn is None else fn)
+    return prev
+
+
+def _out(shape, dtype, device):
+    return _ALLOC(tuple(int(v) for v in shape), dtype=dtype, device=device)
+
+
 def _dev(t: torch.Tensor):
     assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
     return t
@@ -180,20 +204,22 @@ def pattern_gen(pat: Pattern, rows: int, cols: int = 0, device="cuda", stream=No
     """Mask, kept list, count (and tile offsets) as device tensors."""
     cp, ref = _pref(pat)
     if pat.kind == PAT_TILE:
-        TR, TC = -(-rows // max(pat.tile_r, 1)), -(-cols // max(pat.tile_c, 1))
-        n = max(TR * TC, 1)
-        out = dict(mask=torch.empty(n, dtype=torch.uint8, device=device),
+        tr, tc = C.c_int32(), C.c_int32()
+        _check(lib().ard_tile_grid(ref, rows, cols, C.byref(tr), C.byref(tc)))
+        TR, TC = tr.value, tc.value
+        n = TR * TC
+        out = dict(mask=_out((n,), torch.uint8, device),
                    keep=torch.full((n,), -1, dtype=torch.int32, device=device),
                    count=torch.zeros(1, dtype=torch.int32, device=device),
-                   rowptr=torch.empty(TR + 1, dtype=torch.int32, device=device),
-                   colptr=torch.empty(TC + 1, dtype=torch.int32, device=device),
+                   rowptr=_out((TR + 1,), torch.int32, device),
+                   colptr=_out((TC + 1,), torch.int32, device),
                    csc_rows=torch.full((n,), -1, dtype=torch.int32, device=device))
         _check(lib().ard_pattern_gen(ref, rows, cols, out["mask"].data_ptr(), out["keep"].data_ptr(),
                                      out["count"].data_ptr(), out["rowptr"].data_ptr(), out["colptr"].data_ptr(),
                                      out["csc_rows"].data_ptr(), _stream(stream)))
         return out
     n = max(rows, 1)
-    out = dict(mask=torch.empty(n, dtype=torch.uint8, device=device),
+    out = dict(mask=_out((n,), torch.uint8, device),
                keep=torch.full((n,), -1, dtype=torch.int32, device=device),
                count=torch.zeros(1, dtype=torch.int32, device=device))
     _check(lib().ard_pattern_gen(ref, rows, cols, out["mask"].data_ptr(), out["keep"].data_ptr(),
@@ -214,18 +240,17 @@ def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
 
 
 def kept_count(pat: Optional[Pattern], units: int) -> int:
-    """Number of kept units of a ROW / LIST / NONE pattern over `units`."""
-    if pat is None or pat.kind == PAT_NONE:
-        return units
-    if pat.kind == PAT_LIST:
-        return pat.count
-    o = pat.b - 1
-    return -(-(units - o) // pat.dp) if units > o else 0
+    """Number of kept units of a ROW / LIST / NONE pattern over `units` (asked of the library)."""
+    _, r = _pref(pat)
+    n = lib().ard_kept_count(r, units)
+    if n < 0:
+        _check(n)
+    return n
 
 
 def pad8(n: int) -> int:
-    """Compact matrices store their kept-unit axes rounded up to a multiple of 8 (zero filled)."""
-    return (n + 7) & ~7
+    """Stored extent of a compact axis with n kept units (asked of the library)."""
+    return lib().ard_compact_dim(None, n)
 
 
 def pad_compact(t: torch.Tensor) -> torch.Tensor:
@@ -246,7 +271,7 @@ def compact_weight(W, pat_out=None, pat_in=None, out=None, stream=None):
     _dev(W)
     O, I = W.shape
     Ok, Ik = kept_count(pat_out, O), kept_count(pat_in, I)
-    Wc = torch.empty((pad8(Ok), pad8(Ik)), dtype=W.dtype, device=W.device) if out is None else out
+    Wc = _out((pad8(Ok), pad8(Ik)), W.dtype, W.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     _check(lib().ard_compact_weight(_dtype_code(W), I, O, W.data_ptr(), Wc.data_ptr(), ro, ri, _stream(stream)))
@@ -265,7 +290,7 @@ def drop_gemm_fwd(X, W, pat_out=None, pat_in=None, alpha=1.0, relu=False, flags=
     Oc = pad8(kept_count(pat_out, O)) if flags & OUT_COMPACT else O
     if flags & IN_COMPACT:
         _check_compact(X, kept_count(pat_in, I), "X")
-    Y = torch.empty((B, Oc), dtype=X.dtype, device=X.device) if out is None else out
+    Y = _out((B, Oc), X.dtype, X.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), X.device, ws)
@@ -285,7 +310,7 @@ def drop_gemm_bwd_data(dY, W, pat_out=None, pat_in=None, alpha=1.0, relu_src=Non
     Ic = pad8(kept_count(pat_in, I)) if flags & IN_COMPACT else I
     if flags & OUT_COMPACT:
         _check_compact(dY, kept_count(pat_out, O), "dY")
-    dX = torch.empty((B, Ic), dtype=dY.dtype, device=dY.device) if out is None else out
+    dX = _out((B, Ic), dY.dtype, dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
@@ -307,7 +332,7 @@ def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, 
     if flags & IN_COMPACT:
         _check_compact(X, kept_count(pat_in, I), "X")
     shape = (pad8(kept_count(pat_out, O)), pad8(kept_count(pat_in, I))) if flags & DW_COMPACT else (O, I)
-    dW = torch.empty(shape, dtype=dY.dtype, device=dY.device) if out is None else out
+    dW = _out(shape, dY.dtype, dY.device) if out is None else out
     co, ro = _pref(pat_out)
     ci, ri = _pref(pat_in)
     ws = _workspace(gemm_workspace_bytes(dt, B, I, O, pat_out, pat_in), dY.device, ws)
@@ -319,7 +344,7 @@ def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, 
 
 def relu_bwd(dY, Y, out=None, stream=None):
     _dev(dY), _dev(Y)
-    dX = torch.empty_like(dY) if out is None else out
+    dX = _out(dY.shape, dY.dtype, dY.device) if out is None else out
     _check(lib().ard_relu_bwd(_dtype_code(dY), dY.numel(), dY.data_ptr(), Y.data_ptr(), dX.data_ptr(), _stream(stream)))
     return dX
 
@@ -338,9 +363,9 @@ def lstm_fwd(x, W, pat=None, ws=None, stream=None):
     H = W.shape[0] // 4
     assert W.shape == (4 * H, I + H)
     dt = _dtype_code(x)
-    h = torch.empty((T, B, H), dtype=x.dtype, device=x.device)
-    c = torch.empty((T, B, H), dtype=torch.float32, device=x.device)
-    gates = torch.empty((T, B, 4 * H), dtype=torch.float32, device=x.device)
+    h = _out((T, B, H), x.dtype, x.device)
+    c = _out((T, B, H), torch.float32, x.device)
+    gates = _out((T, B, 4 * H), torch.float32, x.device)
     cp, r = _pref(pat)
     ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
     _check(lib().ard_lstm_fwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
@@ -355,8 +380,8 @@ def lstm_bwd(x, W, pat, h, c, gates, dh, ws=None, stream=None):
     T, B, I = x.shape
     H = W.shape[0] // 4
     dt = _dtype_code(x)
-    dx = torch.empty_like(x)
-    dW = torch.empty_like(W)
+    dx = _out(x.shape, x.dtype, x.device)
+    dW = _out(W.shape, W.dtype, W.device)
     cp, r = _pref(pat)
     ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
     _check(lib().ard_lstm_bwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
@@ -387,17 +412,20 @@ def conv_select(A, rate, Cout=1, ksize=(3, 3), stride=1, pad=1, ws=None, stream=
     """Sensitivity scores and channel selection: dict(mask, keep, count, score)."""
     _dev(A)
     N, Cc, H, W = A.shape
-    out = dict(mask=torch.empty(Cc, dtype=torch.uint8, device=A.device),
+    out = dict(mask=_out((Cc,), torch.uint8, A.device),
                keep=torch.full((Cc,), -1, dtype=torch.int32, device=A.device),
                count=torch.zeros(1, dtype=torch.int32, device=A.device),
-               score=torch.empty(Cc, dtype=torch.int64, device=A.device))
+               score=_out((Cc,), torch.int64, A.device))
     fmap_drop_conv(CONV_SELECT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, rate=rate, A=A, mask=out["mask"],
                    keep=out["keep"], count=out["count"], score=out["score"], ws=ws, stream=stream)
     return out
 
 
 def _out_hw(H, W, ksize, stride, pad):
-    return (H + 2 * pad - ksize[0]) // stride + 1, (W + 2 * pad - ksize[1]) // stride + 1
+    ho, wo = lib().ard_conv_out_size(H, ksize[0], stride, pad), lib().ard_conv_out_size(W, ksize[1], stride, pad)
+    if ho < 0 or wo < 0:
+        _check(min(ho, wo))
+    return ho, wo
 
 
 def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None):
@@ -405,7 +433,7 @@ def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None):
     N, Cc, H, W = A.shape
     Cout, _, kh, kw = Wt.shape
     Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
-    Y = torch.empty((N, Cout, Ho, Wo), dtype=A.dtype, device=A.device)
+    Y = _out((N, Cout, Ho, Wo), A.dtype, A.device)
     fmap_drop_conv(CONV_FWD, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
                    keep=keep, ws=ws, stream=stream)
     return Y
@@ -415,7 +443,7 @@ def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=
     _dev(dY), _dev(Wt)
     N = dY.shape[0]
     Cout, Cc, kh, kw = Wt.shape
-    dA = torch.empty((N, Cc, in_hw[0], in_hw[1]), dtype=dY.dtype, device=dY.device)
+    dA = _out((N, Cc, in_hw[0], in_hw[1]), dY.dtype, dY.device)
     fmap_drop_conv(CONV_BWD_DATA, dA.shape, _dtype_code(dY), Cout, (kh, kw), stride, pad, n_keep=n_keep, Wt=Wt, dY=dY,
                    out=dA, keep=keep, ws=ws, stream=stream)
     return dA
@@ -425,7 +453,7 @@ def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None,
     _dev(dY), _dev(A)
     N, Cc, H, W = A.shape
     Cout = dY.shape[1]
-    dW = torch.empty((Cout, Cc, ksize[0], ksize[1]), dtype=A.dtype, device=A.device)
+    dW = _out((Cout, Cc, ksize[0], ksize[1]), A.dtype, A.device)
     fmap_drop_conv(CONV_BWD_WEIGHT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, n_keep=n_keep, A=A, dY=dY,
                    out=dW, keep=keep, ws=ws, stream=stream)
     return dW

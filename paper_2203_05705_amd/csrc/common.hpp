@@ -12,6 +12,22 @@ namespace ard {
 // ---- error plumbing -------------------------------------------------------
 void set_error(const char* fmt, ...);
 int32_t fail(int32_t code, const char* fmt, ...);
+
+// ---- launches -------------------------------------------------------------
+// Every kernel launch of the library goes through ARD_LAUNCH.  In dry-run mode (ard_debug_set_dry_run)
+// nothing is enqueued and no HIP call is made: the entry points run their argument checks, their
+// dispatch and the host-side bounds proof of the LDS-direct loaders, and count the launches they
+// would have issued.  The mode exists so that host logic can be tested on a machine without a GPU.
+bool dry_run();
+void note_dry_launch(const char* kernel);
+hipError_t launch_status();  // hipGetLastError(), or hipSuccess in dry-run mode
+hipError_t raise_lds_limit(const void* kernel, int bytes);  // hipFuncSetAttribute(max dynamic LDS); no-op in dry-run mode
+#define ARD_LAUNCH_NAMED(name, kernel, ...)                      \
+  do {                                                           \
+    if (ard::dry_run()) ard::note_dry_launch(name);              \
+    else hipLaunchKernelGGL(kernel, __VA_ARGS__);                \
+  } while (0)
+#define ARD_LAUNCH(kernel, ...) ARD_LAUNCH_NAMED(#kernel, kernel, __VA_ARGS__)
 #define ARD_HIP_CHECK(expr)                                                        \
   do {                                                                             \
     hipError_t e__ = (expr);                                                       \
@@ -20,10 +36,17 @@ int32_t fail(int32_t code, const char* fmt, ...);
   } while (0)
 #define ARD_LAUNCH_CHECK(name)                                                     \
   do {                                                                             \
-    hipError_t e__ = hipGetLastError();                                            \
+    hipError_t e__ = ard::launch_status();                                           \
     if (e__ != hipSuccess)                                                         \
       return ard::fail(ARD_EHIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
   } while (0)
+
+// byte ranges [lo, hi) the loaders of one LDS-direct launch touch behind A and B (host-side proof)
+struct DirectBounds {
+  long a_lo, a_hi, b_lo, b_hi;
+};
+void note_direct_bounds(const DirectBounds& b, long a_bytes, long b_bytes);
+long extent_slack();  // elements the proofs pretend each operand is shorter by (ard_debug_set_extent_slack; 0 in normal use)
 
 // ---- index maps -------------------------------------------------------------
 // A logical (compact) index j in [0, n) maps to a physical index in [0, nphys):
@@ -61,7 +84,11 @@ static inline bool axis_chunk_contiguous(const Axis& a, int ce) {
   return false;
 }
 
-__device__ __forceinline__ int ax_phys(const Axis& a, int j) {
+__host__ __device__ static inline int imin(int a, int b) { return a < b ? a : b; }
+__host__ __device__ static inline int imax(int a, int b) { return a > b ? a : b; }
+
+// (host callers: every kind except LIST, whose entries live in device memory)
+__host__ __device__ __forceinline__ int ax_phys(const Axis& a, int j) {
   if (a.kind == AX_AFFINE) return a.off + j * a.step;
   if (a.kind == AX_LIST) return a.list[j];
   int q = j / a.bs;
@@ -96,9 +123,12 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // through the general engine, ARD_NO_SCATTER=1 disables the scattering epilogue (partial sums +
 // finishing pass instead), ARD_FORCE_TILE=64|128 pins the general engine's workgroup tile,
 // ARD_CLASS_TILE=1..5 pins the tile of the tile-pattern products (position in their tile list).
+// ARD_PROVE_BOUNDS=1 runs the exhaustive host-side bounds proof of the LDS-direct loaders before
+// every launch (the cheap envelope check always runs).
 struct DevKnobs {
   bool no_fast, no_scatter;
   int force_tile, class_tile;
+  bool prove_bounds;
 };
 const DevKnobs& dev_knobs();
 

@@ -704,24 +704,26 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     dim3 grid((unsigned)(N * ceil_div(Hs * Ws, 64)), (unsigned)(Cp / 64));
-    hipLaunchKernelGGL(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
+    ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
                        Wg, oh, ow, Cp, N, total, dst);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
-  hipLaunchKernelGGL(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
+  ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
                      ow, Cp, valid, total, dst);
   ARD_LAUNCH_CHECK("to_grid_kernel");
   return ARD_OK;
 }
 
 // Y[row][pixel] = sum_k Wp[row][k] * im2col[pixel][k] on the grid; NCHW output
-static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_t* grid_t, const ConvMap& cv, void* out,
-                              hipStream_t stream) {
+static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_t* grid_t, long grid_pixels,
+                              const ConvMap& cv, void* out, hipStream_t stream) {
   FastParams F{};
   F.A = Wp;
   F.B = grid_t;
+  F.a_elems = (long)rows * K;
+  F.b_elems = grid_pixels * cv.Cp;
   F.C = (uint16_t*)out;
   F.lda = K;
   F.ldb = cv.Cp;
@@ -767,11 +769,11 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     int32_t st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, 64, w.grid_a, stream);
     if (st) return st;
     const long total = (long)a.Cout * K;
-    hipLaunchKernelGGL(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
     ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout};
-    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, cv, out, stream);
+    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + 64, cv, out, stream);
   }
   if (a.mode == ARD_CONV_BWD_DATA) {
     // dA = dY (bordered by k-1-pad) convolved with the reversed filter, contraction over (tap, co)
@@ -780,16 +782,16 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     int32_t st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, 64, w.grid_y, stream);
     if (st) return st;
     const long total = (long)Ck * K;
-    hipLaunchKernelGGL(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
-    hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+    ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
     ARD_LAUNCH_CHECK("rank_from_keep_kernel");
-    hipLaunchKernelGGL(zero_dropped_planes_kernel, dim3(a.C, a.N), dim3(256), 0, stream, (uint16_t*)out, (const int*)w.rank,
+    ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, a.N), dim3(256), 0, stream, (uint16_t*)out, (const int*)w.rank,
                        a.C, a.H * a.W);
     ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
     ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck};
-    return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, cv, out, stream);
+    return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + 64, cv, out, stream);
   }
   // BWD_WEIGHT: contraction over the pixels of the input grid; dY sits on the same grid (top-left
   // aligned, zero elsewhere), the tap shifts the activation grid by (r*Wg + s) pixels.
@@ -799,7 +801,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   if (st) return st;
   st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, 0, 0, Cpy, 64, w.grid_y, stream);
   if (st) return st;
-  hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+  ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
   ARD_LAUNCH_CHECK("rank_from_keep_kernel");
   const int Kq = a.N * Hg * Wg, Nn = taps * Cpa;
   FastParams F{};
@@ -807,6 +809,8 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   F.B = w.grid_a;
   F.lda = Cpy;
   F.ldb = Cpa;
+  F.a_elems = ((long)a.N * Hg * Wg + 64) * Cpy;
+  F.b_elems = ((long)a.N * Hg * Wg + margin) * Cpa;
   F.am = axis_identity(Cpy);
   F.bn = axis_identity(Nn);
   F.k = axis_identity(Kq);
@@ -835,7 +839,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
            : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
   if (st) return st;
   const long total = (long)a.Cout * a.C * taps;
-  hipLaunchKernelGGL(wgrad_grid_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+  ARD_LAUNCH(wgrad_grid_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                      (const float*)w.gpart, (const int*)w.rank, splits, a.Cout, a.C, taps, Cpa, (uint16_t*)out);
   ARD_LAUNCH_CHECK("wgrad_grid_reduce_kernel");
   return ARD_OK;
@@ -865,18 +869,18 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (!A || !d_mask || !d_keep) return fail(ARD_EINVAL, "SELECT needs A, d_mask and d_keep");
     if ((long)a.N * a.H * a.W > (1L << 24)) return fail(ARD_ESHAPE, "SELECT needs N*H*W <= 2^24");
     unsigned long long* score = d_score ? (unsigned long long*)d_score : w.score;
-    hipLaunchKernelGGL(zero_u64_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, score, a.C);
+    ARD_LAUNCH(zero_u64_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, score, a.C);
     ARD_LAUNCH_CHECK("zero_u64_kernel");
     int ysplit = ceil_div(2048, a.C);
     if (ysplit > a.N) ysplit = a.N;
     if (ysplit < 1) ysplit = 1;
     const int n_per_block = ceil_div(a.N, ysplit);
     const int vec = ((a.H * a.W) % ce) == 0 && al16c(A);
-    hipLaunchKernelGGL(channel_score_kernel<T>, dim3(a.C, ceil_div(a.N, n_per_block)), dim3(256), 0, stream,
+    ARD_LAUNCH(channel_score_kernel<T>, dim3(a.C, ceil_div(a.N, n_per_block)), dim3(256), 0, stream,
                        (const T*)A, a.N, a.C, a.H * a.W, n_per_block, vec, score);
     ARD_LAUNCH_CHECK("channel_score_kernel");
     const int n_drop = (int)floor(rate * (double)a.C);
-    hipLaunchKernelGGL(channel_select_kernel, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)score, a.C,
+    ARD_LAUNCH(channel_select_kernel, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)score, a.C,
                        n_drop, d_mask, d_keep, d_count);
     ARD_LAUNCH_CHECK("channel_select_kernel");
     return ARD_OK;
@@ -896,7 +900,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (!A || !Wt) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.N * a.Cout * a.Ho * a.Wo, 0.0f, stream);
     const long total = (long)a.Cout * taps * Ck;
-    hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    ARD_LAUNCH(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const T*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, 0, (T*)w.wp);
     ARD_LAUNCH_CHECK("pack_weights_kernel");
     ConvGemmParams P{};
@@ -914,7 +918,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.C.alpha = 1.0f;
     P.tiles_n = ceil_div((int)P.Ncols, 128);
     long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
-    hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
+    ARD_LAUNCH((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
     ARD_LAUNCH_CHECK("conv_gemm_kernel");
     return ARD_OK;
   }
@@ -925,7 +929,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (a.kh - 1 - a.pad < 0 || a.kw - 1 - a.pad < 0) return fail(ARD_EUNSUPPORTED, "BWD_DATA needs pad <= k-1");
     if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.N * a.C * a.H * a.W, 0.0f, stream);
     const long total = (long)Ck * taps * a.Cout;
-    hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    ARD_LAUNCH(pack_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const T*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, 1, (T*)w.wp);
     ARD_LAUNCH_CHECK("pack_weights_kernel");
     ConvGemmParams P{};
@@ -944,7 +948,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.C.alpha = 1.0f;
     P.tiles_n = ceil_div((int)P.Ncols, 128);
     long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
-    hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
+    ARD_LAUNCH((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
     ARD_LAUNCH_CHECK("conv_gemm_kernel");
     return ARD_OK;
   }
@@ -952,7 +956,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
   if (a.mode == ARD_CONV_BWD_WEIGHT) {
     if (!dYin || !A) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
     if (Ck == 0) return fill_matrix(a.dtype, out, (long)a.Cout * a.C * taps, 0.0f, stream);
-    hipLaunchKernelGGL(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
+    ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
     ARD_LAUNCH_CHECK("rank_from_keep_kernel");
     ConvWgradParams P{};
     P.dY = dYin;
@@ -972,10 +976,10 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.k_per_split = (int)per;
     P.tiles_n = ceil_div(P.Nn, 128);
     dim3 grid((unsigned)(ceil_div(P.Cout, 128) * P.tiles_n), (unsigned)splits);
-    hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 128, 2, 2>), grid, dim3(256), 0, stream, P);
+    ARD_LAUNCH((conv_wgrad_kernel<T, 128, 128, 2, 2>), grid, dim3(256), 0, stream, P);
     ARD_LAUNCH_CHECK("conv_wgrad_kernel");
     const long total = (long)a.Cout * a.C * taps;
-    hipLaunchKernelGGL(conv_wgrad_reduce_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    ARD_LAUNCH(conv_wgrad_reduce_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const float*)w.part, (const int*)w.rank, splits, a.Cout, a.C, taps, P.Nn, (T*)out);
     ARD_LAUNCH_CHECK("conv_wgrad_reduce_kernel");
     return ARD_OK;
@@ -986,6 +990,12 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
 }  // namespace ard
 
 using namespace ard;
+
+extern "C" int32_t ard_conv_out_size(int32_t in, int32_t k, int32_t stride, int32_t pad) {
+  if (in <= 0 || k <= 0 || stride <= 0 || pad < 0) return fail(ARD_ESHAPE, "non-positive convolution size");
+  if (in + 2 * pad < k) return fail(ARD_ESHAPE, "kernel larger than the padded input");
+  return (in + 2 * pad - k) / stride + 1;
+}
 
 extern "C" size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad) {

@@ -74,6 +74,7 @@ struct FastParams {
   const uint16_t* B;
   uint16_t* C;
   int lda, ldb, ldc;
+  long a_elems, b_elems;  // elements the caller owns behind A / B: what the loaders may touch (host-side proof)
   Axis am, bn, k;  // plain mode: compact -> physical rows of A (M), rows of B (N), contraction
   ClassTab tab;
   int c_rows_mapped, c_cols_mapped;  // output rows / columns go through the M / N map (else identity)
@@ -106,7 +107,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 static __device__ uint4 g_zero_chunk[4];
 
 // physical start of the 64-wide contraction slab that begins at compact index ks (uniform)
-__device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
+__host__ __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
   if (k.kind == AX_AFFINE) return k.off + ks;
   const int q = ks / k.bs;
   if (k.kind == AX_BAFF) return (k.off + q * k.step) * k.bs + (ks - q * k.bs);
@@ -125,27 +126,28 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
   static_assert(NI >= 1, "tile too small for the workgroup");
   const char* base;
   uint32_t voff[NI];
-  __device__ static __forceinline__ int chunk_k(int lane, int wave, int j) {
+  __host__ __device__ static __forceinline__ int chunk_k(int lane, int wave, int j) {
     const int row = (wave * NI + j) * 8 + (lane >> 3);
     return ((lane & 7) ^ (row & 7) ^ ((row >> 3) & 7)) * 8;
   }
-  __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave) {
+  // (host-callable: the host-side bounds proof runs this very arithmetic for every lane)
+  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave) {
     base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int row = min(row0 + (wave * NI + j) * 8 + (lane >> 3), r.n - 1);
+      const int row = imin(row0 + (wave * NI + j) * 8 + (lane >> 3), r.n - 1);
       // (a block axis counts its last block in full even when the operand ends inside it)
       int prow = ax_phys(r, row);
-      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) prow = min(prow, r.nphys - 1);
+      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) prow = imin(prow, r.nphys - 1);
       voff[j] = (uint32_t)(prow * ld + chunk_k(lane, wave, j)) * 2u;
     }
   }
   // rows = output pixels of a convolution: base pixel of the patch in the bordered grid
-  __device__ __forceinline__ void init_pixels(const uint16_t* p, const ConvMap& cv, int row0, int lane, int wave) {
+  __host__ __device__ __forceinline__ void init_pixels(const uint16_t* p, const ConvMap& cv, int row0, int lane, int wave) {
     base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int row = min(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
+      const int row = imin(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
       const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
       const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
       voff[j] = (uint32_t)((n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j)) * 2u;
@@ -159,14 +161,19 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
   // last, partial step of a contraction: chunks beyond its end come from the zero chunk
+  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
+    const int k = chunk_k(lane, wave, j);
+    return k < krem && kslab + k + 8 <= kphys_end;
+  }
+  // byte offset from the operand's base of instruction j's chunk in the step whose slab starts at kslab
+  __host__ __device__ __forceinline__ long byte_offset(int j, int kslab) const { return (long)kslab * 2 + voff[j]; }
   __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
     asm volatile("; partial contraction step" ::: "memory");  // keeps this path out of the full step's code
     const char* sb = base + (long)kslab * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const char* src = sb + voff[j];
-      const int k = chunk_k(lane, wave, j);
-      if (!(k < krem && kslab + k + 8 <= kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
+      if (!tail_live(lane, wave, j, kslab, krem, kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -176,7 +183,7 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
 // ROWS*2 bytes apart; the XOR makes the four rows a transposing read touches land in different
 // banks (rows of 256+ bytes all start at the same bank, rows of 128 bytes alternate).
 template <int ROWS>
-__device__ __forceinline__ int mc_swz(int k) {
+__host__ __device__ __forceinline__ int mc_swz(int k) {
   return ROWS >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1);
 }
 
@@ -188,32 +195,32 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
   const char* base;
   int ld;
   uint32_t voff[NI];  // (contraction row within the step) * ld + column of this lane's chunk, in bytes
-  __device__ __forceinline__ int lane_chunk(int lane, int wave, int j) const {
+  __host__ __device__ __forceinline__ int lane_chunk(int lane, int wave, int j) const {
     const int kloc = KPI * (wave * NI + j) + lane / CPR;
     return (lane % CPR) ^ mc_swz<ROWS>(kloc);
   }
-  __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave) {
+  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave) {
     base = reinterpret_cast<const char*>(p);
     ld = ld_;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int kloc = KPI * (wave * NI + j) + lane / CPR;
-      const int col = min(row0 + lane_chunk(lane, wave, j) * 8, r.n - 8);  // runs beyond the axis: clamped
+      const int col = imin(row0 + lane_chunk(lane, wave, j) * 8, r.n - 8);  // runs beyond the axis: clamped
       // (a block axis counts its last block in full even when the operand ends inside it)
       int pcol = ax_phys(r, col);
-      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) pcol = max(min(pcol, (r.nphys - 8) & ~7), 0);
+      if (r.kind == AX_BLOCK || r.kind == AX_BAFF) pcol = imax(imin(pcol, (r.nphys - 8) & ~7), 0);
       voff[j] = (uint32_t)(kloc * ld + pcol) * 2u;
     }
   }
   // columns = (tap, channel) of the weight gradient: pixel offset of the tap plus the channel
-  __device__ __forceinline__ void init_tap_columns(const uint16_t* p, const ConvMap& cv, int ncols, int row0, int lane,
-                                                   int wave) {
+  __host__ __device__ __forceinline__ void init_tap_columns(const uint16_t* p, const ConvMap& cv, int ncols, int row0,
+                                                            int lane, int wave) {
     base = reinterpret_cast<const char*>(p);
     ld = cv.Cp;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int kloc = KPI * (wave * NI + j) + lane / CPR;
-      const int col = min(row0 + lane_chunk(lane, wave, j) * 8, ncols - 8);
+      const int col = imin(row0 + lane_chunk(lane, wave, j) * 8, ncols - 8);
       const int t = col / cv.Cp;
       voff[j] = (uint32_t)(kloc * ld + ((t / cv.kw) * cv.Wg + t % cv.kw) * cv.Cp + (col - t * cv.Cp)) * 2u;
     }
@@ -224,14 +231,18 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
     for (int j = 0; j < NI; ++j)
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
+  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
+    const int kloc = KPI * (wave * NI + j) + lane / CPR;
+    return kloc < krem && kslab + kloc < kphys_end;
+  }
+  __host__ __device__ __forceinline__ long byte_offset(int j, int kslab) const { return (long)kslab * ld * 2 + voff[j]; }
   __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
     asm volatile("; partial contraction step" ::: "memory");
     const char* sb = base + (long)kslab * ld * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const char* src = sb + voff[j];
-      const int kloc = KPI * (wave * NI + j) + lane / CPR;
-      if (!(kloc < krem && kslab + kloc < kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
+      if (!tail_live(lane, wave, j, kslab, krem, kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -374,6 +385,88 @@ __device__ __forceinline__ void direct_scatter_tile(const uint16_t* tile, int ld
     for (int r = P.M * sr + rsub; r < rm.nphys; r += RPP) write_row(r, -1);
 }
 
+// What one workgroup computes: its row / column / contraction maps (class-based launches build them
+// from the class tables), the first compact row and column of its tile and its share of the
+// contraction.  Shared by the kernel and by the host-side bounds proof.
+struct DirectWork {
+  Axis am, bn, kax;
+  int m0, n0, split;
+};
+template <int F_BM, int BN>
+__host__ __device__ __forceinline__ bool direct_assign(const FastParams& P, int block_id, DirectWork& w) {
+  // Workgroup ids go round-robin over the 8 XCDs.  XCD x = id % 8 takes, of every class, the
+  // contiguous share [x*n/8, (x+1)*n/8) of its n workgroups: the shares are compact rectangles
+  // (operand panels stay in that XCD's L2) and heavy and light classes are spread evenly.
+  const int xcd = block_id & 7;
+  int local = block_id >> 3;
+  Axis am = P.am, bn = P.bn, kax = P.k;
+  int m0 = 0, n0 = 0;
+  int split = 0;  // share of the contraction this workgroup takes
+  if (P.tab.ncls == 0) {
+    // work items = (split, tile), split-major: an XCD's contiguous share holds whole splits (or long
+    // runs of one), so the workgroups in flight on it read the same slab of the contraction
+    const int total = P.total_tiles * P.splits;
+    const int lo = (int)((long)xcd * total / 8), hi = (int)((long)(xcd + 1) * total / 8);
+    if (local >= hi - lo) return false;
+    int L = lo + local;
+    split = L / P.total_tiles;
+    L -= split * P.total_tiles;
+    // bands of group_m tile rows, walked column by column
+    const int band_sz = P.group_m * P.tiles_n;
+    const int band = L / band_sz, inb = L - band * band_sz;
+    const int rows_in_band = imin(P.group_m, P.tiles_m - band * P.group_m);
+    m0 = (band * P.group_m + inb % rows_in_band) * F_BM;
+    n0 = (inb / rows_in_band) * BN;
+  } else {
+    const ClassTab& t = P.tab;
+    int c = 0, l = -1;
+    for (; c < t.ncls; ++c) {
+      const int lo = (int)((long)xcd * t.nblk[c] / 8), hi = (int)((long)(xcd + 1) * t.nblk[c] / 8);
+      if (local < hi - lo) {
+        l = lo + local;
+        break;
+      }
+      local -= hi - lo;
+    }
+    if (l < 0) return false;
+    // bands of group_m row blocks, walked column by column (as in the plain case): an XCD's share
+    // of a class is about square, so its operand panels are reused out of that XCD's L2
+    const int nbc = t.nblk[c] / t.mblk[c];
+    const int band_sz = P.group_m * nbc;
+    const int band = l / band_sz, inb = l - band * band_sz;
+    const int rows_in_band = imin(P.group_m, t.mblk[c] - band * P.group_m);
+    const int mi = band * P.group_m + inb % rows_in_band, ni = inb / rows_in_band;
+    if (t.m_bs) {
+      const int g = F_BM / t.m_bs;
+      const int left = t.m_cnt[c] - mi * g;
+      am = axis_baff(t.m_off[c] + mi * g * t.m_step, t.m_step, t.m_bs, left < g ? left : g, t.m_phys);
+    } else {
+      m0 = mi * F_BM;
+    }
+    {
+      const int g = BN / t.n_bs;
+      const int left = t.n_cnt[c] - ni * g;
+      bn = axis_baff(t.n_off[c] + ni * g * t.n_step, t.n_step, t.n_bs, left < g ? left : g, t.n_phys);
+    }
+    if (t.k_bs) kax = axis_baff(t.k_off[c], t.k_step, t.k_bs, t.k_cnt[c], t.k_phys);
+  }
+  w.am = am, w.bn = bn, w.kax = kax;
+  w.m0 = m0, w.n0 = n0, w.split = split;
+  return true;
+}
+
+// Physical start of the contraction slab of absolute step s: `ks` along the A operand, `ksb` along B
+// (MODE 1: slab (tap, c0) of the im2col row = offset of the tap's pixel plus the channel).
+template <int MODE>
+__host__ __device__ __forceinline__ void direct_slab(const FastParams& P, const Axis& kax, int s, int& ks, int& ksb) {
+  ks = fast_kslab(kax, s * 64);
+  ksb = ks;
+  if constexpr (MODE == 1) {
+    const int t = ks / P.cv.Cp;
+    ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
+  }
+}
+
 // MODE 0: plain product.  MODE 1: convolution, B rows are output pixels gathered from the
 // bordered channels-last grid (contraction = (tap, channel)), output NCHW.  MODE 2: weight
 // gradient of the convolution, contraction over the grid's pixels, B columns = (tap, channel).
@@ -390,62 +483,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // Workgroup ids go round-robin over the 8 XCDs.  XCD x = id % 8 takes, of every class, the
-  // contiguous share [x*n/8, (x+1)*n/8) of its n workgroups: the shares are compact rectangles
-  // (operand panels stay in that XCD's L2) and heavy and light classes are spread evenly.
-  const int xcd = blockIdx.x & 7;
-  int local = blockIdx.x >> 3;
-  Axis am = P.am, bn = P.bn, kax = P.k;
-  int m0 = 0, n0 = 0;
-  int split = 0;  // share of the contraction this workgroup takes
-  if (P.tab.ncls == 0) {
-    // work items = (split, tile), split-major: an XCD's contiguous share holds whole splits (or long
-    // runs of one), so the workgroups in flight on it read the same slab of the contraction
-    const int total = P.total_tiles * P.splits;
-    const int lo = (int)((long)xcd * total / 8), hi = (int)((long)(xcd + 1) * total / 8);
-    if (local >= hi - lo) return;
-    int L = lo + local;
-    split = L / P.total_tiles;
-    L -= split * P.total_tiles;
-    // bands of group_m tile rows, walked column by column
-    const int band_sz = P.group_m * P.tiles_n;
-    const int band = L / band_sz, inb = L - band * band_sz;
-    const int rows_in_band = min(P.group_m, P.tiles_m - band * P.group_m);
-    m0 = (band * P.group_m + inb % rows_in_band) * F_BM;
-    n0 = (inb / rows_in_band) * BN;
-  } else {
-    const ClassTab& t = P.tab;
-    int c = 0, l = -1;
-    for (; c < t.ncls; ++c) {
-      const int lo = (int)((long)xcd * t.nblk[c] / 8), hi = (int)((long)(xcd + 1) * t.nblk[c] / 8);
-      if (local < hi - lo) {
-        l = lo + local;
-        break;
-      }
-      local -= hi - lo;
-    }
-    if (l < 0) return;
-    // bands of group_m row blocks, walked column by column (as in the plain case): an XCD's share
-    // of a class is about square, so its operand panels are reused out of that XCD's L2
-    const int nbc = t.nblk[c] / t.mblk[c];
-    const int band_sz = P.group_m * nbc;
-    const int band = l / band_sz, inb = l - band * band_sz;
-    const int rows_in_band = min(P.group_m, t.mblk[c] - band * P.group_m);
-    const int mi = band * P.group_m + inb % rows_in_band, ni = inb / rows_in_band;
-    if (t.m_bs) {
-      const int g = F_BM / t.m_bs;
-      const int left = t.m_cnt[c] - mi * g;
-      am = axis_baff(t.m_off[c] + mi * g * t.m_step, t.m_step, t.m_bs, left < g ? left : g, t.m_phys);
-    } else {
-      m0 = mi * F_BM;
-    }
-    {
-      const int g = BN / t.n_bs;
-      const int left = t.n_cnt[c] - ni * g;
-      bn = axis_baff(t.n_off[c] + ni * g * t.n_step, t.n_step, t.n_bs, left < g ? left : g, t.n_phys);
-    }
-    if (t.k_bs) kax = axis_baff(t.k_off[c], t.k_step, t.k_bs, t.k_cnt[c], t.k_phys);
-  }
+  DirectWork wk;
+  if (!direct_assign<F_BM, BN>(P, (int)blockIdx.x, wk)) return;
+  const Axis am = wk.am, bn = wk.bn, kax = wk.kax;
+  const int m0 = wk.m0, n0 = wk.n0, split = wk.split;
   const int Kn = kax.n;
 
   f32x16_t acc[TM][TN];
@@ -494,14 +535,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
     const int S = s_hi - s_lo;
     auto load_stage = [&](int it, int buf) {
       const int krem = Kn - (s_lo + it) * 64;
-      const int ks = fast_kslab(kax, (s_lo + it) * 64);
+      int ks, ksb;
+      direct_slab<MODE>(P, kax, s_lo + it, ks, ksb);
       const bool tail = krem < 64 || ks + 64 > kax.nphys;
-      int ksb = ks;
-      if constexpr (MODE == 1) {
-        // slab (tap, c0) of the im2col row: offset of the tap's pixel plus the channel
-        const int t = ks / P.cv.Cp;
-        ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
-      }
       if (__builtin_expect(tail, 0)) {
         la.issue_tail(lds + buf * OPA, ks, krem, kax.nphys, lane, wave);
         lb.issue_tail(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, lane, wave);
@@ -607,12 +643,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
       wg_barrier();
       issue(NB{}, I0{}, 0);
       mma(1);
-      const int ks = fast_kslab(kax, (s_lo + it + NST) * 64);
-      int ksb = ks;
-      if constexpr (MODE == 1) {
-        const int t = ks / P.cv.Cp;
-        ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
-      }
+      int ks, ksb;
+      direct_slab<MODE>(P, kax, s_lo + it + NST, ks, ksb);
       la.issue(lds + BUF * OPA, ks, wave);
       lb.issue(lds + NST * OPA + BUF * OPB, ksb, wave);
     };
@@ -973,6 +1005,153 @@ static inline int direct_plain_grid(int total_tiles) {
   return worst * 8;
 }
 
+// ---- host-side bounds proof of the LDS-direct loaders -------------------------------------------
+// A lane of these kernels forms its global address as base + uniform slab offset + per-lane offset
+// with no bounds test in the loop, so the host shows before every launch that no lane of any
+// workgroup can leave the operand (a_elems / b_elems elements behind A / B, stated by the caller).
+//  * direct_envelope (always, O(classes)): the extreme physical rows, columns and contraction
+//    indices the clamps in DirectLoader::init* and the tail rules allow, as inequalities.
+//  * direct_prove (dry-run mode and ARD_PROVE_BOUNDS=1, every workgroup x wave x lane x step): runs
+//    the kernel's own assignment and address arithmetic (direct_assign, DirectLoader::init*,
+//    direct_slab, tail_live are host-callable) and records the smallest and largest byte touched.
+static inline bool axis_rows_ok(const Axis& r, bool has_list) {
+  // rows of a KC operand after the clamp of init(): min(row, n-1), block axes also clamped to nphys-1
+  if (r.n < 1 || r.nphys < 1) return false;
+  if (r.kind == AX_AFFINE) return r.off >= 0 && r.step >= 0 && (long)r.off + (long)(r.n - 1) * r.step < r.nphys;
+  if (r.kind == AX_BAFF) return r.off >= 0 && r.step >= 0 && r.bs >= 1;
+  if (r.kind == AX_LIST) return has_list && r.n <= r.nphys;  // entries are the caller's contract
+  return false;
+}
+static inline bool axis_cols_ok(const Axis& r, int ld) {
+  // 8-column runs of an MC operand after the clamp of init(): min(col, n-8), block axes to nphys-8
+  if (r.n < 8 || r.nphys < 8 || r.nphys > ld) return false;
+  if (r.kind == AX_AFFINE) return r.step == 1 && r.off >= 0 && r.off + r.n <= r.nphys;
+  if (r.kind == AX_BAFF) return r.off >= 0 && r.step >= 0 && r.bs >= 8 && (r.bs % 8) == 0;
+  return false;
+}
+
+template <bool A_KC, bool B_KC, int BM, int BN, int MODE>
+static int32_t direct_envelope(const FastParams& F) {
+  if (F.a_elems <= 0 || F.b_elems <= 0) return fail(ARD_EINVAL, "bounds proof: operand extents not stated");
+  if (F.a_elems >= (1L << 31) || F.b_elems >= (1L << 31)) return fail(ARD_ESHAPE, "bounds proof: operand beyond 32-bit offsets");
+  if (F.lda < 8 || F.ldb < 8) return fail(ARD_ESHAPE, "bounds proof: leading dimension below one 16-byte run");
+  const ClassTab& t = F.tab;
+  const int ncls = t.ncls ? t.ncls : 1;
+  for (int c = 0; c < ncls; ++c) {
+    if (t.ncls && t.nblk[c] == 0) continue;
+    // the maps a workgroup of this class can get (direct_assign): whole progression of the class
+    Axis am = F.am, bn = F.bn, k = F.k;
+    if (t.ncls) {
+      if (t.m_bs) am = axis_baff(t.m_off[c], t.m_step, t.m_bs, t.m_cnt[c], t.m_phys);
+      bn = axis_baff(t.n_off[c], t.n_step, t.n_bs, t.n_cnt[c], t.n_phys);
+      if (t.k_bs) k = axis_baff(t.k_off[c], t.k_step, t.k_bs, t.k_cnt[c], t.k_phys);
+    }
+    if (k.n <= 0) continue;  // nothing is loaded
+    if (k.kind != AX_AFFINE && k.kind != AX_BAFF) return fail(ARD_EINVAL, "bounds proof: contraction map kind %d", k.kind);
+    if (k.kind == AX_AFFINE && (k.step != 1 || k.off < 0 || k.off + k.n > k.nphys))
+      return fail(ARD_ESHAPE, "bounds proof: contraction [%d, %d) outside its extent %d", k.off, k.off + k.n, k.nphys);
+    if (k.kind == AX_BAFF && (k.off < 0 || k.step < 0 || k.bs < 64 || (k.bs % 64)))
+      return fail(ARD_ESHAPE, "bounds proof: contraction blocks of %d", k.bs);
+    // every contraction index a live lane touches is < k.nphys (full steps need ks + 64 <= nphys, the
+    // lanes of a partial step test their own chunk against nphys)
+    const long kphys = k.nphys;
+    // A
+    if (A_KC) {
+      if (!axis_rows_ok(am, F.A != nullptr) || kphys > F.lda || (long)am.nphys * F.lda > F.a_elems)
+        return fail(ARD_ESHAPE, "bounds proof: A rows (kind %d, n %d, extent %d, ld %d, k %ld) leave %ld elements", am.kind, am.n,
+                    am.nphys, F.lda, kphys, F.a_elems);
+    } else {
+      if (!axis_cols_ok(am, F.lda) || kphys * F.lda > F.a_elems)
+        return fail(ARD_ESHAPE, "bounds proof: A columns (kind %d, n %d, extent %d, ld %d, k %ld) leave %ld elements", am.kind,
+                    am.n, am.nphys, F.lda, kphys, F.a_elems);
+    }
+    // B
+    if (MODE == 1) {
+      const ConvMap& cv = F.cv;
+      if (cv.npix < 1 || cv.Cp < 64 || (cv.Cp % 64) || cv.kw < 1 || kphys % cv.Cp) return fail(ARD_ESHAPE, "bounds proof: bad grid");
+      const int row = cv.npix - 1, n = row / cv.HoWo, rem = row - n * cv.HoWo;
+      const long base = (long)n * cv.HgWg + (long)(rem / cv.Wo) * cv.Wg + rem % cv.Wo;
+      const int tl = (int)(kphys / cv.Cp) - 1;  // last tap
+      const long last = base + (long)(tl / cv.kw) * cv.Wg + tl % cv.kw;
+      if ((last + 1) * cv.Cp > F.b_elems) return fail(ARD_ESHAPE, "bounds proof: patch rows leave the grid");
+    } else if (MODE == 2) {
+      const ConvMap& cv = F.cv;
+      if (F.N < 8 || cv.Cp < 64 || (cv.Cp % 64) || cv.kw < 1) return fail(ARD_ESHAPE, "bounds proof: bad grid");
+      const int tl = (F.N - 8) / cv.Cp;
+      const long shift = (long)(tl / cv.kw) * cv.Wg + tl % cv.kw;
+      if ((kphys - 1 + shift + 1) * cv.Cp > F.b_elems) return fail(ARD_ESHAPE, "bounds proof: shifted grid rows leave the grid");
+    } else if (B_KC) {
+      if (!axis_rows_ok(bn, F.B != nullptr) || kphys > F.ldb || (long)bn.nphys * F.ldb > F.b_elems)
+        return fail(ARD_ESHAPE, "bounds proof: B rows (kind %d, n %d, extent %d, ld %d, k %ld) leave %ld elements", bn.kind, bn.n,
+                    bn.nphys, F.ldb, kphys, F.b_elems);
+    } else {
+      if (!axis_cols_ok(bn, F.ldb) || kphys * F.ldb > F.b_elems)
+        return fail(ARD_ESHAPE, "bounds proof: B columns (kind %d, n %d, extent %d, ld %d, k %ld) leave %ld elements", bn.kind,
+                    bn.n, bn.nphys, F.ldb, kphys, F.b_elems);
+    }
+  }
+  return ARD_OK;
+}
+
+// A LIST axis cannot be read on the host: its two extreme readings (every row first / last) bound it.
+static inline Axis axis_list_surrogate(const Axis& r, bool last) {
+  return r.kind == AX_LIST ? Axis{nullptr, AX_AFFINE, last ? r.nphys - 1 : 0, 0, 1, r.n, r.nphys} : r;
+}
+
+template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
+static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) {
+  constexpr long NONE_LO = 0x7fffffffffffffffL;
+  out = DirectBounds{NONE_LO, -1, NONE_LO, -1};
+  using LA = DirectLoader<A_KC, BM, NW>;
+  using LB = DirectLoader<B_KC, BN, NW>;
+  for (int bid = 0; bid < grid_x; ++bid) {
+    DirectWork wk;
+    if (!direct_assign<BM, BN>(P, bid, wk)) continue;
+    const int Kn = wk.kax.n;
+    if (Kn <= 0) continue;
+    const int S_all = (Kn + 63) >> 6;
+    const int s_lo = (int)((long)wk.split * S_all / P.splits), s_hi = (int)((long)(wk.split + 1) * S_all / P.splits);
+    for (int pass = 0; pass < 2; ++pass) {  // (second pass only differs for LIST axes)
+      if (pass == 1 && wk.am.kind != AX_LIST && wk.bn.kind != AX_LIST) break;
+      const Axis am = axis_list_surrogate(wk.am, pass == 1), bn = axis_list_surrogate(wk.bn, pass == 1);
+      for (int wave = 0; wave < NW; ++wave)
+        for (int lane = 0; lane < 64; ++lane) {
+          LA la;
+          LB lb;
+          la.init(P.A, P.lda, am, wk.m0, lane, wave);
+          if constexpr (MODE == 1) lb.init_pixels(P.B, P.cv, wk.n0, lane, wave);
+          else if constexpr (MODE == 2) lb.init_tap_columns(P.B, P.cv, P.N, wk.n0, lane, wave);
+          else lb.init(P.B, P.ldb, bn, wk.n0, lane, wave);
+          for (int s = s_lo; s < s_hi; ++s) {
+            const int krem = Kn - s * 64;
+            int ks, ksb;
+            direct_slab<MODE>(P, wk.kax, s, ks, ksb);
+            const bool tail = krem < 64 || ks + 64 > wk.kax.nphys;
+            const int kend_b = MODE == 1 ? 0x7fffffff : wk.kax.nphys;
+            for (int j = 0; j < LA::NI; ++j) {
+              if (tail && !LA::tail_live(lane, wave, j, ks, krem, wk.kax.nphys)) continue;
+              const long o = la.byte_offset(j, ks);
+              out.a_lo = o < out.a_lo ? o : out.a_lo;
+              out.a_hi = o + 16 > out.a_hi ? o + 16 : out.a_hi;
+            }
+            for (int j = 0; j < LB::NI; ++j) {
+              if (tail && !LB::tail_live(lane, wave, j, ksb, krem, kend_b)) continue;
+              const long o = lb.byte_offset(j, ksb);
+              out.b_lo = o < out.b_lo ? o : out.b_lo;
+              out.b_hi = o + 16 > out.b_hi ? o + 16 : out.b_hi;
+            }
+          }
+        }
+    }
+  }
+  const long a_bytes = (P.a_elems - extent_slack()) * 2, b_bytes = (P.b_elems - extent_slack()) * 2;
+  if (out.a_hi >= 0 && (out.a_lo < 0 || out.a_hi > a_bytes))
+    return fail(ARD_ESHAPE, "bounds proof: A bytes [%ld, %ld) outside [0, %ld)", out.a_lo, out.a_hi, a_bytes);
+  if (out.b_hi >= 0 && (out.b_lo < 0 || out.b_hi > b_bytes))
+    return fail(ARD_ESHAPE, "bounds proof: B bytes [%ld, %ld) outside [0, %ld)", out.b_lo, out.b_hi, b_bytes);
+  return ARD_OK;
+}
+
 // Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
 // kernels above the 64 KiB default get their limit raised once.
 template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
@@ -983,12 +1162,19 @@ static int32_t launch_direct_kernel(const FastParams& F_in, int grid_x, hipStrea
   const size_t lds_bytes = (size_t)direct_stages(BM, BN) * (BM + BN) * LDS_ROW_U4 * sizeof(uint4);
   static thread_local bool raised = false;
   if (!raised && lds_bytes >= 65536) {
-    ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    raised = true;
+    ARD_HIP_CHECK(ard::raise_lds_limit((const void*)kernel, (int)lds_bytes));
+    raised = !dry_run();
   }
   // class-free launches: the (split, tile) items are dealt to the XCDs inside the kernel
   if (F.tab.ncls == 0) grid_x = direct_plain_grid(F.total_tiles * (F.splits < 1 ? 1 : F.splits));
-  hipLaunchKernelGGL(kernel, dim3((unsigned)grid_x), dim3(64 * NW), lds_bytes, stream, F);
+  // no lane may leave its operand: cheap envelope always, the exhaustive walk on request
+  if (int32_t st = direct_envelope<A_KC, B_KC, BM, BN, MODE>(F)) return st;
+  if (dry_run() || dev_knobs().prove_bounds) {
+    DirectBounds b;
+    if (int32_t st = direct_prove<A_KC, B_KC, BM, BN, NW, MODE>(F, grid_x, b)) return st;
+    note_direct_bounds(b, F.a_elems * 2, F.b_elems * 2);
+  }
+  ARD_LAUNCH_NAMED("gemm_direct_kernel", kernel, dim3((unsigned)grid_x), dim3(64 * NW), lds_bytes, stream, F);
   ARD_LAUNCH_CHECK("gemm_direct_kernel");
   return ARD_OK;
 }

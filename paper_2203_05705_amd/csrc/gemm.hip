@@ -18,11 +18,11 @@ static int32_t launch_one(K kernel, dim3 grid, dim3 block, size_t lds_bytes, hip
     bool seen = false;
     for (int i = 0; i < n_raised; ++i) seen = seen || raised[i] == (const void*)kernel;
     if (!seen) {
-      ARD_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-      if (n_raised < 64) raised[n_raised++] = (const void*)kernel;
+      ARD_HIP_CHECK(ard::raise_lds_limit((const void*)kernel, (int)lds_bytes));
+      if (n_raised < 64 && !dry_run()) raised[n_raised++] = (const void*)kernel;
     }
   }
-  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, P);
+  ARD_LAUNCH_NAMED("gemm_kernel", kernel, grid, block, lds_bytes, stream, P);
   ARD_LAUNCH_CHECK("gemm_kernel");
   return ARD_OK;
 }
@@ -100,10 +100,10 @@ int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, 
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
   if (dtype == ARD_BF16)
-    hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
+    ARD_LAUNCH(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
                        P.splits, P.M, P.N, C);
   else
-    hipLaunchKernelGGL(gemm_finish_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws, P.splits,
+    ARD_LAUNCH(gemm_finish_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws, P.splits,
                        P.M, P.N, C);
   ARD_LAUNCH_CHECK("gemm_finish_kernel");
   return ARD_OK;
@@ -291,6 +291,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   F.lda = (int)P.A.ld;
   F.ldb = (int)P.B.ld;
   F.ldc = (int)C.ld;
+  // what the caller's matrices hold: physical rows x leading dimension (a contraction-strided operand
+  // has one stored row per contraction index)
+  F.a_elems = (long)(a_kc ? P.A.r.nphys : k.nphys) * P.A.ld;
+  F.b_elems = (long)(b_kc ? P.B.r.nphys : k.nphys) * P.B.ld;
   F.am = ax_m;
   F.bn = ax_n;
   F.k = k;
@@ -331,12 +335,12 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     const int out_rows = C.fill ? C.rm.nphys : P.M;
     const int grid_rows = ceil_div(out_rows, 8) * 8;  // the pass deals rows to the XCDs in eighths
     dim3 grid((unsigned)ceil_div(out_cols / 8, 256), (unsigned)(grid_rows < 32768 ? grid_rows : 32768));
-    hipLaunchKernelGGL(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, (const float*)ws, splits, P.M, P.N, C);
+    ARD_LAUNCH(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, (const float*)ws, splits, P.M, P.N, C);
   }
   else
-    hipLaunchKernelGGL(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
+    ARD_LAUNCH(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
                        splits, P.M, P.N, C);
-  hipError_t e = hipGetLastError();
+  hipError_t e = ard::launch_status();
   if (e != hipSuccess) st = fail(ARD_EHIP, "launch of gemm_finish_kernel failed: %s", hipGetErrorString(e));
   return true;
 }
@@ -349,9 +353,9 @@ int32_t fill_matrix(int32_t dtype, void* p, long n, float beta, hipStream_t stre
   if (n <= 0 || beta == 1.0f) return ARD_OK;
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (dtype == ARD_BF16)
-    hipLaunchKernelGGL(scale_fill_kernel<uint16_t>, grid, block, 0, stream, (uint16_t*)p, n, beta);
+    ARD_LAUNCH(scale_fill_kernel<uint16_t>, grid, block, 0, stream, (uint16_t*)p, n, beta);
   else
-    hipLaunchKernelGGL(scale_fill_kernel<float>, grid, block, 0, stream, (float*)p, n, beta);
+    ARD_LAUNCH(scale_fill_kernel<float>, grid, block, 0, stream, (float*)p, n, beta);
   ARD_LAUNCH_CHECK("scale_fill_kernel");
   return ARD_OK;
 }
@@ -454,6 +458,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
     F.A = (const uint16_t*)Ap, F.lda = I, F.am = axis_identity(B);
     F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.a_elems = (long)B * I, F.b_elems = (long)O * I;
     F.C = (uint16_t*)Cp, F.ldc = O;
     F.c_cols_mapped = 1;
     F.M = B, F.N = O;
@@ -477,6 +482,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
     F.A = (const uint16_t*)Ap, F.lda = O, F.am = axis_identity(B);
     F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.a_elems = (long)B * O, F.b_elems = (long)O * I;
     F.C = (uint16_t*)Cp, F.ldc = I;
     F.c_cols_mapped = 1;
     F.M = B, F.N = I;
@@ -496,6 +502,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
     F.A = (const uint16_t*)Ap, F.lda = O;
     F.B = (const uint16_t*)Bp, F.ldb = I;
+    F.a_elems = (long)B * O, F.b_elems = (long)B * I;
     F.k = axis_identity(B);
     F.C = (uint16_t*)Cp, F.ldc = I;
     F.c_rows_mapped = F.c_cols_mapped = 1;
@@ -530,9 +537,9 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   F.relu = relu;
   F.total_tiles = total;
   if (op == 2) {
-    hipLaunchKernelGGL(zero_dropped_tiles_kernel, dim3((unsigned)(TR * TC)), dim3(256), 0, stream, (uint16_t*)Cp, I, O, I,
+    ARD_LAUNCH(zero_dropped_tiles_kernel, dim3((unsigned)(TR * TC)), dim3(256), 0, stream, (uint16_t*)Cp, I, O, I,
                        x, y, TC, dp, o);
-    hipError_t e = hipGetLastError();
+    hipError_t e = ard::launch_status();
     if (e != hipSuccess) {
       st = fail(ARD_EHIP, "launch of zero_dropped_tiles_kernel failed: %s", hipGetErrorString(e));
       return true;
@@ -576,10 +583,10 @@ static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, con
   if (pad8(ao.n) > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
   dim3 grid(ceil_div(pad8(ai.n), 256), pad8(ao.n)), block(256);
   if (dtype == ARD_BF16)
-    hipLaunchKernelGGL(compact_weight_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)W, (long)I, ao, ai,
+    ARD_LAUNCH(compact_weight_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)W, (long)I, ao, ai,
                        (uint16_t*)Wc);
   else
-    hipLaunchKernelGGL(compact_weight_kernel<float>, grid, block, 0, stream, (const float*)W, (long)I, ao, ai,
+    ARD_LAUNCH(compact_weight_kernel<float>, grid, block, 0, stream, (const float*)W, (long)I, ao, ai,
                        (float*)Wc);
   ARD_LAUNCH_CHECK("compact_weight_kernel");
   return ARD_OK;
@@ -597,7 +604,7 @@ static int32_t aligned_activation(int32_t dtype, const void* p, int rows, int co
   if (!ws || ws_off + need > ws_bytes) return ARD_OK;  // no room: the general kernel copes with the original
   uint16_t* dst = (uint16_t*)((char*)ws + ws_off);
   const long total = (long)rows * pad8(cols);
-  hipLaunchKernelGGL(pad_cols_kernel<uint16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+  ARD_LAUNCH(pad_cols_kernel<uint16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                      (const uint16_t*)p, rows, cols, dst);
   ARD_LAUNCH_CHECK("pad_cols_kernel");
   ws_off += need;
@@ -925,10 +932,10 @@ extern "C" int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const 
   if (!dY || !Y || !dX) return fail(ARD_EINVAL, "null tensor pointer");
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (dtype == ARD_BF16)
-    hipLaunchKernelGGL(relu_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)dY, (const uint16_t*)Y,
+    ARD_LAUNCH(relu_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)dY, (const uint16_t*)Y,
                        (uint16_t*)dX, (long)n);
   else if (dtype == ARD_F32)
-    hipLaunchKernelGGL(relu_bwd_kernel<float>, grid, block, 0, stream, (const float*)dY, (const float*)Y, (float*)dX,
+    ARD_LAUNCH(relu_bwd_kernel<float>, grid, block, 0, stream, (const float*)dY, (const float*)Y, (float*)dX,
                        (long)n);
   else
     return fail(ARD_EDTYPE, "unknown dtype %d", dtype);

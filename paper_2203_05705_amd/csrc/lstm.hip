@@ -242,14 +242,14 @@ static GemmParams plain_gemm(const void* A, long lda, const void* B, long ldb, v
 
 template <typename T>
 static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, hipStream_t stream) {
-  hipLaunchKernelGGL(lstm_setup_kernel, dim3(1), dim3(1024), 0, stream, a.ax, a.H, w.rank);
+  ARD_LAUNCH(lstm_setup_kernel, dim3(1), dim3(1024), 0, stream, a.ax, a.H, w.rank);
   ARD_LAUNCH_CHECK("lstm_setup_kernel");
   const int Hp = pad8(a.Hk);
   if (a.Hk > 0) {
-    hipLaunchKernelGGL(lstm_gather_w_kernel<T>, dim3(ceil_div(a.I, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
+    ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(a.I, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
                        (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, a.I, (T*)w.wxc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
-    hipLaunchKernelGGL(lstm_gather_w_kernel<T>, dim3(ceil_div(Hp, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
+    ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(Hp, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
                        (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 1, Hp, (T*)w.whc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
   }
@@ -287,7 +287,7 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
         if (st) return st;
       }
     }
-    hipLaunchKernelGGL(lstm_cell_fwd_kernel<T>, cgrid, dim3(256), 0, stream, (const float*)Gt, (const float*)w.part, splits,
+    ARD_LAUNCH(lstm_cell_fwd_kernel<T>, cgrid, dim3(256), 0, stream, (const float*)Gt, (const float*)w.part, splits,
                        (long)B * 4 * Hp, (const int*)w.rank,
                        t > 0 ? (const float*)(c + (long)(t - 1) * B * H) : (const float*)nullptr, B, H, Hk, Hp,
                        gates + (long)t * B * 4 * H, c + (long)t * B * H, (T*)h + (long)t * B * H, hc_t);
@@ -311,7 +311,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
   // compact copy of the stored hidden states: hc[T*B x Hp] = h[:, kept]
   for (long r0 = 0; r0 < (long)T_ * B; r0 += 65535) {
     const long rows = (long)T_ * B - r0 < 65535 ? (long)T_ * B - r0 : 65535;
-    hipLaunchKernelGGL(lstm_gather_h_kernel<T>, dim3(ceil_div(Hp, 256), (unsigned)rows), dim3(256), 0, stream,
+    ARD_LAUNCH(lstm_gather_h_kernel<T>, dim3(ceil_div(Hp, 256), (unsigned)rows), dim3(256), 0, stream,
                        (const T*)h + r0 * H, H, a.ax, Hp, (T*)w.hc + r0 * Hp);
     ARD_LAUNCH_CHECK("lstm_gather_h_kernel");
   }
@@ -321,7 +321,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
   int dh_splits = 0;
   for (int t = T_ - 1; t >= 0; --t) {
     T* dGt = dG + (long)t * B * 4 * Hp;
-    hipLaunchKernelGGL(lstm_cell_bwd_kernel<T>, cgrid, dim3(256), 0, stream, gates + (long)t * B * 4 * H,
+    ARD_LAUNCH(lstm_cell_bwd_kernel<T>, cgrid, dim3(256), 0, stream, gates + (long)t * B * 4 * H,
                        c + (long)t * B * H, t > 0 ? c + (long)(t - 1) * B * H : (const float*)nullptr,
                        (const T*)dh + (long)t * B * H, dh_src, dh_splits, (long)B * Hp, w.dc_next, (const int*)w.rank, B, H,
                        Hk, Hp, t == T_ - 1 ? 1 : 0, dGt);
@@ -360,7 +360,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     }
     if (st) return st;
   }
-  hipLaunchKernelGGL(lstm_scatter_dw_kernel<T>, dim3(ceil_div(I + H, 256), 4 * H), dim3(256), 0, stream, (const T*)w.dwx,
+  ARD_LAUNCH(lstm_scatter_dw_kernel<T>, dim3(ceil_div(I + H, 256), 4 * H), dim3(256), 0, stream, (const T*)w.dwx,
                      (const T*)w.dwh, (const int*)w.rank, H, I, Hp, (T*)dW);
   ARD_LAUNCH_CHECK("lstm_scatter_dw_kernel");
   return ARD_OK;

@@ -13,12 +13,47 @@ namespace ard {
 const DevKnobs& dev_knobs() {
   static const DevKnobs k = {getenv("ARD_NO_FAST") != nullptr, getenv("ARD_NO_SCATTER") != nullptr,
                              getenv("ARD_FORCE_TILE") ? atoi(getenv("ARD_FORCE_TILE")) : 0,
-                             getenv("ARD_CLASS_TILE") ? atoi(getenv("ARD_CLASS_TILE")) : 0};
+                             getenv("ARD_CLASS_TILE") ? atoi(getenv("ARD_CLASS_TILE")) : 0,
+                             getenv("ARD_PROVE_BOUNDS") != nullptr};
   return k;
 }
 
 
 static thread_local char g_err[512] = "";
+
+// ---- dry-run mode (see common.hpp) ----------------------------------------
+static int g_dry_run = 0;                       // process-wide switch
+static thread_local int g_dry_count = 0;        // launches skipped on this thread since the last reset
+static thread_local char g_dry_log[2048] = "";  // their kernel names, comma separated (truncated when full)
+bool dry_run() { return g_dry_run != 0; }
+void note_dry_launch(const char* kernel) {
+  ++g_dry_count;
+  // keep the template name without its argument list
+  size_t len = strlen(g_dry_log), n = 0;
+  while (*kernel == '(') ++kernel;
+  while (kernel[n] && kernel[n] != '<' && kernel[n] != '(' && kernel[n] != ')') ++n;
+  if (len + n + 2 < sizeof(g_dry_log)) {
+    if (len) g_dry_log[len++] = ',';
+    memcpy(g_dry_log + len, kernel, n);
+    g_dry_log[len + n] = 0;
+  }
+}
+// [a_lo, a_hi, a_bytes, b_lo, b_hi, b_bytes] of this thread's most recent exhaustive bounds proof, and
+// the number of proofs since the last query
+static thread_local long g_last_bounds[6] = {0, 0, 0, 0, 0, 0};
+static thread_local int g_n_proofs = 0;
+void note_direct_bounds(const DirectBounds& b, long a_bytes, long b_bytes) {
+  g_last_bounds[0] = b.a_lo, g_last_bounds[1] = b.a_hi, g_last_bounds[2] = a_bytes;
+  g_last_bounds[3] = b.b_lo, g_last_bounds[4] = b.b_hi, g_last_bounds[5] = b_bytes;
+  ++g_n_proofs;
+}
+static long g_extent_slack = 0;
+long extent_slack() { return g_extent_slack; }
+hipError_t launch_status() { return g_dry_run ? hipSuccess : hipGetLastError(); }
+hipError_t raise_lds_limit(const void* kernel, int bytes) {
+  if (g_dry_run) return hipSuccess;
+  return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -125,19 +160,19 @@ int32_t pattern_gen_launch(const ard_pattern* pat, int32_t rows, int32_t cols, u
                            hipStream_t stream) {
   const int o = pat->b - 1, dp = pat->dp;
   if (pat->kind == ARD_PAT_ROW) {
-    hipLaunchKernelGGL(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, rows, dp, o, 1, rows, 0, rows, d_mask,
+    ARD_LAUNCH(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, rows, dp, o, 1, rows, 0, rows, d_mask,
                        d_keep, d_count, (int*)nullptr);
     ARD_LAUNCH_CHECK("pattern_compact_kernel");
     return ARD_OK;
   }
   const int TR = ceil_div(rows, pat->tile_r), TC = ceil_div(cols, pat->tile_c);
   if (d_mask || d_keep || d_count || d_rowptr) {
-    hipLaunchKernelGGL(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, TR * TC, dp, o, TR, TC, 0, TC, d_mask,
+    ARD_LAUNCH(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, TR * TC, dp, o, TR, TC, 0, TC, d_mask,
                        d_keep, d_count, d_rowptr);
     ARD_LAUNCH_CHECK("pattern_compact_kernel");
   }
   if (d_colptr || d_csc_rows) {
-    hipLaunchKernelGGL(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, TR * TC, dp, o, TR, TC, 1, TR,
+    ARD_LAUNCH(pattern_compact_kernel, dim3(1), dim3(1024), 0, stream, TR * TC, dp, o, TR, TC, 1, TR,
                        (uint8_t*)nullptr, d_csc_rows, (int*)nullptr, d_colptr);
     ARD_LAUNCH_CHECK("pattern_compact_kernel");
   }
@@ -157,7 +192,55 @@ static const uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
 using namespace ard;
 
 extern "C" const char* ard_last_error(void) { return g_err; }
-extern "C" int32_t ard_version(void) { return 100; }
+extern "C" int32_t ard_version(void) { return 200; }
+
+extern "C" void ard_debug_set_dry_run(int32_t on) {
+  g_dry_run = on ? 1 : 0;
+  g_dry_count = 0;
+  g_dry_log[0] = 0;
+}
+extern "C" int32_t ard_debug_dry_launches(char* names, size_t cap) {
+  if (names && cap) {
+    strncpy(names, g_dry_log, cap - 1);
+    names[cap - 1] = 0;
+  }
+  const int n = g_dry_count;
+  g_dry_count = 0;
+  g_dry_log[0] = 0;
+  return n;
+}
+
+extern "C" void ard_debug_set_extent_slack(int64_t elems) { g_extent_slack = elems; }
+
+extern "C" int32_t ard_debug_last_bounds(int64_t* six) {
+  if (six)
+    for (int i = 0; i < 6; ++i) six[i] = g_last_bounds[i];
+  const int n = g_n_proofs;
+  g_n_proofs = 0;
+  return n;
+}
+
+extern "C" int32_t ard_kept_count(const ard_pattern* pat, int32_t units) {
+  if (units < 0) return fail(ARD_ESHAPE, "negative unit count");
+  if (pat && pat->kind == ARD_PAT_TILE) return fail(ARD_EINVAL, "ard_kept_count takes ROW, LIST or NONE patterns");
+  int32_t st = check_pattern(pat, units, "pattern");
+  if (st) return st;
+  return kept_count(pat, units);
+}
+extern "C" int32_t ard_compact_dim(const ard_pattern* pat, int32_t units) {
+  const int32_t n = ard_kept_count(pat, units);
+  return n < 0 ? n : pad8(n);
+}
+extern "C" int32_t ard_tile_grid(const ard_pattern* pat, int32_t rows, int32_t cols, int32_t* tile_rows,
+                                 int32_t* tile_cols) {
+  if (!pat || pat->kind != ARD_PAT_TILE) return fail(ARD_EINVAL, "ard_tile_grid needs a TILE pattern");
+  if (pat->tile_r <= 0 || pat->tile_c <= 0) return fail(ARD_EINVAL, "tile size must be positive");
+  if (rows <= 0 || cols <= 0) return fail(ARD_ESHAPE, "rows and cols must be positive (got %d, %d)", rows, cols);
+  if (!tile_rows || !tile_cols) return fail(ARD_EINVAL, "null output pointer");
+  *tile_rows = ceil_div(rows, pat->tile_r);
+  *tile_cols = ceil_div(cols, pat->tile_c);
+  return ARD_OK;
+}
 
 extern "C" int32_t ard_pattern_gen(const ard_pattern* pat, int32_t rows, int32_t cols, uint8_t* d_mask,
                                    int32_t* d_keep, int32_t* d_count, int32_t* d_rowptr, int32_t* d_colptr,

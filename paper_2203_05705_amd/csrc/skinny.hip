@@ -1,4 +1,4 @@
-// Layers with at most 16 output neurons (the classifier at the end of the MLP; Sec. III-B applies
+// Layers with at most 16 output neurons (the classifier at the end of the MLP; Section 3.1 applies
 // the row pattern to its INPUT neurons only, since output units are never dropped): bf16 kernels
 // without the tile machinery that take the kept-input map themselves (a dense W is copied into LDS
 // with 16-byte loads and read through the map there), so neither a gathered copy of W in memory
@@ -304,12 +304,11 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
     const size_t lds = 4096 + (w_c ? 0 : (size_t)O * (pad8(ai.off + (ai.n - 1) * ai.step + 1) + 8) * 2);
     static thread_local bool raised = false;
     if (!raised && lds > 65536) {
-      hipError_t e = hipFuncSetAttribute((const void*)skinny_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         4096 + 16 * (SK_MAX_COLS + 8) * 2);  // the most any qualifying layer asks for
+      hipError_t e = ard::raise_lds_limit((const void*)skinny_fwd_kernel, 4096 + 16 * (SK_MAX_COLS + 8) * 2);  // the most any qualifying layer asks for
       if (e != hipSuccess) return false;
-      raised = true;
+      raised = !dry_run();
     }
-    hipLaunchKernelGGL(skinny_fwd_kernel, dim3((unsigned)ceil_div(B, 16)), dim3(256), lds, stream, a);
+    ARD_LAUNCH(skinny_fwd_kernel, dim3((unsigned)ceil_div(B, 16)), dim3(256), lds, stream, a);
   } else if (op == 1) {
     if (!sk_aligned(out, ld_in) || (relu_src && !sk_aligned(relu_src, ld_in))) return false;
     if (!in_c && (I % 8)) return false;
@@ -322,12 +321,11 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
     const size_t lds = SK_BD_ROWS * 64 + (w_c ? 0 : (size_t)O * (pad8(I) + 16) * 2);
     static thread_local bool raised_bd = false;
     if (!raised_bd && lds > 65536) {
-      hipError_t e = hipFuncSetAttribute((const void*)skinny_bwd_data_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         SK_BD_ROWS * 64 + 16 * (SK_MAX_COLS + 16) * 2);
+      hipError_t e = ard::raise_lds_limit((const void*)skinny_bwd_data_kernel, SK_BD_ROWS * 64 + 16 * (SK_MAX_COLS + 16) * 2);
       if (e != hipSuccess) return false;
-      raised_bd = true;
+      raised_bd = !dry_run();
     }
-    hipLaunchKernelGGL(skinny_bwd_data_kernel, dim3((unsigned)ceil_div(pad8(ai.n), SK_BD_COLS), (unsigned)ceil_div(B, SK_BD_ROWS)),
+    ARD_LAUNCH(skinny_bwd_data_kernel, dim3((unsigned)ceil_div(pad8(ai.n), SK_BD_COLS), (unsigned)ceil_div(B, SK_BD_ROWS)),
                        dim3(256), lds, stream, a);
   } else {
     a.dy = (const uint16_t*)p0;
@@ -336,9 +334,9 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
     a.ld_act = ld_in;
     a.dw_compact = (flags & ARD_DW_COMPACT) != 0;
     a.ld_out = a.dw_compact ? pad8(ai.n) : I;
-    hipLaunchKernelGGL(skinny_bwd_weight_kernel, dim3((unsigned)ceil_div(pad8(ai.n), 16)), dim3(256), 0, stream, a);
+    ARD_LAUNCH(skinny_bwd_weight_kernel, dim3((unsigned)ceil_div(pad8(ai.n), 16)), dim3(256), 0, stream, a);
   }
-  hipError_t e = hipGetLastError();
+  hipError_t e = ard::launch_status();
   if (e != hipSuccess) *status = fail(ARD_EHIP, "launch of a skinny-layer kernel failed: %s", hipGetErrorString(e));
   return true;
 }

@@ -30,6 +30,83 @@ def test_library_exports_every_declared_symbol():
     assert ard.lib().ard_version() >= 100
 
 
+def _stationary_point(p, N, lam_p=1.0, lam_e=1e-3):
+    """What Section 3.3's loss fixes, without any descent: on the simplex the minimiser of
+    lam_p (d.p_u - p)^2 + lam_e sum d ln d has d_i proportional to exp(theta p_u[i]) with theta the root of the
+    increasing function r(theta) - p + theta lam_e / (2 lam_p), r = d.p_u.  Root by bisection."""
+    pu = (np.arange(1, N + 1) - 1.0) / np.arange(1, N + 1)
+
+    def dist(theta):
+        w = np.exp(theta * pu - np.max(theta * pu))
+        return w / w.sum()
+    lo, hi = -1e4, 1e4
+    for _ in range(300):
+        mid = 0.5 * (lo + hi)
+        if float(dist(mid) @ pu) - p + mid * lam_e / (2 * lam_p) > 0:
+            hi = mid
+        else:
+            lo = mid
+    return dist(0.5 * (lo + hi)), pu
+
+
+@pytest.mark.parametrize("N", [4, 8, 16])
+@pytest.mark.parametrize("p", [0.3, 0.5, 0.7])
+def test_search_k_reaches_the_stationary_point(p, N):
+    """The library's search pinned to the closed form directly (not to the oracle's descent)."""
+    k, cdf = ard.search_k(p, N)
+    ref, pu = _stationary_point(p, N)
+    k = np.array(k)
+    assert abs(k.sum() - 1) < 1e-12 and np.all(k > 0)
+    assert np.max(np.abs(k - ref)) < 2e-5, (k, ref)
+    assert abs(float(k @ pu) - float(ref @ pu)) < 1e-6          # the rate the search settles on
+    # fixed-point table: round(2^32 * running sum), non-decreasing, last entry exactly 2^32
+    run = np.cumsum(k)
+    assert cdf[-1] == 1 << 32 and all(cdf[i] <= cdf[i + 1] for i in range(N - 1))
+    assert all(abs(cdf[i] - run[i] * 2.0 ** 32) <= 1.0 for i in range(N - 1))
+    # a perturbed start (seed != 0) ends at the same point: the problem has one minimum
+    k2, _ = ard.search_k(p, N, seed=7)
+    assert np.max(np.abs(np.array(k2) - ref)) < 2e-5
+
+
+def test_size_helpers_follow_the_pattern_definition():
+    lib = ard.lib()
+    for units in (1, 7, 10, 64, 2048):
+        for dp in range(1, min(units, 9) + 1):
+            for b in range(1, dp + 1):
+                kept = sum(1 for i in range(1, units + 1) if (i - b) % dp == 0)     # Eq. (1), 1-based
+                assert ard.kept_count(ard.Pattern.row(dp, b), units) == kept
+                assert lib.ard_compact_dim(ctypes.byref(ard.Pattern.row(dp, b).c()), units) == -(-kept // 8) * 8
+    assert ard.kept_count(None, 33) == 33 and ard.pad8(33) == 40 and ard.pad8(0) == 0
+    with pytest.raises(ard.ArdError):
+        ard.kept_count(ard.Pattern.row(3, 4), 10)
+    tr, tc = ctypes.c_int32(), ctypes.c_int32()
+    t = ard.Pattern.tile(2, 1, 64, 48).c()
+    assert lib.ard_tile_grid(ctypes.byref(t), 130, 100, ctypes.byref(tr), ctypes.byref(tc)) == 0
+    assert (tr.value, tc.value) == (3, 3)
+    assert lib.ard_conv_out_size(28, 3, 1, 1) == 28 and lib.ard_conv_out_size(9, 3, 2, 1) == 5
+    assert lib.ard_conv_out_size(2, 5, 1, 0) == -2
+
+
+def test_unsupported_requests_are_refused_before_any_launch():
+    """Tile sizes that are not multiples of 32 and the strided data gradient of the convolution return
+    ARD_EUNSUPPORTED; nothing is launched (dry-run mode counts launches)."""
+    import dryrun as D
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        for tile in ((48, 64), (64, 40), (20, 20)):
+            rc = D.layer_calls(lib, heap, D.BF16, 256, 256, 256, (2, 1), None, 0, tile=tile)
+            assert rc == [-6, -6, -6], (tile, rc)
+            assert b"multiples of 32" in lib.ard_last_error()
+        for dt in (D.BF16, D.F32):
+            rc = D.conv_calls(lib, heap, dt, 2, 8, 12, 9, 9, 3, 2, 1, 4, modes=(2,))
+            assert rc == [-6] and b"stride 1" in lib.ard_last_error()
+        assert D.launches(lib)[0] == 0
+        # the neighbouring supported requests do launch
+        assert D.layer_calls(lib, heap, D.BF16, 256, 256, 256, (2, 1), None, 0, tile=(32, 64)) == [0, 0, 0]
+        assert D.conv_calls(lib, heap, D.BF16, 2, 8, 12, 9, 9, 3, 2, 1, 4, modes=(1, 3)) == [0, 0]
+        assert D.launches(lib)[0] > 0
+
+
 @pytest.mark.parametrize("p", [0.3, 0.5, 0.7])
 def test_search_k_matches_oracle(p):
     k, cdf = ard.search_k(p, 8)

@@ -127,65 +127,115 @@ def test_expanded_outputs_from_compact_inputs_large(I):
     torch.cuda.synchronize()
 
 
-def test_config2_mlp_chain_iterations():
-    """BASELINE config 2: MLP 784-2048-2048-10, batch 1024, bf16; patterns of iterations 0..4 from the
-    searched distribution (rate 0.5), every GEMM of the compact chain against the oracle chain."""
+class _Config2:
+    """BASELINE config 2 (MLP 784-2048-2048-10, batch 1024, bf16), loaded once per session."""
+    _inst = None
+
+    @classmethod
+    def get(cls):
+        if cls._inst is None:
+            wl = WL.mlp_chain(seed=2)
+            c = cls()
+            c.sizes, c.B = wl.params["sizes"], wl.params["B"]
+            c.X0v, c.dYLv = wl.values("X0"), wl.values("dY")
+            c.Wv = [wl.values(f"W{l}") for l in (1, 2, 3)]
+            c.X0, c.dYL = to_dev(wl.arrays["X0"], "bf16"), to_dev(wl.arrays["dY"], "bf16")
+            c.W = [to_dev(wl.arrays[f"W{l}"], "bf16") for l in (1, 2, 3)]
+            c.dYLc = ard.pad_compact(c.dYL)
+            cls._inst = c
+        return cls._inst
+
+
+def _check_config2_iteration(pats, what):
+    """Every product the benchmark's plan issues for the patterns `pats` = ((dp1,b1),(dp2,b2)), with the
+    benchmark's layout flags, each fed with the oracle's stored activations so that it is checked on its
+    own: L1.fwd, L2.compact_w, L2.fwd, L3.fwd, L3.bwd_weight, L3.bwd_data, L2.bwd_weight, L2.bwd_data,
+    L1.bwd_weight; plus the compact-W3 and unpadded-dY variants of the last layer."""
+    c = _Config2.get()
+    sizes, W = c.sizes, c.W
+    IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
+    masks = [P.row_mask(sizes[l + 1], *pats[l]) for l in range(2)]
+    keep = [P.keep_list(m) for m in masks]
+    ref = G.mlp_iteration(c.X0v, c.Wv, c.dYLv, masks, R.to_bf16_values)
+    p1, p2 = ard.Pattern.row(*pats[0]), ard.Pattern.row(*pats[1])
+    Y1o = compact_in(ref["Y"][0][:, keep[0]], "bf16")
+    Y2o = compact_in(ref["Y"][1][:, keep[1]], "bf16")
+    dY2o = compact_in(ref["dY"][1][:, keep[1]], "bf16")
+    dY1o = compact_in(ref["dY"][0][:, keep[0]], "bf16")
+    # forward
+    Y1 = ard.drop_gemm_fwd(c.X0, W[0], p1, None, relu=True, flags=OUT)
+    check_compact(Y1, ref["Y"][0][:, keep[0]], "bf16", what + " Y1")
+    gather2 = pats[0][0] != 1 or pats[1][0] != 1      # the benchmark's dense chain reads W2 itself
+    if gather2:
+        W2x, WC2 = ard.compact_weight(W[1], p2, p1), WC
+        Wc_ref = np.zeros((ard.pad8(len(keep[1])), ard.pad8(len(keep[0]))))
+        Wc_ref[:len(keep[1]), :len(keep[0])] = c.Wv[1][np.ix_(keep[1], keep[0])]
+        assert np.array_equal(to_host(W2x), Wc_ref), what + " W2 compact"
+    else:
+        W2x, WC2 = W[1], 0
+    Y2 = ard.drop_gemm_fwd(Y1o, W2x, p2, p1, relu=True, flags=IN | OUT | WC2, I=sizes[1], O=sizes[2])
+    check_compact(Y2, ref["Y"][1][:, keep[1]], "bf16", what + " Y2")
+    Y3 = ard.drop_gemm_fwd(Y2o, W[2], None, p2, flags=IN, I=sizes[2], O=sizes[3])
+    assert_parity(Y3, ref["Y"][2], "bf16", what=what + " Y3")
+    # backward
+    zw3 = np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape)
+    dW3 = ard.drop_gemm_bwd_weight(c.dYLc, Y2o, None, p2, flags=IN | OUT, I=sizes[2], O=sizes[3])
+    assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3")
+    dY2 = ard.drop_gemm_bwd_data(c.dYLc, W[2], None, p2, relu_src=Y2o, flags=IN | OUT, I=sizes[2], O=sizes[3])
+    check_compact(dY2, ref["dY"][1][:, keep[1]], "bf16", what + " dY2")
+    dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
+    assert_parity(dW2, ref["dW"][1], "bf16", zero_mask=(G.weight_mask_rows(masks[1], masks[0]) == 0), what=what + " dW2")
+    dY1 = ard.drop_gemm_bwd_data(dY2o, W2x, p2, p1, relu_src=Y1o, flags=IN | OUT | WC2, I=sizes[1], O=sizes[2])
+    check_compact(dY1, ref["dY"][0][:, keep[0]], "bf16", what + " dY1")
+    dW1 = ard.drop_gemm_bwd_weight(dY1o, c.X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
+    zw1 = np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape)
+    assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=zw1, what=what + " dW1")
+    # the benchmark's compact-gradient variant of the three weight gradients
+    DW = ard.DW_COMPACT
+    dW2c = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT | DW, I=sizes[1], O=sizes[2])
+    check_compact_dw(dW2c, ref["dW"][1], keep[1], keep[0], "bf16")
+    dW1c = ard.drop_gemm_bwd_weight(dY1o, c.X0, p1, None, flags=IN | OUT | DW, I=sizes[0], O=sizes[1])
+    check_compact_dw(dW1c, ref["dW"][0], keep[0], np.arange(sizes[0]), "bf16")
+    # other ways of issuing the last layer: W3 compacted, loss gradient not padded
+    W3c = ard.compact_weight(W[2], None, p2)
+    Y3c = ard.drop_gemm_fwd(Y2o, W3c, None, p2, flags=IN | WC, I=sizes[2], O=sizes[3])
+    assert_parity(Y3c, ref["Y"][2], "bf16", what=what + " Y3 (compact W3)")
+    dW3u = ard.drop_gemm_bwd_weight(c.dYL, Y2o, None, p2, flags=IN, I=sizes[2], O=sizes[3])
+    assert_parity(dW3u, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3 (unpadded dY)")
+    dY2u = ard.drop_gemm_bwd_data(c.dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
+    check_compact(dY2u, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (unpadded dY, compact W3)")
+    dY2c = ard.drop_gemm_bwd_data(c.dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
+    check_compact(dY2c, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (compact W3)")
+
+
+@pytest.mark.parametrize("rate", [0.3, 0.5, 0.7])
+def test_config2_mlp_chain_iterations(rate):
+    """BASELINE config 2 at its three rates: patterns of iterations 0..4 from the searched distribution
+    (Sections 3.3, 3.4), every product of the benchmark's plan against the oracle chain."""
     from oracle import sampler as S
     from oracle import search as K
-    wl = WL.mlp_chain(seed=2)
-    sizes, B = wl.params["sizes"], wl.params["B"]
-    X0v, dYLv = wl.values("X0"), wl.values("dY")
-    Wv = [wl.values(f"W{l}") for l in (1, 2, 3)]
-    X0, dYL = to_dev(wl.arrays["X0"], "bf16"), to_dev(wl.arrays["dY"], "bf16")
-    W = [to_dev(wl.arrays[f"W{l}"], "bf16") for l in (1, 2, 3)]
-    d, _ = K.search_k(0.5, 8)
+    d, _ = K.search_k(rate, 8)
     cdf = [int(c) for c in K.fixed_point_cdf(d)]
-    IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
     for it in range(5):
         pats = [S.sample_pattern(cdf, 2, it, layer) for layer in (1, 2)]
         assert pats == [ard.pattern_sample(cdf, 2, it, layer) for layer in (1, 2)]
-        print(f"iteration {it}: patterns {pats}", flush=True)
-        masks = [P.row_mask(sizes[l + 1], *pats[l]) for l in range(2)]
-        keep = [P.keep_list(m) for m in masks]
-        ref = G.mlp_iteration(X0v, Wv, dYLv, masks, R.to_bf16_values)
-        p1, p2 = ard.Pattern.row(*pats[0]), ard.Pattern.row(*pats[1])
-        # forward, fed with the oracle's stored activations so each product is checked on its own
-        Y1 = ard.drop_gemm_fwd(X0, W[0], p1, None, relu=True, flags=OUT)
-        check_compact(Y1, ref["Y"][0][:, keep[0]], "bf16", "Y1")
-        W2c = ard.compact_weight(W[1], p2, p1)
-        Y1o = compact_in(ref["Y"][0][:, keep[0]], "bf16")
-        Y2 = ard.drop_gemm_fwd(Y1o, W2c, p2, p1, relu=True, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
-        check_compact(Y2, ref["Y"][1][:, keep[1]], "bf16", "Y2")
-        W3c = ard.compact_weight(W[2], None, p2)
-        Y2o = compact_in(ref["Y"][1][:, keep[1]], "bf16")
-        Y3 = ard.drop_gemm_fwd(Y2o, W3c, None, p2, flags=IN | WC, I=sizes[2], O=sizes[3])
-        assert_parity(Y3, ref["Y"][2], "bf16", what="Y3")
-        # backward
-        dW3 = ard.drop_gemm_bwd_weight(dYL, Y2o, None, p2, flags=IN, I=sizes[2], O=sizes[3])
-        assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3")
-        dY2 = ard.drop_gemm_bwd_data(dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
-        check_compact(dY2, ref["dY"][1][:, keep[1]], "bf16", "dY2")
-        # the same two products fed with the loss gradient in the compact (padded) layout
-        dYLc = ard.pad_compact(dYL)
-        dW3c = ard.drop_gemm_bwd_weight(dYLc, Y2o, None, p2, flags=IN | OUT, I=sizes[2], O=sizes[3])
-        assert_parity(dW3c, ref["dW"][2], "bf16", zero_mask=np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape), what="dW3 (padded dY)")
-        dY2c = ard.drop_gemm_bwd_data(dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
-        check_compact(dY2c, ref["dY"][1][:, keep[1]], "bf16", "dY2 (padded dY)")
-        # the last layer as the benchmark issues it: W3 itself, read through the kept-input map
-        Y3d = ard.drop_gemm_fwd(Y2o, W[2], None, p2, flags=IN, I=sizes[2], O=sizes[3])
-        assert_parity(Y3d, ref["Y"][2], "bf16", what="Y3 (dense W3)")
-        dY2d = ard.drop_gemm_bwd_data(dYLc, W[2], None, p2, relu_src=Y2o, flags=IN | OUT, I=sizes[2], O=sizes[3])
-        check_compact(dY2d, ref["dY"][1][:, keep[1]], "bf16", "dY2 (dense W3)")
-        dY2o = compact_in(ref["dY"][1][:, keep[1]], "bf16")
-        dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
-        MW2 = G.weight_mask_rows(masks[1], masks[0])
-        assert_parity(dW2, ref["dW"][1], "bf16", zero_mask=(MW2 == 0), what="dW2")
-        dY1 = ard.drop_gemm_bwd_data(dY2o, W2c, p2, p1, relu_src=Y1o, flags=IN | OUT | WC, I=sizes[1], O=sizes[2])
-        check_compact(dY1, ref["dY"][0][:, keep[0]], "bf16", "dY1")
-        dY1o = compact_in(ref["dY"][0][:, keep[0]], "bf16")
-        dW1 = ard.drop_gemm_bwd_weight(dY1o, X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
-        assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape), what="dW1")
+        print(f"rate {rate} iteration {it}: patterns {pats}", flush=True)
+        _check_config2_iteration(pats, f"rate {rate} it {it}")
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dp1", range(1, 9))
+def test_config2_every_pattern_pair(dp1):
+    """All 64 (dp1, dp2) period pairs the distribution with N = 8 can draw, one seeded bias each: the
+    dispatch picks tile, split count and store path per (row step, column step, tile count), so every
+    pair is its own launch configuration at the benchmark's size."""
+    rng = np.random.default_rng(640 + dp1)
+    for dp2 in range(1, 9):
+        pats = [(dp1, int(rng.integers(1, dp1 + 1))), (dp2, int(rng.integers(1, dp2 + 1)))]
+        print(f"pair {pats}", flush=True)
+        _check_config2_iteration(pats, f"pair {pats}")
+    torch.cuda.synchronize()
+
 
 @pytest.mark.parametrize("B,O,I,po,pi", [(256, 2044, 1024, (8, 3), (3, 2)), (8192, 520, 512, (8, 1), (2, 1)),
                                           (1024, 2048, 784, (8, 8), None)])

@@ -33,7 +33,7 @@ def _tile_case(Xv, Wv, dYv, X, W, dY, x, y, dp, b, what):
     print(what, "max rel err", ["%.2e" % v for v in e], flush=True)
 
 
-@pytest.mark.parametrize("dp,b", [(2, 1), (3, 2), (4, 4), (1, 1), (5, 3)])
+@pytest.mark.parametrize("dp,b", [(2, 1), (3, 2), (4, 4), (1, 1), (5, 3), (6, 2), (7, 7), (8, 5)])
 def test_config3_tile_gemm_full_size(dp, b):
     """W 4096x4096 ~N(0,0.02), X 4096x4096 ~N(0,1), 64x64 tiles; every output element checked."""
     wl = WL.tile_gemm(seed=3)

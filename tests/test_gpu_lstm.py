@@ -8,7 +8,7 @@ from oracle import patterns as P
 from oracle import rounding as R
 from paper_2203_05705_amd import binding as ard
 from paper_2203_05705_amd import workloads as WL
-from util import assert_parity, from_vals, stored, to_dev
+from util import CEILING, assert_parity, from_vals, stored, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -23,15 +23,18 @@ def _check(dtype, x, W, dh, m, pat, xd, Wd, dhd, what):
     dx, dW = ard.lstm_bwd(xd, Wd, pat, h, c, gates, dhd)
     torch.cuda.synchronize()
     dropped = (m == 0)
-    errs = [assert_parity(h, fwd["h"], dtype, dropped[None, None, :], what + " h"),
-            assert_parity(c, fwd["c"], "bf16" if dtype == "bf16" else "f32", dropped[None, None, :], what + " c"),
+    # recurrent results pass through one bf16 store per step (h_t forward, the gate gradient backward):
+    # the single-product bounds do not apply, the stated acceptance limit does
+    lim = dict(tol=CEILING[dtype], etol=CEILING[dtype])
+    errs = [assert_parity(h, fwd["h"], dtype, dropped[None, None, :], what + " h", **lim),
+            assert_parity(c, fwd["c"], "bf16" if dtype == "bf16" else "f32", dropped[None, None, :], what + " c", **lim),
             # gate activations of dropped units carry no information (the oracle's are sigma(0), tanh(0));
             # the library reports zeros there: compare kept units, require exact zeros elsewhere
             assert_parity(gates, fwd["gates"] * np.tile(m, 4)[None, None, :], "bf16" if dtype == "bf16" else "f32",
-                          np.tile(dropped, 4)[None, None, :], what + " gates"),
-            assert_parity(dx, bwd["dx"], dtype, None, what + " dx")]
+                          np.tile(dropped, 4)[None, None, :], what + " gates", **lim),
+            assert_parity(dx, bwd["dx"], dtype, None, what + " dx", **lim)]
     MW = L.masked_weight(np.ones((4 * H, I + H)), m, I)
-    errs.append(assert_parity(dW, bwd["dW"], dtype, MW == 0, what + " dW"))
+    errs.append(assert_parity(dW, bwd["dW"], dtype, MW == 0, what + " dW", **lim))
     return errs
 
 

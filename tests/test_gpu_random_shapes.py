@@ -79,18 +79,23 @@ def test_random_layers(seed, dtype):
         assert not bits[len(ko):, :].any() and not bits[:, len(ki):].any(), "dW compact padding"
 
 
-@pytest.mark.parametrize("seed", range(8))
-def test_random_tile_patterns(seed):
-    """Tile patterns at sizes that take the class-grouped large-tile kernels: random tile shapes, periods
-    and extents that end inside their last tile row / column."""
-    from test_gpu_fast import _tile_case
-    rng = np.random.default_rng(2000 + seed)
+def draw_tile_case(rng):
     B = int(rng.integers(100, 330)) * 8 + (int(rng.integers(0, 8)) if rng.random() < 0.3 else 0)
     I = int(rng.integers(100, 520)) * 8
     O = int(rng.integers(100, 330)) * 8
     x, y = int(rng.choice([32, 64, 128, 256])), int(rng.choice([32, 64, 128, 256]))
     dp = int(rng.integers(1, 9))
     b = int(rng.integers(1, dp + 1))
+    return B, I, O, x, y, dp, b
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_tile_patterns(seed):
+    """Tile patterns at sizes that take the class-grouped large-tile kernels: random tile shapes, periods
+    and extents that end inside their last tile row / column."""
+    from test_gpu_fast import _tile_case
+    rng = np.random.default_rng(2000 + seed)
+    B, I, O, x, y, dp, b = draw_tile_case(rng)
     print(f"seed {seed}: B={B} I={I} O={O} tile {x}x{y} dp={dp} b={b}", flush=True)
     Xv, Wv, dYv = (stored(rng.standard_normal(s) * 0.5, "bf16") for s in ((B, I), (O, I), (B, O)))
     _tile_case(Xv, Wv, dYv, from_vals(Xv, "bf16"), from_vals(Wv, "bf16"), from_vals(dYv, "bf16"), x, y, dp, b, f"seed {seed}")

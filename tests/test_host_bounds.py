@@ -1,0 +1,110 @@
+"""Host-side bounds proof of the LDS-direct loaders, without a GPU.
+
+In dry-run mode every entry point runs its dispatch and, for each launch that fetches operands with
+unchecked per-lane addresses, walks every workgroup, wavefront, lane and contraction step with the
+kernel's own address arithmetic and checks the bytes touched against the operand's extent.  These
+tests push the benchmark configurations and the seeded random generators of the GPU tests through it."""
+import numpy as np
+import pytest
+
+import dryrun as D
+from paper_2203_05705_amd import binding as ard
+
+IN, OUT, WC, DW = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT, ard.DW_COMPACT
+
+
+def _ok(lib, rcs, what):
+    for rc in rcs:
+        assert rc == 0, f"{what}: status {rc}: {lib.ard_last_error().decode()}"
+
+
+def test_dry_run_launches_nothing_and_reports_kernels():
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 2048, (2, 1), (2, 2), IN | OUT), "layer")
+        n, names = D.launches(lib)
+        assert n >= 3 and "gemm_direct_kernel" in names
+        n_proofs, six = D.last_bounds(lib)
+        assert n_proofs >= 3
+        a_lo, a_hi, a_bytes, b_lo, b_hi, b_bytes = six
+        assert 0 <= a_lo < a_hi <= a_bytes and 0 <= b_lo < b_hi <= b_bytes
+
+
+def test_config2_all_pattern_pairs():
+    """MLP 784-2048-2048-10 at batch 1024: the nine calls of an iteration for all 64 (dp1, dp2)."""
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        proofs = 0
+        for dp1 in range(1, 9):
+            for dp2 in range(1, 9):
+                p1, p2 = (dp1, 1 + (dp1 * 3 + dp2) % dp1), (dp2, 1 + (dp1 + dp2 * 5) % dp2)
+                w = f"pair {p1} {p2}"
+                _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 784, 2048, p1, None, OUT, ops=(0, 2)), w + " L1")
+                _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 2048, p2, p1, IN | OUT), w + " L2")
+                _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 2048, p2, p1, IN | OUT | WC, ops=(0, 1)), w + " L2c")
+                _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 10, None, p2, IN | OUT), w + " L3")
+                proofs += D.last_bounds(lib)[0]
+        assert proofs >= 64 * 5
+
+
+@pytest.mark.parametrize("dp", range(1, 9))
+def test_config3_tile_patterns(dp):
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        for b in range(1, dp + 1):
+            _ok(lib, D.layer_calls(lib, heap, D.BF16, 4096, 4096, 4096, (dp, b), None, 0, tile=(64, 64)), f"dp={dp} b={b}")
+        assert D.last_bounds(lib)[0] >= 1
+
+
+def test_random_layers_and_tile_patterns():
+    from test_gpu_random_shapes import draw_case, draw_tile_case
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        for seed in range(40):
+            rng = np.random.default_rng(1000 + seed)
+            for _ in range(5):
+                B, I, O, po, pi = draw_case(rng)
+                for flags in (0, IN | OUT, IN | OUT | WC, IN, OUT, IN | OUT | DW):
+                    _ok(lib, D.layer_calls(lib, heap, D.BF16, B, I, O, po, pi, flags), f"layer {B} {I} {O} {po} {pi} {flags}")
+        for seed in range(60):
+            B, I, O, x, y, dp, b = draw_tile_case(np.random.default_rng(2000 + seed))
+            _ok(lib, D.layer_calls(lib, heap, D.BF16, B, I, O, (dp, b), None, 0, tile=(x, y)), f"tile {B} {I} {O} {x}x{y} {dp},{b}")
+        assert D.last_bounds(lib)[0] > 100
+
+
+def test_the_shape_that_faulted_once():
+    """W 2480 x 2760 with 256-row tiles: the last tile row holds 176 rows (block axes are clamped)."""
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 1965, 2760, 2480, (7, 1), None, 0, tile=(256, 64)), "256x64")
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 968, 1864, 3144, (3, 3), None, 0, tile=(256, 128)), "256x128")
+
+
+def test_lstm_and_conv_shapes():
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        for T, B, I, H, dp, b in [(64, 128, 1024, 1024, 2, 2), (64, 128, 1024, 1024, 1, 1), (64, 128, 1024, 1024, 3, 1),
+                                  (5, 6, 24, 32, 2, 1), (4, 3, 10, 37, 3, 3), (3, 70, 40, 64, 1, 1), (6, 33, 72, 136, 4, 2),
+                                  (3, 64, 128, 200, 3, 1), (35, 20, 1500, 1500, 2, 1)]:
+            _ok(lib, D.lstm_calls(lib, heap, D.BF16, T, B, I, H, (dp, b)), f"lstm {T} {B} {I} {H} {dp}")
+        n_lstm = D.last_bounds(lib)[0]
+        for N, Cc, Cout, H, W, k, pad, nk in [(128, 256, 256, 28, 28, 3, 1, 128), (128, 256, 256, 28, 28, 3, 1, 256),
+                                              (2, 8, 16, 7, 7, 3, 1, 4), (3, 12, 20, 9, 6, 3, 1, 8), (2, 16, 8, 8, 8, 1, 0, 12),
+                                              (2, 6, 10, 11, 10, 5, 2, 3), (5, 24, 130, 10, 12, 3, 1, 6), (7, 70, 300, 13, 17, 3, 1, 65)]:
+            _ok(lib, D.conv_calls(lib, heap, D.BF16, N, Cc, Cout, H, W, k, 1, pad, nk), f"conv {N} {Cc} {Cout} {H}x{W} k{k} keep {nk}")
+        assert n_lstm >= 10 and D.last_bounds(lib)[0] >= 8 * 3
+
+
+def test_a_shortened_operand_is_rejected():
+    """The proof is tight: with every operand pretended 8 elements shorter than it is, the dense 4096^3
+    product (whose loaders read their operands to the last byte) must be refused, and nothing launched."""
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 4096, 4096, 4096, None, None, 0, ops=(0,)), "dense")
+        n, six = D.last_bounds(lib)
+        assert n == 1 and six[1] == six[2] and six[4] == six[5]      # both operands read up to their end
+        D.launches(lib)
+        lib.ard_debug_set_extent_slack(8)
+        rc = D.layer_calls(lib, heap, D.BF16, 4096, 4096, 4096, None, None, 0, ops=(0,))
+        assert rc == [-2] and "bounds proof" in lib.ard_last_error().decode()
+        assert D.launches(lib)[0] == 0

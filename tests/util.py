@@ -1,10 +1,20 @@
-"""Helpers shared by the GPU parity tests: host<->device marshalling and the error metric."""
+"""Helpers shared by the GPU parity tests: host<->device marshalling, the error metrics and the
+guarded output allocator."""
 import numpy as np
 import torch
 
 from paper_2203_05705_amd import workloads as WL
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}      # max |gpu - oracle| / max |oracle| per output tensor
+# Tensor bound: max |gpu - oracle| / max |oracle| per output tensor.
+# fp32: accumulation-order differences only.  bf16 inputs with fp32 accumulation: the one rounding of the
+# result to bf16 is worth at most half an ulp = 2^-9 = 1.95e-3 relative; an fp32 sum that lands on the
+# other side of a rounding boundary than the oracle's fp64 sum costs a whole ulp, 2^-8 = 3.9e-3.  6e-3
+# leaves room for the fp32 accumulation itself and nothing else; CEILING is the stated acceptance limit,
+# used only where a result passes through several bf16 stores (recurrent LSTM state, BPTT).
+TOL = {"f32": 1e-5, "bf16": 6e-3}
+CEILING = {"f32": 1e-5, "bf16": 2e-2}
+# Elementwise bound: |gpu - oracle| <= ETOL * (|oracle| + rms(oracle)) at every position.
+ETOL = {"f32": 1e-5, "bf16": 6e-3}
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
@@ -40,20 +50,76 @@ def raw_bits(t: torch.Tensor) -> np.ndarray:
 
 
 def max_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
-    den = float(np.max(np.abs(ref)))
+    den = float(np.max(np.abs(ref))) if ref.size else 0.0
     if den == 0.0:
-        return float(np.max(np.abs(got)))
+        return float(np.max(np.abs(got))) if got.size else 0.0
     return float(np.max(np.abs(got - ref)) / den)
 
 
-def assert_parity(got_t: torch.Tensor, ref: np.ndarray, dtype: str, zero_mask=None, what=""):
-    """Float parity within TOL[dtype]; positions where zero_mask is True must hold exactly +0.0."""
+def max_elem_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over positions of |got - ref| / (|ref| + rms(ref)); 0 for an all-zero reference that is matched."""
+    if not ref.size:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+
+
+ERROR_LOG = []   # (what, dtype, tensor error, elementwise error) of every comparison of this session
+
+
+def assert_parity(got_t: torch.Tensor, ref: np.ndarray, dtype: str, zero_mask=None, what="", tol=None, etol=None):
+    """Float parity: the tensor bound TOL[dtype] and the elementwise bound ETOL[dtype] (both can be
+    overridden, never above CEILING); positions where zero_mask is True must hold exactly +0.0."""
     got = to_host(got_t)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
-    assert np.all(np.isfinite(got)), what
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values (unwritten output?)"
+    tol = TOL[dtype] if tol is None else tol
+    etol = ETOL[dtype] if etol is None else etol
+    assert tol <= CEILING[dtype] and etol <= CEILING[dtype], "tolerance above the stated acceptance limit"
     err = max_rel_err(got, ref)
-    assert err <= TOL[dtype], f"{what}: max rel err {err:.3e} > {TOL[dtype]}"
+    ERROR_LOG.append((what, dtype, err, max_elem_err(got, ref)))
+    assert err <= tol, f"{what}: max rel err {err:.3e} > {tol}"
+    eerr = max_elem_err(got, ref)
+    assert eerr <= etol, f"{what}: elementwise err {eerr:.3e} > {etol} (|d| <= etol*(|ref|+rms))"
     if zero_mask is not None:
         bits = raw_bits(got_t)
         assert np.all(bits[np.broadcast_to(zero_mask, bits.shape)] == 0), f"{what}: dropped entries are not +0.0"
     return err
+
+
+# ---- guarded outputs ---------------------------------------------------------------------------------
+GUARD = 4096  # bytes on either side of every output
+
+
+class GuardedAllocator:
+    """Output allocator for the binding: every output sits between two 4 KiB guard bands inside a buffer
+    filled with 0xFF bytes (NaN for bf16 and fp32, -1 for integers), so a kernel that writes outside its
+    output, or leaves part of it unwritten, is caught by check() / the finiteness test of assert_parity."""
+
+    def __init__(self):
+        self.live = []
+
+    def __call__(self, shape, dtype, device):
+        shape = tuple(int(s) for s in shape)
+        n = 1
+        for s in shape:
+            n *= s
+        nbytes = n * torch.empty((), dtype=dtype).element_size()
+        buf = torch.full((nbytes + 2 * GUARD,), 0xFF, dtype=torch.uint8, device=device)
+        self.live.append((buf, nbytes))
+        return buf[GUARD:GUARD + nbytes].view(dtype).view(shape)
+
+    def tensor(self, shape, dtype, device="cuda"):
+        return self(shape, dtype, device)
+
+    def check(self):
+        torch.cuda.synchronize()
+        bad = []
+        for buf, nbytes in self.live:
+            lo, hi = buf[:GUARD], buf[GUARD + nbytes:]
+            if not (bool((lo == 0xFF).all()) and bool((hi == 0xFF).all())):
+                bad.append(nbytes)
+        self.live.clear()
+        assert not bad, f"guard bands overwritten around outputs of {bad} bytes"
