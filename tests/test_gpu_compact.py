@@ -19,11 +19,11 @@ def compact_in(vals, dtype):
     return ard.pad_compact(from_vals(vals, dtype))
 
 
-def check_compact(t, ref, dtype, what):
+def check_compact(t, ref, dtype, what, rounded_ref=False):
     """Kept columns against the oracle; padding columns exactly +0.0."""
     n = ref.shape[1]
     assert t.shape == (ref.shape[0], ard.pad8(n)), (what, t.shape)
-    assert_parity(t[:, :n].contiguous(), ref, dtype, what=what)
+    assert_parity(t[:, :n].contiguous(), ref, dtype, what=what, rounded_ref=rounded_ref)
     assert not t[:, n:].contiguous().view(torch.int16 if dtype == "bf16" else torch.int32).any(), what + ": padding not +0.0"
 
 
@@ -75,11 +75,11 @@ def test_single_layer_compact_layouts(dtype, B, I, O, po, pi):
         ard.drop_gemm_bwd_weight(from_vals(dYv, dtype), Xc, pat_o, pat_i, flags=IN | ard.DW_COMPACT, I=I, O=O)
 
 
-def check_compact_dw(dWc, refdW, ko, ki, dtype):
+def check_compact_dw(dWc, refdW, ko, ki, dtype, rounded_ref=False):
     """Kept synapses against the oracle's full gradient; padding rows and columns exactly +0.0."""
     no, ni = len(ko), len(ki)
     assert dWc.shape == (ard.pad8(no), ard.pad8(ni))
-    assert_parity(dWc[:no, :ni].contiguous(), refdW[np.ix_(ko, ki)], dtype, what="dW compact")
+    assert_parity(dWc[:no, :ni].contiguous(), refdW[np.ix_(ko, ki)], dtype, what="dW compact", rounded_ref=rounded_ref)
     bits = dWc.view(torch.int16 if dtype == "bf16" else torch.int32)
     assert not bits[no:, :].any() and not bits[:, ni:].any(), "dW compact: padding not +0.0"
 
@@ -151,6 +151,11 @@ def _check_config2_iteration(pats, what):
     benchmark's layout flags, each fed with the oracle's stored activations so that it is checked on its
     own: L1.fwd, L2.compact_w, L2.fwd, L3.fwd, L3.bwd_weight, L3.bwd_data, L2.bwd_weight, L2.bwd_data,
     L1.bwd_weight; plus the compact-W3 and unpadded-dY variants of the last layer."""
+    # the oracle's chain rounds every stored tensor to bf16 where the kernels store it: rounded references
+    from functools import partial
+    check_compact_r = partial(check_compact, rounded_ref=True)
+    check_compact_dw_r = partial(check_compact_dw, rounded_ref=True)
+    assert_parity_r = partial(assert_parity, rounded_ref=True)
     c = _Config2.get()
     sizes, W = c.sizes, c.W
     IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
@@ -164,7 +169,7 @@ def _check_config2_iteration(pats, what):
     dY1o = compact_in(ref["dY"][0][:, keep[0]], "bf16")
     # forward
     Y1 = ard.drop_gemm_fwd(c.X0, W[0], p1, None, relu=True, flags=OUT)
-    check_compact(Y1, ref["Y"][0][:, keep[0]], "bf16", what + " Y1")
+    check_compact_r(Y1, ref["Y"][0][:, keep[0]], "bf16", what + " Y1")
     gather2 = pats[0][0] != 1 or pats[1][0] != 1      # the benchmark's dense chain reads W2 itself
     if gather2:
         W2x, WC2 = ard.compact_weight(W[1], p2, p1), WC
@@ -174,38 +179,38 @@ def _check_config2_iteration(pats, what):
     else:
         W2x, WC2 = W[1], 0
     Y2 = ard.drop_gemm_fwd(Y1o, W2x, p2, p1, relu=True, flags=IN | OUT | WC2, I=sizes[1], O=sizes[2])
-    check_compact(Y2, ref["Y"][1][:, keep[1]], "bf16", what + " Y2")
+    check_compact_r(Y2, ref["Y"][1][:, keep[1]], "bf16", what + " Y2")
     Y3 = ard.drop_gemm_fwd(Y2o, W[2], None, p2, flags=IN, I=sizes[2], O=sizes[3])
-    assert_parity(Y3, ref["Y"][2], "bf16", what=what + " Y3")
+    assert_parity_r(Y3, ref["Y"][2], "bf16", what=what + " Y3")
     # backward
     zw3 = np.broadcast_to((masks[1] == 0)[None, :], ref["dW"][2].shape)
     dW3 = ard.drop_gemm_bwd_weight(c.dYLc, Y2o, None, p2, flags=IN | OUT, I=sizes[2], O=sizes[3])
-    assert_parity(dW3, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3")
+    assert_parity_r(dW3, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3")
     dY2 = ard.drop_gemm_bwd_data(c.dYLc, W[2], None, p2, relu_src=Y2o, flags=IN | OUT, I=sizes[2], O=sizes[3])
-    check_compact(dY2, ref["dY"][1][:, keep[1]], "bf16", what + " dY2")
+    check_compact_r(dY2, ref["dY"][1][:, keep[1]], "bf16", what + " dY2")
     dW2 = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2])
-    assert_parity(dW2, ref["dW"][1], "bf16", zero_mask=(G.weight_mask_rows(masks[1], masks[0]) == 0), what=what + " dW2")
+    assert_parity_r(dW2, ref["dW"][1], "bf16", zero_mask=(G.weight_mask_rows(masks[1], masks[0]) == 0), what=what + " dW2")
     dY1 = ard.drop_gemm_bwd_data(dY2o, W2x, p2, p1, relu_src=Y1o, flags=IN | OUT | WC2, I=sizes[1], O=sizes[2])
-    check_compact(dY1, ref["dY"][0][:, keep[0]], "bf16", what + " dY1")
+    check_compact_r(dY1, ref["dY"][0][:, keep[0]], "bf16", what + " dY1")
     dW1 = ard.drop_gemm_bwd_weight(dY1o, c.X0, p1, None, flags=OUT, I=sizes[0], O=sizes[1])
     zw1 = np.broadcast_to((masks[0] == 0)[:, None], ref["dW"][0].shape)
-    assert_parity(dW1, ref["dW"][0], "bf16", zero_mask=zw1, what=what + " dW1")
+    assert_parity_r(dW1, ref["dW"][0], "bf16", zero_mask=zw1, what=what + " dW1")
     # the benchmark's compact-gradient variant of the three weight gradients
     DW = ard.DW_COMPACT
     dW2c = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT | DW, I=sizes[1], O=sizes[2])
-    check_compact_dw(dW2c, ref["dW"][1], keep[1], keep[0], "bf16")
+    check_compact_dw_r(dW2c, ref["dW"][1], keep[1], keep[0], "bf16")
     dW1c = ard.drop_gemm_bwd_weight(dY1o, c.X0, p1, None, flags=IN | OUT | DW, I=sizes[0], O=sizes[1])
-    check_compact_dw(dW1c, ref["dW"][0], keep[0], np.arange(sizes[0]), "bf16")
+    check_compact_dw_r(dW1c, ref["dW"][0], keep[0], np.arange(sizes[0]), "bf16")
     # other ways of issuing the last layer: W3 compacted, loss gradient not padded
     W3c = ard.compact_weight(W[2], None, p2)
     Y3c = ard.drop_gemm_fwd(Y2o, W3c, None, p2, flags=IN | WC, I=sizes[2], O=sizes[3])
-    assert_parity(Y3c, ref["Y"][2], "bf16", what=what + " Y3 (compact W3)")
+    assert_parity_r(Y3c, ref["Y"][2], "bf16", what=what + " Y3 (compact W3)")
     dW3u = ard.drop_gemm_bwd_weight(c.dYL, Y2o, None, p2, flags=IN, I=sizes[2], O=sizes[3])
-    assert_parity(dW3u, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3 (unpadded dY)")
+    assert_parity_r(dW3u, ref["dW"][2], "bf16", zero_mask=zw3, what=what + " dW3 (unpadded dY)")
     dY2u = ard.drop_gemm_bwd_data(c.dYL, W3c, None, p2, relu_src=Y2o, flags=IN | WC, I=sizes[2], O=sizes[3])
-    check_compact(dY2u, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (unpadded dY, compact W3)")
+    check_compact_r(dY2u, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (unpadded dY, compact W3)")
     dY2c = ard.drop_gemm_bwd_data(c.dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
-    check_compact(dY2c, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (compact W3)")
+    check_compact_r(dY2c, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (compact W3)")
 
 
 @pytest.mark.parametrize("rate", [0.3, 0.5, 0.7])

@@ -5,16 +5,21 @@ import torch
 
 from paper_2203_05705_amd import workloads as WL
 
-# Tensor bound: max |gpu - oracle| / max |oracle| per output tensor.
-# fp32: accumulation-order differences only.  bf16 inputs with fp32 accumulation: the one rounding of the
-# result to bf16 is worth at most half an ulp = 2^-9 = 1.95e-3 relative; an fp32 sum that lands on the
-# other side of a rounding boundary than the oracle's fp64 sum costs a whole ulp, 2^-8 = 3.9e-3.  6e-3
-# leaves room for the fp32 accumulation itself and nothing else; CEILING is the stated acceptance limit,
-# used only where a result passes through several bf16 stores (recurrent LSTM state, BPTT).
-TOL = {"f32": 1e-5, "bf16": 6e-3}
+# Tensor bound: max |gpu - oracle| / max |oracle| per output tensor; elementwise bound:
+# |gpu - oracle| <= ETOL * (|oracle| + rms(oracle)) at every position.
+# fp32: accumulation-order differences only.
+# bf16 inputs with fp32 accumulation: bf16 keeps 8 significant bits, so rounding the result once costs
+# at most half an ulp, |x| * 2^-8 = 3.9e-3 |x| at the bottom of a binade; the fp32 accumulation error d
+# adds |d| (round(x + d) is within half an ulp of x + d, so a sum that lands on the other side of a
+# rounding boundary does not cost more).  Against an UNROUNDED fp64 reference: 3.9e-3 |ref| + |d| -> 4.5e-3.
+# Where the oracle itself rounds its result at the storage point (chains of layers: rounded_ref=True) two
+# rounded values are compared and may sit one ulp apart: 2^-7 = 7.8e-3 |ref| + |d| -> 8.5e-3.
+# CEILING is the stated acceptance limit, used only where a result passes through several bf16 stores
+# (recurrent LSTM state, BPTT).
+TOL = {"f32": 1e-5, "bf16": 4.5e-3}
+ETOL = {"f32": 1e-5, "bf16": 4.5e-3}
+ROUNDED_REF_TOL = {"f32": 1e-5, "bf16": 8.5e-3}
 CEILING = {"f32": 1e-5, "bf16": 2e-2}
-# Elementwise bound: |gpu - oracle| <= ETOL * (|oracle| + rms(oracle)) at every position.
-ETOL = {"f32": 1e-5, "bf16": 6e-3}
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
@@ -69,14 +74,16 @@ def max_elem_err(got: np.ndarray, ref: np.ndarray) -> float:
 ERROR_LOG = []   # (what, dtype, tensor error, elementwise error) of every comparison of this session
 
 
-def assert_parity(got_t: torch.Tensor, ref: np.ndarray, dtype: str, zero_mask=None, what="", tol=None, etol=None):
-    """Float parity: the tensor bound TOL[dtype] and the elementwise bound ETOL[dtype] (both can be
-    overridden, never above CEILING); positions where zero_mask is True must hold exactly +0.0."""
+def assert_parity(got_t: torch.Tensor, ref: np.ndarray, dtype: str, zero_mask=None, what="", tol=None, etol=None,
+                  rounded_ref=False):
+    """Float parity: the tensor bound TOL[dtype] and the elementwise bound ETOL[dtype] (ROUNDED_REF_TOL when
+    the reference was itself rounded to the storage dtype; both can be overridden, never above CEILING);
+    positions where zero_mask is True must hold exactly +0.0."""
     got = to_host(got_t)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), f"{what}: non-finite values (unwritten output?)"
-    tol = TOL[dtype] if tol is None else tol
-    etol = ETOL[dtype] if etol is None else etol
+    tol = (ROUNDED_REF_TOL if rounded_ref else TOL)[dtype] if tol is None else tol
+    etol = (ROUNDED_REF_TOL if rounded_ref else ETOL)[dtype] if etol is None else etol
     assert tol <= CEILING[dtype] and etol <= CEILING[dtype], "tolerance above the stated acceptance limit"
     err = max_rel_err(got, ref)
     ERROR_LOG.append((what, dtype, err, max_elem_err(got, ref)))
