@@ -196,6 +196,25 @@ int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I, int32_t O,
                                  float alpha, float beta, int32_t flags,
                                  void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * The weight gradient for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as ard_drop_gemm_bwd_weight without `ws`: the partial sums
+ * of split contractions, padded operand copies and tile lists live in a scratch array that is part
+ * of the library (ard_static_scratch_bytes() bytes, 64 MiB, one copy per GPU, held until the
+ * process ends).  The call makes no allocation of any kind; the first call on a device looks the
+ * array's address up.  A layer for which ard_gemm_workspace_bytes() exceeds the array is refused
+ * with ARD_EWORKSPACE before anything is enqueued.  Nothing in the scratch has to start at zero
+ * (every partial sum is written before it is read), so nothing is cleared.  All calls on one GPU
+ * share that GPU's array: two calls that overlap in time on the same GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.
+ */
+size_t ard_static_scratch_bytes(void);
+int32_t ard_drop_gemm_bwd_weight_static(int32_t dtype, int32_t B, int32_t I, int32_t O,
+                                        const void* dY, const void* X, void* dW,
+                                        const ard_pattern* pat_out, const ard_pattern* pat_in,
+                                        float alpha, float beta, int32_t flags, void* stream);
+
 /* Standalone ReLU backward: dX = dY where Y > 0 else 0; n elements of `dtype`. */
 int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const void* Y, void* dX, void* stream);
 

@@ -83,6 +83,8 @@ _SIGS = {
     "ard_drop_gemm_fwd": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ard_drop_gemm_bwd_data": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ard_drop_gemm_bwd_weight": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ard_static_scratch_bytes": (C.c_size_t, []),
+    "ard_drop_gemm_bwd_weight_static": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_int32, C.c_void_p]),
     "ard_relu_bwd": (C.c_int32, [C.c_int32, C.c_int64] + [C.c_void_p] * 4),
     "ard_lstm_workspace_bytes": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
     "ard_lstm_fwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
@@ -340,6 +342,20 @@ def drop_gemm_bwd_weight(dY, X, pat_out=None, pat_in=None, alpha=1.0, beta=0.0, 
                                           float(alpha), float(beta), int(flags), ws.data_ptr(), ws.numel(),
                                           _stream(stream)))
     return dW
+
+
+def drop_gemm_bwd_weight_static(dY, X, pat_out, pat_in, out, alpha=1.0, beta=0.0, flags=0, stream=None, I=None, O=None):
+    """The weight gradient on the library's own scratch: the caller passes every tensor, output included,
+    and nothing is allocated here or in the library."""
+    _dev(dY), _dev(X), _dev(out)
+    O = dY.shape[1] if O is None else O
+    I = X.shape[1] if I is None else I
+    co, ro = _pref(pat_out)
+    ci, ri = _pref(pat_in)
+    _check(lib().ard_drop_gemm_bwd_weight_static(_dtype_code(dY), dY.shape[0], I, O, dY.data_ptr(), X.data_ptr(),
+                                                 out.data_ptr(), ro, ri, float(alpha), float(beta), int(flags),
+                                                 _stream(stream)))
+    return out
 
 
 def relu_bwd(dY, Y, out=None, stream=None):

@@ -3,6 +3,8 @@
 // MFMA engine.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "engine.hpp"
 #include "fast.hpp"
 #include "pattern.hpp"
@@ -915,6 +917,61 @@ extern "C" int32_t ard_drop_gemm_bwd_weight(int32_t dtype, int32_t B, int32_t I,
   if (P.M == 0 || P.N == 0) return dw_compact ? ARD_OK : fill_matrix(dtype, dW, (long)O * I, beta, stream);
   return run_gemm(dtype, false, false, P, 0, 0, stream, a.tile ? nullptr : (char*)ws + ws_used,
                   a.tile || ws_bytes < ws_used ? 0 : ws_bytes - ws_used);
+}
+
+// ---- weight gradient for callers that cannot allocate ------------------------------------------
+//
+// The library's own scratch: one array per GPU, part of the loaded code object, alive until the
+// process ends.  Host code never uses the array's name as an address: the device address is looked
+// up once per device (with that device current) and kept.
+namespace ard {
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static int32_t static_scratch(void** out) {
+  constexpr int kMaxDev = 64;
+  static void* ptr_of_device[kMaxDev] = {};
+  static std::mutex mu;
+  if (dry_run()) {
+    *out = (void*)(uintptr_t)0x7E0000000000ULL;  // never dereferenced
+    return ARD_OK;
+  }
+  int dev = -1;
+  ARD_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDev) return fail(ARD_EHIP, "device ordinal %d outside 0..%d", dev, kMaxDev - 1);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    ARD_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return fail(ARD_EHIP, "scratch symbol resolved to %p", p);
+    ptr_of_device[dev] = p;
+  }
+  *out = ptr_of_device[dev];
+  return ARD_OK;
+}
+}  // namespace ard
+
+extern "C" size_t ard_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int32_t ard_drop_gemm_bwd_weight_static(int32_t dtype, int32_t B, int32_t I, int32_t O, const void* dY,
+                                                   const void* X, void* dW, const ard_pattern* pat_out,
+                                                   const ard_pattern* pat_in, float alpha, float beta, int32_t flags,
+                                                   void* stream) {
+  // same argument checks as the workspace variant, before the size test (clear errors first)
+  LayerArgs a{dtype, B, I, O, pat_out, pat_in, false, 0, 0};
+  int32_t st = check_layer(a, dY, X, dW);
+  if (st) return st;
+  const size_t need = ard_gemm_workspace_bytes(dtype, B, I, O, pat_out, pat_in);
+  if (need > kStaticScratchBytes)
+    return fail(ARD_EWORKSPACE,
+                "ard_drop_gemm_bwd_weight_static: this layer asks for %zu bytes of scratch (ard_gemm_workspace_bytes), the "
+                "library's static scratch holds %zu; use ard_drop_gemm_bwd_weight with a workspace",
+                need, kStaticScratchBytes);
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st) return st;
+  return ard_drop_gemm_bwd_weight(dtype, B, I, O, dY, X, dW, pat_out, pat_in, alpha, beta, flags, ws, kStaticScratchBytes,
+                                  stream);
 }
 
 namespace ard {

@@ -107,6 +107,26 @@ def test_unsupported_requests_are_refused_before_any_launch():
         assert D.launches(lib)[0] > 0
 
 
+def test_static_scratch_entry_point_checks_sizes_on_the_host():
+    """The variant for callers that cannot allocate refuses, before any launch, layers whose scratch
+    need exceeds the library's static array, and accepts (dry run) those that fit."""
+    import dryrun as D
+    with D.dry_run() as lib:
+        cap = lib.ard_static_scratch_bytes()
+        assert cap == 64 << 20
+        fake = 0x7F0000100000
+        assert lib.ard_gemm_workspace_bytes(ard.BF16, 1024, 4096, 4096, None, None) > cap
+        rc = lib.ard_drop_gemm_bwd_weight_static(ard.BF16, 1024, 4096, 4096, fake, fake, fake, None, None, 1.0, 0.0, 0, None)
+        assert rc == -4 and b"static scratch" in lib.ard_last_error()
+        assert D.launches(lib)[0] == 0
+        p = ard.Pattern.row(2, 1).c()
+        assert lib.ard_gemm_workspace_bytes(ard.BF16, 1024, 2048, 2048, ctypes.byref(p), ctypes.byref(p)) <= cap
+        rc = lib.ard_drop_gemm_bwd_weight_static(ard.BF16, 1024, 2048, 2048, fake, fake, fake, ctypes.byref(p), ctypes.byref(p),
+                                                 1.0, 0.0, 0, None)
+        assert rc == 0 and D.launches(lib)[0] >= 1
+        assert lib.ard_drop_gemm_bwd_weight_static(ard.BF16, 0, 8, 8, fake, fake, fake, None, None, 1.0, 0.0, 0, None) == -2
+
+
 @pytest.mark.parametrize("p", [0.3, 0.5, 0.7])
 def test_search_k_matches_oracle(p):
     k, cdf = ard.search_k(p, 8)
