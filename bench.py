@@ -30,13 +30,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_PEAK_BF16 = 2500.0  # TFLOP/s, dense bf16 on MI355X
+HBM_PEAK = 8000.0        # GB/s
 SIZES = (784, 2048, 2048, 10)
 BATCH = 1024
 N_PATTERNS = 8           # dp_max of the searched distribution
 SEED = 2
-# HBM bytes per launch of the dominant call's GEMM kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of `bench.py --exec eager` (summaries under profiles/); None until measured
-TRAFFIC_BYTES = {"L2.bwd_weight": 16677504}   # 11366 KiB fetched + 4921 KiB written per launch
+REPEATS = 5              # the block of `steps` timed iterations is repeated; median and min are reported
+# HBM bytes per launch (fetched + written) of the kernels the roofline records describe.  A counter run
+# cannot happen inside this program: the figures come from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
+# runs of `bench.py --only-call NAME` (scaled by what the same counters read for a plain copy); the
+# summaries, with their commands, are the files named here.  None: not measured.
+TRAFFIC = {
+    "L2.bwd_weight": (16677504, "profiles/hbm_traffic_L2_bwd_weight.txt"),
+    "C3.fwd.dp2": (None, None),
+    "C5.fwd": (None, None),
+}
 
 
 def parse():
@@ -78,8 +86,9 @@ class MlpChain:
         self.Y = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2, 3)]
         self.dYh = [torch.empty((B, SIZES[l]), dtype=dt, device="cuda") for l in (1, 2)]   # gradient at hidden outputs
         # room for the full [O x I] gradient and for the compact one, whose axes are padded to multiples of 8
-        self.dW = [torch.empty(((w.shape[0] + 7) & ~7, (w.shape[1] + 7) & ~7), dtype=dt, device="cuda") for w in self.W]
-        self.Wc = [torch.empty(((w.shape[0] + 7) & ~7, (w.shape[1] + 7) & ~7), dtype=dt, device="cuda")
+        p8 = ard.pad8
+        self.dW = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda") for w in self.W]
+        self.Wc = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda")
                    for w in self.W[1:]]   # kept blocks of W2, W3 (axes padded to multiples of 8)
         self.ws = [torch.empty(1 << 24, dtype=torch.uint8, device="cuda") for _ in range(2)]  # one per lane
         self.main = torch.cuda.Stream()
@@ -105,8 +114,8 @@ class MlpChain:
         compact_dw, as the gradient of the kept synapses only (a reported variant, not the headline)."""
         lib, B = self.lib, BATCH
         p1, p2 = self._pat(*pats[0]), self._pat(*pats[1])
-        k1 = -(-(SIZES[1] - (pats[0][1] - 1)) // pats[0][0])
-        k2 = -(-(SIZES[2] - (pats[1][1] - 1)) // pats[1][0])
+        k1 = self.ard.kept_count(self.ard.Pattern.row(*pats[0]), SIZES[1])
+        k2 = self.ard.kept_count(self.ard.Pattern.row(*pats[1]), SIZES[2])
         X0, (W1, W2, W3), (Y1, Y2, Y3), (dY1, dY2), (dW1, dW2, dW3) = self.X0, self.W, self.Y, self.dYh, self.dW
         W2c, W3c = self.Wc
         dYL = self.dYLc
@@ -147,6 +156,21 @@ class MlpChain:
 
     def calls(self, plan):
         return [s for s in plan if s[0] == "call"]
+
+    def algorithmic_bytes(self, plan, name):
+        """Bytes the named call of this plan has to move at least: its kept (compact) operands once and its
+        result once -- a weight gradient written in full counts the whole [O x I] matrix, zeros included."""
+        for s in self.calls(plan):
+            if s[4] != name:
+                continue
+            _, B, I, O = s[3][:4]
+            po, pi = s[3][7], s[3][8]
+            k_of = lambda ref, units: units if ref is None else self.ard.kept_count(self.ard.Pattern.row(ref._obj.dp, ref._obj.b), units)
+            Ok, Ik = k_of(po, O), k_of(pi, I)
+            if name.endswith("bwd_weight"):
+                return 2.0 * (B * Ok + B * Ik + O * I)
+            return 2.0 * (B * Ik + Ok * Ik + B * Ok)
+        return 0.0
 
     def run(self, plan, lanes=2):
         """Issue one iteration.  lanes=1: everything on the main stream, waits are no-ops."""
@@ -216,24 +240,39 @@ def spin_up(torch, seconds=0.3):
         torch.cuda.synchronize()
 
 
+def _blocks(torch, step, n_steps, warmup, first_index=0):
+    """Warm up, then time REPEATS blocks of exactly `n_steps` steps, each bracketed by a device
+    synchronisation.  Returns the list of block times in seconds."""
+    for it in range(warmup):
+        step(first_index + it)
+    out = []
+    for r in range(REPEATS):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(n_steps):
+            step(first_index + warmup + it)
+        torch.cuda.synchronize()
+        out.append(time.perf_counter() - t0)
+    return out
+
+
+def _stat(blocks, n_steps):
+    b = sorted(blocks)
+    return dict(median=b[len(b) // 2] / n_steps, min=b[0] / n_steps, max=b[-1] / n_steps)
+
+
 def time_steps(torch, chain, plans, steps, warmup, mode):
-    """Warm up, then time exactly `steps` iterations (plans are used round-robin).  Returns seconds."""
+    """Times the iteration (plans are used round-robin; every repeat runs the same `steps` plans).
+    Returns per-step seconds: dict(median, min, max)."""
     n = len(plans)
     used = sorted({(warmup + it) % n for it in range(steps)} | {it % n for it in range(warmup)})
     with torch.cuda.stream(chain.main):
         if mode == "graph":
             graphs = {i: chain.capture(plans[i]) for i in used}   # capture costs are set-up, not step time
-            step = lambda i: graphs[i].replay()
+            step = lambda i: graphs[i % n].replay()
         else:
-            step = lambda i: chain.run(plans[i], lanes=1)
-        for it in range(warmup):
-            step(it % n)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for it in range(steps):
-            step((warmup + it) % n)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+            step = lambda i: chain.run(plans[i % n], lanes=1)
+        return _stat(_blocks(torch, step, steps, warmup), steps)
 
 
 def time_torch_dense(torch, chain, steps, warmup, mode):
@@ -244,17 +283,10 @@ def time_torch_dense(torch, chain, steps, warmup, mode):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=chain.main):
                 keep = chain.torch_dense_step(chain.side)  # noqa: F841  (outputs live in the graph's pool)
-            step = g.replay
+            step = lambda i: g.replay()
         else:
-            step = chain.torch_dense_step
-        for _ in range(warmup):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+            step = lambda i: chain.torch_dense_step()
+        return _stat(_blocks(torch, step, steps, warmup), steps)
 
 
 def per_call_times(torch, chain, plans, reps=3, only=None):
@@ -310,91 +342,158 @@ def cpu_baseline(wl, cdf, budget_s):
                 seconds=dt)
 
 
-def extra_workloads(ard, torch):
-    """Configs 3 (tile pattern, 4096^3 bf16, dp sweep and rate mixtures), 5 (convolution), 4 (LSTM), 1 and the
-    HBM-bound passes: per-call times and speedups.  Short by design."""
-    out = {}
-    n = 4096
-    g = torch.Generator(device="cuda").manual_seed(3)
-    X = torch.randn((n, n), generator=g, device="cuda").to(torch.bfloat16)
-    W = (0.02 * torch.randn((n, n), generator=g, device="cuda")).to(torch.bfloat16)
-    dY = torch.randn((n, n), generator=g, device="cuda").to(torch.bfloat16)
-    outb = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
-    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+def roofline_record(name, kernel, kept_flops, algo_bytes, launch_us, launches):
+    """Both floors of one launch -- matrix cores (kept FLOPs / 2.5 PFLOP/s) and HBM (algorithmic bytes /
+    8 TB/s) -- the binding one decides `bound`; `frac` is that floor over the measured launch time."""
+    mfma_us = kept_flops / (MFMA_PEAK_BF16 * 1e12) * 1e6
+    hbm_us = algo_bytes / (HBM_PEAK * 1e9) * 1e6
+    traffic, src = TRAFFIC.get(name, (None, None))
+    if hbm_us > mfma_us:
+        rec = dict(bound="hbm", achieved=algo_bytes / launch_us / 1e3, peak=HBM_PEAK, unit="GB/s", frac=hbm_us / launch_us)
+    else:
+        rec = dict(bound="mfma", achieved=kept_flops / launch_us / 1e6, peak=MFMA_PEAK_BF16, unit="TFLOP/s", frac=mfma_us / launch_us)
+    rec.update(kernel=kernel, call=name, avg_launch_us=launch_us, launches_timed=launches, kept_flops_per_launch=kept_flops,
+               algorithmic_bytes_per_launch=algo_bytes, floors_us=dict(mfma=mfma_us, hbm=hbm_us),
+               frac_of_mfma_peak=mfma_us / launch_us, frac_of_hbm_peak=hbm_us / launch_us,
+               traffic=traffic, traffic_source=src,
+               traffic_over_algorithmic=(traffic / algo_bytes if traffic else None))
+    return rec
 
-    def t_us(fn, reps=20, warm=5):
-        for _ in range(warm):
-            fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e3
-    vendor = dict(fwd=t_us(lambda: torch.matmul(X, W.t(), out=outb)), bwd_data=t_us(lambda: torch.matmul(dY, W, out=outb)),
-                  bwd_weight=t_us(lambda: torch.matmul(dY.t(), X, out=outb)))
-    res = {"vendor_dense_us": vendor}
+
+def event_us(torch, fn, reps=20, warm=5, blocks=REPEATS, flush=None):
+    """HIP-event time of fn() on the current stream, in microseconds: median and min over `blocks` blocks of
+    `reps` back-to-back calls.  flush: a large tensor rewritten before every call (cache-cold figure; the
+    rewrite sits outside the event bracket, so reps is 1 per bracket then)."""
+    for _ in range(warm):
+        fn()
+    out = []
+    for _ in range(blocks):
+        if flush is None:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / reps * 1e3)
+        else:
+            tot = 0.0
+            for _ in range(reps):
+                flush.add_(1)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                torch.cuda.synchronize()
+                tot += e0.elapsed_time(e1)
+            out.append(tot / reps * 1e3)
+    out.sort()
+    return dict(median=out[len(out) // 2], min=out[0])
+
+
+class TileGemm:
+    """Config 3: 4096^3 bf16, 64 x 64 weight tiles dropped per the tile pattern (seeded host inputs)."""
+
+    def __init__(self, ard, torch):
+        from paper_2203_05705_amd import workloads as WL
+        wl = WL.tile_gemm(seed=3)
+        self.ard, self.torch = ard, torch
+        self.n = wl.params["B"]
+        self.X, self.W, self.dY = (ard.to_device(wl.arrays[k]) for k in ("X", "W", "dY"))
+        self.out = torch.empty((self.n, self.n), dtype=torch.bfloat16, device="cuda")
+        self.ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+
+    def kept_tiles(self, dp, b):
+        t = (self.n // 64) ** 2
+        return -(-(t - (b - 1)) // dp)
+
+    def ops(self, dp, b):
+        ard = self.ard
+        pat = ard.Pattern.tile(dp, b, 64, 64)
+        return (("fwd", lambda: ard.drop_gemm_fwd(self.X, self.W, pat, out=self.out, ws=self.ws)),
+                ("bwd_data", lambda: ard.drop_gemm_bwd_data(self.dY, self.W, pat, out=self.out, ws=self.ws)),
+                ("bwd_weight", lambda: ard.drop_gemm_bwd_weight(self.dY, self.X, pat, out=self.out, ws=self.ws)))
+
+
+def extra_tile_gemm(ard, torch, rooflines):
+    tg = TileGemm(ard, torch)
+    n, X, W, dY, outb = tg.n, tg.X, tg.W, tg.dY, tg.out
     ops = ("fwd", "bwd_data", "bwd_weight")
+    vendor = dict(fwd=event_us(torch, lambda: torch.matmul(X, W.t(), out=outb)),
+                  bwd_data=event_us(torch, lambda: torch.matmul(dY, W, out=outb)),
+                  bwd_weight=event_us(torch, lambda: torch.matmul(dY.t(), X, out=outb)))
+    res = {"vendor_dense_us": {k: round(v["median"], 1) for k, v in vendor.items()}}
     for dp in range(1, N_PATTERNS + 1):
-        pat = ard.Pattern.tile(dp, 1, 64, 64)
-        pat = ard.Pattern.tile(dp, 1, 64, 64, lists=ard.pattern_gen(pat, n, n))
-        kept = int(pat.lists["count"].item())
-        flops = 2.0 * n * 64 * 64 * kept
+        flops = 2.0 * n * 64 * 64 * tg.kept_tiles(dp, 1)
         row = {}
-        for name, fn in (("fwd", lambda: ard.drop_gemm_fwd(X, W, pat, out=outb, ws=ws)),
-                         ("bwd_data", lambda: ard.drop_gemm_bwd_data(dY, W, pat, out=outb, ws=ws)),
-                         ("bwd_weight", lambda: ard.drop_gemm_bwd_weight(dY, X, pat, out=outb, ws=ws))):
-            us = t_us(fn)
-            row[name] = dict(us=round(us, 1), kept_tflops=round(flops / us / 1e6, 1),
+        for name, fn in tg.ops(dp, 1):
+            t = event_us(torch, fn)
+            us = t["median"]
+            row[name] = dict(us=round(us, 1), us_min=round(t["min"], 1), kept_tflops=round(flops / us / 1e6, 1),
                              frac_mfma_peak=round(flops / us / 1e6 / MFMA_PEAK_BF16, 4))
         res[f"dp{dp}"] = row
-    dense = {name: min(vendor[name], res["dp1"][name]["us"]) for name in ops}
+    dense = {name: min(vendor[name]["median"], res["dp1"][name]["us"]) for name in ops}
     for name in ops:
         res["dp2"][name]["speedup_vs_dense"] = round(dense[name] / res["dp2"][name]["us"], 3)
-    # target rates as mixtures over the searched distribution: expected time of the three products
-    # under dp ~ K (per-dp times from the sweep above; the bias b only moves which tiles are kept)
+    # dominant large-shape kernel: the forward product at dp = 2 (rate 0.5).  Algorithmic bytes: the kept
+    # tiles of W, the columns of X under a kept tile (dp = 2 over an even tile grid keeps every other tile
+    # column: half of X), and all of Y.
+    kept = tg.kept_tiles(2, 1)
+    rooflines.append(roofline_record("C3.fwd.dp2", "gemm_direct_kernel<true, true, 256, 256, 8, 0> (config 3, tile pattern dp=2, forward)",
+                                     2.0 * n * 64 * 64 * kept, 2.0 * (n * n / 2 + 64 * 64 * kept + n * n),
+                                     res["dp2"]["fwd"]["us"], 20 * REPEATS))
+    # target rates: the three products under (dp, b) ~ the searched distribution, 100 sampled patterns each
+    dense_sum = sum(dense.values())
     for p in (0.3, 0.5, 0.7):
-        k, _ = ard.search_k(p, N_PATTERNS)
-        t_mix = sum(float(k[dp - 1]) * sum(res[f"dp{dp}"][name]["us"] for name in ops) for dp in range(1, N_PATTERNS + 1))
-        kept_frac = sum(float(k[dp - 1]) / dp for dp in range(1, N_PATTERNS + 1))
-        res[f"rate{p}"] = dict(expected_us_fwd_bwd=round(t_mix, 1), speedup_vs_dense=round(sum(dense.values()) / t_mix, 3),
-                               ideal_speedup=round(1.0 / kept_frac, 3))
-    out["tile_gemm_4096_bf16_tile64"] = res
-    out["conv_fmap_drop_128x256x28x28_bf16"] = extra_conv(ard, torch, t_us)
-    out["lstm_1024_1024_b128_t64_bf16"] = extra_lstm(ard, torch, t_us)
-    out["small_and_hbm_bound"] = extra_small(ard, torch, t_us)
-    return out
+        k, cdf = ard.search_k(p, N_PATTERNS)
+        pats = [ard.pattern_sample(cdf, 3, it, 0) for it in range(100)]
+        fns = [fn for dp, b in pats for _, fn in tg.ops(dp, b)]
+
+        def all_patterns():
+            for fn in fns:
+                fn()
+        t = event_us(torch, all_patterns, reps=1, warm=1, blocks=3)
+        kept_frac = sum(tg.kept_tiles(dp, b) for dp, b in pats) / (len(pats) * (n // 64) ** 2)
+        res[f"rate{p}"] = dict(patterns=len(pats), us_per_pattern_fwd_bwd=round(t["median"] / len(pats), 1),
+                               speedup_vs_dense=round(dense_sum * len(pats) / t["median"], 3),
+                               kept_fraction=round(kept_frac, 4), ideal_speedup=round(1.0 / kept_frac, 3),
+                               target_speedup=round(1.0 / (1.0 - p), 3))
+    return res
 
 
-def extra_small(ard, torch, t_us):
+def extra_small(ard, torch):
     """The latency- and HBM-bound pieces: config 1 (one fp32 layer, 64 x 784 -> 1024), pattern_gen, channel scoring."""
     from paper_2203_05705_amd import workloads as WL
     wl = WL.mlp_layer_f32()
     X, W, dY = (ard.to_device(wl.arrays[k]) for k in ("X", "W", "dY"))
     pat = ard.Pattern.row(2, 1)
     ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    flush = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
     Y, dX, dW = torch.empty((64, 1024), device="cuda"), torch.empty_like(X), torch.empty_like(W)
-    res = {"config1_fp32_layer_us": dict(
-        fwd=round(t_us(lambda: ard.drop_gemm_fwd(X, W, pat, out=Y, ws=ws)), 2),
-        bwd_data=round(t_us(lambda: ard.drop_gemm_bwd_data(dY, W, pat, out=dX, ws=ws)), 2),
-        bwd_weight=round(t_us(lambda: ard.drop_gemm_bwd_weight(dY, X, pat, out=dW, ws=ws)), 2))}
+    calls = dict(fwd=lambda: ard.drop_gemm_fwd(X, W, pat, out=Y, ws=ws),
+                 bwd_data=lambda: ard.drop_gemm_bwd_data(dY, W, pat, out=dX, ws=ws),
+                 bwd_weight=lambda: ard.drop_gemm_bwd_weight(dY, X, pat, out=dW, ws=ws))
+    res = {"config1_fp32_layer_us": {k: round(event_us(torch, f)["median"], 2) for k, f in calls.items()},
+           "config1_fp32_layer_us_cache_cold": {k: round(event_us(torch, f, reps=10, blocks=3, flush=flush)["median"], 2)
+                                                for k, f in calls.items()}}
     tp = ard.Pattern.tile(3, 2, 64, 64)
-    res["pattern_gen_us"] = dict(rows_2048=round(t_us(lambda: ard.pattern_gen(ard.Pattern.row(3, 2), 2048)), 2),
-                                 tiles_64x64_grid=round(t_us(lambda: ard.pattern_gen(tp, 4096, 4096)), 2),
+    res["pattern_gen_us"] = dict(rows_2048=round(event_us(torch, lambda: ard.pattern_gen(ard.Pattern.row(3, 2), 2048))["median"], 2),
+                                 tiles_64x64_grid=round(event_us(torch, lambda: ard.pattern_gen(tp, 4096, 4096))["median"], 2),
                                  note="includes the binding's output allocations; one workgroup, latency-bound")
     wlc = WL.conv_layer()
     A = ard.to_device(wlc.arrays["A"])
     N, C, H, Wd = A.shape
     wsc = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, C, H, Wd, 256, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
-    us = t_us(lambda: ard.conv_select(A, 0.5, ws=wsc))
+    sel = ard.conv_select(A, 0.5, ws=wsc)
+    us = event_us(torch, lambda: ard.conv_select(A, 0.5, ws=wsc, out=sel))["median"]
     res["channel_score_select"] = dict(us=round(us, 1), bytes_read=A.numel() * 2,
-                                       gb_per_s=round(A.numel() * 2 / us / 1e3, 1), frac_hbm_peak=round(A.numel() * 2 / us / 1e3 / 8000.0, 4))
+                                       gb_per_s=round(A.numel() * 2 / us / 1e3, 1), frac_hbm_peak=round(A.numel() * 2 / us / 1e3 / HBM_PEAK, 4))
+    del flush
     return res
 
 
-def extra_conv(ard, torch, t_us):
+def extra_conv(ard, torch, rooflines):
     """Config 5: 3x3 convolution, N=128, C=Cout=256, 28x28, half of the input feature maps dropped."""
     import torch.nn.functional as F
     from paper_2203_05705_amd import workloads as WL
@@ -407,17 +506,23 @@ def extra_conv(ard, torch, t_us):
         sel = ard.conv_select(A, rate, ws=ws)
         nk = int(sel["count"].item())
         fl = 2.0 * N * H * W * 256 * nk * 9
-        row = {"kept_channels": nk, "select_us": round(t_us(lambda: ard.conv_select(A, rate, ws=ws)), 1)}
+        row = {"kept_channels": nk}
         for name, fn in (("fwd", lambda: ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws)),
                          ("bwd_data", lambda: ard.conv_bwd_data(dY, Wt, sel["keep"], nk, (H, W), ws=ws)),
                          ("bwd_weight", lambda: ard.conv_bwd_weight(dY, A, sel["keep"], nk, ws=ws))):
-            us = t_us(fn)
-            row[name] = dict(us=round(us, 1), kept_tflops=round(fl / us / 1e6, 1), frac_mfma_peak=round(fl / us / 1e6 / MFMA_PEAK_BF16, 4))
+            t = event_us(torch, fn)
+            us = t["median"]
+            row[name] = dict(us=round(us, 1), us_min=round(t["min"], 1), kept_tflops=round(fl / us / 1e6, 1),
+                             frac_mfma_peak=round(fl / us / 1e6 / MFMA_PEAK_BF16, 4))
         res[f"rate{rate}"] = row
+        if rate == 0.5:
+            rooflines.append(roofline_record(
+                "C5.fwd", "to_grid + gemm_direct_kernel<true, true, 256, *, 8, 1> (config 5, 128 of 256 input maps kept, forward call)",
+                fl, 2.0 * (N * nk * H * W + 256 * nk * 9 + N * 256 * H * W), row["fwd"]["us"], 20 * REPEATS))
     Ag, Wg = A.clone().requires_grad_(True), Wt.clone().requires_grad_(True)
     Y = F.conv2d(Ag, Wg, padding=1)
-    res["vendor_dense_us"] = dict(fwd=round(t_us(lambda: F.conv2d(A, Wt, padding=1)), 1),
-                                  bwd_data_plus_weight=round(t_us(lambda: torch.autograd.grad(Y, (Ag, Wg), dY, retain_graph=True)), 1))
+    res["vendor_dense_us"] = dict(fwd=round(event_us(torch, lambda: F.conv2d(A, Wt, padding=1))["median"], 1),
+                                  bwd_data_plus_weight=round(event_us(torch, lambda: torch.autograd.grad(Y, (Ag, Wg), dY, retain_graph=True))["median"], 1))
     ours = sum(res["rate0.5"][k]["us"] for k in ("fwd", "bwd_data", "bwd_weight"))
     dense = min(sum(res["rate0.0"][k]["us"] for k in ("fwd", "bwd_data", "bwd_weight")),
                 res["vendor_dense_us"]["fwd"] + res["vendor_dense_us"]["bwd_data_plus_weight"])
@@ -425,7 +530,7 @@ def extra_conv(ard, torch, t_us):
     return res
 
 
-def extra_lstm(ard, torch, t_us):
+def extra_lstm(ard, torch):
     """Config 4: LSTM layer, input 1024, hidden 1024, batch 128, 64 steps; row pattern on the hidden units."""
     from paper_2203_05705_amd import workloads as WL
     wl = WL.lstm_layer()
@@ -433,23 +538,58 @@ def extra_lstm(ard, torch, t_us):
     T, B, I = x.shape
     Hh = Wl.shape[0] // 4
     res = {}
+    flush = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
     for dp in (1, 2, 3):
         pat = ard.Pattern.row(dp, 1) if dp > 1 else None
         ws = torch.empty(ard.lstm_workspace_bytes(ard.BF16, T, B, I, Hh, pat), dtype=torch.uint8, device="cuda")
         h, c, g = ard.lstm_fwd(x, Wl, pat, ws=ws)
-        res[f"dp{dp}"] = dict(fwd_us=round(t_us(lambda: ard.lstm_fwd(x, Wl, pat, ws=ws), reps=5, warm=2), 1),
-                              bwd_us=round(t_us(lambda: ard.lstm_bwd(x, Wl, pat, h, c, g, dh, ws=ws), reps=5, warm=2), 1))
+        out = (h, c, g)
+        fwd = event_us(torch, lambda: ard.lstm_fwd(x, Wl, pat, ws=ws, out=out), reps=5, warm=2)
+        bwd = event_us(torch, lambda: ard.lstm_bwd(x, Wl, pat, h, c, g, dh, ws=ws), reps=5, warm=2)
+        res[f"dp{dp}"] = dict(fwd_us=round(fwd["median"], 1), bwd_us=round(bwd["median"], 1), fwd_us_min=round(fwd["min"], 1),
+                              fwd_us_per_step=round(fwd["median"] / T, 2))
+        if dp == 2:
+            cold = event_us(torch, lambda: ard.lstm_fwd(x, Wl, pat, ws=ws, out=out), reps=3, warm=1, blocks=3, flush=flush)
+            res["dp2"]["fwd_us_cache_cold"] = round(cold["median"], 1)
+    del flush
     lstm = torch.nn.LSTM(I, Hh).cuda().to(torch.bfloat16)
     xx = x.clone().requires_grad_(True)
     out_, _ = lstm(xx)
-    res["vendor_dense_us"] = dict(fwd=round(t_us(lambda: lstm(xx), reps=5, warm=2), 1),
-                                  bwd=round(t_us(lambda: torch.autograd.grad(out_, [xx] + list(lstm.parameters()), dh,
-                                                                              retain_graph=True), reps=5, warm=2), 1))
-    for dp in (1, 2, 3):
-        res[f"dp{dp}"]["fwd_us_per_step"] = round(res[f"dp{dp}"]["fwd_us"] / T, 2)
+    res["vendor_dense_us"] = dict(fwd=round(event_us(torch, lambda: lstm(xx), reps=5, warm=2, blocks=3)["median"], 1),
+                                  bwd=round(event_us(torch, lambda: torch.autograd.grad(out_, [xx] + list(lstm.parameters()), dh,
+                                                                                         retain_graph=True), reps=5, warm=2, blocks=3)["median"], 1))
     d = min(res["dp1"]["fwd_us"] + res["dp1"]["bwd_us"], res["vendor_dense_us"]["fwd"] + res["vendor_dense_us"]["bwd"])
     res["speedup_vs_dense_dp2"] = round(d / (res["dp2"]["fwd_us"] + res["dp2"]["bwd_us"]), 3)
     return res
+
+
+def only_call(args, ard, torch, chain):
+    """Profiling aid: issue one call in a tight loop so that a rocprofv3 run sees little else."""
+    name = args.only_call
+    if name in ("C3.fwd.dp2", "C5.fwd"):
+        if name == "C3.fwd.dp2":
+            fn = dict(TileGemm(ard, torch).ops(2, 1))["fwd"]
+        else:
+            from paper_2203_05705_amd import workloads as WL
+            wl = WL.conv_layer()
+            A, Wt = (ard.to_device(wl.arrays[k]) for k in ("A", "Wt"))
+            N, C, H, W = A.shape
+            ws = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, C, H, W, 256, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
+            sel = ard.conv_select(A, 0.5, ws=ws)
+            nk = int(sel["count"].item())
+            Y = ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws)
+            fn = lambda: ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws, out=Y)
+        t = event_us(torch, fn, reps=args.steps, warm=args.warmup, blocks=1)
+        print(json.dumps({"call": name, "launches": args.steps + args.warmup, "avg_us": t["median"]}))
+        return
+    _, cdf = ard.search_k(0.5, N_PATTERNS)
+    n_plan = max(100, args.steps + args.warmup)
+    pats = [tuple(ard.pattern_sample(cdf, SEED, it, layer) for layer in (1, 2)) for it in range(n_plan)]
+    plans = [chain.plan(pp) for pp in pats]
+    used = [plans[(args.warmup + it) % len(plans)] for it in range(args.steps)]
+    tot, cnt, fl = per_call_times(torch, chain, used, only=name)
+    print(json.dumps({"call": name, "launches": cnt[name] * 4, "avg_us": tot[name] / cnt[name] * 1e3,
+                      "kept_tflops": fl[name] / (tot[name] / 1e3) / 1e12}))
 
 
 def main():
@@ -479,24 +619,19 @@ def main():
     spin_up(torch)
 
     if args.only_call:
-        _, cdf = ard.search_k(0.5, N_PATTERNS)
-        pats = [tuple(ard.pattern_sample(cdf, SEED, it, layer) for layer in (1, 2)) for it in range(n_plan)]
-        plans = [chain.plan(pp) for pp in pats]
-        used = [plans[(args.warmup + it) % len(plans)] for it in range(args.steps)]
-        tot, cnt, fl = per_call_times(torch, chain, used, only=args.only_call)
-        name = args.only_call
-        print(json.dumps({"call": name, "launches": cnt[name] * 4, "avg_us": tot[name] / cnt[name] * 1e3,
-                          "kept_tflops": fl[name] / (tot[name] / 1e3) / 1e12}))
+        only_call(args, ard, torch, chain)
         return
 
+    steps = args.steps
     # dense chains: this library at dp=1, and the vendor GEMM, run the same way as the dropout chain
     dense_plan = [chain.plan(((1, 1), (1, 1)))]
-    t_lib_dense = time_steps(torch, chain, dense_plan, args.steps, args.warmup, args.mode)
-    t_vendor = {m: time_torch_dense(torch, chain, args.steps, args.warmup, m) for m in ("eager", "graph")}
-    t_vendor_dense = min(t_vendor.values())
-    t_dense = min(t_lib_dense, t_vendor_dense)
+    t_lib_dense = time_steps(torch, chain, dense_plan, steps, args.warmup, args.mode)
+    t_vendor = {m: time_torch_dense(torch, chain, steps, args.warmup, m) for m in ("eager", "graph")}
+    t_vendor_dense = min(v["median"] for v in t_vendor.values())
+    t_dense = min(t_lib_dense["median"], t_vendor_dense)
 
     rates, headline, roof = {}, None, None
+    rooflines = []
     cdf05 = None
     for p in (0.3, 0.5, 0.7):
         _, cdf = ard.search_k(p, N_PATTERNS)
@@ -504,50 +639,55 @@ def main():
             cdf05 = cdf
         pats = [tuple(ard.pattern_sample(cdf, SEED, it, layer) for layer in (1, 2)) for it in range(n_plan)]
         plans = [chain.plan(pp) for pp in pats]
-        dt = time_steps(torch, chain, plans, args.steps, args.warmup, args.mode)
-        used = [plans[(args.warmup + it) % len(plans)] for it in range(args.steps)]
-        kept_f = sum(c[5] for plan in used for c in chain.calls(plan))
-        rates[str(p)] = dict(ms_per_step=dt / args.steps * 1e3, effective_tflops=dense_f * args.steps / dt / 1e12,
-                             kept_tflops=kept_f / dt / 1e12, speedup_vs_lib_dense=t_lib_dense / dt,
-                             speedup_vs_vendor_dense=t_vendor_dense / dt, speedup_vs_dense=t_dense / dt,
-                             ideal_speedup=dense_f * args.steps / kept_f)
+        t = time_steps(torch, chain, plans, steps, args.warmup, args.mode)
+        dt = t["median"]
+        used = [plans[(args.warmup + it) % len(plans)] for it in range(steps)]
+        kept_f = sum(c[5] for plan in used for c in chain.calls(plan)) / steps
+        rates[str(p)] = dict(ms_per_step=dt * 1e3, ms_per_step_min=t["min"] * 1e3, ms_per_step_max=t["max"] * 1e3,
+                             effective_tflops=dense_f / dt / 1e12, kept_tflops=kept_f / dt / 1e12,
+                             speedup_vs_lib_dense=t_lib_dense["median"] / dt, speedup_vs_vendor_dense=t_vendor_dense / dt,
+                             speedup_vs_dense=t_dense / dt, ideal_speedup_kept_flops=dense_f / kept_f,
+                             target_speedup=1.0 / (1.0 - p))
         if p == 0.5:
-            headline = dt
+            headline = t
             other = "eager" if args.mode == "graph" else "graph"
-            rates[str(p)][f"{other}_ms_per_step"] = time_steps(torch, chain, plans, args.steps, args.warmup,
-                                                               other) / args.steps * 1e3
+            rates[str(p)][f"{other}_ms_per_step"] = time_steps(torch, chain, plans, steps, args.warmup, other)["median"] * 1e3
             cplans = [chain.plan(pp, compact_dw=True) for pp in pats]
-            rates[str(p)]["compact_dw_ms_per_step"] = time_steps(torch, chain, cplans, args.steps, args.warmup,
-                                                                 args.mode) / args.steps * 1e3
+            rates[str(p)]["compact_dw_ms_per_step"] = time_steps(torch, chain, cplans, steps, args.warmup, args.mode)["median"] * 1e3
             # roofline of the call that takes the largest share of the iteration, over the timed plans
             tot, cnt, fl = per_call_times(torch, chain, used)
             name = max(tot, key=tot.get)
-            ksec = tot[name] / 1e3
-            roof = dict(bound="mfma", kernel=f"gemm_direct_kernel ({name}; the call's finishing pass included)",
-                        achieved=fl[name] / ksec / 1e12, peak=MFMA_PEAK_BF16, unit="TFLOP/s",
-                        frac=fl[name] / ksec / 1e12 / MFMA_PEAK_BF16, avg_launch_us=ksec / cnt[name] * 1e6,
-                        traffic=TRAFFIC_BYTES.get(name),
-                        per_call_avg_us={k: round(v / cnt[k] * 1e3, 2) for k, v in tot.items()})
-    dt = headline
+            launch_us = tot[name] / cnt[name] * 1e3
+            algo = sum(chain.algorithmic_bytes(plan, name) for plan in used) / len(used)
+            roof = roofline_record(name, f"gemm_direct_kernel ({name}; the call's finishing pass, where it has one, included)",
+                                   fl[name] / cnt[name], algo, launch_us, cnt[name] * 3)
+            roof["per_call_avg_us"] = {k: round(v / cnt[k] * 1e3, 2) for k, v in tot.items()}
+    dt = headline["median"]
     result = {
         "metric": "effective TFLOP/s + speedup vs dense GEMM at dropout 0.3/0.5/0.7, 1 MI355X",
-        "value": dense_f * args.steps / dt / 1e12, "unit": "effective TFLOP/s (dense-equivalent FLOPs / time) at rate 0.5",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "value": dense_f / dt / 1e12, "unit": "effective TFLOP/s (dense-equivalent FLOPs / time) at rate 0.5",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "ms_per_step_min": headline["min"] * 1e3, "ms_per_step_max": headline["max"] * 1e3, "repeats": REPEATS,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "MLP 784-2048-2048-10, batch 1024, bf16 in / fp32 accumulate, row-based dropout on both "
                                "hidden layers, pattern per iteration from the searched distribution (N=8); fwd + bwd",
-                   "rate": 0.5, "seed": SEED,
+                   "rate": 0.5, "seed": SEED, "timing": f"median of {REPEATS} blocks of `steps` iterations",
                    "execution": "one HIP-graph replay per iteration, weight gradients on a second lane" if args.mode == "graph"
                                 else "calls issued one by one on one stream"},
-        "dense_ms_per_step": {"libard_dp1": t_lib_dense / args.steps * 1e3,
-                              "vendor_torch_matmul_eager": t_vendor["eager"] / args.steps * 1e3,
-                              "vendor_torch_matmul_graph": t_vendor["graph"] / args.steps * 1e3},
+        "dense_ms_per_step": {"libard_dp1": t_lib_dense["median"] * 1e3, "libard_dp1_min": t_lib_dense["min"] * 1e3,
+                              "vendor_torch_matmul_eager": t_vendor["eager"]["median"] * 1e3,
+                              "vendor_torch_matmul_graph": t_vendor["graph"]["median"] * 1e3},
         "rates": rates, "roofline": roof,
     }
+    if not args.no_extra:
+        extra = {"tile_gemm_4096_bf16_tile64": extra_tile_gemm(ard, torch, rooflines),
+                 "conv_fmap_drop_128x256x28x28_bf16": extra_conv(ard, torch, rooflines),
+                 "lstm_1024_1024_b128_t64_bf16": extra_lstm(ard, torch),
+                 "small_and_hbm_bound": extra_small(ard, torch)}
+        result["roofline_large_shapes"] = rooflines
+        result["extra"] = extra
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, cdf05, budget_s=12.0)
-    if not args.no_extra:
-        result["extra"] = extra_workloads(ard, torch)
     print(json.dumps(result))
 
 

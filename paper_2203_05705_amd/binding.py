@@ -372,16 +372,19 @@ def lstm_workspace_bytes(dtype_code, T, B, I, H, pat=None) -> int:
     return int(lib().ard_lstm_workspace_bytes(dtype_code, T, B, I, H, r))
 
 
-def lstm_fwd(x, W, pat=None, ws=None, stream=None):
-    """x[T,B,I], W[4H, I+H] -> (h[T,B,H] dtype, c[T,B,H] fp32, gates[T,B,4H] fp32)."""
+def lstm_fwd(x, W, pat=None, ws=None, stream=None, out=None):
+    """x[T,B,I], W[4H, I+H] -> (h[T,B,H] dtype, c[T,B,H] fp32, gates[T,B,4H] fp32); out: reuse such a triple."""
     _dev(x), _dev(W)
     T, B, I = x.shape
     H = W.shape[0] // 4
     assert W.shape == (4 * H, I + H)
     dt = _dtype_code(x)
-    h = _out((T, B, H), x.dtype, x.device)
-    c = _out((T, B, H), torch.float32, x.device)
-    gates = _out((T, B, 4 * H), torch.float32, x.device)
+    if out is not None:
+        h, c, gates = out
+    else:
+        h = _out((T, B, H), x.dtype, x.device)
+        c = _out((T, B, H), torch.float32, x.device)
+        gates = _out((T, B, 4 * H), torch.float32, x.device)
     cp, r = _pref(pat)
     ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
     _check(lib().ard_lstm_fwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
@@ -389,15 +392,14 @@ def lstm_fwd(x, W, pat=None, ws=None, stream=None):
     return h, c, gates
 
 
-def lstm_bwd(x, W, pat, h, c, gates, dh, ws=None, stream=None):
-    """Returns (dx[T,B,I], dW[4H, I+H]) in the storage dtype."""
+def lstm_bwd(x, W, pat, h, c, gates, dh, ws=None, stream=None, out=None):
+    """Returns (dx[T,B,I], dW[4H, I+H]) in the storage dtype; out: reuse such a pair."""
     for t in (x, W, h, c, gates, dh):
         _dev(t)
     T, B, I = x.shape
     H = W.shape[0] // 4
     dt = _dtype_code(x)
-    dx = _out(x.shape, x.dtype, x.device)
-    dW = _out(W.shape, W.dtype, W.device)
+    dx, dW = out if out is not None else (_out(x.shape, x.dtype, x.device), _out(W.shape, W.dtype, W.device))
     cp, r = _pref(pat)
     ws = _workspace(lstm_workspace_bytes(dt, T, B, I, H, pat), x.device, ws)
     _check(lib().ard_lstm_bwd(dt, T, B, I, H, x.data_ptr(), W.data_ptr(), r, h.data_ptr(), c.data_ptr(),
@@ -424,14 +426,15 @@ def fmap_drop_conv(mode, shape, dtype_code, Cout, ksize, stride, pad, rate=0.0, 
                                     _ptr(score), ws.data_ptr(), ws.numel(), _stream(stream)))
 
 
-def conv_select(A, rate, Cout=1, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None):
-    """Sensitivity scores and channel selection: dict(mask, keep, count, score)."""
+def conv_select(A, rate, Cout=1, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None, out=None):
+    """Sensitivity scores and channel selection: dict(mask, keep, count, score) (out: reuse such a dict)."""
     _dev(A)
     N, Cc, H, W = A.shape
-    out = dict(mask=_out((Cc,), torch.uint8, A.device),
-               keep=torch.full((Cc,), -1, dtype=torch.int32, device=A.device),
-               count=torch.zeros(1, dtype=torch.int32, device=A.device),
-               score=_out((Cc,), torch.int64, A.device))
+    if out is None:
+        out = dict(mask=_out((Cc,), torch.uint8, A.device),
+                   keep=torch.full((Cc,), -1, dtype=torch.int32, device=A.device),
+                   count=torch.zeros(1, dtype=torch.int32, device=A.device),
+                   score=_out((Cc,), torch.int64, A.device))
     fmap_drop_conv(CONV_SELECT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, rate=rate, A=A, mask=out["mask"],
                    keep=out["keep"], count=out["count"], score=out["score"], ws=ws, stream=stream)
     return out
@@ -444,32 +447,32 @@ def _out_hw(H, W, ksize, stride, pad):
     return ho, wo
 
 
-def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None):
+def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None, out=None):
     _dev(A), _dev(Wt)
     N, Cc, H, W = A.shape
     Cout, _, kh, kw = Wt.shape
     Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
-    Y = _out((N, Cout, Ho, Wo), A.dtype, A.device)
+    Y = _out((N, Cout, Ho, Wo), A.dtype, A.device) if out is None else out
     fmap_drop_conv(CONV_FWD, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
                    keep=keep, ws=ws, stream=stream)
     return Y
 
 
-def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=None):
+def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=None, out=None):
     _dev(dY), _dev(Wt)
     N = dY.shape[0]
     Cout, Cc, kh, kw = Wt.shape
-    dA = _out((N, Cc, in_hw[0], in_hw[1]), dY.dtype, dY.device)
+    dA = _out((N, Cc, in_hw[0], in_hw[1]), dY.dtype, dY.device) if out is None else out
     fmap_drop_conv(CONV_BWD_DATA, dA.shape, _dtype_code(dY), Cout, (kh, kw), stride, pad, n_keep=n_keep, Wt=Wt, dY=dY,
                    out=dA, keep=keep, ws=ws, stream=stream)
     return dA
 
 
-def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None):
+def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None, out=None):
     _dev(dY), _dev(A)
     N, Cc, H, W = A.shape
     Cout = dY.shape[1]
-    dW = _out((Cout, Cc, ksize[0], ksize[1]), A.dtype, A.device)
+    dW = _out((Cout, Cc, ksize[0], ksize[1]), A.dtype, A.device) if out is None else out
     fmap_drop_conv(CONV_BWD_WEIGHT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, n_keep=n_keep, A=A, dY=dY,
                    out=dW, keep=keep, ws=ws, stream=stream)
     return dW
