@@ -52,9 +52,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--exec", dest="mode", choices=("eager", "graph"), default="eager",
-                    help="eager: the calls are issued one by one on one stream (default, the faster one on this "
-                         "machine); graph: every iteration is one replay of a captured two-lane HIP graph")
+    ap.add_argument("--exec", dest="mode", choices=("grouped", "eager", "graph", "graph1"), default="grouped",
+                    help="grouped (default): the independent calls of every dependency level of the iteration are "
+                         "issued as one grouped launch (ard_batch_begin / ard_batch_launch), one stream; eager: the calls "
+                         "are issued one by one on one stream; graph: every iteration is one replay of a captured "
+                         "two-lane HIP graph of the eager calls; graph1: a single-lane HIP graph of the grouped launches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (reference for the HBM traffic counters)")
     ap.add_argument("--only-call", default=None, metavar="NAME",
@@ -90,7 +92,7 @@ class MlpChain:
         self.dW = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda") for w in self.W]
         self.Wc = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda")
                    for w in self.W[1:]]   # kept blocks of W2, W3 (axes padded to multiples of 8)
-        self.ws = [torch.empty(1 << 24, dtype=torch.uint8, device="cuda") for _ in range(2)]  # one per lane
+        self.ws = [torch.empty(1 << 24, dtype=torch.uint8, device="cuda") for _ in range(3)]  # one per call of a level
         self.main = torch.cuda.Stream()
         self.side = torch.cuda.Stream()
         self._keep = []
@@ -131,26 +133,27 @@ class MlpChain:
         st = [self.main.cuda_stream, self.side.cuda_stream]
         fwd, bwd_d, bwd_w, cw = lib.ard_drop_gemm_fwd, lib.ard_drop_gemm_bwd_data, lib.ard_drop_gemm_bwd_weight, lib.ard_compact_weight
 
-        def call(lane, fn, args, name, flops):
-            # the trailing arguments of every GEMM entry point are (workspace, bytes, stream)
-            tail = (st[lane],) if fn is cw else (wsp[lane], n, st[lane])
-            return ("call", lane, fn, args + tail, name, flops)
+        def call(lane, fn, args, name, flops, level, slot):
+            # the trailing arguments of every GEMM entry point are (workspace, bytes, stream); `level` is the
+            # call's depth in the iteration's dependency graph, `slot` its workspace within the level
+            tail = (st[lane],) if fn is cw else (wsp[slot], n, st[lane])
+            return ("call", lane, fn, args + tail, name, flops, level)
         # nothing dropped around layer 2 (the dense baseline, a (1, 1) sample): its products read W2 itself
         gather2 = pats[0][0] != 1 or pats[1][0] != 1
         W2x, WC2 = (W2c, WC) if gather2 else (W2, 0)
-        return ([call(1, cw, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1), "L2.compact_w", 0.0)] if gather2 else []) + [
-            call(0, fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, OUT), "L1.fwd", f * SIZES[0] * k1),
+        return ([call(1, cw, (bf, SIZES[1], SIZES[2], P(W2), P(W2c), p2, p1), "L2.compact_w", 0.0, 0, 1)] if gather2 else []) + [
+            call(0, fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), p1, None, 1.0, 1, OUT), "L1.fwd", f * SIZES[0] * k1, 0, 0),
             ("wait", 0, 1),
-            call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2x), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC2), "L2.fwd", f * k1 * k2),
+            call(0, fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2x), P(Y2), p2, p1, 1.0, 1, IN | OUT | WC2), "L2.fwd", f * k1 * k2, 1, 0),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT | DW), "L3.bwd_weight", f * k2 * SIZES[3]),
-            call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, p2, 1.0, 0, IN), "L3.fwd", f * k2 * SIZES[3]),
-            call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3), P(dY2), None, p2, 1.0, P(Y2), IN | OUT), "L3.bwd_data", f * k2 * SIZES[3]),
+            call(1, bwd_w, (bf, B, SIZES[2], SIZES[3], P(dYL), P(Y2), P(dW3), None, p2, 1.0, 0.0, IN | OUT | DW), "L3.bwd_weight", f * k2 * SIZES[3], 2, 1),
+            call(0, fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, p2, 1.0, 0, IN), "L3.fwd", f * k2 * SIZES[3], 2, 0),
+            call(0, bwd_d, (bf, B, SIZES[2], SIZES[3], P(dYL), P(W3), P(dY2), None, p2, 1.0, P(Y2), IN | OUT), "L3.bwd_data", f * k2 * SIZES[3], 2, 2),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT | DW), "L2.bwd_weight", f * k1 * k2),
-            call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2x), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC2), "L2.bwd_data", f * k1 * k2),
+            call(1, bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), p2, p1, 1.0, 0.0, IN | OUT | DW), "L2.bwd_weight", f * k1 * k2, 3, 1),
+            call(0, bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2x), P(dY1), p2, p1, 1.0, P(Y1), IN | OUT | WC2), "L2.bwd_data", f * k1 * k2, 3, 0),
             ("wait", 1, 0),
-            call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT | DW1), "L1.bwd_weight", f * SIZES[0] * k1),
+            call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT | DW1), "L1.bwd_weight", f * SIZES[0] * k1, 4, 0),
             ("wait", 0, 1),
         ]
 
@@ -181,12 +184,41 @@ class MlpChain:
                 if lanes == 2:
                     streams[s[1]].wait_stream(streams[s[2]])
                 continue
-            _, lane, fn, args, _, _ = s
+            _, lane, fn, args, _, _, _ = s
             if lanes == 1 and lane == 1:
                 args = args[:-1] + (self.main.cuda_stream,)
             rc = fn(*args)
             if rc != 0:
                 raise RuntimeError(f"libard call {s[4]} failed with {rc}: {self.lib.ard_last_error().decode()}")
+
+    def run_grouped(self, plan):
+        """Issue one iteration on the main stream, one grouped launch per dependency level: the calls of a
+        level are independent of each other, each has its own workspace."""
+        lib, stream = self.lib, self.main.cuda_stream
+        calls = self.calls(plan)
+        i = 0
+        while i < len(calls):
+            j = i
+            while j < len(calls) and calls[j][6] == calls[i][6]:
+                j += 1
+            group = j - i > 1
+            if group and lib.ard_batch_begin() != 0:
+                raise RuntimeError(lib.ard_last_error().decode())
+            for s in calls[i:j]:
+                rc = s[2](*(s[3][:-1] + (stream,)))
+                if rc != 0:
+                    lib.ard_batch_abort()
+                    raise RuntimeError(f"libard call {s[4]} failed with {rc}: {lib.ard_last_error().decode()}")
+            if group and lib.ard_batch_launch(stream) != 0:
+                raise RuntimeError(lib.ard_last_error().decode())
+            i = j
+
+    def capture_grouped(self, plan):
+        """One iteration as a single-lane HIP graph of the grouped launches."""
+        g = self.torch.cuda.CUDAGraph()
+        with self.torch.cuda.graph(g, stream=self.main):
+            self.run_grouped(plan)
+        return g
 
     def capture(self, plan):
         """One iteration as a HIP graph: lane 1 forks from and joins lane 0."""
@@ -270,6 +302,11 @@ def time_steps(torch, chain, plans, steps, warmup, mode):
         if mode == "graph":
             graphs = {i: chain.capture(plans[i]) for i in used}   # capture costs are set-up, not step time
             step = lambda i: graphs[i % n].replay()
+        elif mode == "graph1":
+            graphs = {i: chain.capture_grouped(plans[i]) for i in used}
+            step = lambda i: graphs[i % n].replay()
+        elif mode == "grouped":
+            step = lambda i: chain.run_grouped(plans[i % n])
         else:
             step = lambda i: chain.run(plans[i % n], lanes=1)
         return _stat(_blocks(torch, step, steps, warmup), steps)
@@ -299,7 +336,7 @@ def per_call_times(torch, chain, plans, reps=3, only=None):
         for i, plan in enumerate(plans):
             if only is None or i == 0:
                 chain.run(plan, lanes=1)   # inputs of every call hold this plan's values (only: shapes suffice)
-            for _, lane, fn, args, name, fl in chain.calls(plan):
+            for _, lane, fn, args, name, fl, _lvl in chain.calls(plan):
                 if only is not None and name != only:
                     continue
                 if lane == 1:
@@ -627,6 +664,7 @@ def main():
     dense_plan = [chain.plan(((1, 1), (1, 1)))]
     t_lib_dense = time_steps(torch, chain, dense_plan, steps, args.warmup, args.mode)
     t_vendor = {m: time_torch_dense(torch, chain, steps, args.warmup, m) for m in ("eager", "graph")}
+    t_lib_dense_eager = time_steps(torch, chain, dense_plan, steps, args.warmup, "eager")
     t_vendor_dense = min(v["median"] for v in t_vendor.values())
     t_dense = min(t_lib_dense["median"], t_vendor_dense)
 
@@ -650,8 +688,9 @@ def main():
                              target_speedup=1.0 / (1.0 - p))
         if p == 0.5:
             headline = t
-            other = "eager" if args.mode == "graph" else "graph"
-            rates[str(p)][f"{other}_ms_per_step"] = time_steps(torch, chain, plans, steps, args.warmup, other)["median"] * 1e3
+            for other in ("grouped", "eager", "graph", "graph1"):
+                if other != args.mode:
+                    rates[str(p)][f"{other}_ms_per_step"] = time_steps(torch, chain, plans, steps, args.warmup, other)["median"] * 1e3
             cplans = [chain.plan(pp, compact_dw=True) for pp in pats]
             rates[str(p)]["compact_dw_ms_per_step"] = time_steps(torch, chain, cplans, steps, args.warmup, args.mode)["median"] * 1e3
             # roofline of the call that takes the largest share of the iteration, over the timed plans
@@ -672,9 +711,13 @@ def main():
         "config": {"workload": "MLP 784-2048-2048-10, batch 1024, bf16 in / fp32 accumulate, row-based dropout on both "
                                "hidden layers, pattern per iteration from the searched distribution (N=8); fwd + bwd",
                    "rate": 0.5, "seed": SEED, "timing": f"median of {REPEATS} blocks of `steps` iterations",
-                   "execution": "one HIP-graph replay per iteration, weight gradients on a second lane" if args.mode == "graph"
-                                else "calls issued one by one on one stream"},
+                   "execution": {"graph": "one HIP-graph replay per iteration, weight gradients on a second lane",
+                                 "eager": "calls issued one by one on one stream",
+                                 "graph1": "one single-lane HIP-graph replay of the grouped launches per iteration",
+                                 "grouped": "one stream; the independent calls of each of the iteration's 5 dependency levels "
+                                            "issued as one grouped launch"}[args.mode]},
         "dense_ms_per_step": {"libard_dp1": t_lib_dense["median"] * 1e3, "libard_dp1_min": t_lib_dense["min"] * 1e3,
+                              "libard_dp1_calls_one_by_one": t_lib_dense_eager["median"] * 1e3,
                               "vendor_torch_matmul_eager": t_vendor["eager"]["median"] * 1e3,
                               "vendor_torch_matmul_graph": t_vendor["graph"]["median"] * 1e3},
         "rates": rates, "roofline": roof,

@@ -215,6 +215,29 @@ int32_t ard_drop_gemm_bwd_weight_static(int32_t dtype, int32_t B, int32_t I, int
                                         const ard_pattern* pat_out, const ard_pattern* pat_in,
                                         float alpha, float beta, int32_t flags, void* stream);
 
+/*
+ * Grouped launches.  A training iteration of a small layer chain (Section 3.2, last paragraph: FC ->
+ * activation with the dropout layer skipped) is a handful of products of a few microseconds each, so
+ * most of its time is the fixed cost of launches.  Calls that do not depend on each other can be
+ * issued as ONE launch:
+ *     ard_batch_begin();
+ *     ard_drop_gemm_bwd_weight(...);  ard_drop_gemm_bwd_data(...);   // recorded, nothing is enqueued
+ *     ard_batch_launch(stream);                                      // one grid runs all of them
+ * Between begin and launch (per host thread) ard_compact_weight and the three layer calls record
+ * their kernels when these are of the kinds a batch-sized layer chain uses (bf16 LDS-direct products
+ * on 4-wavefront tiles, the narrow-layer kernels, the 16-byte finishing pass); everything else
+ * (fp32, tile patterns on large tiles, LSTM, convolution) is enqueued at once as usual on the stream
+ * given to that call.  ard_batch_launch enqueues, on ITS stream, one launch with every recorded
+ * kernel that depends on nothing else in the batch, then (if any) one with the finishing passes.
+ * The caller promises that no call of a batch reads what another call of the same batch writes, and
+ * gives every call of a batch its own workspace.  Results are bit-identical to the same calls issued
+ * one by one.  ard_batch_abort() drops what was recorded.  Errors: ARD_EINVAL for begin inside an
+ * open batch or launch without one.
+ */
+int32_t ard_batch_begin(void);
+int32_t ard_batch_launch(void* stream);
+void ard_batch_abort(void);
+
 /* Standalone ReLU backward: dX = dY where Y > 0 else 0; n elements of `dtype`. */
 int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const void* Y, void* dX, void* stream);
 

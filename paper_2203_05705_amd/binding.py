@@ -85,6 +85,9 @@ _SIGS = {
     "ard_drop_gemm_bwd_weight": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ard_static_scratch_bytes": (C.c_size_t, []),
     "ard_drop_gemm_bwd_weight_static": (C.c_int32, [C.c_int32] * 4 + [C.c_void_p] * 5 + [C.c_float, C.c_float, C.c_int32, C.c_void_p]),
+    "ard_batch_begin": (C.c_int32, []),
+    "ard_batch_launch": (C.c_int32, [C.c_void_p]),
+    "ard_batch_abort": (None, []),
     "ard_relu_bwd": (C.c_int32, [C.c_int32, C.c_int64] + [C.c_void_p] * 4),
     "ard_lstm_workspace_bytes": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
     "ard_lstm_fwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
@@ -356,6 +359,25 @@ def drop_gemm_bwd_weight_static(dY, X, pat_out, pat_in, out, alpha=1.0, beta=0.0
                                                  out.data_ptr(), ro, ri, float(alpha), float(beta), int(flags),
                                                  _stream(stream)))
     return out
+
+
+class batch:
+    """Context manager: the library calls made inside are recorded and issued as one grouped launch on
+    leaving it (they must be independent of each other and use separate workspaces)."""
+
+    def __init__(self, stream=None):
+        self.stream = stream
+
+    def __enter__(self):
+        _check(lib().ard_batch_begin())
+        return self
+
+    def __exit__(self, exc_type, exc, tb):
+        if exc_type is not None:
+            lib().ard_batch_abort()
+            return False
+        _check(lib().ard_batch_launch(_stream(self.stream)))
+        return False
 
 
 def relu_bwd(dY, Y, out=None, stream=None):

@@ -48,6 +48,20 @@ struct DirectBounds {
 void note_direct_bounds(const DirectBounds& b, long a_bytes, long b_bytes);
 long extent_slack();  // elements the proofs pretend each operand is shorter by (ard_debug_set_extent_slack; 0 in normal use)
 
+// ---- grouped launches -------------------------------------------------------
+// Between ard_batch_begin() and ard_batch_launch() (per thread) the launches of the kernels that have a
+// GK_* kind are recorded instead of issued; ard_batch_launch() then runs all recorded launches of a
+// stage as ONE grid of a kernel that holds every such body (gemm.hip).  Stage 0: launches that depend on
+// nothing recorded in the batch; stage 1: passes that finish a stage-0 product of the same call.
+bool batch_open();
+// While one lives, this thread's launches are issued at once even inside an open batch: for kernels
+// whose consumer in the same call is recorded too, or issued at once, and must find their result.
+struct BatchSuspend {
+  bool was_open;
+  BatchSuspend();
+  ~BatchSuspend();
+};
+
 // ---- index maps -------------------------------------------------------------
 // A logical (compact) index j in [0, n) maps to a physical index in [0, nphys):
 //   AFFINE  off + j*step          (row pattern: off = b-1, step = dp; identity: 0, 1)

@@ -1009,6 +1009,7 @@ extern "C" int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype, int32_t N, in
                                       int32_t n_keep, const void* A, const void* Wt, const void* dYin, void* out,
                                       uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score, void* ws,
                                       size_t ws_bytes, void* stream) {
+  BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
   ConvArgs a{mode, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, n_keep, 0, 0, 0};
   int32_t st = conv_check(a);
   if (st) return st;

@@ -522,12 +522,6 @@ __global__ void scale_fill_kernel(T* p, long n, float beta) {
   if (i < n) p[i] = beta == 0.0f ? ElemTraits<T>::from_f32(0.0f) : ElemTraits<T>::from_f32(beta * ElemTraits<T>::to_f32(p[i]));
 }
 
-// Layers with at most 16 (never dropped) output neurons, bf16: dedicated kernels that take the
-// kept-input map themselves.  op 0 forward (p0 = X, p1 = W), 1 data gradient (p0 = dY, p1 = W),
-// 2 weight gradient (p0 = dY, p1 = X).  Returns false (nothing launched) when the layer does not qualify.
-bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, const void* p1, void* out, const Axis& ao,
-                const Axis& ai, int32_t flags, float alpha, float beta, int relu, const void* relu_src, hipStream_t stream,
-                int32_t* status);
 // Host-side dispatch: picks the workgroup tile for the problem and launches.
 // max_bn: the widest column tile the contraction lists allow (tile pattern), or 0.
 int32_t run_gemm(int32_t dtype, bool a_kc, bool b_kc, GemmParams P, int max_bn, int max_bm, hipStream_t stream,

@@ -470,21 +470,22 @@ __host__ __device__ __forceinline__ void direct_slab(const FastParams& P, const 
 // MODE 0: plain product.  MODE 1: convolution, B rows are output pixels gathered from the
 // bordered channels-last grid (contraction = (tap, channel)), output NCHW.  MODE 2: weight
 // gradient of the convolution, contraction over the grid's pixels, B columns = (tap, channel).
+// (body of the kernel as a device function: the grouped kernel of gemm.hip runs it on a range of
+// its workgroups; block_id is the workgroup's index within the product, lds its dynamic LDS)
 template <bool A_KC, bool B_KC, int F_BM, int BN, int NW, int MODE = 0>
-__global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P) {
+__device__ __forceinline__ void direct_body(const FastParams& P, const int block_id, uint4* const lds) {
   constexpr int NST = direct_stages(F_BM, BN);
   constexpr int WGN = (NW == 8 && BN == 256) ? 4 : 2, WGM = NW / WGN;
   constexpr int WTM = F_BM / WGM, WTN = BN / WGN;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must hold whole MFMA tiles");
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int OPA = F_BM * LDS_ROW_U4, OPB = BN * LDS_ROW_U4;  // u4 entries of one operand stage
-  extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
   DirectWork wk;
-  if (!direct_assign<F_BM, BN>(P, (int)blockIdx.x, wk)) return;
+  if (!direct_assign<F_BM, BN>(P, block_id, wk)) return;
   const Axis am = wk.am, bn = wk.bn, kax = wk.kax;
   const int m0 = wk.m0, n0 = wk.n0, split = wk.split;
   const int Kn = kax.n;
@@ -854,6 +855,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P
   }
 }
 
+template <bool A_KC, bool B_KC, int F_BM, int BN, int NW, int MODE = 0>
+__global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(const FastParams P) {
+  extern __shared__ uint4 direct_lds[];
+  direct_body<A_KC, B_KC, F_BM, BN, NW, MODE>(P, (int)blockIdx.x, direct_lds);
+}
+
 // Finishing pass of a product whose result could not be stored by the GEMM itself (split
 // contraction, or an output scattered at element granularity with dropped positions to zero):
 // sums the fp32 partials part[split][M][N] and writes the output through its maps, walking the
@@ -908,19 +915,27 @@ __global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int
 // The same pass for bf16 outputs whose rows can be written in 16-byte pieces (host checks:
 // bf16 result, beta == 0, 16-byte aligned rows, column count a multiple of 8; without zero
 // fill the column map is the identity).  A thread produces 8 adjacent physical columns.
-static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float* part, int splits, int M, int N, OutMat C) {
+struct FinishArgs {
+  const float* part;
+  int splits, M, N;
+  OutMat C;
+};
+static __device__ __forceinline__ void finish_vec_body(const FinishArgs& a, const int bx, const int by, const int gy) {
+  const float* part = a.part;
+  const int splits = a.splits, M = a.M, N = a.N;
+  const OutMat& C = a.C;
   // grid: x over the 8-column pieces of a row, y over rows (uniform per workgroup, so the row
   // lookup is scalar work)
   const int rows = C.fill ? C.rm.nphys : M, cols8 = (C.fill ? C.cn.nphys : N) >> 3;
   const long MN = (long)M * N;
-  const int piece = blockIdx.x * 256 + threadIdx.x;
+  const int piece = bx * 256 + threadIdx.x;
   if (piece >= cols8) return;
   const int c0 = piece * 8;
   // Workgroup ids go round-robin over the 8 XCDs: XCD x takes the contiguous rows
   // [x * chunk, (x + 1) * chunk).  (Row r on XCD r % 8 would put every kept row of a step-8
   // pattern, i.e. all the work, on one XCD.)
   const int chunk = (rows + 7) >> 3;
-  for (int y = blockIdx.y; y < chunk * 8; y += gridDim.y) {
+  for (int y = by; y < chunk * 8; y += gy) {
     const int r = (y & 7) * chunk + (y >> 3);
     if (r >= rows) continue;
     const int i = C.fill ? ax_inverse(C.rm, r) : r;
@@ -972,6 +987,10 @@ static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const float
     }
     *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(C.p) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
   }
+}
+
+static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const FinishArgs a) {
+  finish_vec_body(a, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
 }
 
 // Zero the dropped tiles of a tile-masked matrix (weight gradient): one workgroup per tile.
@@ -1152,6 +1171,20 @@ static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) 
   return ARD_OK;
 }
 
+// Kinds of LDS-direct products the grouped kernel holds (the 4-wavefront tiles a batch-1024 layer chain
+// uses); -1: this instantiation is always launched by itself.
+enum { GK_DIRECT_KK_64 = 0, GK_DIRECT_KM_64 = 1, GK_DIRECT_MM_64 = 2, GK_DIRECT_MM_128x64 = 3, GK_COMPACT_W = 10, GK_FINISH_VEC = 11 };
+template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
+constexpr int direct_group_kind() {
+  if (MODE != 0 || NW != 4) return -1;
+  if (BM == 64 && BN == 64) return A_KC ? (B_KC ? GK_DIRECT_KK_64 : GK_DIRECT_KM_64) : (B_KC ? -1 : GK_DIRECT_MM_64);
+  if (BM == 128 && BN == 64 && !A_KC && !B_KC) return GK_DIRECT_MM_128x64;
+  return -1;
+}
+// records the launch in this thread's open batch; false: no batch is open (gemm.hip)
+bool batch_push_direct(int kind, const FastParams& F, int grid_x, size_t lds_bytes);
+bool batch_push_finish(const FinishArgs& a, int gx, int gy);
+
 // Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
 // kernels above the 64 KiB default get their limit raised once.
 template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
@@ -1174,6 +1207,8 @@ static int32_t launch_direct_kernel(const FastParams& F_in, int grid_x, hipStrea
     if (int32_t st = direct_prove<A_KC, B_KC, BM, BN, NW, MODE>(F, grid_x, b)) return st;
     note_direct_bounds(b, F.a_elems * 2, F.b_elems * 2);
   }
+  constexpr int gk = direct_group_kind<A_KC, B_KC, BM, BN, NW, MODE>();
+  if (gk >= 0 && batch_open() && batch_push_direct(gk, F, grid_x, lds_bytes)) return ARD_OK;
   ARD_LAUNCH_NAMED("gemm_direct_kernel", kernel, dim3((unsigned)grid_x), dim3(64 * NW), lds_bytes, stream, F);
   ARD_LAUNCH_CHECK("gemm_direct_kernel");
   return ARD_OK;

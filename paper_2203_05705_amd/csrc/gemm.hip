@@ -5,9 +5,14 @@
 
 #include <mutex>
 
+#include <string.h>
+
+#include <vector>
+
 #include "engine.hpp"
 #include "fast.hpp"
 #include "pattern.hpp"
+#include "skinny.hpp"
 
 namespace ard {
 
@@ -319,17 +324,23 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     F.scatter_vec = (C.cn.nphys % 8) == 0 && (C.ld % 8) == 0 && ((uintptr_t)C.p & 15) == 0 &&
                     (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) && C.cn.nphys < (1 << 23);
   }
-  st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
-  if (raw_splits) {
-    *raw_splits = splits;
-    return true;
-  }
-  if (st || !need) return true;
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
   const int out_cols = C.fill ? C.cn.nphys : P.N;
   const bool vec_out = !C.out_f32 && C.beta == 0.0f && (out_cols % 8) == 0 && (C.ld % 8) == 0 &&
                        ((uintptr_t)C.p & 15) == 0 && (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) &&
                        (C.fill || ident(C.cn)) && out_cols < (1 << 23);
+  if (raw_splits || (need && !vec_out)) {
+    // whoever sums these partial sums is not a recordable kernel: the product runs at once
+    BatchSuspend now;
+    st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  } else {
+    st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  }
+  if (raw_splits) {
+    *raw_splits = splits;
+    return true;
+  }
+  if (st || !need) return true;
   long blocks = (total + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
@@ -337,7 +348,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     const int out_rows = C.fill ? C.rm.nphys : P.M;
     const int grid_rows = ceil_div(out_rows, 8) * 8;  // the pass deals rows to the XCDs in eighths
     dim3 grid((unsigned)ceil_div(out_cols / 8, 256), (unsigned)(grid_rows < 32768 ? grid_rows : 32768));
-    ARD_LAUNCH(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, (const float*)ws, splits, P.M, P.N, C);
+    const FinishArgs fa{(const float*)ws, splits, P.M, P.N, C};
+    if (!batch_push_finish(fa, (int)grid.x, (int)grid.y)) ARD_LAUNCH(gemm_finish_vec_kernel, grid, dim3(256), 0, stream, fa);
   }
   else
     ARD_LAUNCH(gemm_finish_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)ws,
@@ -561,13 +573,26 @@ using namespace ard;
 namespace ard {
 
 // Wc[r][c] = W[out(r)][in(c)]; rows and columns up to the next multiple of 8 are zero
+struct CompactWArgs {
+  const void* W;
+  void* Wc;
+  long ld;
+  Axis ao, ai;
+};
 template <typename T>
-__global__ void compact_weight_kernel(const T* W, long ld, Axis ao, Axis ai, T* Wc) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  const int r = blockIdx.y;
-  const int cols = pad8(ai.n);
-  if (c < cols) Wc[(long)r * cols + c] = (c < ai.n && r < ao.n) ? W[(long)ax_phys(ao, r) * ld + ax_phys(ai, c)] : (T)0;
+__device__ __forceinline__ void compact_weight_body(const CompactWArgs& a, const int bx, const int by) {
+  const int c = bx * 256 + threadIdx.x;
+  const int r = by;
+  const int cols = pad8(a.ai.n);
+  if (c < cols)
+    reinterpret_cast<T*>(a.Wc)[(long)r * cols + c] =
+        (c < a.ai.n && r < a.ao.n) ? reinterpret_cast<const T*>(a.W)[(long)ax_phys(a.ao, r) * a.ld + ax_phys(a.ai, c)] : (T)0;
 }
+template <typename T>
+__global__ __launch_bounds__(256) void compact_weight_kernel(const CompactWArgs a) {
+  compact_weight_body<T>(a, (int)blockIdx.x, (int)blockIdx.y);
+}
+static bool batch_push_compact_w(const CompactWArgs& a, int gx, int gy);
 
 // out[r][c] = c < cols ? in[r*cols + c] : 0 for c < pad8(cols): aligned copy of a narrow activation
 template <typename T>
@@ -584,12 +609,12 @@ static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, con
   if (ao.n <= 0 || ai.n <= 0) return ARD_OK;
   if (pad8(ao.n) > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
   dim3 grid(ceil_div(pad8(ai.n), 256), pad8(ao.n)), block(256);
-  if (dtype == ARD_BF16)
-    ARD_LAUNCH(compact_weight_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)W, (long)I, ao, ai,
-                       (uint16_t*)Wc);
-  else
-    ARD_LAUNCH(compact_weight_kernel<float>, grid, block, 0, stream, (const float*)W, (long)I, ao, ai,
-                       (float*)Wc);
+  const CompactWArgs ca{W, Wc, (long)I, ao, ai};
+  if (dtype == ARD_BF16) {
+    if (!batch_push_compact_w(ca, (int)grid.x, (int)grid.y)) ARD_LAUNCH(compact_weight_kernel<uint16_t>, grid, block, 0, stream, ca);
+  } else {
+    ARD_LAUNCH(compact_weight_kernel<float>, grid, block, 0, stream, ca);
+  }
   ARD_LAUNCH_CHECK("compact_weight_kernel");
   return ARD_OK;
 }
@@ -651,7 +676,11 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
     // the kept input neurons are strided along the contiguous axis of W: gather the kept block once
     const size_t need = (size_t)pad8(L.ao.n) * pad8(L.ai.n) * es;
     if (!ws || ws_bytes < need) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
-    int32_t st = compact_weight(a.dtype, a.I, W, ws, L.ao, L.ai, stream);
+    int32_t st;
+    {
+      BatchSuspend now;  // the product of this very call reads the gathered block
+      st = compact_weight(a.dtype, a.I, W, ws, L.ao, L.ai, stream);
+    }
     if (st) return st;
     L.Wp = ws;
     L.w_compact = true;
@@ -666,6 +695,216 @@ static int32_t resolve_row_layer(const LayerArgs& a, int32_t flags, const void* 
 }
 
 }  // namespace ard
+
+
+// ---- grouped launches ----------------------------------------------------------------------------
+//
+// A training iteration of a small layer chain is a handful of products of a few microseconds each,
+// so what it costs is mostly the fixed part of every launch.  Calls that do not depend on each other
+// (the weight compaction and the first forward product; the three products of the classifier layer;
+// the weight and data gradients of a hidden layer) can be recorded and then issued as one grid of
+// group_kernel, which holds the bodies of every kernel such a chain uses (all run 256 threads per
+// workgroup); each workgroup looks up the segment of the grid it belongs to and runs that body.
+namespace ard {
+
+constexpr int kGroupMaxSeg = 6;
+constexpr int kGroupArgBytes = 3584;
+struct GroupSeg {
+  int kind;      // GK_*
+  int first;     // first workgroup of the segment (a multiple of 8: workgroup ids go round-robin over the XCDs)
+  int nblocks;   // gx * gy
+  int gx, gy;
+  int arg_off;   // byte offset of the body's argument struct in GroupTable::args
+};
+struct GroupTable {
+  int nseg;
+  GroupSeg seg[kGroupMaxSeg];
+  alignas(16) char args[kGroupArgBytes];
+};
+static_assert(sizeof(GroupTable) <= 4096, "kernel arguments are limited to 4 KiB");
+
+// (The table is read through the kernel-argument segment itself: indexing the by-value parameter with a
+// run-time segment number would make the compiler copy all of it into every lane's private memory.)
+__global__ __launch_bounds__(256) void group_kernel(const GroupTable table_in_kernarg) {
+  extern __shared__ uint4 group_lds[];
+  const GroupTable& T = *(const GroupTable*)__builtin_amdgcn_kernarg_segment_ptr();
+  int s = 0;
+  while (s + 1 < T.nseg && (int)blockIdx.x >= T.seg[s + 1].first) ++s;
+  const GroupSeg sg = T.seg[s];
+  const int local = (int)blockIdx.x - sg.first;
+  if (local >= sg.nblocks) return;
+  const char* arg = T.args + sg.arg_off;
+  switch (sg.kind) {
+    case GK_DIRECT_KK_64:
+      direct_body<true, true, 64, 64, 4, 0>(*reinterpret_cast<const FastParams*>(arg), local, group_lds);
+      break;
+    case GK_DIRECT_KM_64:
+      direct_body<true, false, 64, 64, 4, 0>(*reinterpret_cast<const FastParams*>(arg), local, group_lds);
+      break;
+    case GK_DIRECT_MM_64:
+      direct_body<false, false, 64, 64, 4, 0>(*reinterpret_cast<const FastParams*>(arg), local, group_lds);
+      break;
+    case GK_DIRECT_MM_128x64:
+      direct_body<false, false, 128, 64, 4, 0>(*reinterpret_cast<const FastParams*>(arg), local, group_lds);
+      break;
+    case GK_SKINNY_FWD:
+      skinny_fwd_body(*reinterpret_cast<const SkinnyArgs*>(arg), local, group_lds);
+      break;
+    case GK_SKINNY_BWD_DATA:
+      skinny_bwd_data_body(*reinterpret_cast<const SkinnyArgs*>(arg), local % sg.gx, local / sg.gx, group_lds);
+      break;
+    case GK_SKINNY_BWD_WEIGHT:
+      skinny_bwd_weight_body(*reinterpret_cast<const SkinnyArgs*>(arg), local, group_lds);
+      break;
+    case GK_COMPACT_W:
+      compact_weight_body<uint16_t>(*reinterpret_cast<const CompactWArgs*>(arg), local % sg.gx, local / sg.gx);
+      break;
+    case GK_FINISH_VEC:
+      finish_vec_body(*reinterpret_cast<const FinishArgs*>(arg), local % sg.gx, local / sg.gx, sg.gy);
+      break;
+    default:
+      break;
+  }
+}
+
+struct BatchItem {
+  int kind, stage, gx, gy;
+  size_t lds, arg_bytes;
+  alignas(16) char args[1024];
+};
+struct Batch {
+  bool open = false;
+  std::vector<BatchItem> items;
+};
+static thread_local Batch g_batch;
+
+bool batch_open() { return g_batch.open; }
+BatchSuspend::BatchSuspend() : was_open(g_batch.open) { g_batch.open = false; }
+BatchSuspend::~BatchSuspend() { g_batch.open = was_open; }
+
+static bool batch_push(int kind, int stage, const void* args, size_t arg_bytes, int gx, int gy, size_t lds) {
+  if (!g_batch.open) return false;
+  if (arg_bytes > sizeof(BatchItem::args) || gx < 1 || gy < 1 || (long)gx * gy >= (1L << 30)) return false;
+  BatchItem it{};
+  it.kind = kind, it.stage = stage, it.gx = gx, it.gy = gy, it.lds = lds, it.arg_bytes = arg_bytes;
+  memcpy(it.args, args, arg_bytes);
+  g_batch.items.push_back(it);
+  return true;
+}
+bool batch_push_direct(int kind, const FastParams& F, int grid_x, size_t lds_bytes) {
+  return batch_push(kind, 0, &F, sizeof(F), grid_x, 1, lds_bytes);
+}
+bool batch_push_finish(const FinishArgs& a, int gx, int gy) { return batch_push(GK_FINISH_VEC, 1, &a, sizeof(a), gx, gy, 0); }
+static bool batch_push_skinny(int kind, const SkinnyArgs& a, int gx, int gy, size_t lds) {
+  return batch_push(kind, 0, &a, sizeof(a), gx, gy, lds);
+}
+static bool batch_push_compact_w(const CompactWArgs& a, int gx, int gy) { return batch_push(GK_COMPACT_W, 0, &a, sizeof(a), gx, gy, 0); }
+
+// one recorded launch by itself, exactly as it would have been issued without a batch
+static int32_t launch_item_alone(const BatchItem& it, hipStream_t stream) {
+  const dim3 grid((unsigned)it.gx, (unsigned)it.gy), block(256);
+  switch (it.kind) {
+    case GK_DIRECT_KK_64:
+      ARD_LAUNCH_NAMED("gemm_direct_kernel", (gemm_direct_kernel<true, true, 64, 64, 4, 0>), grid, block, it.lds, stream,
+                       *reinterpret_cast<const FastParams*>(it.args));
+      break;
+    case GK_DIRECT_KM_64:
+      ARD_LAUNCH_NAMED("gemm_direct_kernel", (gemm_direct_kernel<true, false, 64, 64, 4, 0>), grid, block, it.lds, stream,
+                       *reinterpret_cast<const FastParams*>(it.args));
+      break;
+    case GK_DIRECT_MM_64:
+      ARD_LAUNCH_NAMED("gemm_direct_kernel", (gemm_direct_kernel<false, false, 64, 64, 4, 0>), grid, block, it.lds, stream,
+                       *reinterpret_cast<const FastParams*>(it.args));
+      break;
+    case GK_DIRECT_MM_128x64:
+      ARD_LAUNCH_NAMED("gemm_direct_kernel", (gemm_direct_kernel<false, false, 128, 64, 4, 0>), grid, block, it.lds, stream,
+                       *reinterpret_cast<const FastParams*>(it.args));
+      break;
+    case GK_SKINNY_FWD:
+      ARD_LAUNCH(skinny_fwd_kernel, grid, block, it.lds, stream, *reinterpret_cast<const SkinnyArgs*>(it.args));
+      break;
+    case GK_SKINNY_BWD_DATA:
+      ARD_LAUNCH(skinny_bwd_data_kernel, grid, block, it.lds, stream, *reinterpret_cast<const SkinnyArgs*>(it.args));
+      break;
+    case GK_SKINNY_BWD_WEIGHT:
+      ARD_LAUNCH(skinny_bwd_weight_kernel, grid, block, it.lds, stream, *reinterpret_cast<const SkinnyArgs*>(it.args));
+      break;
+    case GK_COMPACT_W:
+      ARD_LAUNCH(compact_weight_kernel<uint16_t>, grid, block, 0, stream, *reinterpret_cast<const CompactWArgs*>(it.args));
+      break;
+    case GK_FINISH_VEC:
+      ARD_LAUNCH(gemm_finish_vec_kernel, grid, block, 0, stream, *reinterpret_cast<const FinishArgs*>(it.args));
+      break;
+    default:
+      return fail(ARD_EINVAL, "unknown recorded kernel kind %d", it.kind);
+  }
+  ARD_LAUNCH_CHECK("recorded kernel");
+  return ARD_OK;
+}
+
+static int32_t launch_stage(const std::vector<const BatchItem*>& items, hipStream_t stream) {
+  size_t i = 0;
+  while (i < items.size()) {
+    // as many consecutive items as fit into one table
+    GroupTable T{};
+    size_t lds = 0, arg_used = 0;
+    int blocks = 0;
+    size_t j = i;
+    for (; j < items.size() && T.nseg < kGroupMaxSeg; ++j) {
+      const BatchItem& it = *items[j];
+      const size_t a16 = align_up(it.arg_bytes, 16);
+      if (arg_used + a16 > (size_t)kGroupArgBytes) break;
+      GroupSeg& sg = T.seg[T.nseg++];
+      sg.kind = it.kind, sg.first = blocks, sg.gx = it.gx, sg.gy = it.gy, sg.nblocks = it.gx * it.gy;
+      sg.arg_off = (int)arg_used;
+      memcpy(T.args + arg_used, it.args, it.arg_bytes);
+      arg_used += a16;
+      blocks += (sg.nblocks + 7) & ~7;
+      lds = it.lds > lds ? it.lds : lds;
+    }
+    if (j - i == 1) {
+      if (int32_t st = launch_item_alone(*items[i], stream)) return st;
+    } else {
+      static thread_local bool raised = false;
+      if (!raised) {
+        ARD_HIP_CHECK(raise_lds_limit((const void*)group_kernel, 4096 + 16 * (SK_MAX_COLS + 16) * 2 + 256));
+        raised = !dry_run();
+      }
+      ARD_LAUNCH(group_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, T);
+      ARD_LAUNCH_CHECK("group_kernel");
+    }
+    i = j;
+  }
+  return ARD_OK;
+}
+
+}  // namespace ard
+
+extern "C" int32_t ard_batch_begin(void) {
+  if (g_batch.open) return fail(ARD_EINVAL, "ard_batch_begin: a batch is already open on this thread");
+  g_batch.open = true;
+  g_batch.items.clear();
+  return ARD_OK;
+}
+
+extern "C" int32_t ard_batch_launch(void* stream_) {
+  if (!g_batch.open) return fail(ARD_EINVAL, "ard_batch_launch without ard_batch_begin");
+  g_batch.open = false;
+  int32_t st = ARD_OK;
+  for (int stage = 0; stage < 2 && !st; ++stage) {
+    std::vector<const BatchItem*> sel;
+    for (const BatchItem& it : g_batch.items)
+      if (it.stage == stage) sel.push_back(&it);
+    if (!sel.empty()) st = launch_stage(sel, (hipStream_t)stream_);
+  }
+  g_batch.items.clear();
+  return st;
+}
+
+extern "C" void ard_batch_abort(void) {
+  g_batch.open = false;
+  g_batch.items.clear();
+}
 
 extern "C" size_t ard_gemm_workspace_bytes(int32_t dtype, int32_t B, int32_t I, int32_t O, const ard_pattern* pat_out,
                                            const ard_pattern* pat_in) {

@@ -380,6 +380,7 @@ extern "C" size_t ard_lstm_workspace_bytes(int32_t dtype, int32_t T, int32_t B, 
 extern "C" int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const void* x,
                                 const void* W, const ard_pattern* pat, void* h, float* c, float* gates, void* ws,
                                 size_t ws_bytes, void* stream) {
+  BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
   LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
   int32_t st = lstm_check(a, pat);
   if (st) return st;
@@ -394,6 +395,7 @@ extern "C" int32_t ard_lstm_bwd(int32_t dtype, int32_t T, int32_t B, int32_t I, 
                                 const void* W, const ard_pattern* pat, const void* h, const float* c,
                                 const float* gates, const void* dh, void* dx, void* dW, void* ws, size_t ws_bytes,
                                 void* stream) {
+  BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
   LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
   int32_t st = lstm_check(a, pat);
   if (st) return st;

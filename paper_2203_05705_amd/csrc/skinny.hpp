@@ -10,6 +10,7 @@
 //
 // Xc / dXc are activations in the compact layout (pad8(K') columns, zero padded) or, without a
 // pattern on the inputs, the dense ones.  W is the dense [O x I] matrix or its compact form.
+#pragma once
 #include "common.hpp"
 #include "engine.hpp"
 
@@ -49,7 +50,7 @@ __device__ __forceinline__ sk_bf16x8_t sk_load8(const uint16_t* p) {
 // column ki(j) - p0 of the copy.
 constexpr int SK_MAX_COLS = 2048;  // physical inputs a workgroup can hold (up to 16 rows of bf16 in LDS)
 __device__ __forceinline__ int sk_pitch(int span) { return span + 8; }  // in elements: rows start 16 bytes apart in the banks
-__device__ void sk_stage_w(uint16_t* wl, const SkinnyArgs& a, int p0, int span) {
+__device__ __forceinline__ void sk_stage_w(uint16_t* wl, const SkinnyArgs& a, int p0, int span) {
   const int pitch = sk_pitch(span), chunks = span >> 3, total = a.O * chunks;
 #pragma unroll 4
   for (int i = threadIdx.x; i < total; i += 256) {
@@ -64,13 +65,12 @@ __device__ void sk_stage_w(uint16_t* wl, const SkinnyArgs& a, int p0, int span) 
 // MFMA 16x16x32: lane l supplies row (l % 16), contraction chunk (l / 16) * 8 .. +8 of each
 // operand and receives column (l % 16), rows 4 * (l / 16) + v of the product.
 // A dense W is first gathered into LDS (sk_stage_w); a compact one is read from global memory.
-__global__ __launch_bounds__(256) void skinny_fwd_kernel(const SkinnyArgs a) {
-  extern __shared__ uint4 sk_lds[];
+__device__ __forceinline__ void skinny_fwd_body(const SkinnyArgs& a, const int bx, uint4* const sk_lds) {
   float(*part)[256] = reinterpret_cast<float(*)[256]>(sk_lds);  // [4][256]
   uint16_t* wl = reinterpret_cast<uint16_t*>(sk_lds + 256);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, kc = (lane >> 4) * 8;
-  const int row = blockIdx.x * 16 + r;
+  const int row = bx * 16 + r;
   const bool row_ok = row < a.B, w_ok = r < a.w_rows;
   const int kpad = pad8(a.Kk);
   // a dense W: all columns up to the last kept one
@@ -111,8 +111,12 @@ __global__ __launch_bounds__(256) void skinny_fwd_kernel(const SkinnyArgs a) {
   const int src = ((m >> 2) * 16 + n) * 4 + (m & 3);
   float v = a.alpha * (part[0][src] + part[1][src] + part[2][src] + part[3][src]);
   if (a.relu) v = fmaxf(v, 0.0f);
-  const int orow = blockIdx.x * 16 + m;
+  const int orow = bx * 16 + m;
   if (orow < a.B && n < a.out_cols) a.out[(long)orow * a.ld_out + n] = n < a.O ? f32_to_bf16_bits(v) : (uint16_t)0;
+}
+__global__ __launch_bounds__(256) void skinny_fwd_kernel(const SkinnyArgs a) {
+  extern __shared__ uint4 sk_lds_fwd[];
+  skinny_fwd_body(a, (int)blockIdx.x, sk_lds_fwd);
 }
 
 // Data gradient.  One workgroup = 1024 kept inputs x SK_BD_ROWS batch rows: thread t owns the 8
@@ -120,16 +124,15 @@ __global__ __launch_bounds__(256) void skinny_fwd_kernel(const SkinnyArgs a) {
 // their 16 x 8 weights in registers.  The rows of dY go through LDS, the masks of a thread's rows
 // are fetched before its first store: nothing in the row loop waits for memory.
 constexpr int SK_BD_ROWS = 4, SK_BD_COLS = 1024;
-__global__ __launch_bounds__(256) void skinny_bwd_data_kernel(const SkinnyArgs a) {
-  extern __shared__ uint4 sk_lds[];
+__device__ __forceinline__ void skinny_bwd_data_body(const SkinnyArgs& a, const int bx, const int by, uint4* const sk_lds) {
   float(*dys)[16] = reinterpret_cast<float(*)[16]>(sk_lds);  // [SK_BD_ROWS][16]
   uint16_t* wl = reinterpret_cast<uint16_t*>(sk_lds + SK_BD_ROWS * 4);
   const int kpad = pad8(a.Kk);
-  const int jb = blockIdx.x * SK_BD_COLS;
+  const int jb = bx * SK_BD_COLS;
   const int cols = min(SK_BD_COLS, kpad - jb);
   const int g = threadIdx.x & 127, half = threadIdx.x >> 7;
   const int j0 = jb + g * 8;
-  const int r0 = blockIdx.y * SK_BD_ROWS;
+  const int r0 = by * SK_BD_ROWS;
   constexpr int RPT = SK_BD_ROWS / 2;  // rows per thread
   if (threadIdx.x < SK_BD_ROWS * 16) {
     const int i = threadIdx.x >> 4, m = threadIdx.x & 15;
@@ -198,17 +201,21 @@ __global__ __launch_bounds__(256) void skinny_bwd_data_kernel(const SkinnyArgs a
     *reinterpret_cast<uint4*>(a.out + (long)row * a.ld_out + j0) = o;
   }
 }
+__global__ __launch_bounds__(256) void skinny_bwd_data_kernel(const SkinnyArgs a) {
+  extern __shared__ uint4 sk_lds_bd[];
+  skinny_bwd_data_body(a, (int)blockIdx.x, (int)blockIdx.y, sk_lds_bd);
+}
 
 // Weight gradient.  One workgroup = 16 kept inputs; wave w contracts the 32-row slabs w, w+4, ...
 // of the batch.  Operand rows run along the batch here, so a lane gathers its 8 values of dY
 // (output neuron l % 16) and of Xc (kept input l % 16) with 2-byte loads; the 16 lanes of a group
 // read 32 contiguous bytes of each row.  The workgroup also writes the zeros of the dropped
 // inputs between its first kept input and the next workgroup's.
-__global__ __launch_bounds__(256) void skinny_bwd_weight_kernel(const SkinnyArgs a) {
-  __shared__ float part[4][256];
+__device__ __forceinline__ void skinny_bwd_weight_body(const SkinnyArgs& a, const int bx, uint4* const sk_lds) {
+  float(*part)[256] = reinterpret_cast<float(*)[256]>(sk_lds);  // [4][256]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, rc = (lane >> 4) * 8;
-  const int j = blockIdx.x * 16 + c;  // kept input of this lane (B operand); output neuron c (A operand)
+  const int j = bx * 16 + c;  // kept input of this lane (B operand); output neuron c (A operand)
   const int xcols = pad8(a.Kk);
   const bool j_ok = j < a.Kk, m_ok = c < a.O;
   sk_f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -231,11 +238,11 @@ __global__ __launch_bounds__(256) void skinny_bwd_weight_kernel(const SkinnyArgs
 #pragma unroll
   for (int v = 0; v < 4; ++v) part[wave][lane * 4 + v] = acc[v];
   __syncthreads();
-  // thread e -> output neuron e / 16, kept input blockIdx.x * 16 + e % 16
+  // thread e -> output neuron e / 16, kept input bx * 16 + e % 16
   const int m = threadIdx.x >> 4, n = threadIdx.x & 15;
   const int src = ((m >> 2) * 16 + n) * 4 + (m & 3);
   const float v = a.alpha * (part[0][src] + part[1][src] + part[2][src] + part[3][src]);
-  const int jj = blockIdx.x * 16 + n;
+  const int jj = bx * 16 + n;
   if (a.dw_compact) {
     if (m < pad8(a.O) && jj < xcols) a.out[(long)m * a.ld_out + jj] = (m < a.O && jj < a.Kk) ? f32_to_bf16_bits(v) : (uint16_t)0;
     return;
@@ -243,8 +250,8 @@ __global__ __launch_bounds__(256) void skinny_bwd_weight_kernel(const SkinnyArgs
   if (m >= a.O) return;
   // physical columns owned by this workgroup: from its first kept input (from 0 for the first
   // workgroup) up to the next workgroup's first kept input (up to I for the last)
-  const int jb = blockIdx.x * 16, je = min(jb + 16, a.Kk);
-  const int p_lo = blockIdx.x == 0 ? 0 : a.ki.off + jb * a.ki.step;
+  const int jb = bx * 16, je = min(jb + 16, a.Kk);
+  const int p_lo = bx == 0 ? 0 : a.ki.off + jb * a.ki.step;
   const int p_hi = je >= a.Kk ? a.I : a.ki.off + je * a.ki.step;
   uint16_t* orow = a.out + (long)m * a.ld_out;
   if (a.ki.step != 1 || a.ki.off != 0) {
@@ -256,13 +263,21 @@ __global__ __launch_bounds__(256) void skinny_bwd_weight_kernel(const SkinnyArgs
   }
   if (jj < a.Kk) orow[a.ki.off + jj * a.ki.step] = f32_to_bf16_bits(v);
 }
+__global__ __launch_bounds__(256) void skinny_bwd_weight_kernel(const SkinnyArgs a) {
+  extern __shared__ uint4 sk_lds_bw[];
+  skinny_bwd_weight_body(a, (int)blockIdx.x, sk_lds_bw);
+}
+
+enum { GK_SKINNY_FWD = 100, GK_SKINNY_BWD_DATA = 101, GK_SKINNY_BWD_WEIGHT = 102 };
+// records the launch in the open batch of this thread (gemm.hip); false: no batch is open, launch now
+static bool batch_push_skinny(int kind, const SkinnyArgs& a, int gx, int gy, size_t lds);
 
 static bool sk_aligned(const void* p, long ld) { return ((uintptr_t)p & 15) == 0 && (ld % 8) == 0; }
 
 // op 0: forward (p0 = X, p1 = W, out = Y); op 1: data gradient (p0 = dY, p1 = W, out = dX);
 // op 2: weight gradient (p0 = dY, p1 = X, out = dW).  Returns false when the layer is not one of
 // the shapes above (nothing launched); otherwise *status holds the launch result.
-bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, const void* p1, void* out, const Axis& ao,
+static bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, const void* p1, void* out, const Axis& ao,
                 const Axis& ai, int32_t flags, float alpha, float beta, int relu, const void* relu_src, hipStream_t stream,
                 int32_t* status) {
   *status = ARD_OK;
@@ -308,7 +323,8 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
       if (e != hipSuccess) return false;
       raised = !dry_run();
     }
-    ARD_LAUNCH(skinny_fwd_kernel, dim3((unsigned)ceil_div(B, 16)), dim3(256), lds, stream, a);
+    if (!batch_push_skinny(GK_SKINNY_FWD, a, ceil_div(B, 16), 1, lds))
+      ARD_LAUNCH(skinny_fwd_kernel, dim3((unsigned)ceil_div(B, 16)), dim3(256), lds, stream, a);
   } else if (op == 1) {
     if (!sk_aligned(out, ld_in) || (relu_src && !sk_aligned(relu_src, ld_in))) return false;
     if (!in_c && (I % 8)) return false;
@@ -325,8 +341,9 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
       if (e != hipSuccess) return false;
       raised_bd = !dry_run();
     }
-    ARD_LAUNCH(skinny_bwd_data_kernel, dim3((unsigned)ceil_div(pad8(ai.n), SK_BD_COLS), (unsigned)ceil_div(B, SK_BD_ROWS)),
-                       dim3(256), lds, stream, a);
+    if (!batch_push_skinny(GK_SKINNY_BWD_DATA, a, ceil_div(pad8(ai.n), SK_BD_COLS), ceil_div(B, SK_BD_ROWS), lds))
+      ARD_LAUNCH(skinny_bwd_data_kernel, dim3((unsigned)ceil_div(pad8(ai.n), SK_BD_COLS), (unsigned)ceil_div(B, SK_BD_ROWS)),
+                 dim3(256), lds, stream, a);
   } else {
     a.dy = (const uint16_t*)p0;
     a.ld_dy = ld_o;
@@ -334,7 +351,8 @@ bool try_skinny(int op, int32_t dtype, int B, int I, int O, const void* p0, cons
     a.ld_act = ld_in;
     a.dw_compact = (flags & ARD_DW_COMPACT) != 0;
     a.ld_out = a.dw_compact ? pad8(ai.n) : I;
-    ARD_LAUNCH(skinny_bwd_weight_kernel, dim3((unsigned)ceil_div(pad8(ai.n), 16)), dim3(256), 0, stream, a);
+    if (!batch_push_skinny(GK_SKINNY_BWD_WEIGHT, a, ceil_div(pad8(ai.n), 16), 1, 4096))
+      ARD_LAUNCH(skinny_bwd_weight_kernel, dim3((unsigned)ceil_div(pad8(ai.n), 16)), dim3(256), 4096, stream, a);
   }
   hipError_t e = ard::launch_status();
   if (e != hipSuccess) *status = fail(ARD_EHIP, "launch of a skinny-layer kernel failed: %s", hipGetErrorString(e));

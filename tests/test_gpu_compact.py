@@ -142,6 +142,7 @@ class _Config2:
             c.X0, c.dYL = to_dev(wl.arrays["X0"], "bf16"), to_dev(wl.arrays["dY"], "bf16")
             c.W = [to_dev(wl.arrays[f"W{l}"], "bf16") for l in (1, 2, 3)]
             c.dYLc = ard.pad_compact(c.dYL)
+            c.batch_ws = [torch.empty(1 << 27, dtype=torch.uint8, device="cuda") for _ in range(3)]
             cls._inst = c
         return cls._inst
 
@@ -211,6 +212,27 @@ def _check_config2_iteration(pats, what):
     check_compact_r(dY2u, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (unpadded dY, compact W3)")
     dY2c = ard.drop_gemm_bwd_data(c.dYLc, W3c, None, p2, relu_src=Y2o, flags=IN | OUT | WC, I=sizes[2], O=sizes[3])
     check_compact_r(dY2c, ref["dY"][1][:, keep[1]], "bf16", what + " dY2 (compact W3)")
+    # the benchmark issues the independent calls of a dependency level as ONE grouped launch: the results
+    # must be bit-identical to the calls issued one by one (every call of a batch has its own workspace)
+    ws = c.batch_ws
+    with ard.batch():
+        Y1b = ard.drop_gemm_fwd(c.X0, W[0], p1, None, relu=True, flags=OUT, ws=ws[0])
+        W2b = ard.compact_weight(W[1], p2, p1) if gather2 else None
+    assert torch.equal(Y1b, Y1), what + " grouped Y1"
+    assert W2b is None or torch.equal(W2b, W2x), what + " grouped W2 compact"
+    with ard.batch():
+        Y3b = ard.drop_gemm_fwd(Y2o, W[2], None, p2, flags=IN, I=sizes[2], O=sizes[3], ws=ws[0])
+        dW3b = ard.drop_gemm_bwd_weight(c.dYLc, Y2o, None, p2, flags=IN | OUT, I=sizes[2], O=sizes[3], ws=ws[1])
+        dY2b = ard.drop_gemm_bwd_data(c.dYLc, W[2], None, p2, relu_src=Y2o, flags=IN | OUT, I=sizes[2], O=sizes[3], ws=ws[2])
+    assert torch.equal(Y3b, Y3) and torch.equal(dW3b, dW3) and torch.equal(dY2b, dY2), what + " grouped layer 3"
+    with ard.batch():
+        dW2b = ard.drop_gemm_bwd_weight(dY2o, Y1o, p2, p1, flags=IN | OUT, I=sizes[1], O=sizes[2], ws=ws[0])
+        dY1b = ard.drop_gemm_bwd_data(dY2o, W2x, p2, p1, relu_src=Y1o, flags=IN | OUT | WC2, I=sizes[1], O=sizes[2], ws=ws[1])
+    assert torch.equal(dW2b, dW2) and torch.equal(dY1b, dY1), what + " grouped layer 2 gradients"
+    # a batch of one call, and a batch around a call that gathers W itself, behave like plain calls
+    with ard.batch():
+        Y2b = ard.drop_gemm_fwd(Y1o, W[1], p2, p1, relu=True, flags=IN | OUT, I=sizes[1], O=sizes[2], ws=ws[0])
+    assert torch.equal(Y2b, Y2), what + " grouped Y2 (W gathered inside the call)"
 
 
 @pytest.mark.parametrize("rate", [0.3, 0.5, 0.7])

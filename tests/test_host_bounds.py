@@ -108,3 +108,36 @@ def test_a_shortened_operand_is_rejected():
         rc = D.layer_calls(lib, heap, D.BF16, 4096, 4096, 4096, None, None, 0, ops=(0,))
         assert rc == [-2] and "bounds proof" in lib.ard_last_error().decode()
         assert D.launches(lib)[0] == 0
+
+
+def test_grouped_launch_of_a_dependency_level():
+    """Independent calls recorded between ard_batch_begin and ard_batch_launch become one launch of the
+    grouped kernel (plus one for their finishing passes); kernels the batch cannot hold are issued at once."""
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        p1, p2 = (3, 2), (5, 1)
+        assert lib.ard_batch_begin() == 0
+        assert lib.ard_batch_begin() == -1            # already open
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 2048, p2, p1, IN | OUT | WC, ops=(1, 2)), "level 4")
+        assert D.launches(lib)[0] == 0                # everything recorded
+        assert lib.ard_batch_launch(None) == 0
+        n, names = D.launches(lib)
+        assert names[0] == "group_kernel" and n <= 2, names
+        assert lib.ard_batch_launch(None) == -1       # no batch open
+        # the three products of the 10-neuron layer: one launch
+        lib.ard_batch_begin()
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 10, None, p2, IN | OUT), "level 3")
+        assert lib.ard_batch_launch(None) == 0
+        assert D.launches(lib) == (1, ["group_kernel"])
+        # a call that gathers W itself issues the gather at once and records the product
+        lib.ard_batch_begin()
+        _ok(lib, D.layer_calls(lib, heap, D.BF16, 1024, 2048, 2048, p2, p1, IN | OUT, ops=(0,)), "gather inside")
+        assert D.launches(lib) == (1, ["compact_weight_kernel"])
+        assert lib.ard_batch_launch(None) == 0
+        assert D.launches(lib) == (1, ["gemm_direct_kernel"])
+        # fp32 is never recorded; abort drops a batch
+        lib.ard_batch_begin()
+        _ok(lib, D.layer_calls(lib, heap, D.F32, 64, 784, 1024, (2, 1), None, 0, ops=(0,)), "fp32")
+        assert D.launches(lib)[0] >= 1
+        lib.ard_batch_abort()
+        assert lib.ard_batch_launch(None) == -1
