@@ -201,7 +201,7 @@ class MlpChain:
             j = i
             while j < len(calls) and calls[j][6] == calls[i][6]:
                 j += 1
-            group = j - i > 1
+            group = True   # (a single call may still be several kernels: zero fill + product)
             if group and lib.ard_batch_begin() != 0:
                 raise RuntimeError(lib.ard_last_error().decode())
             for s in calls[i:j]:
@@ -352,6 +352,30 @@ def per_call_times(torch, chain, plans, reps=3, only=None):
                 cnt[name] = cnt.get(name, 0) + 1
                 flops[name] = flops.get(name, 0.0) + fl
     return tot, cnt, flops
+
+
+def per_level_times(torch, chain, plans, reps=3):
+    """HIP-event time of each dependency level issued as a grouped launch (averaged over the plans; every
+    level is issued once untimed and then `reps` times back to back inside its bracket)."""
+    tot, cnt = {}, {}
+    with torch.cuda.stream(chain.main):
+        for plan in plans:
+            chain.run_grouped(plan)
+            calls = chain.calls(plan)
+            for lvl in sorted({c[6] for c in calls}):
+                sub = [c for c in calls if c[6] == lvl]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                chain.run_grouped(sub)
+                e0.record(chain.main)
+                for _ in range(reps):
+                    chain.run_grouped(sub)
+                e1.record(chain.main)
+                torch.cuda.synchronize()
+                key = "+".join(c[4] for c in sub)
+                key = f"level{lvl}:" + ("+".join(c[4] for c in sub if c[4] != "L2.compact_w") + ("(+compact_w)" if any(c[4] == "L2.compact_w" for c in sub) else ""))
+                tot[key] = tot.get(key, 0.0) + e0.elapsed_time(e1) / reps
+                cnt[key] = cnt.get(key, 0) + 1
+    return {k: round(v / cnt[k] * 1e3, 2) for k, v in sorted(tot.items())}, cnt
 
 
 def cpu_baseline(wl, cdf, budget_s):
@@ -701,6 +725,9 @@ def main():
             roof = roofline_record(name, f"gemm_direct_kernel ({name}; the call's finishing pass, where it has one, included)",
                                    fl[name] / cnt[name], algo, launch_us, cnt[name] * 3)
             roof["per_call_avg_us"] = {k: round(v / cnt[k] * 1e3, 2) for k, v in tot.items()}
+            lv, lcnt = per_level_times(torch, chain, used)
+            roof["per_level_grouped_avg_us"] = lv
+            roof["per_level_plans"] = lcnt
     dt = headline["median"]
     result = {
         "metric": "effective TFLOP/s + speedup vs dense GEMM at dropout 0.3/0.5/0.7, 1 MI355X",

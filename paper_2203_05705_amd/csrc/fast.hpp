@@ -88,6 +88,7 @@ struct FastParams {
   // Scattering epilogue (row patterns without compact outputs): the tile's results go through
   // LDS and are written, with the dropped positions it owns as +0.0, through these affine maps.
   int scatter, scatter_vec;
+  int scatter_rows_only;  // the tile writes its kept rows only (a separate pass zeroes the dropped rows)
   Axis srm, scn;
 };
 
@@ -373,6 +374,11 @@ __device__ __forceinline__ void direct_scatter_tile(const uint16_t* tile, int ld
       else rowp[c0] = (uint16_t)w[0];
     }
   };
+  if (P.scatter_rows_only) {
+    // kept rows only, whole rows (kept columns and the zeros between them)
+    for (int i = m0 + rsub; i < m1; i += RPP) write_row(i * sr + rm.off, i - m0);
+    return;
+  }
   // the groups of this tile's compact rows: one kept row and step - 1 dropped ones each
   for (int i = m0 + rsub; i < m1; i += RPP)
     for (int g = 0; g < sr; ++g) {
@@ -993,6 +999,34 @@ static __global__ __launch_bounds__(256) void gemm_finish_vec_kernel(const Finis
   finish_vec_body(a, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
 }
 
+// Rows of a bf16 matrix that an affine row map (off + i * step, i < n_kept) does NOT reach, set to +0.0:
+// the dropped output neurons of a weight gradient.  Independent of the product that writes the kept rows.
+struct ZeroRowsArgs {
+  uint16_t* C;
+  int ld, rows, cols, off, step, n_kept, vec;
+};
+static __device__ __forceinline__ void zero_rows_body(const ZeroRowsArgs& a, const int bx, const int nblocks) {
+  const int dropped = a.rows - a.n_kept;
+  const int per_row = a.vec ? a.cols >> 3 : a.cols;
+  const long total = (long)dropped * per_row;
+  for (long e = (long)bx * 256 + threadIdx.x; e < total; e += (long)nblocks * 256) {
+    const int d = (int)(e / per_row), c = (int)(e - (long)d * per_row);
+    // d-th dropped row: rows before `off` come first, then step - 1 per group, then the tail
+    int r;
+    if (d < a.off) {
+      r = d;
+    } else {
+      const int q = (d - a.off) / (a.step - 1), t = (d - a.off) - q * (a.step - 1);
+      r = q < a.n_kept ? a.off + q * a.step + 1 + t : a.off + a.n_kept * a.step + (d - a.off - a.n_kept * (a.step - 1)) - (a.step - 1);
+    }
+    if (a.vec) *reinterpret_cast<uint4*>(a.C + (long)r * a.ld + c * 8) = make_uint4(0, 0, 0, 0);
+    else a.C[(long)r * a.ld + c] = 0;
+  }
+}
+static __global__ __launch_bounds__(256) void zero_rows_kernel(const ZeroRowsArgs a) {
+  zero_rows_body(a, (int)blockIdx.x, (int)gridDim.x);
+}
+
 // Zero the dropped tiles of a tile-masked matrix (weight gradient): one workgroup per tile.
 static __global__ __launch_bounds__(256) void zero_dropped_tiles_kernel(uint16_t* C, int ld, int rows, int cols, int tr, int tc,
                                                                  int TC, int dp, int o) {
@@ -1173,7 +1207,8 @@ static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) 
 
 // Kinds of LDS-direct products the grouped kernel holds (the 4-wavefront tiles a batch-1024 layer chain
 // uses); -1: this instantiation is always launched by itself.
-enum { GK_DIRECT_KK_64 = 0, GK_DIRECT_KM_64 = 1, GK_DIRECT_MM_64 = 2, GK_DIRECT_MM_128x64 = 3, GK_COMPACT_W = 10, GK_FINISH_VEC = 11 };
+enum { GK_DIRECT_KK_64 = 0, GK_DIRECT_KM_64 = 1, GK_DIRECT_MM_64 = 2, GK_DIRECT_MM_128x64 = 3, GK_COMPACT_W = 10, GK_FINISH_VEC = 11,
+       GK_ZERO_ROWS = 12 };
 template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
 constexpr int direct_group_kind() {
   if (MODE != 0 || NW != 4) return -1;
@@ -1184,6 +1219,7 @@ constexpr int direct_group_kind() {
 // records the launch in this thread's open batch; false: no batch is open (gemm.hip)
 bool batch_push_direct(int kind, const FastParams& F, int grid_x, size_t lds_bytes);
 bool batch_push_finish(const FinishArgs& a, int gx, int gy);
+bool batch_push_zero_rows(const ZeroRowsArgs& a, int gx);
 
 // Host side: launch one instantiation with its dynamic LDS (stages x (BM + BN) rows of 128 bytes);
 // kernels above the 64 KiB default get their limit raised once.

@@ -253,12 +253,12 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     // ragged).  With identity columns it always beats the finishing pass; with column step 2 up
     // to row step 4; beyond that only while the region is small or the tiles many, and never for
     // column groups wider than 4 (25 us against 15 us through the pass).
+    // What made wide groups slow was the volume of zeros a tile had to write for the dropped ROWS of its
+    // region (step^2 times its own size, by 16 to 64 workgroups): those rows are now zeroed by a pass of
+    // their own that runs beside the product (zero_rows_kernel), the tile writes its kept rows in full.
     const int cs = C.cn.step;
-    const bool small_or_many = region <= 16384 || tiles >= 160;
-    if (cs == 1) scatter = tiles >= 4;
-    else if (cs == 2) scatter = tiles >= 64 ? (small_or_many || C.rm.step <= 4) : false;
-    else if (cs <= 4) scatter = tiles >= 64 && small_or_many;
-    else scatter = tiles >= 64 && region <= 16384;
+    (void)region;
+    scatter = cs == 1 ? tiles >= 4 : tiles >= 64;
   }
   // Splitting the contraction s ways shortens a workgroup's loop by steps * (1 - 1/s) steps of about
   // 0.19 us (a step takes that long however few tiles there are), and costs about 2.6 us per
@@ -323,6 +323,21 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     F.scn = C.cn;
     F.scatter_vec = (C.cn.nphys % 8) == 0 && (C.ld % 8) == 0 && ((uintptr_t)C.p & 15) == 0 &&
                     (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) && C.cn.nphys < (1 << 23);
+    const int dropped_rows = C.rm.nphys - C.rm.n;
+    if (C.rm.step > 1 && dropped_rows > 0) {
+      // dropped rows: their own pass over all CUs (recorded with the product in a grouped launch)
+      F.scatter_rows_only = 1;
+      const ZeroRowsArgs za{(uint16_t*)C.p, (int)C.ld, C.rm.nphys, C.cn.nphys, C.rm.off, C.rm.step, C.rm.n, F.scatter_vec};
+      const long pieces = (long)dropped_rows * (F.scatter_vec ? C.cn.nphys / 8 : C.cn.nphys);
+      long gx = (pieces + 1023) / 1024;  // four stores per thread
+      gx = gx < 1 ? 1 : (gx > 2048 ? 2048 : gx);
+      if (!batch_push_zero_rows(za, (int)gx)) ARD_LAUNCH(zero_rows_kernel, dim3((unsigned)gx), dim3(256), 0, stream, za);
+      hipError_t e = ard::launch_status();
+      if (e != hipSuccess) {
+        st = fail(ARD_EHIP, "launch of zero_rows_kernel failed: %s", hipGetErrorString(e));
+        return true;
+      }
+    }
   }
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
   const int out_cols = C.fill ? C.cn.nphys : P.N;
@@ -579,14 +594,31 @@ struct CompactWArgs {
   long ld;
   Axis ao, ai;
 };
+// a workgroup gathers kCwRows rows x 256 columns: a thread's loads of its rows are independent and in
+// flight together
+constexpr int kCwRows = 16;
 template <typename T>
 __device__ __forceinline__ void compact_weight_body(const CompactWArgs& a, const int bx, const int by) {
   const int c = bx * 256 + threadIdx.x;
-  const int r = by;
-  const int cols = pad8(a.ai.n);
-  if (c < cols)
-    reinterpret_cast<T*>(a.Wc)[(long)r * cols + c] =
-        (c < a.ai.n && r < a.ao.n) ? reinterpret_cast<const T*>(a.W)[(long)ax_phys(a.ao, r) * a.ld + ax_phys(a.ai, c)] : (T)0;
+  const int cols = pad8(a.ai.n), rows = pad8(a.ao.n);
+  if (c >= cols) return;
+  const T* W = reinterpret_cast<const T*>(a.W);
+  T* Wc = reinterpret_cast<T*>(a.Wc);
+  const bool c_ok = c < a.ai.n;
+  const long pc = c_ok ? ax_phys(a.ai, c) : 0;
+  T v[kCwRows];
+#pragma unroll
+  for (int i = 0; i < kCwRows; ++i) {
+    const int r = by * kCwRows + i;
+    const bool ok = c_ok && r < a.ao.n;
+    const T t = W[(long)(ok ? ax_phys(a.ao, r) : 0) * a.ld + pc];  // unconditional (clamped) load
+    v[i] = ok ? t : (T)0;
+  }
+#pragma unroll
+  for (int i = 0; i < kCwRows; ++i) {
+    const int r = by * kCwRows + i;
+    if (r < rows) Wc[(long)r * cols + c] = v[i];
+  }
 }
 template <typename T>
 __global__ __launch_bounds__(256) void compact_weight_kernel(const CompactWArgs a) {
@@ -607,8 +639,8 @@ __global__ void pad_cols_kernel(const T* in, int rows, int cols, T* out) {
 static int32_t compact_weight(int32_t dtype, int I, const void* W, void* Wc, const Axis& ao, const Axis& ai,
                               hipStream_t stream) {
   if (ao.n <= 0 || ai.n <= 0) return ARD_OK;
-  if (pad8(ao.n) > 65535) return fail(ARD_ESHAPE, "more than 65535 kept output neurons");
-  dim3 grid(ceil_div(pad8(ai.n), 256), pad8(ao.n)), block(256);
+  if (ceil_div(pad8(ao.n), kCwRows) > 65535) return fail(ARD_ESHAPE, "too many kept output neurons for one launch");
+  dim3 grid(ceil_div(pad8(ai.n), 256), ceil_div(pad8(ao.n), kCwRows)), block(256);
   const CompactWArgs ca{W, Wc, (long)I, ao, ai};
   if (dtype == ARD_BF16) {
     if (!batch_push_compact_w(ca, (int)grid.x, (int)grid.y)) ARD_LAUNCH(compact_weight_kernel<uint16_t>, grid, block, 0, stream, ca);
@@ -762,6 +794,9 @@ __global__ __launch_bounds__(256) void group_kernel(const GroupTable table_in_ke
     case GK_FINISH_VEC:
       finish_vec_body(*reinterpret_cast<const FinishArgs*>(arg), local % sg.gx, local / sg.gx, sg.gy);
       break;
+    case GK_ZERO_ROWS:
+      zero_rows_body(*reinterpret_cast<const ZeroRowsArgs*>(arg), local, sg.nblocks);
+      break;
     default:
       break;
   }
@@ -795,6 +830,7 @@ bool batch_push_direct(int kind, const FastParams& F, int grid_x, size_t lds_byt
   return batch_push(kind, 0, &F, sizeof(F), grid_x, 1, lds_bytes);
 }
 bool batch_push_finish(const FinishArgs& a, int gx, int gy) { return batch_push(GK_FINISH_VEC, 1, &a, sizeof(a), gx, gy, 0); }
+bool batch_push_zero_rows(const ZeroRowsArgs& a, int gx) { return batch_push(GK_ZERO_ROWS, 0, &a, sizeof(a), gx, 1, 0); }
 static bool batch_push_skinny(int kind, const SkinnyArgs& a, int gx, int gy, size_t lds) {
   return batch_push(kind, 0, &a, sizeof(a), gx, gy, lds);
 }
@@ -834,6 +870,9 @@ static int32_t launch_item_alone(const BatchItem& it, hipStream_t stream) {
       break;
     case GK_FINISH_VEC:
       ARD_LAUNCH(gemm_finish_vec_kernel, grid, block, 0, stream, *reinterpret_cast<const FinishArgs*>(it.args));
+      break;
+    case GK_ZERO_ROWS:
+      ARD_LAUNCH(zero_rows_kernel, grid, block, 0, stream, *reinterpret_cast<const ZeroRowsArgs*>(it.args));
       break;
     default:
       return fail(ARD_EINVAL, "unknown recorded kernel kind %d", it.kind);
