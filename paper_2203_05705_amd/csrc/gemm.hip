@@ -551,15 +551,33 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     }
     return total;
   };
-  // the largest tile that still gives (about) every CU a workgroup with work
-  int heavy = 0, bm = 256, bn = 256, total = 0;
-  for (const TileCfg& c : kTileCfgs) {
+  // Tile choice by estimated time: rounds of workgroups over the chip x contraction steps x the time one
+  // round of one step takes with that tile.  A period that does not divide the tile grid leaves classes of
+  // 21 or 13 tile rows: wide tiles then end in a mostly empty block and the workgroup count lands just above
+  // a multiple of the CU count (288 for dp = 3), which smaller tiles avoid.  Round times (us) measured on
+  // the dense 4096^3 product per tile and operand layout; an 8-wavefront tile has one slot per CU, a
+  // 4-wavefront tile two.
+  static const float kRoundUs[3][5] = {{2.21f, 1.33f, 1.32f, 0.79f, 0.464f},   // forward (both operands contraction-contiguous)
+                                       {2.04f, 1.19f, 1.17f, 0.70f, 0.43f},    // data gradient
+                                       {1.98f, 1.14f, 1.16f, 0.66f, 0.44f}};   // weight gradient
+  int steps = op == 2 ? ceil_div(B, 64) : 0;
+  if (op != 2)
+    for (int c = 0; c < t.ncls; ++c) steps = steps > t.k_cnt[c] * (t.k_bs / 64) ? steps : t.k_cnt[c] * (t.k_bs / 64);
+  int heavy = 0, bm = 0, bn = 0, total = 0;
+  float best = 0.0f;
+  for (int ci = 0; ci < 5; ++ci) {
+    const TileCfg& c = kTileCfgs[ci];
     if ((c.bn % t.n_bs) || (op == 2 && (c.bm % x))) continue;
-    if (dev_knobs().class_tile && &c != &kTileCfgs[dev_knobs().class_tile - 1]) continue;
-    bm = c.bm, bn = c.bn;
-    total = count(bm, bn, heavy);
-    if (heavy >= (bm * bn >= 256 * 128 ? 200 : 440)) break;  // (two workgroups per CU for the 4-wavefront tiles)
+    if (dev_knobs().class_tile && ci != dev_knobs().class_tile - 1) continue;
+    int h = 0;
+    const int tot = count(c.bm, c.bn, h);
+    if (tot == 0) continue;
+    const int slots = c.bm * c.bn >= 256 * 128 ? 256 : 512;
+    const float est = (float)ceil_div(h > 0 ? h : 1, slots) * (float)steps * kRoundUs[op][ci];
+    if (bm == 0 || est < best) best = est, bm = c.bm, bn = c.bn;
   }
+  if (bm == 0) return false;
+  total = count(bm, bn, heavy);
   if (total == 0) return false;
   if (heavy < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
   F.alpha = alpha;
