@@ -304,6 +304,23 @@ int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype,
                            uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* ---- dynamic dropout-ratio tuning (Section 5.3, host only) ---------------- */
+
+/*
+ * The prune possibility over the training epochs follows the skew-normal curve of Eq. (4),
+ * f(y) = (2/sigma) phi((y-mu)/sigma) Phi(lambda (y-mu)/sigma).
+ * ard_skew_normal_params solves Eq. (5) and (6) for mu and sigma given the mean E(Y), the variance
+ * D(Y) > 0 and the skew lambda; ard_skew_normal_pdf evaluates Eq. (4).
+ * ard_prune_schedule fills p_out[n_epochs] (host doubles): epoch e sits at the normalised time
+ * (e + 1/2) / n_epochs, its possibility is proportional to the curve there, scaled so that the
+ * average over the run equals `total`, then clipped to [0, p_max] (how the curve becomes a per-epoch
+ * value is not spelled out in the paper; this is the reading taken).  mean and var are in normalised time.
+ */
+int32_t ard_skew_normal_params(double mean, double var, double lambda, double* mu, double* sigma);
+double ard_skew_normal_pdf(double y, double mu, double sigma, double lambda);
+int32_t ard_prune_schedule(int32_t n_epochs, double total, double mean, double var, double lambda,
+                           double p_max, double* p_out);
+
 /* ---- sizes of compact buffers and grids (host only, nothing is launched) --- */
 
 /* Number of kept units of a ROW / LIST / NONE pattern over `units` units: ceil((units - (b-1)) / dp)

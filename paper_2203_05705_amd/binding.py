@@ -94,6 +94,9 @@ _SIGS = {
     "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
     "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
+    "ard_skew_normal_params": (C.c_int32, [C.c_double] * 3 + [C.c_void_p] * 2),
+    "ard_skew_normal_pdf": (C.c_double, [C.c_double] * 4),
+    "ard_prune_schedule": (C.c_int32, [C.c_int32] + [C.c_double] * 5 + [C.c_void_p]),
     "ard_kept_count": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ard_compact_dim": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ard_tile_grid": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
@@ -201,6 +204,13 @@ def pattern_sample(cdf, seed: int, it: int, stream_id: int):
     dp, b = C.c_int32(), C.c_int32()
     _check(lib().ard_pattern_sample(arr, len(cdf), seed, it, stream_id, C.byref(dp), C.byref(b)))
     return dp.value, b.value
+
+
+def prune_schedule(n_epochs: int, total: float, mean: float, var: float, lam: float, p_max: float = 1.0):
+    """Per-epoch prune possibilities along the skew-normal curve of Section 5.3 (host doubles)."""
+    out = (C.c_double * n_epochs)()
+    _check(lib().ard_prune_schedule(n_epochs, total, mean, var, lam, p_max, out))
+    return list(out)
 
 
 # ---- device entry points ---------------------------------------------------------
