@@ -568,9 +568,16 @@ def extra_conv(ard, torch, rooflines):
         nk = int(sel["count"].item())
         fl = 2.0 * N * H * W * 256 * nk * 9
         row = {"kept_channels": nk}
-        for name, fn in (("fwd", lambda: ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws)),
-                         ("bwd_data", lambda: ard.conv_bwd_data(dY, Wt, sel["keep"], nk, (H, W), ws=ws)),
-                         ("bwd_weight", lambda: ard.conv_bwd_weight(dY, A, sel["keep"], nk, ws=ws))):
+        # the layer's three passes on one workspace: the forward pass builds the channels-last grid of the
+        # kept maps, the data gradient that of dY, the weight gradient takes both
+        both = ard.CONV_REUSE_A | ard.CONV_REUSE_DY
+        Yb = ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws)
+        dAb = ard.conv_bwd_data(dY, Wt, sel["keep"], nk, (H, W), ws=ws)
+        dWb = ard.conv_bwd_weight(dY, A, sel["keep"], nk, ws=ws)
+        for name, fn in (("fwd", lambda: ard.conv_fwd(A, Wt, sel["keep"], nk, ws=ws, out=Yb)),
+                         ("bwd_data", lambda: ard.conv_bwd_data(dY, Wt, sel["keep"], nk, (H, W), ws=ws, out=dAb)),
+                         ("bwd_weight", lambda: ard.conv_bwd_weight(dY, A, sel["keep"], nk, ws=ws, out=dWb, reuse=both)),
+                         ("bwd_weight_own_grids", lambda: ard.conv_bwd_weight(dY, A, sel["keep"], nk, ws=ws, out=dWb))):
             t = event_us(torch, fn)
             us = t["median"]
             row[name] = dict(us=round(us, 1), us_min=round(t["min"], 1), kept_tflops=round(fl / us / 1e6, 1),

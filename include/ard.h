@@ -277,6 +277,20 @@ typedef enum {
   ARD_CONV_BWD_DATA = 2,  /* out = dA[N,C,H,W], dropped channels exactly 0               */
   ARD_CONV_BWD_WEIGHT = 3 /* out = dWt[Cout,C,KH,KW], dropped channels exactly 0         */
 } ard_conv_mode;
+/*
+ * bf16, stride 1: every pass first copies what it convolves into a channels-last, zero-bordered grid
+ * in the workspace (the kept maps of A for FWD and BWD_WEIGHT, dY for BWD_DATA and BWD_WEIGHT).  The
+ * passes of one layer can share those copies: OR a flag into `mode` and the pass takes the grid an
+ * earlier call left in the SAME workspace instead of building it again.  The caller vouches that the
+ * earlier call had the same shape arguments, the same tensor (A or dYin), the same kept list, and that
+ * nothing else wrote the workspace in between (the other passes of the layer do not disturb it).
+ *   ARD_CONV_REUSE_A   FWD, BWD_WEIGHT: the grid of A built by an earlier FWD or BWD_WEIGHT
+ *   ARD_CONV_REUSE_DY  BWD_DATA, BWD_WEIGHT: the grid of dY built by an earlier BWD_DATA or BWD_WEIGHT;
+ *                      across the two passes only for size-preserving filters (k - 1 = 2 pad), else
+ *                      ARD_EUNSUPPORTED
+ * Any other use of the flags (fp32, stride > 1, n_keep = 0, SELECT) is refused.
+ */
+enum { ARD_CONV_REUSE_A = 0x100, ARD_CONV_REUSE_DY = 0x200 };
 
 size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd,
                                 int32_t Cout, int32_t kh, int32_t kw, int32_t stride, int32_t pad);

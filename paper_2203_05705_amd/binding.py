@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(HERE, "libard.so")
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
 CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT = 0, 1, 2, 3
+CONV_REUSE_A, CONV_REUSE_DY = 0x100, 0x200
 IN_COMPACT, OUT_COMPACT, W_COMPACT, DW_COMPACT = 1, 2, 4, 8
 
 
@@ -479,32 +480,32 @@ def _out_hw(H, W, ksize, stride, pad):
     return ho, wo
 
 
-def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None, out=None):
+def conv_fwd(A, Wt, keep, n_keep, stride=1, pad=1, ws=None, stream=None, out=None, reuse=0):
     _dev(A), _dev(Wt)
     N, Cc, H, W = A.shape
     Cout, _, kh, kw = Wt.shape
     Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
     Y = _out((N, Cout, Ho, Wo), A.dtype, A.device) if out is None else out
-    fmap_drop_conv(CONV_FWD, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
+    fmap_drop_conv(CONV_FWD | reuse, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
                    keep=keep, ws=ws, stream=stream)
     return Y
 
 
-def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=None, out=None):
+def conv_bwd_data(dY, Wt, keep, n_keep, in_hw, stride=1, pad=1, ws=None, stream=None, out=None, reuse=0):
     _dev(dY), _dev(Wt)
     N = dY.shape[0]
     Cout, Cc, kh, kw = Wt.shape
     dA = _out((N, Cc, in_hw[0], in_hw[1]), dY.dtype, dY.device) if out is None else out
-    fmap_drop_conv(CONV_BWD_DATA, dA.shape, _dtype_code(dY), Cout, (kh, kw), stride, pad, n_keep=n_keep, Wt=Wt, dY=dY,
+    fmap_drop_conv(CONV_BWD_DATA | reuse, dA.shape, _dtype_code(dY), Cout, (kh, kw), stride, pad, n_keep=n_keep, Wt=Wt, dY=dY,
                    out=dA, keep=keep, ws=ws, stream=stream)
     return dA
 
 
-def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None, out=None):
+def conv_bwd_weight(dY, A, keep, n_keep, ksize=(3, 3), stride=1, pad=1, ws=None, stream=None, out=None, reuse=0):
     _dev(dY), _dev(A)
     N, Cc, H, W = A.shape
     Cout = dY.shape[1]
     dW = _out((Cout, Cc, ksize[0], ksize[1]), A.dtype, A.device) if out is None else out
-    fmap_drop_conv(CONV_BWD_WEIGHT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, n_keep=n_keep, A=A, dY=dY,
+    fmap_drop_conv(CONV_BWD_WEIGHT | reuse, A.shape, _dtype_code(A), Cout, ksize, stride, pad, n_keep=n_keep, A=A, dY=dY,
                    out=dW, keep=keep, ws=ws, stream=stream)
     return dW

@@ -607,6 +607,7 @@ __global__ void wgrad_grid_reduce_kernel(const float* part, const int* rank, int
 
 struct ConvArgs {
   int32_t mode, dtype, N, C, H, W, Cout, kh, kw, stride, pad, n_keep, Ho, Wo, es;
+  int32_t reuse;  // ARD_CONV_REUSE_* bits of the mode argument
 };
 
 struct ConvWs {
@@ -764,22 +765,33 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   int hgm, wgm;
   const long pix_cap = conv_grid_pixels(a, &hgm, &wgm);
   (void)pix_cap;
+  // Both grids are laid out the same way whichever pass builds them, so a later pass of the same layer
+  // can take the grid an earlier one left in the workspace (ARD_CONV_REUSE_A / ARD_CONV_REUSE_DY):
+  // A: zero border of `pad` pixels; dY: zero border of k-1-pad pixels (what the data gradient convolves).
+  // The weight gradient wants dY on the grid of A without a border: for a size-preserving filter
+  // (k - 1 = 2 pad) that is the bordered dY grid read from (k-1-pad) rows and columns further on.
+  const long margin = (long)a.kh * wgm + a.kw + 128;
+  const bool same = a.kh - 1 == 2 * a.pad && a.kw - 1 == 2 * a.pad;
   if (a.mode == ARD_CONV_FWD) {
     const int Cp = pad64(Ck), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
-    int32_t st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, 64, w.grid_a, stream);
+    int32_t st = ARD_OK;
+    if (!(a.reuse & ARD_CONV_REUSE_A))
+      st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream);
     if (st) return st;
     const long total = (long)a.Cout * K;
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
     ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout};
-    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + 64, cv, out, stream);
+    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
   if (a.mode == ARD_CONV_BWD_DATA) {
     // dA = dY (bordered by k-1-pad) convolved with the reversed filter, contraction over (tap, co)
     const int ph = a.kh - 1 - a.pad, pw = a.kw - 1 - a.pad;
     const int Cp = pad64(a.Cout), Hg = a.Ho + 2 * ph, Wg = a.Wo + 2 * pw, K = taps * Cp;
-    int32_t st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, 64, w.grid_y, stream);
+    int32_t st = ARD_OK;
+    if (!(a.reuse & ARD_CONV_REUSE_DY))
+      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream);
     if (st) return st;
     const long total = (long)Ck * K;
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
@@ -791,25 +803,30 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
                        a.C, a.H * a.W);
     ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
     ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck};
-    return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + 64, cv, out, stream);
+    return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
   // BWD_WEIGHT: contraction over the pixels of the input grid; dY sits on the same grid (top-left
   // aligned, zero elsewhere), the tap shifts the activation grid by (r*Wg + s) pixels.
   const int Cpa = pad64(Ck), Cpy = pad64(a.Cout), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad;
-  const long margin = (long)a.kh * Wg + a.kw + 128;
-  int32_t st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cpa, margin, w.grid_a, stream);
+  int32_t st = ARD_OK;
+  if (!(a.reuse & ARD_CONV_REUSE_A))
+    st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cpa, margin, w.grid_a, stream);
   if (st) return st;
-  st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, 0, 0, Cpy, 64, w.grid_y, stream);
+  // dY: bordered like the data gradient's grid when the filter preserves the size (then shared with it)
+  const int ph = same ? a.kh - 1 - a.pad : 0, pw = same ? a.kw - 1 - a.pad : 0;
+  const long y_shift = (long)ph * Wg + pw;  // pixels between the bordered grid's origin and dY(., 0, 0)
+  if (!(a.reuse & ARD_CONV_REUSE_DY))
+    st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cpy, margin, w.grid_y, stream);
   if (st) return st;
   ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
   ARD_LAUNCH_CHECK("rank_from_keep_kernel");
   const int Kq = a.N * Hg * Wg, Nn = taps * Cpa;
   FastParams F{};
-  F.A = w.grid_y;
+  F.A = w.grid_y + y_shift * Cpy;
   F.B = w.grid_a;
   F.lda = Cpy;
   F.ldb = Cpa;
-  F.a_elems = ((long)a.N * Hg * Wg + 64) * Cpy;
+  F.a_elems = ((long)a.N * Hg * Wg + margin - y_shift) * Cpy;
   F.b_elems = ((long)a.N * Hg * Wg + margin) * Cpa;
   F.am = axis_identity(Cpy);
   F.bn = axis_identity(Nn);
@@ -889,6 +906,14 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
   if (a.n_keep > 0 && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
   if (!out) return fail(ARD_EINVAL, "null output pointer");
   const int Ck = a.n_keep;
+  if (a.reuse) {
+    const bool grid_path = Ck > 0 && w.grid_a && !dev_knobs().no_fast;
+    if (!grid_path) return fail(ARD_EUNSUPPORTED, "grid reuse needs the bf16 stride-1 path and at least one kept channel");
+    if ((a.reuse & ARD_CONV_REUSE_A) && a.mode == ARD_CONV_BWD_DATA) return fail(ARD_EINVAL, "BWD_DATA has no grid of A to reuse");
+    if ((a.reuse & ARD_CONV_REUSE_DY) && a.mode == ARD_CONV_FWD) return fail(ARD_EINVAL, "FWD has no grid of dY to reuse");
+    if ((a.reuse & ARD_CONV_REUSE_DY) && a.mode == ARD_CONV_BWD_WEIGHT && !(a.kh - 1 == 2 * a.pad && a.kw - 1 == 2 * a.pad))
+      return fail(ARD_EUNSUPPORTED, "the weight gradient shares dY's grid with the data gradient only for k - 1 = 2 pad");
+  }
   if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast) {
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
@@ -999,7 +1024,7 @@ extern "C" int32_t ard_conv_out_size(int32_t in, int32_t k, int32_t stride, int3
 
 extern "C" size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad) {
-  ConvArgs a{0, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, 0, 0, 0, 0};
+  ConvArgs a{0, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, 0, 0, 0, 0, 0};
   if (conv_check(a)) return 0;
   return conv_ws_layout(nullptr, a).total;
 }
@@ -1010,7 +1035,9 @@ extern "C" int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype, int32_t N, in
                                       uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score, void* ws,
                                       size_t ws_bytes, void* stream) {
   BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
-  ConvArgs a{mode, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, n_keep, 0, 0, 0};
+  if (mode < 0 || (mode & ~(0xff | ARD_CONV_REUSE_A | ARD_CONV_REUSE_DY))) return fail(ARD_EINVAL, "unknown conv mode bits 0x%x", mode);
+  ConvArgs a{mode & 0xff, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, n_keep, 0, 0, 0, mode & (ARD_CONV_REUSE_A | ARD_CONV_REUSE_DY)};
+  if (a.reuse && a.mode == ARD_CONV_SELECT) return fail(ARD_EINVAL, "SELECT builds no grid");
   int32_t st = conv_check(a);
   if (st) return st;
   ConvWs w = conv_ws_layout((char*)ws, a);

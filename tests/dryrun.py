@@ -84,7 +84,7 @@ def lstm_calls(lib, heap, dtype, T, B, I, H, pat):
             lib.ard_lstm_bwd(dtype, T, B, I, H, x, W, r, h, c, g, dh, dx, dW, ws, n, None)]
 
 
-def conv_calls(lib, heap, dtype, N, Cc, Cout, H, W, k, stride, pad, n_keep, modes=(1, 2, 3)):
+def conv_calls(lib, heap, dtype, N, Cc, Cout, H, W, k, stride, pad, n_keep, modes=(1, 2, 3, 0x101, 0x202, 0x103)):
     n = lib.ard_conv_workspace_bytes(dtype, N, Cc, H, W, Cout, k, k, stride, pad)
     ws = heap(n)
     big = N * max(Cc, Cout) * (H + 2 * pad) * (W + 2 * pad) * 4

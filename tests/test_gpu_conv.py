@@ -40,11 +40,38 @@ def _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed, check_bwd_da
     dW = ard.conv_bwd_weight(dYd, Ad, sel["keep"], cnt, (k, k), stride, pad)
     zero_w = np.broadcast_to((m == 0)[None, :, None, None], (Cout, C, k, k))
     assert_parity(dW, OC.conv_bwd_weight(dYv, Av, m, (k, k), stride, pad), dtype, zero_w, "conv dW")
+    dA = None
     if check_bwd_data:
         dA = ard.conv_bwd_data(dYd, Wd, sel["keep"], cnt, (H, W), stride, pad)
         zero_a = np.broadcast_to((m == 0)[None, :, None, None], (N, C, H, W))
         assert_parity(dA, OC.conv_bwd_data(dYv, Wv, m, (H, W), stride, pad), dtype, zero_a, "conv dA")
+    if dtype == "bf16" and stride == 1 and cnt > 0 and dA is not None:
+        _check_grid_sharing(Ad, Wd, dYd, sel["keep"], cnt, k, pad, Y, dA, dW)
     torch.cuda.synchronize()
+
+
+def _check_grid_sharing(Ad, Wd, dYd, keep, cnt, k, pad, Y, dA, dW):
+    """The passes of one layer sharing the channels-last grids in one workspace give the same bits as
+    passes that each build their own, in either order."""
+    N, C, H, W = Ad.shape
+    Cout = Wd.shape[0]
+    RA, RY = ard.CONV_REUSE_A, ard.CONV_REUSE_DY
+    same = k - 1 == 2 * pad
+    ws = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, C, H, W, Cout, k, k, 1, pad), dtype=torch.uint8, device="cuda")
+    # forward builds A's grid, the data gradient dY's, the weight gradient takes both
+    assert torch.equal(ard.conv_fwd(Ad, Wd, keep, cnt, 1, pad, ws=ws), Y)
+    assert torch.equal(ard.conv_bwd_data(dYd, Wd, keep, cnt, (H, W), 1, pad, ws=ws), dA)
+    assert torch.equal(ard.conv_bwd_weight(dYd, Ad, keep, cnt, (k, k), 1, pad, ws=ws, reuse=RA | (RY if same else 0)), dW)
+    # the other way round: the weight gradient builds both
+    ws.fill_(0x5A)
+    assert torch.equal(ard.conv_bwd_weight(dYd, Ad, keep, cnt, (k, k), 1, pad, ws=ws), dW)
+    assert torch.equal(ard.conv_fwd(Ad, Wd, keep, cnt, 1, pad, ws=ws, reuse=RA), Y)
+    if same:
+        assert torch.equal(ard.conv_bwd_data(dYd, Wd, keep, cnt, (H, W), 1, pad, ws=ws, reuse=RY), dA)
+    else:
+        with pytest.raises(ard.ArdError) as e:
+            ard.conv_bwd_weight(dYd, Ad, keep, cnt, (k, k), 1, pad, ws=ws, reuse=RY)
+        assert e.value.code == -6
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -55,6 +82,8 @@ def _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed, check_bwd_da
     (2, 6, 10, 11, 10, 5, 1, 2, 0.5),       # 5x5
     (4, 32, 40, 14, 14, 3, 1, 1, 0.0),      # nothing dropped
     (5, 24, 130, 10, 12, 3, 1, 1, 0.75),    # more than one row tile
+    (2, 8, 16, 9, 9, 3, 1, 0, 0.5),         # no padding: the output is smaller than the input
+    (3, 8, 12, 8, 10, 5, 1, 1, 0.25),       # 5x5 with pad 1
 ])
 def test_conv_parity(dtype, N, C, Cout, H, W, k, stride, pad, rate):
     _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed=N * 1000 + C)
@@ -90,5 +119,9 @@ def test_config5_conv_layer_full_size():
                        "bf16", zero_a, "dA")
     print("config 5 bwd_data done", flush=True)
     zero_w = np.broadcast_to((m == 0)[None, :, None, None], Wv.shape)
-    e3 = assert_parity(ard.conv_bwd_weight(dYd, Ad, sel["keep"], cnt), OC.conv_bwd_weight(dYv, Av, m), "bf16", zero_w, "dW")
+    dW = ard.conv_bwd_weight(dYd, Ad, sel["keep"], cnt)
+    e3 = assert_parity(dW, OC.conv_bwd_weight(dYv, Av, m), "bf16", zero_w, "dW")
     print(f"config 5 max rel err: Y {e1:.2e} dA {e2:.2e} dW {e3:.2e}", flush=True)
+    # the layer as the benchmark issues it: one workspace, grids shared between the passes
+    _check_grid_sharing(Ad, Wd, dYd, sel["keep"], cnt, 3, 1, ard.conv_fwd(Ad, Wd, sel["keep"], cnt),
+                        ard.conv_bwd_data(dYd, Wd, sel["keep"], cnt, (28, 28)), dW)
