@@ -580,29 +580,73 @@ __global__ void pack_weights_grid_kernel(const uint16_t* Wt, const int* keep, in
   out[idx] = v;
 }
 
-// planes of dropped channels of an NCHW tensor to +0.0 (the GEMM writes the kept ones)
-__global__ __launch_bounds__(256) void zero_dropped_planes_kernel(uint16_t* dst, const int* rank, int C, int HW) {
-  const int c = blockIdx.x, n = blockIdx.y;
-  if (rank[c] >= 0) return;
-  uint16_t* p = dst + ((long)n * C + c) * HW;
-  for (int i = threadIdx.x; i < HW; i += 256) p[i] = 0;
+// position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
+__device__ __forceinline__ int kept_rank(const int* keep, int n_keep, int c) {
+  int lo = 0, hi = n_keep - 1;
+  while (lo <= hi) {
+    const int mid = (lo + hi) >> 1, v = keep[mid];
+    if (v == c) return mid;
+    if (v < c) lo = mid + 1;
+    else hi = mid - 1;
+  }
+  return -1;
 }
 
-// dW[co][c][tap] = sum over splits of part[sp][co][tap*Cp + rank(c)] (dropped channels: +0.0)
-__global__ void wgrad_grid_reduce_kernel(const float* part, const int* rank, int splits, int Cout, int C, int taps, int Cp,
-                                         uint16_t* dWt) {
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  const long total = (long)Cout * C * taps;
-  if (idx >= total) return;
-  const int tap = (int)(idx % taps);
-  const int c = (int)((idx / taps) % C);
-  const int co = (int)(idx / ((long)taps * C));
+// planes of dropped channels of an NCHW tensor to +0.0 (the GEMM writes the kept ones); a workgroup
+// takes one channel of ZP_IMGS images, 16-byte stores where the planes allow them
+constexpr int ZP_IMGS = 8;
+__global__ __launch_bounds__(256) void zero_dropped_planes_kernel(uint16_t* dst, const int* keep, int n_keep, int N, int C,
+                                                                  int HW, int vec) {
+  const int c = blockIdx.x;
+  if (kept_rank(keep, n_keep, c) >= 0) return;
+  const int n0 = blockIdx.y * ZP_IMGS, n1 = min(n0 + ZP_IMGS, N);
+  if (vec) {
+    const int chunks = HW >> 3;
+    for (int i = threadIdx.x; i < (n1 - n0) * chunks; i += 256) {
+      const int n = n0 + i / chunks, q = i % chunks;
+      *reinterpret_cast<uint4*>(dst + ((long)n * C + c) * HW + q * 8) = make_uint4(0, 0, 0, 0);
+    }
+  } else {
+    for (int i = threadIdx.x; i < (n1 - n0) * HW; i += 256) dst[((long)(n0 + i / HW) * C + c) * HW + i % HW] = 0;
+  }
+}
+
+// dW[co][c][tap] = sum over splits of part[sp][co][tap*Cp + rank(c)] (dropped channels: +0.0).
+// A thread owns one kept synapse (co, tap, r): consecutive threads read consecutive r (coalesced), the
+// loads of the splits are independent and summed in split order.  The same launch writes the zeros of
+// the dropped channels (its first gridDim.x - zero_blocks workgroups sum, the rest zero).
+__global__ __launch_bounds__(256) void wgrad_grid_reduce_kernel(const float* part, const int* keep, int n_keep, int splits,
+                                                                int Cout, int C, int taps, int Cp, int sum_blocks,
+                                                                uint16_t* dWt) {
   const int Nn = taps * Cp;
-  float s = 0.0f;
-  const int r = rank[c];
-  if (r >= 0)
-    for (int sp = 0; sp < splits; ++sp) s += part[((long)sp * Cout + co) * Nn + tap * Cp + r];
-  dWt[idx] = f32_to_bf16_bits(s);
+  if ((int)blockIdx.x < sum_blocks) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)Cout * taps * n_keep) return;
+    const int r = (int)(idx % n_keep);
+    const int tap = (int)((idx / n_keep) % taps);
+    const int co = (int)(idx / ((long)n_keep * taps));
+    const float* p = part + (long)co * Nn + tap * Cp + r;
+    const long stride = (long)Cout * Nn;
+    float s = 0.0f;
+    int sp = 0;
+    for (; sp + 4 <= splits; sp += 4) {
+      const float v0 = p[(sp + 0) * stride], v1 = p[(sp + 1) * stride], v2 = p[(sp + 2) * stride], v3 = p[(sp + 3) * stride];
+      s += v0;
+      s += v1;
+      s += v2;
+      s += v3;
+    }
+    for (; sp < splits; ++sp) s += p[sp * stride];
+    dWt[((long)co * C + keep[r]) * taps + tap] = f32_to_bf16_bits(s);
+    return;
+  }
+  // zeros of the dropped channels: one thread per (co, c)
+  const long idx = (long)(blockIdx.x - sum_blocks) * 256 + threadIdx.x;
+  if (idx >= (long)Cout * C) return;
+  const int c = (int)(idx % C);
+  if (kept_rank(keep, n_keep, c) >= 0) return;
+  uint16_t* o = dWt + idx * taps;
+  for (int t = 0; t < taps; ++t) o[t] = 0;
 }
 
 struct ConvArgs {
@@ -797,11 +841,12 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
-    ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
-    ARD_LAUNCH_CHECK("rank_from_keep_kernel");
-    ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, a.N), dim3(256), 0, stream, (uint16_t*)out, (const int*)w.rank,
-                       a.C, a.H * a.W);
-    ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
+    if (Ck < a.C) {
+      const int hw = a.H * a.W;
+      ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, ceil_div(a.N, ZP_IMGS)), dim3(256), 0, stream, (uint16_t*)out,
+                 (const int*)d_keep, Ck, a.N, a.C, hw, (int)((hw % 8) == 0 && al16c(out)));
+      ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
+    }
     ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck};
     return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
@@ -818,8 +863,6 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   if (!(a.reuse & ARD_CONV_REUSE_DY))
     st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cpy, margin, w.grid_y, stream);
   if (st) return st;
-  ARD_LAUNCH(rank_from_keep_kernel, dim3(1), dim3(1024), 0, stream, (const int*)d_keep, Ck, a.C, w.rank);
-  ARD_LAUNCH_CHECK("rank_from_keep_kernel");
   const int Kq = a.N * Hg * Wg, Nn = taps * Cpa;
   FastParams F{};
   F.A = w.grid_y + y_shift * Cpy;
@@ -855,9 +898,10 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   st = big ? launch_direct_kernel<false, false, 256, 128, 8, 2>(F, direct_plain_grid(F.total_tiles), stream)
            : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
   if (st) return st;
-  const long total = (long)a.Cout * a.C * taps;
-  ARD_LAUNCH(wgrad_grid_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                     (const float*)w.gpart, (const int*)w.rank, splits, a.Cout, a.C, taps, Cpa, (uint16_t*)out);
+  const int sum_blocks = (int)(((long)a.Cout * taps * Ck + 255) / 256);
+  const int zero_blocks = Ck < a.C ? (int)(((long)a.Cout * a.C + 255) / 256) : 0;
+  ARD_LAUNCH(wgrad_grid_reduce_kernel, dim3((unsigned)(sum_blocks + zero_blocks)), dim3(256), 0, stream, (const float*)w.gpart,
+             (const int*)d_keep, Ck, splits, a.Cout, a.C, taps, Cpa, sum_blocks, (uint16_t*)out);
   ARD_LAUNCH_CHECK("wgrad_grid_reduce_kernel");
   return ARD_OK;
 }
