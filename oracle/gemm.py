@@ -81,3 +81,31 @@ def mlp_iteration(X0, Ws, dYL, m_hidden, store):
             dXs[l] = store(drop_gemm_bwd_data(dYs[l], Ws[l], MW, masks_out[l]))
             dYs[l - 1] = store(relu_bwd(dXs[l], Ys[l - 1]))
     return dict(X=Xs, Y=Ys, dY=dYs, dX=dXs, dW=dWs, m_in=masks_in, m_out=masks_out)
+
+
+def mlp_iteration_masked(X0, Ws, dYL, MWs, store):
+    """The same iteration with an explicit 0/1 mask MWs[l] on every weight matrix
+    (tile patterns, Section 3.2: synapses are dropped tile by tile, no neuron is;
+    a layer without a pattern gets a mask of ones).  ReLU after every layer but
+    the last; `store` as in mlp_iteration.  Returns dict(Y, dY, dW): Y[l] the
+    stored output of layer l, dY[l] the gradient at that output (after the ReLU
+    backward), dW[l] the weight gradient, zero on dropped synapses.
+    """
+    L = len(Ws)
+    Xs, Ys = [np.asarray(X0, dtype=np.float64)], []
+    for l in range(L):
+        Wm = np.asarray(Ws[l], dtype=np.float64) * MWs[l]
+        Y = Xs[l] @ Wm.T
+        if l < L - 1:
+            Y = np.maximum(Y, 0.0)
+        Y = store(Y)
+        Ys.append(Y)
+        Xs.append(Y)
+    dYs, dWs = [None] * L, [None] * L
+    dYs[L - 1] = np.asarray(dYL, dtype=np.float64)
+    for l in range(L - 1, -1, -1):
+        dWs[l] = store((dYs[l].T @ Xs[l]) * MWs[l])
+        if l > 0:
+            Wm = np.asarray(Ws[l], dtype=np.float64) * MWs[l]
+            dYs[l - 1] = store(relu_bwd(store(dYs[l] @ Wm), Ys[l - 1]))
+    return dict(Y=Ys, dY=dYs, dW=dWs)

@@ -175,3 +175,52 @@ def test_mlp_iteration_against_autograd():
     # dropped hidden units: exact zeros in activations, their weight rows/cols get zero gradient
     assert np.all(out["Y"][0][:, m_hidden[0] == 0] == 0)
     assert np.all(out["dW"][1][:, m_hidden[0] == 0] == 0) and np.all(out["dW"][1][m_hidden[1] == 0, :] == 0)
+
+
+def test_masked_iteration_reduces_to_the_row_pattern_iteration():
+    """With MW = outer(m_out, m_in) the synapse-masked chain is the neuron-masked one."""
+    rng = np.random.default_rng(23)
+    sizes, B = (9, 14, 10, 4), 6
+    X0 = rng.uniform(0, 1, (B, sizes[0]))
+    Ws = [rng.standard_normal((sizes[l + 1], sizes[l])) * 0.5 for l in range(3)]
+    dYL = rng.standard_normal((B, sizes[-1]))
+    m = [P.row_mask(14, 3, 1), P.row_mask(10, 2, 2)]
+    ones = lambda n: np.ones(n, np.uint8)
+    MWs = [G.weight_mask_rows(m[0], ones(9)), G.weight_mask_rows(m[1], m[0]), G.weight_mask_rows(ones(4), m[1])]
+    a = G.mlp_iteration(X0, Ws, dYL, m, R.identity)
+    b = G.mlp_iteration_masked(X0, Ws, dYL, MWs, R.identity)
+    for l in range(3):
+        assert np.allclose(a["Y"][l], b["Y"][l], atol=1e-13) and np.allclose(a["dW"][l], b["dW"][l], atol=1e-12)
+    for l in range(2):
+        assert np.allclose(a["dY"][l], b["dY"][l], atol=1e-12)
+
+
+def test_masked_iteration_against_autograd():
+    """Tile-masked weights on the two hidden layers (Section 3.2) against torch autograd."""
+    import torch
+    rng = np.random.default_rng(29)
+    sizes, B = (12, 16, 8, 5), 5
+    X0 = rng.uniform(0, 1, (B, sizes[0]))
+    Ws = [rng.standard_normal((sizes[l + 1], sizes[l])) * 0.5 for l in range(3)]
+    dYL = rng.standard_normal((B, sizes[-1]))
+    MWs = [P.expand_tile_mask(P.tile_mask(16, 12, 4, 4, 3, 2), 16, 12, 4, 4).astype(np.float64),
+           P.expand_tile_mask(P.tile_mask(8, 16, 4, 4, 2, 1), 8, 16, 4, 4).astype(np.float64), np.ones((5, 8))]
+    out = G.mlp_iteration_masked(X0, Ws, dYL, MWs, R.identity)
+    tW = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in Ws]
+    x = torch.tensor(X0, dtype=torch.float64)
+    acts = []
+    for l in range(3):
+        x = x @ (tW[l] * torch.tensor(MWs[l])).T
+        if l < 2:
+            x = torch.relu(x)
+        x.retain_grad()
+        acts.append(x)
+    (x * torch.tensor(dYL)).sum().backward()
+    assert np.allclose(out["Y"][2], x.detach().numpy(), atol=1e-12)
+    for l in range(3):
+        assert np.allclose(out["dW"][l], tW[l].grad.numpy(), atol=1e-11), l
+        assert np.all(out["dW"][l][MWs[l] == 0] == 0)
+    # gradient at a hidden output after the ReLU backward = autograd's gradient at the post-ReLU activation
+    # gated by the activation's sign
+    for l in range(2):
+        assert np.allclose(out["dY"][l], acts[l].grad.numpy() * (acts[l].detach().numpy() > 0), atol=1e-11)
