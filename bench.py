@@ -74,9 +74,11 @@ class MlpChain:
     weight compactions are leaves.  The plan puts them on a second lane (its own stream and
     workspace) so they overlap with the activation / data-gradient chain on the main lane."""
 
-    def __init__(self, ard, torch, wl):
+    def __init__(self, ard, torch, wl, sizes=None, batch=None, ws_bytes=1 << 24):
         to_dev = lambda a, _dt: ard.to_device(a)
         self.ard, self.torch = ard, torch
+        SIZES = self.sizes = tuple(sizes) if sizes else globals()["SIZES"]
+        BATCH = self.B = batch if batch else globals()["BATCH"]
         self.lib = ard.lib()
         dt = torch.bfloat16
         self.X0 = to_dev(wl.arrays["X0"], "bf16")
@@ -92,7 +94,7 @@ class MlpChain:
         self.dW = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda") for w in self.W]
         self.Wc = [torch.empty((p8(w.shape[0]), p8(w.shape[1])), dtype=dt, device="cuda")
                    for w in self.W[1:]]   # kept blocks of W2, W3 (axes padded to multiples of 8)
-        self.ws = [torch.empty(1 << 24, dtype=torch.uint8, device="cuda") for _ in range(3)]  # one per call of a level
+        self.ws = [torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") for _ in range(3)]  # one per call of a level
         self.main = torch.cuda.Stream()
         self.side = torch.cuda.Stream()
         self._keep = []
@@ -114,7 +116,7 @@ class MlpChain:
         neurons are stored); W2's kept block is gathered once per iteration and shared by the
         forward and the data-gradient product (the 10-neuron last layer reads W3 through the map); weight gradients are written in full, or, with
         compact_dw, as the gradient of the kept synapses only (a reported variant, not the headline)."""
-        lib, B = self.lib, BATCH
+        lib, B, SIZES = self.lib, self.B, self.sizes
         p1, p2 = self._pat(*pats[0]), self._pat(*pats[1])
         k1 = self.ard.kept_count(self.ard.Pattern.row(*pats[0]), SIZES[1])
         k2 = self.ard.kept_count(self.ard.Pattern.row(*pats[1]), SIZES[2])
@@ -155,6 +157,36 @@ class MlpChain:
             ("wait", 1, 0),
             call(1, bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), p1, None, 1.0, 0.0, OUT | DW1), "L1.bwd_weight", f * SIZES[0] * k1, 4, 0),
             ("wait", 0, 1),
+        ]
+
+    def plan_tile(self, pats, tile=32):
+        """The same iteration under TILE patterns (Section 3.2) on the two hidden layers' weights: synapses
+        are dropped tile by tile, every neuron stays, so activations are full size and no weight is gathered."""
+        lib, B, SIZES = self.lib, self.B, self.sizes
+        A = self.ard
+        mk = lambda dp, b: A.CPattern(A.PAT_TILE, dp, b, tile, tile, 0, None, None, None, None, None)
+        t1, t2 = mk(*pats[0]), mk(*pats[1])
+        self._keep += [t1, t2]
+        t1, t2 = C.byref(t1), C.byref(t2)
+        X0, (W1, W2, W3), (Y1, Y2, Y3), (dY1, dY2), (dW1, dW2, dW3) = self.X0, self.W, self.Y, self.dYh, self.dW
+        P = lambda t: t.data_ptr()
+        bf, n = A.BF16, self.ws[0].numel()
+        wsp = [P(w) for w in self.ws]
+        st = self.main.cuda_stream
+        fwd, bwd_d, bwd_w = lib.ard_drop_gemm_fwd, lib.ard_drop_gemm_bwd_data, lib.ard_drop_gemm_bwd_weight
+        f = 2.0 * B * tile * tile
+        kt = lambda l, pat: -(-(-(-SIZES[l + 1] // tile) * -(-SIZES[l] // tile) - (pat[1] - 1)) // pat[0])   # kept tiles
+        k1, k2 = kt(0, pats[0]), kt(1, pats[1])
+        call = lambda fn, args, name, flops, level, slot: ("call", 0, fn, args + (wsp[slot], n, st), name, flops, level)
+        return [
+            call(fwd, (bf, B, SIZES[0], SIZES[1], P(X0), P(W1), P(Y1), t1, None, 1.0, 1, 0), "L1.fwd", f * k1, 0, 0),
+            call(fwd, (bf, B, SIZES[1], SIZES[2], P(Y1), P(W2), P(Y2), t2, None, 1.0, 1, 0), "L2.fwd", f * k2, 1, 0),
+            call(bwd_w, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(Y2), P(dW3), None, None, 1.0, 0.0, 0), "L3.bwd_weight", 2.0 * B * SIZES[2] * SIZES[3], 2, 1),
+            call(fwd, (bf, B, SIZES[2], SIZES[3], P(Y2), P(W3), P(Y3), None, None, 1.0, 0, 0), "L3.fwd", 2.0 * B * SIZES[2] * SIZES[3], 2, 0),
+            call(bwd_d, (bf, B, SIZES[2], SIZES[3], P(self.dYL), P(W3), P(dY2), None, None, 1.0, P(Y2), 0), "L3.bwd_data", 2.0 * B * SIZES[2] * SIZES[3], 2, 2),
+            call(bwd_w, (bf, B, SIZES[1], SIZES[2], P(dY2), P(Y1), P(dW2), t2, None, 1.0, 0.0, 0), "L2.bwd_weight", f * k2, 3, 1),
+            call(bwd_d, (bf, B, SIZES[1], SIZES[2], P(dY2), P(W2), P(dY1), t2, None, 1.0, P(Y1), 0), "L2.bwd_data", f * k2, 3, 0),
+            call(bwd_w, (bf, B, SIZES[0], SIZES[1], P(dY1), P(X0), P(dW1), t1, None, 1.0, 0.0, 0), "L1.bwd_weight", f * k1, 4, 0),
         ]
 
     def calls(self, plan):
@@ -256,9 +288,10 @@ class MlpChain:
         return Y3, dW1, dW2, dW3
 
 
-def dense_flops_per_iter():
-    f = 2.0 * BATCH
-    l1, l2, l3 = SIZES[0] * SIZES[1], SIZES[1] * SIZES[2], SIZES[2] * SIZES[3]
+def dense_flops_per_iter(sizes=None, batch=None):
+    sizes, batch = sizes or SIZES, batch or BATCH
+    f = 2.0 * batch
+    l1, l2, l3 = sizes[0] * sizes[1], sizes[1] * sizes[2], sizes[2] * sizes[3]
     return f * (2 * l1 + 3 * l2 + 3 * l3)      # fwd x3, dW x3, dX for L2 and L3
 
 
@@ -631,6 +664,52 @@ def extra_lstm(ard, torch):
     return res
 
 
+def extra_table1(ard, torch):
+    """The network sweep of the paper's Table 1 (Section 7.2.2): MLP 784-h1-h2-10, batch 128, rate 0.7, ROW and
+    TILE (32 x 32) patterns from the searched distribution, against the same chain with nothing dropped."""
+    from paper_2203_05705_amd import workloads as WL
+    _, cdf = ard.search_k(0.7, N_PATTERNS)
+    paper = {(1024, 64): (1.27, 1.19), (1024, 1024): (1.45, 1.41), (2048, 2048): (1.77, 1.60), (4096, 4096): (2.16, 1.95)}
+    res = {}
+    for (h1, h2), (p_row, p_tile) in paper.items():
+        sizes = (784, h1, h2, 10)
+        chain = MlpChain(ard, torch, WL.mlp_chain(seed=SEED, B=128, sizes=sizes), sizes=sizes, batch=128, ws_bytes=1 << 26)
+        pats = [tuple(ard.pattern_sample(cdf, SEED, it, layer) for layer in (1, 2)) for it in range(100)]
+        t_dense = time_steps(torch, chain, [chain.plan(((1, 1), (1, 1)))], 50, 5, "grouped")["median"]
+        t_row = time_steps(torch, chain, [chain.plan(pp) for pp in pats], 50, 5, "grouped")["median"]
+        t_tile = time_steps(torch, chain, [chain.plan_tile(pp) for pp in pats], 50, 5, "grouped")["median"]
+        res[f"{h1}x{h2}"] = dict(dense_us=round(t_dense * 1e6, 1), row_us=round(t_row * 1e6, 1), tile_us=round(t_tile * 1e6, 1),
+                                 row_speedup=round(t_dense / t_row, 3), tile_speedup=round(t_dense / t_tile, 3),
+                                 paper_row_speedup_gtx1080ti=p_row, paper_tile_speedup_gtx1080ti=p_tile)
+        del chain
+    return res
+
+
+def extra_lstm_batch_scaling(ard, torch):
+    """Section 7.2.3: LSTM layer with 1500 hidden units, sequence length 35, batch 20 and 40; row pattern on the
+    hidden units at dp = 2 and 3 against dp = 1."""
+    from paper_2203_05705_amd import workloads as WL
+    res = {}
+    for B in (20, 40):
+        wl = WL.lstm_layer(seed=4, T=35, B=B, I=1500, H=1500)
+        x, Wl, dh = (ard.to_device(wl.arrays[k]) for k in ("x", "W", "dh"))
+        T, _, I = x.shape
+        row = {}
+        for dp in (1, 2, 3):
+            pat = ard.Pattern.row(dp, 1) if dp > 1 else None
+            ws = torch.empty(ard.lstm_workspace_bytes(ard.BF16, T, B, I, 1500, pat), dtype=torch.uint8, device="cuda")
+            out = ard.lstm_fwd(x, Wl, pat, ws=ws)
+            h, c, g = out
+            gout = ard.lstm_bwd(x, Wl, pat, h, c, g, dh, ws=ws)
+            fwd = event_us(torch, lambda: ard.lstm_fwd(x, Wl, pat, ws=ws, out=out), reps=5, warm=2, blocks=3)["median"]
+            bwd = event_us(torch, lambda: ard.lstm_bwd(x, Wl, pat, h, c, g, dh, ws=ws, out=gout), reps=5, warm=2, blocks=3)["median"]
+            row[f"dp{dp}_fwd_bwd_us"] = round(fwd + bwd, 1)
+        row["speedup_dp2"] = round(row["dp1_fwd_bwd_us"] / row["dp2_fwd_bwd_us"], 3)
+        row["speedup_dp3"] = round(row["dp1_fwd_bwd_us"] / row["dp3_fwd_bwd_us"], 3)
+        res[f"batch{B}"] = row
+    return res
+
+
 def only_call(args, ard, torch, chain):
     """Profiling aid: issue one call in a tight loop so that a rocprofv3 run sees little else."""
     name = args.only_call
@@ -760,7 +839,9 @@ def main():
         extra = {"tile_gemm_4096_bf16_tile64": extra_tile_gemm(ard, torch, rooflines),
                  "conv_fmap_drop_128x256x28x28_bf16": extra_conv(ard, torch, rooflines),
                  "lstm_1024_1024_b128_t64_bf16": extra_lstm(ard, torch),
-                 "small_and_hbm_bound": extra_small(ard, torch)}
+                 "small_and_hbm_bound": extra_small(ard, torch),
+                 "table1_mlp_sweep_batch128_rate0.7": extra_table1(ard, torch),
+                 "lstm_1500_t35_batch_scaling": extra_lstm_batch_scaling(ard, torch)}
         result["roofline_large_shapes"] = rooflines
         result["extra"] = extra
     if not args.no_cpu:

@@ -128,13 +128,15 @@ def test_expanded_outputs_from_compact_inputs_large(I):
 
 
 class _Config2:
-    """BASELINE config 2 (MLP 784-2048-2048-10, batch 1024, bf16), loaded once per session."""
-    _inst = None
+    """An MLP chain workload on the device, loaded once per session: BASELINE config 2 (MLP 784-2048-2048-10,
+    batch 1024, bf16) by default, or the same recipe at other sizes (Table 1 of the paper, batch 128)."""
+    _cache = {}
 
     @classmethod
-    def get(cls):
-        if cls._inst is None:
-            wl = WL.mlp_chain(seed=2)
+    def get(cls, sizes=(784, 2048, 2048, 10), B=1024):
+        key = (tuple(sizes), B)
+        if key not in cls._cache:
+            wl = WL.mlp_chain(seed=2, B=B, sizes=tuple(sizes))
             c = cls()
             c.sizes, c.B = wl.params["sizes"], wl.params["B"]
             c.X0v, c.dYLv = wl.values("X0"), wl.values("dY")
@@ -143,11 +145,11 @@ class _Config2:
             c.W = [to_dev(wl.arrays[f"W{l}"], "bf16") for l in (1, 2, 3)]
             c.dYLc = ard.pad_compact(c.dYL)
             c.batch_ws = [torch.empty(1 << 27, dtype=torch.uint8, device="cuda") for _ in range(3)]
-            cls._inst = c
-        return cls._inst
+            cls._cache = {key: c}      # one workload at a time stays on the device
+        return cls._cache[key]
 
 
-def _check_config2_iteration(pats, what):
+def _check_config2_iteration(pats, what, sizes=(784, 2048, 2048, 10), B=1024):
     """Every product the benchmark's plan issues for the patterns `pats` = ((dp1,b1),(dp2,b2)), with the
     benchmark's layout flags, each fed with the oracle's stored activations so that it is checked on its
     own: L1.fwd, L2.compact_w, L2.fwd, L3.fwd, L3.bwd_weight, L3.bwd_data, L2.bwd_weight, L2.bwd_data,
@@ -157,7 +159,7 @@ def _check_config2_iteration(pats, what):
     check_compact_r = partial(check_compact, rounded_ref=True)
     check_compact_dw_r = partial(check_compact_dw, rounded_ref=True)
     assert_parity_r = partial(assert_parity, rounded_ref=True)
-    c = _Config2.get()
+    c = _Config2.get(sizes, B)
     sizes, W = c.sizes, c.W
     IN, OUT, WC = ard.IN_COMPACT, ard.OUT_COMPACT, ard.W_COMPACT
     masks = [P.row_mask(sizes[l + 1], *pats[l]) for l in range(2)]
@@ -261,6 +263,53 @@ def test_config2_every_pattern_pair(dp1):
         pats = [(dp1, int(rng.integers(1, dp1 + 1))), (dp2, int(rng.integers(1, dp2 + 1)))]
         print(f"pair {pats}", flush=True)
         _check_config2_iteration(pats, f"pair {pats}")
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("h1,h2", [(1024, 64), (1024, 1024), (2048, 2048), (4096, 4096)])
+def test_table1_networks_row_pattern(h1, h2):
+    """The four hidden-layer shapes of the paper's Table 1 (Section 7.2.2), batch 128 (Section 7.2.1), rate 0.7:
+    patterns of iterations 0..2 from the searched distribution, every product of the chain against the oracle."""
+    from oracle import sampler as S
+    from oracle import search as K
+    d, _ = K.search_k(0.7, 8)
+    cdf = [int(c) for c in K.fixed_point_cdf(d)]
+    for it in range(3):
+        pats = [S.sample_pattern(cdf, 2, it, layer) for layer in (1, 2)]
+        print(f"table 1 network {h1}x{h2} iteration {it}: patterns {pats}", flush=True)
+        _check_config2_iteration(pats, f"{h1}x{h2} it {it}", sizes=(784, h1, h2, 10), B=128)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("h1,h2,B", [(1024, 64, 128), (2048, 2048, 128), (4096, 4096, 128), (2048, 2048, 1024)])
+def test_mlp_chain_under_tile_patterns(h1, h2, B):
+    """Tile-based pattern (Section 3.2, 32 x 32 tiles as in the paper) on both hidden layers' weights: forward,
+    data gradients with the ReLU backward fused, weight gradients, against the oracle's synapse-masked chain."""
+    from oracle import sampler as S
+    from oracle import search as K
+    sizes = (784, h1, h2, 10)
+    c = _Config2.get(sizes, B)
+    d, _ = K.search_k(0.7, 8)
+    cdf = [int(v) for v in K.fixed_point_cdf(d)]
+    x = y = 32
+    for it in range(2):
+        pats = [S.sample_pattern(cdf, 2, it, layer) for layer in (1, 2)]
+        print(f"tile chain {h1}x{h2} B={B} iteration {it}: patterns {pats}", flush=True)
+        MWs = [P.expand_tile_mask(P.tile_mask(sizes[l + 1], sizes[l], x, y, *pats[l]), sizes[l + 1], sizes[l], x, y).astype(np.float64)
+               for l in range(2)] + [np.ones((sizes[3], sizes[2]))]
+        ref = G.mlp_iteration_masked(c.X0v, c.Wv, c.dYLv, MWs, R.to_bf16_values)
+        t1, t2 = ard.Pattern.tile(*pats[0], x, y), ard.Pattern.tile(*pats[1], x, y)
+        ap = lambda t, r, w, zm=None: assert_parity(t, r, "bf16", zero_mask=zm, what=f"tile chain it {it} {w}", rounded_ref=True)
+        Y1o, Y2o = from_vals(ref["Y"][0], "bf16"), from_vals(ref["Y"][1], "bf16")
+        dY2o, dY1o = from_vals(ref["dY"][1], "bf16"), from_vals(ref["dY"][0], "bf16")
+        ap(ard.drop_gemm_fwd(c.X0, c.W[0], t1, relu=True), ref["Y"][0], "Y1")
+        ap(ard.drop_gemm_fwd(Y1o, c.W[1], t2, relu=True), ref["Y"][1], "Y2")
+        ap(ard.drop_gemm_fwd(Y2o, c.W[2]), ref["Y"][2], "Y3")
+        ap(ard.drop_gemm_bwd_weight(c.dYL, Y2o), ref["dW"][2], "dW3")
+        ap(ard.drop_gemm_bwd_data(c.dYL, c.W[2], relu_src=Y2o), ref["dY"][1], "dY2")
+        ap(ard.drop_gemm_bwd_weight(dY2o, Y1o, t2), ref["dW"][1], "dW2", MWs[1] == 0)
+        ap(ard.drop_gemm_bwd_data(dY2o, c.W[1], t2, relu_src=Y1o), ref["dY"][0], "dY1")
+        ap(ard.drop_gemm_bwd_weight(dY1o, c.X0, t1), ref["dW"][0], "dW1", MWs[0] == 0)
     torch.cuda.synchronize()
 
 
