@@ -275,7 +275,8 @@ typedef enum {
   ARD_CONV_SELECT = 0,    /* sensitivity score + selection -> d_mask, d_keep, d_count, d_score */
   ARD_CONV_FWD = 1,       /* out = Y[N,Cout,Ho,Wo]                                        */
   ARD_CONV_BWD_DATA = 2,  /* out = dA[N,C,H,W], dropped channels exactly 0               */
-  ARD_CONV_BWD_WEIGHT = 3 /* out = dWt[Cout,C,KH,KW], dropped channels exactly 0         */
+  ARD_CONV_BWD_WEIGHT = 3,/* out = dWt[Cout,C,KH,KW], dropped channels exactly 0         */
+  ARD_CONV_FWD_ROWS = 4   /* out = Y under a row-based sensitivity-aware pattern (below)  */
 } ard_conv_mode;
 /*
  * bf16, stride 1: every pass first copies what it convolves into a channels-last, zero-bordered grid
@@ -304,6 +305,11 @@ size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, 
  *   channels that come first in ascending (score, channel) order are dropped.
  *   Writes d_mask[C] (1 = kept), d_keep[C - floor(rate*C)] ascending, d_count[1]
  *   and, if non-NULL, d_score[C] (int64).  Needs N*H*Wd <= 2^24.
+ * FWD_ROWS (row-based sensitivity-aware pattern, Section 5.2.1): every channel takes part, but only the
+ *   kept rows of the input matrix (= output positions) are gathered and multiplied; d_keep lists them
+ *   as n * Ho*Wo + p, ascending, n_keep entries (0 .. N*Ho*Wo), d_mask[N*Ho*Wo] is the same set as a
+ *   0/1 mask (both as written by ard_sens_row_pattern).  out = Y[N,Cout,Ho,Wo], dropped positions +0.0.
+ *   Needs A, Wt.  fp32 and strided layers compute every position and zero the dropped ones.
  * FWD / BWD_DATA / BWD_WEIGHT read the kept channels from d_keep (n_keep entries,
  *   n_keep given on the host) and never load a dropped channel:
  *   FWD        Y  = conv(A restricted to kept channels, Wt)       needs A, Wt
@@ -317,6 +323,49 @@ int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype,
                            const void* A, const void* Wt, const void* dYin, void* out,
                            uint8_t* d_mask, int32_t* d_keep, int32_t* d_count, int64_t* d_score,
                            void* ws, size_t ws_bytes, void* stream);
+
+/* ---- sensitivity prediction and sensitivity-aware patterns (Sections 5.1, 5.2) ---- */
+
+/*
+ * The input matrix of one image (Section 5.1) has one row per output position p = oh*Wo + ow and one
+ * column per (c, kh, kw), q = (c*kh_size + kh)*kw_size + kw; its entries are the zero-padded
+ * activations.  It is cut into x-by-y regions (y = 0: regions span the whole width), edge regions
+ * clipped: row band rb = p / x, column block cb = q / y, region id (image*RB + rb)*CB + cb.
+ * ard_sens_regions returns rows = Ho*Wo, RB and CB for buffer sizing (host only).
+ *
+ * Random draws: the 32-bit word u(seed, iteration, stream, index) = upper half of the SplitMix64
+ * finaliser chained over the four values (as ard_pattern_sample chains three), streams 0x5E01
+ * (samples), 0x5E02 (rows), 0x5E03 (blocks).  A possibility p becomes the threshold floor(p * 2^32)
+ * and a unit is dropped iff u < threshold.
+ *
+ * ard_sens_predict (steps 2, 3): per region, s = max(1, k_permille * size / 1000) draws with
+ *   replacement (at most 65536), draw j (index region*65536 + j) picks element (u * size) >> 32 of the
+ *   region in row-major order; d_count = how many drawn entries exceed `threshold`, d_samples = s,
+ *   d_sens = 1 iff 1000 * count >= t_permille * s.  All three are device arrays of N*RB*CB entries.
+ * ard_sens_row_pattern (Section 5.2.1; regions span the width, d_sens[N*RB]): row g = image*rows + p is
+ *   dropped with possibility m if its band is sensitive, n otherwise (index g).  Writes d_mask[N*rows]
+ *   (1 = kept, Section 6), the ascending kept list d_keep[>= kept] and d_count[1]; any may be NULL.
+ * ard_sens_block_pattern (Section 5.2.2): the blocks of one row band form a group.  balance != 0:
+ *   S = mean number of sensitive blocks per group of the image, rounded half up; in every group the
+ *   S blocks with the largest share count/samples (exact comparison, ties to the lower block) become
+ *   the sensitive ones (d_sens_out, may be NULL), so all groups hold the same number.  Then block
+ *   (image*RB + rb)*CB + cb (= its index) is dropped with possibility m (sensitive) or n:
+ *   d_block_keep[N*RB*CB], 1 = kept.
+ * The paper fixes none of these procedures beyond k, t, the threshold and m < n; see the oracle's notes.
+ */
+int32_t ard_sens_regions(int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                         int32_t x, int32_t y, int32_t* rows, int32_t* row_bands, int32_t* col_blocks);
+int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t kh, int32_t kw,
+                         int32_t stride, int32_t pad, int32_t x, int32_t y, int32_t k_permille, int32_t t_permille,
+                         float threshold, uint64_t seed, uint64_t iteration, const void* A,
+                         int32_t* d_count, int32_t* d_samples, uint8_t* d_sens, void* stream);
+int32_t ard_sens_row_pattern(int32_t N, int32_t rows, int32_t x, const uint8_t* d_sens, double m, double n,
+                             uint64_t seed, uint64_t iteration, uint8_t* d_mask, int32_t* d_keep, int32_t* d_count,
+                             void* stream);
+int32_t ard_sens_block_pattern(int32_t N, int32_t row_bands, int32_t col_blocks, const int32_t* d_count,
+                               const int32_t* d_samples, const uint8_t* d_sens, int32_t balance, double m, double n,
+                               uint64_t seed, uint64_t iteration, uint8_t* d_sens_out, uint8_t* d_block_keep,
+                               void* stream);
 
 /* ---- dynamic dropout-ratio tuning (Section 5.3, host only) ---------------- */
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libard.so")
 
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
-CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT = 0, 1, 2, 3
+CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT, CONV_FWD_ROWS = 0, 1, 2, 3, 4
 CONV_REUSE_A, CONV_REUSE_DY = 0x100, 0x200
 IN_COMPACT, OUT_COMPACT, W_COMPACT, DW_COMPACT = 1, 2, 4, 8
 
@@ -95,6 +95,10 @@ _SIGS = {
     "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
     "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
+    "ard_sens_regions": (C.c_int32, [C.c_int32] * 10 + [C.c_void_p] * 3),
+    "ard_sens_predict": (C.c_int32, [C.c_int32] * 13 + [C.c_float, C.c_uint64, C.c_uint64] + [C.c_void_p] * 5),
+    "ard_sens_row_pattern": (C.c_int32, [C.c_int32] * 3 + [C.c_void_p, C.c_double, C.c_double, C.c_uint64, C.c_uint64] + [C.c_void_p] * 4),
+    "ard_sens_block_pattern": (C.c_int32, [C.c_int32] * 3 + [C.c_void_p] * 3 + [C.c_int32, C.c_double, C.c_double, C.c_uint64, C.c_uint64] + [C.c_void_p] * 3),
     "ard_skew_normal_params": (C.c_int32, [C.c_double] * 3 + [C.c_void_p] * 2),
     "ard_skew_normal_pdf": (C.c_double, [C.c_double] * 4),
     "ard_prune_schedule": (C.c_int32, [C.c_int32] + [C.c_double] * 5 + [C.c_void_p]),
@@ -471,6 +475,62 @@ def conv_select(A, rate, Cout=1, ksize=(3, 3), stride=1, pad=1, ws=None, stream=
     fmap_drop_conv(CONV_SELECT, A.shape, _dtype_code(A), Cout, ksize, stride, pad, rate=rate, A=A, mask=out["mask"],
                    keep=out["keep"], count=out["count"], score=out["score"], ws=ws, stream=stream)
     return out
+
+
+def sens_regions(shape, ksize, stride, pad, x, y=0):
+    """(rows, row_bands, col_blocks) of the input matrix of one image under x-by-y regions."""
+    N, Cc, H, W = shape
+    r, rb, cb = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().ard_sens_regions(N, Cc, H, W, ksize[0], ksize[1], stride, pad, x, y, C.byref(r), C.byref(rb), C.byref(cb)))
+    return r.value, rb.value, cb.value
+
+
+def sens_predict(A, ksize, stride, pad, x, y, k_permille, t_permille, threshold, seed, iteration, stream=None):
+    """Region-level sensitivity prediction: dict(count, samples, sens), each [N, RB, CB] on the device."""
+    _dev(A)
+    N = A.shape[0]
+    _, RB, CB = sens_regions(A.shape, ksize, stride, pad, x, y)
+    out = dict(count=_out((N, RB, CB), torch.int32, A.device), samples=_out((N, RB, CB), torch.int32, A.device),
+               sens=_out((N, RB, CB), torch.uint8, A.device))
+    _check(lib().ard_sens_predict(_dtype_code(A), N, A.shape[1], A.shape[2], A.shape[3], ksize[0], ksize[1], stride, pad, x, y,
+                                  k_permille, t_permille, float(threshold), seed, iteration, A.data_ptr(),
+                                  out["count"].data_ptr(), out["samples"].data_ptr(), out["sens"].data_ptr(), _stream(stream)))
+    return out
+
+
+def sens_row_pattern(sens, rows, x, m, n, seed, iteration, stream=None):
+    """Row-based pattern from the per-band sensitivity sens[N, RB, 1]: dict(mask[N*rows], keep, count)."""
+    _dev(sens)
+    N = sens.shape[0]
+    out = dict(mask=_out((N * rows,), torch.uint8, sens.device),
+               keep=torch.full((N * rows,), -1, dtype=torch.int32, device=sens.device),
+               count=torch.zeros(1, dtype=torch.int32, device=sens.device))
+    _check(lib().ard_sens_row_pattern(N, rows, x, sens.data_ptr(), float(m), float(n), seed, iteration, out["mask"].data_ptr(),
+                                      out["keep"].data_ptr(), out["count"].data_ptr(), _stream(stream)))
+    return out
+
+
+def sens_block_pattern(pred, balance, m, n, seed, iteration, stream=None):
+    """Block-based pattern from ard_sens_predict's outputs: dict(sens (balanced), keep), each [N, RB, CB]."""
+    N, RB, CB = pred["sens"].shape
+    dev = pred["sens"].device
+    out = dict(sens=_out((N, RB, CB), torch.uint8, dev), keep=_out((N, RB, CB), torch.uint8, dev))
+    _check(lib().ard_sens_block_pattern(N, RB, CB, pred["count"].data_ptr(), pred["samples"].data_ptr(), pred["sens"].data_ptr(),
+                                        int(bool(balance)), float(m), float(n), seed, iteration, out["sens"].data_ptr(),
+                                        out["keep"].data_ptr(), _stream(stream)))
+    return out
+
+
+def conv_fwd_rows(A, Wt, row_pat, n_keep, stride=1, pad=1, ws=None, stream=None, out=None):
+    """Forward convolution over the kept output positions of a row pattern (dict from sens_row_pattern)."""
+    _dev(A), _dev(Wt)
+    N, Cc, H, W = A.shape
+    Cout, _, kh, kw = Wt.shape
+    Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
+    Y = _out((N, Cout, Ho, Wo), A.dtype, A.device) if out is None else out
+    fmap_drop_conv(CONV_FWD_ROWS, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
+                   keep=row_pat["keep"], mask=row_pat["mask"], ws=ws, stream=stream)
+    return Y
 
 
 def _out_hw(H, W, ksize, stride, pad):

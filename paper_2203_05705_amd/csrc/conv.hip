@@ -125,7 +125,7 @@ __global__ void pack_weights_kernel(const T* Wt, const int* keep, int C, int tap
   const int q = (int)(idx % inner);
   const int tap = (int)((idx / inner) % taps);
   const int r = (int)(idx / ((long)inner * taps));
-  long src = flip ? ((long)q * C + keep[r]) * taps + (taps - 1 - tap) : ((long)r * C + keep[q]) * taps + tap;
+  long src = flip ? ((long)q * C + (keep ? keep[r] : r)) * taps + (taps - 1 - tap) : ((long)r * C + (keep ? keep[q] : q)) * taps + tap;
   out[idx] = Wt[src];
 }
 
@@ -576,8 +576,21 @@ __global__ void pack_weights_grid_kernel(const uint16_t* Wt, const int* keep, in
   const int tap = (int)((idx / Cp) % taps);
   const int r = (int)(idx / ((long)Cp * taps));
   uint16_t v = 0;
-  if (q < inner) v = flip ? Wt[((long)q * C + keep[r]) * taps + (taps - 1 - tap)] : Wt[((long)r * C + keep[q]) * taps + tap];
+  if (q < inner)
+    v = flip ? Wt[((long)q * C + (keep ? keep[r] : r)) * taps + (taps - 1 - tap)] : Wt[((long)r * C + (keep ? keep[q] : q)) * taps + tap];
   out[idx] = v;
+}
+
+// output positions of dropped rows of the input matrix to +0.0 (row-based sensitivity-aware pattern,
+// Section 5.2.1: the results of the kept rows fill the same rows of the output, the others are zero);
+// one workgroup per (channel, image) plane
+template <typename T>
+__global__ __launch_bounds__(256) void zero_dropped_pixels_kernel(T* Y, const uint8_t* row_mask, int Cout, int HW) {
+  const int co = blockIdx.x, n = blockIdx.y;
+  T* p = Y + ((long)n * Cout + co) * HW;
+  const uint8_t* m = row_mask + (long)n * HW;
+  for (int i = threadIdx.x; i < HW; i += 256)
+    if (!m[i]) p[i] = (T)0;
 }
 
 // position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
@@ -804,7 +817,7 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
 }
 
 static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, const void* dYin, void* out,
-                             const int32_t* d_keep, const ConvWs& w, hipStream_t stream) {
+                             const int32_t* d_keep, const uint8_t* row_mask, const ConvWs& w, hipStream_t stream) {
   const int taps = a.kh * a.kw, Ck = a.n_keep;
   int hgm, wgm;
   const long pix_cap = conv_grid_pixels(a, &hgm, &wgm);
@@ -816,6 +829,22 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   // (k - 1 = 2 pad) that is the bordered dY grid read from (k-1-pad) rows and columns further on.
   const long margin = (long)a.kh * wgm + a.kw + 128;
   const bool same = a.kh - 1 == 2 * a.pad && a.kw - 1 == 2 * a.pad;
+  if (a.mode == ARD_CONV_FWD_ROWS) {
+    // every channel, only the kept output positions: the product's columns are the listed pixels
+    const int Cp = pad64(a.C), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
+    int32_t st = to_grid(A, nullptr, a.C, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream);
+    if (st) return st;
+    const long total = (long)a.Cout * K;
+    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, (const uint16_t*)Wt,
+               (const int*)nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp);
+    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    ARD_LAUNCH(zero_dropped_pixels_kernel<uint16_t>, dim3(a.Cout, a.N), dim3(256), 0, stream, (uint16_t*)out, row_mask, a.Cout,
+               a.Ho * a.Wo);
+    ARD_LAUNCH_CHECK("zero_dropped_pixels_kernel");
+    if (Ck == 0) return ARD_OK;
+    ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, Ck, a.Cout, nullptr, a.Cout, (const int*)d_keep, a.N * a.Ho * a.Wo, -1};
+    return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream);
+  }
   if (a.mode == ARD_CONV_FWD) {
     const int Cp = pad64(Ck), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
     int32_t st = ARD_OK;
@@ -826,7 +855,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
-    ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout};
+    ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout, nullptr, 0, -1};
     return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
   if (a.mode == ARD_CONV_BWD_DATA) {
@@ -847,7 +876,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
                  (const int*)d_keep, Ck, a.N, a.C, hw, (int)((hw % 8) == 0 && al16c(out)));
       ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
     }
-    ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck};
+    ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck, nullptr, 0, -1};
     return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
   // BWD_WEIGHT: contraction over the pixels of the input grid; dY sits on the same grid (top-left
@@ -893,7 +922,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   F.splits = splits;
   F.M = a.Cout;
   F.N = Nn;
-  F.cv = ConvMap{0, 0, Hg * Wg, Wg, Cpa, a.kw, 0, 0, nullptr, 0};
+  F.cv = ConvMap{0, 0, Hg * Wg, Wg, Cpa, a.kw, 0, 0, nullptr, 0, nullptr, 0, -1};
   F.group_m = direct_group_m(F.total_tiles);
   st = big ? launch_direct_kernel<false, false, 256, 128, 8, 2>(F, direct_plain_grid(F.total_tiles), stream)
            : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
@@ -946,8 +975,27 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     ARD_LAUNCH_CHECK("channel_select_kernel");
     return ARD_OK;
   }
+  if (a.mode == ARD_CONV_FWD_ROWS) {
+    // d_keep lists the kept rows (output positions) of the input matrices, n * Ho*Wo + p, ascending;
+    // d_mask is the same set as a 0/1 mask
+    const long n_rows = (long)a.N * a.Ho * a.Wo;
+    if (a.n_keep < 0 || a.n_keep > n_rows) return fail(ARD_EINVAL, "n_keep=%d outside 0..%ld", a.n_keep, n_rows);
+    if (!A || !Wt || !out || !d_mask || (a.n_keep > 0 && !d_keep)) return fail(ARD_EINVAL, "FWD_ROWS needs A, Wt, out, d_mask and d_keep");
+    if (a.reuse) return fail(ARD_EUNSUPPORTED, "FWD_ROWS builds its own grid");
+    if (w.grid_a && !dev_knobs().no_fast) return conv_run_grid(a, A, Wt, nullptr, out, d_keep, d_mask, w, stream);
+    // general path (fp32, strides): every position is computed, the dropped ones are zeroed afterwards
+    ConvArgs full = a;
+    full.mode = ARD_CONV_FWD;
+    full.n_keep = a.C;
+    int32_t st = conv_run<T>(full, 0.0, A, Wt, nullptr, out, nullptr, nullptr, nullptr, nullptr, w, stream);
+    if (st) return st;
+    ARD_LAUNCH(zero_dropped_pixels_kernel<T>, dim3(a.Cout, a.N), dim3(256), 0, stream, (T*)out, (const uint8_t*)d_mask, a.Cout,
+               a.Ho * a.Wo);
+    ARD_LAUNCH_CHECK("zero_dropped_pixels_kernel");
+    return ARD_OK;
+  }
   if (a.n_keep < 0 || a.n_keep > a.C) return fail(ARD_EINVAL, "n_keep=%d outside 0..%d", a.n_keep, a.C);
-  if (a.n_keep > 0 && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
+  if (a.n_keep > 0 && a.n_keep < a.C && !d_keep) return fail(ARD_EINVAL, "d_keep is required");
   if (!out) return fail(ARD_EINVAL, "null output pointer");
   const int Ck = a.n_keep;
   if (a.reuse) {
@@ -962,7 +1010,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
     if (a.mode == ARD_CONV_BWD_WEIGHT && (!dYin || !A)) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
-    return conv_run_grid(a, A, Wt, dYin, out, d_keep, w, stream);
+    return conv_run_grid(a, A, Wt, dYin, out, d_keep, nullptr, w, stream);
   }
 
   if (a.mode == ARD_CONV_FWD) {

@@ -67,6 +67,11 @@ struct ConvMap {
   int out_chan;     // channels per image of the output tensor (NCHW)
   const int* chan;  // optional: output channel of compact row i (kept-channel list), else i
   int n_rows;       // valid compact output rows (channels)
+  // optional list of kept output pixels (row-based sensitivity-aware pattern, Section 5.2.1): compact
+  // column j of the product is pixel pix[j] of the pix_total pixels; npix then counts the kept ones.
+  // pix_fixed >= 0 (host-side bounds proof only): every column reads that pixel instead of the list.
+  const int* pix;
+  int pix_total, pix_fixed;
 };
 
 struct FastParams {
@@ -148,7 +153,9 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
     base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int row = imin(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
+      int row = imin(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
+      if (cv.pix_fixed >= 0) row = cv.pix_fixed;
+      else if (cv.pix) row = cv.pix[row];
       const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
       const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
       voff[j] = (uint32_t)((n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j)) * 2u;
@@ -719,11 +726,12 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
     const ConvMap& cv = P.cv;
     const int HW = cv.HoWo;
     const bool odd = lane & 1;
-    const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0);
+    const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0) && !cv.pix;  // (listed pixels are not adjacent)
 #pragma unroll
     for (int in = 0; in < TN; ++in) {
-      const int j = n0 + wn * WTN + in * 32 + (lane & 31);
-      if (j >= cv.npix) continue;  // npix is even whenever pair_ok, so a pair is in or out together
+      const int jc = n0 + wn * WTN + in * 32 + (lane & 31);
+      if (jc >= cv.npix) continue;  // npix is even whenever pair_ok, so a pair is in or out together
+      const int j = cv.pix ? cv.pix[jc] : jc;
       const int n = j / HW;
       uint16_t* col = P.C + (long)n * cv.out_chan * HW + (j - n * HW);
 #pragma unroll
@@ -1122,7 +1130,8 @@ static int32_t direct_envelope(const FastParams& F) {
     if (MODE == 1) {
       const ConvMap& cv = F.cv;
       if (cv.npix < 1 || cv.Cp < 64 || (cv.Cp % 64) || cv.kw < 1 || kphys % cv.Cp) return fail(ARD_ESHAPE, "bounds proof: bad grid");
-      const int row = cv.npix - 1, n = row / cv.HoWo, rem = row - n * cv.HoWo;
+      if (cv.pix && (cv.pix_total < 1 || cv.npix > cv.pix_total)) return fail(ARD_ESHAPE, "bounds proof: pixel list longer than the pixels");
+      const int row = (cv.pix ? cv.pix_total : cv.npix) - 1, n = row / cv.HoWo, rem = row - n * cv.HoWo;
       const long base = (long)n * cv.HgWg + (long)(rem / cv.Wo) * cv.Wg + rem % cv.Wo;
       const int tl = (int)(kphys / cv.Cp) - 1;  // last tap
       const long last = base + (long)(tl / cv.kw) * cv.Wg + tl % cv.kw;
@@ -1164,15 +1173,17 @@ static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) 
     if (Kn <= 0) continue;
     const int S_all = (Kn + 63) >> 6;
     const int s_lo = (int)((long)wk.split * S_all / P.splits), s_hi = (int)((long)(wk.split + 1) * S_all / P.splits);
-    for (int pass = 0; pass < 2; ++pass) {  // (second pass only differs for LIST axes)
-      if (pass == 1 && wk.am.kind != AX_LIST && wk.bn.kind != AX_LIST) break;
+    for (int pass = 0; pass < 2; ++pass) {  // (second pass only differs for LIST axes and pixel lists)
+      if (pass == 1 && wk.am.kind != AX_LIST && wk.bn.kind != AX_LIST && !P.cv.pix) break;
       const Axis am = axis_list_surrogate(wk.am, pass == 1), bn = axis_list_surrogate(wk.bn, pass == 1);
+      ConvMap cvp = P.cv;  // a pixel list lives in device memory: its two extreme readings bound it
+      if (cvp.pix) cvp.pix = nullptr, cvp.pix_fixed = pass == 1 ? cvp.pix_total - 1 : 0;
       for (int wave = 0; wave < NW; ++wave)
         for (int lane = 0; lane < 64; ++lane) {
           LA la;
           LB lb;
           la.init(P.A, P.lda, am, wk.m0, lane, wave);
-          if constexpr (MODE == 1) lb.init_pixels(P.B, P.cv, wk.n0, lane, wave);
+          if constexpr (MODE == 1) lb.init_pixels(P.B, cvp, wk.n0, lane, wave);
           else if constexpr (MODE == 2) lb.init_tap_columns(P.B, P.cv, P.N, wk.n0, lane, wave);
           else lb.init(P.B, P.ldb, bn, wk.n0, lane, wave);
           for (int s = s_lo; s < s_hi; ++s) {

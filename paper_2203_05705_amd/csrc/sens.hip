@@ -1,0 +1,254 @@
+// Region-level sensitivity prediction and the sensitivity-aware dropout patterns of the CNN variant
+// (Sections 5.1, 5.2.1, 5.2.2): which rows (output positions) or blocks of a layer's input matrix are
+// dropped in this iteration.
+//
+// The input matrix of an image has one row per output position p = oh * Wo + ow and one column per
+// (c, kh, kw), q = (c * KH + kh) * KW + kw, entry = zero-padded A[c, oh*s + kh - pad, ow*s + kw - pad];
+// it is never built: the kernels address the activations directly.  It is cut into x-by-y regions
+// (row band rb = p / x, column block cb = q / y, edge regions clipped).
+//
+// Every random draw is a 32-bit word of the SplitMix64 finaliser chained over
+// (seed, iteration, stream, index) -- stateless and integer only, so the masks are reproducible bit for
+// bit on any number of devices (the host folds the first three links, the kernels add the index).
+#include <math.h>
+
+#include "common.hpp"
+
+namespace ard {
+
+static __host__ __device__ inline uint64_t sens_mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+constexpr uint64_t kSensGolden = 0x9E3779B97F4A7C15ULL;
+enum { SENS_STREAM_SAMPLE = 0x5E01, SENS_STREAM_ROWS = 0x5E02, SENS_STREAM_BLOCKS = 0x5E03 };
+
+static uint64_t sens_prefix(uint64_t seed, uint64_t iter, uint32_t stream) {
+  uint64_t h = sens_mix64(seed + kSensGolden);
+  h = sens_mix64((h ^ iter) + kSensGolden);
+  return sens_mix64((h ^ (uint64_t)stream) + kSensGolden);
+}
+static __device__ __forceinline__ uint32_t sens_draw(uint64_t prefix, uint64_t index) {
+  return (uint32_t)(sens_mix64((prefix ^ index) + kSensGolden) >> 32);
+}
+static uint64_t sens_threshold(double p) {
+  double q = floor(p * 4294967296.0);
+  if (q < 0) q = 0;
+  if (q > 4294967296.0) q = 4294967296.0;
+  return (uint64_t)q;
+}
+
+struct SensGeom {
+  int N, C, H, W, KH, KW, stride, pad, Ho, Wo;
+  int rows, cols;  // of the input matrix of one image
+  int x, y, RB, CB;
+};
+
+// One workgroup per (image, region): s = max(1, k * size / 1000) draws with replacement, count of the
+// drawn entries above the threshold (Section 5.1, steps 2 and 3).
+template <typename T>
+__global__ __launch_bounds__(256) void sens_predict_kernel(const T* A, SensGeom g, int k_permille, int t_permille, float thr,
+                                                           uint64_t prefix, int* count, int* samples, uint8_t* sens) {
+  __shared__ int wave_cnt[4];
+  const int region = blockIdx.x;  // (image * RB + rb) * CB + cb
+  const int cb = region % g.CB, rb = (region / g.CB) % g.RB, n = region / (g.CB * g.RB);
+  const int r0 = rb * g.x, q0 = cb * g.y;
+  const int h = min(g.x, g.rows - r0), w = min(g.y, g.cols - q0);
+  const int size = h * w;
+  int s = (int)(((long)k_permille * size) / 1000);
+  if (s < 1) s = 1;
+  const T* img = A + (long)n * g.C * g.H * g.W;
+  const int taps = g.KH * g.KW;
+  int c = 0;
+  for (int j = threadIdx.x; j < s; j += 256) {
+    const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
+    const int e = (int)(((uint64_t)u * (uint64_t)size) >> 32);
+    const int p = r0 + e / w, q = q0 + e % w;
+    const int oh = p / g.Wo, ow = p - oh * g.Wo;
+    const int ch = q / taps, tap = q - ch * taps;
+    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+    const int ih = oh * g.stride + kh - g.pad, iw = ow * g.stride + kw - g.pad;
+    float v = 0.0f;  // the zero border of the input matrix
+    if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(img[((long)ch * g.H + ih) * g.W + iw]);
+    c += v > thr ? 1 : 0;
+  }
+  for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off, 64);
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int tot = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    count[region] = tot;
+    samples[region] = s;
+    sens[region] = (1000L * tot >= (long)t_permille * s) ? 1 : 0;
+  }
+}
+
+// Row-based pattern (Section 5.2.1): global row g = image * rows + p is dropped iff its draw is below the
+// possibility of its band (m if sensitive, n otherwise); mask (1 = kept) and ascending kept list by
+// ballot + mbcnt compaction, one workgroup walking all rows.
+__global__ __launch_bounds__(1024) void sens_row_pattern_kernel(const uint8_t* sens, int n_rows_total, int rows, int x, int RB,
+                                                               int CB, uint64_t tm, uint64_t tn, uint64_t prefix, uint8_t* mask,
+                                                               int* keep, int* count) {
+  __shared__ int wave_tot[16];
+  __shared__ int running_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) running_s = 0;
+  __syncthreads();
+  for (int base = 0; base < n_rows_total; base += 1024) {
+    const int gr = base + tid;
+    bool kept = false;
+    if (gr < n_rows_total) {
+      const int n = gr / rows, p = gr - n * rows;
+      const bool sv = sens[((long)n * RB + p / x) * CB] != 0;  // (regions span the width: CB = 1)
+      kept = !((uint64_t)sens_draw(prefix, (uint64_t)gr) < (sv ? tm : tn));
+      if (mask) mask[gr] = kept ? 1 : 0;
+    }
+    const unsigned long long bal = __ballot(kept);
+    const int r = __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0));
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int before = running_s, total = 0;
+    for (int w = 0; w < 16; ++w) {
+      const int t = wave_tot[w];
+      if (w < wave) before += t;
+      total += t;
+    }
+    if (kept && keep) keep[before + r] = gr;
+    __syncthreads();
+    if (tid == 0) running_s += total;
+    __syncthreads();
+  }
+  if (tid == 0 && count) *count = running_s;
+}
+
+// Block-based pattern (Section 5.2.2): one workgroup per (image, row band).  Balancing: S = mean number
+// of sensitive blocks per band of this image, rounded half up; the S blocks of the band with the
+// largest share count / samples (compared exactly by cross-multiplication, ties to the lower block)
+// are the sensitive ones.  Then every block is dropped iff its draw is below m (sensitive) or n.
+__global__ __launch_bounds__(256) void sens_block_pattern_kernel(const int* count, const int* samples, const uint8_t* sens,
+                                                                 int RB, int CB, int balance, uint64_t tm, uint64_t tn,
+                                                                 uint64_t prefix, uint8_t* sens_out, uint8_t* block_keep) {
+  __shared__ int wave_sum[4];
+  __shared__ int S_s;
+  const int band = blockIdx.x;  // image * RB + rb
+  const int n = band / RB;
+  int tot = 0;
+  for (int i = threadIdx.x; i < RB * CB; i += 256) tot += sens[(long)n * RB * CB + i];
+  for (int off = 32; off > 0; off >>= 1) tot += __shfl_down(tot, off, 64);
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = tot;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+    int S = (2 * total + RB) / (2 * RB);
+    S_s = S < CB ? S : CB;
+  }
+  __syncthreads();
+  const int S = S_s;
+  const int* cnt = count + (long)band * CB;
+  const int* smp = samples + (long)band * CB;
+  for (int cb = threadIdx.x; cb < CB; cb += 256) {
+    uint8_t sv = sens[(long)band * CB + cb];
+    if (balance) {
+      // rank = number of blocks of the band that come before this one
+      const long ca = cnt[cb], sa = smp[cb];
+      int rank = 0;
+      for (int o = 0; o < CB; ++o) {
+        const long lhs = (long)cnt[o] * sa, rhs = ca * (long)smp[o];  // o before cb iff cnt_o/smp_o > cnt_cb/smp_cb
+        rank += (lhs > rhs || (lhs == rhs && o < cb)) ? 1 : 0;
+      }
+      sv = rank < S ? 1 : 0;
+    }
+    if (sens_out) sens_out[(long)band * CB + cb] = sv;
+    const uint32_t u = sens_draw(prefix, (uint64_t)band * (uint64_t)CB + (uint64_t)cb);
+    block_keep[(long)band * CB + cb] = ((uint64_t)u < (sv ? tm : tn)) ? 0 : 1;
+  }
+}
+
+static int32_t sens_geom(SensGeom& g, int32_t dtype, int N, int C, int H, int W, int kh, int kw, int stride, int pad, int x,
+                         int y) {
+  if (dtype != ARD_F32 && dtype != ARD_BF16) return fail(ARD_EDTYPE, "unknown dtype %d", dtype);
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
+    return fail(ARD_ESHAPE, "non-positive convolution size");
+  if (H + 2 * pad < kh || W + 2 * pad < kw) return fail(ARD_ESHAPE, "kernel larger than the padded input");
+  g = SensGeom{N, C, H, W, kh, kw, stride, pad, (H + 2 * pad - kh) / stride + 1, (W + 2 * pad - kw) / stride + 1, 0, 0, 0, 0, 0, 0};
+  g.rows = g.Ho * g.Wo;
+  if ((long)C * kh * kw > 0x7fffff00L || (long)N * g.rows > 0x7fffff00L) return fail(ARD_ESHAPE, "input matrix too large");
+  g.cols = C * kh * kw;
+  if (x < 1 || y < 0) return fail(ARD_EINVAL, "region size must be positive (y = 0: the whole width)");
+  g.x = x;
+  g.y = y == 0 ? g.cols : y;
+  g.RB = ceil_div(g.rows, g.x);
+  g.CB = ceil_div(g.cols, g.y);
+  if ((long)N * g.RB * g.CB > 0x7fffff00L) return fail(ARD_ESHAPE, "too many regions");
+  return ARD_OK;
+}
+
+}  // namespace ard
+
+using namespace ard;
+
+extern "C" int32_t ard_sens_regions(int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t kh, int32_t kw, int32_t stride,
+                                    int32_t pad, int32_t x, int32_t y, int32_t* rows, int32_t* row_bands,
+                                    int32_t* col_blocks) {
+  SensGeom g;
+  if (int32_t st = sens_geom(g, ARD_BF16, N, C, H, Wd, kh, kw, stride, pad, x, y)) return st;
+  if (rows) *rows = g.rows;
+  if (row_bands) *row_bands = g.RB;
+  if (col_blocks) *col_blocks = g.CB;
+  return ARD_OK;
+}
+
+extern "C" int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t kh, int32_t kw,
+                                    int32_t stride, int32_t pad, int32_t x, int32_t y, int32_t k_permille,
+                                    int32_t t_permille, float threshold, uint64_t seed, uint64_t iteration, const void* A,
+                                    int32_t* d_count, int32_t* d_samples, uint8_t* d_sens, void* stream) {
+  BatchSuspend not_recorded;
+  SensGeom g;
+  if (int32_t st = sens_geom(g, dtype, N, C, H, Wd, kh, kw, stride, pad, x, y)) return st;
+  if (k_permille < 1 || k_permille > 1000 || t_permille < 0 || t_permille > 1000)
+    return fail(ARD_EINVAL, "k and t are per-mille values (k in 1..1000, t in 0..1000)");
+  if ((long)g.x * g.y > (1L << 31) - 1 || ((long)k_permille * g.x * g.y) / 1000 > 65536)
+    return fail(ARD_ESHAPE, "a region may hold at most 65536 samples (x * y * k / 1000)");
+  if (!A || !d_count || !d_samples || !d_sens) return fail(ARD_EINVAL, "null pointer");
+  const uint64_t prefix = sens_prefix(seed, iteration, SENS_STREAM_SAMPLE);
+  const unsigned regions = (unsigned)((long)N * g.RB * g.CB);
+  if (dtype == ARD_BF16)
+    ARD_LAUNCH(sens_predict_kernel<uint16_t>, dim3(regions), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)A, g, k_permille,
+               t_permille, threshold, prefix, d_count, d_samples, d_sens);
+  else
+    ARD_LAUNCH(sens_predict_kernel<float>, dim3(regions), dim3(256), 0, (hipStream_t)stream, (const float*)A, g, k_permille,
+               t_permille, threshold, prefix, d_count, d_samples, d_sens);
+  ARD_LAUNCH_CHECK("sens_predict_kernel");
+  return ARD_OK;
+}
+
+extern "C" int32_t ard_sens_row_pattern(int32_t N, int32_t rows, int32_t x, const uint8_t* d_sens, double m, double n,
+                                        uint64_t seed, uint64_t iteration, uint8_t* d_mask, int32_t* d_keep, int32_t* d_count,
+                                        void* stream) {
+  BatchSuspend not_recorded;
+  if (N <= 0 || rows <= 0 || x <= 0) return fail(ARD_ESHAPE, "N, rows and x must be positive");
+  if ((long)N * rows > 0x7fffff00L) return fail(ARD_ESHAPE, "too many rows");
+  if (!(m >= 0.0 && m <= 1.0) || !(n >= 0.0 && n <= 1.0)) return fail(ARD_EINVAL, "possibilities must lie in [0, 1]");
+  if (!d_sens || (!d_mask && !d_keep && !d_count)) return fail(ARD_EINVAL, "null pointer");
+  ARD_LAUNCH(sens_row_pattern_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, d_sens, N * rows, rows, x, ceil_div(rows, x),
+             1, sens_threshold(m), sens_threshold(n), sens_prefix(seed, iteration, SENS_STREAM_ROWS), d_mask, d_keep, d_count);
+  ARD_LAUNCH_CHECK("sens_row_pattern_kernel");
+  return ARD_OK;
+}
+
+extern "C" int32_t ard_sens_block_pattern(int32_t N, int32_t row_bands, int32_t col_blocks, const int32_t* d_count,
+                                          const int32_t* d_samples, const uint8_t* d_sens, int32_t balance, double m, double n,
+                                          uint64_t seed, uint64_t iteration, uint8_t* d_sens_out, uint8_t* d_block_keep,
+                                          void* stream) {
+  BatchSuspend not_recorded;
+  if (N <= 0 || row_bands <= 0 || col_blocks <= 0) return fail(ARD_ESHAPE, "N, row_bands and col_blocks must be positive");
+  if ((long)N * row_bands * col_blocks > 0x7fffff00L) return fail(ARD_ESHAPE, "too many blocks");
+  if (!(m >= 0.0 && m <= 1.0) || !(n >= 0.0 && n <= 1.0)) return fail(ARD_EINVAL, "possibilities must lie in [0, 1]");
+  if (!d_sens || !d_block_keep || (balance && (!d_count || !d_samples))) return fail(ARD_EINVAL, "null pointer");
+  ARD_LAUNCH(sens_block_pattern_kernel, dim3((unsigned)(N * row_bands)), dim3(256), 0, (hipStream_t)stream, d_count, d_samples,
+             d_sens, row_bands, col_blocks, balance, sens_threshold(m), sens_threshold(n),
+             sens_prefix(seed, iteration, SENS_STREAM_BLOCKS), d_sens_out, d_block_keep);
+  ARD_LAUNCH_CHECK("sens_block_pattern_kernel");
+  return ARD_OK;
+}

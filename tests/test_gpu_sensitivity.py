@@ -1,0 +1,143 @@
+"""GPU parity of the sensitivity prediction and the sensitivity-aware patterns (Sections 5.1, 5.2): counts,
+flags, masks and lists bit-exact against the oracle; the forward convolution over the kept rows within the
+float tolerance, dropped positions exactly +0.0."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sensitivity as S
+from paper_2203_05705_amd import binding as ard
+from paper_2203_05705_amd import workloads as WL
+from util import assert_parity, from_vals, stored, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _predict_both(Av, Ad, k, stride, pad, x, y, kpm, tpm, thr, seed, it):
+    pred = ard.sens_predict(Ad, (k, k), stride, pad, x, y, kpm, tpm, thr, seed, it)
+    torch.cuda.synchronize()
+    N = Av.shape[0]
+    cnts, smps = [], []
+    for n in range(N):
+        X = S.input_matrix(Av[n], (k, k), stride, pad)
+        c, s = S.region_counts(X, x, y if y else X.shape[1], kpm, thr, seed, it, n)
+        cnts.append(c)
+        smps.append(s)
+    cnt, smp = np.stack(cnts), np.stack(smps)
+    assert np.array_equal(pred["samples"].cpu().numpy(), smp)
+    assert np.array_equal(pred["count"].cpu().numpy(), cnt)
+    sens = np.stack([S.sensitive_regions(cnt[n], smp[n], tpm) for n in range(N)])
+    assert np.array_equal(pred["sens"].cpu().numpy(), sens)
+    return pred, cnt, smp, sens
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,H,W,k,stride,pad,x,y,kpm,tpm", [
+    (2, 3, 6, 5, 3, 1, 1, 4, 6, 300, 500),       # the worked example's k = 30 %, t = 50 %; ragged regions
+    (3, 8, 9, 9, 3, 1, 1, 8, 0, 300, 500),       # regions span the width (row-based pattern)
+    (2, 4, 8, 8, 5, 2, 2, 3, 16, 1000, 250),     # strided 5x5, every element's worth of draws
+    (1, 16, 7, 7, 1, 1, 0, 7, 4, 100, 0),        # 1x1, t = 0: everything sensitive
+])
+def test_prediction_and_patterns_bit_exact(dtype, N, C, H, W, k, stride, pad, x, y, kpm, tpm):
+    print(f"sensitivity case {dtype} N={N} C={C} {H}x{W} k={k} s={stride} p={pad} region {x}x{y} k={kpm} t={tpm}", flush=True)
+    rng = np.random.default_rng(N * 100 + C)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Ad = from_vals(Av, dtype)
+    for it in (0, 7):
+        pred, cnt, smp, sens = _predict_both(Av, Ad, k, stride, pad, x, y, kpm, tpm, 0.5, 11, it)
+        rows, RB, CB = ard.sens_regions(Av.shape, (k, k), stride, pad, x, y)
+        assert sens.shape == (N, RB, CB)
+        # block-based pattern with and without balancing
+        for balance in (1, 0):
+            bp = ard.sens_block_pattern(pred, balance, 0.2, 0.7, 5, it)
+            torch.cuda.synchronize()
+            for n in range(N):
+                want = S.balance_groups(cnt[n], smp[n], sens[n])[0] if balance else sens[n]
+                assert np.array_equal(bp["sens"][n].cpu().numpy(), want)
+                assert np.array_equal(bp["keep"][n].cpu().numpy(), S.bsdp_block_mask(want, 0.2, 0.7, 5, it, n))
+        # row-based pattern from the first column block's flags (regions spanning the width have only one)
+        band = pred["sens"][:, :, :1].contiguous()
+        rp = ard.sens_row_pattern(band, rows, x, 0.25, 0.75, 3, it)
+        torch.cuda.synchronize()
+        mask = np.concatenate([S.rsdp_row_mask(sens[n][:, 0], x, rows, 0.25, 0.75, 3, it, n) for n in range(N)])
+        assert np.array_equal(rp["mask"].cpu().numpy(), mask)
+        keep = np.flatnonzero(mask).astype(np.int32)
+        assert int(rp["count"].item()) == len(keep)
+        got = rp["keep"].cpu().numpy()
+        assert np.array_equal(got[:len(keep)], keep) and np.all(got[len(keep):] == -1)
+
+
+def test_row_mask_example_of_section_6_on_the_device():
+    sens = torch.tensor([1, 0, 1, 1, 0, 0], dtype=torch.uint8, device="cuda").view(1, 6, 1)
+    rp = ard.sens_row_pattern(sens, 6, 1, 0.0, 1.0, 0, 0)
+    assert rp["mask"].cpu().tolist() == [1, 0, 1, 1, 0, 0] and rp["keep"].cpu().tolist()[:3] == [0, 2, 3]
+
+
+def _rows_forward_case(dtype, N, C, Cout, H, W, k, stride, pad, x, m, n_, seed):
+    print(f"rows forward {dtype} N={N} C={C} Cout={Cout} {H}x{W} k={k} s={stride} p={pad} x={x}", flush=True)
+    rng = np.random.default_rng(seed)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Wv = stored(rng.standard_normal((Cout, C, k, k)) * 0.2, dtype)
+    Ad, Wd = from_vals(Av, dtype), from_vals(Wv, dtype)
+    pred = ard.sens_predict(Ad, (k, k), stride, pad, x, 0, 300, 500, 0.5, seed, 1)
+    rows, RB, CB = ard.sens_regions(Av.shape, (k, k), stride, pad, x, 0)
+    rp = ard.sens_row_pattern(pred["sens"], rows, x, m, n_, seed, 1)
+    nk = int(rp["count"].item())
+    mask = rp["mask"].cpu().numpy().reshape(N, rows)
+    Y = ard.conv_fwd_rows(Ad, Wd, rp, nk, stride, pad)
+    ref = S.conv_fwd_rows(Av, Wv, mask, stride, pad)
+    zero = np.broadcast_to((mask == 0).reshape(N, 1, *ref.shape[2:]), ref.shape)
+    assert_parity(Y, ref, dtype, zero, "conv rows Y")
+    return nk, N * rows
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,x", [(2, 8, 16, 7, 7, 3, 1, 1, 4), (3, 12, 20, 9, 6, 3, 1, 1, 5),
+                                                           (2, 6, 10, 11, 10, 5, 1, 2, 8), (2, 8, 12, 9, 9, 3, 2, 1, 3),
+                                                           (5, 24, 130, 10, 12, 3, 1, 1, 16)])
+def test_forward_over_the_kept_rows(dtype, N, C, Cout, H, W, k, stride, pad, x):
+    _rows_forward_case(dtype, N, C, Cout, H, W, k, stride, pad, x, 0.2, 0.7, seed=N * 10 + C)
+
+
+def test_forward_over_the_kept_rows_degenerate():
+    """Nothing dropped (m = n = 0) equals the plain forward pass; everything dropped gives zeros."""
+    nk, tot = _rows_forward_case("bf16", 2, 8, 16, 7, 7, 3, 1, 1, 4, 0.0, 0.0, seed=1)
+    assert nk == tot
+    nk, _ = _rows_forward_case("bf16", 2, 8, 16, 7, 7, 3, 1, 1, 4, 1.0, 1.0, seed=2)
+    assert nk == 0
+
+
+def test_config5_layer_under_the_row_pattern():
+    """The config-5 layer (N=128, C=Cout=256, 28x28, 3x3) under the row-based sensitivity-aware pattern: bands
+    of 8 output positions, k = 30 %, threshold 0.5, t = 50 %, possibilities 0.3 / 0.7."""
+    wl = WL.conv_layer(seed=5)
+    Av, Wv = wl.values("A"), wl.values("Wt")
+    Ad, Wd = (to_dev(wl.arrays[k], "bf16") for k in ("A", "Wt"))
+    x = 8
+    pred = ard.sens_predict(Ad, (3, 3), 1, 1, x, 0, 300, 500, 0.5, 5, 0)
+    rows, RB, CB = ard.sens_regions(Av.shape, (3, 3), 1, 1, x, 0)
+    # prediction checked on a sample of images (the oracle walks the draws one by one)
+    got_c, got_s = pred["count"].cpu().numpy(), pred["sens"].cpu().numpy()
+    for n in (0, 57, 127):
+        X = S.input_matrix(Av[n], (3, 3), 1, 1)
+        Q = X.shape[1]
+        for rb in (0, 40, RB - 1):
+            r0 = rb * x
+            size = min(x, rows - r0) * Q
+            sn = max(1, 300 * size // 1000)
+            cc = 0
+            for j in range(sn):
+                e = (S.draw_u32(5, 0, S.STREAM_SAMPLE, ((n * RB + rb) * CB) * 65536 + j) * size) >> 32
+                cc += 1 if X[r0 + e // Q, e % Q] > 0.5 else 0
+            assert got_c[n, rb, 0] == cc and got_s[n, rb, 0] == (1 if 1000 * cc >= 500 * sn else 0)
+    rp = ard.sens_row_pattern(pred["sens"], rows, x, 0.3, 0.7, 5, 0)
+    nk = int(rp["count"].item())
+    mask = rp["mask"].cpu().numpy().reshape(128, rows)
+    want = np.stack([S.rsdp_row_mask(got_s[n][:, 0], x, rows, 0.3, 0.7, 5, 0, n) for n in range(128)])
+    assert np.array_equal(mask, want) and nk == int(want.sum())
+    print(f"config 5 under the row pattern: {nk} of {128 * rows} positions kept", flush=True)
+    Y = ard.conv_fwd_rows(Ad, Wd, rp, nk)
+    from oracle import conv as OC
+    ref = OC.conv_fwd(Av, Wv, np.ones(256, np.uint8)) * mask.reshape(128, 1, 28, 28)
+    zero = np.broadcast_to((mask == 0).reshape(128, 1, 28, 28), ref.shape)
+    assert_parity(Y, ref, "bf16", zero, "config 5 rows Y")
