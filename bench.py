@@ -620,6 +620,27 @@ def extra_conv(ard, torch, rooflines):
             rooflines.append(roofline_record(
                 "C5.fwd", "to_grid + gemm_direct_kernel<true, true, 256, *, 8, 1> (config 5, 128 of 256 input maps kept, forward call)",
                 fl, 2.0 * (N * nk * H * W + 256 * nk * 9 + N * 256 * H * W), row["fwd"]["us"], 20 * REPEATS))
+    # the paper's own mechanism on the same layer (Sections 5.1, 5.2.1): sensitivity of bands of 8 output
+    # positions from 30 % sampled values against threshold 0.5 (t = 50 %), rows dropped with possibility 0.3
+    # (sensitive) / 0.7 (insensitive), forward pass over the kept rows only
+    x = 8
+    rows, RB, CB = ard.sens_regions(A.shape, (3, 3), 1, 1, x, 0)
+    pred = ard.sens_predict(A, (3, 3), 1, 1, x, 0, 300, 500, 0.5, 5, 0)
+    rp = ard.sens_row_pattern(pred["sens"], rows, x, 0.3, 0.7, 5, 0)
+    nkr = int(rp["count"].item())
+    Yr = ard.conv_fwd_rows(A, Wt, rp, nkr, ws=ws)
+    lib, P = ard.lib(), (lambda t: t.data_ptr())
+    st = torch.cuda.current_stream().cuda_stream
+    t_pred = event_us(torch, lambda: lib.ard_sens_predict(ard.BF16, N, C, H, W, 3, 3, 1, 1, x, 0, 300, 500, 0.5, 5, 0, P(A),
+                                                          P(pred["count"]), P(pred["samples"]), P(pred["sens"]), st))["median"]
+    t_pat = event_us(torch, lambda: lib.ard_sens_row_pattern(N, rows, x, P(pred["sens"]), 0.3, 0.7, 5, 0, P(rp["mask"]), P(rp["keep"]),
+                                                             P(rp["count"]), st))["median"]
+    t_fwd = event_us(torch, lambda: ard.conv_fwd_rows(A, Wt, rp, nkr, ws=ws, out=Yr))["median"]
+    dense_fwd = res["rate0.0"]["fwd"]["us"]
+    res["row_sensitivity_pattern"] = dict(kept_rows=nkr, rows=N * rows, kept_fraction=round(nkr / (N * rows), 4),
+                                          predict_us=round(t_pred, 1), row_pattern_us=round(t_pat, 1), fwd_rows_us=round(t_fwd, 1),
+                                          fwd_speedup_vs_all_rows=round(dense_fwd / t_fwd, 3),
+                                          fwd_speedup_with_prediction=round(dense_fwd / (t_fwd + t_pred + t_pat), 3))
     Ag, Wg = A.clone().requires_grad_(True), Wt.clone().requires_grad_(True)
     Y = F.conv2d(Ag, Wg, padding=1)
     res["vendor_dense_us"] = dict(fwd=round(event_us(torch, lambda: F.conv2d(A, Wt, padding=1))["median"], 1),

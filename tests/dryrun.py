@@ -88,6 +88,6 @@ def conv_calls(lib, heap, dtype, N, Cc, Cout, H, W, k, stride, pad, n_keep, mode
     n = lib.ard_conv_workspace_bytes(dtype, N, Cc, H, W, Cout, k, k, stride, pad)
     ws = heap(n)
     big = N * max(Cc, Cout) * (H + 2 * pad) * (W + 2 * pad) * 4
-    A, Wt, dY, out, keep = (heap(big) for _ in range(5))
+    A, Wt, dY, out, keep, mask = (heap(big) for _ in range(6))
     return [lib.ard_fmap_drop_conv(m, dtype, N, Cc, H, W, Cout, k, k, stride, pad, 0.0, n_keep, A, Wt, dY, out,
-                                   None, keep, None, None, ws, n, None) for m in modes]
+                                   mask, keep, None, None, ws, n, None) for m in modes]

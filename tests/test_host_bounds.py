@@ -95,6 +95,12 @@ def test_lstm_and_conv_shapes():
             modes = (1, 2, 3, 0x101, 0x202, 0x103) + ((0x303,) if k - 1 == 2 * pad else ())   # with and without shared grids
             _ok(lib, D.conv_calls(lib, heap, D.BF16, N, Cc, Cout, H, W, k, 1, pad, nk, modes=modes), f"conv {N} {Cc} {Cout} {H}x{W} k{k} keep {nk}")
         assert n_lstm >= 10 and D.last_bounds(lib)[0] >= 10 * 3
+        # forward over a list of kept output positions (row-based sensitivity-aware pattern): the list lives in
+        # device memory, the proof takes its two extreme readings
+        for N, Cc, Cout, H, W, k, pad, rows_kept in [(128, 256, 256, 28, 28, 3, 1, 50000), (2, 8, 16, 7, 7, 3, 1, 40),
+                                                       (5, 24, 130, 10, 12, 3, 1, 1), (3, 12, 20, 9, 6, 3, 1, 162)]:
+            _ok(lib, D.conv_calls(lib, heap, D.BF16, N, Cc, Cout, H, W, k, 1, pad, rows_kept, modes=(4,)), f"rows {N} {Cc} {H}x{W}")
+        assert D.last_bounds(lib)[0] == 4
 
 
 def test_a_shortened_operand_is_rejected():
