@@ -258,6 +258,15 @@ int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
                      void* h, float* c, float* gates,
                      void* ws, size_t ws_bytes, void* stream);
 /*
+ * bf16 layers whose kept state is small enough run the whole recurrence of ard_lstm_fwd in ONE launch
+ * whose workgroups exchange h_t through memory and wait for each other step by step.  The wait is
+ * bounded: should the workgroups not all be resident together (another kernel holding CUs), they give
+ * up, leave normally and set an int32 in the workspace to 1; the outputs are then incomplete.
+ * ard_lstm_status_offset returns that word's byte offset in the workspace ((size_t)-1 when this layer
+ * takes the launch-per-step path, which has no such state); it is 0 after a completed call.
+ */
+size_t ard_lstm_status_offset(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const ard_pattern* pat);
+/*
  * Back-propagation through time with the same pattern.  dh[T,B,H] (dtype) is the
  * gradient arriving on every h_t; h, c, gates are ard_lstm_fwd's outputs.
  * Writes dx[T,B,I] (dtype) and dW[4H x (I+H)] (dtype; zero outside kept gate rows

@@ -91,6 +91,7 @@ _SIGS = {
     "ard_batch_abort": (None, []),
     "ard_relu_bwd": (C.c_int32, [C.c_int32, C.c_int64] + [C.c_void_p] * 4),
     "ard_lstm_workspace_bytes": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
+    "ard_lstm_status_offset": (C.c_size_t, [C.c_int32] * 5 + [C.c_void_p]),
     "ard_lstm_fwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
     "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
@@ -407,6 +408,13 @@ def relu_bwd(dY, Y, out=None, stream=None):
 def lstm_workspace_bytes(dtype_code, T, B, I, H, pat=None) -> int:
     _, r = _pref(pat)
     return int(lib().ard_lstm_workspace_bytes(dtype_code, T, B, I, H, r))
+
+
+def lstm_status_offset(dtype_code, T, B, I, H, pat=None):
+    """Byte offset in the workspace of the recurrence's give-up flag, or None (launch-per-step path)."""
+    _, r = _pref(pat)
+    off = int(lib().ard_lstm_status_offset(dtype_code, T, B, I, H, r))
+    return None if off == (1 << 64) - 1 else off
 
 
 def lstm_fwd(x, W, pat=None, ws=None, stream=None, out=None):

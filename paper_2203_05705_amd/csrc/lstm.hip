@@ -458,6 +458,31 @@ static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, h
   return ARD_OK;
 }
 
+// Does the forward pass of this layer run its recurrence in one launch, and how?  (bf16, affine pattern,
+// at most one workgroup per CU, bounded exchange traffic)
+struct PersistPlan {
+  int tmb, S, nbb;
+  size_t lds;
+};
+static bool lstm_persist_plan(const LstmArgs& a, PersistPlan& p) {
+  const int Hp = pad8(a.Hk);
+  if (a.dtype != ARD_BF16 || a.Hk <= 0 || a.T <= 1 || a.ax.kind != AX_AFFINE || getenv("ARD_NO_PERSIST")) return false;
+  p.S = Hp / 8;
+  p.tmb = 0;
+  const int cus = lstm_cu_count();
+  for (int cand = 1; cand <= 4 && !p.tmb; cand *= 2)
+    if ((long)p.S * ceil_div(a.B, 32 * cand) <= cus) p.tmb = cand;
+  if (!p.tmb) return false;
+  p.nbb = ceil_div(a.B, 32 * p.tmb);
+  p.lds = (size_t)32 * (Hp * 2 + 16) + (size_t)4 * 32 * p.tmb * 33 * 4;
+  // every unit slice reads the whole h_{t-1} of its batch rows with device-scope loads (they come from
+  // the memory side, not from an XCD's L2): S * B * Hp * 2 bytes per step.  Measured at B = 128: 8 MB
+  // (512 kept units) 7.7 us per step against 12.6 for two launches per step; 33 MB (1024 units) 18.9
+  // against 14.1, so large states keep the launch-per-step path.
+  const bool traffic_ok = (long)p.S * a.B * Hp * 2 <= 12L << 20;
+  return traffic_ok && p.lds <= 160 * 1024 - 1024;
+}
+
 template <typename T>
 static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void* h, float* c, float* gates,
                           const LstmWs& w, hipStream_t stream) {
@@ -472,33 +497,25 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
     if (st) return st;
   }
   // the whole recurrence in one launch when all of its workgroups fit on the chip together
-  if (std::is_same<T, uint16_t>::value && Hk > 0 && T_ > 1 && a.ax.kind == AX_AFFINE && !getenv("ARD_NO_PERSIST")) {
-    const int S = Hp / 8, cus = lstm_cu_count();
-    int tmb = 0;
-    for (int cand = 1; cand <= 4 && !tmb; cand *= 2)
-      if ((long)S * ceil_div(B, 32 * cand) <= cus) tmb = cand;
-    const size_t lds = tmb ? (size_t)32 * (Hp * 2 + 16) + (size_t)4 * 32 * tmb * 33 * 4 : 0;
-    // every unit slice reads the whole h_{t-1} of its batch rows with device-scope loads (they come from
-    // the memory side, not from an XCD's L2): S * B * Hp * 2 bytes per step.  Measured at B = 128: 8 MB
-    // (512 kept units) 7.7 us per step against 12.6 for two launches per step; 33 MB (1024 units) 18.9
-    // against 14.1, so large states keep the launch-per-step path.
-    const bool traffic_ok = (long)S * B * Hp * 2 <= 12L << 20;
-    if (tmb && traffic_ok && lds <= 160 * 1024 - 1024) {
-      const int nbb = ceil_div(B, 32 * tmb);
-      LstmPersist P{Gx, (const uint16_t*)w.whc, (uint16_t*)w.hc, (uint16_t*)h, c, gates, w.sync, w.sync + S * nbb, T_, B, H, Hk, Hp, S,
-                    a.ax.off, a.ax.step, 4000000L};
-      ARD_LAUNCH(lstm_zero_ints_kernel, dim3(ceil_div(S * nbb + 1, 256)), dim3(256), 0, stream, w.sync, S * nbb + 1);
-      ARD_LAUNCH_CHECK("lstm_zero_ints_kernel");
-      const void* kfn = tmb == 1 ? (const void*)lstm_persist_fwd_kernel<1> : tmb == 2 ? (const void*)lstm_persist_fwd_kernel<2>
-                                                                                       : (const void*)lstm_persist_fwd_kernel<4>;
-      if (lds > 65536) ARD_HIP_CHECK(raise_lds_limit(kfn, (int)lds));
-      const dim3 grid((unsigned)(S * nbb));
-      if (tmb == 1) ARD_LAUNCH(lstm_persist_fwd_kernel<1>, grid, dim3(256), lds, stream, P);
-      else if (tmb == 2) ARD_LAUNCH(lstm_persist_fwd_kernel<2>, grid, dim3(256), lds, stream, P);
-      else ARD_LAUNCH(lstm_persist_fwd_kernel<4>, grid, dim3(256), lds, stream, P);
-      ARD_LAUNCH_CHECK("lstm_persist_fwd_kernel");
-      return ARD_OK;
-    }
+  PersistPlan pp;
+  if (std::is_same<T, uint16_t>::value && lstm_persist_plan(a, pp)) {
+    const int S = pp.S, nbb = pp.nbb, tmb = pp.tmb;
+    const size_t lds = pp.lds;
+    // (ARD_LSTM_SPIN_LIMIT: test hook for the give-up path; a workgroup that gives up leaves normally)
+    const long spin_limit = getenv("ARD_LSTM_SPIN_LIMIT") ? atol(getenv("ARD_LSTM_SPIN_LIMIT")) : 4000000L;
+    LstmPersist P{Gx, (const uint16_t*)w.whc, (uint16_t*)w.hc, (uint16_t*)h, c, gates, w.sync + 1, w.sync, T_, B, H, Hk, Hp, S,
+                  a.ax.off, a.ax.step, spin_limit};
+    ARD_LAUNCH(lstm_zero_ints_kernel, dim3(ceil_div(S * nbb + 1, 256)), dim3(256), 0, stream, w.sync, S * nbb + 1);
+    ARD_LAUNCH_CHECK("lstm_zero_ints_kernel");
+    const void* kfn = tmb == 1 ? (const void*)lstm_persist_fwd_kernel<1> : tmb == 2 ? (const void*)lstm_persist_fwd_kernel<2>
+                                                                                     : (const void*)lstm_persist_fwd_kernel<4>;
+    if (lds > 65536) ARD_HIP_CHECK(raise_lds_limit(kfn, (int)lds));
+    const dim3 grid((unsigned)(S * nbb));
+    if (tmb == 1) ARD_LAUNCH(lstm_persist_fwd_kernel<1>, grid, dim3(256), lds, stream, P);
+    else if (tmb == 2) ARD_LAUNCH(lstm_persist_fwd_kernel<2>, grid, dim3(256), lds, stream, P);
+    else ARD_LAUNCH(lstm_persist_fwd_kernel<4>, grid, dim3(256), lds, stream, P);
+    ARD_LAUNCH_CHECK("lstm_persist_fwd_kernel");
+    return ARD_OK;
   }
   dim3 cgrid(ceil_div(H + (Hp - Hk), 256), B);
   for (int t = 0; t < T_; ++t) {
@@ -606,6 +623,14 @@ extern "C" size_t ard_lstm_workspace_bytes(int32_t dtype, int32_t T, int32_t B, 
   LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
   if (lstm_check(a, pat)) return 0;
   return lstm_ws_layout(nullptr, a.es, T, B, I, H, a.Hk).total;
+}
+
+extern "C" size_t ard_lstm_status_offset(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const ard_pattern* pat) {
+  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
+  PersistPlan pp;
+  if (lstm_check(a, pat) || !lstm_persist_plan(a, pp)) return (size_t)-1;
+  const LstmWs w = lstm_ws_layout((char*)nullptr + 256, a.es, T, B, I, H, a.Hk);
+  return (size_t)((char*)w.sync - ((char*)nullptr + 256));
 }
 
 extern "C" int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const void* x,
