@@ -168,6 +168,11 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
     for (int j = 0; j < NI; ++j)
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
+  // one of the NI loads of a full step (for callers that spread them between other instructions)
+  __device__ __forceinline__ void issue_one(uint4* op_tile, int kslab, int wave, int j) const {
+    const char* sb = base + (long)kslab * 2;
+    __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
+  }
   // last, partial step of a contraction: chunks beyond its end come from the zero chunk
   __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
     const int k = chunk_k(lane, wave, j);
@@ -238,6 +243,10 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
 #pragma unroll
     for (int j = 0; j < NI; ++j)
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
+  }
+  __device__ __forceinline__ void issue_one(uint4* op_tile, int kslab, int wave, int j) const {
+    const char* sb = base + (long)kslab * ld * 2;
+    __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
   __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
     const int kloc = KPI * (wave * NI + j) + lane / CPR;
@@ -656,11 +665,30 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
       wait_vmcnt<(NST - 2) * LPS>();
       wg_barrier();
       issue(NB{}, I0{}, 0);
-      mma(1);
       int ks, ksb;
       direct_slab<MODE>(P, kax, s_lo + it + NST, ks, ksb);
-      la.issue(lds + BUF * OPA, ks, wave);
-      lb.issue(lds + NST * OPA + BUF * OPB, ksb, wave);
+      // the loads of stage it+NST spread between the last slice's MFMAs (a burst of LPS load instructions
+      // keeps this wavefront from issuing MFMAs for as long as it takes to issue them)
+      {
+        constexpr int NA = decltype(la)::NI, MM = TM * TN;
+        int li = 0, mi = 0;
+#pragma unroll
+        for (int im = 0; im < TM; ++im)
+#pragma unroll
+          for (int in = 0; in < TN; ++in) {
+            acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_value<A_KC>(fa[1][im]), frag_value<B_KC>(fb[1][in]),
+                                                                  acc[im][in], 0, 0, 0);
+            ++mi;
+#pragma unroll
+            for (int r = 0; r < (LPS + MM - 1) / MM; ++r)
+              if (li < LPS && li * MM < mi * LPS) {
+                if (li < NA) la.issue_one(lds + BUF * OPA, ks, wave, li);
+                else lb.issue_one(lds + NST * OPA + BUF * OPB, ksb, wave, li - NA);
+                ++li;
+              }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      }
     };
     if (S > 0) {
 #pragma unroll
