@@ -248,6 +248,9 @@ int32_t ard_relu_bwd(int32_t dtype, int64_t n, const void* dY, const void* Y, vo
  * columns [x | h]; no bias; zero initial state.  `pat` (ROW/LIST/NONE over the H
  * hidden units) holds for the whole sequence: a dropped unit has h = c = 0 at
  * every step, its four gate rows and its recurrent column are never loaded.
+ * A TILE pattern (Section 3.2 applied to this layer, the "TILE" variant of Section 7.2.3) lies over the
+ * fused weight itself: tile grid ceil(4H/tile_r) x ceil((I+H)/tile_c), any positive tile size; the synapses
+ * of dropped tiles are absent for the whole sequence, every unit stays alive, and dW is zero on them.
  * x[T,B,I] dtype; outputs h[T,B,H] dtype, c[T,B,H] fp32, gates[T,B,4H] fp32
  * (activated i,f,g,o; entries of dropped units are 0), all fully written.
  */

@@ -29,20 +29,37 @@ __global__ __launch_bounds__(1024) void lstm_setup_kernel(Axis ax, int H, int* r
   for (int j = threadIdx.x; j < ax.n; j += 1024) rank[ax_phys(ax, j)] = j;
 }
 
-// out[g*Hp + j][q] = W[(g*H + unit(j)) * ldw + col(q)] for kept j, 0 at the padding.
+// Tile pattern over the fused weight W[4H x (I+H)] (Section 3.2): the synapse at (row, col) lies in tile
+// (row / tr, col / tc), tiles are numbered row-major over a grid of `tcols` tile columns, and tile number
+// t (0-based) is kept iff (t - o) mod dp == 0 (o = b - 1).  dp == 0: no tile pattern.
+struct LstmTiles {
+  int dp, o, tr, tc, tcols;
+};
+__device__ __forceinline__ bool lstm_synapse_kept(const LstmTiles& tp, int row, int col) {
+  if (tp.dp <= 1) return true;
+  const long t = (long)(row / tp.tr) * tp.tcols + col / tp.tc - tp.o;
+  return t % tp.dp == 0;  // (sign of t is irrelevant for == 0)
+}
+
+// out[g*Hp + j][q] = W[(g*H + unit(j)) * ldw + col(q)] for kept j, 0 at the padding and for synapses of
+// dropped tiles.
 // cols == 0: the input columns, q < ncol identity; cols == 1: the recurrent columns,
 // q < Hp -> I + unit(q) (0 at the padding); out has `ldo` columns.
 template <typename T>
-__global__ void lstm_gather_w_kernel(const T* W, long ldw, Axis ax, int H, int I, int Hp, int recurrent, int ldo, T* out) {
+__global__ void lstm_gather_w_kernel(const T* W, long ldw, Axis ax, int H, int I, int Hp, int recurrent, int ldo,
+                                     LstmTiles tp, T* out) {
   const int q = blockIdx.x * blockDim.x + threadIdx.x;
   const int r = blockIdx.y;  // compact gate row
   if (q >= ldo) return;
   const int g = r / Hp, j = r - g * Hp;
   T v = (T)0;
   if (j < ax.n) {
-    const long row = (long)(g * H + ax_phys(ax, j)) * ldw;
-    if (!recurrent) v = W[row + q];
-    else if (q < ax.n) v = W[row + I + ax_phys(ax, q)];
+    const int prow = g * H + ax_phys(ax, j);
+    const long row = (long)prow * ldw;
+    int col = -1;
+    if (!recurrent) col = q;
+    else if (q < ax.n) col = I + ax_phys(ax, q);
+    if (col >= 0 && lstm_synapse_kept(tp, prow, col)) v = W[row + col];
   }
   out[(long)r * ldo + q] = v;
 }
@@ -136,16 +153,17 @@ __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const f
 }
 
 // dW[(g*H + u)][q] from the compact gradients dwx[4Hp x I] and dwh[4Hp x Hp]; +0.0 for every
-// row of a dropped unit and every recurrent column of a dropped unit.
+// row of a dropped unit, every recurrent column of a dropped unit and every synapse of a dropped tile.
 template <typename T>
-__global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* rank, int H, int I, int Hp, T* dW) {
+__global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* rank, int H, int I, int Hp, LstmTiles tp,
+                                       T* dW) {
   const int q = blockIdx.x * blockDim.x + threadIdx.x;
   const int p = blockIdx.y;  // physical gate row
   if (q >= I + H) return;
   const int g = p / H, u = p - g * H;
   const int j = rank[u];
   T v = (T)0;
-  if (j >= 0) {
+  if (j >= 0 && lstm_synapse_kept(tp, p, q)) {
     const long r = (long)g * Hp + j;
     if (q < I) {
       v = dwx[r * I + q];
@@ -403,21 +421,33 @@ static LstmWs lstm_ws_layout(char* base, int es, int T, int B, int I, int H, int
 struct LstmArgs {
   int32_t dtype, T, B, I, H, Hk, es;
   Axis ax;
+  LstmTiles tiles;
 };
 
 static int32_t lstm_check(LstmArgs& a, const ard_pattern* pat) {
   if (a.dtype != ARD_F32 && a.dtype != ARD_BF16) return fail(ARD_EDTYPE, "unknown dtype %d", a.dtype);
   if (a.T <= 0 || a.B <= 0 || a.I <= 0 || a.H <= 0)
     return fail(ARD_ESHAPE, "T, B, I, H must be positive (got %d, %d, %d, %d)", a.T, a.B, a.I, a.H);
-  if (pat && pat->kind == ARD_PAT_TILE) return fail(ARD_EINVAL, "the LSTM takes a ROW, LIST or NONE pattern");
-  int32_t st = check_pattern(pat, a.H, "pat");
-  if (st) return st;
-  a.ax = axis_of_pattern(pat, a.H);
+  if (4L * a.H > 65535) return fail(ARD_ESHAPE, "more than 16383 hidden units");
+  a.tiles = LstmTiles{0, 0, 1, 1, 1};
+  int32_t st;
+  if (pat && pat->kind == ARD_PAT_TILE) {
+    // synapses are dropped, every unit stays
+    if (pat->tile_r <= 0 || pat->tile_c <= 0) return fail(ARD_EINVAL, "tile size must be positive");
+    const int TR = ceil_div(4 * a.H, pat->tile_r), TC = ceil_div(a.I + a.H, pat->tile_c);
+    st = check_pattern(pat, TR * TC, "pat");
+    if (st) return st;
+    a.tiles = LstmTiles{pat->dp, pat->b - 1, pat->tile_r, pat->tile_c, TC};
+    a.ax = axis_identity(a.H);
+  } else {
+    st = check_pattern(pat, a.H, "pat");
+    if (st) return st;
+    a.ax = axis_of_pattern(pat, a.H);
+  }
   a.Hk = a.ax.n;
   a.es = a.dtype == ARD_BF16 ? 2 : 4;
   if ((long)a.T * a.B > 0x7fffffffL / 4 || (long)a.B > 65535 || (long)a.T * a.B > 65535 * 64L)
     return fail(ARD_ESHAPE, "T*B or B too large");
-  if (4L * a.H > 65535) return fail(ARD_ESHAPE, "more than 16383 hidden units");
   return ARD_OK;
 }
 
@@ -449,10 +479,10 @@ static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, h
   const int Hp = pad8(a.Hk);
   if (a.Hk > 0) {
     ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(a.I, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
-                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, a.I, (T*)w.wxc);
+                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, a.I, a.tiles, (T*)w.wxc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
     ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(Hp, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
-                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 1, Hp, (T*)w.whc);
+                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 1, Hp, a.tiles, (T*)w.whc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
   }
   return ARD_OK;
@@ -609,7 +639,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     if (st) return st;
   }
   ARD_LAUNCH(lstm_scatter_dw_kernel<T>, dim3(ceil_div(I + H, 256), 4 * H), dim3(256), 0, stream, (const T*)w.dwx,
-                     (const T*)w.dwh, (const int*)w.rank, H, I, Hp, (T*)dW);
+                     (const T*)w.dwh, (const int*)w.rank, H, I, Hp, a.tiles, (T*)dW);
   ARD_LAUNCH_CHECK("lstm_scatter_dw_kernel");
   return ARD_OK;
 }
@@ -620,13 +650,13 @@ using namespace ard;
 
 extern "C" size_t ard_lstm_workspace_bytes(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
                                            const ard_pattern* pat) {
-  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
+  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}, LstmTiles{}};
   if (lstm_check(a, pat)) return 0;
   return lstm_ws_layout(nullptr, a.es, T, B, I, H, a.Hk).total;
 }
 
 extern "C" size_t ard_lstm_status_offset(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H, const ard_pattern* pat) {
-  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
+  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}, LstmTiles{}};
   PersistPlan pp;
   if (lstm_check(a, pat) || !lstm_persist_plan(a, pp)) return (size_t)-1;
   const LstmWs w = lstm_ws_layout((char*)nullptr + 256, a.es, T, B, I, H, a.Hk);
@@ -637,7 +667,7 @@ extern "C" int32_t ard_lstm_fwd(int32_t dtype, int32_t T, int32_t B, int32_t I, 
                                 const void* W, const ard_pattern* pat, void* h, float* c, float* gates, void* ws,
                                 size_t ws_bytes, void* stream) {
   BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
-  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
+  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}, LstmTiles{}};
   int32_t st = lstm_check(a, pat);
   if (st) return st;
   if (!x || !W || !h || !c || !gates) return fail(ARD_EINVAL, "null tensor pointer");
@@ -652,7 +682,7 @@ extern "C" int32_t ard_lstm_bwd(int32_t dtype, int32_t T, int32_t B, int32_t I, 
                                 const float* gates, const void* dh, void* dx, void* dW, void* ws, size_t ws_bytes,
                                 void* stream) {
   BatchSuspend not_recorded;  // this entry point's kernels depend on each other: never part of a grouped launch
-  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}};
+  LstmArgs a{dtype, T, B, I, H, 0, 0, Axis{}, LstmTiles{}};
   int32_t st = lstm_check(a, pat);
   if (st) return st;
   if (!x || !W || !h || !c || !gates || !dh || !dx || !dW) return fail(ARD_EINVAL, "null tensor pointer");

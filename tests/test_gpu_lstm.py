@@ -104,3 +104,48 @@ def test_one_launch_recurrence_status_and_give_up_path():
     h1, c1, g1 = ard.lstm_fwd(x, W, pat, ws=ws)
     torch.cuda.synchronize()
     assert status() == 0 and torch.equal(h1, h0) and torch.equal(c1, c0) and torch.equal(g1, g0)
+
+
+def _check_tile(dtype, x, W, dh, tile, what):
+    """Tile pattern on the fused weight (Section 3.2 on the layer of Section 7.2.3): synapses dropped, units kept."""
+    store = R.to_bf16_values if dtype == "bf16" else (lambda a: np.asarray(a, np.float64).astype(np.float32).astype(np.float64))
+    tr, tc, dp, b = tile
+    T, B, I = x.shape
+    H = W.shape[0] // 4
+    S = P.expand_tile_mask(P.tile_mask(4 * H, I + H, tr, tc, dp, b), 4 * H, I + H, tr, tc)
+    fwd = L.lstm_forward_synapse(x, W, S, store)
+    bwd = L.lstm_backward_synapse(x, W, S, fwd, dh, store)
+    pat = ard.Pattern.tile(dp, b, tr, tc)
+    xd, Wd, dhd = from_vals(x, dtype), from_vals(W, dtype), from_vals(dh, dtype)
+    h, c, gates = ard.lstm_fwd(xd, Wd, pat)
+    dx, dW = ard.lstm_bwd(xd, Wd, pat, h, c, gates, dhd)
+    torch.cuda.synchronize()
+    lim = dict(tol=CEILING[dtype], etol=CEILING[dtype])
+    soft = "bf16" if dtype == "bf16" else "f32"
+    return [assert_parity(h, fwd["h"], dtype, None, what + " h", **lim),
+            assert_parity(c, fwd["c"], soft, None, what + " c", **lim),
+            assert_parity(gates, fwd["gates"], soft, None, what + " gates", **lim),
+            assert_parity(dx, bwd["dx"], dtype, None, what + " dx", **lim),
+            assert_parity(dW, bwd["dW"], dtype, S == 0, what + " dW", **lim)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,B,I,H,tr,tc,dp,b", [(5, 6, 24, 32, 32, 32, 2, 1), (4, 3, 10, 37, 8, 5, 3, 3),
+                                                 (3, 70, 64, 64, 32, 32, 4, 2), (6, 33, 72, 136, 64, 64, 2, 2),
+                                                 (2, 16, 128, 128, 32, 32, 1, 1), (3, 64, 128, 200, 32, 64, 5, 4)])
+def test_lstm_tile_pattern_parity(dtype, T, B, I, H, tr, tc, dp, b):
+    print(f"lstm tile case dtype={dtype} T={T} B={B} I={I} H={H} tile={tr}x{tc} dp={dp} b={b}", flush=True)
+    rng = np.random.default_rng(T * 1000 + H + dp)
+    x = stored(rng.standard_normal((T, B, I)), dtype)
+    W = stored(rng.uniform(-0.3, 0.3, (4 * H, I + H)), dtype)
+    dh = stored(rng.standard_normal((T, B, H)), dtype)
+    _check_tile(dtype, x, W, dh, (tr, tc, dp, b), f"lstm tile {dtype}")
+
+
+@pytest.mark.parametrize("dp,b", [(2, 2), (3, 1)])
+def test_config4_lstm_layer_tile_pattern_full_size(dp, b):
+    """Config 4's layer (1024/1024, batch 128, 64 steps, bf16) under 64x64 tiles on its 4096x2048 weight."""
+    wl = WL.lstm_layer(seed=4)
+    print(f"config 4 tile dp={dp} b={b}: running oracle (fp64) ...", flush=True)
+    errs = _check_tile("bf16", wl.values("x"), wl.values("W"), wl.values("dh"), (64, 64, dp, b), "config4 tile")
+    print("config 4 tile max rel err (h, c, gates, dx, dW):", ["%.2e" % e for e in errs], flush=True)
