@@ -187,8 +187,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
   if (P.A.kdense && P.B.kdense) k = axis_identity(P.k.n);
   else if ((P.A.kdense || P.B.kdense) && !ident(P.k)) return false;
   if (k.kind != AX_AFFINE || k.step != 1 || (k.off % 8)) return false;
-  if (k.n % 8) {
-    // both operands carry zero padding along the contraction: run it to the padded length
+  if ((k.n % 8) && (a_kc || b_kc)) {
+    // (an operand whose rows run along the contraction ends at any row: only contraction-contiguous ones
+    // are fetched in pieces of 8.)  Both operands carry zero padding along the contraction: run it to the
+    // padded length
     if (!P.A.kpad || !P.B.kpad || !ident(k)) return false;
     k = axis_identity(pad8(k.n));
   }

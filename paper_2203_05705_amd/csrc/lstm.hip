@@ -57,7 +57,7 @@ __global__ void lstm_gather_w_kernel(const T* W, long ldw, Axis ax, int H, int I
     const int prow = g * H + ax_phys(ax, j);
     const long row = (long)prow * ldw;
     int col = -1;
-    if (!recurrent) col = q;
+    if (!recurrent) col = q < I ? q : -1;
     else if (q < ax.n) col = I + ax_phys(ax, q);
     if (col >= 0 && lstm_synapse_kept(tp, prow, col)) v = W[row + col];
   }
@@ -152,10 +152,18 @@ __global__ void lstm_cell_bwd_kernel(const float* gates, const float* c, const f
   dc_next[(long)b * H + u] = dc * gf;
 }
 
-// dW[(g*H + u)][q] from the compact gradients dwx[4Hp x I] and dwh[4Hp x Hp]; +0.0 for every
+// dst[r][0..cols) = src[r][0..cols) for rows of different lengths (ld_src, ld_dst): strips the padding of dx
+template <typename T>
+__global__ void lstm_copy_rows_kernel(const T* src, long ld_src, int cols, long ld_dst, T* dst) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const long r = blockIdx.y;
+  if (j < cols) dst[r * ld_dst + j] = src[r * ld_src + j];
+}
+
+// dW[(g*H + u)][q] from the compact gradients dwx[4Hp x Ip] and dwh[4Hp x Hp]; +0.0 for every
 // row of a dropped unit, every recurrent column of a dropped unit and every synapse of a dropped tile.
 template <typename T>
-__global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* rank, int H, int I, int Hp, LstmTiles tp,
+__global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* rank, int H, int I, int Ip, int Hp, LstmTiles tp,
                                        T* dW) {
   const int q = blockIdx.x * blockDim.x + threadIdx.x;
   const int p = blockIdx.y;  // physical gate row
@@ -166,7 +174,7 @@ __global__ void lstm_scatter_dw_kernel(const T* dwx, const T* dwh, const int* ra
   if (j >= 0 && lstm_synapse_kept(tp, p, q)) {
     const long r = (long)g * Hp + j;
     if (q < I) {
-      v = dwx[r * I + q];
+      v = dwx[r * Ip + q];
     } else {
       const int jv = rank[q - I];
       if (jv >= 0) v = dwh[r * Hp + jv];
@@ -375,13 +383,15 @@ static int lstm_cu_count() {
 
 struct LstmWs {
   int* rank;
-  char* wxc;     // [4Hp x I] dtype
+  char* wxc;     // [4Hp x Ip] dtype (Ip = I rounded up to 8: every row a whole number of 16-byte pieces)
+  char* xp;      // [T*B x Ip] dtype, only when Ip != I: x with padded rows (forward, weight gradient)
+  char* dxp;     // [T*B x Ip] dtype, only when Ip != I: dx before its padding is stripped
   char* whc;     // [4Hp x Hp] dtype
   char* hc;      // [T*B x Hp] dtype
   char* big;     // fwd: Gx [T*B x 4Hp] fp32; bwd: dG [T*B x 4Hp] dtype
   float* dh_next;  // [B x Hp]
   float* dc_next;  // [B x H]
-  char* dwx;     // [4Hp x I] dtype
+  char* dwx;     // [4Hp x Ip] dtype
   char* dwh;     // [4Hp x Hp] dtype
   char* part;    // fp32 partial sums of split products
   size_t part_bytes;
@@ -399,16 +409,19 @@ static LstmWs lstm_ws_layout(char* base, int es, int T, int B, int I, int H, int
   };
   const size_t Hp = pad8(Hk);
   w.rank = (int*)take((size_t)H * 4);
-  w.wxc = take(4 * Hp * I * es);
+  const size_t Ip = pad8(I);
+  w.wxc = take(4 * Hp * Ip * es);
+  w.xp = (int)Ip != I ? take((size_t)T * B * Ip * es) : nullptr;
+  w.dxp = (int)Ip != I ? take((size_t)T * B * Ip * es) : nullptr;
   w.whc = take(4 * Hp * Hp * es);
   w.hc = take((size_t)T * B * Hp * es);
   w.big = take((size_t)T * B * 4 * Hp * 4);
   w.dh_next = (float*)take((size_t)B * Hp * 4);
   w.dc_next = (float*)take((size_t)B * H * 4);
-  w.dwx = take(4 * Hp * I * es);
+  w.dwx = take(4 * Hp * Ip * es);
   w.dwh = take(4 * Hp * Hp * es);
   // room for the partial sums of any product here split 8 ways, capped at 256 MiB
-  size_t big = 4 * Hp * (size_t)(I > (int)Hp ? I : (int)Hp);
+  size_t big = 4 * Hp * (size_t)(Ip > Hp ? Ip : Hp);
   if ((size_t)B * 4 * Hp > big) big = (size_t)B * 4 * Hp;
   w.part_bytes = big * 4 * 8;
   if (w.part_bytes > ((size_t)256 << 20)) w.part_bytes = (size_t)256 << 20;
@@ -478,13 +491,31 @@ static int32_t lstm_prepare(const LstmArgs& a, const void* W, const LstmWs& w, h
   ARD_LAUNCH_CHECK("lstm_setup_kernel");
   const int Hp = pad8(a.Hk);
   if (a.Hk > 0) {
-    ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(a.I, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
-                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, a.I, a.tiles, (T*)w.wxc);
+    ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(pad8(a.I), 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
+                       (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 0, pad8(a.I), a.tiles, (T*)w.wxc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
     ARD_LAUNCH(lstm_gather_w_kernel<T>, dim3(ceil_div(Hp, 256), 4 * Hp), dim3(256), 0, stream, (const T*)W,
                        (long)(a.I + a.H), a.ax, a.H, a.I, Hp, 1, Hp, a.tiles, (T*)w.whc);
     ARD_LAUNCH_CHECK("lstm_gather_w_kernel");
   }
+  return ARD_OK;
+}
+
+// x with rows padded to a multiple of 8 elements (zeros), so that the products over it can use 16-byte
+// loads whatever the input width; returns x itself when no padding is needed
+template <typename T>
+static int32_t lstm_padded_x(const LstmArgs& a, const void* x, const LstmWs& w, hipStream_t stream, const void** xo) {
+  const int Ip = pad8(a.I);
+  *xo = x;
+  if (Ip == a.I) return ARD_OK;
+  const long rows_total = (long)a.T * a.B;
+  for (long r0 = 0; r0 < rows_total; r0 += 65535) {
+    const long rows = rows_total - r0 < 65535 ? rows_total - r0 : 65535;
+    ARD_LAUNCH(lstm_gather_h_kernel<T>, dim3(ceil_div(Ip, 256), (unsigned)rows), dim3(256), 0, stream,
+                       (const T*)x + r0 * a.I, a.I, axis_identity(a.I), Ip, (T*)w.xp + r0 * Ip);
+    ARD_LAUNCH_CHECK("lstm_gather_h_kernel");
+  }
+  *xo = w.xp;
   return ARD_OK;
 }
 
@@ -520,9 +551,13 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
   int32_t st = lstm_prepare<T>(a, W, w, stream);
   if (st) return st;
   float* Gx = (float*)w.big;
+  const int Ip = pad8(I);
   if (Hk > 0) {
     // input projection of every step: Gx[T*B x 4Hp] = x . Wx'^T
-    GemmParams P = plain_gemm(x, I, w.wxc, I, Gx, 4 * Hp, T_ * B, 4 * Hp, I, true, true, ce, true, 0.0f);
+    const void* xs;
+    st = lstm_padded_x<T>(a, x, w, stream, &xs);
+    if (st) return st;
+    GemmParams P = plain_gemm(xs, Ip, w.wxc, Ip, Gx, 4 * Hp, T_ * B, 4 * Hp, Ip, true, true, ce, true, 0.0f);
     st = run_gemm(a.dtype, true, true, P, 0, 0, stream, w.part, w.part_bytes);
     if (st) return st;
   }
@@ -579,6 +614,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
                           const float* gates, const void* dh, void* dx, void* dW, const LstmWs& w,
                           hipStream_t stream) {
   const int T_ = a.T, B = a.B, I = a.I, H = a.H, Hk = a.Hk, Hp = pad8(Hk), ce = 16 / a.es;
+  const int Ip = pad8(I);
   int32_t st = lstm_prepare<T>(a, W, w, stream);
   if (st) return st;
   if (Hk == 0) {
@@ -620,13 +656,26 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
   }
   {
     // dx[T*B x I] = dG . Wx'
-    GemmParams P = plain_gemm(dG, 4 * Hp, w.wxc, I, dx, I, T_ * B, I, 4 * Hp, true, false, ce, false, 0.0f);
+    void* dxo = Ip != I ? (void*)w.dxp : dx;
+    GemmParams P = plain_gemm(dG, 4 * Hp, w.wxc, Ip, dxo, Ip, T_ * B, Ip, 4 * Hp, true, false, ce, false, 0.0f);
     st = run_gemm(a.dtype, true, false, P, 0, 0, stream, w.part, w.part_bytes);
     if (st) return st;
+    if (Ip != I) {
+      const long rows_total = (long)T_ * B;
+      for (long r0 = 0; r0 < rows_total; r0 += 65535) {
+        const long rows = rows_total - r0 < 65535 ? rows_total - r0 : 65535;
+        ARD_LAUNCH(lstm_copy_rows_kernel<T>, dim3(ceil_div(I, 256), (unsigned)rows), dim3(256), 0, stream,
+                           (const T*)w.dxp + r0 * Ip, (long)Ip, I, (long)I, (T*)dx + r0 * I);
+        ARD_LAUNCH_CHECK("lstm_copy_rows_kernel");
+      }
+    }
   }
   {
     // compact weight gradients: dwx[4Hp x I] = dG^T . x, dwh[4Hp x Hp] = dG[1:]^T . h[kept][:-1]
-    GemmParams P = plain_gemm(dG, 4 * Hp, x, I, w.dwx, I, 4 * Hp, I, T_ * B, false, false, ce, false, 0.0f);
+    const void* xs;
+    st = lstm_padded_x<T>(a, x, w, stream, &xs);
+    if (st) return st;
+    GemmParams P = plain_gemm(dG, 4 * Hp, xs, Ip, w.dwx, Ip, 4 * Hp, Ip, T_ * B, false, false, ce, false, 0.0f);
     st = run_gemm(a.dtype, false, false, P, 0, 0, stream, w.part, w.part_bytes);
     if (st) return st;
     if (T_ > 1) {
@@ -639,7 +688,7 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
     if (st) return st;
   }
   ARD_LAUNCH(lstm_scatter_dw_kernel<T>, dim3(ceil_div(I + H, 256), 4 * H), dim3(256), 0, stream, (const T*)w.dwx,
-                     (const T*)w.dwh, (const int*)w.rank, H, I, Hp, a.tiles, (T*)dW);
+                     (const T*)w.dwh, (const int*)w.rank, H, I, Ip, Hp, a.tiles, (T*)dW);
   ARD_LAUNCH_CHECK("lstm_scatter_dw_kernel");
   return ARD_OK;
 }

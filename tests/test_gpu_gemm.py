@@ -94,6 +94,14 @@ def test_row_pattern_epilogue_options(dtype):
     _run_row_case(dtype, 70, 136, 90, (3, 1), None, alpha=3.0, relu=False, beta=1.0, seed=6, use_relu_src=True)
 
 
+@pytest.mark.parametrize("B", [700, 61, 1027])
+def test_weight_gradient_contracts_a_batch_that_is_no_multiple_of_8(B):
+    """16-byte aligned widths, ragged batch: the weight gradient contracts over rows, so its last step
+    ends at any row (the forward and data gradient contract along the rows' 16-byte pieces)."""
+    _run_row_case("bf16", B, 512, 768, None, None, seed=B)
+    _run_row_case("bf16", B, 1024, 640, (2, 2), (3, 1), seed=B + 1)
+
+
 def test_row_pattern_multi_tile_bf16():
     """Large enough for the 128x128 workgroup tile, ragged in every dimension."""
     _run_row_case("bf16", 1000, 1048, 2050, (2, 1), (2, 2), seed=9)
