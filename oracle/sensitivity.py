@@ -8,10 +8,10 @@ zero-padded activations A[c, oh*s + kh - pad, ow*s + kw - pad].  It is cut into 
 
 Readings taken where the paper leaves the procedure open (each draw is counter-based and integer
 only, so that masks can be reproduced bit for bit):
-  * "randomly select k% values" (step 2): s = max(1, floor(k_permille * size / 1000)) draws WITH
+  * the k% sample of a region (step 2): s = max(1, floor(k_permille * size / 1000)) draws WITH
     replacement, draw j picks element e = (u * size) >> 32 of the region in row-major order, u the
     32-bit draw for index (region * 65536 + j) of stream STREAM_SAMPLE.
-  * "t% of them are larger than the threshold" (step 3): sensitive iff 1000 * count >= t_permille * s.
+  * the share t% of the sample that must exceed the threshold (step 3): sensitive iff 1000 * count >= t_permille * s.
   * possibilities m (sensitive) < n (insensitive) become 32-bit thresholds floor(p * 2^32) (p = 1 -> 2^32);
     a unit is DROPPED iff its draw u < threshold.
   * RSDP (Section 5.2.1): the unit is a row of the input matrix; regions span the whole width
