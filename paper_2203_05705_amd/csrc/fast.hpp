@@ -120,6 +120,14 @@ __host__ __device__ __forceinline__ int fast_kslab(const Axis& k, int ks) {
   return (k.list[q] + k.off) * k.bs + (ks - q * k.bs);
 }
 
+// A contraction axis made of 32-wide blocks in arithmetic progression (the paper's 32 x 32 tiles): a
+// 64-deep step holds two kept blocks, `step` blocks apart in memory.  The slab of a step starts at its
+// first block; the lanes that fetch the step's upper half add this constant (in contraction elements) to
+// their offset once, at set-up, so the loop itself does not change.
+__host__ __device__ __forceinline__ int direct_kbump(const Axis& k) {
+  return (k.kind == AX_BAFF && k.bs == 32) ? (k.step - 1) * 32 : 0;
+}
+
 template <bool KC, int ROWS, int NW> struct DirectLoader;
 
 // Both loaders keep, per lane and instruction, a loop-invariant 32-bit BYTE offset from a base that
@@ -137,7 +145,8 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
     return ((lane & 7) ^ (row & 7) ^ ((row >> 3) & 7)) * 8;
   }
   // (host-callable: the host-side bounds proof runs this very arithmetic for every lane)
-  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave) {
+  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld, const Axis& r, int row0, int lane, int wave,
+                                                int kbump = 0) {
     base = reinterpret_cast<const char*>(p);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
@@ -145,7 +154,8 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
       // (a block axis counts its last block in full even when the operand ends inside it)
       int prow = ax_phys(r, row);
       if (r.kind == AX_BLOCK || r.kind == AX_BAFF) prow = imin(prow, r.nphys - 1);
-      voff[j] = (uint32_t)(prow * ld + chunk_k(lane, wave, j)) * 2u;
+      const int ck = chunk_k(lane, wave, j);
+      voff[j] = (uint32_t)(prow * ld + ck + (ck >= 32 ? kbump : 0)) * 2u;
     }
   }
   // rows = output pixels of a convolution: base pixel of the patch in the bordered grid
@@ -174,19 +184,21 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
     __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
   // last, partial step of a contraction: chunks beyond its end come from the zero chunk
-  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
+  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end,
+                                                            int kbump = 0) {
     const int k = chunk_k(lane, wave, j);
-    return k < krem && kslab + k + 8 <= kphys_end;
+    return k < krem && kslab + k + (k >= 32 ? kbump : 0) + 8 <= kphys_end;
   }
   // byte offset from the operand's base of instruction j's chunk in the step whose slab starts at kslab
   __host__ __device__ __forceinline__ long byte_offset(int j, int kslab) const { return (long)kslab * 2 + voff[j]; }
-  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
+  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave,
+                                             int kbump = 0) const {
     asm volatile("; partial contraction step" ::: "memory");  // keeps this path out of the full step's code
     const char* sb = base + (long)kslab * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const char* src = sb + voff[j];
-      if (!tail_live(lane, wave, j, kslab, krem, kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
+      if (!tail_live(lane, wave, j, kslab, krem, kphys_end, kbump)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -212,12 +224,14 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
     const int kloc = KPI * (wave * NI + j) + lane / CPR;
     return (lane % CPR) ^ mc_swz<ROWS>(kloc);
   }
-  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave) {
+  __host__ __device__ __forceinline__ void init(const uint16_t* p, int ld_, const Axis& r, int row0, int lane, int wave,
+                                                int kbump = 0) {
     base = reinterpret_cast<const char*>(p);
     ld = ld_;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int kloc = KPI * (wave * NI + j) + lane / CPR;
+      const int kl = KPI * (wave * NI + j) + lane / CPR;
+      const int kloc = kl + (kl >= 32 ? kbump : 0);
       const int col = imin(row0 + lane_chunk(lane, wave, j) * 8, r.n - 8);  // runs beyond the axis: clamped
       // (a block axis counts its last block in full even when the operand ends inside it)
       int pcol = ax_phys(r, col);
@@ -248,18 +262,20 @@ template <int ROWS, int NW> struct DirectLoader<false, ROWS, NW> {
     const char* sb = base + (long)kslab * ld * 2;
     __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(sb + voff[j]), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
   }
-  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end) {
+  __host__ __device__ static __forceinline__ bool tail_live(int lane, int wave, int j, int kslab, int krem, int kphys_end,
+                                                            int kbump = 0) {
     const int kloc = KPI * (wave * NI + j) + lane / CPR;
-    return kloc < krem && kslab + kloc < kphys_end;
+    return kloc < krem && kslab + kloc + (kloc >= 32 ? kbump : 0) < kphys_end;
   }
   __host__ __device__ __forceinline__ long byte_offset(int j, int kslab) const { return (long)kslab * ld * 2 + voff[j]; }
-  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave) const {
+  __device__ __forceinline__ void issue_tail(uint4* op_tile, int kslab, int krem, int kphys_end, int lane, int wave,
+                                             int kbump = 0) const {
     asm volatile("; partial contraction step" ::: "memory");
     const char* sb = base + (long)kslab * ld * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const char* src = sb + voff[j];
-      if (!tail_live(lane, wave, j, kslab, krem, kphys_end)) src = reinterpret_cast<const char*>(g_zero_chunk);
+      if (!tail_live(lane, wave, j, kslab, krem, kphys_end, kbump)) src = reinterpret_cast<const char*>(g_zero_chunk);
       __builtin_amdgcn_global_load_lds(ARD_GLB_PTR(src), ARD_LDS_PTR(op_tile + (wave * NI + j) * 64), 16, 0, 0);
     }
   }
@@ -523,10 +539,11 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
   if (Kn > 0) {
     DirectLoader<A_KC, F_BM, NW> la;
     DirectLoader<B_KC, BN, NW> lb;
-    la.init(P.A, P.lda, am, m0, lane, wave);
+    const int kbump = MODE == 0 ? direct_kbump(kax) : 0;
+    la.init(P.A, P.lda, am, m0, lane, wave, kbump);
     if constexpr (MODE == 1) lb.init_pixels(P.B, P.cv, n0, lane, wave);
     else if constexpr (MODE == 2) lb.init_tap_columns(P.B, P.cv, P.N, n0, lane, wave);
-    else lb.init(P.B, P.ldb, bn, n0, lane, wave);
+    else lb.init(P.B, P.ldb, bn, n0, lane, wave, kbump);
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
     unsigned aaddr[TM][A_KC ? 4 : 1], baddr[TN][B_KC ? 4 : 1];
 #pragma unroll
@@ -560,10 +577,10 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
       const int krem = Kn - (s_lo + it) * 64;
       int ks, ksb;
       direct_slab<MODE>(P, kax, s_lo + it, ks, ksb);
-      const bool tail = krem < 64 || ks + 64 > kax.nphys;
+      const bool tail = krem < 64 || ks + 64 + kbump > kax.nphys;
       if (__builtin_expect(tail, 0)) {
-        la.issue_tail(lds + buf * OPA, ks, krem, kax.nphys, lane, wave);
-        lb.issue_tail(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, lane, wave);
+        la.issue_tail(lds + buf * OPA, ks, krem, kax.nphys, lane, wave, kbump);
+        lb.issue_tail(lds + NST * OPA + buf * OPB, ksb, krem, MODE == 1 ? 0x7fffffff : kax.nphys, lane, wave, kbump);
       } else {
         la.issue(lds + buf * OPA, ks, wave);
         lb.issue(lds + NST * OPA + buf * OPB, ksb, wave);
@@ -699,7 +716,7 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
       wg_barrier();
       issue(I0{}, I0{}, 0);
       int it0 = 0;
-      if (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && kax.bs % 64 == 0 && kax.nphys % kax.bs == 0)) {
+      if (kax.kind == AX_AFFINE || (kax.kind == AX_BAFF && (kax.bs % 64 == 0 || kax.bs == 32) && kax.nphys % kax.bs == 0)) {
         // steps whose stage it+NST is not the last one (only the last can be partial)
         for (; it0 + 2 * NST < S; it0 += NST) {
           steady_step(I0{}, it0);
@@ -1139,8 +1156,14 @@ static int32_t direct_envelope(const FastParams& F) {
     if (k.kind != AX_AFFINE && k.kind != AX_BAFF) return fail(ARD_EINVAL, "bounds proof: contraction map kind %d", k.kind);
     if (k.kind == AX_AFFINE && (k.step != 1 || k.off < 0 || k.off + k.n > k.nphys))
       return fail(ARD_ESHAPE, "bounds proof: contraction [%d, %d) outside its extent %d", k.off, k.off + k.n, k.nphys);
-    if (k.kind == AX_BAFF && (k.off < 0 || k.step < 0 || k.bs < 64 || (k.bs % 64)))
+    if (k.kind == AX_BAFF && (k.off < 0 || k.step < 0 || k.bs < 32 || (k.bs % 64 && k.bs != 32)))
       return fail(ARD_ESHAPE, "bounds proof: contraction blocks of %d", k.bs);
+    // 32-wide blocks: the upper half of a step lies `step` blocks further; the last kept block must
+    // start inside the extent (a step that reaches beyond it takes the tail rule, chunk by chunk)
+    if (k.kind == AX_BAFF && k.bs == 32 &&
+        ((k.nphys % 8) || (k.n % 32) || ((long)k.off + (long)(k.n / 32 - 1) * k.step) * 32 >= k.nphys))
+      return fail(ARD_ESHAPE, "bounds proof: 32-wide contraction blocks (%d of them from %d every %d) leave the extent %d", k.n / 32,
+                  k.off, k.step, k.nphys);
     // every contraction index a live lane touches is < k.nphys (full steps need ks + 64 <= nphys, the
     // lanes of a partial step test their own chunk against nphys)
     const long kphys = k.nphys;
@@ -1210,24 +1233,25 @@ static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) 
         for (int lane = 0; lane < 64; ++lane) {
           LA la;
           LB lb;
-          la.init(P.A, P.lda, am, wk.m0, lane, wave);
+          const int kbump = MODE == 0 ? direct_kbump(wk.kax) : 0;
+          la.init(P.A, P.lda, am, wk.m0, lane, wave, kbump);
           if constexpr (MODE == 1) lb.init_pixels(P.B, cvp, wk.n0, lane, wave);
           else if constexpr (MODE == 2) lb.init_tap_columns(P.B, P.cv, P.N, wk.n0, lane, wave);
-          else lb.init(P.B, P.ldb, bn, wk.n0, lane, wave);
+          else lb.init(P.B, P.ldb, bn, wk.n0, lane, wave, kbump);
           for (int s = s_lo; s < s_hi; ++s) {
             const int krem = Kn - s * 64;
             int ks, ksb;
             direct_slab<MODE>(P, wk.kax, s, ks, ksb);
-            const bool tail = krem < 64 || ks + 64 > wk.kax.nphys;
+            const bool tail = krem < 64 || ks + 64 + kbump > wk.kax.nphys;
             const int kend_b = MODE == 1 ? 0x7fffffff : wk.kax.nphys;
             for (int j = 0; j < LA::NI; ++j) {
-              if (tail && !LA::tail_live(lane, wave, j, ks, krem, wk.kax.nphys)) continue;
+              if (tail && !LA::tail_live(lane, wave, j, ks, krem, wk.kax.nphys, kbump)) continue;
               const long o = la.byte_offset(j, ks);
               out.a_lo = o < out.a_lo ? o : out.a_lo;
               out.a_hi = o + 16 > out.a_hi ? o + 16 : out.a_hi;
             }
             for (int j = 0; j < LB::NI; ++j) {
-              if (tail && !LB::tail_live(lane, wave, j, ksb, krem, kend_b)) continue;
+              if (tail && !LB::tail_live(lane, wave, j, ksb, krem, kend_b, kbump)) continue;
               const long o = lb.byte_offset(j, ksb);
               out.b_lo = o < out.b_lo ? o : out.b_lo;
               out.b_hi = o + 16 > out.b_hi ? o + 16 : out.b_hi;

@@ -464,7 +464,7 @@ static int32_t tile_lists(const LayerArgs& a, void* ws, size_t ws_bytes, hipStre
 // Tile pattern on the large-tile path: classes of tile rows / columns (see fast.hpp).
 // op 0: Y = X . W^T   1: dX = dY . W   2: dW = dY^T . X
 static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void* Bp, void* Cp, float alpha, int relu,
-                          hipStream_t stream, int32_t& st) {
+                          hipStream_t stream, int32_t& st, const void* relu_src = nullptr) {
   if (a.dtype != ARD_BF16 || dev_knobs().no_fast) return false;
   const int x = a.po->tile_r, y = a.po->tile_c, dp = a.po->dp, o = a.po->b - 1, TR = a.TR, TC = a.TC;
   const int B = a.B, I = a.I, O = a.O;
@@ -475,7 +475,8 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   ClassTab& t = F.tab;
   auto cnt = [](int total, int first, int step) { return first < total ? (total - first + step - 1) / step : 0; };
   if (op == 0) {
-    if ((256 % x) || (y % 64) || Pp > F_MAXCLS) return false;
+    // contraction blocks: whole 64-deep steps, or the 32-wide tiles of Section 3.2 taken two per step
+    if ((256 % x) || ((y % 64) && y != 32) || Pp > F_MAXCLS) return false;
     t.ncls = Pp;
     t.n_step = Pp, t.n_bs = x, t.n_phys = O;
     t.k_step = dp, t.k_bs = y, t.k_phys = I;
@@ -494,7 +495,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
     F.c_cols_mapped = 1;
     F.M = B, F.N = O;
   } else if (op == 1) {
-    if ((256 % y) || (x % 64) || dp > F_MAXCLS) return false;
+    if ((256 % y) || ((x % 64) && x != 32) || dp > F_MAXCLS) return false;
     t.ncls = dp;
     t.n_step = dp, t.n_bs = y, t.n_phys = I;
     t.k_step = Pp, t.k_bs = x, t.k_phys = O;
@@ -564,13 +565,14 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
                                        {1.98f, 1.14f, 1.16f, 0.66f, 0.44f}};   // weight gradient
   int steps = op == 2 ? ceil_div(B, 64) : 0;
   if (op != 2)
-    for (int c = 0; c < t.ncls; ++c) steps = steps > t.k_cnt[c] * (t.k_bs / 64) ? steps : t.k_cnt[c] * (t.k_bs / 64);
+    for (int c = 0; c < t.ncls; ++c) steps = imax(steps, ceil_div(t.k_cnt[c] * t.k_bs, 64));
   int heavy = 0, bm = 0, bn = 0, total = 0;
   float best = 0.0f;
   for (int ci = 0; ci < 5; ++ci) {
     const TileCfg& c = kTileCfgs[ci];
     if ((c.bn % t.n_bs) || (op == 2 && (c.bm % x))) continue;
     if (dev_knobs().class_tile && ci != dev_knobs().class_tile - 1) continue;
+    if (relu_src && c.bm == 256 && c.bn == 256) continue;  // (that tile only stores plain results)
     int h = 0;
     const int tot = count(c.bm, c.bn, h);
     if (tot == 0) continue;
@@ -584,6 +586,7 @@ static bool try_fast_tile(int op, const LayerArgs& a, const void* Ap, const void
   if (heavy < 64) return false;  // too few large tiles to fill the chip: the small-tile kernel does better
   F.alpha = alpha;
   F.relu = relu;
+  F.relu_src = (const uint16_t*)relu_src;
   F.total_tiles = total;
   if (op == 2) {
     ARD_LAUNCH(zero_dropped_tiles_kernel, dim3((unsigned)(TR * TC)), dim3(256), 0, stream, (uint16_t*)Cp, I, O, I,
@@ -1078,7 +1081,7 @@ extern "C" int32_t ard_drop_gemm_bwd_data(int32_t dtype, int32_t B, int32_t I, i
   size_t ws_used = 0;
   if (a.tile) {
     if (flags) return fail(ARD_EINVAL, "tile patterns take no layout flags");
-    if (!relu_src && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st)) return st;
+    if ((!relu_src || ((uintptr_t)relu_src & 3) == 0) && try_fast_tile(1, a, dY, W, dX, alpha, 0, stream, st, relu_src)) return st;
     TileLists L;
     st = tile_lists(a, ws, ws_bytes, stream, L);
     if (st) return st;

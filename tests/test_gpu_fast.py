@@ -61,6 +61,35 @@ def test_large_tile_path_other_shapes(B, I, O, x, y, dp, b):
     _tile_case(Xv, Wv, dYv, from_vals(Xv, "bf16"), from_vals(Wv, "bf16"), from_vals(dYv, "bf16"), x, y, dp, b, "large")
 
 
+@pytest.mark.parametrize("B,I,O,x,y,dp,b", [
+    (2048, 2048, 2048, 32, 32, 2, 1),      # the tile size of Section 3.2: two kept 32-wide blocks per 64-deep step
+    (1024, 2048, 2048, 32, 32, 3, 3),      # kept-block counts of both parities over the classes
+    (512, 784, 2048, 32, 32, 3, 1),        # input width ends 16 columns into its last tile column
+    (512, 1024, 1000, 32, 32, 2, 2),       # output width ends 8 rows into its last tile row
+    (1030, 1096, 1192, 32, 32, 7, 4),      # everything ragged
+    (2048, 2048, 2048, 64, 32, 5, 2),
+    (2048, 2048, 2048, 32, 128, 4, 3),
+])
+def test_large_tile_path_32_wide_tiles(B, I, O, x, y, dp, b):
+    print(f"32-wide tile case B={B} I={I} O={O} tile={x}x{y} dp={dp} b={b}", flush=True)
+    rng = np.random.default_rng(B + O + dp + 32)
+    Xv, Wv, dYv = (stored(rng.standard_normal(s), "bf16") for s in ((B, I), (O, I), (B, O)))
+    _tile_case(Xv, Wv, dYv, from_vals(Xv, "bf16"), from_vals(Wv, "bf16"), from_vals(dYv, "bf16"), x, y, dp, b, "tile32")
+
+
+def test_tile_pattern_data_gradient_with_fused_relu_gradient():
+    """dX gated by the sign of a second matrix in the epilogue of the tile-class product."""
+    B, I, O, x, y, dp, b = 1024, 2048, 2048, 32, 32, 3, 2
+    rng = np.random.default_rng(99)
+    Wv, dYv, src = (stored(rng.standard_normal(s), "bf16") for s in ((O, I), (B, O), (B, I)))
+    MW = P.expand_tile_mask(P.tile_mask(O, I, x, y, dp, b), O, I, x, y).astype(np.float64)
+    dX = torch.full((B, I), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ard.drop_gemm_bwd_data(from_vals(dYv, "bf16"), from_vals(Wv, "bf16"), ard.Pattern.tile(dp, b, x, y),
+                           relu_src=from_vals(src, "bf16"), out=dX)
+    ref = G.relu_bwd(G.drop_gemm_bwd_data(dYv, Wv, MW, np.ones(O, np.uint8)), src)
+    assert_parity(dX, ref, "bf16", zero_mask=(src <= 0), what="tile dX relu")
+
+
 @pytest.mark.parametrize("B,I,O", [(4096, 2048, 4096), (4000, 2056, 4104)])
 def test_large_dense_path(B, I, O):
     """Rate 0 (no pattern) through the large-tile kernels, all three products."""
