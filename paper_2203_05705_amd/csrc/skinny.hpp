@@ -48,7 +48,7 @@ __device__ __forceinline__ sk_bf16x8_t sk_load8(const uint16_t* p) {
 // Columns [p0, p0 + span) of a dense W for one workgroup, copied into LDS with 16-byte loads:
 // wl[m][c] = W[m][p0 + c] for m < O (p0 and span multiples of 8).  Kept input j is then read from
 // column ki(j) - p0 of the copy.
-constexpr int SK_MAX_COLS = 2048;  // physical inputs a workgroup can hold (up to 16 rows of bf16 in LDS)
+constexpr int SK_MAX_COLS = 4096;  // physical inputs a workgroup can hold (up to 16 rows of bf16 in LDS: 129 KiB of the 160)
 __device__ __forceinline__ int sk_pitch(int span) { return span + 8; }  // in elements: rows start 16 bytes apart in the banks
 __device__ __forceinline__ void sk_stage_w(uint16_t* wl, const SkinnyArgs& a, int p0, int span) {
   const int pitch = sk_pitch(span), chunks = span >> 3, total = a.O * chunks;

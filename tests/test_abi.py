@@ -171,7 +171,8 @@ def test_host_side_argument_errors():
     assert lib.ard_drop_gemm_fwd(7, 4, 8, 8, fake, fake, fake, ctypes.byref(ok), None, 1.0, 0, 0, None, 0, None) == -3
     assert lib.ard_drop_gemm_fwd(ard.F32, 4, 8, 8, None, fake, fake, ctypes.byref(ok), None, 1.0, 0, 0, None, 0, None) == -1
     tile = ard.CPattern(ard.PAT_TILE, 2, 1, 64, 64, 0, None, None, None, None, None)
-    assert lib.ard_drop_gemm_fwd(ard.BF16, 4, 128, 128, fake, fake, fake, ctypes.byref(tile), None, 1.0, 0, 0, None, 0, None) == -4
-    assert lib.ard_gemm_workspace_bytes(ard.BF16, 4, 128, 128, ctypes.byref(tile), None) > 0
+    # (an fp32 tile product keeps its kept-tile lists in the workspace)
+    assert lib.ard_drop_gemm_fwd(ard.F32, 4, 128, 128, fake, fake, fake, ctypes.byref(tile), None, 1.0, 0, 0, None, 0, None) == -4
+    assert lib.ard_gemm_workspace_bytes(ard.F32, 4, 128, 128, ctypes.byref(tile), None) > 0
     assert lib.ard_pattern_gen(ctypes.byref(ok), 0, 0, None, None, None, None, None, None, None) == -2
     assert lib.ard_pattern_gen(None, 8, 0, None, None, None, None, None, None, None) == -1
