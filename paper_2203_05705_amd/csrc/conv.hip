@@ -22,83 +22,133 @@ namespace ard {
 
 // ---- sensitivity score and selection -------------------------------------------------------
 
-// score[c] += sum over this block's share of (n, h, w) of floor(min(|a|, 2^15) * 2^24):
-// exact integers, so the result does not depend on the order of summation.
+// part[y * C + c] = sum over workgroup (c, y)'s share of (n, h, w) of floor(min(|a|, 2^15) * 2^24): exact
+// integers, so the result does not depend on the order of summation.  Every workgroup writes its own
+// partial (no atomics, nothing to clear beforehand); the selection kernel adds the few partials of a map.
+constexpr int kScoreParts = 64;  // at most this many workgroups share a feature map
+constexpr int kScorePlanes = 4;  // planes a wavefront reads at a time (x 2 pieces per lane = 8 loads in flight)
 template <typename T>
 __global__ __launch_bounds__(256) void channel_score_kernel(const T* A, int N, int C, int HW, int n_per_block, int vec,
-                                                           unsigned long long* score) {
+                                                           unsigned long long* part) {
   constexpr int CE = ElemTraits<T>::CE;
+  __shared__ unsigned long long wave_acc[4];
   const int c = blockIdx.x;
   const int n_begin = blockIdx.y * n_per_block;
   const int n_end = min(N, n_begin + n_per_block);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // floor(x * 2^24) for x in [0, 2^15] needs 40 bits; a float-to-64-bit conversion per element made this
+  // pass ALU-bound.  Split exactly instead: hi = trunc(x * 2^8) < 2^24, lo = trunc(x * 2^24 - hi * 2^16)
+  // < 2^16 (both products and the difference are exact in fp32), floor(x * 2^24) = hi * 2^16 + lo.
+  // hi and lo are summed in 32 bits and folded into the 64-bit sum every `flush` (at most 128 elements).
   unsigned long long acc = 0;
+  uint32_t acc_hi = 0, acc_lo = 0;
   auto add = [&](T v) {
-    const float a = fminf(fabsf(ElemTraits<T>::to_f32(v)), 32768.0f);
-    acc += (unsigned long long)(a * 16777216.0f);
+    const float x = fminf(fabsf(ElemTraits<T>::to_f32(v)), 32768.0f);
+    const uint32_t hi = (uint32_t)(x * 256.0f);
+    const float lo_f = fmaf(-65536.0f, (float)hi, x * 16777216.0f);
+    acc_hi += hi;
+    acc_lo += (uint32_t)lo_f;
+  };
+  auto flush = [&]() {
+    acc += ((unsigned long long)acc_hi << 16) + acc_lo;
+    acc_hi = acc_lo = 0;
   };
   if (vec) {
-    // planes are whole numbers of 16-byte pieces: a wavefront walks one plane at a time
+    // planes are whole numbers of 16-byte pieces.  A wavefront takes kScorePlanes planes at a time and its
+    // lanes two pieces of each: 8 loads, all unconditional (clamped index, contribution zeroed afterwards)
+    // so that they are in flight together -- a load behind a branch is waited for before the next is issued.
     const int chunks = HW / CE;
-    for (int n = n_begin + wave; n < n_end; n += 4) {
-      const uint4* p = reinterpret_cast<const uint4*>(A + ((long)n * C + c) * HW);
-      for (int i = lane; i < chunks; i += 64) {
-        const uint4 q = p[i];
-        const T* e = reinterpret_cast<const T*>(&q);
+    const int planes = n_end - n_begin;
+    const T* const a0 = A + ((long)n_begin * C + c) * HW;
+    for (int pb = wave * kScorePlanes; pb < planes; pb += 4 * kScorePlanes)
+      for (int cb = lane; cb < chunks; cb += 128) {
+        uint4 q[kScorePlanes][2];
 #pragma unroll
-        for (int t = 0; t < CE; ++t) add(e[t]);
+        for (int u = 0; u < kScorePlanes; ++u) {
+          const uint4* pl = reinterpret_cast<const uint4*>(a0 + (long)min(pb + u, planes - 1) * C * HW);
+#pragma unroll
+          for (int v = 0; v < 2; ++v) q[u][v] = pl[min(cb + 64 * v, chunks - 1)];
+        }
+#pragma unroll
+        for (int u = 0; u < kScorePlanes; ++u)
+#pragma unroll
+          for (int v = 0; v < 2; ++v) {
+            const bool live = pb + u < planes && cb + 64 * v < chunks;
+            const uint4 z = live ? q[u][v] : uint4{0u, 0u, 0u, 0u};
+            const T* e = reinterpret_cast<const T*>(&z);
+#pragma unroll
+            for (int t = 0; t < CE; ++t) add(e[t]);   // (a zero piece adds nothing)
+          }
+        flush();
       }
-    }
   } else {
     for (int n = n_begin; n < n_end; ++n) {
       const T* p = A + ((long)n * C + c) * HW;
-      for (int i = threadIdx.x; i < HW; i += 256) add(p[i]);
+      for (int i = threadIdx.x; i < HW; i += 256) {
+        add(p[i]);
+        flush();
+      }
     }
   }
-  // wavefront reduction, then one integer atomic per wavefront
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-  if (lane == 0 && acc) atomicAdd(score + c, acc);
+  if (lane == 0) wave_acc[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) part[(long)blockIdx.y * C + c] = wave_acc[0] + wave_acc[1] + wave_acc[2] + wave_acc[3];
 }
 
-__global__ void zero_u64_kernel(unsigned long long* p, int n) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
-
-// Drop the n_drop channels that come first in ascending (score, index) order; write the
-// mask (1 = kept) and the ascending kept list (ballot + mbcnt compaction, one workgroup).
-__global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned long long* score_g, int C, int n_drop,
-                                                             uint8_t* mask, int* keep, int* count) {
-  constexpr int STAGED = 4096;  // scores kept in LDS for the rank loop (larger C reads them from memory)
-  __shared__ unsigned long long staged[STAGED];
+// Adds the `parts` partial scores of every map (score_out gets the totals), then drops the n_drop maps that
+// come first in ascending (score, index) order; writes the mask (1 = kept) and the ascending kept list
+// (ballot + mbcnt compaction, one workgroup).  The rank of a map is counted by four threads, a quarter
+// of the other maps each.  IN_LDS: the scores fit the staging array (else they are re-read from memory).
+// The code is kept short on purpose: a single workgroup that runs once pays every instruction-cache line it
+// touches with a fetch from memory (3 KB of straight-line code took 10 us for 256 maps).
+template <bool IN_LDS>
+__global__ __launch_bounds__(1024) void channel_select_kernel(const unsigned long long* part, int parts,
+                                                             unsigned long long* score_out, int C, int n_drop, uint8_t* mask,
+                                                             int* keep, int* count) {
+  constexpr int STAGED = 4096;
+  __shared__ unsigned long long staged[IN_LDS ? STAGED : 1];
   __shared__ int wave_tot[16];
   __shared__ int running_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) running_s = 0;
-  const bool in_lds = C <= STAGED;
-  if (in_lds)
-    for (int i = tid; i < C; i += 1024) staged[i] = score_g[i];
-  const unsigned long long* score = in_lds ? staged : score_g;
+  for (int i = tid; i < C; i += 1024) {
+    unsigned long long t = 0;
+#pragma unroll 1
+    for (int y0 = 0; y0 < parts; y0 += 8) {
+      unsigned long long v[8];  // eight unconditional loads in flight (clamped index, contribution zeroed)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = part[(long)min(y0 + u, parts - 1) * C + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += y0 + u < parts ? v[u] : 0ull;
+    }
+    score_out[i] = t;
+    if (IN_LDS) staged[i] = t;
+  }
+  if (!IN_LDS) __threadfence_block();
   __syncthreads();
-  for (int base = 0; base < C; base += 1024) {
-    const int c = base + tid;
-    bool kept = false;
+  for (int base = 0; base < C; base += 256) {
+    const int c = base + (tid >> 2), part_id = tid & 3;
+    int rank = 0;
     if (c < C) {
-      const unsigned long long s = score[c];
-      int rank = 0;
-#pragma unroll 8
-      for (int o = 0; o < C; ++o) {
-        const unsigned long long so = score[o];
+      const int o_lo = (int)((long)C * part_id / 4), o_hi = (int)((long)C * (part_id + 1) / 4);
+      const unsigned long long s = IN_LDS ? staged[c] : score_out[c];
+#pragma unroll 4
+      for (int o = o_lo; o < o_hi; ++o) {
+        const unsigned long long so = IN_LDS ? staged[o] : score_out[o];
         rank += (so < s || (so == s && o < c)) ? 1 : 0;
       }
-      kept = rank >= n_drop;
-      mask[c] = kept ? 1 : 0;
     }
+    rank += __shfl_xor(rank, 1, 64);
+    rank += __shfl_xor(rank, 2, 64);
+    const bool kept = c < C && part_id == 0 && rank >= n_drop;
+    if (c < C && part_id == 0) mask[c] = kept ? 1 : 0;
     const unsigned long long bal = __ballot(kept);
     const int r = __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0));
     if (lane == 0) wave_tot[wave] = __popcll(bal);
     __syncthreads();
     int before = running_s, total = 0;
+#pragma unroll 1
     for (int w = 0; w < 16; ++w) {
       int t = wave_tot[w];
       if (w < wave) before += t;
@@ -669,6 +719,7 @@ struct ConvArgs {
 
 struct ConvWs {
   unsigned long long* score;
+  unsigned long long* score_part;  // [kScoreParts x C] partial scores of the workgroups
   int* rank;
   char* wp;
   float* part;
@@ -706,6 +757,7 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
   const size_t taps = (size_t)a.kh * a.kw;
   w.splits = wgrad_splits(a);
   w.score = (unsigned long long*)take((size_t)a.C * 8);
+  w.score_part = (unsigned long long*)take((size_t)a.C * 8 * kScoreParts);
   w.rank = (int*)take((size_t)a.C * 4);
   w.wp = take((size_t)a.Cout * a.C * taps * a.es);
   w.part = (float*)take((size_t)w.splits * a.Cout * a.C * taps * 4);
@@ -959,19 +1011,23 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if (!A || !d_mask || !d_keep) return fail(ARD_EINVAL, "SELECT needs A, d_mask and d_keep");
     if ((long)a.N * a.H * a.W > (1L << 24)) return fail(ARD_ESHAPE, "SELECT needs N*H*W <= 2^24");
     unsigned long long* score = d_score ? (unsigned long long*)d_score : w.score;
-    ARD_LAUNCH(zero_u64_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, score, a.C);
-    ARD_LAUNCH_CHECK("zero_u64_kernel");
     int ysplit = ceil_div(2048, a.C);
     if (ysplit > a.N) ysplit = a.N;
+    if (ysplit > kScoreParts) ysplit = kScoreParts;
     if (ysplit < 1) ysplit = 1;
     const int n_per_block = ceil_div(a.N, ysplit);
+    const int parts = ceil_div(a.N, n_per_block);
     const int vec = ((a.H * a.W) % ce) == 0 && al16c(A);
-    ARD_LAUNCH(channel_score_kernel<T>, dim3(a.C, ceil_div(a.N, n_per_block)), dim3(256), 0, stream,
-                       (const T*)A, a.N, a.C, a.H * a.W, n_per_block, vec, score);
+    ARD_LAUNCH(channel_score_kernel<T>, dim3(a.C, parts), dim3(256), 0, stream, (const T*)A, a.N, a.C, a.H * a.W,
+                       n_per_block, vec, w.score_part);
     ARD_LAUNCH_CHECK("channel_score_kernel");
     const int n_drop = (int)floor(rate * (double)a.C);
-    ARD_LAUNCH(channel_select_kernel, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)score, a.C,
-                       n_drop, d_mask, d_keep, d_count);
+    if (a.C <= 4096)
+      ARD_LAUNCH(channel_select_kernel<true>, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)w.score_part, parts,
+                         score, a.C, n_drop, d_mask, d_keep, d_count);
+    else
+      ARD_LAUNCH(channel_select_kernel<false>, dim3(1), dim3(1024), 0, stream, (const unsigned long long*)w.score_part, parts,
+                         score, a.C, n_drop, d_mask, d_keep, d_count);
     ARD_LAUNCH_CHECK("channel_select_kernel");
     return ARD_OK;
   }
