@@ -571,10 +571,18 @@ def extra_small(ard, torch):
     res = {"config1_fp32_layer_us": {k: round(event_us(torch, f)["median"], 2) for k, f in calls.items()},
            "config1_fp32_layer_us_cache_cold": {k: round(event_us(torch, f, reps=10, blocks=3, flush=flush)["median"], 2)
                                                 for k, f in calls.items()}}
-    tp = ard.Pattern.tile(3, 2, 64, 64)
-    res["pattern_gen_us"] = dict(rows_2048=round(event_us(torch, lambda: ard.pattern_gen(ard.Pattern.row(3, 2), 2048))["median"], 2),
-                                 tiles_64x64_grid=round(event_us(torch, lambda: ard.pattern_gen(tp, 4096, 4096))["median"], 2),
-                                 note="includes the binding's output allocations; one workgroup, latency-bound")
+    # pattern_gen at the C ABI, outputs allocated once (the binding's convenience wrapper allocates them per call)
+    lib, st = ard.lib(), torch.cuda.current_stream().cuda_stream
+    rp, tp = ard.Pattern.row(3, 2).c(), ard.Pattern.tile(3, 2, 64, 64).c()
+    o_row, o_tile = ard.pattern_gen(ard.Pattern.row(3, 2), 2048), ard.pattern_gen(ard.Pattern.tile(3, 2, 64, 64), 4096, 4096)
+    P = lambda t: t.data_ptr()
+    res["pattern_gen_us"] = dict(
+        rows_2048=round(event_us(torch, lambda: lib.ard_pattern_gen(C.byref(rp), 2048, 0, P(o_row["mask"]), P(o_row["keep"]),
+                                                                    P(o_row["count"]), None, None, None, st))["median"], 2),
+        tiles_64x64_grid=round(event_us(torch, lambda: lib.ard_pattern_gen(
+            C.byref(tp), 4096, 4096, P(o_tile["mask"]), P(o_tile["keep"]), P(o_tile["count"]), P(o_tile["rowptr"]),
+            P(o_tile["colptr"]), P(o_tile["csc_rows"]), st))["median"], 2),
+        note="one workgroup (two launches for a tile grid), latency-bound; outputs preallocated")
     wlc = WL.conv_layer()
     A = ard.to_device(wlc.arrays["A"])
     N, C, H, Wd = A.shape

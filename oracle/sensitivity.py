@@ -168,3 +168,31 @@ def conv_fwd_blocks(A, Wt, block_keep, x, y, stride=1, pad=1):
     Ho = (A.shape[2] + 2 * pad - KH) // stride + 1
     Wo = (A.shape[3] + 2 * pad - KW) // stride + 1
     return np.stack(out).reshape(N, Co, Ho, Wo)
+
+
+def conv_bwd_rows(dY, A, Wt, row_keep, stride=1, pad=1):
+    """Gradients of conv_fwd_rows: the product of Section 5.2.1 only involves the kept rows of the input
+    matrix, so only those rows carry gradient.  Per image, with G[p, co] = dY[n, co, p] on kept rows p and 0
+    on dropped ones:  dWmat[co, q] += sum_p G[p, co] X_n[p, q],  dX_n[p, q] = sum_co G[p, co] Wmat[co, q],
+    and dA collects dX_n back through the positions the input matrix was cut from.
+    Returns (dA[N, C, H, W], dWt[Co, C, KH, KW])."""
+    A = np.asarray(A, dtype=np.float64)
+    Wt = np.asarray(Wt, dtype=np.float64)
+    dY = np.asarray(dY, dtype=np.float64)
+    N, C, H, W = A.shape
+    Co, _, KH, KW = Wt.shape
+    Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    Wm = Wt.reshape(Co, -1)
+    dWm = np.zeros_like(Wm)
+    dA = np.zeros_like(A)
+    for n in range(N):
+        X = input_matrix(A[n], (KH, KW), stride, pad)
+        G = dY[n].reshape(Co, Ho * Wo).T * row_keep[n].astype(np.float64)[:, None]      # [rows x Co]
+        dWm += G.T @ X
+        dX = G @ Wm                                                                      # [rows x C*KH*KW]
+        dAp = np.zeros((C, H + 2 * pad, W + 2 * pad))
+        for oh in range(Ho):
+            for ow in range(Wo):
+                dAp[:, oh * stride:oh * stride + KH, ow * stride:ow * stride + KW] += dX[oh * Wo + ow].reshape(C, KH, KW)
+        dA[n] = dAp[:, pad:pad + H, pad:pad + W]
+    return dA, dWm.reshape(Wt.shape)

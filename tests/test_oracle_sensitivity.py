@@ -147,3 +147,46 @@ def test_forward_under_row_and_block_masks():
                 ref = sum(X[p, q] * Wm[co, q] for q in range(27) if bk[n, p // x, q // y])
                 assert abs(Yb[n, co, p // 4, p % 4] - ref) < 1e-12
     assert np.allclose(S.conv_fwd_blocks(A, Wt, np.ones((2, 7, 6), np.uint8), x, y, 1, 1), full, atol=1e-12)
+
+
+@pytest.mark.parametrize("stride,pad,k", [(1, 1, 3), (2, 1, 3), (1, 0, 2), (1, 2, 5)])
+def test_row_pattern_gradients_are_autograd_of_the_masked_convolution(stride, pad, k):
+    """Y = (row kept) * conv(A, W): torch's convolution and autograd on the output masked position by position."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(10 + stride + pad + k)
+    N, C, H, W, Co = 2, 3, 7, 6, 4
+    A = rng.standard_normal((N, C, H, W))
+    Wt = rng.standard_normal((Co, C, k, k))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    keep = (rng.uniform(size=(N, Ho * Wo)) < 0.6).astype(np.uint8)
+    keep[0, 0], keep[1, -1] = 1, 0
+    dY = rng.standard_normal((N, Co, Ho, Wo))
+    At, Wtt = torch.tensor(A, requires_grad=True), torch.tensor(Wt, requires_grad=True)
+    Y = F.conv2d(At, Wtt, stride=stride, padding=pad) * torch.tensor(keep.reshape(N, 1, Ho, Wo).astype(np.float64))
+    assert np.allclose(S.conv_fwd_rows(A, Wt, keep, stride, pad), Y.detach().numpy(), atol=1e-12)
+    (Y * torch.tensor(dY)).sum().backward()
+    dA, dW = S.conv_bwd_rows(dY, A, Wt, keep, stride, pad)
+    assert np.allclose(dA, At.grad.numpy(), atol=1e-11)
+    assert np.allclose(dW, Wtt.grad.numpy(), atol=1e-11)
+
+
+def test_row_pattern_gradients_special_cases():
+    """All rows kept: the plain convolution's gradients (oracle/conv.py).  No row kept: zero.  Gradient arriving
+    on a dropped position has no influence."""
+    rng = np.random.default_rng(21)
+    N, C, H, W, Co = 2, 4, 6, 6, 3
+    A, Wt, dY = rng.standard_normal((N, C, H, W)), rng.standard_normal((Co, C, 3, 3)), rng.standard_normal((N, Co, 6, 6))
+    ones = np.ones((N, 36), np.uint8)
+    dA, dW = S.conv_bwd_rows(dY, A, Wt, ones)
+    allc = np.ones(C, np.uint8)
+    assert np.allclose(dA, OC.conv_bwd_data(dY, Wt, allc, (H, W)), atol=1e-11)
+    assert np.allclose(dW, OC.conv_bwd_weight(dY, A, allc), atol=1e-11)
+    dA0, dW0 = S.conv_bwd_rows(dY, A, Wt, np.zeros((N, 36), np.uint8))
+    assert not dA0.any() and not dW0.any()
+    keep = (rng.uniform(size=(N, 36)) < 0.5).astype(np.uint8)
+    dY2 = dY + 9.0 * (1 - keep.reshape(N, 1, 6, 6))
+    a1, w1 = S.conv_bwd_rows(dY, A, Wt, keep)
+    a2, w2 = S.conv_bwd_rows(dY2, A, Wt, keep)
+    assert np.array_equal(a1, a2) and np.array_equal(w1, w2)
+    assert not np.allclose(a1, dA)
