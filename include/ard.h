@@ -288,7 +288,9 @@ typedef enum {
   ARD_CONV_FWD = 1,       /* out = Y[N,Cout,Ho,Wo]                                        */
   ARD_CONV_BWD_DATA = 2,  /* out = dA[N,C,H,W], dropped channels exactly 0               */
   ARD_CONV_BWD_WEIGHT = 3,/* out = dWt[Cout,C,KH,KW], dropped channels exactly 0         */
-  ARD_CONV_FWD_ROWS = 4   /* out = Y under a row-based sensitivity-aware pattern (below)  */
+  ARD_CONV_FWD_ROWS = 4,  /* out = Y under a row-based sensitivity-aware pattern (below)  */
+  ARD_CONV_BWD_DATA_ROWS = 5,   /* out = dA, gradient of FWD_ROWS                         */
+  ARD_CONV_BWD_WEIGHT_ROWS = 6  /* out = dWt, gradient of FWD_ROWS                        */
 } ard_conv_mode;
 /*
  * bf16, stride 1: every pass first copies what it convolves into a channels-last, zero-bordered grid
@@ -322,6 +324,11 @@ size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, 
  *   as n * Ho*Wo + p, ascending, n_keep entries (0 .. N*Ho*Wo), d_mask[N*Ho*Wo] is the same set as a
  *   0/1 mask (both as written by ard_sens_row_pattern).  out = Y[N,Cout,Ho,Wo], dropped positions +0.0.
  *   Needs A, Wt.  fp32 and strided layers compute every position and zero the dropped ones.
+ * BWD_DATA_ROWS / BWD_WEIGHT_ROWS: the gradients of FWD_ROWS with respect to A and Wt.  Only kept rows took
+ *   part in the product, so gradient arriving on a dropped position counts as zero: d_mask[N*Ho*Wo] is the
+ *   row mask, dYin is copied once with the dropped positions zeroed and BWD_DATA / BWD_WEIGHT run on that
+ *   copy with every channel kept (no time is saved over an undropped layer; n_keep, d_keep are ignored).
+ *   Needs dYin, d_mask and Wt (data) or A (weight).
  * FWD / BWD_DATA / BWD_WEIGHT read the kept channels from d_keep (n_keep entries,
  *   n_keep given on the host) and never load a dropped channel:
  *   FWD        Y  = conv(A restricted to kept channels, Wt)       needs A, Wt

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libard.so")
 
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3
-CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT, CONV_FWD_ROWS = 0, 1, 2, 3, 4
+CONV_SELECT, CONV_FWD, CONV_BWD_DATA, CONV_BWD_WEIGHT, CONV_FWD_ROWS, CONV_BWD_DATA_ROWS, CONV_BWD_WEIGHT_ROWS = 0, 1, 2, 3, 4, 5, 6
 CONV_REUSE_A, CONV_REUSE_DY = 0x100, 0x200
 IN_COMPACT, OUT_COMPACT, W_COMPACT, DW_COMPACT = 1, 2, 4, 8
 
@@ -539,6 +539,19 @@ def conv_fwd_rows(A, Wt, row_pat, n_keep, stride=1, pad=1, ws=None, stream=None,
     fmap_drop_conv(CONV_FWD_ROWS, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
                    keep=row_pat["keep"], mask=row_pat["mask"], ws=ws, stream=stream)
     return Y
+
+
+def conv_bwd_rows(dY, A, Wt, row_pat, stride=1, pad=1, ws=None, stream=None, out=None):
+    """Gradients (dA, dWt) of conv_fwd_rows: gradient arriving on dropped output positions counts as zero."""
+    _dev(dY), _dev(A), _dev(Wt)
+    Cout, _, kh, kw = Wt.shape
+    dA, dWt = out if out is not None else (_out(A.shape, A.dtype, A.device), _out(Wt.shape, Wt.dtype, Wt.device))
+    dt = _dtype_code(A)
+    fmap_drop_conv(CONV_BWD_DATA_ROWS, A.shape, dt, Cout, (kh, kw), stride, pad, Wt=Wt, dY=dY, out=dA, mask=row_pat["mask"],
+                   ws=ws, stream=stream)
+    fmap_drop_conv(CONV_BWD_WEIGHT_ROWS, A.shape, dt, Cout, (kh, kw), stride, pad, A=A, dY=dY, out=dWt, mask=row_pat["mask"],
+                   ws=ws, stream=stream)
+    return dA, dWt
 
 
 def _out_hw(H, W, ksize, stride, pad):

@@ -643,6 +643,20 @@ __global__ __launch_bounds__(256) void zero_dropped_pixels_kernel(T* Y, const ui
     if (!m[i]) p[i] = (T)0;
 }
 
+// out = Y with the positions of dropped rows of the input matrix as +0.0 (the gradient of a row pattern's
+// forward pass only arrives on kept positions); one workgroup per (channel, image) plane
+template <typename T>
+__global__ __launch_bounds__(256) void mask_pixels_kernel(const T* Y, const uint8_t* row_mask, int Cout, int HW, T* out) {
+  const int co = blockIdx.x, n = blockIdx.y;
+  const long base = ((long)n * Cout + co) * HW;
+  const uint8_t* m = row_mask + (long)n * HW;
+  for (int i = threadIdx.x; i < HW; i += 256) out[base + i] = m[i] ? Y[base + i] : (T)0;
+}
+__global__ void iota_kernel(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
+
 // position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
 __device__ __forceinline__ int kept_rank(const int* keep, int n_keep, int c) {
   int lo = 0, hi = n_keep - 1;
@@ -721,6 +735,8 @@ struct ConvWs {
   unsigned long long* score;
   unsigned long long* score_part;  // [kScoreParts x C] partial scores of the workgroups
   int* rank;
+  int* all_chan;   // 0 .. C-1: the kept list of the passes that drop no channel
+  char* dy_rows;   // [N, Cout, Ho, Wo] dtype: dY with the dropped rows of a row pattern zeroed
   char* wp;
   float* part;
   uint16_t *grid_a, *grid_y;  // channels-last grids of the fast path (NULL when it does not apply)
@@ -759,6 +775,8 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
   w.score = (unsigned long long*)take((size_t)a.C * 8);
   w.score_part = (unsigned long long*)take((size_t)a.C * 8 * kScoreParts);
   w.rank = (int*)take((size_t)a.C * 4);
+  w.all_chan = (int*)take((size_t)a.C * 4);
+  w.dy_rows = take((size_t)a.N * a.Cout * a.Ho * a.Wo * a.es);
   w.wp = take((size_t)a.Cout * a.C * taps * a.es);
   w.part = (float*)take((size_t)w.splits * a.Cout * a.C * taps * 4);
   w.grid_a = w.grid_y = w.gwp = nullptr;
@@ -1049,6 +1067,21 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
                a.Ho * a.Wo);
     ARD_LAUNCH_CHECK("zero_dropped_pixels_kernel");
     return ARD_OK;
+  }
+  if (a.mode == ARD_CONV_BWD_DATA_ROWS || a.mode == ARD_CONV_BWD_WEIGHT_ROWS) {
+    // gradients of FWD_ROWS: positions of dropped rows carry no gradient.  dY is copied once with those
+    // positions zeroed, then the ordinary passes run over every position with every channel kept.
+    if (!dYin || !d_mask || !out) return fail(ARD_EINVAL, "the row-pattern gradients need dYin, d_mask and out");
+    if (a.reuse) return fail(ARD_EUNSUPPORTED, "the row-pattern gradients build their own grids");
+    ARD_LAUNCH(mask_pixels_kernel<T>, dim3(a.Cout, a.N), dim3(256), 0, stream, (const T*)dYin, (const uint8_t*)d_mask, a.Cout,
+               a.Ho * a.Wo, (T*)w.dy_rows);
+    ARD_LAUNCH_CHECK("mask_pixels_kernel");
+    ARD_LAUNCH(iota_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, w.all_chan, a.C);
+    ARD_LAUNCH_CHECK("iota_kernel");
+    ConvArgs full = a;
+    full.mode = a.mode == ARD_CONV_BWD_DATA_ROWS ? ARD_CONV_BWD_DATA : ARD_CONV_BWD_WEIGHT;
+    full.n_keep = a.C;
+    return conv_run<T>(full, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan, nullptr, nullptr, w, stream);
   }
   if (a.n_keep < 0 || a.n_keep > a.C) return fail(ARD_EINVAL, "n_keep=%d outside 0..%d", a.n_keep, a.C);
   if (a.n_keep > 0 && a.n_keep < a.C && !d_keep) return fail(ARD_EINVAL, "d_keep is required");

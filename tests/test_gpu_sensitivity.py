@@ -88,6 +88,13 @@ def _rows_forward_case(dtype, N, C, Cout, H, W, k, stride, pad, x, m, n_, seed):
     ref = S.conv_fwd_rows(Av, Wv, mask, stride, pad)
     zero = np.broadcast_to((mask == 0).reshape(N, 1, *ref.shape[2:]), ref.shape)
     assert_parity(Y, ref, dtype, zero, "conv rows Y")
+    if stride == 1:
+        # gradients of the same pass (the library's data gradient is built for stride 1)
+        dYv = stored(rng.standard_normal(ref.shape), dtype)
+        dA, dWt = ard.conv_bwd_rows(from_vals(dYv, dtype), Ad, Wd, rp, stride, pad)
+        rA, rW = S.conv_bwd_rows(dYv, Av, Wv, mask, stride, pad)
+        assert_parity(dA, rA, dtype, None, "conv rows dA")
+        assert_parity(dWt, rW, dtype, None, "conv rows dWt")
     return nk, N * rows
 
 
