@@ -386,6 +386,20 @@ int32_t ard_sens_block_pattern(int32_t N, int32_t row_bands, int32_t col_blocks,
                                uint64_t seed, uint64_t iteration, uint8_t* d_sens_out, uint8_t* d_block_keep,
                                void* stream);
 
+/*
+ * Forward convolution under a block-based sensitivity-aware pattern (Section 5.2.2): entry (p, q) of an
+ * image's input matrix takes part iff d_block_keep[(image*RB + p/x)*CB + q/y] != 0 (the array
+ * ard_sens_block_pattern writes; y = 0: blocks span the width).  out = Y[N,Cout,Ho,Wo], every element
+ * written.  Arguments and workspace as for ard_fmap_drop_conv(ARD_CONV_FWD) with every channel kept.
+ * This pass runs on the general convolution engine, which applies the block mask while it gathers the
+ * patches: it is correct in both dtypes and for any stride, and it saves no time (dropped blocks are
+ * loaded as zeros, not skipped).
+ */
+int32_t ard_conv_fwd_blocks(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
+                            int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y,
+                            const void* A, const void* Wt, const uint8_t* d_block_keep, void* out,
+                            void* ws, size_t ws_bytes, void* stream);
+
 /* ---- dynamic dropout-ratio tuning (Section 5.3, host only) ---------------- */
 
 /*

@@ -96,6 +96,7 @@ _SIGS = {
     "ard_lstm_bwd": (C.c_int32, [C.c_int32] * 5 + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]),
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
     "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
+    "ard_conv_fwd_blocks": (C.c_int32, [C.c_int32] * 12 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]),
     "ard_sens_regions": (C.c_int32, [C.c_int32] * 10 + [C.c_void_p] * 3),
     "ard_sens_predict": (C.c_int32, [C.c_int32] * 13 + [C.c_float, C.c_uint64, C.c_uint64] + [C.c_void_p] * 5),
     "ard_sens_row_pattern": (C.c_int32, [C.c_int32] * 3 + [C.c_void_p, C.c_double, C.c_double, C.c_uint64, C.c_uint64] + [C.c_void_p] * 4),
@@ -538,6 +539,20 @@ def conv_fwd_rows(A, Wt, row_pat, n_keep, stride=1, pad=1, ws=None, stream=None,
     Y = _out((N, Cout, Ho, Wo), A.dtype, A.device) if out is None else out
     fmap_drop_conv(CONV_FWD_ROWS, A.shape, _dtype_code(A), Cout, (kh, kw), stride, pad, n_keep=n_keep, A=A, Wt=Wt, out=Y,
                    keep=row_pat["keep"], mask=row_pat["mask"], ws=ws, stream=stream)
+    return Y
+
+
+def conv_fwd_blocks(A, Wt, block_keep, x, y, stride=1, pad=1, ws=None, stream=None, out=None):
+    """Forward convolution under a block pattern (block_keep from sens_block_pattern, uint8 [N*RB*CB])."""
+    _dev(A), _dev(Wt), _dev(block_keep)
+    N, Cc, H, W = A.shape
+    Cout, _, kh, kw = Wt.shape
+    Ho, Wo = _out_hw(H, W, (kh, kw), stride, pad)
+    Y = _out((N, Cout, Ho, Wo), A.dtype, A.device) if out is None else out
+    dt = _dtype_code(A)
+    ws = _workspace(conv_workspace_bytes(dt, N, Cc, H, W, Cout, kh, kw, stride, pad), A.device, ws)
+    _check(lib().ard_conv_fwd_blocks(dt, N, Cc, H, W, Cout, kh, kw, stride, pad, int(x), int(y), A.data_ptr(), Wt.data_ptr(),
+                                     block_keep.data_ptr(), Y.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
     return Y
 
 

@@ -187,6 +187,10 @@ struct ConvGeom {
   int KH, KW, stride, pad_h, pad_w;
   int Ck;                    // gathered channels per tap
   const int* chan;           // channel list (NULL = identity)
+  // block-based sensitivity-aware pattern (Section 5.2.2), forward only: entry (p, q) of an image's input
+  // matrix, q = (channel * KH + kh) * KW + kw, is absent when blk[(n * RB + p / bx) * CB + q / by] == 0
+  const uint8_t* blk;
+  int bx, by, RB, CB;
 };
 
 // B operand of FWD / BWD_DATA: row = position (n, oh, ow), contraction index k = tap*Ck + cc.
@@ -199,6 +203,7 @@ struct PatchLoader {
   ConvGeom g;
   int K;
   long ibase[PASSES];
+  int bband[PASSES];  // (n * RB + row band) * CB of this thread's position (block pattern only)
   int ih0[PASSES], iw0[PASSES];
   bool rvalid[PASSES];
   int lr[PASSES], lc[PASSES];
@@ -230,6 +235,7 @@ struct PatchLoader {
       ibase[ps] = (long)n * g.Cin * g.Hin * g.Win;
       ih0[ps] = oh * g.stride - g.pad_h;
       iw0[ps] = ow * g.stride - g.pad_w;
+      bband[ps] = g.blk ? (n * g.RB + rem / g.bx) * g.CB : 0;
     }
   }
 
@@ -253,7 +259,8 @@ struct PatchLoader {
             const int ih = ih0[ps] + kh, iw = iw0[ps] + kw;
             if (ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win) {
               const int ch = g.chan ? g.chan[cc] : cc;
-              x = src[ibase[ps] + ((long)ch * g.Hin + ih) * g.Win + iw];
+              if (!g.blk || g.blk[bband[ps] + (ch * g.KH * g.KW + tap) / g.by])
+                x = src[ibase[ps] + ((long)ch * g.Hin + ih) * g.Win + iw];
             }
           }
           tmp[e] = x;
@@ -729,6 +736,9 @@ __global__ __launch_bounds__(256) void wgrad_grid_reduce_kernel(const float* par
 struct ConvArgs {
   int32_t mode, dtype, N, C, H, W, Cout, kh, kw, stride, pad, n_keep, Ho, Wo, es;
   int32_t reuse;  // ARD_CONV_REUSE_* bits of the mode argument
+  // block-based pattern of the forward pass (ard_conv_fwd_blocks): x-by-y blocks of the input matrices
+  const uint8_t* blk;
+  int32_t bx, by;
 };
 
 struct ConvWs {
@@ -1095,7 +1105,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     if ((a.reuse & ARD_CONV_REUSE_DY) && a.mode == ARD_CONV_BWD_WEIGHT && !(a.kh - 1 == 2 * a.pad && a.kw - 1 == 2 * a.pad))
       return fail(ARD_EUNSUPPORTED, "the weight gradient shares dY's grid with the data gradient only for k - 1 = 2 pad");
   }
-  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast) {
+  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast && !a.blk) {
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
     if (a.mode == ARD_CONV_BWD_WEIGHT && (!dYin || !A)) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
@@ -1114,6 +1124,11 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.Wp = Operand{w.wp, P.K, axis_identity(a.Cout), (P.K % ce) == 0};
     P.src = A;
     P.g = ConvGeom{a.N, a.C, a.H, a.W, a.Ho, a.Wo, a.kh, a.kw, a.stride, a.pad, a.pad, Ck, d_keep};
+    if (a.blk) {
+      P.g.blk = a.blk;
+      P.g.bx = a.bx, P.g.by = a.by;
+      P.g.RB = ceil_div(a.Ho * a.Wo, a.bx), P.g.CB = ceil_div(a.C * taps, a.by);
+    }
     P.M = a.Cout;
     P.Ncols = (long)a.N * a.Ho * a.Wo;
     P.C.p = out;
@@ -1208,6 +1223,24 @@ extern "C" size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, 
   ConvArgs a{0, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, 0, 0, 0, 0, 0};
   if (conv_check(a)) return 0;
   return conv_ws_layout(nullptr, a).total;
+}
+
+extern "C" int32_t ard_conv_fwd_blocks(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout, int32_t kh,
+                                       int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y, const void* A,
+                                       const void* Wt, const uint8_t* d_block_keep, void* out, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  BatchSuspend not_recorded;
+  ConvArgs a{ARD_CONV_FWD, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, C, 0, 0, 0, 0, d_block_keep, x, y};
+  int32_t st = conv_check(a);
+  if (st) return st;
+  if (x < 1 || y < 0) return fail(ARD_EINVAL, "block size must be positive (y = 0: the whole width)");
+  if (y == 0) a.by = C * kh * kw;
+  if (!A || !Wt || !d_block_keep || !out) return fail(ARD_EINVAL, "null pointer");
+  ConvWs w = conv_ws_layout((char*)ws, a);
+  if (!ws || ws_bytes < w.total) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
+  if (dtype == ARD_BF16)
+    return conv_run<uint16_t>(a, 0.0, A, Wt, nullptr, out, nullptr, nullptr, nullptr, nullptr, w, (hipStream_t)stream);
+  return conv_run<float>(a, 0.0, A, Wt, nullptr, out, nullptr, nullptr, nullptr, nullptr, w, (hipStream_t)stream);
 }
 
 extern "C" int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd,

@@ -148,3 +148,23 @@ def test_config5_layer_under_the_row_pattern():
     ref = OC.conv_fwd(Av, Wv, np.ones(256, np.uint8)) * mask.reshape(128, 1, 28, 28)
     zero = np.broadcast_to((mask == 0).reshape(128, 1, 28, 28), ref.shape)
     assert_parity(Y, ref, "bf16", zero, "config 5 rows Y")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,x,y", [(2, 8, 16, 7, 7, 3, 1, 1, 4, 8), (3, 12, 20, 9, 6, 3, 1, 1, 5, 16),
+                                                             (2, 6, 10, 11, 10, 5, 1, 2, 8, 32), (2, 8, 12, 9, 9, 3, 2, 1, 3, 9),
+                                                             (4, 24, 130, 10, 12, 3, 1, 1, 16, 64)])
+def test_forward_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad, x, y):
+    """Section 5.2.2: prediction per x-by-y region, balanced groups, block mask, forward product over the kept blocks."""
+    print(f"blocks forward {dtype} N={N} C={C} Cout={Cout} {H}x{W} k={k} s={stride} p={pad} x={x} y={y}", flush=True)
+    rng = np.random.default_rng(N * 7 + C + y)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Wv = stored(rng.standard_normal((Cout, C, k, k)) * 0.2, dtype)
+    Ad, Wd = from_vals(Av, dtype), from_vals(Wv, dtype)
+    pred = ard.sens_predict(Ad, (k, k), stride, pad, x, y, 300, 500, 0.5, 3, 2)
+    rows, RB, CB = ard.sens_regions(Av.shape, (k, k), stride, pad, x, y)
+    bp = ard.sens_block_pattern(pred, 1, 0.2, 0.7, 3, 2)
+    keep = bp["keep"].cpu().numpy().reshape(N, RB, CB)
+    assert 0 < keep.sum() < keep.size
+    Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y, stride, pad)
+    assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, y, stride, pad), dtype, None, "conv blocks Y")
