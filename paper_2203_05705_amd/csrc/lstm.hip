@@ -250,6 +250,18 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
     for (int rt = 0; rt < TMB; ++rt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[rt][v] = 0.0f;
+    // this step's input projections do not depend on h_{t-1}: fetched before the wait, so that their
+    // trip to memory overlaps it
+    float zx[TMB][4];
+    {
+      const float* Gt = P.Gx + (long)t * B * 4 * Hp;
+#pragma unroll
+      for (int rt = 0; rt < TMB; ++rt) {
+        const int row = bb * MB + rt * 32 + rb;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) zx[rt][g] = (row < B && kept) ? Gt[(long)row * 4 * Hp + g * Hp + j] : 0.0f;
+      }
+    }
     if (t > 0) {
       if (wave == 0) {
         // every workgroup of this batch block has posted step t - 1: one flag per workgroup (no contended
@@ -316,46 +328,34 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
       for (int v = 0; v < 16; ++v)
         red[(wave * MB + rt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = acc[rt][v];
     __syncthreads();
-    const float* Gt = P.Gx + (long)t * B * 4 * Hp;
+    // cell.  What the other workgroups wait for is h_t alone: it is stored first (device scope), the
+    // workgroup signals as soon as those stores have completed, and only then writes gates, c and h to
+    // the caller's tensors (their trip to memory is off the critical path of the recurrence).
+    float gi[TMB], gf[TMB], gg[TMB], go[TMB], hv[TMB];
 #pragma unroll
     for (int rt = 0; rt < TMB; ++rt) {
       const int rl = rt * 32 + rb, row = bb * MB + rl;
-      float hv = 0.0f;
+      hv[rt] = gi[rt] = gf[rt] = gg[rt] = go[rt] = 0.0f;
       if (row < B && kept) {
         float z[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int col = g * 8 + ul;
-          z[g] = Gt[(long)row * 4 * Hp + g * Hp + j] + ((red[(0 * MB + rl) * 33 + col] + red[(1 * MB + rl) * 33 + col]) +
-                                                       (red[(2 * MB + rl) * 33 + col] + red[(3 * MB + rl) * 33 + col]));
+          z[g] = zx[rt][g] + ((red[(0 * MB + rl) * 33 + col] + red[(1 * MB + rl) * 33 + col]) +
+                              (red[(2 * MB + rl) * 33 + col] + red[(3 * MB + rl) * 33 + col]));
         }
-        const float gi = sigmoidf_(z[0]), gf = sigmoidf_(z[1]), gg = tanhf(z[2]), go = sigmoidf_(z[3]);
-        const float cv = gf * c_reg[rt] + gi * gg;
+        gi[rt] = sigmoidf_(z[0]), gf[rt] = sigmoidf_(z[1]), gg[rt] = tanhf(z[2]), go[rt] = sigmoidf_(z[3]);
+        const float cv = gf[rt] * c_reg[rt] + gi[rt] * gg[rt];
         c_reg[rt] = cv;
-        hv = go * tanhf(cv);
-        float* ga = P.gates + ((long)t * B + row) * 4 * H;
-        ga[u] = gi;
-        ga[H + u] = gf;
-        ga[2 * H + u] = gg;
-        ga[3 * H + u] = go;
-        P.c[((long)t * B + row) * H + u] = cv;
-        P.h[((long)t * B + row) * H + u] = f32_to_bf16_bits(hv);
+        hv[rt] = go[rt] * tanhf(cv);
       }
       if (row < B) {
         // compact h_t for the next step: device-scope store (the padding units store their zero)
-        const unsigned bits = f32_to_bf16_bits(hv);
+        const unsigned bits = f32_to_bf16_bits(hv[rt]);
         const unsigned other = (unsigned)__shfl_xor((int)bits, 1, 64);
         if (!(ul & 1))
           __hip_atomic_store(reinterpret_cast<unsigned*>(P.hc + ((long)t * B + row) * Hp + j), bits | (other << 16), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
-        // zeros of the dropped units of this thread's group
-        for (int uz = z_lo; uz < z_hi; ++uz) {
-          if (uz == u) continue;
-          float* ga = P.gates + ((long)t * B + row) * 4 * H;
-          ga[uz] = ga[H + uz] = ga[2 * H + uz] = ga[3 * H + uz] = 0.0f;
-          P.c[((long)t * B + row) * H + uz] = 0.0f;
-          P.h[((long)t * B + row) * H + uz] = 0;
-        }
       }
     }
     // every thread's h_t stores have completed before the workgroup signals
@@ -363,6 +363,27 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
     __syncthreads();
     if (tid == 0 && t + 1 < P.T)
       __hip_atomic_store(&P.counters[(long)bb * P.S + s], t + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int rt = 0; rt < TMB; ++rt) {
+      const int row = bb * MB + rt * 32 + rb;
+      if (row >= B) continue;
+      float* ga = P.gates + ((long)t * B + row) * 4 * H;
+      if (kept) {
+        ga[u] = gi[rt];
+        ga[H + u] = gf[rt];
+        ga[2 * H + u] = gg[rt];
+        ga[3 * H + u] = go[rt];
+        P.c[((long)t * B + row) * H + u] = c_reg[rt];
+        P.h[((long)t * B + row) * H + u] = f32_to_bf16_bits(hv[rt]);
+      }
+      // zeros of the dropped units of this thread's group
+      for (int uz = z_lo; uz < z_hi; ++uz) {
+        if (uz == u) continue;
+        ga[uz] = ga[H + uz] = ga[2 * H + uz] = ga[3 * H + uz] = 0.0f;
+        P.c[((long)t * B + row) * H + uz] = 0.0f;
+        P.h[((long)t * B + row) * H + uz] = 0;
+      }
+    }
   }
 }
 
