@@ -681,6 +681,14 @@ def extra_lstm(ard, torch):
         if dp == 2:
             cold = event_us(torch, lambda: ard.lstm_fwd(x, Wl, pat, ws=ws, out=out), reps=3, warm=1, blocks=3, flush=flush)
             res["dp2"]["fwd_us_cache_cold"] = round(cold["median"], 1)
+    # the TILE variant (Section 7.2.3): 32 x 32 tiles of the fused weight dropped, every unit kept; the products
+    # run dense on the masked weight, so this row shows what the masking costs, not a gain
+    tpat = ard.Pattern.tile(2, 1, 32, 32)
+    ws = torch.empty(ard.lstm_workspace_bytes(ard.BF16, T, B, I, Hh, tpat), dtype=torch.uint8, device="cuda")
+    out = ard.lstm_fwd(x, Wl, tpat, ws=ws)
+    fwd = event_us(torch, lambda: ard.lstm_fwd(x, Wl, tpat, ws=ws, out=out), reps=5, warm=2)
+    bwd = event_us(torch, lambda: ard.lstm_bwd(x, Wl, tpat, out[0], out[1], out[2], dh, ws=ws), reps=5, warm=2)
+    res["tile32_dp2_masked_dense"] = dict(fwd_us=round(fwd["median"], 1), bwd_us=round(bwd["median"], 1))
     del flush
     lstm = torch.nn.LSTM(I, Hh).cuda().to(torch.bfloat16)
     xx = x.clone().requires_grad_(True)
