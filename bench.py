@@ -41,9 +41,9 @@ REPEATS = 5              # the block of `steps` timed iterations is repeated; me
 # runs of `bench.py --only-call NAME` (scaled by what the same counters read for a plain copy); the
 # summaries, with their commands, are the files named here.  None: not measured.
 TRAFFIC = {
-    "L2.bwd_weight": (14963568, "profiles/hbm_traffic_L2_bwd_weight.txt"),
-    "C3.fwd.dp2": (151188714, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
-    "C5.fwd": (108395923, "profiles/hbm_traffic_config5_conv_fwd.txt"),
+    "L2.bwd_weight": (14987336, "profiles/hbm_traffic_L2_bwd_weight.txt"),
+    "C3.fwd.dp2": (151177927, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
+    "C5.fwd": (108529598, "profiles/hbm_traffic_config5_conv_fwd.txt"),
 }
 
 
@@ -585,8 +585,8 @@ def extra_small(ard, torch):
         note="one workgroup (two launches for a tile grid), latency-bound; outputs preallocated")
     wlc = WL.conv_layer()
     A = ard.to_device(wlc.arrays["A"])
-    N, C, H, Wd = A.shape
-    wsc = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, C, H, Wd, 256, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
+    N, Cc, H, Wd = A.shape
+    wsc = torch.empty(ard.conv_workspace_bytes(ard.BF16, N, Cc, H, Wd, 256, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
     sel = ard.conv_select(A, 0.5, ws=wsc)
     us = event_us(torch, lambda: ard.conv_select(A, 0.5, ws=wsc, out=sel))["median"]
     res["channel_score_select"] = dict(us=round(us, 1), bytes_read=A.numel() * 2,
