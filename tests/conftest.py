@@ -39,14 +39,15 @@ def guarded_outputs(request):
 
 
 def pytest_sessionfinish(session, exitstatus):
-    """Leaves the error levels of every float comparison of a GPU session under gpurun_out/."""
+    """Leaves the error levels of every float comparison of a GPU session in parity_errors.txt (folder
+    ARD_TEST_LOG_DIR, default: the run's output folder at the repository root)."""
     try:
         from util import ERROR_LOG
     except Exception:
         return
     if not ERROR_LOG:
         return
-    out = os.path.join(ROOT, "gpurun_out")
+    out = os.environ.get("ARD_TEST_LOG_DIR") or os.path.join(ROOT, "gpurun_out")
     os.makedirs(out, exist_ok=True)
     with open(os.path.join(out, "parity_errors.txt"), "w") as f:
         f.write("# what | dtype | max|d|/max|ref| | max |d|/(|ref|+rms)\n")
