@@ -1098,12 +1098,18 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
   if (!out) return fail(ARD_EINVAL, "null output pointer");
   const int Ck = a.n_keep;
   if (a.reuse) {
-    const bool grid_path = Ck > 0 && w.grid_a && !dev_knobs().no_fast;
+    const bool grid_path = Ck > 0 && w.grid_a;
     if (!grid_path) return fail(ARD_EUNSUPPORTED, "grid reuse needs the bf16 stride-1 path and at least one kept channel");
     if ((a.reuse & ARD_CONV_REUSE_A) && a.mode == ARD_CONV_BWD_DATA) return fail(ARD_EINVAL, "BWD_DATA has no grid of A to reuse");
     if ((a.reuse & ARD_CONV_REUSE_DY) && a.mode == ARD_CONV_FWD) return fail(ARD_EINVAL, "FWD has no grid of dY to reuse");
     if ((a.reuse & ARD_CONV_REUSE_DY) && a.mode == ARD_CONV_BWD_WEIGHT && !(a.kh - 1 == 2 * a.pad && a.kw - 1 == 2 * a.pad))
       return fail(ARD_EUNSUPPORTED, "the weight gradient shares dY's grid with the data gradient only for k - 1 = 2 pad");
+    if (dev_knobs().no_fast) {
+      // (development switch: every pass runs on the general engine, which builds no grid; nothing to share)
+      ConvArgs plain = a;
+      plain.reuse = 0;
+      return conv_run<T>(plain, rate, A, Wt, dYin, out, d_mask, d_keep, d_count, d_score, w, stream);
+    }
   }
   if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast && !a.blk) {
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
