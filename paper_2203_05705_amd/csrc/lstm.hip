@@ -213,7 +213,8 @@ struct LstmPersist {
   long spin_limit;
 };
 
-template <int TMB>
+// VIA_L2: h_{t-1} is read through the XCD's L2 after an agent-scope acquire (else with device-scope loads)
+template <int TMB, bool VIA_L2>
 __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist P) {
   constexpr int MB = 32 * TMB;
   extern __shared__ uint4 lp_lds[];
@@ -280,6 +281,8 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
           }
         }
         if (lane == 0) go_s = ok;
+        // (h_{t-1} is complete in memory: drop what this CU's L1 and this XCD's L2 may hold of it)
+        if (VIA_L2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       }
       __syncthreads();
       if (!go_s) return;  // uniform: every thread of the workgroup leaves
@@ -301,8 +304,13 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
             int row = bb * MB + rt * 32 + (lane & 31);
             row = row < B ? row : B - 1;  // rows beyond the batch are never stored
             const unsigned long long* src = hp + (((long)row * Hp + kc) >> 2);
-            lo[i][rt] = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            hi[i][rt] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (VIA_L2) {
+              const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(src);
+              lo[i][rt] = v.x, hi[i][rt] = v.y;
+            } else {
+              lo[i][rt] = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              hi[i][rt] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
           }
         }
 #pragma unroll
@@ -544,6 +552,7 @@ static int32_t lstm_padded_x(const LstmArgs& a, const void* x, const LstmWs& w, 
 // at most one workgroup per CU, bounded exchange traffic)
 struct PersistPlan {
   int tmb, S, nbb;
+  int via_l2;  // read h_{t-1} through L2 (large states) instead of with device-scope loads
   size_t lds;
 };
 static bool lstm_persist_plan(const LstmArgs& a, PersistPlan& p) {
@@ -557,11 +566,16 @@ static bool lstm_persist_plan(const LstmArgs& a, PersistPlan& p) {
   if (!p.tmb) return false;
   p.nbb = ceil_div(a.B, 32 * p.tmb);
   p.lds = (size_t)32 * (Hp * 2 + 16) + (size_t)4 * 32 * p.tmb * 33 * 4;
-  // every unit slice reads the whole h_{t-1} of its batch rows with device-scope loads (they come from
-  // the memory side, not from an XCD's L2): S * B * Hp * 2 bytes per step.  Measured at B = 128: 8 MB
-  // (512 kept units) 7.7 us per step against 12.6 for two launches per step; 33 MB (1024 units) 18.9
-  // against 14.1, so large states keep the launch-per-step path.
-  const bool traffic_ok = (long)p.S * a.B * Hp * 2 <= 12L << 20;
+  // Every unit slice reads the whole h_{t-1} of its batch rows: S * B * Hp * 2 bytes per step over the chip.
+  // Device-scope loads fetch each copy from the memory side: best while that volume is small (B = 128,
+  // 512 kept units: 8 MB, 6.5 us per step against 12.6 for two launches per step), 15 us per step at 33 MB
+  // (1024 units).  Larger states are read through the XCD's L2 after an agent-scope acquire, so the slices
+  // of one XCD share one fetch: 12.8 us per step at 33 MB against 14.6 for launches, but 7.1 against 6.5 at
+  // 8 MB (every workgroup's acquire drops what its neighbours just fetched).  Beyond 40 MB nothing was
+  // measured: launch per step.
+  const long traffic = (long)p.S * a.B * Hp * 2;
+  p.via_l2 = traffic > (12L << 20);
+  const bool traffic_ok = traffic <= (40L << 20);
   return traffic_ok && p.lds <= 160 * 1024 - 1024;
 }
 
@@ -593,13 +607,17 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
                   a.ax.off, a.ax.step, spin_limit};
     ARD_LAUNCH(lstm_zero_ints_kernel, dim3(ceil_div(S * nbb + 1, 256)), dim3(256), 0, stream, w.sync, S * nbb + 1);
     ARD_LAUNCH_CHECK("lstm_zero_ints_kernel");
-    const void* kfn = tmb == 1 ? (const void*)lstm_persist_fwd_kernel<1> : tmb == 2 ? (const void*)lstm_persist_fwd_kernel<2>
-                                                                                     : (const void*)lstm_persist_fwd_kernel<4>;
-    if (lds > 65536) ARD_HIP_CHECK(raise_lds_limit(kfn, (int)lds));
     const dim3 grid((unsigned)(S * nbb));
-    if (tmb == 1) ARD_LAUNCH(lstm_persist_fwd_kernel<1>, grid, dim3(256), lds, stream, P);
-    else if (tmb == 2) ARD_LAUNCH(lstm_persist_fwd_kernel<2>, grid, dim3(256), lds, stream, P);
-    else ARD_LAUNCH(lstm_persist_fwd_kernel<4>, grid, dim3(256), lds, stream, P);
+    auto launch = [&](auto kernel) -> int32_t {
+      if (lds > 65536) ARD_HIP_CHECK(raise_lds_limit((const void*)kernel, (int)lds));
+      ARD_LAUNCH_NAMED("lstm_persist_fwd_kernel", kernel, grid, dim3(256), lds, stream, P);
+      return ARD_OK;
+    };
+    if (pp.via_l2) st = tmb == 1 ? launch(lstm_persist_fwd_kernel<1, true>) : tmb == 2 ? launch(lstm_persist_fwd_kernel<2, true>)
+                                                                                          : launch(lstm_persist_fwd_kernel<4, true>);
+    else st = tmb == 1 ? launch(lstm_persist_fwd_kernel<1, false>) : tmb == 2 ? launch(lstm_persist_fwd_kernel<2, false>)
+                                                                               : launch(lstm_persist_fwd_kernel<4, false>);
+    if (st) return st;
     ARD_LAUNCH_CHECK("lstm_persist_fwd_kernel");
     return ARD_OK;
   }
