@@ -273,7 +273,9 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
         for (;;) {
           bool ready = true;
           for (int i = lane; i < P.S; i += 64) ready = ready && __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= t;
-          if (__all(ready)) break;
+          // (a negative bound is the host's way to force the give-up path: the first wait fails whatever it saw --
+          // with a bound of zero a poll that finds everything posted, which is the common case, would still pass)
+          if (__all(ready) && P.spin_limit >= 0) break;
           if (++spins > P.spin_limit || __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
             __hip_atomic_store(P.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ok = 0;
@@ -601,7 +603,8 @@ static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void*
   if (std::is_same<T, uint16_t>::value && lstm_persist_plan(a, pp)) {
     const int S = pp.S, nbb = pp.nbb, tmb = pp.tmb;
     const size_t lds = pp.lds;
-    // (ARD_LSTM_SPIN_LIMIT: test hook for the give-up path; a workgroup that gives up leaves normally)
+    // (ARD_LSTM_SPIN_LIMIT: test hook for the give-up path, negative = the first wait fails; a workgroup that
+    // gives up leaves normally)
     const long spin_limit = getenv("ARD_LSTM_SPIN_LIMIT") ? atol(getenv("ARD_LSTM_SPIN_LIMIT")) : 4000000L;
     LstmPersist P{Gx, (const uint16_t*)w.whc, (uint16_t*)w.hc, (uint16_t*)h, c, gates, w.sync + 1, w.sync, T_, B, H, Hk, Hp, S,
                   a.ax.off, a.ax.step, spin_limit};

@@ -10,8 +10,9 @@ pytestmark = pytest.mark.gpu
 
 
 def test_one_launch_recurrence_status_and_give_up_path():
-    """The forward recurrence in one launch leaves its status word at 0; with the wait bound forced to zero
-    from the host the workgroups give up, leave normally and set the word; the next call is unaffected."""
+    """The forward recurrence in one launch leaves its status word at 0; with a negative wait bound set from
+    the host every workgroup's first wait fails: they give up, leave normally and set the word; the next call
+    is unaffected."""
     import os
     T, B, I, H, dp = 12, 128, 256, 1024, 2
     dt = ard.BF16
@@ -27,12 +28,12 @@ def test_one_launch_recurrence_status_and_give_up_path():
     torch.cuda.synchronize()
     assert status() == 0, "a complete call left the status word set"
     assert bool(torch.isfinite(h0.float()).all()), "h of a complete call holds unwritten entries"
-    os.environ["ARD_LSTM_SPIN_LIMIT"] = "0"
+    os.environ["ARD_LSTM_SPIN_LIMIT"] = "-1"
     try:
-        print("forcing the give-up path (spin limit 0)", flush=True)
+        print("forcing the give-up path (negative spin limit)", flush=True)
         ard.lstm_fwd(x, W, pat, ws=ws)
         torch.cuda.synchronize()          # every workgroup left on its own
-        assert status() == 1, "no workgroup gave up although the wait bound was zero"
+        assert status() == 1, "no workgroup gave up although the wait bound was negative"
     finally:
         del os.environ["ARD_LSTM_SPIN_LIMIT"]
     h1, c1, g1 = ard.lstm_fwd(x, W, pat, ws=ws)
