@@ -86,40 +86,67 @@ __global__ __launch_bounds__(256) void sens_predict_kernel(const T* A, SensGeom 
 
 // Row-based pattern (Section 5.2.1): global row g = image * rows + p is dropped iff its draw is below the
 // possibility of its band (m if sensitive, n otherwise); mask (1 = kept) and ascending kept list by
-// ballot + mbcnt compaction, one workgroup walking all rows.
+// ballot + mbcnt compaction.  A workgroup takes `chunk` consecutive rows.  Where its part of the kept list
+// starts is the number of kept rows before its chunk.  No scratch memory and no hand-over between
+// workgroups: with a mask, a first launch (phase 0) writes it and the second (phase 1) counts its ones
+// before the chunk with 16-byte loads; without one (phase 2, a single launch) the workgroup recounts the
+// rows before its chunk -- a draw is a pure function of the row.
 __global__ __launch_bounds__(1024) void sens_row_pattern_kernel(const uint8_t* sens, int n_rows_total, int rows, int x, int RB,
-                                                               int CB, uint64_t tm, uint64_t tn, uint64_t prefix, uint8_t* mask,
-                                                               int* keep, int* count) {
+                                                               int CB, uint64_t tm, uint64_t tn, uint64_t prefix, int chunk,
+                                                               int phase, uint8_t* mask, int* keep, int* count) {
   __shared__ int wave_tot[16];
   __shared__ int running_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) running_s = 0;
+  const int start = blockIdx.x * chunk, end = min(n_rows_total, start + chunk);
+  auto row_kept = [&](int gr) {
+    const int n = gr / rows, p = gr - n * rows;
+    const bool sv = sens[((long)n * RB + p / x) * CB] != 0;  // (regions span the width: CB = 1)
+    return !((uint64_t)sens_draw(prefix, (uint64_t)gr) < (sv ? tm : tn));
+  };
+  if (phase == 0) {
+    for (int gr = start + tid; gr < end; gr += 1024) mask[gr] = row_kept(gr) ? 1 : 0;
+    return;
+  }
+  int before = 0;
+  if (phase == 1) {
+    // ones of mask[0, start): start is a multiple of 1024, the mask 16-byte aligned (host checks)
+    const uint4* m16 = reinterpret_cast<const uint4*>(mask);
+    for (int i = tid; i < start / 16; i += 1024) {
+      const uint4 v = m16[i];
+      before += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+    }
+  } else {
+    for (int gr = tid; gr < start; gr += 1024) before += row_kept(gr) ? 1 : 0;
+  }
+  for (int off = 32; off > 0; off >>= 1) before += __shfl_down(before, off, 64);
+  if (lane == 0) wave_tot[wave] = before;
   __syncthreads();
-  for (int base = 0; base < n_rows_total; base += 1024) {
+  if (tid == 0) {
+    int t = 0;
+    for (int w = 0; w < 16; ++w) t += wave_tot[w];
+    running_s = t;
+  }
+  __syncthreads();
+  for (int base = start; base < end; base += 1024) {
     const int gr = base + tid;
     bool kept = false;
-    if (gr < n_rows_total) {
-      const int n = gr / rows, p = gr - n * rows;
-      const bool sv = sens[((long)n * RB + p / x) * CB] != 0;  // (regions span the width: CB = 1)
-      kept = !((uint64_t)sens_draw(prefix, (uint64_t)gr) < (sv ? tm : tn));
-      if (mask) mask[gr] = kept ? 1 : 0;
-    }
+    if (gr < end) kept = phase == 1 ? mask[gr] != 0 : row_kept(gr);
     const unsigned long long bal = __ballot(kept);
     const int r = __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0));
     if (lane == 0) wave_tot[wave] = __popcll(bal);
     __syncthreads();
-    int before = running_s, total = 0;
+    int before_me = running_s, total = 0;
     for (int w = 0; w < 16; ++w) {
       const int t = wave_tot[w];
-      if (w < wave) before += t;
+      if (w < wave) before_me += t;
       total += t;
     }
-    if (kept && keep) keep[before + r] = gr;
+    if (kept && keep) keep[before_me + r] = gr;
     __syncthreads();
     if (tid == 0) running_s += total;
     __syncthreads();
   }
-  if (tid == 0 && count) *count = running_s;
+  if (tid == 0 && count && end == n_rows_total) *count = running_s;
 }
 
 // Block-based pattern (Section 5.2.2): one workgroup per (image, row band).  Balancing: S = mean number
@@ -231,8 +258,20 @@ extern "C" int32_t ard_sens_row_pattern(int32_t N, int32_t rows, int32_t x, cons
   if ((long)N * rows > 0x7fffff00L) return fail(ARD_ESHAPE, "too many rows");
   if (!(m >= 0.0 && m <= 1.0) || !(n >= 0.0 && n <= 1.0)) return fail(ARD_EINVAL, "possibilities must lie in [0, 1]");
   if (!d_sens || (!d_mask && !d_keep && !d_count)) return fail(ARD_EINVAL, "null pointer");
-  ARD_LAUNCH(sens_row_pattern_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, d_sens, N * rows, rows, x, ceil_div(rows, x),
-             1, sens_threshold(m), sens_threshold(n), sens_prefix(seed, iteration, SENS_STREAM_ROWS), d_mask, d_keep, d_count);
+  const int total = N * rows;
+  const int chunk = (int)align_up((size_t)ceil_div(total, 128), 1024);  // at most 128 workgroups of whole 1024-row rounds
+  const dim3 grid((unsigned)ceil_div(total, chunk));
+  const uint64_t tm = sens_threshold(m), tn = sens_threshold(n), pre = sens_prefix(seed, iteration, SENS_STREAM_ROWS);
+  const int RB = ceil_div(rows, x);
+  const bool via_mask = d_mask && (((uintptr_t)d_mask & 15) == 0);
+  if (d_mask) {
+    ARD_LAUNCH(sens_row_pattern_kernel, grid, dim3(1024), 0, (hipStream_t)stream, d_sens, total, rows, x, RB, 1, tm, tn, pre, chunk, 0,
+               d_mask, d_keep, d_count);
+    ARD_LAUNCH_CHECK("sens_row_pattern_kernel");
+    if (!d_keep && !d_count) return ARD_OK;
+  }
+  ARD_LAUNCH(sens_row_pattern_kernel, grid, dim3(1024), 0, (hipStream_t)stream, d_sens, total, rows, x, RB, 1, tm, tn, pre, chunk,
+             via_mask ? 1 : 2, d_mask, d_keep, d_count);
   ARD_LAUNCH_CHECK("sens_row_pattern_kernel");
   return ARD_OK;
 }

@@ -168,3 +168,31 @@ def test_forward_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad
     assert 0 < keep.sum() < keep.size
     Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y, stride, pad)
     assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, y, stride, pad), dtype, None, "conv blocks Y")
+
+
+@pytest.mark.parametrize("N,rows,x", [(3, 50, 4), (40, 784, 8), (128, 784, 8)])
+def test_row_pattern_without_a_mask_and_with_an_unaligned_one(N, rows, x):
+    """The kept list and the count do not depend on whether (or where) the mask is written: with a mask the
+    list offsets come from its ones, without one (or with one that is not 16-byte aligned) from recounting."""
+    rng = np.random.default_rng(N + rows)
+    RB = -(-rows // x)
+    sens = torch.from_numpy((rng.uniform(size=(N, RB, 1)) < 0.4).astype(np.uint8)).cuda()
+    ref = ard.sens_row_pattern(sens, rows, x, 0.25, 0.75, 11, 3)
+    nk = int(ref["count"].item())
+    lib = ard.lib()
+    total = N * rows
+    st = torch.cuda.current_stream().cuda_stream
+    for variant in ("no mask", "unaligned mask"):
+        keep = torch.full((total,), -1, dtype=torch.int32, device="cuda")
+        count = torch.zeros(1, dtype=torch.int32, device="cuda")
+        buf = torch.zeros(total + 16, dtype=torch.uint8, device="cuda")
+        mask_ptr = None if variant == "no mask" else buf.data_ptr() + 3
+        rc = lib.ard_sens_row_pattern(N, rows, x, sens.data_ptr(), 0.25, 0.75, 11, 3, mask_ptr, keep.data_ptr(), count.data_ptr(), st)
+        torch.cuda.synchronize()
+        assert rc == 0 and int(count.item()) == nk, variant
+        assert torch.equal(keep, ref["keep"]), variant
+        if mask_ptr is not None:
+            assert torch.equal(buf[3:3 + total], ref["mask"]) and not buf[:3].any() and not buf[3 + total:].any()
+    # the list is the ascending set of ones of the mask
+    m = ref["mask"].cpu().numpy()
+    assert np.array_equal(ref["keep"].cpu().numpy()[:nk], np.flatnonzero(m)) and nk == int(m.sum())
