@@ -84,6 +84,161 @@ __global__ __launch_bounds__(256) void sens_predict_kernel(const T* A, SensGeom 
   }
 }
 
+// Exact unsigned division by a divisor known on the host (multiply-high and shifts instead of the 30-odd
+// instructions of a division by a run-time value).
+struct FastDiv {
+  uint32_t mul;
+  int shift;  // -1: divisor 1
+};
+static FastDiv fast_div(uint32_t d) {
+  if (d <= 1) return FastDiv{0u, -1};
+  int l = 0;
+  while ((1ull << l) < d) ++l;  // ceil(log2 d) >= 1
+  const uint64_t m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+  return FastDiv{(uint32_t)m, l - 1};
+}
+static __device__ __forceinline__ uint32_t fdiv(uint32_t a, const FastDiv& f) {
+  if (f.shift < 0) return a;
+  const uint32_t t = __umulhi(a, f.mul);
+  return (t + ((a - t) >> 1)) >> f.shift;
+}
+
+// The same prediction with the region's geometry tabulated in LDS once per workgroup: per column of the
+// region its channel's offset in the image and its tap (kh, kw), per row of the band its top-left input
+// position.  A draw is then the mixer, one division by the region's width, two LDS reads and the gather.
+// Same draws, same elements, same counts as sens_predict_kernel (bit for bit); used when the table fits
+// (region width <= kSensLutCols, channel offsets below 2^24, taps below 16).
+constexpr int kSensLutCols = 8192, kSensLutRows = 1024;
+template <typename T>
+__global__ __launch_bounds__(256) void sens_predict_lut_kernel(const T* A, SensGeom g, int k_permille, int t_permille, float thr,
+                                                               uint64_t prefix, FastDiv div_w, int* count, int* samples,
+                                                               uint8_t* sens) {
+  extern __shared__ int sens_lut[];  // [w] columns, then [h] rows
+  __shared__ int wave_cnt[4];
+  const int region = blockIdx.x;  // (image * RB + rb) * CB + cb
+  const int cb = region % g.CB, rb = (region / g.CB) % g.RB, n = region / (g.CB * g.RB);
+  const int r0 = rb * g.x, q0 = cb * g.y;
+  const int h = min(g.x, g.rows - r0), w = min(g.y, g.cols - q0);
+  const int size = h * w;
+  int s = (int)(((long)k_permille * size) / 1000);
+  if (s < 1) s = 1;
+  const int taps = g.KH * g.KW;
+  int* col_lut = sens_lut;
+  int* row_lut = sens_lut + w;
+  for (int i = threadIdx.x; i < w; i += 256) {
+    const int q = q0 + i;
+    const int ch = q / taps, tap = q - ch * taps;
+    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+    col_lut[i] = (ch * g.H * g.W) | (kh << 24) | (kw << 28);
+  }
+  for (int i = threadIdx.x; i < h; i += 256) {
+    const int p = r0 + i;
+    const int oh = p / g.Wo, ow = p - oh * g.Wo;
+    // input position of tap (0, 0), biased by the padding so that both halves are non-negative
+    row_lut[i] = (oh * g.stride) | ((ow * g.stride) << 16);
+  }
+  __syncthreads();
+  const T* img = A + (long)n * g.C * g.H * g.W;
+  int c = 0;
+  for (int j = threadIdx.x; j < s; j += 256) {
+    const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
+    const uint32_t e = (uint32_t)(((uint64_t)u * (uint64_t)size) >> 32);
+    const uint32_t r = fdiv(e, div_w), q = e - r * (uint32_t)w;
+    const int ci = col_lut[q], ri = row_lut[r];
+    const int ih = (ri & 0xffff) + ((ci >> 24) & 15) - g.pad, iw = (ri >> 16) + ((ci >> 28) & 15) - g.pad;
+    float v = 0.0f;  // the zero border of the input matrix
+    if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(img[(ci & 0xffffff) + ih * g.W + iw]);
+    c += v > thr ? 1 : 0;
+  }
+  for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off, 64);
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int tot = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    count[region] = tot;
+    samples[region] = s;
+    sens[region] = (1000L * tot >= (long)t_permille * s) ? 1 : 0;
+  }
+}
+
+// The prediction once more, with the region's footprint in the activations copied into LDS first: the
+// draws of a region fall on a few input rows of its channels (config 5: 4 rows x 28 x 256 channels = 57 KB
+// for 5529 draws), and a gather from memory costs a whole cache-line transaction per draw (69 M of them
+// made the pass take 460 us) where the copy is a few coalesced 16-byte loads per thread.  Same draws, same
+// elements, same counts.  Needs planes that are whole numbers of 16-byte pieces (then every channel's run
+// starts at the same offset within a piece) and a footprint that fits the LDS; the host checks both.
+struct SensStage {
+  int nrow_max, chp;  // input rows a region can touch; elements reserved per channel (a multiple of the piece)
+  FastDiv div_taps, div_kw, div_wo;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, SensGeom g, SensStage sg, int k_permille,
+                                                                  int t_permille, float thr, uint64_t prefix, FastDiv div_w,
+                                                                  int* count, int* samples, uint8_t* sens) {
+  constexpr int CE = ElemTraits<T>::CE;  // elements per 16-byte piece
+  extern __shared__ uint4 sens_stage_lds[];
+  __shared__ int wave_cnt[4];
+  const int region = blockIdx.x;  // (image * RB + rb) * CB + cb
+  const int cb = region % g.CB, rb = (region / g.CB) % g.RB, n = region / (g.CB * g.RB);
+  const int r0 = rb * g.x, q0 = cb * g.y;
+  const int h = min(g.x, g.rows - r0), w = min(g.y, g.cols - q0);
+  const int size = h * w;
+  int s = (int)(((long)k_permille * size) / 1000);
+  if (s < 1) s = 1;
+  const int taps = g.KH * g.KW;
+  // footprint: channels [ch_lo, ch_hi], input rows [ih_lo, ih_hi] (clipped to the image), all columns
+  const int ch_lo = q0 / taps, ch_hi = (q0 + w - 1) / taps;
+  const int oh_lo = r0 / g.Wo, oh_hi = (r0 + h - 1) / g.Wo;
+  const int ih_lo = max(0, oh_lo * g.stride - g.pad), ih_hi = min(g.H - 1, oh_hi * g.stride - g.pad + g.KH - 1);
+  const int nch = ch_hi - ch_lo + 1;
+  const int run0 = ih_lo * g.W, run = max(0, ih_hi - ih_lo + 1) * g.W;  // elements of a channel's plane that are staged
+  const int off = run0 % CE;                                           // the run's offset within its first piece
+  const int pieces = run > 0 ? (off + run + CE - 1) / CE : 0;           // 16-byte pieces per channel
+  T* stage = reinterpret_cast<T*>(sens_stage_lds);
+  const int nch_max = min(g.C, (g.y + taps - 2) / taps + 1);  // channels a column block can touch
+  int* col_lut = reinterpret_cast<int*>(stage + (size_t)sg.chp * nch_max);  // (chp is a multiple of the piece: aligned)
+  int* row_lut = col_lut + w;
+  const T* img = A + (long)n * g.C * g.H * g.W;
+  // consecutive threads take consecutive pieces, running on from one channel into the next
+  for (int i = threadIdx.x; i < nch * pieces; i += 256) {
+    const int c = i / pieces, pc = i - c * pieces;
+    const T* src = img + (long)(ch_lo + c) * g.H * g.W + (run0 - off) + pc * CE;
+    *reinterpret_cast<uint4*>(stage + (size_t)c * sg.chp + pc * CE) = *reinterpret_cast<const uint4*>(src);
+  }
+  for (int i = threadIdx.x; i < w; i += 256) {
+    const int q = q0 + i;
+    const int ch = (int)fdiv((uint32_t)q, sg.div_taps), tap = q - ch * taps;
+    const int kh = (int)fdiv((uint32_t)tap, sg.div_kw), kw = tap - kh * g.KW;
+    col_lut[i] = ((ch - ch_lo) * sg.chp) | (kh << 24) | (kw << 28);
+  }
+  for (int i = threadIdx.x; i < h; i += 256) {
+    const int p = r0 + i;
+    const int oh = (int)fdiv((uint32_t)p, sg.div_wo), ow = p - oh * g.Wo;
+    row_lut[i] = (oh * g.stride) | ((ow * g.stride) << 16);
+  }
+  __syncthreads();
+  int c = 0;
+  for (int j = threadIdx.x; j < s; j += 256) {
+    const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
+    const uint32_t e = (uint32_t)(((uint64_t)u * (uint64_t)size) >> 32);
+    const uint32_t r = fdiv(e, div_w), q = e - r * (uint32_t)w;
+    const int ci = col_lut[q], ri = row_lut[r];
+    const int ih = (ri & 0xffff) + ((ci >> 24) & 15) - g.pad, iw = (ri >> 16) + ((ci >> 28) & 15) - g.pad;
+    float v = 0.0f;  // the zero border of the input matrix
+    if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(stage[(ci & 0xffffff) + off + (ih - ih_lo) * g.W + iw]);
+    c += v > thr ? 1 : 0;
+  }
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int tot = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    count[region] = tot;
+    samples[region] = s;
+    sens[region] = (1000L * tot >= (long)t_permille * s) ? 1 : 0;
+  }
+}
+
 // Row-based pattern (Section 5.2.1): global row g = image * rows + p is dropped iff its draw is below the
 // possibility of its band (m if sensitive, n otherwise); mask (1 = kept) and ascending kept list by
 // ballot + mbcnt compaction.  A workgroup takes `chunk` consecutive rows.  Where its part of the kept list
@@ -240,6 +395,49 @@ extern "C" int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t
   if (!A || !d_count || !d_samples || !d_sens) return fail(ARD_EINVAL, "null pointer");
   const uint64_t prefix = sens_prefix(seed, iteration, SENS_STREAM_SAMPLE);
   const unsigned regions = (unsigned)((long)N * g.RB * g.CB);
+  // tabulated geometry when it fits: the width of every region is g.y except the clipped last column block,
+  // which only exists when the width does not divide the matrix -- then each region would need its own divisor
+  const bool lut_ok = g.y <= kSensLutCols && g.x <= kSensLutRows && (long)C * H * Wd < (1L << 24) && kh < 16 && kw < 16 &&
+                      (long)(g.Ho - 1) * stride < 65536 && (long)(g.Wo - 1) * stride < 32768 && g.cols % g.y == 0;
+  if (lut_ok) {
+    const FastDiv dw = fast_div((uint32_t)g.y);
+    // footprint of a region in LDS when it fits: rows a band can touch x whole width x channels of a block
+    const int ce = dtype == ARD_BF16 ? 8 : 4, es = dtype == ARD_BF16 ? 2 : 4, taps = kh * kw;
+    const int oh_span = (g.x + g.Wo - 2) / g.Wo + 1;
+    const int nrow_max = imin(H, (oh_span - 1) * stride + kh);
+    const int chp = (int)align_up((size_t)(ce - 1 + nrow_max * Wd), (size_t)ce);
+    const int nch_max = imin(C, (g.y + taps - 2) / taps + 1);
+    const size_t stage_bytes = (size_t)chp * nch_max * es + (size_t)(g.y + g.x) * sizeof(int);
+    // (pad < filter size: every window then starts inside the image, which the copy's bounds rely on)
+    if (((H * Wd) % ce) == 0 && (((uintptr_t)A) & 15) == 0 && stage_bytes <= 150 * 1024 && (long)chp * nch_max < (1L << 24) &&
+        pad < kh && pad < kw) {
+      const SensStage sg{nrow_max, chp, fast_div((uint32_t)taps), fast_div((uint32_t)kw), fast_div((uint32_t)g.Wo)};
+      hipError_t e = hipSuccess;
+      if (dtype == ARD_BF16) {
+        if (stage_bytes > 65536) e = raise_lds_limit((const void*)sens_predict_staged_kernel<uint16_t>, (int)stage_bytes);
+        if (e == hipSuccess)
+          ARD_LAUNCH(sens_predict_staged_kernel<uint16_t>, dim3(regions), dim3(256), stage_bytes, (hipStream_t)stream,
+                     (const uint16_t*)A, g, sg, k_permille, t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
+      } else {
+        if (stage_bytes > 65536) e = raise_lds_limit((const void*)sens_predict_staged_kernel<float>, (int)stage_bytes);
+        if (e == hipSuccess)
+          ARD_LAUNCH(sens_predict_staged_kernel<float>, dim3(regions), dim3(256), stage_bytes, (hipStream_t)stream, (const float*)A, g,
+                     sg, k_permille, t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
+      }
+      if (e != hipSuccess) return fail(ARD_EHIP, "raising the LDS limit failed: %s", hipGetErrorString(e));
+      ARD_LAUNCH_CHECK("sens_predict_staged_kernel");
+      return ARD_OK;
+    }
+    const size_t lds = (size_t)(g.y + g.x) * sizeof(int);
+    if (dtype == ARD_BF16)
+      ARD_LAUNCH(sens_predict_lut_kernel<uint16_t>, dim3(regions), dim3(256), lds, (hipStream_t)stream, (const uint16_t*)A, g, k_permille,
+                 t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
+    else
+      ARD_LAUNCH(sens_predict_lut_kernel<float>, dim3(regions), dim3(256), lds, (hipStream_t)stream, (const float*)A, g, k_permille,
+                 t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
+    ARD_LAUNCH_CHECK("sens_predict_lut_kernel");
+    return ARD_OK;
+  }
   if (dtype == ARD_BF16)
     ARD_LAUNCH(sens_predict_kernel<uint16_t>, dim3(regions), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)A, g, k_permille,
                t_permille, threshold, prefix, d_count, d_samples, d_sens);
