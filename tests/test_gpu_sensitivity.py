@@ -37,6 +37,11 @@ def _predict_both(Av, Ad, k, stride, pad, x, y, kpm, tpm, thr, seed, it):
     (3, 8, 9, 9, 3, 1, 1, 8, 0, 300, 500),       # regions span the width (row-based pattern)
     (2, 4, 8, 8, 5, 2, 2, 3, 16, 1000, 250),     # strided 5x5, every element's worth of draws
     (1, 16, 7, 7, 1, 1, 0, 7, 4, 100, 0),        # 1x1, t = 0: everything sensitive
+    # planes that are whole 16-byte pieces: the region's footprint is staged in LDS before the draws
+    (2, 8, 8, 8, 3, 1, 1, 4, 0, 300, 500),       # bands that start mid-row and wrap into the next output row
+    (2, 6, 8, 12, 3, 1, 1, 5, 18, 500, 400),     # column blocks of two channels: footprint channels start above 0
+    (2, 4, 8, 8, 3, 2, 1, 3, 0, 700, 300),       # strided
+    (3, 8, 16, 8, 5, 1, 2, 40, 0, 200, 500),     # tall bands, 5x5 filter with two rows of padding
 ])
 def test_prediction_and_patterns_bit_exact(dtype, N, C, H, W, k, stride, pad, x, y, kpm, tpm):
     print(f"sensitivity case {dtype} N={N} C={C} {H}x{W} k={k} s={stride} p={pad} region {x}x{y} k={kpm} t={tpm}", flush=True)
