@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libard.so")
+# (ARD_LIBRARY: another build of the same library, e.g. the host-sanitized one of build.py)
+LIB_PATH = os.environ.get("ARD_LIBRARY") or os.path.join(HERE, "libard.so")
 
 F32, BF16 = 0, 1
 PAT_NONE, PAT_ROW, PAT_TILE, PAT_LIST = 0, 1, 2, 3

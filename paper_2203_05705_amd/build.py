@@ -31,16 +31,29 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build_library(verbose: bool = True, jobs: int = 8) -> str:
-    """Compile every csrc/*.hip and link libard.so next to this file. Always recompiles."""
+# host code under AddressSanitizer + UBSan (device code untouched): for running the CPU test-suite -- dispatch,
+# class tables, the host-side bounds proofs -- against, see build_library(host_sanitizers=True)
+HOST_SAN_FLAGS = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                  "-Xarch_host", "-fno-omit-frame-pointer"]
+LIB_HOSTSAN = os.path.join(HERE, "libard_hostsan.so")
+
+
+def build_library(verbose: bool = True, jobs: int = 8, host_sanitizers: bool = False) -> str:
+    """Compile every csrc/*.hip and link libard.so next to this file. Always recompiles.
+    host_sanitizers: build libard_hostsan.so instead (load it with ARD_LIBRARY=<path> and the ASan runtime
+    preloaded: LD_PRELOAD=$(hipcc -print-file-name=libclang_rt.asan-x86_64.so) ASAN_OPTIONS=detect_leaks=0)."""
     hipcc = _hipcc()
-    os.makedirs(BUILD_DIR, exist_ok=True)
+    build_dir = BUILD_DIR + ("_hostsan" if host_sanitizers else "")
+    lib = LIB_HOSTSAN if host_sanitizers else LIB
+    flags = HIPCC_FLAGS + (HOST_SAN_FLAGS if host_sanitizers else [])
+    link_flags = ["-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize"] if host_sanitizers else []
+    os.makedirs(build_dir, exist_ok=True)
     srcs = sources()
-    objs = [os.path.join(BUILD_DIR, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    objs = [os.path.join(build_dir, os.path.basename(s)[:-4] + ".o") for s in srcs]
 
     def compile_one(pair):
         src, obj = pair
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", src, "-o", obj]
+        cmd = [hipcc, *flags, "-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -51,17 +64,17 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
 
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(srcs)))) as ex:
         list(ex.map(compile_one, zip(srcs, objs)))
-    tmp = LIB + ".tmp"
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp],
+    tmp = lib + ".tmp"
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *link_flags, *objs, "-o", tmp],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print(f"[build] linked {LIB}", flush=True)
-    return LIB
+        print(f"[build] linked {lib}", flush=True)
+    return lib
 
 
 if __name__ == "__main__":
-    build_library()
+    build_library(host_sanitizers="--host-sanitizers" in sys.argv[1:])
     sys.exit(0)
