@@ -196,3 +196,33 @@ def conv_bwd_rows(dY, A, Wt, row_keep, stride=1, pad=1):
                 dAp[:, oh * stride:oh * stride + KH, ow * stride:ow * stride + KW] += dX[oh * Wo + ow].reshape(C, KH, KW)
         dA[n] = dAp[:, pad:pad + H, pad:pad + W]
     return dA, dWm.reshape(Wt.shape)
+
+
+def conv_bwd_blocks(dY, A, Wt, block_keep, x, y, stride=1, pad=1):
+    """Gradients of conv_fwd_blocks (Section 5.2.2): the product runs over the input matrix with the dropped
+    blocks removed, so an entry (p, q) of a dropped block neither contributes to the weight gradient nor
+    receives gradient.  Per image, with G[p, co] = dY[n, co, p] and M the block mask spread over entries:
+    dWmat[co, q] += sum_p G[p, co] (X_n * M)[p, q],  dX_n = (G Wmat) * M,  and dA collects dX_n back through
+    the positions the input matrix was cut from.  Returns (dA[N, C, H, W], dWt[Co, C, KH, KW])."""
+    A = np.asarray(A, dtype=np.float64)
+    Wt = np.asarray(Wt, dtype=np.float64)
+    dY = np.asarray(dY, dtype=np.float64)
+    N, C, H, W = A.shape
+    Co, _, KH, KW = Wt.shape
+    Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    Wm = Wt.reshape(Co, -1)
+    dWm = np.zeros_like(Wm)
+    dA = np.zeros_like(A)
+    for n in range(N):
+        X = input_matrix(A[n], (KH, KW), stride, pad)
+        R, Q = X.shape
+        M = np.kron(block_keep[n].astype(np.float64), np.ones((x, y)))[:R, :Q]
+        G = dY[n].reshape(Co, Ho * Wo).T                                                 # [rows x Co]
+        dWm += G.T @ (X * M)
+        dX = (G @ Wm) * M                                                                # [rows x C*KH*KW]
+        dAp = np.zeros((C, H + 2 * pad, W + 2 * pad))
+        for oh in range(Ho):
+            for ow in range(Wo):
+                dAp[:, oh * stride:oh * stride + KH, ow * stride:ow * stride + KW] += dX[oh * Wo + ow].reshape(C, KH, KW)
+        dA[n] = dAp[:, pad:pad + H, pad:pad + W]
+    return dA, dWm.reshape(Wt.shape)

@@ -190,3 +190,83 @@ def test_row_pattern_gradients_special_cases():
     a2, w2 = S.conv_bwd_rows(dY2, A, Wt, keep)
     assert np.array_equal(a1, a2) and np.array_equal(w1, w2)
     assert not np.allclose(a1, dA)
+
+
+@pytest.mark.parametrize("stride,pad,k,x,y", [(1, 1, 3, 3, 5), (2, 1, 3, 4, 9), (1, 0, 2, 7, 2), (1, 2, 5, 5, 25)])
+def test_block_pattern_gradients_are_autograd_of_the_masked_product(stride, pad, k, x, y):
+    """Y_n = W (unfold(A_n) * M): torch's unfold and autograd, with the mask spread entry by entry in loops."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(40 + stride + pad + k)
+    N, C, H, W, Co = 2, 3, 7, 6, 4
+    A = rng.standard_normal((N, C, H, W))
+    Wt = rng.standard_normal((Co, C, k, k))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    R, Q = Ho * Wo, C * k * k
+    RB, CB = -(-R // x), -(-Q // y)
+    bk = (rng.uniform(size=(N, RB, CB)) < 0.55).astype(np.uint8)
+    M = np.zeros((N, Q, R))
+    for n in range(N):
+        for q in range(Q):
+            for p in range(R):
+                M[n, q, p] = bk[n, p // x, q // y]
+    dY = rng.standard_normal((N, Co, Ho, Wo))
+    At, Wtt = torch.tensor(A, requires_grad=True), torch.tensor(Wt, requires_grad=True)
+    cols = F.unfold(At, (k, k), padding=pad, stride=stride) * torch.tensor(M)        # [N, C*k*k, Ho*Wo]
+    Y = (Wtt.reshape(Co, Q) @ cols).reshape(N, Co, Ho, Wo)
+    assert np.allclose(S.conv_fwd_blocks(A, Wt, bk, x, y, stride, pad), Y.detach().numpy(), atol=1e-11)
+    (Y * torch.tensor(dY)).sum().backward()
+    dA, dW = S.conv_bwd_blocks(dY, A, Wt, bk, x, y, stride, pad)
+    assert np.allclose(dA, At.grad.numpy(), atol=1e-11)
+    assert np.allclose(dW, Wtt.grad.numpy(), atol=1e-11)
+
+
+def test_block_pattern_gradients_special_cases():
+    """Every block kept: the plain convolution's gradients.  None kept: zero.  Whole block rows dropped: the
+    row pattern's gradients.  Blocks of one channel's taps over all rows of an image: that channel dropped in
+    that image.  One entry by brute force."""
+    rng = np.random.default_rng(22)
+    N, C, H, W, Co = 2, 4, 6, 6, 3
+    A, Wt, dY = rng.standard_normal((N, C, H, W)), rng.standard_normal((Co, C, 3, 3)), rng.standard_normal((N, Co, 6, 6))
+    allc = np.ones(C, np.uint8)
+    dA, dW = S.conv_bwd_blocks(dY, A, Wt, np.ones((N, 9, 8), np.uint8), 4, 5)
+    assert np.allclose(dA, OC.conv_bwd_data(dY, Wt, allc, (H, W)), atol=1e-11)
+    assert np.allclose(dW, OC.conv_bwd_weight(dY, A, allc), atol=1e-11)
+    dA0, dW0 = S.conv_bwd_blocks(dY, A, Wt, np.zeros((N, 9, 8), np.uint8), 4, 5)
+    assert not dA0.any() and not dW0.any()
+    # block rows: bands of 4 rows, kept or dropped as a whole
+    band = (rng.uniform(size=(N, 9)) < 0.5).astype(np.uint8)
+    a1, w1 = S.conv_bwd_blocks(dY, A, Wt, np.repeat(band[:, :, None], 8, axis=2), 4, 5)
+    a2, w2 = S.conv_bwd_rows(dY, A, Wt, np.repeat(band, 4, axis=1))
+    assert np.allclose(a1, a2, atol=1e-12) and np.allclose(w1, w2, atol=1e-12)
+    # block columns of 9 = one channel's taps, one band of 36 rows = the whole image
+    ch = np.array([[1, 0, 1, 1], [0, 1, 1, 0]], np.uint8)
+    a3, w3 = S.conv_bwd_blocks(dY, A, Wt, ch[:, None, :], 36, 9)
+    for n in range(N):
+        an = OC.conv_bwd_data(dY[n:n + 1], Wt, ch[n], (H, W))
+        assert np.allclose(a3[n], an[0], atol=1e-11)
+        assert not a3[n][ch[n] == 0].any()
+    wsum = sum(OC.conv_bwd_weight(dY[n:n + 1], A[n:n + 1], ch[n]) for n in range(N))
+    assert np.allclose(w3, wsum, atol=1e-11)
+    # brute force: dW[co, c, kh, kw] and dA[n, c, ih, iw] of a random mask
+    bk = (rng.uniform(size=(N, 9, 8)) < 0.5).astype(np.uint8)
+    a4, w4 = S.conv_bwd_blocks(dY, A, Wt, bk, 4, 5)
+    for (co, c, kh, kw) in [(0, 0, 0, 0), (2, 3, 1, 2), (1, 2, 2, 1)]:
+        q = (c * 3 + kh) * 3 + kw
+        ref = 0.0
+        for n in range(N):
+            for oh in range(6):
+                for ow in range(6):
+                    ih, iw = oh + kh - 1, ow + kw - 1
+                    if 0 <= ih < 6 and 0 <= iw < 6 and bk[n, (oh * 6 + ow) // 4, q // 5]:
+                        ref += dY[n, co, oh, ow] * A[n, c, ih, iw]
+        assert abs(w4[co, c, kh, kw] - ref) < 1e-11
+    for (n, c, ih, iw) in [(0, 0, 0, 0), (1, 3, 5, 2), (0, 2, 3, 3)]:
+        ref = 0.0
+        for kh in range(3):
+            for kw in range(3):
+                oh, ow = ih - kh + 1, iw - kw + 1
+                q = (c * 3 + kh) * 3 + kw
+                if 0 <= oh < 6 and 0 <= ow < 6 and bk[n, (oh * 6 + ow) // 4, q // 5]:
+                    ref += sum(dY[n, co, oh, ow] * Wt[co, c, kh, kw] for co in range(Co))
+        assert abs(a4[n, c, ih, iw] - ref) < 1e-11
