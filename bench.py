@@ -671,6 +671,25 @@ def extra_conv(ard, torch, rooflines):
                                           predict_us=round(t_pred, 1), row_pattern_us=round(t_pat, 1), fwd_rows_us=round(t_fwd, 1),
                                           fwd_speedup_vs_all_rows=round(dense_fwd / t_fwd, 3),
                                           fwd_speedup_with_prediction=round(dense_fwd / (t_fwd + t_pred + t_pat), 3))
+    # the block-based pattern of Section 5.2.2 on the same layer: blocks of 112 output positions (four rows) by one
+    # 64-channel group over all taps, balanced groups; the forward pass skips the dropped blocks, the gradients run
+    # on the general engine with the mask applied (no work skipped)
+    x, by = 112, 576
+    predb = ard.sens_predict(A, (3, 3), 1, 1, x, by, 300, 500, 0.5, 5, 0)
+    bp = ard.sens_block_pattern(predb, 1, 0.3, 0.7, 5, 0)
+    Ybl = ard.conv_fwd_blocks(A, Wt, bp["keep"], x, by, ws=ws)
+    gb = ard.conv_bwd_blocks(dY, A, Wt, bp["keep"], x, by, ws=ws)
+    t_predb = event_us(torch, lambda: lib.ard_sens_predict(ard.BF16, N, C, H, W, 3, 3, 1, 1, x, by, 300, 500, 0.5, 5, 0, P(A),
+                                                           P(predb["count"]), P(predb["samples"]), P(predb["sens"]), st))["median"]
+    t_bpat = event_us(torch, lambda: ard.sens_block_pattern(predb, 1, 0.3, 0.7, 5, 0), reps=5, warm=2)["median"]
+    t_bfwd = event_us(torch, lambda: ard.conv_fwd_blocks(A, Wt, bp["keep"], x, by, ws=ws, out=Ybl), reps=5, warm=2)["median"]
+    t_bbwd = event_us(torch, lambda: ard.conv_bwd_blocks(dY, A, Wt, bp["keep"], x, by, ws=ws, out=gb), reps=5, warm=2)["median"]
+    res["block_sensitivity_pattern"] = dict(kept_fraction=round(float(bp["keep"].float().mean().item()), 4), predict_us=round(t_predb, 1),
+                                            block_pattern_us=round(t_bpat, 1), fwd_blocks_us=round(t_bfwd, 1),
+                                            fwd_speedup_vs_all_blocks=round(dense_fwd / t_bfwd, 3),
+                                            fwd_speedup_with_prediction=round(dense_fwd / (t_bfwd + t_predb + t_bpat), 3),
+                                            bwd_data_plus_weight_us=round(t_bbwd, 1), blocks="112 x 576",
+                                            bwd_engine="general (masked, no work skipped)")
     Ag, Wg = A.clone().requires_grad_(True), Wt.clone().requires_grad_(True)
     Y = F.conv2d(Ag, Wg, padding=1)
     res["vendor_dense_us"] = dict(fwd=round(event_us(torch, lambda: F.conv2d(A, Wt, padding=1))["median"], 1),

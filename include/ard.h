@@ -391,14 +391,35 @@ int32_t ard_sens_block_pattern(int32_t N, int32_t row_bands, int32_t col_blocks,
  * image's input matrix takes part iff d_block_keep[(image*RB + p/x)*CB + q/y] != 0 (the array
  * ard_sens_block_pattern writes; y = 0: blocks span the width).  out = Y[N,Cout,Ho,Wo], every element
  * written.  Arguments and workspace as for ard_fmap_drop_conv(ARD_CONV_FWD) with every channel kept.
- * This pass runs on the general convolution engine, which applies the block mask while it gathers the
- * patches: it is correct in both dtypes and for any stride, and it saves no time (dropped blocks are
- * loaded as zeros, not skipped).
+ * Dropped blocks are skipped (neither loaded nor multiplied) when the blocks are whole 64-channel groups
+ * over all filter taps and the bands fill at least half a tile: bf16, stride 1, Cout > 64,
+ * y % (64*kh*kw) == 0, kh*kw*ceil(C/64) <= 128, and x such that the bands of an image, each padded to
+ * whole tiles of 128 or 256 positions, take at most twice the image's positions.  Any other shape runs on
+ * the general convolution engine, which applies the mask while it gathers the patches: correct in both
+ * dtypes and for any stride, no time saved.
  */
 int32_t ard_conv_fwd_blocks(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
                             int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y,
                             const void* A, const void* Wt, const uint8_t* d_block_keep, void* out,
                             void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Gradients of ard_conv_fwd_blocks (Section 5.2.2): an entry of a dropped block takes no part in the
+ * product, so it contributes nothing to the weight gradient and receives no gradient itself.
+ *   mode = ARD_CONV_BWD_WEIGHT: out = dWt[Cout,C,kh,kw], dWt[co,q] = sum over images and positions p with
+ *          block (p/x, q/y) kept of dY[n,co,p] * X_n[p,q]; needs A and dYin (Wt unused, may be NULL).
+ *   mode = ARD_CONV_BWD_DATA:   out = dA[N,C,H,W], the sum over the kept entries (p, q) that were cut from a
+ *          pixel of sum_co dY[n,co,p] * Wt[co,q]; needs Wt and dYin (A unused, may be NULL); stride 1 and
+ *          pad <= k-1 only, as for ARD_CONV_BWD_DATA of ard_fmap_drop_conv (else ARD_EUNSUPPORTED).
+ * Every element of out is written.  d_block_keep, x, y, workspace and dtypes as for ard_conv_fwd_blocks.
+ * Both run on the general convolution engine (the weight gradient masks the patches it gathers, the data
+ * gradient contracts tap by tap and adds a tap's partial product where the mask keeps the entry): correct
+ * in both dtypes, no time saved.
+ */
+int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
+                            int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y,
+                            const void* A, const void* Wt, const void* dYin, const uint8_t* d_block_keep,
+                            void* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- dynamic dropout-ratio tuning (Section 5.3, host only) ---------------- */
 

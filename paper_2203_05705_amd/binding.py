@@ -98,6 +98,7 @@ _SIGS = {
     "ard_conv_workspace_bytes": (C.c_size_t, [C.c_int32] * 10),
     "ard_fmap_drop_conv": (C.c_int32, [C.c_int32] * 11 + [C.c_double, C.c_int32] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]),
     "ard_conv_fwd_blocks": (C.c_int32, [C.c_int32] * 12 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]),
+    "ard_conv_bwd_blocks": (C.c_int32, [C.c_int32] * 13 + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]),
     "ard_sens_regions": (C.c_int32, [C.c_int32] * 10 + [C.c_void_p] * 3),
     "ard_sens_predict": (C.c_int32, [C.c_int32] * 13 + [C.c_float, C.c_uint64, C.c_uint64] + [C.c_void_p] * 5),
     "ard_sens_row_pattern": (C.c_int32, [C.c_int32] * 3 + [C.c_void_p, C.c_double, C.c_double, C.c_uint64, C.c_uint64] + [C.c_void_p] * 4),
@@ -555,6 +556,21 @@ def conv_fwd_blocks(A, Wt, block_keep, x, y, stride=1, pad=1, ws=None, stream=No
     _check(lib().ard_conv_fwd_blocks(dt, N, Cc, H, W, Cout, kh, kw, stride, pad, int(x), int(y), A.data_ptr(), Wt.data_ptr(),
                                      block_keep.data_ptr(), Y.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
     return Y
+
+
+def conv_bwd_blocks(dY, A, Wt, block_keep, x, y, stride=1, pad=1, ws=None, stream=None, out=None):
+    """Gradients (dA, dWt) of conv_fwd_blocks."""
+    _dev(dY), _dev(A), _dev(Wt), _dev(block_keep)
+    N, Cc, H, W = A.shape
+    Cout, _, kh, kw = Wt.shape
+    dA, dWt = out if out is not None else (_out(A.shape, A.dtype, A.device), _out(Wt.shape, Wt.dtype, Wt.device))
+    dt = _dtype_code(A)
+    ws = _workspace(conv_workspace_bytes(dt, N, Cc, H, W, Cout, kh, kw, stride, pad), A.device, ws)
+    for mode, o in ((CONV_BWD_DATA, dA), (CONV_BWD_WEIGHT, dWt)):
+        _check(lib().ard_conv_bwd_blocks(mode, dt, N, Cc, H, W, Cout, kh, kw, stride, pad, int(x), int(y), A.data_ptr(),
+                                         Wt.data_ptr(), dY.data_ptr(), block_keep.data_ptr(), o.data_ptr(), ws.data_ptr(),
+                                         ws.numel(), _stream(stream)))
+    return dA, dWt
 
 
 def conv_bwd_rows(dY, A, Wt, row_pat, stride=1, pad=1, ws=None, stream=None, out=None):

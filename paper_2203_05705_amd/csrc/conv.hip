@@ -187,8 +187,8 @@ struct ConvGeom {
   int KH, KW, stride, pad_h, pad_w;
   int Ck;                    // gathered channels per tap
   const int* chan;           // channel list (NULL = identity)
-  // block-based sensitivity-aware pattern (Section 5.2.2), forward only: entry (p, q) of an image's input
-  // matrix, q = (channel * KH + kh) * KW + kw, is absent when blk[(n * RB + p / bx) * CB + q / by] == 0
+  // block-based sensitivity-aware pattern (Section 5.2.2): entry (p, q) of an image's input matrix,
+  // q = (channel * KH + kh) * KW + kw, is absent when blk[(n * RB + p / bx) * CB + q / by] == 0
   const uint8_t* blk;
   int bx, by, RB, CB;
 };
@@ -315,6 +315,81 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const ConvGemmParams P) 
   gemm_epilogue<T, BM, BN, WGM, WGN>(P.C, acc, m0, n0, P.M, (int)P.Ncols);
 }
 
+// Data gradient under the block pattern (Section 5.2.2).  An entry (p, q) of a dropped block of the input
+// matrix receives no gradient, so the term of (input channel c, output position p, filter tap) counts or
+// not as a whole: whether it does depends on the output row (c), the output column (the input pixel, which
+// with the tap fixes p) and the tap, on no operand alone.  The contraction therefore runs tap by tap into
+// a second accumulator that is added where the mask keeps the entry.  P.g is the geometry of the ordinary
+// data gradient (positions = input pixels, source = dY, taps flipped, stride 1) and carries the mask with
+// RB, CB of the forward input matrices; Cin_fwd = P.M channels, all kept.
+template <typename T, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void conv_bwd_data_blocks_kernel(const ConvGemmParams P) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  __shared__ uint4 lds[2 * (BM + BN) * LDS_ROW_U4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int mb = blockIdx.x / P.tiles_n, nb = blockIdx.x % P.tiles_n;
+  const int m0 = mb * BM, n0 = nb * BN;
+  const ConvGeom& g = P.g;
+  bool act[TM][TN];
+  f32x16_t acc[TM][TN], tacc[TM][TN];
+#pragma unroll
+  for (int im = 0; im < TM; ++im)
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      act[im][in] = true;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
+    }
+  // this lane's output columns: image and input pixel
+  int img[TN], ph[TN], pw[TN];
+  bool cvalid[TN];
+  const int hw = g.Hout * g.Wout;
+#pragma unroll
+  for (int in = 0; in < TN; ++in) {
+    const long j = (long)n0 + wn * WTN + in * 32 + (lane & 31);
+    cvalid[in] = j < P.Ncols;
+    img[in] = cvalid[in] ? (int)(j / hw) : 0;
+    const int rem = cvalid[in] ? (int)(j - (long)img[in] * hw) : 0;
+    ph[in] = rem / g.Wout;
+    pw[in] = rem - ph[in] * g.Wout;
+  }
+  LoaderKC<T, BM, 256> la;
+  PatchLoader<T, BN> lb;
+  la.init(P.Wp, axis_identity(P.K), m0, tid);
+  ConvGeom plain = g;
+  plain.blk = nullptr;
+  lb.init(P.src, plain, n0, tid);
+  const int taps = g.KH * g.KW;
+  for (int tap = 0; tap < taps; ++tap) {
+#pragma unroll
+    for (int im = 0; im < TM; ++im)
+#pragma unroll
+      for (int in = 0; in < TN; ++in)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tacc[im][in][v] = 0.0f;
+    lb.K = (tap + 1) * g.Ck;  // the patch loader returns zeros beyond this tap's output channels
+    gemm_mainloop<T, BM, BN, WGM, WGN>(la, lb, tap * g.Ck, (tap + 1) * g.Ck, lds, tacc, act);
+    const int fh = tap / g.KW, fw = tap - fh * g.KW;        // flipped tap the loader walked
+    const int kh = g.KH - 1 - fh, kw = g.KW - 1 - fw;        // the filter tap it stands for
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      const int oh = ph[in] - g.pad_h + fh, ow = pw[in] - g.pad_w + fw;   // output position of this term
+      if (!cvalid[in] || oh < 0 || oh >= g.Hin || ow < 0 || ow >= g.Win) continue;
+      const uint8_t* band = g.blk + (long)(img[in] * g.RB + (oh * g.Win + ow) / g.bx) * g.CB;
+#pragma unroll
+      for (int im = 0; im < TM; ++im)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int c = m0 + wm * WTM + im * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (c < P.M && band[((c * g.KH + kh) * g.KW + kw) / g.by]) acc[im][in][v] += tacc[im][in][v];
+        }
+    }
+  }
+  gemm_epilogue<T, BM, BN, WGM, WGN>(P.C, acc, m0, n0, P.M, (int)P.Ncols);
+}
+
 // A operand of BWD_WEIGHT: row = co, contraction index k = (n, oh, ow) over dY[N, Cout, Ho, Wo].
 template <typename T, int ROWS>
 struct GradRowLoader {
@@ -388,6 +463,7 @@ struct PatchColLoader {
   long K;
   long rbase[PASSES];
   int kh[PASSES], kw[PASSES];
+  int cblk[PASSES];  // column block of this row's (channel, tap) (block pattern only)
   bool rvalid[PASSES];
   int lr[PASSES], lc;
 
@@ -408,6 +484,7 @@ struct PatchColLoader {
       rbase[ps] = (long)ch * g.Hin * g.Win;
       kh[ps] = tap / g.KW;
       kw[ps] = tap - kh[ps] * g.KW;
+      cblk[ps] = g.blk ? (ch * taps + tap) / g.by : 0;
     }
   }
   __device__ __forceinline__ void load(int k0, uint4 (&regs)[PASSES]) const {
@@ -434,7 +511,8 @@ struct PatchColLoader {
           T x = 0;
           if (kc + e < K) {
             const int ih = oh * g.stride - g.pad_h + kh[ps], iw = ow * g.stride - g.pad_w + kw[ps];
-            if (ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win)
+            if (ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win &&
+                (!g.blk || g.blk[(n * g.RB + (oh * g.Wout + ow) / g.bx) * g.CB + cblk[ps]]))
               x = src[(long)n * g.Cin * g.Hin * g.Win + rbase[ps] + (long)ih * g.Win + iw];
           }
           tmp[e] = x;
@@ -752,6 +830,8 @@ struct ConvWs {
   uint16_t *grid_a, *grid_y;  // channels-last grids of the fast path (NULL when it does not apply)
   uint16_t* gwp;              // its packed weights
   float* gpart;               // its weight-gradient partial sums
+  int *blk_pix, *blk_kb, *blk_cnt;  // block pattern on the fast path: padded pixel list, per-tile block lists and counts
+  size_t blk_ints;                  // ints reserved for blk_pix and for blk_kb
   size_t total;
   int splits;
   int gsplits;  // contraction splits of the fast weight-gradient product
@@ -791,6 +871,8 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
   w.part = (float*)take((size_t)w.splits * a.Cout * a.C * taps * 4);
   w.grid_a = w.grid_y = w.gwp = nullptr;
   w.gpart = nullptr;
+  w.blk_pix = w.blk_kb = w.blk_cnt = nullptr;
+  w.blk_ints = 0;
   w.gsplits = 1;
   if (conv_fast_ok(a)) {
     int hg, wg;
@@ -801,6 +883,11 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
     w.grid_y = (uint16_t*)take((size_t)pix * cpy * 2);
     w.gwp = (uint16_t*)take((size_t)(a.Cout > a.C ? a.Cout : a.C) * taps * (cpa > cpy ? cpa : cpy) * 2);
     w.gpart = (float*)take((size_t)w.gsplits * a.Cout * taps * cpa * 4);
+    // tiles padded to at most twice the output positions; at most 128 blocks per tile of at least 128 positions
+    w.blk_ints = 2 * (size_t)a.N * a.Ho * a.Wo + 512;
+    w.blk_pix = (int*)take(w.blk_ints * 4);
+    w.blk_kb = (int*)take(w.blk_ints * 4);
+    w.blk_cnt = (int*)take((w.blk_ints / 128 + 1) * 4);
   }
   w.total = off;
   return w;
@@ -855,8 +942,10 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
 }
 
 // Y[row][pixel] = sum_k Wp[row][k] * im2col[pixel][k] on the grid; NCHW output
+// force_bn / kb_*: the block-based pattern's launch (column tile fixed by its plan, per-tile contraction lists)
 static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_t* grid_t, long grid_pixels,
-                              const ConvMap& cv, void* out, hipStream_t stream) {
+                              const ConvMap& cv, void* out, hipStream_t stream, int force_bn = 0,
+                              const int* kb_list = nullptr, const int* kb_cnt = nullptr, int kb_stride = 0) {
   FastParams F{};
   F.A = Wp;
   F.B = grid_t;
@@ -873,8 +962,12 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
   F.M = rows;
   F.N = cv.npix;
   F.cv = cv;
+  F.kb_list = kb_list, F.kb_cnt = kb_cnt, F.kb_stride = kb_stride;
   int bm, bn;
-  if (rows > 128) {
+  if (force_bn) {
+    bm = force_bn == 128 || rows > 128 ? 256 : 128;
+    bn = force_bn;
+  } else if (rows > 128) {
     bm = 256;
     bn = (long)ceil_div(rows, 256) * ceil_div(cv.npix, 256) >= 220 ? 256 : 128;
   } else if (rows > 64) {
@@ -894,6 +987,54 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
   if (bm == 256) return launch_direct_kernel<true, true, 256, 128, 8, 1>(F, grid, stream);
   if (bm == 128) return launch_direct_kernel<true, true, 128, 256, 8, 1>(F, grid, stream);
   return launch_direct_kernel<true, true, 64, 64, 4, 1>(F, grid, stream);
+}
+
+// Block-based pattern on the LDS-direct path (Section 5.2.2).  When a block of the input matrix spans
+// whole 64-channel groups over all filter taps (y a multiple of 64 * taps), a kept block is a set of whole
+// 64-deep contraction steps of the grid's (tap, channel) order, and a row band of x output positions can be
+// laid out as column tiles of its own (padded with entries that store nothing): every tile then contracts
+// over the kept blocks of ONE band, and dropped blocks are neither loaded nor multiplied.
+// Tile T = ((image * RB + band) * tpb + part) holds positions band*x + part*BN ... of its image.
+struct BlockPlan {
+  int N, HoWo, x, RB, CB, tpb, BN, taps, CG, cg_per_blk, KB;
+};
+__global__ void block_plan_kernel(const uint8_t* blk, BlockPlan p, int* pix, int* kb_list, int* kb_cnt) {
+  const int T = blockIdx.x, i = threadIdx.x;
+  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
+  const int in_band = part * p.BN + i, pos = band * p.x + in_band;
+  if (i < p.BN) pix[(long)T * p.BN + i] = (in_band < p.x && pos < p.HoWo) ? n * p.HoWo + pos : -1;
+  if (i == 0) {
+    int cnt = 0;
+    const bool any = part * p.BN < p.x && band * p.x + part * p.BN < p.HoWo;
+    const uint8_t* row = blk + (long)(n * p.RB + band) * p.CB;
+    if (any)
+      for (int tap = 0; tap < p.taps; ++tap)
+        for (int cg = 0; cg < p.CG; ++cg)
+          if (row[cg / p.cg_per_blk]) kb_list[(long)T * p.KB + cnt++] = tap * p.CG + cg;
+    kb_cnt[T] = cnt;
+  }
+}
+
+// The column tile (128 or 256 positions) that wastes the least padding, or 0 when this path does not apply.
+static int block_fast_tile(const ConvArgs& a, const ConvWs& w) {
+  const int taps = a.kh * a.kw;
+  if (!w.grid_a || !w.blk_pix || dev_knobs().no_fast || a.Cout <= 64) return 0;
+  if (a.by % (64 * taps)) return 0;
+  const int CG = pad64(a.C) / 64;
+  if (taps * CG > 128) return 0;
+  const long hw = (long)a.Ho * a.Wo, RB = ceil_div(a.Ho * a.Wo, a.bx);
+  int best = 0;
+  long best_len = 0;
+  for (int bn : {256, 128}) {
+    if (bn == 128 && a.Cout <= 128) continue;  // (the 128-row tile comes with 256 columns only)
+    const long len = RB * ceil_div(a.bx, bn) * bn;  // padded positions per image
+    if (len > 2 * hw) continue;
+    if (!best || len < best_len) best = bn, best_len = len;
+  }
+  if (!best) return 0;
+  const long tiles = (long)a.N * best_len / best;
+  if ((size_t)(a.N * best_len) > w.blk_ints || (size_t)(tiles * taps * CG) > w.blk_ints || tiles >= (1L << 22)) return 0;
+  return best;
 }
 
 static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, const void* dYin, void* out,
@@ -935,6 +1076,20 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    if (a.blk) {
+      const int bn = block_fast_tile(a, w);
+      if (!bn) return fail(ARD_EUNSUPPORTED, "block pattern outside the fast path");  // (callers test block_fast_tile first)
+      BlockPlan bp{a.N, a.Ho * a.Wo, a.bx, ceil_div(a.Ho * a.Wo, a.bx), ceil_div(a.C * taps, a.by), ceil_div(a.bx, bn), bn, taps,
+                   Cp / 64, a.by / (64 * taps), taps * (Cp / 64)};
+      const int tiles = a.N * bp.RB * bp.tpb;
+      ARD_LAUNCH(block_plan_kernel, dim3((unsigned)tiles), dim3(bn), 0, stream, a.blk, bp, w.blk_pix, w.blk_kb, w.blk_cnt);
+      ARD_LAUNCH_CHECK("block_plan_kernel");
+      // bands of an even number of positions in planes of an even size: the tiles hold whole pairs of neighbours
+      const int pairs = (a.bx % 2 == 0) && ((a.Ho * a.Wo) % 2 == 0);
+      ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, tiles * bn, a.Cout, nullptr, a.Cout, w.blk_pix, a.N * a.Ho * a.Wo, -1, pairs};
+      return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream, bn, w.blk_kb, w.blk_cnt,
+                            bp.KB);
+    }
     ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, a.N * a.Ho * a.Wo, a.Cout, nullptr, a.Cout, nullptr, 0, -1};
     return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
@@ -1111,7 +1266,8 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
       return conv_run<T>(plain, rate, A, Wt, dYin, out, d_mask, d_keep, d_count, d_score, w, stream);
     }
   }
-  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast && !a.blk) {
+  if (Ck > 0 && w.grid_a && a.mode >= ARD_CONV_FWD && a.mode <= ARD_CONV_BWD_WEIGHT && !dev_knobs().no_fast &&
+      (!a.blk || (a.mode == ARD_CONV_FWD && block_fast_tile(a, w)))) {
     if (a.mode == ARD_CONV_FWD && (!A || !Wt)) return fail(ARD_EINVAL, "FWD needs A and Wt");
     if (a.mode == ARD_CONV_BWD_DATA && (!dYin || !Wt)) return fail(ARD_EINVAL, "BWD_DATA needs dYin and Wt");
     if (a.mode == ARD_CONV_BWD_WEIGHT && (!dYin || !A)) return fail(ARD_EINVAL, "BWD_WEIGHT needs dYin and A");
@@ -1164,6 +1320,12 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.Wp = Operand{w.wp, P.K, axis_identity(Ck), (P.K % ce) == 0};
     P.src = dYin;
     P.g = ConvGeom{a.N, a.Cout, a.Ho, a.Wo, a.H, a.W, a.kh, a.kw, 1, a.kh - 1 - a.pad, a.kw - 1 - a.pad, a.Cout, nullptr};
+    if (a.blk) {
+      P.Wp.vec = (a.Cout % ce) == 0;  // the contraction is walked tap by tap: every tap must start on a chunk
+      P.g.blk = a.blk;
+      P.g.bx = a.bx, P.g.by = a.by;
+      P.g.RB = ceil_div(a.Ho * a.Wo, a.bx), P.g.CB = ceil_div(a.C * taps, a.by);
+    }
     P.M = Ck;
     P.Ncols = (long)a.N * a.H * a.W;
     P.C.p = out;
@@ -1175,6 +1337,11 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.C.alpha = 1.0f;
     P.tiles_n = ceil_div((int)P.Ncols, 128);
     long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
+    if (a.blk) {
+      ARD_LAUNCH((conv_bwd_data_blocks_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
+      ARD_LAUNCH_CHECK("conv_bwd_data_blocks_kernel");
+      return ARD_OK;
+    }
     ARD_LAUNCH((conv_gemm_kernel<T, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, P);
     ARD_LAUNCH_CHECK("conv_gemm_kernel");
     return ARD_OK;
@@ -1189,6 +1356,11 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.dY = dYin;
     P.A = A;
     P.g = ConvGeom{a.N, a.C, a.H, a.W, a.Ho, a.Wo, a.kh, a.kw, a.stride, a.pad, a.pad, Ck, d_keep};
+    if (a.blk) {
+      P.g.blk = a.blk;
+      P.g.bx = a.bx, P.g.by = a.by;
+      P.g.RB = ceil_div(a.Ho * a.Wo, a.bx), P.g.CB = ceil_div(a.C * taps, a.by);
+    }
     P.part = w.part;
     P.Cout = a.Cout;
     P.Nn = Ck * taps;
@@ -1247,6 +1419,30 @@ extern "C" int32_t ard_conv_fwd_blocks(int32_t dtype, int32_t N, int32_t C, int3
   if (dtype == ARD_BF16)
     return conv_run<uint16_t>(a, 0.0, A, Wt, nullptr, out, nullptr, nullptr, nullptr, nullptr, w, (hipStream_t)stream);
   return conv_run<float>(a, 0.0, A, Wt, nullptr, out, nullptr, nullptr, nullptr, nullptr, w, (hipStream_t)stream);
+}
+
+extern "C" int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
+                                       int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y,
+                                       const void* A, const void* Wt, const void* dYin, const uint8_t* d_block_keep, void* out,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  BatchSuspend not_recorded;
+  if (mode != ARD_CONV_BWD_DATA && mode != ARD_CONV_BWD_WEIGHT)
+    return fail(ARD_EINVAL, "mode must be ARD_CONV_BWD_DATA or ARD_CONV_BWD_WEIGHT (got %d)", mode);
+  ConvArgs a{mode, dtype, N, C, H, Wd, Cout, kh, kw, stride, pad, C, 0, 0, 0, 0, d_block_keep, x, y};
+  int32_t st = conv_check(a);
+  if (st) return st;
+  if (x < 1 || y < 0) return fail(ARD_EINVAL, "block size must be positive (y = 0: the whole width)");
+  if (y == 0) a.by = C * kh * kw;
+  if (!dYin || !d_block_keep || !out) return fail(ARD_EINVAL, "null pointer");
+  ConvWs w = conv_ws_layout((char*)ws, a);
+  if (!ws || ws_bytes < w.total) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  // every channel is kept: the passes take the identity list
+  ARD_LAUNCH(iota_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, s, w.all_chan, C);
+  ARD_LAUNCH_CHECK("iota_kernel");
+  if (dtype == ARD_BF16)
+    return conv_run<uint16_t>(a, 0.0, A, Wt, dYin, out, nullptr, w.all_chan, nullptr, nullptr, w, s);
+  return conv_run<float>(a, 0.0, A, Wt, dYin, out, nullptr, w.all_chan, nullptr, nullptr, w, s);
 }
 
 extern "C" int32_t ard_fmap_drop_conv(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd,

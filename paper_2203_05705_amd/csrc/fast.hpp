@@ -72,6 +72,7 @@ struct ConvMap {
   // pix_fixed >= 0 (host-side bounds proof only): every column reads that pixel instead of the list.
   const int* pix;
   int pix_total, pix_fixed;
+  int pix_pairs;  // list entries 2i, 2i+1 are pixels 2m, 2m+1 of one image (or both padding): stored as one word
 };
 
 struct FastParams {
@@ -90,6 +91,12 @@ struct FastParams {
   int splits;
   int M, N, tiles_m, tiles_n, group_m, total_tiles;
   ConvMap cv;  // MODE 1 / 2 of the kernel only
+  // MODE 1, optional (block-based sensitivity-aware pattern, Section 5.2.2): the column tile t of the
+  // product contracts over the kb_cnt[t] 64-wide blocks kb_list[t * kb_stride ...] of the contraction only
+  // (at most 128 of them); entries of cv.pix may then be -1 (padding of a tile: nothing is stored).
+  const int* kb_list;
+  const int* kb_cnt;
+  int kb_stride;
   // Scattering epilogue (row patterns without compact outputs): the tile's results go through
   // LDS and are written, with the dropped positions it owns as +0.0, through these affine maps.
   int scatter, scatter_vec;
@@ -165,7 +172,7 @@ template <int ROWS, int NW> struct DirectLoader<true, ROWS, NW> {
     for (int j = 0; j < NI; ++j) {
       int row = imin(row0 + (wave * NI + j) * 8 + (lane >> 3), cv.npix - 1);
       if (cv.pix_fixed >= 0) row = cv.pix_fixed;
-      else if (cv.pix) row = cv.pix[row];
+      else if (cv.pix) row = imax(cv.pix[row], 0);  // (-1: padding entry, reads pixel 0, stores nothing)
       const int n = row / cv.HoWo, rem = row - n * cv.HoWo;
       const int ho = rem / cv.Wo, wo = rem - ho * cv.Wo;
       voff[j] = (uint32_t)((n * cv.HgWg + ho * cv.Wg + wo) * cv.Cp + chunk_k(lane, wave, j)) * 2u;
@@ -455,6 +462,9 @@ __host__ __device__ __forceinline__ bool direct_assign(const FastParams& P, int 
     const int rows_in_band = imin(P.group_m, P.tiles_m - band * P.group_m);
     m0 = (band * P.group_m + inb % rows_in_band) * F_BM;
     n0 = (inb / rows_in_band) * BN;
+    // per-tile contraction lists: the length comes from the tile's count, the blocks are looked up step
+    // by step (the host-side proof clears kb_cnt and walks the whole contraction, which bounds every list)
+    if (P.kb_cnt) kax.n = imin(imax(P.kb_cnt[n0 / BN], 0), imin(kax.nphys / 64, 128)) * 64;
   } else {
     const ClassTab& t = P.tab;
     int c = 0, l = -1;
@@ -536,6 +546,31 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[im][in][v] = 0.0f;
 
+  // per-tile contraction list (MODE 1): lane l keeps the tile's l-th and (64+l)-th block, a step reads its
+  // block out of the lane that holds it, so the loop touches no memory for the list
+  int kbl0 = 0, kbl1 = 0;
+  bool kb_mode = false;
+  if constexpr (MODE == 1) {
+    if (P.kb_cnt) {
+      kb_mode = true;
+      const int* lst = P.kb_list + (long)(n0 / BN) * P.kb_stride;
+      const int cnt = Kn >> 6, last = kax.nphys / 64 - 1;
+      kbl0 = lane < cnt ? imin(imax(lst[lane], 0), last) : 0;
+      kbl1 = 64 + lane < cnt ? imin(imax(lst[64 + lane], 0), last) : 0;
+    }
+  }
+  auto slab = [&](int s, int& ks, int& ksb) {
+    if constexpr (MODE == 1) {
+      if (kb_mode) {
+        ks = (s < 64 ? __builtin_amdgcn_readlane(kbl0, s) : __builtin_amdgcn_readlane(kbl1, s - 64)) * 64;
+        const int t = ks / P.cv.Cp;
+        ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
+        return;
+      }
+    }
+    direct_slab<MODE>(P, kax, s, ks, ksb);
+  };
+
   if (Kn > 0) {
     DirectLoader<A_KC, F_BM, NW> la;
     DirectLoader<B_KC, BN, NW> lb;
@@ -576,7 +611,7 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
     auto load_stage = [&](int it, int buf) {
       const int krem = Kn - (s_lo + it) * 64;
       int ks, ksb;
-      direct_slab<MODE>(P, kax, s_lo + it, ks, ksb);
+      slab(s_lo + it, ks, ksb);
       const bool tail = krem < 64 || ks + 64 + kbump > kax.nphys;
       if (__builtin_expect(tail, 0)) {
         la.issue_tail(lds + buf * OPA, ks, krem, kax.nphys, lane, wave, kbump);
@@ -683,7 +718,7 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
       wg_barrier();
       issue(NB{}, I0{}, 0);
       int ks, ksb;
-      direct_slab<MODE>(P, kax, s_lo + it + NST, ks, ksb);
+      slab(s_lo + it + NST, ks, ksb);
       // the loads of stage it+NST spread between the last slice's MFMAs (a burst of LPS load instructions
       // keeps this wavefront from issuing MFMAs for as long as it takes to issue them)
       {
@@ -771,12 +806,14 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
     const ConvMap& cv = P.cv;
     const int HW = cv.HoWo;
     const bool odd = lane & 1;
-    const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0) && !cv.pix;  // (listed pixels are not adjacent)
+    // (listed pixels are not adjacent unless the list says so)
+    const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0) && (!cv.pix || cv.pix_pairs);
 #pragma unroll
     for (int in = 0; in < TN; ++in) {
       const int jc = n0 + wn * WTN + in * 32 + (lane & 31);
       if (jc >= cv.npix) continue;  // npix is even whenever pair_ok, so a pair is in or out together
       const int j = cv.pix ? cv.pix[jc] : jc;
+      if (j < 0) continue;  // padding entry of a tile
       const int n = j / HW;
       uint16_t* col = P.C + (long)n * cv.out_chan * HW + (j - n * HW);
 #pragma unroll
@@ -1181,7 +1218,11 @@ static int32_t direct_envelope(const FastParams& F) {
     if (MODE == 1) {
       const ConvMap& cv = F.cv;
       if (cv.npix < 1 || cv.Cp < 64 || (cv.Cp % 64) || cv.kw < 1 || kphys % cv.Cp) return fail(ARD_ESHAPE, "bounds proof: bad grid");
-      if (cv.pix && (cv.pix_total < 1 || cv.npix > cv.pix_total)) return fail(ARD_ESHAPE, "bounds proof: pixel list longer than the pixels");
+      // (a list with per-tile contraction lists is padded tile by tile and may be longer than the pixels)
+      if (cv.pix && (cv.pix_total < 1 || (cv.npix > cv.pix_total && !F.kb_cnt)))
+        return fail(ARD_ESHAPE, "bounds proof: pixel list longer than the pixels");
+      if (F.kb_cnt && (!cv.pix || !F.kb_list || F.kb_stride < 1 || F.splits > 1 || k.kind != AX_AFFINE || (kphys % 64)))
+        return fail(ARD_EINVAL, "bounds proof: per-tile contraction lists need a pixel list, whole 64-wide blocks and no split");
       const int row = (cv.pix ? cv.pix_total : cv.npix) - 1, n = row / cv.HoWo, rem = row - n * cv.HoWo;
       const long base = (long)n * cv.HgWg + (long)(rem / cv.Wo) * cv.Wg + rem % cv.Wo;
       const int tl = (int)(kphys / cv.Cp) - 1;  // last tap
@@ -1212,11 +1253,14 @@ static inline Axis axis_list_surrogate(const Axis& r, bool last) {
 }
 
 template <bool A_KC, bool B_KC, int BM, int BN, int NW, int MODE>
-static int32_t direct_prove(const FastParams& P, int grid_x, DirectBounds& out) {
+static int32_t direct_prove(const FastParams& P_in, int grid_x, DirectBounds& out) {
   constexpr long NONE_LO = 0x7fffffffffffffffL;
   out = DirectBounds{NONE_LO, -1, NONE_LO, -1};
   using LA = DirectLoader<A_KC, BM, NW>;
   using LB = DirectLoader<B_KC, BN, NW>;
+  FastParams P = P_in;
+  P.kb_cnt = nullptr;  // device memory: every list of whole blocks stays inside the full contraction walked here
+  P.kb_list = nullptr;
   for (int bid = 0; bid < grid_x; ++bid) {
     DirectWork wk;
     if (!direct_assign<BM, BN>(P, bid, wk)) continue;

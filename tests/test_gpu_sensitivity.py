@@ -158,7 +158,12 @@ def test_config5_layer_under_the_row_pattern():
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,x,y", [(2, 8, 16, 7, 7, 3, 1, 1, 4, 8), (3, 12, 20, 9, 6, 3, 1, 1, 5, 16),
                                                              (2, 6, 10, 11, 10, 5, 1, 2, 8, 32), (2, 8, 12, 9, 9, 3, 2, 1, 3, 9),
-                                                             (4, 24, 130, 10, 12, 3, 1, 1, 16, 64)])
+                                                             (4, 24, 130, 10, 12, 3, 1, 1, 16, 64),
+                                                             # blocks of whole 64-channel groups over all taps, bands of
+                                                             # half a tile or more: dropped blocks are skipped (bf16)
+                                                             (2, 128, 200, 12, 12, 3, 1, 1, 72, 576), (3, 100, 140, 12, 13, 3, 1, 1, 78, 576), (3, 100, 100, 12, 13, 3, 1, 1, 156, 576),
+                                                             (2, 192, 130, 9, 16, 3, 1, 1, 144, 576), (5, 256, 300, 14, 14, 3, 1, 1, 98, 1152),
+                                                             (2, 128, 136, 16, 16, 1, 1, 0, 128, 64), (2, 64, 256, 15, 15, 5, 1, 2, 75, 1600)])
 def test_forward_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad, x, y):
     """Section 5.2.2: prediction per x-by-y region, balanced groups, block mask, forward product over the kept blocks."""
     print(f"blocks forward {dtype} N={N} C={C} Cout={Cout} {H}x{W} k={k} s={stride} p={pad} x={x} y={y}", flush=True)
@@ -173,6 +178,65 @@ def test_forward_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad
     assert 0 < keep.sum() < keep.size
     Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y, stride, pad)
     assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, y, stride, pad), dtype, None, "conv blocks Y")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,x,y", [(2, 8, 16, 7, 7, 3, 1, 1, 4, 8), (3, 12, 20, 9, 6, 3, 1, 1, 5, 16),
+                                                             (2, 6, 10, 11, 10, 5, 1, 2, 8, 32), (2, 8, 12, 9, 9, 3, 2, 1, 3, 9),
+                                                             (4, 24, 130, 10, 12, 3, 1, 1, 16, 64), (3, 140, 20, 12, 13, 3, 1, 0, 8, 0),
+                                                             (2, 5, 7, 6, 6, 2, 1, 1, 7, 3)])
+def test_gradients_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad, x, y):
+    """Section 5.2.2: gradients of the product over the kept blocks (the data gradient for stride 1 only)."""
+    print(f"blocks gradients {dtype} N={N} C={C} Cout={Cout} {H}x{W} k={k} s={stride} p={pad} x={x} y={y}", flush=True)
+    rng = np.random.default_rng(N * 11 + C + y)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Wv = stored(rng.standard_normal((Cout, C, k, k)) * 0.2, dtype)
+    rows, RB, CB = ard.sens_regions(Av.shape, (k, k), stride, pad, x, y)
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    dYv = stored(rng.standard_normal((N, Cout, Ho, Wo)), dtype)
+    keep = (rng.uniform(size=(N, RB, CB)) < 0.5).astype(np.uint8)
+    keep[0, 0, 0], keep[-1, -1, -1] = 1, 0
+    Ad, Wd, dYd = from_vals(Av, dtype), from_vals(Wv, dtype), from_vals(dYv, dtype)
+    kd = torch.from_numpy(keep.reshape(-1)).cuda()
+    yy = y if y else C * k * k
+    ref_dA, ref_dW = S.conv_bwd_blocks(dYv, Av, Wv, keep, x, yy, stride, pad)
+    if stride == 1:
+        dA, dW = ard.conv_bwd_blocks(dYd, Ad, Wd, kd, x, y, stride, pad)
+        assert_parity(dA, ref_dA, dtype, None, "conv blocks dA")
+    else:
+        dW = torch.empty_like(Wd)
+        ws = torch.empty(ard.conv_workspace_bytes(ard._dtype_code(Ad), N, C, H, W, Cout, k, k, stride, pad), dtype=torch.uint8, device="cuda")
+        args = [ard._dtype_code(Ad), N, C, H, W, Cout, k, k, stride, pad, x, y, Ad.data_ptr(), Wd.data_ptr(), dYd.data_ptr(),
+                kd.data_ptr()]
+        tail = [ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream]
+        assert ard.lib().ard_conv_bwd_blocks(ard.CONV_BWD_WEIGHT, *args, dW.data_ptr(), *tail) == 0
+        dA = torch.empty_like(Ad)
+        assert ard.lib().ard_conv_bwd_blocks(ard.CONV_BWD_DATA, *args, dA.data_ptr(), *tail) == -6  # ARD_EUNSUPPORTED
+    torch.cuda.synchronize()
+    assert_parity(dW, ref_dW, dtype, None, "conv blocks dW")
+
+
+def test_config5_layer_under_the_block_pattern():
+    """The config-5 layer under the block-based pattern: 112-by-576 blocks of the 784 x 2304 input matrices (four
+    rows of output positions by one 64-channel group over all taps: the forward pass skips the dropped blocks),
+    balanced groups, possibilities 0.3 / 0.7; forward pass and both gradients against the oracle on every element."""
+    wl = WL.conv_layer(seed=5)
+    Av, Wv, dYv = wl.values("A"), wl.values("Wt"), wl.values("dY")
+    Ad, Wd, dYd = (to_dev(wl.arrays[k], "bf16") for k in ("A", "Wt", "dY"))
+    x, y = 112, 576
+    pred = ard.sens_predict(Ad, (3, 3), 1, 1, x, y, 300, 500, 0.5, 5, 0)
+    rows, RB, CB = ard.sens_regions(Av.shape, (3, 3), 1, 1, x, y)
+    bp = ard.sens_block_pattern(pred, 1, 0.3, 0.7, 5, 0)
+    keep = bp["keep"].cpu().numpy().reshape(128, RB, CB)
+    print(f"config 5 under the block pattern: {int(keep.sum())} of {keep.size} blocks kept; running oracle ...", flush=True)
+    assert 0.2 < keep.mean() < 0.8
+    Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y)
+    dA, dW = ard.conv_bwd_blocks(dYd, Ad, Wd, bp["keep"], x, y)
+    torch.cuda.synchronize()
+    assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, y), "bf16", None, "config 5 blocks Y")
+    ref_dA, ref_dW = S.conv_bwd_blocks(dYv, Av, Wv, keep, x, y)
+    assert_parity(dA, ref_dA, "bf16", None, "config 5 blocks dA")
+    assert_parity(dW, ref_dW, "bf16", None, "config 5 blocks dW")
 
 
 @pytest.mark.parametrize("N,rows,x", [(3, 50, 4), (40, 784, 8), (128, 784, 8)])

@@ -103,6 +103,40 @@ def test_lstm_and_conv_shapes():
         assert D.last_bounds(lib)[0] == 4
 
 
+def test_block_pattern_dispatch_and_bounds():
+    """Forward pass under the block pattern: blocks of whole 64-channel groups over all taps with bands of at
+    least half a tile go to the LDS-direct kernel (plan kernel + per-tile block lists, proof over the whole
+    contraction); any other block shape goes to the general engine."""
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        for (N, Cc, Cout, H, W, k, pad, x, y), fast in [((128, 256, 256, 28, 28, 3, 1, 112, 576), True),
+                                                         ((128, 256, 256, 28, 28, 3, 1, 196, 1152), True),
+                                                         ((2, 128, 200, 12, 12, 3, 1, 72, 576), True),
+                                                         ((3, 100, 140, 12, 13, 3, 1, 78, 576), True),
+                                                         ((3, 100, 100, 12, 13, 3, 1, 156, 576), True),
+                                                         ((2, 192, 130, 9, 16, 3, 1, 144, 0), True),
+                                                         ((2, 128, 64, 12, 12, 3, 1, 72, 576), False),     # too few output channels
+                                                         ((128, 256, 256, 28, 28, 3, 1, 8, 576), False),   # bands far below a tile
+                                                         ((128, 256, 256, 28, 28, 3, 1, 112, 64), False),  # blocks cut channels
+                                                         ((2, 128, 200, 12, 12, 3, 2, 18, 576), False)]:   # stride 2
+            stride = 2 if (pad == 2) else 1
+            pad = 1 if stride == 2 else pad
+            n = lib.ard_conv_workspace_bytes(D.BF16, N, Cc, H, W, Cout, k, k, stride, pad)
+            ws = heap(n)
+            big = N * max(Cc, Cout) * (H + 2) * (W + 2) * 4
+            A, Wt, out, keep = (heap(big) for _ in range(4))
+            D.launches(lib)
+            before = D.last_bounds(lib)[0]
+            rc = lib.ard_conv_fwd_blocks(D.BF16, N, Cc, H, W, Cout, k, k, stride, pad, x, y, A, Wt, keep, out, ws, n, None)
+            assert rc == 0, lib.ard_last_error().decode()
+            names = D.launches(lib)[1]
+            assert ("block_plan_kernel" in names and "gemm_direct_kernel" in names) == fast, (N, Cc, Cout, x, y, names)
+            assert ("conv_gemm_kernel" in names) == (not fast)
+            if fast:
+                nb, six = D.last_bounds(lib)
+                assert nb == 1 and 0 <= six[0] < six[1] <= six[2] and 0 <= six[3] < six[4] <= six[5]
+
+
 def test_a_shortened_operand_is_rejected():
     """The proof is tight: with every operand pretended 8 elements shorter than it is, the dense 4096^3
     product (whose loaders read their operands to the last byte) must be refused, and nothing launched."""
