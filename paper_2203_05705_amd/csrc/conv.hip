@@ -887,7 +887,7 @@ static ConvWs conv_ws_layout(char* base, const ConvArgs& a) {
     w.blk_ints = 2 * (size_t)a.N * a.Ho * a.Wo + 512;
     w.blk_pix = (int*)take(w.blk_ints * 4);
     w.blk_kb = (int*)take(w.blk_ints * 4);
-    w.blk_cnt = (int*)take((w.blk_ints / 128 + 1) * 4);
+    w.blk_cnt = (int*)take((w.blk_ints / 128 + 1) * 4 * 2);  // counts, then the tiles' places in the launch
   }
   w.total = off;
   return w;
@@ -998,11 +998,60 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
 struct BlockPlan {
   int N, HoWo, x, RB, CB, tpb, BN, taps, CG, cg_per_blk, KB;
 };
-__global__ void block_plan_kernel(const uint8_t* blk, BlockPlan p, int* pix, int* kb_list, int* kb_cnt) {
+// kept 64-channel groups of tile T's band (0 for a tile that holds no position)
+__device__ __forceinline__ int block_tile_groups(const uint8_t* blk, const BlockPlan& p, int T) {
+  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
+  if (part * p.BN >= p.x || band * p.x + part * p.BN >= p.HoWo) return 0;
+  const uint8_t* row = blk + (long)(n * p.RB + band) * p.CB;
+  int g = 0;
+  for (int cg = 0; cg < p.CG; ++cg) g += row[cg / p.cg_per_blk] ? 1 : 0;
+  return g;
+}
+
+// Where each tile goes in the launch: longest contraction first on every XCD (workgroups start in order,
+// so the long ones do not end up alone at the end).  One workgroup: counting sort of the tiles by kept groups;
+// tiles of equal length keep no particular order among themselves (the results do not depend on it).
+constexpr int kBlockOrderMaxTiles = 1 << 15;
+__global__ __launch_bounds__(1024) void block_order_kernel(const uint8_t* blk, BlockPlan p, int tiles, int* slot) {
+  __shared__ int hist[130], start[130];
+  for (int i = threadIdx.x; i <= p.CG; i += blockDim.x) hist[i] = 0;
+  __syncthreads();
+  for (int T = threadIdx.x; T < tiles; T += blockDim.x) atomicAdd(&hist[block_tile_groups(blk, p, T)], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int at = 0;
+    for (int g = p.CG; g >= 0; --g) {
+      start[g] = at;
+      at += hist[g];
+    }
+  }
+  __syncthreads();
+  // The kernel deals its work items to the 8 XCDs in contiguous shares [x*n/8, (x+1)*n/8) and a share's
+  // workgroups start in order: rank r (longest first) goes to XCD r % 8, place r / 8 of its share; the last
+  // n % 8 ranks fill the shares that are one longer than the others.
+  const int even = tiles / 8;
+  for (int T = threadIdx.x; T < tiles; T += blockDim.x) {
+    const int r = atomicAdd(&start[block_tile_groups(blk, p, T)], 1);
+    int x = r & 7, at = r >> 3;
+    if (r >= 8 * even) {
+      int j = r - 8 * even;
+      at = even;
+      for (x = 0; x < 8; ++x) {
+        const int size = (int)((long)(x + 1) * tiles / 8) - (int)((long)x * tiles / 8);
+        if (size > even && j-- == 0) break;
+      }
+    }
+    slot[T] = (int)((long)x * tiles / 8) + at;
+  }
+}
+
+// slot: position of tile T in the launch (NULL: T itself)
+__global__ void block_plan_kernel(const uint8_t* blk, BlockPlan p, const int* slot, int* pix, int* kb_list, int* kb_cnt) {
   const int T = blockIdx.x, i = threadIdx.x;
+  const int at = slot ? slot[T] : T;
   const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
   const int in_band = part * p.BN + i, pos = band * p.x + in_band;
-  if (i < p.BN) pix[(long)T * p.BN + i] = (in_band < p.x && pos < p.HoWo) ? n * p.HoWo + pos : -1;
+  if (i < p.BN) pix[(long)at * p.BN + i] = (in_band < p.x && pos < p.HoWo) ? n * p.HoWo + pos : -1;
   if (i == 0) {
     int cnt = 0;
     const bool any = part * p.BN < p.x && band * p.x + part * p.BN < p.HoWo;
@@ -1010,8 +1059,8 @@ __global__ void block_plan_kernel(const uint8_t* blk, BlockPlan p, int* pix, int
     if (any)
       for (int tap = 0; tap < p.taps; ++tap)
         for (int cg = 0; cg < p.CG; ++cg)
-          if (row[cg / p.cg_per_blk]) kb_list[(long)T * p.KB + cnt++] = tap * p.CG + cg;
-    kb_cnt[T] = cnt;
+          if (row[cg / p.cg_per_blk]) kb_list[(long)at * p.KB + cnt++] = tap * p.CG + cg;
+    kb_cnt[at] = cnt;
   }
 }
 
@@ -1082,7 +1131,14 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
       BlockPlan bp{a.N, a.Ho * a.Wo, a.bx, ceil_div(a.Ho * a.Wo, a.bx), ceil_div(a.C * taps, a.by), ceil_div(a.bx, bn), bn, taps,
                    Cp / 64, a.by / (64 * taps), taps * (Cp / 64)};
       const int tiles = a.N * bp.RB * bp.tpb;
-      ARD_LAUNCH(block_plan_kernel, dim3((unsigned)tiles), dim3(bn), 0, stream, a.blk, bp, w.blk_pix, w.blk_kb, w.blk_cnt);
+      int* slot = nullptr;
+      if (tiles > 256 && tiles <= kBlockOrderMaxTiles) {  // (up to one tile per CU there is nothing to order)
+        slot = w.blk_cnt + tiles;
+        ARD_LAUNCH(block_order_kernel, dim3(1), dim3(1024), 0, stream, a.blk, bp, tiles, slot);
+        ARD_LAUNCH_CHECK("block_order_kernel");
+      }
+      ARD_LAUNCH(block_plan_kernel, dim3((unsigned)tiles), dim3(bn), 0, stream, a.blk, bp, (const int*)slot, w.blk_pix, w.blk_kb,
+                 w.blk_cnt);
       ARD_LAUNCH_CHECK("block_plan_kernel");
       // bands of an even number of positions in planes of an even size: the tiles hold whole pairs of neighbours
       const int pairs = (a.bx % 2 == 0) && ((a.Ho * a.Wo) % 2 == 0);
