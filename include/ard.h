@@ -412,9 +412,12 @@ int32_t ard_conv_fwd_blocks(int32_t dtype, int32_t N, int32_t C, int32_t H, int3
  *          pixel of sum_co dY[n,co,p] * Wt[co,q]; needs Wt and dYin (A unused, may be NULL); stride 1 and
  *          pad <= k-1 only, as for ARD_CONV_BWD_DATA of ard_fmap_drop_conv (else ARD_EUNSUPPORTED).
  * Every element of out is written.  d_block_keep, x, y, workspace and dtypes as for ard_conv_fwd_blocks.
- * Both run on the general convolution engine (the weight gradient masks the patches it gathers, the data
- * gradient contracts tap by tap and adds a tap's partial product where the mask keeps the entry): correct
- * in both dtypes, no time saved.
+ * No work is skipped.  Blocks of whole channels (y % (kh*kw) == 0, at most 16 column blocks): per column
+ * block, dY is copied with the positions of that block's dropped bands zeroed and the ordinary gradient
+ * pass runs on the copy with the block's channels as the kept list (the fast path where the shape allows).
+ * Other block shapes run on the general convolution engine: the weight gradient masks the patches it
+ * gathers, the data gradient contracts tap by tap and adds a tap's partial product where the mask keeps
+ * the entry.  Both dtypes.
  */
 int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t Wd, int32_t Cout,
                             int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t x, int32_t y,

@@ -580,7 +580,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const ConvWgradParams P
 // dWt[co][c][tap] = rank[c] >= 0 ? sum over splits of part[s][co][rank[c]*taps + tap] : 0
 template <typename T>
 __global__ void conv_wgrad_reduce_kernel(const float* part, const int* rank, int splits, int Cout, int C, int taps,
-                                         int Nn, T* dWt) {
+                                         int Nn, int kept_only, T* dWt) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const long total = (long)Cout * C * taps;
   if (idx >= total) return;
@@ -589,6 +589,7 @@ __global__ void conv_wgrad_reduce_kernel(const float* part, const int* rank, int
   const int co = (int)(idx / ((long)taps * C));
   float s = 0.0f;
   const int r = rank[c];
+  if (r < 0 && kept_only) return;
   if (r >= 0)
     for (int sp = 0; sp < splits; ++sp) s += part[((long)sp * Cout + co) * Nn + (long)r * taps + tap];
   dWt[idx] = ElemTraits<T>::from_f32(s);
@@ -737,6 +738,16 @@ __global__ __launch_bounds__(256) void mask_pixels_kernel(const T* Y, const uint
   const uint8_t* m = row_mask + (long)n * HW;
   for (int i = threadIdx.x; i < HW; i += 256) out[base + i] = m[i] ? Y[base + i] : (T)0;
 }
+// the same with the mask of one column block of a block pattern: position p of image n is kept iff
+// blk[(n * RB + p / x) * CB + cb] != 0
+template <typename T>
+__global__ __launch_bounds__(256) void mask_bands_kernel(const T* Y, const uint8_t* blk, int RB, int CB, int cb, int x, int Cout,
+                                                         int HW, T* out) {
+  const int co = blockIdx.x, n = blockIdx.y;
+  const long base = ((long)n * Cout + co) * HW;
+  const uint8_t* m = blk + (long)n * RB * CB + cb;
+  for (int i = threadIdx.x; i < HW; i += 256) out[base + i] = m[(long)(i / x) * CB] ? Y[base + i] : (T)0;
+}
 __global__ void iota_kernel(int* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = i;
@@ -817,6 +828,7 @@ struct ConvArgs {
   // block-based pattern of the forward pass (ard_conv_fwd_blocks): x-by-y blocks of the input matrices
   const uint8_t* blk;
   int32_t bx, by;
+  int32_t kept_only;  // gradients: write the kept channels' part of the output only (the caller covers the rest)
 };
 
 struct ConvWs {
@@ -1161,7 +1173,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
-    if (Ck < a.C) {
+    if (Ck < a.C && !a.kept_only) {
       const int hw = a.H * a.W;
       ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, ceil_div(a.N, ZP_IMGS)), dim3(256), 0, stream, (uint16_t*)out,
                  (const int*)d_keep, Ck, a.N, a.C, hw, (int)((hw % 8) == 0 && al16c(out)));
@@ -1219,7 +1231,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
            : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
   if (st) return st;
   const int sum_blocks = (int)(((long)a.Cout * taps * Ck + 255) / 256);
-  const int zero_blocks = Ck < a.C ? (int)(((long)a.Cout * a.C + 255) / 256) : 0;
+  const int zero_blocks = Ck < a.C && !a.kept_only ? (int)(((long)a.Cout * a.C + 255) / 256) : 0;
   ARD_LAUNCH(wgrad_grid_reduce_kernel, dim3((unsigned)(sum_blocks + zero_blocks)), dim3(256), 0, stream, (const float*)w.gpart,
              (const int*)d_keep, Ck, splits, a.Cout, a.C, taps, Cpa, sum_blocks, (uint16_t*)out);
   ARD_LAUNCH_CHECK("wgrad_grid_reduce_kernel");
@@ -1389,7 +1401,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     P.C.cn = axis_identity((int)P.Ncols);
     P.C.plane = a.H * a.W;
     P.C.img_stride = (long)a.C * a.H * a.W;
-    P.C.fill = 1;
+    P.C.fill = a.kept_only ? 0 : 1;
     P.C.alpha = 1.0f;
     P.tiles_n = ceil_div((int)P.Ncols, 128);
     long blocks = (long)ceil_div(P.M, 128) * P.tiles_n;
@@ -1435,7 +1447,7 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     ARD_LAUNCH_CHECK("conv_wgrad_kernel");
     const long total = (long)a.Cout * a.C * taps;
     ARD_LAUNCH(conv_wgrad_reduce_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       (const float*)w.part, (const int*)w.rank, splits, a.Cout, a.C, taps, P.Nn, (T*)out);
+                       (const float*)w.part, (const int*)w.rank, splits, a.Cout, a.C, taps, P.Nn, a.kept_only, (T*)out);
     ARD_LAUNCH_CHECK("conv_wgrad_reduce_kernel");
     return ARD_OK;
   }
@@ -1496,6 +1508,34 @@ extern "C" int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, i
   // every channel is kept: the passes take the identity list
   ARD_LAUNCH(iota_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, s, w.all_chan, C);
   ARD_LAUNCH_CHECK("iota_kernel");
+  // Blocks of whole channels (y a multiple of kh*kw), not too many of them: column block cb is the channel
+  // range [cb*cpb, (cb+1)*cpb) over all taps, and whether a term of those channels counts depends on the band
+  // of the output position alone.  Per column block: dY copied with the positions of its dropped bands zeroed,
+  // then the ordinary gradient pass (whichever engine takes the shape) with that channel range as the kept
+  // list, writing its channels' part of the output only.  Work is not skipped, but the passes are the fast ones.
+  const int taps = kh * kw;
+  const int CB = ceil_div(C * taps, a.by), RB = ceil_div(a.Ho * a.Wo, a.bx);
+  if (a.by % taps == 0 && CB <= 16 && !(mode == ARD_CONV_BWD_DATA && stride != 1)) {
+    const int cpb = a.by / taps;
+    for (int cb = 0; cb < CB; ++cb) {
+      ConvArgs g = a;
+      g.blk = nullptr;
+      g.kept_only = 1;
+      g.n_keep = (cb + 1) * cpb <= C ? cpb : C - cb * cpb;
+      if (dtype == ARD_BF16)
+        ARD_LAUNCH(mask_bands_kernel<uint16_t>, dim3(Cout, N), dim3(256), 0, s, (const uint16_t*)dYin, d_block_keep, RB, CB, cb, a.bx,
+                   Cout, a.Ho * a.Wo, (uint16_t*)w.dy_rows);
+      else
+        ARD_LAUNCH(mask_bands_kernel<float>, dim3(Cout, N), dim3(256), 0, s, (const float*)dYin, d_block_keep, RB, CB, cb, a.bx, Cout,
+                   a.Ho * a.Wo, (float*)w.dy_rows);
+      ARD_LAUNCH_CHECK("mask_bands_kernel");
+      st = dtype == ARD_BF16
+               ? conv_run<uint16_t>(g, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s)
+               : conv_run<float>(g, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s);
+      if (st) return st;
+    }
+    return ARD_OK;
+  }
   if (dtype == ARD_BF16)
     return conv_run<uint16_t>(a, 0.0, A, Wt, dYin, out, nullptr, w.all_chan, nullptr, nullptr, w, s);
   return conv_run<float>(a, 0.0, A, Wt, dYin, out, nullptr, w.all_chan, nullptr, nullptr, w, s);

@@ -184,7 +184,11 @@ def test_forward_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad
 @pytest.mark.parametrize("N,C,Cout,H,W,k,stride,pad,x,y", [(2, 8, 16, 7, 7, 3, 1, 1, 4, 8), (3, 12, 20, 9, 6, 3, 1, 1, 5, 16),
                                                              (2, 6, 10, 11, 10, 5, 1, 2, 8, 32), (2, 8, 12, 9, 9, 3, 2, 1, 3, 9),
                                                              (4, 24, 130, 10, 12, 3, 1, 1, 16, 64), (3, 140, 20, 12, 13, 3, 1, 0, 8, 0),
-                                                             (2, 5, 7, 6, 6, 2, 1, 1, 7, 3)])
+                                                             (2, 5, 7, 6, 6, 2, 1, 1, 7, 3),
+                                                             # blocks of whole channels: one ordinary pass per column block
+                                                             (2, 8, 16, 7, 7, 3, 1, 1, 4, 18), (2, 40, 24, 9, 9, 3, 1, 1, 5, 90),
+                                                             (2, 37, 12, 8, 8, 3, 1, 1, 6, 90), (3, 128, 136, 12, 12, 3, 1, 1, 72, 576),
+                                                             (2, 20, 16, 9, 9, 3, 2, 1, 5, 45)])
 def test_gradients_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, pad, x, y):
     """Section 5.2.2: gradients of the product over the kept blocks (the data gradient for stride 1 only)."""
     print(f"blocks gradients {dtype} N={N} C={C} Cout={Cout} {H}x{W} k={k} s={stride} p={pad} x={x} y={y}", flush=True)
