@@ -273,7 +273,10 @@ size_t ard_lstm_status_offset(int32_t dtype, int32_t T, int32_t B, int32_t I, in
  * Back-propagation through time with the same pattern.  dh[T,B,H] (dtype) is the
  * gradient arriving on every h_t; h, c, gates are ard_lstm_fwd's outputs.
  * Writes dx[T,B,I] (dtype) and dW[4H x (I+H)] (dtype; zero outside kept gate rows
- * x ([x] + kept recurrent columns)).
+ * x ([x] + kept recurrent columns)).  bf16 layers whose backward exchange (the gate gradient
+ * of a step, read by every unit slice) is small enough run this recurrence in one launch as
+ * well, with the same bounded wait and the same status word as ard_lstm_fwd (a layer may take
+ * the one-launch form forward and the launch-per-step form backward; the word then stays 0).
  */
 int32_t ard_lstm_bwd(int32_t dtype, int32_t T, int32_t B, int32_t I, int32_t H,
                      const void* x, const void* W, const ard_pattern* pat,

@@ -397,6 +397,197 @@ __global__ __launch_bounds__(256) void lstm_persist_fwd_kernel(const LstmPersist
   }
 }
 
+// ---- the backward recurrence in one launch ------------------------------------------------------
+//
+// Back-propagation through time has the same shape of problem: step t needs dG_{t+1} . Wh', the gradient
+// that reaches h_t through the recurrence -- a contraction over all 4Hp gate rows (four times the forward
+// one) for Hp outputs.  Workgroup (s, bb) owns UW kept units (16 or 32: their columns of Wh' are staged
+// once in LDS, transposed) and MB = 16 * TM16 batch rows.  Per step it multiplies dG_{t+1}[rows, :] by its
+// columns (16x16x32 MFMAs, the contraction dealt over the four wavefronts and summed through LDS), adds the
+// gradient arriving at the output, runs the cell's backward for its (row, unit) pairs (the cell-state
+// gradient stays in registers) and writes its 4 x UW columns of dG_t, which is the result and also what
+// the other workgroups of the batch block wait for.  What a workgroup reads per step is MB x 4Hp values
+// whatever UW is, so few rows per workgroup (and many workgroups) keep the step short.  Flags, scopes and
+// the bounded wait are those of the forward kernel.
+struct LstmPersistBwd {
+  const float* gates;   // [T][B][4H]
+  const float* c;       // [T][B][H]
+  const uint16_t* dh;   // [T][B][H] gradient arriving at the outputs
+  const uint16_t* Wh;   // [4Hp][Hp] compact recurrent weight
+  uint16_t* dG;         // [T][B][4Hp] compact gate gradients
+  int* counters;        // flags[batch block][unit slice] = steps posted by that workgroup, zero at launch
+  int* err;             // zero at launch; 1: the recurrence gave up
+  int T, B, H, Hk, Hp, S, UW;
+  int off, step;        // kept unit j is physical unit off + j * step
+  long spin_limit;
+};
+
+template <int TM16, bool VIA_L2>
+__global__ __launch_bounds__(256) void lstm_persist_bwd_kernel(const LstmPersistBwd P) {
+  constexpr int MB = 16 * TM16;
+  constexpr int NPMAX = 2 * TM16;  // (row, unit) pairs of a thread when UW = 32
+  extern __shared__ uint4 lp_lds[];
+  __shared__ int go_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int s = blockIdx.x % P.S, bb = blockIdx.x / P.S;
+  const int Hp = P.Hp, B = P.B, H = P.H, UW = P.UW, K = 4 * Hp;
+  const int pitch = K * 2 + 64;  // bytes between the staged columns (64 bytes apart in the banks)
+  const int RW = UW + 1;
+  char* wl = reinterpret_cast<char*>(lp_lds);
+  float* red = reinterpret_cast<float*>(wl + UW * pitch);  // [4][MB][RW]
+  // this workgroup's UW columns of Wh', wl[local unit][gate row], staged once
+  // (a row of Wh' is read in 16-byte pieces of 8 units: Hp and UW are multiples of 8)
+  const int cpr = UW >> 3;
+  for (int i = tid; i < K * cpr; i += 256) {
+    const int k = i / cpr, x0 = (i - k * cpr) * 8;
+    const int jj = s * UW + x0;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (jj < Hp) v = *reinterpret_cast<const uint4*>(P.Wh + (long)k * Hp + jj);
+    const unsigned w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      *reinterpret_cast<uint16_t*>(wl + (x0 + e) * pitch + k * 2) = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+  }
+  __syncthreads();
+  const int nslice = K >> 5;  // 32-deep slices (4Hp is a multiple of 32: no partial slice)
+  const int nct = UW >> 4;    // 16-unit column tiles
+  // cell: thread = (local unit ul, rows r0, r0 + rstep, ...)
+  const int ul = tid % UW, r0 = tid / UW, rstep = 256 / UW, np = MB / rstep;
+  const int j = s * UW + ul;  // compact unit
+  const bool kept = j < P.Hk, in_store = j < Hp;
+  const int u = kept ? P.off + j * P.step : 0;  // physical unit
+  float dc_next[NPMAX];
+#pragma unroll
+  for (int i = 0; i < NPMAX; ++i) dc_next[i] = 0.0f;
+  for (int tt = 0; tt < P.T; ++tt) {
+    const int t = P.T - 1 - tt;
+    // what the cell needs of the forward pass does not depend on the other workgroups: fetched before the wait
+    float gi[NPMAX], gf[NPMAX], gg[NPMAX], go[NPMAX], ct[NPMAX], cp[NPMAX], dhe[NPMAX];
+#pragma unroll
+    for (int i = 0; i < NPMAX; ++i) {
+      gi[i] = gf[i] = gg[i] = go[i] = ct[i] = cp[i] = dhe[i] = 0.0f;
+      const int row = bb * MB + r0 + i * rstep;
+      if (i < np && row < B && kept) {
+        const float* ga = P.gates + ((long)t * B + row) * 4 * H;
+        gi[i] = ga[u], gf[i] = ga[H + u], gg[i] = ga[2 * H + u], go[i] = ga[3 * H + u];
+        ct[i] = P.c[((long)t * B + row) * H + u];
+        if (t > 0) cp[i] = P.c[((long)(t - 1) * B + row) * H + u];
+        dhe[i] = bf16_bits_to_f32(P.dh[((long)t * B + row) * H + u]);
+      }
+    }
+    f32x4_t acc[TM16][2];
+#pragma unroll
+    for (int rt = 0; rt < TM16; ++rt)
+#pragma unroll
+      for (int cti = 0; cti < 2; ++cti)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[rt][cti][v] = 0.0f;
+    if (tt > 0) {
+      if (wave == 0) {
+        // every workgroup of this batch block has posted dG_{t+1}
+        const int* flags = P.counters + (long)bb * P.S;
+        long spins = 0;
+        int ok = 1;
+        for (;;) {
+          bool ready = true;
+          for (int i = lane; i < P.S; i += 64) ready = ready && __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= tt;
+          if (__all(ready) && P.spin_limit >= 0) break;  // (a negative bound forces the give-up path)
+          if (++spins > P.spin_limit || __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+            __hip_atomic_store(P.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = 0;
+            break;
+          }
+        }
+        if (lane == 0) go_s = ok;
+        if (VIA_L2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+      __syncthreads();
+      if (!go_s) return;  // uniform: every thread of the workgroup leaves
+      const uint16_t* gsrc = P.dG + (long)(t + 1) * B * K;
+      const int kgrp = lane >> 4, n = lane & 15;
+      constexpr int CH = 16 / TM16;  // slices whose loads a wavefront issues together
+      for (int q0 = wave; q0 < nslice; q0 += 4 * CH) {
+        uint4 av[CH][TM16];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          const int q = q0 + 4 * i;
+          const int kc = q < nslice ? q * 32 + kgrp * 8 : 0;  // (clamped: the value is discarded below)
+#pragma unroll
+          for (int rt = 0; rt < TM16; ++rt) {
+            int row = bb * MB + rt * 16 + n;
+            row = row < B ? row : B - 1;  // rows beyond the batch are never stored
+            const uint16_t* src = gsrc + (long)row * K + kc;
+            if (VIA_L2) {
+              av[i][rt] = *reinterpret_cast<const uint4*>(src);
+            } else {
+              const unsigned long long* s8 = reinterpret_cast<const unsigned long long*>(src);
+              const unsigned long long lo = __hip_atomic_load(s8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              const unsigned long long hi = __hip_atomic_load(s8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              av[i][rt] = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          const int q = q0 + 4 * i;
+          if (q >= nslice) break;
+          const int kk = q * 32 + kgrp * 8;
+#pragma unroll
+          for (int cti = 0; cti < 2; ++cti) {
+            if (cti >= nct) break;  // (uniform)
+            const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wl + (cti * 16 + n) * pitch + kk * 2));
+#pragma unroll
+            for (int rt = 0; rt < TM16; ++rt)
+              acc[rt][cti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[i][rt]), bfrag, acc[rt][cti], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // partial tiles of the four wavefronts -> LDS: lane holds column (lane & 15) of a tile, rows 4*(lane>>4) + v
+#pragma unroll
+    for (int rt = 0; rt < TM16; ++rt)
+#pragma unroll
+      for (int cti = 0; cti < 2; ++cti) {
+        if (cti >= nct) break;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          red[(wave * MB + rt * 16 + 4 * (lane >> 4) + v) * RW + cti * 16 + (lane & 15)] = acc[rt][cti][v];
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NPMAX; ++i) {
+      if (i >= np) break;  // (uniform)
+      const int rl = r0 + i * rstep, row = bb * MB + rl;
+      float d[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (row < B && kept) {
+        const float dh = dhe[i] + ((red[(0 * MB + rl) * RW + ul] + red[(1 * MB + rl) * RW + ul]) +
+                                   (red[(2 * MB + rl) * RW + ul] + red[(3 * MB + rl) * RW + ul]));
+        const float tc = tanhf(ct[i]);
+        const float dc = dh * go[i] * (1.0f - tc * tc) + dc_next[i];
+        d[0] = dc * gg[i] * gi[i] * (1.0f - gi[i]);
+        d[1] = dc * cp[i] * gf[i] * (1.0f - gf[i]);
+        d[2] = dc * gi[i] * (1.0f - gg[i] * gg[i]);
+        d[3] = dh * tc * go[i] * (1.0f - go[i]);
+        dc_next[i] = dc * gf[i];
+      }
+      // dG_t: pairs of adjacent units as one word, device-scope stores (the padding units store their zeros)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const unsigned bits = f32_to_bf16_bits(d[g]);
+        const unsigned other = (unsigned)__shfl_xor((int)bits, 1, 64);
+        if (!(ul & 1) && row < B && in_store)
+          __hip_atomic_store(reinterpret_cast<unsigned*>(P.dG + ((long)t * B + row) * K + g * Hp + j), bits | (other << 16),
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    // every thread's stores have completed before the workgroup signals
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0 && tt + 1 < P.T)
+      __hip_atomic_store(&P.counters[(long)bb * P.S + s], tt + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 __global__ void lstm_zero_ints_kernel(int* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -581,6 +772,33 @@ static bool lstm_persist_plan(const LstmArgs& a, PersistPlan& p) {
   return traffic_ok && p.lds <= 160 * 1024 - 1024;
 }
 
+struct PersistBwdPlan {
+  int tm16, S, nbb, UW, via_l2;
+  size_t lds;
+};
+// The backward recurrence in one launch.  Every unit slice reads the whole dG_{t+1} of its batch rows:
+// S * B * 4Hp * 2 bytes per step over the chip, MB * 4Hp * 2 per workgroup.
+static bool lstm_persist_bwd_plan(const LstmArgs& a, PersistBwdPlan& p) {
+  const int Hp = pad8(a.Hk);
+  if (a.dtype != ARD_BF16 || a.Hk <= 0 || a.T <= 1 || a.ax.kind != AX_AFFINE || getenv("ARD_NO_PERSIST")) return false;
+  const int cus = lstm_cu_count();
+  // Few rows and narrow slices first (most workgroups): at B = 128 with 512 kept units, per step of the whole
+  // backward pass, 16 rows x 16 units (256 workgroups) 8.9 us, 16 x 32 10.4, 32 x 16 11.2, 32 x 32 13.6;
+  // a launch per step 15.5.
+  for (int tm = 1; tm <= 4; tm *= 2)
+    for (int uw = 16; uw <= 32; uw *= 2) {
+      const size_t lds = (size_t)uw * (8 * Hp + 64) + (size_t)4 * 16 * tm * (uw + 1) * 4;
+      const int S = ceil_div(Hp, uw), nbb = ceil_div(a.B, 16 * tm);
+      if (lds > 160 * 1024 - 1024 || (long)S * nbb > cus) continue;
+      const long traffic = (long)S * a.B * 4 * Hp * 2;
+      if (traffic > (40L << 20)) continue;
+      // device-scope loads up to the volume they were measured best at (16 MB: 8.9 against 9.5 us through L2)
+      p = PersistBwdPlan{tm, S, nbb, uw, traffic > (20L << 20), lds};
+      return true;
+    }
+  return false;
+}
+
 template <typename T>
 static int32_t lstm_fwd_t(const LstmArgs& a, const void* x, const void* W, void* h, float* c, float* gates,
                           const LstmWs& w, hipStream_t stream) {
@@ -675,7 +893,29 @@ static int32_t lstm_bwd_t(const LstmArgs& a, const void* x, const void* W, const
   dim3 cgrid(ceil_div(H + (Hp - Hk), 256), B);
   const float* dh_src = nullptr;  // dh_t[kept] from the product of step t+1: partial sums or w.dh_next
   int dh_splits = 0;
-  for (int t = T_ - 1; t >= 0; --t) {
+  PersistBwdPlan bp;
+  const bool one_launch = std::is_same<T, uint16_t>::value && lstm_persist_bwd_plan(a, bp);
+  if (one_launch) {
+    const long spin_limit = getenv("ARD_LSTM_SPIN_LIMIT") ? atol(getenv("ARD_LSTM_SPIN_LIMIT")) : 4000000L;
+    LstmPersistBwd P{gates, c, (const uint16_t*)dh, (const uint16_t*)w.whc, (uint16_t*)dG, w.sync + 1, w.sync, T_, B, H, Hk, Hp,
+                     bp.S, bp.UW, a.ax.off, a.ax.step, spin_limit};
+    ARD_LAUNCH(lstm_zero_ints_kernel, dim3(ceil_div(bp.S * bp.nbb + 1, 256)), dim3(256), 0, stream, w.sync, bp.S * bp.nbb + 1);
+    ARD_LAUNCH_CHECK("lstm_zero_ints_kernel");
+    const dim3 grid((unsigned)(bp.S * bp.nbb));
+    const size_t lds = bp.lds;
+    auto launch = [&](auto kernel) -> int32_t {
+      if (lds > 65536) ARD_HIP_CHECK(raise_lds_limit((const void*)kernel, (int)lds));
+      ARD_LAUNCH_NAMED("lstm_persist_bwd_kernel", kernel, grid, dim3(256), lds, stream, P);
+      return ARD_OK;
+    };
+    if (bp.via_l2) st = bp.tm16 == 1 ? launch(lstm_persist_bwd_kernel<1, true>) : bp.tm16 == 2 ? launch(lstm_persist_bwd_kernel<2, true>)
+                                                                                              : launch(lstm_persist_bwd_kernel<4, true>);
+    else st = bp.tm16 == 1 ? launch(lstm_persist_bwd_kernel<1, false>) : bp.tm16 == 2 ? launch(lstm_persist_bwd_kernel<2, false>)
+                                                                                    : launch(lstm_persist_bwd_kernel<4, false>);
+    if (st) return st;
+    ARD_LAUNCH_CHECK("lstm_persist_bwd_kernel");
+  }
+  for (int t = one_launch ? -1 : T_ - 1; t >= 0; --t) {
     T* dGt = dG + (long)t * B * 4 * Hp;
     ARD_LAUNCH(lstm_cell_bwd_kernel<T>, cgrid, dim3(256), 0, stream, gates + (long)t * B * 4 * H,
                        c + (long)t * B * H, t > 0 ? c + (long)(t - 1) * B * H : (const float*)nullptr,

@@ -53,6 +53,37 @@ def test_lstm_row_pattern_parity(dtype, T, B, I, H, dp, b):
            f"lstm {dtype}")
 
 
+def test_lstm_row_pattern_parity_with_a_launch_per_step():
+    """The same layer with the one-launch recurrences switched off (bf16 otherwise always takes them)."""
+    import os
+    dtype, T, B, I, H, dp, b = "bf16", 6, 33, 72, 136, 2, 1
+    rng = np.random.default_rng(606)
+    x = stored(rng.standard_normal((T, B, I)), dtype)
+    W = stored(rng.uniform(-0.3, 0.3, (4 * H, I + H)), dtype)
+    dh = stored(rng.standard_normal((T, B, H)), dtype)
+    os.environ["ARD_NO_PERSIST"] = "1"
+    try:
+        assert ard.lstm_status_offset(ard.BF16, T, B, I, H, ard.Pattern.row(dp, b)) is None
+        _check(dtype, x, W, dh, P.row_mask(H, dp, b), ard.Pattern.row(dp, b), from_vals(x, dtype), from_vals(W, dtype),
+               from_vals(dh, dtype), "lstm bf16 launch per step")
+    finally:
+        del os.environ["ARD_NO_PERSIST"]
+
+
+@pytest.mark.parametrize("T,B,I,H,dp,b", [(7, 50, 64, 256, 2, 2), (5, 128, 32, 384, 3, 1), (4, 20, 40, 96, 1, 1), (9, 16, 24, 40, 5, 3)])
+def test_lstm_backward_recurrence_in_one_launch_shapes(T, B, I, H, dp, b):
+    """Shapes that exercise the backward kernel's tiling: 16- and 32-row tiles, ragged batch blocks, unit slices
+    that end inside the padding, a single slice."""
+    print(f"lstm bwd one-launch case T={T} B={B} I={I} H={H} dp={dp} b={b}", flush=True)
+    dtype = "bf16"
+    rng = np.random.default_rng(T * 31 + H)
+    x = stored(rng.standard_normal((T, B, I)), dtype)
+    W = stored(rng.uniform(-0.08, 0.08, (4 * H, I + H)), dtype)
+    dh = stored(rng.standard_normal((T, B, H)), dtype)
+    _check(dtype, x, W, dh, P.row_mask(H, dp, b), ard.Pattern.row(dp, b), from_vals(x, dtype), from_vals(W, dtype),
+           from_vals(dh, dtype), "lstm bf16 one launch")
+
+
 def test_lstm_list_pattern_parity():
     dtype, T, B, I, H = "bf16", 4, 16, 32, 48
     rng = np.random.default_rng(77)
