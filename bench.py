@@ -41,9 +41,9 @@ REPEATS = 5              # the block of `steps` timed iterations is repeated; me
 # runs of `bench.py --only-call NAME` (scaled by what the same counters read for a plain copy); the
 # summaries, with their commands, are the files named here.  None: not measured.
 TRAFFIC = {
-    "L2.bwd_weight": (14958636, "profiles/hbm_traffic_L2_bwd_weight.txt"),
-    "C3.fwd.dp2": (151159374, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
-    "C5.fwd": (108080733, "profiles/hbm_traffic_config5_conv_fwd.txt"),
+    "L2.bwd_weight": (14958593, "profiles/hbm_traffic_L2_bwd_weight.txt"),
+    "C3.fwd.dp2": (151154572, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
+    "C5.fwd": (108283919, "profiles/hbm_traffic_config5_conv_fwd.txt"),
 }
 
 
