@@ -673,7 +673,7 @@ def extra_conv(ard, torch, rooflines):
                                           fwd_speedup_with_prediction=round(dense_fwd / (t_fwd + t_pred + t_pat), 3))
     # the block-based pattern of Section 5.2.2 on the same layer: blocks of 112 output positions (four rows) by one
     # 64-channel group over all taps, balanced groups; the forward pass skips the dropped blocks, the gradients run
-    # the ordinary passes once per column block on a copy of dY with that block's dropped bands zeroed
+    # the ordinary passes once per column block on a dY whose positions in that block's dropped bands are zeroed
     x, by = 112, 576
     predb = ard.sens_predict(A, (3, 3), 1, 1, x, by, 300, 500, 0.5, 5, 0)
     bp = ard.sens_block_pattern(predb, 1, 0.3, 0.7, 5, 0)
@@ -689,7 +689,7 @@ def extra_conv(ard, torch, rooflines):
                                             fwd_speedup_vs_all_blocks=round(dense_fwd / t_bfwd, 3),
                                             fwd_speedup_with_prediction=round(dense_fwd / (t_bfwd + t_predb + t_bpat), 3),
                                             bwd_data_plus_weight_us=round(t_bbwd, 1), blocks="112 x 576",
-                                            bwd_passes="one ordinary pass per column block on a masked copy of dY (no work skipped)")
+                                            bwd_passes="one ordinary pass per column block, dY masked while it is copied into its grid (no work skipped)")
     Ag, Wg = A.clone().requires_grad_(True), Wt.clone().requires_grad_(True)
     Y = F.conv2d(Ag, Wg, padding=1)
     res["vendor_dense_us"] = dict(fwd=round(event_us(torch, lambda: F.conv2d(A, Wt, padding=1))["median"], 1),

@@ -612,10 +612,20 @@ __global__ void rank_from_keep_kernel(const int* keep, int n_keep, int C, int* r
 
 __host__ __device__ static inline int pad64(int n) { return (n + 63) & ~63; }
 
+// Optional mask of the copy (gradients under a block pattern, Section 5.2.2): source pixel p of image n is
+// copied iff blk[(n * RB + p / x) * CB + cb] != 0, else it becomes zeros.  blk == NULL: everything is copied.
+struct BandMask {
+  const uint8_t* blk;
+  int RB, CB, cb, x;
+};
+__device__ __forceinline__ bool band_kept(const BandMask& m, int n, int p) {
+  return !m.blk || m.blk[((long)n * m.RB + p / m.x) * m.CB + m.cb] != 0;
+}
+
 // dst tile of 64 grid pixels x 64 channels per workgroup: read along pixels, write along channels
 __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                       int Ws, int Hg, int Wg, int oh, int ow, int Cp, long n_pix_valid,
-                                                      long n_pix_total, uint16_t* dst) {
+                                                      long n_pix_total, BandMask bm, uint16_t* dst) {
   __shared__ uint16_t tile[64][66];
   const long p0 = (long)blockIdx.x * 64;
   const int c0 = blockIdx.y * 64;
@@ -627,7 +637,7 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
     if (p < n_pix_valid) {
       const int n = (int)(p / ((long)Hg * Wg)), rem = (int)(p - (long)n * Hg * Wg);
       const int h = rem / Wg - oh, w = rem % Wg - ow;
-      if (h >= 0 && h < Hs && w >= 0 && w < Ws) off = ((long)n * Cs * Hs + h) * Ws + w;
+      if (h >= 0 && h < Hs && w >= 0 && w < Ws && band_kept(bm, n, h * Ws + w)) off = ((long)n * Cs * Hs + h) * Ws + w;
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -657,7 +667,7 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
 // that every workgroup also runs over its share [zb, ze) of the grid's pixels.
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                           int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
-                                                          long n_pix_total, uint16_t* dst) {
+                                                          long n_pix_total, BandMask bm, uint16_t* dst) {
   __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
   const int HW = Hs * Ws;
   const int px_tiles = (HW + 63) / 64;
@@ -671,6 +681,13 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     const int c = c0 + cl, p = p0 + q * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (c < n_chan && p < HW) v = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
+    if (bm.blk && p < HW) {
+      uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (!band_kept(bm, n, p + e)) w4[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+      v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    }
     *reinterpret_cast<uint4*>(&tile[cl][q * 8]) = v;
   }
   __syncthreads();
@@ -829,6 +846,7 @@ struct ConvArgs {
   const uint8_t* blk;
   int32_t bx, by;
   int32_t kept_only;  // gradients: write the kept channels' part of the output only (the caller covers the rest)
+  BandMask dy_mask;   // gradients on the channels-last grids: positions of dY that count (blk == NULL: all)
 };
 
 struct ConvWs {
@@ -937,18 +955,18 @@ static int conv_grid_splits(const ConvArgs& a) {
 static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
-                       int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream) {
+                       int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     dim3 grid((unsigned)(N * ceil_div(Hs * Ws, 64)), (unsigned)(Cp / 64));
     ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, dst);
+                       Wg, oh, ow, Cp, N, total, bm, dst);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
-                     ow, Cp, valid, total, dst);
+                     ow, Cp, valid, total, bm, dst);
   ARD_LAUNCH_CHECK("to_grid_kernel");
   return ARD_OK;
 }
@@ -1167,7 +1185,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     const int Cp = pad64(a.Cout), Hg = a.Ho + 2 * ph, Wg = a.Wo + 2 * pw, K = taps * Cp;
     int32_t st = ARD_OK;
     if (!(a.reuse & ARD_CONV_REUSE_DY))
-      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream);
+      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream, a.dy_mask);
     if (st) return st;
     const long total = (long)Ck * K;
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
@@ -1193,7 +1211,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   const int ph = same ? a.kh - 1 - a.pad : 0, pw = same ? a.kw - 1 - a.pad : 0;
   const long y_shift = (long)ph * Wg + pw;  // pixels between the bordered grid's origin and dY(., 0, 0)
   if (!(a.reuse & ARD_CONV_REUSE_DY))
-    st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cpy, margin, w.grid_y, stream);
+    st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cpy, margin, w.grid_y, stream, a.dy_mask);
   if (st) return st;
   const int Kq = a.N * Hg * Wg, Nn = taps * Cpa;
   FastParams F{};
@@ -1522,16 +1540,22 @@ extern "C" int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, i
       g.blk = nullptr;
       g.kept_only = 1;
       g.n_keep = (cb + 1) * cpb <= C ? cpb : C - cb * cpb;
-      if (dtype == ARD_BF16)
-        ARD_LAUNCH(mask_bands_kernel<uint16_t>, dim3(Cout, N), dim3(256), 0, s, (const uint16_t*)dYin, d_block_keep, RB, CB, cb, a.bx,
-                   Cout, a.Ho * a.Wo, (uint16_t*)w.dy_rows);
-      else
-        ARD_LAUNCH(mask_bands_kernel<float>, dim3(Cout, N), dim3(256), 0, s, (const float*)dYin, d_block_keep, RB, CB, cb, a.bx, Cout,
-                   a.Ho * a.Wo, (float*)w.dy_rows);
-      ARD_LAUNCH_CHECK("mask_bands_kernel");
-      st = dtype == ARD_BF16
-               ? conv_run<uint16_t>(g, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s)
-               : conv_run<float>(g, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s);
+      const void* dy_use = w.dy_rows;
+      if (w.grid_a && !dev_knobs().no_fast) {
+        // the pass copies dY into a channels-last grid anyway: that copy applies the mask
+        g.dy_mask = BandMask{d_block_keep, RB, CB, cb, a.bx};
+        dy_use = dYin;
+      } else {
+        if (dtype == ARD_BF16)
+          ARD_LAUNCH(mask_bands_kernel<uint16_t>, dim3(Cout, N), dim3(256), 0, s, (const uint16_t*)dYin, d_block_keep, RB, CB, cb,
+                     a.bx, Cout, a.Ho * a.Wo, (uint16_t*)w.dy_rows);
+        else
+          ARD_LAUNCH(mask_bands_kernel<float>, dim3(Cout, N), dim3(256), 0, s, (const float*)dYin, d_block_keep, RB, CB, cb, a.bx,
+                     Cout, a.Ho * a.Wo, (float*)w.dy_rows);
+        ARD_LAUNCH_CHECK("mask_bands_kernel");
+      }
+      st = dtype == ARD_BF16 ? conv_run<uint16_t>(g, 0.0, A, Wt, dy_use, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s)
+                             : conv_run<float>(g, 0.0, A, Wt, dy_use, out, nullptr, w.all_chan + cb * cpb, nullptr, nullptr, w, s);
       if (st) return st;
     }
     return ARD_OK;
