@@ -167,9 +167,12 @@ __global__ __launch_bounds__(256) void sens_predict_lut_kernel(const T* A, SensG
 // made the pass take 460 us) where the copy is a few coalesced 16-byte loads per thread.  Same draws, same
 // elements, same counts.  Needs planes that are whole numbers of 16-byte pieces (then every channel's run
 // starts at the same offset within a piece) and a footprint that fits the LDS; the host checks both.
+// Neighbouring row bands touch nearly the same input rows (bands of 8 positions: 4 rows each, 98 bands of a
+// 28 x 28 image would copy it 14 times over), so a workgroup takes G consecutive bands on one copy.
 struct SensStage {
-  int nrow_max, chp;  // input rows a region can touch; elements reserved per channel (a multiple of the piece)
+  int nrow_max, chp;  // input rows a workgroup's bands can touch; elements reserved per channel (a multiple of the piece)
   FastDiv div_taps, div_kw, div_wo;
+  int G, RBG;         // consecutive row bands (of one image and column block) per workgroup; groups per image
 };
 template <typename T>
 __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, SensGeom g, SensStage sg, int k_permille,
@@ -178,13 +181,11 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
   constexpr int CE = ElemTraits<T>::CE;  // elements per 16-byte piece
   extern __shared__ uint4 sens_stage_lds[];
   __shared__ int wave_cnt[4];
-  const int region = blockIdx.x;  // (image * RB + rb) * CB + cb
-  const int cb = region % g.CB, rb = (region / g.CB) % g.RB, n = region / (g.CB * g.RB);
-  const int r0 = rb * g.x, q0 = cb * g.y;
-  const int h = min(g.x, g.rows - r0), w = min(g.y, g.cols - q0);
-  const int size = h * w;
-  int s = (int)(((long)k_permille * size) / 1000);
-  if (s < 1) s = 1;
+  // workgroup = (image, group of G row bands, column block)
+  const int cb = blockIdx.x % g.CB, rbg = (blockIdx.x / g.CB) % sg.RBG, n = blockIdx.x / (g.CB * sg.RBG);
+  const int rb_first = rbg * sg.G, nb = min(sg.G, g.RB - rb_first);
+  const int r0 = rb_first * g.x, q0 = cb * g.y;
+  const int h = min(nb * g.x, g.rows - r0), w = min(g.y, g.cols - q0);  // rows of the group, columns of the block
   const int taps = g.KH * g.KW;
   // footprint: channels [ch_lo, ch_hi], input rows [ih_lo, ih_hi] (clipped to the image), all columns
   const int ch_lo = q0 / taps, ch_hi = (q0 + w - 1) / taps;
@@ -217,25 +218,34 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
     row_lut[i] = (oh * g.stride) | ((ow * g.stride) << 16);
   }
   __syncthreads();
-  int c = 0;
-  for (int j = threadIdx.x; j < s; j += 256) {
-    const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
-    const uint32_t e = (uint32_t)(((uint64_t)u * (uint64_t)size) >> 32);
-    const uint32_t r = fdiv(e, div_w), q = e - r * (uint32_t)w;
-    const int ci = col_lut[q], ri = row_lut[r];
-    const int ih = (ri & 0xffff) + ((ci >> 24) & 15) - g.pad, iw = (ri >> 16) + ((ci >> 28) & 15) - g.pad;
-    float v = 0.0f;  // the zero border of the input matrix
-    if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(stage[(ci & 0xffffff) + off + (ih - ih_lo) * g.W + iw]);
-    c += v > thr ? 1 : 0;
-  }
-  for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
-  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int tot = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-    count[region] = tot;
-    samples[region] = s;
-    sens[region] = (1000L * tot >= (long)t_permille * s) ? 1 : 0;
+  for (int gi = 0; gi < nb; ++gi) {
+    const int region = ((n * g.RB) + rb_first + gi) * g.CB + cb;
+    const int rr0 = gi * g.x;                   // first row of this band within the group
+    const int hb = min(g.x, h - rr0);
+    const int size = hb * w;
+    int s = (int)(((long)k_permille * size) / 1000);
+    if (s < 1) s = 1;
+    int c = 0;
+    for (int j = threadIdx.x; j < s; j += 256) {
+      const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
+      const uint32_t e = (uint32_t)(((uint64_t)u * (uint64_t)size) >> 32);
+      const uint32_t r = fdiv(e, div_w), q = e - r * (uint32_t)w;
+      const int ci = col_lut[q], ri = row_lut[rr0 + r];
+      const int ih = (ri & 0xffff) + ((ci >> 24) & 15) - g.pad, iw = (ri >> 16) + ((ci >> 28) & 15) - g.pad;
+      float v = 0.0f;  // the zero border of the input matrix
+      if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(stage[(ci & 0xffffff) + off + (ih - ih_lo) * g.W + iw]);
+      c += v > thr ? 1 : 0;
+    }
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
+    if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int tot = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+      count[region] = tot;
+      samples[region] = s;
+      sens[region] = (1000L * tot >= (long)t_permille * s) ? 1 : 0;
+    }
+    __syncthreads();  // (wave_cnt is reused by the next band)
   }
 }
 
@@ -403,25 +413,40 @@ extern "C" int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t
     const FastDiv dw = fast_div((uint32_t)g.y);
     // footprint of a region in LDS when it fits: rows a band can touch x whole width x channels of a block
     const int ce = dtype == ARD_BF16 ? 8 : 4, es = dtype == ARD_BF16 ? 2 : 4, taps = kh * kw;
-    const int oh_span = (g.x + g.Wo - 2) / g.Wo + 1;
-    const int nrow_max = imin(H, (oh_span - 1) * stride + kh);
-    const int chp = (int)align_up((size_t)(ce - 1 + nrow_max * Wd), (size_t)ce);
     const int nch_max = imin(C, (g.y + taps - 2) / taps + 1);
-    const size_t stage_bytes = (size_t)chp * nch_max * es + (size_t)(g.y + g.x) * sizeof(int);
+    // Bands per workgroup: the most whose common footprint leaves as many workgroups on a CU as one band's does
+    // (bands of 8 positions of a 28-wide image: three share the four input rows one of them touches) while the
+    // launch keeps two workgroups per CU.  Config-5 layer, 30 % sampled: rows of 8 positions 300 -> 224 us, of 4
+    // positions 447 -> 216 us, 8 x 64 blocks 908 -> 270 us; regions of 112 x 576 stay alone (113 us; two per
+    // workgroup 152 us: fewer resident workgroups).
+    int G = 1, nrow_max = 0, chp = 0, occ1 = 0;
+    size_t stage_bytes = 0;
+    for (int cand = 1; cand <= 16 && cand <= imax(1, g.RB); ++cand) {
+      const int oh_span = (cand * g.x + g.Wo - 2) / g.Wo + 1;
+      const int nr = imin(H, (oh_span - 1) * stride + kh);
+      const int cp = (int)align_up((size_t)(ce - 1 + nr * Wd), (size_t)ce);
+      const size_t bytes = (size_t)cp * nch_max * es + (size_t)(g.y + cand * g.x) * sizeof(int);
+      const int occ = (int)imin(8, (long)(160 * 1024 / (bytes + 512)));
+      if (cand == 1) occ1 = occ;
+      if (cand == 1 || (occ == occ1 && occ >= 1 && (long)N * ceil_div(g.RB, cand) * g.CB >= 512))
+        G = cand, nrow_max = nr, chp = cp, stage_bytes = bytes;
+    }
     // (pad < filter size: every window then starts inside the image, which the copy's bounds rely on)
     if (((H * Wd) % ce) == 0 && (((uintptr_t)A) & 15) == 0 && stage_bytes <= 150 * 1024 && (long)chp * nch_max < (1L << 24) &&
         pad < kh && pad < kw) {
-      const SensStage sg{nrow_max, chp, fast_div((uint32_t)taps), fast_div((uint32_t)kw), fast_div((uint32_t)g.Wo)};
+      const int RBG = ceil_div(g.RB, G);
+      const SensStage sg{nrow_max, chp, fast_div((uint32_t)taps), fast_div((uint32_t)kw), fast_div((uint32_t)g.Wo), G, RBG};
+      const unsigned groups = (unsigned)((long)N * RBG * g.CB);
       hipError_t e = hipSuccess;
       if (dtype == ARD_BF16) {
         if (stage_bytes > 65536) e = raise_lds_limit((const void*)sens_predict_staged_kernel<uint16_t>, (int)stage_bytes);
         if (e == hipSuccess)
-          ARD_LAUNCH(sens_predict_staged_kernel<uint16_t>, dim3(regions), dim3(256), stage_bytes, (hipStream_t)stream,
+          ARD_LAUNCH(sens_predict_staged_kernel<uint16_t>, dim3(groups), dim3(256), stage_bytes, (hipStream_t)stream,
                      (const uint16_t*)A, g, sg, k_permille, t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
       } else {
         if (stage_bytes > 65536) e = raise_lds_limit((const void*)sens_predict_staged_kernel<float>, (int)stage_bytes);
         if (e == hipSuccess)
-          ARD_LAUNCH(sens_predict_staged_kernel<float>, dim3(regions), dim3(256), stage_bytes, (hipStream_t)stream, (const float*)A, g,
+          ARD_LAUNCH(sens_predict_staged_kernel<float>, dim3(groups), dim3(256), stage_bytes, (hipStream_t)stream, (const float*)A, g,
                      sg, k_permille, t_permille, threshold, prefix, dw, d_count, d_samples, d_sens);
       }
       if (e != hipSuccess) return fail(ARD_EHIP, "raising the LDS limit failed: %s", hipGetErrorString(e));

@@ -42,6 +42,9 @@ def _predict_both(Av, Ad, k, stride, pad, x, y, kpm, tpm, thr, seed, it):
     (2, 6, 8, 12, 3, 1, 1, 5, 18, 500, 400),     # column blocks of two channels: footprint channels start above 0
     (2, 4, 8, 8, 3, 2, 1, 3, 0, 700, 300),       # strided
     (3, 8, 16, 8, 5, 1, 2, 40, 0, 200, 500),     # tall bands, 5x5 filter with two rows of padding
+    # enough regions for several bands to share one workgroup's copy of their footprint (3 and 7 per workgroup)
+    (8, 16, 28, 28, 3, 1, 1, 4, 0, 300, 500),
+    (4, 32, 14, 14, 3, 1, 1, 2, 32, 300, 500),
 ])
 def test_prediction_and_patterns_bit_exact(dtype, N, C, H, W, k, stride, pad, x, y, kpm, tpm):
     print(f"sensitivity case {dtype} N={N} C={C} {H}x{W} k={k} s={stride} p={pad} region {x}x{y} k={kpm} t={tpm}", flush=True)
