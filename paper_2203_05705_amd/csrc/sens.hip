@@ -226,6 +226,9 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
     int s = (int)(((long)k_permille * size) / 1000);
     if (s < 1) s = 1;
     int c = 0;
+    // (a footprint of tens of KB leaves two wavefronts per SIMD: four draws in flight per thread hide the
+    // table and LDS reads that occupancy does not)
+#pragma unroll 4
     for (int j = threadIdx.x; j < s; j += 256) {
       const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
       const uint32_t e = (uint32_t)(((uint64_t)u * (uint64_t)size) >> 32);
@@ -415,20 +418,21 @@ extern "C" int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t
     const int ce = dtype == ARD_BF16 ? 8 : 4, es = dtype == ARD_BF16 ? 2 : 4, taps = kh * kw;
     const int nch_max = imin(C, (g.y + taps - 2) / taps + 1);
     // Bands per workgroup: the most whose common footprint leaves as many workgroups on a CU as one band's does
-    // (bands of 8 positions of a 28-wide image: three share the four input rows one of them touches) while the
-    // launch keeps two workgroups per CU.  Config-5 layer, 30 % sampled: rows of 8 positions 300 -> 224 us, of 4
-    // positions 447 -> 216 us, 8 x 64 blocks 908 -> 270 us; regions of 112 x 576 stay alone (113 us; two per
+    // (bands of 8 positions of a 28-wide image: seven are two whole rows, the four input rows of one band) while the
+    // launch keeps two workgroups per CU.  Config-5 layer, 30 % sampled: rows of 8 positions 300 -> 185 us, of 4
+    // positions 447 -> 201 us, 8 x 64 blocks 908 -> 295 us; regions of 112 x 576 stay alone (108 us; two per
     // workgroup 152 us: fewer resident workgroups).
     int G = 1, nrow_max = 0, chp = 0, occ1 = 0;
     size_t stage_bytes = 0;
     for (int cand = 1; cand <= 16 && cand <= imax(1, g.RB); ++cand) {
-      const int oh_span = (cand * g.x + g.Wo - 2) / g.Wo + 1;
+      // output rows a group can span: groups of whole rows start on a row, any other may start anywhere in one
+      const int oh_span = (cand * g.x) % g.Wo == 0 ? cand * g.x / g.Wo : (cand * g.x + g.Wo - 2) / g.Wo + 1;
       const int nr = imin(H, (oh_span - 1) * stride + kh);
       const int cp = (int)align_up((size_t)(ce - 1 + nr * Wd), (size_t)ce);
       const size_t bytes = (size_t)cp * nch_max * es + (size_t)(g.y + cand * g.x) * sizeof(int);
       const int occ = (int)imin(8, (long)(160 * 1024 / (bytes + 512)));
       if (cand == 1) occ1 = occ;
-      if (cand == 1 || (occ == occ1 && occ >= 1 && (long)N * ceil_div(g.RB, cand) * g.CB >= 512))
+      if (cand == 1 || (occ >= occ1 && occ >= 1 && (long)N * ceil_div(g.RB, cand) * g.CB >= 512))
         G = cand, nrow_max = nr, chp = cp, stage_bytes = bytes;
     }
     // (pad < filter size: every window then starts inside the image, which the copy's bounds rely on)
