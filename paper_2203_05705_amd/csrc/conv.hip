@@ -660,6 +660,32 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
   }
 }
 
+// Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
+// data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
+struct PackJob {
+  const uint16_t* Wt;
+  const int* keep;
+  int C, taps, rows, inner, Cp, flip;
+  uint16_t* out;
+  int blocks;  // workgroups of 256 threads that cover rows * taps * Cp entries (0: no job)
+};
+__device__ __forceinline__ void pack_weights_body(const PackJob& j, long idx) {
+  const long total = (long)j.rows * j.taps * j.Cp;
+  if (idx >= total) return;
+  const int q = (int)(idx % j.Cp);
+  const int tap = (int)((idx / j.Cp) % j.taps);
+  const int r = (int)(idx / ((long)j.Cp * j.taps));
+  uint16_t v = 0;
+  if (q < j.inner)
+    v = j.flip ? j.Wt[((long)q * j.C + (j.keep ? j.keep[r] : r)) * j.taps + (j.taps - 1 - tap)]
+               : j.Wt[((long)r * j.C + (j.keep ? j.keep[q] : q)) * j.taps + tap];
+  j.out[idx] = v;
+}
+__global__ void pack_weights_grid_kernel(PackJob j) { pack_weights_body(j, (long)blockIdx.x * blockDim.x + threadIdx.x); }
+static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int rows, int inner, int Cp, int flip, uint16_t* out) {
+  return PackJob{(const uint16_t*)Wt, keep, C, taps, rows, inner, Cp, flip, out, (int)(((long)rows * taps * Cp + 255) / 256)};
+}
+
 // The same copy driven from the source side, for planes that are whole numbers of 16-byte pieces:
 // a workgroup reads 64 channels x 64 source pixels with 16-byte loads (8 pixels of one channel
 // each), transposes through LDS and writes each pixel's 64 channels as 128 contiguous bytes.
@@ -667,8 +693,14 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
 // that every workgroup also runs over its share [zb, ze) of the grid's pixels.
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                           int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
-                                                          long n_pix_total, BandMask bm, uint16_t* dst) {
+                                                          long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj, int main_x) {
   __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
+  // (workgroups beyond the copy's own pack the weights of the product that follows: an independent small job
+  // that would otherwise be a launch of its own)
+  if ((int)blockIdx.x >= main_x) {
+    if (blockIdx.y == 0) pack_weights_body(pj, (long)(blockIdx.x - main_x) * 256 + threadIdx.x);
+    return;
+  }
   const int HW = Hs * Ws;
   const int px_tiles = (HW + 63) / 64;
   const int n = blockIdx.x / px_tiles, p0 = (blockIdx.x - n * px_tiles) * 64;
@@ -704,7 +736,7 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     *reinterpret_cast<uint4*>(dst + g * Cp + c0 + c8) = make_uint4(o[0], o[1], o[2], o[3]);
   }
   // zero pass: this workgroup's share of the grid pixels, for its 64 channels
-  const long nblk = (long)gridDim.x, per = (n_pix_total + nblk - 1) / nblk;
+  const long nblk = (long)main_x, per = (n_pix_total + nblk - 1) / nblk;
   const long zb = blockIdx.x * per, ze = zb + per < n_pix_total ? zb + per : n_pix_total;
   const long valid = (long)N * Hg * Wg;
   for (long g = zb + (t >> 3); g < ze; g += 32) {
@@ -718,21 +750,6 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
   }
 }
 
-// Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
-// data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
-__global__ void pack_weights_grid_kernel(const uint16_t* Wt, const int* keep, int C, int taps, int rows, int inner, int Cp,
-                                         int flip, uint16_t* out) {
-  const long total = (long)rows * taps * Cp;
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int q = (int)(idx % Cp);
-  const int tap = (int)((idx / Cp) % taps);
-  const int r = (int)(idx / ((long)Cp * taps));
-  uint16_t v = 0;
-  if (q < inner)
-    v = flip ? Wt[((long)q * C + (keep ? keep[r] : r)) * taps + (taps - 1 - tap)] : Wt[((long)r * C + (keep ? keep[q] : q)) * taps + tap];
-  out[idx] = v;
-}
 
 // output positions of dropped rows of the input matrix to +0.0 (row-based sensitivity-aware pattern,
 // Section 5.2.1: the results of the kept rows fill the same rows of the output, the others are zero);
@@ -955,14 +972,20 @@ static int conv_grid_splits(const ConvArgs& a) {
 static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
-                       int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{}) {
+                       int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{},
+                       PackJob pj = PackJob{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
-    dim3 grid((unsigned)(N * ceil_div(Hs * Ws, 64)), (unsigned)(Cp / 64));
+    const int main_x = N * ceil_div(Hs * Ws, 64);
+    dim3 grid((unsigned)(main_x + pj.blocks), (unsigned)(Cp / 64));
     ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, bm, dst);
+                       Wg, oh, ow, Cp, N, total, bm, dst, pj, main_x);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
+  }
+  if (pj.blocks) {
+    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
+    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
@@ -1132,12 +1155,9 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   if (a.mode == ARD_CONV_FWD_ROWS) {
     // every channel, only the kept output positions: the product's columns are the listed pixels
     const int Cp = pad64(a.C), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
-    int32_t st = to_grid(A, nullptr, a.C, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream);
+    int32_t st = to_grid(A, nullptr, a.C, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{},
+                         pack_job(Wt, nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp));
     if (st) return st;
-    const long total = (long)a.Cout * K;
-    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, (const uint16_t*)Wt,
-               (const int*)nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp);
-    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
     ARD_LAUNCH(zero_dropped_pixels_kernel<uint16_t>, dim3(a.Cout, a.N), dim3(256), 0, stream, (uint16_t*)out, row_mask, a.Cout,
                a.Ho * a.Wo);
     ARD_LAUNCH_CHECK("zero_dropped_pixels_kernel");
@@ -1148,13 +1168,14 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   if (a.mode == ARD_CONV_FWD) {
     const int Cp = pad64(Ck), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
     int32_t st = ARD_OK;
-    if (!(a.reuse & ARD_CONV_REUSE_A))
-      st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream);
+    const PackJob pj = pack_job(Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
+    if (!(a.reuse & ARD_CONV_REUSE_A)) {
+      st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{}, pj);
+    } else {
+      ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
+      ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    }
     if (st) return st;
-    const long total = (long)a.Cout * K;
-    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
-    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
     if (a.blk) {
       const int bn = block_fast_tile(a, w);
       if (!bn) return fail(ARD_EUNSUPPORTED, "block pattern outside the fast path");  // (callers test block_fast_tile first)
@@ -1184,13 +1205,14 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     const int ph = a.kh - 1 - a.pad, pw = a.kw - 1 - a.pad;
     const int Cp = pad64(a.Cout), Hg = a.Ho + 2 * ph, Wg = a.Wo + 2 * pw, K = taps * Cp;
     int32_t st = ARD_OK;
-    if (!(a.reuse & ARD_CONV_REUSE_DY))
-      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream, a.dy_mask);
+    const PackJob pj = pack_job(Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
+    if (!(a.reuse & ARD_CONV_REUSE_DY)) {
+      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream, a.dy_mask, pj);
+    } else {
+      ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
+      ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+    }
     if (st) return st;
-    const long total = (long)Ck * K;
-    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       (const uint16_t*)Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
-    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
     if (Ck < a.C && !a.kept_only) {
       const int hw = a.H * a.W;
       ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, ceil_div(a.N, ZP_IMGS)), dim3(256), 0, stream, (uint16_t*)out,
