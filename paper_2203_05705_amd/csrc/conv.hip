@@ -660,6 +660,43 @@ __global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const
   }
 }
 
+// position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
+__device__ __forceinline__ int kept_rank(const int* keep, int n_keep, int c) {
+  int lo = 0, hi = n_keep - 1;
+  while (lo <= hi) {
+    const int mid = (lo + hi) >> 1, v = keep[mid];
+    if (v == c) return mid;
+    if (v < c) lo = mid + 1;
+    else hi = mid - 1;
+  }
+  return -1;
+}
+
+// planes of dropped channels of an NCHW tensor to +0.0 (the GEMM writes the kept ones); a workgroup
+// takes one channel of ZP_IMGS images, 16-byte stores where the planes allow them
+constexpr int ZP_IMGS = 8;
+struct ZeroPlanesJob {
+  uint16_t* dst;
+  const int* keep;
+  int n_keep, N, C, HW, vec;
+  int blocks;  // C * ceil(N / ZP_IMGS) workgroups of 256 threads (0: no job)
+};
+__device__ __forceinline__ void zero_dropped_planes_body(const ZeroPlanesJob& z, int block) {
+  const int c = block % z.C;
+  if (kept_rank(z.keep, z.n_keep, c) >= 0) return;
+  const int n0 = (block / z.C) * ZP_IMGS, n1 = min(n0 + ZP_IMGS, z.N);
+  if (z.vec) {
+    const int chunks = z.HW >> 3;
+    for (int i = threadIdx.x; i < (n1 - n0) * chunks; i += 256) {
+      const int n = n0 + i / chunks, q = i % chunks;
+      *reinterpret_cast<uint4*>(z.dst + ((long)n * z.C + c) * z.HW + q * 8) = make_uint4(0, 0, 0, 0);
+    }
+  } else {
+    for (int i = threadIdx.x; i < (n1 - n0) * z.HW; i += 256) z.dst[((long)(n0 + i / z.HW) * z.C + c) * z.HW + i % z.HW] = 0;
+  }
+}
+__global__ __launch_bounds__(256) void zero_dropped_planes_kernel(ZeroPlanesJob z) { zero_dropped_planes_body(z, (int)blockIdx.x); }
+
 // Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
 // data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
 struct PackJob {
@@ -693,12 +730,17 @@ static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int ro
 // that every workgroup also runs over its share [zb, ze) of the grid's pixels.
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                           int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
-                                                          long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj, int main_x) {
+                                                          long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj,
+                                                          ZeroPlanesJob zj, int main_x) {
   __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
-  // (workgroups beyond the copy's own pack the weights of the product that follows: an independent small job
-  // that would otherwise be a launch of its own)
+  // (workgroups beyond the copy's own pack the weights of the product that follows and zero the planes it will
+  // not write: independent small jobs that would otherwise be launches of their own)
   if ((int)blockIdx.x >= main_x) {
-    if (blockIdx.y == 0) pack_weights_body(pj, (long)(blockIdx.x - main_x) * 256 + threadIdx.x);
+    const int b = (int)blockIdx.x - main_x;
+    if (blockIdx.y == 0) {
+      if (b < pj.blocks) pack_weights_body(pj, (long)b * 256 + threadIdx.x);
+      else zero_dropped_planes_body(zj, b - pj.blocks);
+    }
     return;
   }
   const int HW = Hs * Ws;
@@ -785,37 +827,6 @@ __global__ __launch_bounds__(256) void mask_bands_kernel(const T* Y, const uint8
 __global__ void iota_kernel(int* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = i;
-}
-
-// position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
-__device__ __forceinline__ int kept_rank(const int* keep, int n_keep, int c) {
-  int lo = 0, hi = n_keep - 1;
-  while (lo <= hi) {
-    const int mid = (lo + hi) >> 1, v = keep[mid];
-    if (v == c) return mid;
-    if (v < c) lo = mid + 1;
-    else hi = mid - 1;
-  }
-  return -1;
-}
-
-// planes of dropped channels of an NCHW tensor to +0.0 (the GEMM writes the kept ones); a workgroup
-// takes one channel of ZP_IMGS images, 16-byte stores where the planes allow them
-constexpr int ZP_IMGS = 8;
-__global__ __launch_bounds__(256) void zero_dropped_planes_kernel(uint16_t* dst, const int* keep, int n_keep, int N, int C,
-                                                                  int HW, int vec) {
-  const int c = blockIdx.x;
-  if (kept_rank(keep, n_keep, c) >= 0) return;
-  const int n0 = blockIdx.y * ZP_IMGS, n1 = min(n0 + ZP_IMGS, N);
-  if (vec) {
-    const int chunks = HW >> 3;
-    for (int i = threadIdx.x; i < (n1 - n0) * chunks; i += 256) {
-      const int n = n0 + i / chunks, q = i % chunks;
-      *reinterpret_cast<uint4*>(dst + ((long)n * C + c) * HW + q * 8) = make_uint4(0, 0, 0, 0);
-    }
-  } else {
-    for (int i = threadIdx.x; i < (n1 - n0) * HW; i += 256) dst[((long)(n0 + i / HW) * C + c) * HW + i % HW] = 0;
-  }
 }
 
 // dW[co][c][tap] = sum over splits of part[sp][co][tap*Cp + rank(c)] (dropped channels: +0.0).
@@ -973,19 +984,23 @@ static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
                        int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{},
-                       PackJob pj = PackJob{}) {
+                       PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     const int main_x = N * ceil_div(Hs * Ws, 64);
-    dim3 grid((unsigned)(main_x + pj.blocks), (unsigned)(Cp / 64));
+    dim3 grid((unsigned)(main_x + pj.blocks + zj.blocks), (unsigned)(Cp / 64));
     ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, bm, dst, pj, main_x);
+                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, main_x);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }
   if (pj.blocks) {
     ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
     ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+  }
+  if (zj.blocks) {
+    ARD_LAUNCH(zero_dropped_planes_kernel, dim3((unsigned)zj.blocks), dim3(256), 0, stream, zj);
+    ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
@@ -1206,19 +1221,23 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     const int Cp = pad64(a.Cout), Hg = a.Ho + 2 * ph, Wg = a.Wo + 2 * pw, K = taps * Cp;
     int32_t st = ARD_OK;
     const PackJob pj = pack_job(Wt, (const int*)d_keep, a.C, taps, Ck, a.Cout, Cp, 1, w.gwp);
+    ZeroPlanesJob zj{};
+    if (Ck < a.C && !a.kept_only) {
+      const int hw = a.H * a.W;
+      zj = ZeroPlanesJob{(uint16_t*)out, (const int*)d_keep, Ck, a.N, a.C, hw, (int)((hw % 8) == 0 && al16c(out)),
+                         a.C * ceil_div(a.N, ZP_IMGS)};
+    }
     if (!(a.reuse & ARD_CONV_REUSE_DY)) {
-      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream, a.dy_mask, pj);
+      st = to_grid(dYin, nullptr, a.Cout, a.Cout, a.Ho, a.Wo, a.N, Hg, Wg, ph, pw, Cp, margin, w.grid_y, stream, a.dy_mask, pj, zj);
     } else {
       ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
       ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+      if (zj.blocks) {
+        ARD_LAUNCH(zero_dropped_planes_kernel, dim3((unsigned)zj.blocks), dim3(256), 0, stream, zj);
+        ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
+      }
     }
     if (st) return st;
-    if (Ck < a.C && !a.kept_only) {
-      const int hw = a.H * a.W;
-      ARD_LAUNCH(zero_dropped_planes_kernel, dim3(a.C, ceil_div(a.N, ZP_IMGS)), dim3(256), 0, stream, (uint16_t*)out,
-                 (const int*)d_keep, Ck, a.N, a.C, hw, (int)((hw % 8) == 0 && al16c(out)));
-      ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
-    }
     ConvMap cv{a.H * a.W, a.W, Hg * Wg, Wg, Cp, a.kw, a.N * a.H * a.W, a.C, (const int*)d_keep, Ck, nullptr, 0, -1};
     return conv_grid_gemm(w.gwp, Ck, K, w.grid_y, (long)a.N * Hg * Wg + margin, cv, out, stream);
   }
