@@ -1561,6 +1561,12 @@ extern "C" int32_t ard_conv_bwd_blocks(int32_t mode, int32_t dtype, int32_t N, i
   if (x < 1 || y < 0) return fail(ARD_EINVAL, "block size must be positive (y = 0: the whole width)");
   if (y == 0) a.by = C * kh * kw;
   if (!dYin || !d_block_keep || !out) return fail(ARD_EINVAL, "null pointer");
+  if (mode == ARD_CONV_BWD_WEIGHT && !A) return fail(ARD_EINVAL, "BWD_WEIGHT needs A");
+  if (mode == ARD_CONV_BWD_DATA) {
+    if (!Wt) return fail(ARD_EINVAL, "BWD_DATA needs Wt");
+    if (stride != 1) return fail(ARD_EUNSUPPORTED, "BWD_DATA is built for stride 1 only (got %d)", stride);
+    if (kh - 1 - pad < 0 || kw - 1 - pad < 0) return fail(ARD_EUNSUPPORTED, "BWD_DATA needs pad <= k-1");
+  }
   ConvWs w = conv_ws_layout((char*)ws, a);
   if (!ws || ws_bytes < w.total) return fail(ARD_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", w.total, ws_bytes);
   hipStream_t s = (hipStream_t)stream;

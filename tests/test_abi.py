@@ -100,8 +100,15 @@ def test_unsupported_requests_are_refused_before_any_launch():
         for dt in (D.BF16, D.F32):
             rc = D.conv_calls(lib, heap, dt, 2, 8, 12, 9, 9, 3, 2, 1, 4, modes=(2,))
             assert rc == [-6] and b"stride 1" in lib.ard_last_error()
+        # the same for the gradients under a block pattern (mode 2 = data gradient)
+        n = lib.ard_conv_workspace_bytes(D.BF16, 2, 8, 9, 9, 12, 3, 3, 2, 1)
+        bufs = [heap(1 << 20) for _ in range(5)]
+        rc = lib.ard_conv_bwd_blocks(2, D.BF16, 2, 8, 9, 9, 12, 3, 3, 2, 1, 5, 18, *bufs, heap(n), n, None)
+        assert rc == -6 and b"stride 1" in lib.ard_last_error()
+        assert lib.ard_conv_bwd_blocks(1, D.BF16, 2, 8, 9, 9, 12, 3, 3, 1, 1, 5, 18, *bufs, heap(n), n, None) == -1   # not a gradient mode
         assert D.launches(lib)[0] == 0
         # the neighbouring supported requests do launch
+        assert lib.ard_conv_bwd_blocks(3, D.BF16, 2, 8, 9, 9, 12, 3, 3, 2, 1, 5, 18, *bufs, heap(n), n, None) == 0
         assert D.layer_calls(lib, heap, D.BF16, 256, 256, 256, (2, 1), None, 0, tile=(32, 64)) == [0, 0, 0]
         assert D.conv_calls(lib, heap, D.BF16, 2, 8, 12, 9, 9, 3, 2, 1, 4, modes=(1, 3)) == [0, 0]
         assert D.launches(lib)[0] > 0
