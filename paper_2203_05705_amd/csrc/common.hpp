@@ -54,6 +54,10 @@ long extent_slack();  // elements the proofs pretend each operand is shorter by 
 // stage as ONE grid of a kernel that holds every such body (gemm.hip).  Stage 0: launches that depend on
 // nothing recorded in the batch; stage 1: passes that finish a stage-0 product of the same call.
 bool batch_open();
+// A call may open a batch of its own for kernels of its that do not depend on each other (then launches it
+// itself): only when the caller has none, open or suspended.  false: launch one by one.
+bool batch_self_begin();
+int32_t batch_self_end(bool ok, hipStream_t stream);
 // While one lives, this thread's launches are issued at once even inside an open batch: for kernels
 // whose consumer in the same call is recorded too, or issued at once, and must find their result.
 struct BatchSuspend {

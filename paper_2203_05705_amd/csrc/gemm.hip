@@ -293,6 +293,7 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     splits = 1;
     need = 0;
   }
+  bool self_batch = false;
   FastParams F{};
   F.A = (const uint16_t*)P.A.p;
   F.B = (const uint16_t*)P.B.p;
@@ -327,8 +328,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
                     (!C.relu_src || ((uintptr_t)C.relu_src & 15) == 0) && C.cn.nphys < (1 << 23);
     const int dropped_rows = C.rm.nphys - C.rm.n;
     if (C.rm.step > 1 && dropped_rows > 0) {
-      // dropped rows: their own pass over all CUs (recorded with the product in a grouped launch)
+      // dropped rows: their own pass over all CUs (recorded with the product in a grouped launch; a call that
+      // is not part of a caller's batch makes one of its own for the two)
       F.scatter_rows_only = 1;
+      self_batch = batch_self_begin();
       const ZeroRowsArgs za{(uint16_t*)C.p, (int)C.ld, C.rm.nphys, C.cn.nphys, C.rm.off, C.rm.step, C.rm.n, F.scatter_vec};
       const long pieces = (long)dropped_rows * (F.scatter_vec ? C.cn.nphys / 8 : C.cn.nphys);
       long gx = (pieces + 1023) / 1024;  // four stores per thread
@@ -337,6 +340,7 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
       hipError_t e = ard::launch_status();
       if (e != hipSuccess) {
         st = fail(ARD_EHIP, "launch of zero_rows_kernel failed: %s", hipGetErrorString(e));
+        if (self_batch) batch_self_end(false, stream);
         return true;
       }
     }
@@ -352,6 +356,10 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
   } else {
     st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  }
+  if (self_batch) {
+    const int32_t bst = batch_self_end(st == ARD_OK, stream);
+    if (!st) st = bst;
   }
   if (raw_splits) {
     *raw_splits = splits;
@@ -833,13 +841,33 @@ struct BatchItem {
 };
 struct Batch {
   bool open = false;
+  int suspended = 0;  // live BatchSuspend objects
   std::vector<BatchItem> items;
 };
 static thread_local Batch g_batch;
 
 bool batch_open() { return g_batch.open; }
-BatchSuspend::BatchSuspend() : was_open(g_batch.open) { g_batch.open = false; }
-BatchSuspend::~BatchSuspend() { g_batch.open = was_open; }
+BatchSuspend::BatchSuspend() : was_open(g_batch.open) {
+  g_batch.open = false;
+  ++g_batch.suspended;
+}
+BatchSuspend::~BatchSuspend() {
+  g_batch.open = was_open;
+  --g_batch.suspended;
+}
+bool batch_self_begin() {
+  if (g_batch.open || g_batch.suspended > 0 || !g_batch.items.empty()) return false;
+  g_batch.open = true;
+  return true;
+}
+int32_t batch_self_end(bool ok, hipStream_t stream) {
+  if (!ok) {
+    g_batch.open = false;
+    g_batch.items.clear();
+    return ARD_OK;
+  }
+  return ard_batch_launch(stream);
+}
 
 static bool batch_push(int kind, int stage, const void* args, size_t arg_bytes, int gx, int gy, size_t lds) {
   if (!g_batch.open) return false;
