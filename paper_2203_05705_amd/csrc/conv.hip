@@ -697,6 +697,45 @@ __device__ __forceinline__ void zero_dropped_planes_body(const ZeroPlanesJob& z,
 }
 __global__ __launch_bounds__(256) void zero_dropped_planes_kernel(ZeroPlanesJob z) { zero_dropped_planes_body(z, (int)blockIdx.x); }
 
+// output positions of dropped rows of the input matrix to +0.0 (row-based sensitivity-aware pattern,
+// Section 5.2.1: the results of the kept rows fill the same rows of the output, the others are zero);
+// one workgroup per (channel, image) plane, eight positions per thread and step
+constexpr int ZPX = 8;  // planes (channels of one image) per workgroup
+struct ZeroPixelsJob {
+  uint16_t* Y;
+  const uint8_t* row_mask;
+  int Cout, HW;
+  int blocks;  // N * ceil(Cout / ZPX) workgroups of 256 threads (0: no job)
+};
+__device__ __forceinline__ void zero_dropped_pixels_body(const ZeroPixelsJob& z, int block) {
+  const int cgs = (z.Cout + ZPX - 1) / ZPX;
+  const int co0 = (block % cgs) * ZPX, n = block / cgs;
+  const int nco = min(ZPX, z.Cout - co0);
+  uint16_t* p = z.Y + ((long)n * z.Cout + co0) * z.HW;
+  const uint8_t* m = z.row_mask + (long)n * z.HW;
+  const bool vec = (z.HW % 8) == 0 && (((uintptr_t)z.Y | (uintptr_t)z.row_mask) & 15) == 0;
+  if (vec) {
+    const int chunks = z.HW >> 3;
+    for (int i = threadIdx.x; i < nco * chunks; i += 256) {
+      const int c = i / chunks, q = (i - c * chunks) * 8;
+      const uint2 mk = *reinterpret_cast<const uint2*>(m + q);
+      uint16_t* dst = p + (long)c * z.HW + q;
+      if ((mk.x | mk.y) == 0) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(0, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (!(((e < 4 ? mk.x : mk.y) >> ((e & 3) * 8)) & 0xff)) dst[e] = 0;
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < nco * z.HW; i += 256)
+      if (!m[i % z.HW]) p[i] = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_dropped_pixels_grid_kernel(ZeroPixelsJob z) { zero_dropped_pixels_body(z, (int)blockIdx.x); }
+
 // Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
 // data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
 struct PackJob {
@@ -731,16 +770,15 @@ static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int ro
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                           int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
                                                           long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj,
-                                                          ZeroPlanesJob zj, int main_x) {
+                                                          ZeroPlanesJob zj, ZeroPixelsJob zp, int main_x) {
   __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
   // (workgroups beyond the copy's own pack the weights of the product that follows and zero the planes it will
   // not write: independent small jobs that would otherwise be launches of their own)
   if ((int)blockIdx.x >= main_x) {
-    const int b = (int)blockIdx.x - main_x;
-    if (blockIdx.y == 0) {
-      if (b < pj.blocks) pack_weights_body(pj, (long)b * 256 + threadIdx.x);
-      else zero_dropped_planes_body(zj, b - pj.blocks);
-    }
+    const int b = ((int)blockIdx.x - main_x) * (int)gridDim.y + (int)blockIdx.y;
+    if (b < pj.blocks) pack_weights_body(pj, (long)b * 256 + threadIdx.x);
+    else if (b < pj.blocks + zj.blocks) zero_dropped_planes_body(zj, b - pj.blocks);
+    else if (b < pj.blocks + zj.blocks + zp.blocks) zero_dropped_pixels_body(zp, b - pj.blocks - zj.blocks);
     return;
   }
   const int HW = Hs * Ws;
@@ -984,13 +1022,14 @@ static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
                        int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{},
-                       PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}) {
+                       PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}, ZeroPixelsJob zp = ZeroPixelsJob{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     const int main_x = N * ceil_div(Hs * Ws, 64);
-    dim3 grid((unsigned)(main_x + pj.blocks + zj.blocks), (unsigned)(Cp / 64));
+    const int gy = Cp / 64;
+    dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks, gy)), (unsigned)gy);
     ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, main_x);
+                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, main_x);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }
@@ -1001,6 +1040,10 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
   if (zj.blocks) {
     ARD_LAUNCH(zero_dropped_planes_kernel, dim3((unsigned)zj.blocks), dim3(256), 0, stream, zj);
     ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
+  }
+  if (zp.blocks) {
+    ARD_LAUNCH(zero_dropped_pixels_grid_kernel, dim3((unsigned)zp.blocks), dim3(256), 0, stream, zp);
+    ARD_LAUNCH_CHECK("zero_dropped_pixels_grid_kernel");
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
@@ -1170,12 +1213,11 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   if (a.mode == ARD_CONV_FWD_ROWS) {
     // every channel, only the kept output positions: the product's columns are the listed pixels
     const int Cp = pad64(a.C), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
+    // (the zeros of the dropped positions and the packed weights ride in the copy's launch)
+    const ZeroPixelsJob zp{(uint16_t*)out, row_mask, a.Cout, a.Ho * a.Wo, a.N * ceil_div(a.Cout, ZPX)};
     int32_t st = to_grid(A, nullptr, a.C, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{},
-                         pack_job(Wt, nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp));
+                         pack_job(Wt, nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp), ZeroPlanesJob{}, zp);
     if (st) return st;
-    ARD_LAUNCH(zero_dropped_pixels_kernel<uint16_t>, dim3(a.Cout, a.N), dim3(256), 0, stream, (uint16_t*)out, row_mask, a.Cout,
-               a.Ho * a.Wo);
-    ARD_LAUNCH_CHECK("zero_dropped_pixels_kernel");
     if (Ck == 0) return ARD_OK;
     ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, Ck, a.Cout, nullptr, a.Cout, (const int*)d_keep, a.N * a.Ho * a.Wo, -1};
     return conv_grid_gemm(w.gwp, a.Cout, K, w.grid_a, (long)a.N * Hg * Wg + margin, cv, out, stream);
