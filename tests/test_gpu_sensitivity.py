@@ -223,6 +223,39 @@ def test_gradients_under_the_block_pattern(dtype, N, C, Cout, H, W, k, stride, p
     assert_parity(dW, ref_dW, dtype, None, "conv blocks dW")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_block_pattern_random_shapes(seed):
+    """Seeded random layers under random block masks: forward and both gradients against the oracle, whichever
+    path (skipping, per-column-block passes, general engine) the shape takes."""
+    import random
+    rnd = random.Random(900 + seed)
+    k = rnd.choice((1, 3, 3, 5))
+    pad = rnd.choice((0, k // 2))
+    H, W = rnd.randint(k + 3, 16), rnd.randint(k + 3, 16)
+    N, C, Cout = rnd.randint(1, 3), rnd.choice((8, 40, 64, 100, 128)), rnd.choice((24, 65, 130, 200))
+    Ho, Wo = H + 2 * pad - k + 1, W + 2 * pad - k + 1
+    x = rnd.choice((rnd.randint(1, Ho * Wo), max(1, Ho * Wo // rnd.randint(1, 3))))
+    y = rnd.choice((0, 64 * k * k, k * k * rnd.randint(1, 40), rnd.randint(1, C * k * k)))
+    print(f"random blocks case N={N} C={C} Cout={Cout} {H}x{W} k={k} p={pad} x={x} y={y}", flush=True)
+    rng = np.random.default_rng(seed)
+    dtype = "bf16"
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), dtype)
+    Wv = stored(rng.standard_normal((Cout, C, k, k)) * 0.2, dtype)
+    dYv = stored(rng.standard_normal((N, Cout, Ho, Wo)), dtype)
+    rows, RB, CB = ard.sens_regions(Av.shape, (k, k), 1, pad, x, y)
+    keep = (rng.uniform(size=(N, RB, CB)) < 0.5).astype(np.uint8)
+    Ad, Wd, dYd = from_vals(Av, dtype), from_vals(Wv, dtype), from_vals(dYv, dtype)
+    kd = torch.from_numpy(keep.reshape(-1)).cuda()
+    yy = y if y else C * k * k
+    Y = ard.conv_fwd_blocks(Ad, Wd, kd, x, y, 1, pad)
+    dA, dW = ard.conv_bwd_blocks(dYd, Ad, Wd, kd, x, y, 1, pad)
+    torch.cuda.synchronize()
+    assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, yy, 1, pad), dtype, None, "random blocks Y")
+    ref_dA, ref_dW = S.conv_bwd_blocks(dYv, Av, Wv, keep, x, yy, 1, pad)
+    assert_parity(dA, ref_dA, dtype, None, "random blocks dA")
+    assert_parity(dW, ref_dW, dtype, None, "random blocks dW")
+
+
 def test_config5_layer_under_the_block_pattern():
     """The config-5 layer under the block-based pattern: 112-by-576 blocks of the 784 x 2304 input matrices (four
     rows of output positions by one 64-channel group over all taps: the forward pass skips the dropped blocks),

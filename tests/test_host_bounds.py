@@ -137,6 +137,36 @@ def test_block_pattern_dispatch_and_bounds():
                 assert nb == 1 and 0 <= six[0] < six[1] <= six[2] and 0 <= six[3] < six[4] <= six[5]
 
 
+def test_block_pattern_random_shapes_pass_the_proof():
+    """Seeded random layers under the block pattern (forward, both gradient modes): whatever path dispatch picks,
+    every LDS-direct launch passes the exhaustive bounds proof and every request is accepted or refused cleanly."""
+    import random
+    rnd = random.Random(52)
+    with D.dry_run() as lib:
+        heap = D.FakeHeap()
+        fast = 0
+        for _ in range(60):
+            k = rnd.choice((1, 3, 3, 5))
+            pad = rnd.choice((0, k // 2))
+            H, W = rnd.randint(k + 4, 30), rnd.randint(k + 4, 30)
+            N, Cc, Cout = rnd.randint(1, 6), rnd.choice((8, 40, 64, 100, 128, 192, 256)), rnd.choice((24, 65, 128, 130, 256, 300))
+            Ho, Wo = H + 2 * pad - k + 1, W + 2 * pad - k + 1
+            x = rnd.choice((rnd.randint(1, Ho * Wo), max(1, Ho * Wo // rnd.randint(1, 8))))
+            y = rnd.choice((0, 64 * k * k, 128 * k * k, k * k * rnd.randint(1, 70), rnd.randint(1, Cc * k * k)))
+            n = lib.ard_conv_workspace_bytes(D.BF16, N, Cc, H, W, Cout, k, k, 1, pad)
+            ws = heap(n)
+            big = N * max(Cc, Cout) * (H + 2 * pad + 2) * (W + 2 * pad + 2) * 4
+            A, Wt, dY, out, keep = (heap(big) for _ in range(5))
+            D.launches(lib)
+            rc = lib.ard_conv_fwd_blocks(D.BF16, N, Cc, H, W, Cout, k, k, 1, pad, x, y, A, Wt, keep, out, ws, n, None)
+            assert rc == 0, (N, Cc, Cout, H, W, k, pad, x, y, lib.ard_last_error().decode())
+            fast += "block_plan_kernel" in D.launches(lib)[1]
+            for mode in (2, 3):
+                rc = lib.ard_conv_bwd_blocks(mode, D.BF16, N, Cc, H, W, Cout, k, k, 1, pad, x, y, A, Wt, dY, keep, out, ws, n, None)
+                assert rc == 0, (mode, N, Cc, Cout, H, W, k, pad, x, y, lib.ard_last_error().decode())
+        assert fast >= 3, "the random shapes never reached the path that skips dropped blocks"
+
+
 def test_a_shortened_operand_is_rejected():
     """The proof is tight: with every operand pretended 8 elements shorter than it is, the dense 4096^3
     product (whose loaders read their operands to the last byte) must be refused, and nothing launched."""
