@@ -84,6 +84,26 @@ def test_lstm_backward_recurrence_in_one_launch_shapes(T, B, I, H, dp, b):
            from_vals(dh, dtype), "lstm bf16 one launch")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_lstm_random_shapes_both_recurrences_in_one_launch(seed):
+    """Seeded random bf16 layers: ragged batch blocks, unit slices that end inside the padding, odd input widths."""
+    import random
+    rnd = random.Random(4100 + seed)
+    T, B, I, H = rnd.randint(2, 6), rnd.randint(1, 70), rnd.randint(1, 64), rnd.randint(8, 300)
+    dp = rnd.randint(1, 5)
+    b = rnd.randint(1, dp)
+    if -(-(H - (b - 1)) // dp) < 1:
+        dp, b = 1, 1
+    print(f"lstm random case T={T} B={B} I={I} H={H} dp={dp} b={b}", flush=True)
+    dtype = "bf16"
+    rng = np.random.default_rng(seed)
+    x = stored(rng.standard_normal((T, B, I)), dtype)
+    W = stored(rng.uniform(-0.15, 0.15, (4 * H, I + H)), dtype)
+    dh = stored(rng.standard_normal((T, B, H)), dtype)
+    _check(dtype, x, W, dh, P.row_mask(H, dp, b), ard.Pattern.row(dp, b), from_vals(x, dtype), from_vals(W, dtype),
+           from_vals(dh, dtype), "lstm bf16 random")
+
+
 def test_lstm_list_pattern_parity():
     dtype, T, B, I, H = "bf16", 4, 16, 32, 48
     rng = np.random.default_rng(77)
