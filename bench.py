@@ -667,10 +667,16 @@ def extra_conv(ard, torch, rooflines):
                                                              P(rp["count"]), st))["median"]
     t_fwd = event_us(torch, lambda: ard.conv_fwd_rows(A, Wt, rp, nkr, ws=ws, out=Yr))["median"]
     dense_fwd = res["rate0.0"]["fwd"]["us"]
+    gr = ard.conv_bwd_rows(dY, A, Wt, rp, ws=ws)
+    # (the weight gradient takes the grid of A the forward pass left and the masked grid of dY the data gradient left)
+    t_rbwd = event_us(torch, lambda: ard.conv_bwd_rows(dY, A, Wt, rp, ws=ws, out=gr, reuse=ard.CONV_REUSE_A | ard.CONV_REUSE_DY),
+                      reps=5, warm=2)["median"]
     res["row_sensitivity_pattern"] = dict(kept_rows=nkr, rows=N * rows, kept_fraction=round(nkr / (N * rows), 4),
                                           predict_us=round(t_pred, 1), row_pattern_us=round(t_pat, 1), fwd_rows_us=round(t_fwd, 1),
                                           fwd_speedup_vs_all_rows=round(dense_fwd / t_fwd, 3),
-                                          fwd_speedup_with_prediction=round(dense_fwd / (t_fwd + t_pred + t_pat), 3))
+                                          fwd_speedup_with_prediction=round(dense_fwd / (t_fwd + t_pred + t_pat), 3),
+                                          bwd_data_plus_weight_us=round(t_rbwd, 1),
+                                          bwd_passes="the ordinary passes, dY's dropped positions zeroed while it is copied into its grid (no work skipped)")
     # the block-based pattern of Section 5.2.2 on the same layer: blocks of 112 output positions (four rows) by one
     # 64-channel group over all taps, balanced groups; the forward pass skips the dropped blocks, the gradients run
     # the ordinary passes once per column block on a dY whose positions in that block's dropped bands are zeroed

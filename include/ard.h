@@ -302,7 +302,8 @@ typedef enum {
  * earlier call left in the SAME workspace instead of building it again.  The caller vouches that the
  * earlier call had the same shape arguments, the same tensor (A or dYin), the same kept list, and that
  * nothing else wrote the workspace in between (the other passes of the layer do not disturb it).
- *   ARD_CONV_REUSE_A   FWD, BWD_WEIGHT: the grid of A built by an earlier FWD or BWD_WEIGHT
+ *   ARD_CONV_REUSE_A   FWD, BWD_WEIGHT: the grid of A built by an earlier FWD or BWD_WEIGHT (of the *_ROWS modes:
+ *                      by FWD_ROWS or BWD_WEIGHT_ROWS)
  *   ARD_CONV_REUSE_DY  BWD_DATA, BWD_WEIGHT: the grid of dY built by an earlier BWD_DATA or BWD_WEIGHT;
  *                      across the two passes only for size-preserving filters (k - 1 = 2 pad), else
  *                      ARD_EUNSUPPORTED
@@ -329,9 +330,11 @@ size_t ard_conv_workspace_bytes(int32_t dtype, int32_t N, int32_t C, int32_t H, 
  *   Needs A, Wt.  fp32 and strided layers compute every position and zero the dropped ones.
  * BWD_DATA_ROWS / BWD_WEIGHT_ROWS: the gradients of FWD_ROWS with respect to A and Wt.  Only kept rows took
  *   part in the product, so gradient arriving on a dropped position counts as zero: d_mask[N*Ho*Wo] is the
- *   row mask, dYin is copied once with the dropped positions zeroed and BWD_DATA / BWD_WEIGHT run on that
- *   copy with every channel kept (no time is saved over an undropped layer; n_keep, d_keep are ignored).
- *   Needs dYin, d_mask and Wt (data) or A (weight).
+ *   row mask; BWD_DATA / BWD_WEIGHT run with every channel kept on a dY whose dropped positions are zero
+ *   (zeroed while dY is copied into its grid; a masked copy for fp32 and strided layers).  No time is saved
+ *   over an undropped layer; n_keep, d_keep are ignored.  Needs dYin, d_mask and Wt (data) or A (weight).
+ *   The reuse flags apply as for BWD_DATA / BWD_WEIGHT: ARD_CONV_REUSE_A takes the grid FWD_ROWS left,
+ *   ARD_CONV_REUSE_DY the masked grid an earlier *_ROWS gradient of the same mask left.
  * FWD / BWD_DATA / BWD_WEIGHT read the kept channels from d_keep (n_keep entries,
  *   n_keep given on the host) and never load a dropped channel:
  *   FWD        Y  = conv(A restricted to kept channels, Wt)       needs A, Wt

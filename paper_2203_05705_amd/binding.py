@@ -573,15 +573,16 @@ def conv_bwd_blocks(dY, A, Wt, block_keep, x, y, stride=1, pad=1, ws=None, strea
     return dA, dWt
 
 
-def conv_bwd_rows(dY, A, Wt, row_pat, stride=1, pad=1, ws=None, stream=None, out=None):
-    """Gradients (dA, dWt) of conv_fwd_rows: gradient arriving on dropped output positions counts as zero."""
+def conv_bwd_rows(dY, A, Wt, row_pat, stride=1, pad=1, ws=None, stream=None, out=None, reuse=0):
+    """Gradients (dA, dWt) of conv_fwd_rows: gradient arriving on dropped output positions counts as zero.
+    reuse: CONV_REUSE_* flags for the weight gradient (grids that conv_fwd_rows and the data gradient left in ws)."""
     _dev(dY), _dev(A), _dev(Wt)
     Cout, _, kh, kw = Wt.shape
     dA, dWt = out if out is not None else (_out(A.shape, A.dtype, A.device), _out(Wt.shape, Wt.dtype, Wt.device))
     dt = _dtype_code(A)
     fmap_drop_conv(CONV_BWD_DATA_ROWS, A.shape, dt, Cout, (kh, kw), stride, pad, Wt=Wt, dY=dY, out=dA, mask=row_pat["mask"],
                    ws=ws, stream=stream)
-    fmap_drop_conv(CONV_BWD_WEIGHT_ROWS, A.shape, dt, Cout, (kh, kw), stride, pad, A=A, dY=dY, out=dWt, mask=row_pat["mask"],
+    fmap_drop_conv(CONV_BWD_WEIGHT_ROWS | reuse, A.shape, dt, Cout, (kh, kw), stride, pad, A=A, dY=dY, out=dWt, mask=row_pat["mask"],
                    ws=ws, stream=stream)
     return dA, dWt
 

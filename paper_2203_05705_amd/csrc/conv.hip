@@ -1406,16 +1406,24 @@ static int32_t conv_run(const ConvArgs& a, double rate, const void* A, const voi
     // gradients of FWD_ROWS: positions of dropped rows carry no gradient.  dY is copied once with those
     // positions zeroed, then the ordinary passes run over every position with every channel kept.
     if (!dYin || !d_mask || !out) return fail(ARD_EINVAL, "the row-pattern gradients need dYin, d_mask and out");
-    if (a.reuse) return fail(ARD_EUNSUPPORTED, "the row-pattern gradients build their own grids");
-    ARD_LAUNCH(mask_pixels_kernel<T>, dim3(a.Cout, a.N), dim3(256), 0, stream, (const T*)dYin, (const uint8_t*)d_mask, a.Cout,
-               a.Ho * a.Wo, (T*)w.dy_rows);
-    ARD_LAUNCH_CHECK("mask_pixels_kernel");
+    // (the reuse flags mean what they mean for the ordinary gradients: the grid of A that FWD_ROWS left, the
+    // masked grid of dY that BWD_DATA_ROWS left -- same mask, same layout)
     ARD_LAUNCH(iota_kernel, dim3(ceil_div(a.C, 256)), dim3(256), 0, stream, w.all_chan, a.C);
     ARD_LAUNCH_CHECK("iota_kernel");
     ConvArgs full = a;
     full.mode = a.mode == ARD_CONV_BWD_DATA_ROWS ? ARD_CONV_BWD_DATA : ARD_CONV_BWD_WEIGHT;
     full.n_keep = a.C;
-    return conv_run<T>(full, 0.0, A, Wt, w.dy_rows, out, nullptr, w.all_chan, nullptr, nullptr, w, stream);
+    const void* dy_use = w.dy_rows;
+    if (w.grid_a && !dev_knobs().no_fast) {
+      // the pass copies dY into a channels-last grid anyway: that copy drops the positions (bands of one row)
+      full.dy_mask = BandMask{(const uint8_t*)d_mask, a.Ho * a.Wo, 1, 0, 1};
+      dy_use = dYin;
+    } else {
+      ARD_LAUNCH(mask_pixels_kernel<T>, dim3(a.Cout, a.N), dim3(256), 0, stream, (const T*)dYin, (const uint8_t*)d_mask, a.Cout,
+                 a.Ho * a.Wo, (T*)w.dy_rows);
+      ARD_LAUNCH_CHECK("mask_pixels_kernel");
+    }
+    return conv_run<T>(full, 0.0, A, Wt, dy_use, out, nullptr, w.all_chan, nullptr, nullptr, w, stream);
   }
   if (a.n_keep < 0 || a.n_keep > a.C) return fail(ARD_EINVAL, "n_keep=%d outside 0..%d", a.n_keep, a.C);
   if (a.n_keep > 0 && a.n_keep < a.C && !d_keep) return fail(ARD_EINVAL, "d_keep is required");

@@ -165,6 +165,7 @@ def test_block_pattern_random_shapes_pass_the_proof():
                 rc = lib.ard_conv_bwd_blocks(mode, D.BF16, N, Cc, H, W, Cout, k, k, 1, pad, x, y, A, Wt, dY, keep, out, ws, n, None)
                 assert rc == 0, (mode, N, Cc, Cout, H, W, k, pad, x, y, lib.ard_last_error().decode())
         assert fast >= 3, "the random shapes never reached the path that skips dropped blocks"
+        assert D.last_bounds(lib)[0] >= fast      # (reading them also resets the count for the next test)
 
 
 def test_a_shortened_operand_is_rejected():
@@ -172,6 +173,7 @@ def test_a_shortened_operand_is_rejected():
     product (whose loaders read their operands to the last byte) must be refused, and nothing launched."""
     with D.dry_run() as lib:
         heap = D.FakeHeap()
+        D.last_bounds(lib)
         _ok(lib, D.layer_calls(lib, heap, D.BF16, 4096, 4096, 4096, None, None, 0, ops=(0,)), "dense")
         n, six = D.last_bounds(lib)
         assert n == 1 and six[1] == six[2] and six[4] == six[5]      # both operands read up to their end
