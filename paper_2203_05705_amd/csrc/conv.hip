@@ -786,6 +786,19 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
   const int n = blockIdx.x / px_tiles, p0 = (blockIdx.x - n * px_tiles) * 64;
   const int c0 = blockIdx.y * 64;
   const int t = threadIdx.x;
+  // masked copy: which of the tile's 64 pixels count is the same for all of its channels, looked up once
+  __shared__ uint8_t piece_keep[8];
+  if (bm.blk) {
+    if (t < 8) {
+      unsigned bits = 0;
+      for (int e = 0; e < 8; ++e) {
+        const int p = p0 + t * 8 + e;
+        if (p < HW && band_kept(bm, n, p)) bits |= 1u << e;
+      }
+      piece_keep[t] = (uint8_t)bits;
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int u = t + 256 * i;             // 512 pieces: 64 channels x 8 pieces of 8 pixels
@@ -793,11 +806,12 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     const int c = c0 + cl, p = p0 + q * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (c < n_chan && p < HW) v = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
-    if (bm.blk && p < HW) {
+    if (bm.blk) {
+      const unsigned bits = piece_keep[q];
       uint32_t w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        if (!band_kept(bm, n, p + e)) w4[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+        if (!((bits >> e) & 1)) w4[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
       v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
     }
     *reinterpret_cast<uint4*>(&tile[cl][q * 8]) = v;
