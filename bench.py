@@ -39,11 +39,13 @@ REPEATS = 5              # the block of `steps` timed iterations is repeated; me
 # HBM bytes per launch (fetched + written) of the kernels the roofline records describe.  A counter run
 # cannot happen inside this program: the figures come from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
 # runs of `bench.py --only-call NAME` (scaled by what the same counters read for a plain copy); the
-# summaries, with their commands, are the files named here.  None: not measured.
+# summaries, with their commands, are the files named here.  None: not measured.  L2.bwd_weight: per CALL, every
+# kernel of the call (the product alone or grouped with the pass that zeroes dropped rows, the finishing pass
+# where the pattern needs one), as its time is; the other two: the product kernel, per launch.
 TRAFFIC = {
-    "L2.bwd_weight": (14958635, "profiles/hbm_traffic_L2_bwd_weight.txt"),
-    "C3.fwd.dp2": (151159407, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
-    "C5.fwd": (108194094, "profiles/hbm_traffic_config5_conv_fwd.txt"),
+    "L2.bwd_weight": (20421584, "profiles/hbm_traffic_L2_bwd_weight.txt"),
+    "C3.fwd.dp2": (151170438, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
+    "C5.fwd": (108297814, "profiles/hbm_traffic_config5_conv_fwd.txt"),
 }
 
 
