@@ -263,6 +263,11 @@ def test_block_pattern_random_shapes(seed):
     ref_dA, ref_dW = S.conv_bwd_blocks(dYv, Av, Wv, keep, x, yy, 1, pad)
     assert_parity(dA, ref_dA, dtype, None, "random blocks dA")
     assert_parity(dW, ref_dW, dtype, None, "random blocks dW")
+    # a second call gives the same bits (the order the tiles are placed in may differ between calls, results may not)
+    Y2 = ard.conv_fwd_blocks(Ad, Wd, kd, x, y, 1, pad)
+    dA2, dW2 = ard.conv_bwd_blocks(dYd, Ad, Wd, kd, x, y, 1, pad)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y) and torch.equal(dA2, dA) and torch.equal(dW2, dW)
 
 
 def test_config5_layer_under_the_block_pattern():
@@ -282,6 +287,9 @@ def test_config5_layer_under_the_block_pattern():
     Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y)
     dA, dW = ard.conv_bwd_blocks(dYd, Ad, Wd, bp["keep"], x, y)
     torch.cuda.synchronize()
+    Y2 = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y), "two forward calls under the same block mask differ"
     assert_parity(Y, S.conv_fwd_blocks(Av, Wv, keep, x, y), "bf16", None, "config 5 blocks Y")
     ref_dA, ref_dW = S.conv_bwd_blocks(dYv, Av, Wv, keep, x, y)
     assert_parity(dA, ref_dA, "bf16", None, "config 5 blocks dA")
