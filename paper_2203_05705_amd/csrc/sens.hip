@@ -161,14 +161,12 @@ __global__ __launch_bounds__(256) void sens_predict_lut_kernel(const T* A, SensG
   }
 }
 
-// The prediction once more, with the region's footprint in the activations copied into LDS first: the
-// draws of a region fall on a few input rows of its channels (config 5: 4 rows x 28 x 256 channels = 57 KB
-// for 5529 draws), and a gather from memory costs a whole cache-line transaction per draw (69 M of them
-// made the pass take 460 us) where the copy is a few coalesced 16-byte loads per thread.  Same draws, same
-// elements, same counts.  Needs planes that are whole numbers of 16-byte pieces (then every channel's run
-// starts at the same offset within a piece) and a footprint that fits the LDS; the host checks both.
-// Neighbouring row bands touch nearly the same input rows (bands of 8 positions: 4 rows each, 98 bands of a
-// 28 x 28 image would copy it 14 times over), so a workgroup takes G consecutive bands on one copy.
+// The prediction once more, with the footprint of the workgroup's regions in the activations brought into LDS
+// first: the draws of a region fall on a few input rows of its channels (config 5, a band of 8 positions:
+// 4 rows x 28 x 256 channels for 5529 draws), and a gather from memory costs a whole cache-line transaction per
+// draw (69 M of them made the pass take 460 us) where the copy is a few coalesced 16-byte loads per thread.
+// Same draws, same elements, same counts.  Needs planes that are whole numbers of 16-byte pieces (then every
+// channel's run starts at the same offset within a piece); the host checks it.
 struct SensStage {
   int nrow_max, chp;  // input rows a workgroup's bands can touch; elements reserved per channel (a multiple of the piece)
   FastDiv div_taps, div_kw, div_wo;
@@ -195,17 +193,28 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
   const int run0 = ih_lo * g.W, run = max(0, ih_hi - ih_lo + 1) * g.W;  // elements of a channel's plane that are staged
   const int off = run0 % CE;                                           // the run's offset within its first piece
   const int pieces = run > 0 ? (off + run + CE - 1) / CE : 0;           // 16-byte pieces per channel
-  T* stage = reinterpret_cast<T*>(sens_stage_lds);
+  // What a draw needs of an element is one bit (above the threshold or not): the copy keeps one byte per
+  // 16-byte piece, bit e = element e of the piece.  The footprint shrinks 16 (bf16) or 32 (fp32) times, so
+  // the CU holds as many workgroups as its wavefront slots allow and many bands can share one copy.
+  uint8_t* stage = reinterpret_cast<uint8_t*>(sens_stage_lds);
+  const int chpb = sg.chp / CE;                               // bytes per channel (chp is a multiple of the piece)
   const int nch_max = min(g.C, (g.y + taps - 2) / taps + 1);  // channels a column block can touch
-  int* col_lut = reinterpret_cast<int*>(stage + (size_t)sg.chp * nch_max);  // (chp is a multiple of the piece: aligned)
+  int* col_lut = reinterpret_cast<int*>(stage + (((size_t)chpb * nch_max + 3) & ~(size_t)3));
   int* row_lut = col_lut + w;
   const T* img = A + (long)n * g.C * g.H * g.W;
   // consecutive threads take consecutive pieces, running on from one channel into the next
   for (int i = threadIdx.x; i < nch * pieces; i += 256) {
     const int c = i / pieces, pc = i - c * pieces;
     const T* src = img + (long)(ch_lo + c) * g.H * g.W + (run0 - off) + pc * CE;
-    *reinterpret_cast<uint4*>(stage + (size_t)c * sg.chp + pc * CE) = *reinterpret_cast<const uint4*>(src);
+    const uint4 v = *reinterpret_cast<const uint4*>(src);
+    T el[CE];
+    *reinterpret_cast<uint4*>(el) = v;
+    unsigned bits = 0;
+#pragma unroll
+    for (int e = 0; e < CE; ++e) bits |= (ElemTraits<T>::to_f32(el[e]) > thr ? 1u : 0u) << e;
+    stage[(size_t)c * chpb + pc] = (uint8_t)bits;
   }
+  const int border_above = 0.0f > thr ? 1 : 0;  // the zero border of the input matrix
   for (int i = threadIdx.x; i < w; i += 256) {
     const int q = q0 + i;
     const int ch = (int)fdiv((uint32_t)q, sg.div_taps), tap = q - ch * taps;
@@ -226,8 +235,7 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
     int s = (int)(((long)k_permille * size) / 1000);
     if (s < 1) s = 1;
     int c = 0;
-    // (a footprint of tens of KB leaves two wavefronts per SIMD: four draws in flight per thread hide the
-    // table and LDS reads that occupancy does not)
+    // (four draws in flight per thread: their table and LDS reads overlap)
 #pragma unroll 4
     for (int j = threadIdx.x; j < s; j += 256) {
       const uint32_t u = sens_draw(prefix, (uint64_t)region * 65536u + (uint64_t)j);
@@ -235,9 +243,12 @@ __global__ __launch_bounds__(256) void sens_predict_staged_kernel(const T* A, Se
       const uint32_t r = fdiv(e, div_w), q = e - r * (uint32_t)w;
       const int ci = col_lut[q], ri = row_lut[rr0 + r];
       const int ih = (ri & 0xffff) + ((ci >> 24) & 15) - g.pad, iw = (ri >> 16) + ((ci >> 28) & 15) - g.pad;
-      float v = 0.0f;  // the zero border of the input matrix
-      if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = ElemTraits<T>::to_f32(stage[(ci & 0xffffff) + off + (ih - ih_lo) * g.W + iw]);
-      c += v > thr ? 1 : 0;
+      int above = border_above;
+      if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
+        const int idx = (ci & 0xffffff) + off + (ih - ih_lo) * g.W + iw;  // element within the staged channels
+        above = (stage[idx / CE] >> (idx % CE)) & 1;
+      }
+      c += above;
     }
     for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
     if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
@@ -415,24 +426,28 @@ extern "C" int32_t ard_sens_predict(int32_t dtype, int32_t N, int32_t C, int32_t
   if (lut_ok) {
     const FastDiv dw = fast_div((uint32_t)g.y);
     // footprint of a region in LDS when it fits: rows a band can touch x whole width x channels of a block
-    const int ce = dtype == ARD_BF16 ? 8 : 4, es = dtype == ARD_BF16 ? 2 : 4, taps = kh * kw;
+    const int ce = dtype == ARD_BF16 ? 8 : 4, taps = kh * kw;
     const int nch_max = imin(C, (g.y + taps - 2) / taps + 1);
-    // Bands per workgroup: the most whose common footprint leaves as many workgroups on a CU as one band's does
-    // (bands of 8 positions of a 28-wide image: seven are two whole rows, the four input rows of one band) while the
-    // launch keeps two workgroups per CU.  Config-5 layer, 30 % sampled: rows of 8 positions 300 -> 185 us, of 4
-    // positions 447 -> 201 us, 8 x 64 blocks 908 -> 295 us; regions of 112 x 576 stay alone (108 us; two per
-    // workgroup 152 us: fewer resident workgroups).
-    int G = 1, nrow_max = 0, chp = 0, occ1 = 0;
+    // Bands per workgroup.  Consecutive bands touch nearly the same input rows when they are shorter than an
+    // output row (98 bands of 8 positions would copy a 28 x 28 image 14 times over), and a band with few draws
+    // does not pay for its copy: a workgroup takes up to 16 bands, as many as bring it to about 40 k draws,
+    // provided their common footprint is well below the sum of theirs (else grouping only costs workgroups) and
+    // the launch keeps two workgroups per CU.  Config-5 layer, 30 % sampled, one band -> chosen number:
+    // rows of 8 positions 185 -> 138 us (7 bands: two whole rows), of 4 positions 248 -> 139 us (14), of 16
+    // positions 149 -> 147 us (3), 8 x 64 blocks 951 -> 285 us (16); regions of 112 x 576 stay alone (113 us,
+    // two per workgroup 131 us).
+    int G = 1, nrow_max = 0, chp = 0, rows1 = 0;
     size_t stage_bytes = 0;
-    for (int cand = 1; cand <= 16 && cand <= imax(1, g.RB); ++cand) {
+    const long draws = imax(1, (int)(((long)k_permille * g.x * g.y) / 1000));
+    const int g_cap = (int)imin(16, imax(1, (int)(40000 / draws)));
+    for (int cand = 1; cand <= g_cap && cand <= imax(1, g.RB); ++cand) {
       // output rows a group can span: groups of whole rows start on a row, any other may start anywhere in one
       const int oh_span = (cand * g.x) % g.Wo == 0 ? cand * g.x / g.Wo : (cand * g.x + g.Wo - 2) / g.Wo + 1;
       const int nr = imin(H, (oh_span - 1) * stride + kh);
       const int cp = (int)align_up((size_t)(ce - 1 + nr * Wd), (size_t)ce);
-      const size_t bytes = (size_t)cp * nch_max * es + (size_t)(g.y + cand * g.x) * sizeof(int);
-      const int occ = (int)imin(8, (long)(160 * 1024 / (bytes + 512)));
-      if (cand == 1) occ1 = occ;
-      if (cand == 1 || (occ >= occ1 && occ >= 1 && (long)N * ceil_div(g.RB, cand) * g.CB >= 512))
+      const size_t bytes = align_up((size_t)(cp / ce) * nch_max, (size_t)4) + (size_t)(g.y + cand * g.x) * sizeof(int);
+      if (cand == 1) rows1 = nr;
+      if (cand == 1 || (4 * nr <= 3 * cand * rows1 && bytes <= 64 * 1024 && (long)N * ceil_div(g.RB, cand) * g.CB >= 512))
         G = cand, nrow_max = nr, chp = cp, stage_bytes = bytes;
     }
     // (pad < filter size: every window then starts inside the image, which the copy's bounds rely on)
