@@ -736,6 +736,90 @@ __device__ __forceinline__ void zero_dropped_pixels_body(const ZeroPixelsJob& z,
 
 __global__ __launch_bounds__(256) void zero_dropped_pixels_grid_kernel(ZeroPixelsJob z) { zero_dropped_pixels_body(z, (int)blockIdx.x); }
 
+// Block-based pattern on the LDS-direct path (Section 5.2.2).  When a block of the input matrix spans
+// whole 64-channel groups over all filter taps (y a multiple of 64 * taps), a kept block is a set of whole
+// 64-deep contraction steps of the grid's (tap, channel) order, and a row band of x output positions can be
+// laid out as column tiles of its own (padded with entries that store nothing): every tile then contracts
+// over the kept blocks of ONE band, and dropped blocks are neither loaded nor multiplied.
+// Tile T = ((image * RB + band) * tpb + part) holds positions band*x + part*BN ... of its image.
+struct BlockPlan {
+  int N, HoWo, x, RB, CB, tpb, BN, taps, CG, cg_per_blk, KB;
+};
+// kept 64-channel groups of tile T's band (0 for a tile that holds no position)
+__device__ __forceinline__ int block_tile_groups(const uint8_t* blk, const BlockPlan& p, int T) {
+  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
+  if (part * p.BN >= p.x || band * p.x + part * p.BN >= p.HoWo) return 0;
+  const uint8_t* row = blk + (long)(n * p.RB + band) * p.CB;
+  int g = 0;
+  for (int cg = 0; cg < p.CG; ++cg) g += row[cg / p.cg_per_blk] ? 1 : 0;
+  return g;
+}
+
+// One workgroup (256 threads) lays out tile T: its padded pixel list, the list of its kept contraction steps
+// and their number.  Where the tile goes in the launch: longest contraction first on every XCD (workgroups
+// start in order, so the long ones do not end up alone at the end).  Every workgroup finds the rank of its own
+// tile by counting the tiles that come before it (more kept groups, or as many and a lower index): no pass of
+// its own, no hand-over.  order = 0: tile T stays at T.
+constexpr int kBlockOrderMaxTiles = 1 << 11;  // (each of n workgroups reads n keys)
+struct BlockPlanJob {
+  const uint8_t* blk;
+  BlockPlan p;
+  int tiles, order;
+  int *pix, *kb_list, *kb_cnt;
+  int blocks;  // = tiles (0: no job)
+};
+__device__ __forceinline__ void block_plan_body(const BlockPlanJob& j, int T, int* red4) {
+  const BlockPlan& p = j.p;
+  const int tid = threadIdx.x;
+  int at = T;
+  if (j.order) {
+    const int mine = block_tile_groups(j.blk, p, T);
+    int before = 0;
+    for (int U = tid; U < j.tiles; U += 256) {
+      const int k = block_tile_groups(j.blk, p, U);
+      before += (k > mine || (k == mine && U < T)) ? 1 : 0;
+    }
+    for (int o = 32; o > 0; o >>= 1) before += __shfl_down(before, o, 64);
+    if ((tid & 63) == 0) red4[tid >> 6] = before;
+    __syncthreads();
+    const int r = red4[0] + red4[1] + red4[2] + red4[3];
+    // The kernel deals its work items to the 8 XCDs in contiguous shares [x*n/8, (x+1)*n/8) and a share's
+    // workgroups start in order: rank r goes to XCD r % 8, place r / 8 of its share; the last n % 8 ranks
+    // fill the shares that are one longer than the others.
+    const int even = j.tiles / 8;
+    int x = r & 7;
+    at = r >> 3;
+    if (r >= 8 * even) {
+      int q = r - 8 * even;
+      at = even;
+      for (x = 0; x < 8; ++x) {
+        const int size = (int)((long)(x + 1) * j.tiles / 8) - (int)((long)x * j.tiles / 8);
+        if (size > even && q-- == 0) break;
+      }
+    }
+    at += (int)((long)x * j.tiles / 8);
+  }
+  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
+  for (int i = tid; i < p.BN; i += 256) {
+    const int in_band = part * p.BN + i, pos = band * p.x + in_band;
+    j.pix[(long)at * p.BN + i] = (in_band < p.x && pos < p.HoWo) ? n * p.HoWo + pos : -1;
+  }
+  if (tid == 0) {
+    int cnt = 0;
+    const bool any = part * p.BN < p.x && band * p.x + part * p.BN < p.HoWo;
+    const uint8_t* row = j.blk + (long)(n * p.RB + band) * p.CB;
+    if (any)
+      for (int tap = 0; tap < p.taps; ++tap)
+        for (int cg = 0; cg < p.CG; ++cg)
+          if (row[cg / p.cg_per_blk]) j.kb_list[(long)at * p.KB + cnt++] = tap * p.CG + cg;
+    j.kb_cnt[at] = cnt;
+  }
+}
+__global__ __launch_bounds__(256) void block_plan_kernel(BlockPlanJob j) {
+  __shared__ int red4[4];
+  block_plan_body(j, (int)blockIdx.x, red4);
+}
+
 // Wp[row][tap*Cp + q]: forward (flip = 0): row = output channel, q = kept input channel;
 // data gradient (flip = 1): row = kept input channel, q = output channel, taps reversed.
 struct PackJob {
@@ -770,8 +854,9 @@ static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int ro
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
                                                           int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
                                                           long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj,
-                                                          ZeroPlanesJob zj, ZeroPixelsJob zp, int main_x) {
+                                                          ZeroPlanesJob zj, ZeroPixelsJob zp, BlockPlanJob bj, int main_x) {
   __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
+  __shared__ int red4[4];
   // (workgroups beyond the copy's own pack the weights of the product that follows and zero the planes it will
   // not write: independent small jobs that would otherwise be launches of their own)
   if ((int)blockIdx.x >= main_x) {
@@ -779,6 +864,7 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     if (b < pj.blocks) pack_weights_body(pj, (long)b * 256 + threadIdx.x);
     else if (b < pj.blocks + zj.blocks) zero_dropped_planes_body(zj, b - pj.blocks);
     else if (b < pj.blocks + zj.blocks + zp.blocks) zero_dropped_pixels_body(zp, b - pj.blocks - zj.blocks);
+    else if (b < pj.blocks + zj.blocks + zp.blocks + bj.blocks) block_plan_body(bj, b - pj.blocks - zj.blocks - zp.blocks, red4);
     return;
   }
   const int HW = Hs * Ws;
@@ -1036,14 +1122,15 @@ static bool al16c(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int Hs, int Ws, int N, int Hg, int Wg, int oh,
                        int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{},
-                       PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}, ZeroPixelsJob zp = ZeroPixelsJob{}) {
+                       PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}, ZeroPixelsJob zp = ZeroPixelsJob{},
+                       BlockPlanJob bj = BlockPlanJob{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     const int main_x = N * ceil_div(Hs * Ws, 64);
     const int gy = Cp / 64;
-    dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks, gy)), (unsigned)gy);
+    dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks + bj.blocks, gy)), (unsigned)gy);
     ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, main_x);
+                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, bj, main_x);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }
@@ -1058,6 +1145,10 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
   if (zp.blocks) {
     ARD_LAUNCH(zero_dropped_pixels_grid_kernel, dim3((unsigned)zp.blocks), dim3(256), 0, stream, zp);
     ARD_LAUNCH_CHECK("zero_dropped_pixels_grid_kernel");
+  }
+  if (bj.blocks) {
+    ARD_LAUNCH(block_plan_kernel, dim3((unsigned)bj.blocks), dim3(256), 0, stream, bj);
+    ARD_LAUNCH_CHECK("block_plan_kernel");
   }
   dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
   ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
@@ -1114,81 +1205,6 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
   return launch_direct_kernel<true, true, 64, 64, 4, 1>(F, grid, stream);
 }
 
-// Block-based pattern on the LDS-direct path (Section 5.2.2).  When a block of the input matrix spans
-// whole 64-channel groups over all filter taps (y a multiple of 64 * taps), a kept block is a set of whole
-// 64-deep contraction steps of the grid's (tap, channel) order, and a row band of x output positions can be
-// laid out as column tiles of its own (padded with entries that store nothing): every tile then contracts
-// over the kept blocks of ONE band, and dropped blocks are neither loaded nor multiplied.
-// Tile T = ((image * RB + band) * tpb + part) holds positions band*x + part*BN ... of its image.
-struct BlockPlan {
-  int N, HoWo, x, RB, CB, tpb, BN, taps, CG, cg_per_blk, KB;
-};
-// kept 64-channel groups of tile T's band (0 for a tile that holds no position)
-__device__ __forceinline__ int block_tile_groups(const uint8_t* blk, const BlockPlan& p, int T) {
-  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
-  if (part * p.BN >= p.x || band * p.x + part * p.BN >= p.HoWo) return 0;
-  const uint8_t* row = blk + (long)(n * p.RB + band) * p.CB;
-  int g = 0;
-  for (int cg = 0; cg < p.CG; ++cg) g += row[cg / p.cg_per_blk] ? 1 : 0;
-  return g;
-}
-
-// Where each tile goes in the launch: longest contraction first on every XCD (workgroups start in order,
-// so the long ones do not end up alone at the end).  One workgroup: counting sort of the tiles by kept groups;
-// tiles of equal length keep no particular order among themselves (the results do not depend on it).
-constexpr int kBlockOrderMaxTiles = 1 << 15;
-__global__ __launch_bounds__(1024) void block_order_kernel(const uint8_t* blk, BlockPlan p, int tiles, int* slot) {
-  __shared__ int hist[130], start[130];
-  for (int i = threadIdx.x; i <= p.CG; i += blockDim.x) hist[i] = 0;
-  __syncthreads();
-  for (int T = threadIdx.x; T < tiles; T += blockDim.x) atomicAdd(&hist[block_tile_groups(blk, p, T)], 1);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int at = 0;
-    for (int g = p.CG; g >= 0; --g) {
-      start[g] = at;
-      at += hist[g];
-    }
-  }
-  __syncthreads();
-  // The kernel deals its work items to the 8 XCDs in contiguous shares [x*n/8, (x+1)*n/8) and a share's
-  // workgroups start in order: rank r (longest first) goes to XCD r % 8, place r / 8 of its share; the last
-  // n % 8 ranks fill the shares that are one longer than the others.
-  const int even = tiles / 8;
-  for (int T = threadIdx.x; T < tiles; T += blockDim.x) {
-    const int r = atomicAdd(&start[block_tile_groups(blk, p, T)], 1);
-    int x = r & 7, at = r >> 3;
-    if (r >= 8 * even) {
-      int j = r - 8 * even;
-      at = even;
-      for (x = 0; x < 8; ++x) {
-        const int size = (int)((long)(x + 1) * tiles / 8) - (int)((long)x * tiles / 8);
-        if (size > even && j-- == 0) break;
-      }
-    }
-    slot[T] = (int)((long)x * tiles / 8) + at;
-  }
-}
-
-// slot: position of tile T in the launch (NULL: T itself)
-__global__ void block_plan_kernel(const uint8_t* blk, BlockPlan p, const int* slot, int* pix, int* kb_list, int* kb_cnt) {
-  const int T = blockIdx.x, i = threadIdx.x;
-  const int at = slot ? slot[T] : T;
-  const int part = T % p.tpb, band = (T / p.tpb) % p.RB, n = T / (p.tpb * p.RB);
-  const int in_band = part * p.BN + i, pos = band * p.x + in_band;
-  if (i < p.BN) pix[(long)at * p.BN + i] = (in_band < p.x && pos < p.HoWo) ? n * p.HoWo + pos : -1;
-  if (i == 0) {
-    int cnt = 0;
-    const bool any = part * p.BN < p.x && band * p.x + part * p.BN < p.HoWo;
-    const uint8_t* row = blk + (long)(n * p.RB + band) * p.CB;
-    if (any)
-      for (int tap = 0; tap < p.taps; ++tap)
-        for (int cg = 0; cg < p.CG; ++cg)
-          if (row[cg / p.cg_per_blk]) kb_list[(long)at * p.KB + cnt++] = tap * p.CG + cg;
-    kb_cnt[at] = cnt;
-  }
-}
-
 // The column tile (128 or 256 positions) that wastes the least padding, or 0 when this path does not apply.
 static int block_fast_tile(const ConvArgs& a, const ConvWs& w) {
   const int taps = a.kh * a.kw;
@@ -1240,28 +1256,34 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     const int Cp = pad64(Ck), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
     int32_t st = ARD_OK;
     const PackJob pj = pack_job(Wt, (const int*)d_keep, a.C, taps, a.Cout, Ck, Cp, 0, w.gwp);
+    BlockPlanJob bj{};
+    int bn = 0;
+    if (a.blk) {
+      bn = block_fast_tile(a, w);
+      if (!bn) return fail(ARD_EUNSUPPORTED, "block pattern outside the fast path");  // (callers test block_fast_tile first)
+      bj.p = BlockPlan{a.N, a.Ho * a.Wo, a.bx, ceil_div(a.Ho * a.Wo, a.bx), ceil_div(a.C * taps, a.by), ceil_div(a.bx, bn), bn, taps,
+                       Cp / 64, a.by / (64 * taps), taps * (Cp / 64)};
+      bj.blk = a.blk;
+      bj.tiles = bj.blocks = a.N * bj.p.RB * bj.p.tpb;
+      bj.order = bj.tiles > 256 && bj.tiles <= kBlockOrderMaxTiles;  // (up to one tile per CU there is nothing to order)
+      bj.pix = w.blk_pix, bj.kb_list = w.blk_kb, bj.kb_cnt = w.blk_cnt;
+    }
     if (!(a.reuse & ARD_CONV_REUSE_A)) {
-      st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{}, pj);
+      // (the packed weights and the tile plan of a block pattern ride in the copy's launch)
+      st = to_grid(A, d_keep, Ck, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{}, pj,
+                   ZeroPlanesJob{}, ZeroPixelsJob{}, bj);
     } else {
       ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
       ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
+      if (bj.blocks) {
+        ARD_LAUNCH(block_plan_kernel, dim3((unsigned)bj.blocks), dim3(256), 0, stream, bj);
+        ARD_LAUNCH_CHECK("block_plan_kernel");
+      }
     }
     if (st) return st;
     if (a.blk) {
-      const int bn = block_fast_tile(a, w);
-      if (!bn) return fail(ARD_EUNSUPPORTED, "block pattern outside the fast path");  // (callers test block_fast_tile first)
-      BlockPlan bp{a.N, a.Ho * a.Wo, a.bx, ceil_div(a.Ho * a.Wo, a.bx), ceil_div(a.C * taps, a.by), ceil_div(a.bx, bn), bn, taps,
-                   Cp / 64, a.by / (64 * taps), taps * (Cp / 64)};
-      const int tiles = a.N * bp.RB * bp.tpb;
-      int* slot = nullptr;
-      if (tiles > 256 && tiles <= kBlockOrderMaxTiles) {  // (up to one tile per CU there is nothing to order)
-        slot = w.blk_cnt + tiles;
-        ARD_LAUNCH(block_order_kernel, dim3(1), dim3(1024), 0, stream, a.blk, bp, tiles, slot);
-        ARD_LAUNCH_CHECK("block_order_kernel");
-      }
-      ARD_LAUNCH(block_plan_kernel, dim3((unsigned)tiles), dim3(bn), 0, stream, a.blk, bp, (const int*)slot, w.blk_pix, w.blk_kb,
-                 w.blk_cnt);
-      ARD_LAUNCH_CHECK("block_plan_kernel");
+      const BlockPlan& bp = bj.p;
+      const int tiles = bj.tiles;
       // bands of an even number of positions in planes of an even size: the tiles hold whole pairs of neighbours
       const int pairs = (a.bx % 2 == 0) && ((a.Ho * a.Wo) % 2 == 0);
       ConvMap cv{a.Ho * a.Wo, a.Wo, Hg * Wg, Wg, Cp, a.kw, tiles * bn, a.Cout, nullptr, a.Cout, w.blk_pix, a.N * a.Ho * a.Wo, -1, pairs};
