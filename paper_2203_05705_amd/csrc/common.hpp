@@ -160,4 +160,23 @@ int kept_count(const ard_pattern* p, int units);
 // logical->physical map of a ROW / LIST / NONE pattern over `units`
 Axis axis_of_pattern(const ard_pattern* p, int units);
 
+// Exact unsigned division by a divisor known on the host (multiply-high and shifts instead of the 30-odd
+// instructions of a division by a run-time value).
+struct FastDiv {
+  uint32_t mul;
+  int shift;  // -1: divisor 1
+};
+static FastDiv fast_div(uint32_t d) {
+  if (d <= 1) return FastDiv{0u, -1};
+  int l = 0;
+  while ((1ull << l) < d) ++l;  // ceil(log2 d) >= 1
+  const uint64_t m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+  return FastDiv{(uint32_t)m, l - 1};
+}
+static __device__ __forceinline__ uint32_t fdiv(uint32_t a, const FastDiv& f) {
+  if (f.shift < 0) return a;
+  const uint32_t t = __umulhi(a, f.mul);
+  return (t + ((a - t) >> 1)) >> f.shift;
+}
+
 }  // namespace ard

@@ -809,9 +809,9 @@ __device__ __forceinline__ void block_plan_body(const BlockPlanJob& j, int T, in
     const bool any = part * p.BN < p.x && band * p.x + part * p.BN < p.HoWo;
     const uint8_t* row = j.blk + (long)(n * p.RB + band) * p.CB;
     if (any)
-      for (int tap = 0; tap < p.taps; ++tap)
-        for (int cg = 0; cg < p.CG; ++cg)
-          if (row[cg / p.cg_per_blk]) j.kb_list[(long)at * p.KB + cnt++] = tap * p.CG + cg;
+      for (int cg = 0; cg < p.CG; ++cg)  // (all taps of a channel group in a row: they share their lines in L2)
+        if (row[cg / p.cg_per_blk])
+          for (int tap = 0; tap < p.taps; ++tap) j.kb_list[(long)at * p.KB + cnt++] = tap * p.CG + cg;
     j.kb_cnt[at] = cnt;
   }
 }
@@ -847,15 +847,19 @@ static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int ro
 }
 
 // The same copy driven from the source side, for planes that are whole numbers of 16-byte pieces:
-// a workgroup reads 64 channels x 64 source pixels with 16-byte loads (8 pixels of one channel
-// each), transposes through LDS and writes each pixel's 64 channels as 128 contiguous bytes.
-// Border pixels, the margin behind the last image and nothing else are left to the zero pass
-// that every workgroup also runs over its share [zb, ze) of the grid's pixels.
+// a workgroup reads 64 channels x 64 source pixels with 16-byte loads (a thread takes 8 pixels of two
+// neighbouring channels), pairs the channels in registers, transposes the pairs through LDS and writes each
+// pixel's 64 channels as 128 contiguous bytes.  The border pixels of an image are dealt to the image's
+// workgroups and the margin behind the last image to all of them: every pixel of the grid is written once.
+// LDS holds [pixel row][32 channel pairs] without padding: pixel 8q + e sits in row 8e + q and its 16-byte
+// groups are exchanged by q's upper bits, which spreads both the 4-byte stores of a wave and its 16-byte
+// loads over all banks.
 __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
-                                                          int Ws, int Hg, int Wg, int oh, int ow, int Cp, int N,
+                                                          int Ws, FastDiv div_ws, int Hg, int Wg, int oh, int ow, int Cp,
+                                                          int N,
                                                           long n_pix_total, BandMask bm, uint16_t* dst, PackJob pj,
                                                           ZeroPlanesJob zj, ZeroPixelsJob zp, BlockPlanJob bj, int main_x) {
-  __shared__ uint16_t tile[64][72];  // [channel][pixel], rows 144 bytes apart
+  __shared__ uint32_t tile[64 * 32];
   __shared__ int red4[4];
   // (workgroups beyond the copy's own pack the weights of the product that follows and zero the planes it will
   // not write: independent small jobs that would otherwise be launches of their own)
@@ -869,7 +873,12 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
   }
   const int HW = Hs * Ws;
   const int px_tiles = (HW + 63) / 64;
-  const int n = blockIdx.x / px_tiles, p0 = (blockIdx.x - n * px_tiles) * 64;
+  // Channel rows start at any multiple of 2 * HW bytes, so a tile's 128-byte runs straddle cache lines that the
+  // neighbouring pixel tile reads too.  Workgroups are dealt to the 8 XCDs in turn: XCD x takes the x-th eighth
+  // of the tiles in order, so the second read of a line finds it in that XCD's L2 (half the fetched bytes).
+  const int even = main_x / 8;
+  const int m = (int)blockIdx.x < 8 * even ? ((int)blockIdx.x & 7) * even + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+  const int n = m / px_tiles, tile_j = m - n * px_tiles, p0 = tile_j * 64;
   const int c0 = blockIdx.y * 64;
   const int t = threadIdx.x;
   // masked copy: which of the tile's 64 pixels count is the same for all of its channels, looked up once
@@ -885,49 +894,58 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     }
     __syncthreads();
   }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int u = t + 256 * i;             // 512 pieces: 64 channels x 8 pieces of 8 pixels
-    const int cl = u >> 3, q = u & 7;
-    const int c = c0 + cl, p = p0 + q * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (c < n_chan && p < HW) v = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
+  {
+    const int cp = t >> 3, q = t & 7;  // channel pair, piece of 8 pixels
+    const int c = c0 + 2 * cp, p = p0 + q * 8;
+    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    if (p < HW) {
+      if (c < n_chan) v0 = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
+      if (c + 1 < n_chan) v1 = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c + 1] : c + 1)) * HW + p);
+    }
+    uint32_t lo[4] = {v0.x, v0.y, v0.z, v0.w}, hi[4] = {v1.x, v1.y, v1.z, v1.w};
     if (bm.blk) {
       const unsigned bits = piece_keep[q];
-      uint32_t w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        if (!((bits >> e) & 1)) w4[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-      v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        if (!((bits >> e) & 1)) {
+          lo[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+          hi[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+        }
     }
-    *reinterpret_cast<uint4*>(&tile[cl][q * 8]) = v;
+    const int col = (((cp >> 2) ^ (q & 6)) << 2) | (cp & 3);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)  // pixel e of the piece: channel c in the low half, c + 1 in the high half
+      tile[(e * 8 + q) * 32 + col] = __builtin_amdgcn_perm(hi[e >> 1], lo[e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
   }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int pl = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
-    const int p = p0 + pl;
+    const int r = (t >> 3) + 32 * i, c8 = t & 7;  // LDS row, group of 8 channels
+    const int q = r & 7, p = p0 + 8 * q + (r >> 3);
     if (p >= HW) continue;
-    const int h = p / Ws, w = p - h * Ws;
+    const int h = (int)fdiv((uint32_t)p, div_ws), w = p - h * Ws;
     const long g = ((long)n * Hg + h + oh) * Wg + w + ow;
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = (uint32_t)tile[c8 + 2 * e][pl] | ((uint32_t)tile[c8 + 2 * e + 1][pl] << 16);
-    *reinterpret_cast<uint4*>(dst + g * Cp + c0 + c8) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint4*>(dst + g * Cp + c0 + c8 * 8) = *reinterpret_cast<const uint4*>(&tile[r * 32 + ((c8 ^ (q & 6)) << 2)]);
   }
-  // zero pass: this workgroup's share of the grid pixels, for its 64 channels
-  const long nblk = (long)main_x, per = (n_pix_total + nblk - 1) / nblk;
-  const long zb = blockIdx.x * per, ze = zb + per < n_pix_total ? zb + per : n_pix_total;
-  const long valid = (long)N * Hg * Wg;
-  for (long g = zb + (t >> 3); g < ze; g += 32) {
-    bool border = g >= valid;
-    if (!border) {
-      const int rem = (int)(g % ((long)Hg * Wg));
-      const int h = rem / Wg - oh, w = rem % Wg - ow;
-      border = h < 0 || h >= Hs || w < 0 || w >= Ws;
+  // zero pass, for this workgroup's 64 channels.  The border of image n: `top` whole rows above, `bot` below,
+  // then per image row ow pixels on the left and the rest of `side` on the right; border index b of the image
+  // belongs to workgroup b * px_tiles / B of the image's px_tiles.
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+  const int top = oh * Wg, bot = (Hg - oh - Hs) * Wg, side = Wg - Ws, B = top + bot + Hs * side;
+  const int b0 = (int)((long)tile_j * B / px_tiles), b1 = (int)((long)(tile_j + 1) * B / px_tiles);
+  for (int b = b0 + (t >> 3); b < b1; b += 32) {
+    int pos;
+    if (b < top) pos = b;
+    else if (b < top + bot) pos = (oh + Hs) * Wg + (b - top);
+    else {
+      const int s = b - top - bot, row = s / (side > 0 ? side : 1), k = s - row * side;
+      pos = (oh + row) * Wg + (k < ow ? k : k + Ws);
     }
-    if (border) *reinterpret_cast<uint4*>(dst + g * Cp + c0 + (t & 7) * 8) = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(dst + ((long)n * Hg * Wg + pos) * Cp + c0 + (t & 7) * 8) = zero;
   }
+  // the margin behind the last image, 32 pixels per workgroup
+  for (long g = (long)N * Hg * Wg + (long)blockIdx.x * 32 + (t >> 3); g < n_pix_total; g += (long)main_x * 32)
+    *reinterpret_cast<uint4*>(dst + g * Cp + c0 + (t & 7) * 8) = zero;
 }
 
 
@@ -1125,12 +1143,13 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
                        PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}, ZeroPixelsJob zp = ZeroPixelsJob{},
                        BlockPlanJob bj = BlockPlanJob{}) {
   const long valid = (long)N * Hg * Wg, total = valid + margin;
+  if (oh < 0 || ow < 0 || Hg < oh + Hs || Wg < ow + Ws) return fail(ARD_EINVAL, "grid copy: the image does not fit the grid");
   if (((Hs * Ws) % 8) == 0 && al16c(src)) {
     const int main_x = N * ceil_div(Hs * Ws, 64);
     const int gy = Cp / 64;
     dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks + bj.blocks, gy)), (unsigned)gy);
-    ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg,
-                       Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, bj, main_x);
+    ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws,
+               fast_div((uint32_t)Ws), Hg, Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, bj, main_x);
     ARD_LAUNCH_CHECK("to_grid_src_kernel");
     return ARD_OK;
   }

@@ -507,12 +507,17 @@ __host__ __device__ __forceinline__ bool direct_assign(const FastParams& P, int 
 // (MODE 1: slab (tap, c0) of the im2col row = offset of the tap's pixel plus the channel).
 template <int MODE>
 __host__ __device__ __forceinline__ void direct_slab(const FastParams& P, const Axis& kax, int s, int& ks, int& ksb) {
+  if constexpr (MODE == 1) {
+    // The steps run channel group by channel group, all taps of a group in a row: consecutive steps then read
+    // the same 128 bytes of pixels that lie a few positions apart, nearly all of them lines the step before
+    // left in L2 (tap by tap, a whole pass over the tile's channels lies between two reads of a line).
+    const int taps = kax.nphys / P.cv.Cp, cg = s / taps, t = s - cg * taps;
+    ks = t * P.cv.Cp + cg * 64;
+    ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + cg * 64;
+    return;
+  }
   ks = fast_kslab(kax, s * 64);
   ksb = ks;
-  if constexpr (MODE == 1) {
-    const int t = ks / P.cv.Cp;
-    ksb = ((t / P.cv.kw) * P.cv.Wg + t % P.cv.kw) * P.cv.Cp + (ks - t * P.cv.Cp);
-  }
 }
 
 // MODE 0: plain product.  MODE 1: convolution, B rows are output pixels gathered from the

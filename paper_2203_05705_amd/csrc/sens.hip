@@ -84,25 +84,6 @@ __global__ __launch_bounds__(256) void sens_predict_kernel(const T* A, SensGeom 
   }
 }
 
-// Exact unsigned division by a divisor known on the host (multiply-high and shifts instead of the 30-odd
-// instructions of a division by a run-time value).
-struct FastDiv {
-  uint32_t mul;
-  int shift;  // -1: divisor 1
-};
-static FastDiv fast_div(uint32_t d) {
-  if (d <= 1) return FastDiv{0u, -1};
-  int l = 0;
-  while ((1ull << l) < d) ++l;  // ceil(log2 d) >= 1
-  const uint64_t m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
-  return FastDiv{(uint32_t)m, l - 1};
-}
-static __device__ __forceinline__ uint32_t fdiv(uint32_t a, const FastDiv& f) {
-  if (f.shift < 0) return a;
-  const uint32_t t = __umulhi(a, f.mul);
-  return (t + ((a - t) >> 1)) >> f.shift;
-}
-
 // The same prediction with the region's geometry tabulated in LDS once per workgroup: per column of the
 // region its channel's offset in the image and its tap (kh, kw), per row of the band its top-left input
 // position.  A draw is then the mixer, one division by the region's width, two LDS reads and the gather.
