@@ -706,6 +706,7 @@ struct ZeroPixelsJob {
   const uint8_t* row_mask;
   int Cout, HW;
   int blocks;  // N * ceil(Cout / ZPX) workgroups of 256 threads (0: no job)
+  int all;     // 1: zero every position (a plain stream of 16-byte stores; the product that follows writes the kept ones)
 };
 __device__ __forceinline__ void zero_dropped_pixels_body(const ZeroPixelsJob& z, int block) {
   const int cgs = (z.Cout + ZPX - 1) / ZPX;
@@ -714,7 +715,10 @@ __device__ __forceinline__ void zero_dropped_pixels_body(const ZeroPixelsJob& z,
   uint16_t* p = z.Y + ((long)n * z.Cout + co0) * z.HW;
   const uint8_t* m = z.row_mask + (long)n * z.HW;
   const bool vec = (z.HW % 8) == 0 && (((uintptr_t)z.Y | (uintptr_t)z.row_mask) & 15) == 0;
-  if (vec) {
+  if (z.all) {  // (host: only with HW % 8 == 0 and Y on a 16-byte boundary)
+    uint4* dst = reinterpret_cast<uint4*>(p);
+    for (int i = threadIdx.x; i < nco * (z.HW >> 3); i += 256) dst[i] = make_uint4(0, 0, 0, 0);
+  } else if (vec) {
     const int chunks = z.HW >> 3;
     for (int i = threadIdx.x; i < nco * chunks; i += 256) {
       const int c = i / chunks, q = (i - c * chunks) * 8;
@@ -1203,8 +1207,12 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
     bm = force_bn == 128 || rows > 128 ? 256 : 128;
     bn = force_bn;
   } else if (rows > 128) {
+    // One workgroup of either shape fills a CU, so a launch runs in rounds of 256 tiles; a round of 256 x 128
+    // tiles takes about 0.68 of a round of 256 x 256 (measured on the 3x3 layers): fewest rounds x cost wins.
     bm = 256;
-    bn = (long)ceil_div(rows, 256) * ceil_div(cv.npix, 256) >= 220 ? 256 : 128;
+    const long tm = ceil_div(rows, 256);
+    const long r256 = ceil_div(tm * ceil_div(cv.npix, 256), 256L), r128 = ceil_div(tm * ceil_div(cv.npix, 128), 256L);
+    bn = r256 * 100 <= r128 * 68 ? 256 : 128;
   } else if (rows > 64) {
     bm = 128;
     bn = 256;
@@ -1263,7 +1271,9 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
     // every channel, only the kept output positions: the product's columns are the listed pixels
     const int Cp = pad64(a.C), Hg = a.H + 2 * a.pad, Wg = a.W + 2 * a.pad, K = taps * Cp;
     // (the zeros of the dropped positions and the packed weights ride in the copy's launch)
-    const ZeroPixelsJob zp{(uint16_t*)out, row_mask, a.Cout, a.Ho * a.Wo, a.N * ceil_div(a.Cout, ZPX)};
+    // (with few rows kept, zeros everywhere as one stream cost less than the masked stores of the dropped ones)
+    const int fill_all = ((a.Ho * a.Wo) % 8) == 0 && al16c(out) && (long)Ck * 10 <= (long)a.N * a.Ho * a.Wo * 7;
+    const ZeroPixelsJob zp{(uint16_t*)out, row_mask, a.Cout, a.Ho * a.Wo, a.N * ceil_div(a.Cout, ZPX), fill_all};
     int32_t st = to_grid(A, nullptr, a.C, a.C, a.H, a.W, a.N, Hg, Wg, a.pad, a.pad, Cp, margin, w.grid_a, stream, BandMask{},
                          pack_job(Wt, nullptr, a.C, taps, a.Cout, a.C, Cp, 0, w.gwp), ZeroPlanesJob{}, zp);
     if (st) return st;
