@@ -813,6 +813,58 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
     const bool odd = lane & 1;
     // (listed pixels are not adjacent unless the list says so)
     const bool pair_ok = ((HW & 1) == 0) && (((uintptr_t)P.C & 3) == 0) && (!cv.pix || cv.pix_pairs);
+    // Consecutive pixels in planes of whole 16-byte pieces: the tile goes through LDS (the operand stages are
+    // dead by now) as bf16 [row][BN pixels] and leaves as 16-byte stores, a row of the tile one contiguous run
+    // of 2 BN bytes of its channel's plane (straight from the registers a store instruction writes runs of 64).
+    // Rows lie 2 BN bytes apart; the 16-byte pieces of a row are exchanged by two bits of its number, so the
+    // four rows one store instruction of a wave touches land on different banks.
+    if (!cv.pix && (HW & 7) == 0 && (((uintptr_t)P.C & 15) == 0)) {
+      constexpr int CH = BN / 8;                               // 16-byte pieces per row
+      constexpr int NT = 64 * NW;
+      static_assert(NT % CH == 0, "whole rows per pass");
+      static_assert(F_BM * BN * 2 <= NST * (F_BM + BN) * LDS_ROW_U4 * 16, "the staged tile fits the operand stages");
+      char* const tile = reinterpret_cast<char*>(lds);
+      auto piece_of = [](int row, int piece) { return piece ^ ((((row & 1) << 2) | (((row >> 2) & 1) << 3)) & (CH - 1)); };
+      __syncthreads();
+#pragma unroll
+      for (int in = 0; in < TN; ++in) {
+        const int lj = wn * WTN + in * 32 + (lane & 31);
+#pragma unroll
+        for (int im = 0; im < TM; ++im) {
+          const int li0 = wm * WTM + im * 32 + 4 * (lane >> 5);
+#pragma unroll
+          for (int v = 0; v < 16; v += 2) {
+            float x0 = P.alpha * acc[im][in][v], x1 = P.alpha * acc[im][in][v + 1];
+            if (P.relu) {
+              x0 = fmaxf(x0, 0.0f);
+              x1 = fmaxf(x1, 0.0f);
+            }
+            const uint32_t b01 = pack_bf16x2(x0, x1);
+            const uint32_t b0 = b01 & 0xffffu, b1 = b01 >> 16;
+            // the even lane keeps row v of its own and its neighbour's pixel, the odd lane row v + 1
+            const uint32_t send = odd ? b0 : b1;
+            const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, true);
+            const uint32_t word = odd ? (got | (b1 << 16)) : (b0 | (got << 16));
+            const int row = li0 + 8 * (v >> 2) + (v & 3) + (odd ? 1 : 0);
+            const int w = lj >> 1;  // word of the row: pixels 2w, 2w + 1
+            *reinterpret_cast<uint32_t*>(tile + row * (BN * 2) + piece_of(row, w >> 2) * 16 + (w & 3) * 4) = word;
+          }
+        }
+      }
+      __syncthreads();
+      const int piece = tid % CH;
+      const int jc = n0 + piece * 8;
+      if (jc >= cv.npix) return;  // (npix is a multiple of 8 here: a piece is in or out as a whole)
+      const int n = jc / HW;
+      uint16_t* const col = P.C + (long)n * cv.out_chan * HW + (jc - n * HW);
+      for (int r = tid / CH; r < F_BM; r += NT / CH) {
+        const int i = m0 + r;
+        if (i >= cv.n_rows) break;
+        const int ch = cv.chan ? cv.chan[i] : i;
+        *reinterpret_cast<uint4*>(col + (long)ch * HW) = *reinterpret_cast<const uint4*>(tile + r * (BN * 2) + piece_of(r, piece) * 16);
+      }
+      return;
+    }
 #pragma unroll
     for (int in = 0; in < TN; ++in) {
       const int jc = n0 + wn * WTN + in * 32 + (lane & 31);
