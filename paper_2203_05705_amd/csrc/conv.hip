@@ -622,44 +622,6 @@ __device__ __forceinline__ bool band_kept(const BandMask& m, int n, int p) {
   return !m.blk || m.blk[((long)n * m.RB + p / m.x) * m.CB + m.cb] != 0;
 }
 
-// dst tile of 64 grid pixels x 64 channels per workgroup: read along pixels, write along channels
-__global__ __launch_bounds__(256) void to_grid_kernel(const uint16_t* src, const int* chan, int n_chan, int Cs, int Hs,
-                                                      int Ws, int Hg, int Wg, int oh, int ow, int Cp, long n_pix_valid,
-                                                      long n_pix_total, BandMask bm, uint16_t* dst) {
-  __shared__ uint16_t tile[64][66];
-  const long p0 = (long)blockIdx.x * 64;
-  const int c0 = blockIdx.y * 64;
-  const int t = threadIdx.x;
-  {
-    const int pl = t & 63;
-    const long p = p0 + pl;
-    long off = -1;
-    if (p < n_pix_valid) {
-      const int n = (int)(p / ((long)Hg * Wg)), rem = (int)(p - (long)n * Hg * Wg);
-      const int h = rem / Wg - oh, w = rem % Wg - ow;
-      if (h >= 0 && h < Hs && w >= 0 && w < Ws && band_kept(bm, n, h * Ws + w)) off = ((long)n * Cs * Hs + h) * Ws + w;
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int cl = (t >> 6) + 4 * i, c = c0 + cl;
-      uint16_t v = 0;
-      if (off >= 0 && c < n_chan) v = src[off + (long)(chan ? chan[c] : c) * Hs * Ws];
-      tile[cl][pl] = v;
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int pl = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
-    const long p = p0 + pl;
-    if (p >= n_pix_total) continue;
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[c8 + 2 * e][pl] | ((uint32_t)tile[c8 + 2 * e + 1][pl] << 16);
-    *reinterpret_cast<uint4*>(dst + p * Cp + c0 + c8) = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
-
 // position of channel c in the ascending kept list, or -1 (uniform per workgroup where c is)
 __device__ __forceinline__ int kept_rank(const int* keep, int n_keep, int c) {
   int lo = 0, hi = n_keep - 1;
@@ -850,7 +812,23 @@ static PackJob pack_job(const void* Wt, const int* keep, int C, int taps, int ro
   return PackJob{(const uint16_t*)Wt, keep, C, taps, rows, inner, Cp, flip, out, (int)(((long)rows * taps * Cp + 255) / 256)};
 }
 
-// The same copy driven from the source side, for planes that are whole numbers of 16-byte pieces:
+// 8 neighbouring pixels of one channel plane, of which the first `valid` exist: one 16-byte load where the
+// address allows it, two 8-byte loads or element by element elsewhere (planes of 14 x 14 or 7 x 7 positions
+// do not start on 16-byte boundaries)
+__device__ __forceinline__ uint4 load_pixels8(const uint16_t* p, int valid) {
+  if (valid >= 8 && (((uintptr_t)p) & 15) == 0) return *reinterpret_cast<const uint4*>(p);
+  if (valid >= 8 && (((uintptr_t)p) & 7) == 0) {
+    const uint2 a = *reinterpret_cast<const uint2*>(p), b = *reinterpret_cast<const uint2*>(p + 4);
+    return make_uint4(a.x, a.y, b.x, b.y);
+  }
+  uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    if (e < valid) w[e >> 1] |= (uint32_t)p[e] << ((e & 1) * 16);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The copy, driven from the source side:
 // a workgroup reads 64 channels x 64 source pixels with 16-byte loads (a thread takes 8 pixels of two
 // neighbouring channels), pairs the channels in registers, transposes the pairs through LDS and writes each
 // pixel's 64 channels as 128 contiguous bytes.  The border pixels of an image are dealt to the image's
@@ -903,8 +881,8 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     const int c = c0 + 2 * cp, p = p0 + q * 8;
     uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
     if (p < HW) {
-      if (c < n_chan) v0 = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p);
-      if (c + 1 < n_chan) v1 = *reinterpret_cast<const uint4*>(src + ((long)n * Cs + (chan ? chan[c + 1] : c + 1)) * HW + p);
+      if (c < n_chan) v0 = load_pixels8(src + ((long)n * Cs + (chan ? chan[c] : c)) * HW + p, HW - p);
+      if (c + 1 < n_chan) v1 = load_pixels8(src + ((long)n * Cs + (chan ? chan[c + 1] : c + 1)) * HW + p, HW - p);
     }
     uint32_t lo[4] = {v0.x, v0.y, v0.z, v0.w}, hi[4] = {v1.x, v1.y, v1.z, v1.w};
     if (bm.blk) {
@@ -1146,37 +1124,14 @@ static int32_t to_grid(const void* src, const int* chan, int n_chan, int Cs, int
                        int ow, int Cp, long margin, uint16_t* dst, hipStream_t stream, BandMask bm = BandMask{},
                        PackJob pj = PackJob{}, ZeroPlanesJob zj = ZeroPlanesJob{}, ZeroPixelsJob zp = ZeroPixelsJob{},
                        BlockPlanJob bj = BlockPlanJob{}) {
-  const long valid = (long)N * Hg * Wg, total = valid + margin;
+  const long total = (long)N * Hg * Wg + margin;
   if (oh < 0 || ow < 0 || Hg < oh + Hs || Wg < ow + Ws) return fail(ARD_EINVAL, "grid copy: the image does not fit the grid");
-  if (((Hs * Ws) % 8) == 0 && al16c(src)) {
-    const int main_x = N * ceil_div(Hs * Ws, 64);
-    const int gy = Cp / 64;
-    dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks + bj.blocks, gy)), (unsigned)gy);
-    ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws,
-               fast_div((uint32_t)Ws), Hg, Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, bj, main_x);
-    ARD_LAUNCH_CHECK("to_grid_src_kernel");
-    return ARD_OK;
-  }
-  if (pj.blocks) {
-    ARD_LAUNCH(pack_weights_grid_kernel, dim3((unsigned)pj.blocks), dim3(256), 0, stream, pj);
-    ARD_LAUNCH_CHECK("pack_weights_grid_kernel");
-  }
-  if (zj.blocks) {
-    ARD_LAUNCH(zero_dropped_planes_kernel, dim3((unsigned)zj.blocks), dim3(256), 0, stream, zj);
-    ARD_LAUNCH_CHECK("zero_dropped_planes_kernel");
-  }
-  if (zp.blocks) {
-    ARD_LAUNCH(zero_dropped_pixels_grid_kernel, dim3((unsigned)zp.blocks), dim3(256), 0, stream, zp);
-    ARD_LAUNCH_CHECK("zero_dropped_pixels_grid_kernel");
-  }
-  if (bj.blocks) {
-    ARD_LAUNCH(block_plan_kernel, dim3((unsigned)bj.blocks), dim3(256), 0, stream, bj);
-    ARD_LAUNCH_CHECK("block_plan_kernel");
-  }
-  dim3 grid((unsigned)((total + 63) / 64), (unsigned)(Cp / 64));
-  ARD_LAUNCH(to_grid_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws, Hg, Wg, oh,
-                     ow, Cp, valid, total, bm, dst);
-  ARD_LAUNCH_CHECK("to_grid_kernel");
+  const int main_x = N * ceil_div(Hs * Ws, 64);
+  const int gy = Cp / 64;
+  dim3 grid((unsigned)(main_x + ceil_div(pj.blocks + zj.blocks + zp.blocks + bj.blocks, gy)), (unsigned)gy);
+  ARD_LAUNCH(to_grid_src_kernel, grid, dim3(256), 0, stream, (const uint16_t*)src, chan, n_chan, Cs, Hs, Ws,
+             fast_div((uint32_t)Ws), Hg, Wg, oh, ow, Cp, N, total, bm, dst, pj, zj, zp, bj, main_x);
+  ARD_LAUNCH_CHECK("to_grid_src_kernel");
   return ARD_OK;
 }
 
@@ -1206,18 +1161,23 @@ static int32_t conv_grid_gemm(const uint16_t* Wp, int rows, int K, const uint16_
   if (force_bn) {
     bm = force_bn == 128 || rows > 128 ? 256 : 128;
     bn = force_bn;
-  } else if (rows > 128) {
-    // One workgroup of either shape fills a CU, so a launch runs in rounds of 256 tiles; a round of 256 x 128
-    // tiles takes about 0.68 of a round of 256 x 256 (measured on the 3x3 layers): fewest rounds x cost wins.
-    bm = 256;
-    const long tm = ceil_div(rows, 256);
-    const long r256 = ceil_div(tm * ceil_div(cv.npix, 256), 256L), r128 = ceil_div(tm * ceil_div(cv.npix, 128), 256L);
-    bn = r256 * 100 <= r128 * 68 ? 256 : 128;
-  } else if (rows > 64) {
-    bm = 128;
-    bn = 256;
   } else {
+    // A launch runs in rounds: one workgroup of a large shape fills a CU (256 at a time), three of the 64 x 64
+    // shape share one (768 at a time).  Measured on the 3x3 layers, a round of 256 x 128 or 128 x 256 tiles
+    // takes 0.68 and a round of 64 x 64 tiles 0.34 of a round of 256 x 256 tiles: fewest rounds x cost wins
+    // (so a layer with few output positions goes to small tiles on many CUs instead of large ones on a few).
+    const auto rounds = [&](int tm, int tn, long slots) { return ((long)ceil_div(rows, tm) * ceil_div(cv.npix, tn) + slots - 1) / slots; };
+    long best = rounds(64, 64, 768) * 34;
     bm = bn = 64;
+    if (rows > 64) {
+      const long c = rounds(128, 256, 256) * 68;
+      if (c <= best) best = c, bm = 128, bn = 256;
+    }
+    if (rows > 128) {
+      const long c1 = rounds(256, 128, 256) * 68, c2 = rounds(256, 256, 256) * 100;
+      if (c1 <= best) best = c1, bm = 256, bn = 128;
+      if (c2 <= best) best = c2, bm = 256, bn = 256;
+    }
   }
   F.tiles_m = ceil_div(rows, bm);
   F.tiles_n = ceil_div(cv.npix, bn);

@@ -105,9 +105,8 @@ def test_lstm_and_conv_shapes():
 
 def test_block_pattern_dispatch_and_bounds():
     """Forward pass under the block pattern: blocks of whole 64-channel groups over all taps with bands of at
-    least half a tile go to the LDS-direct kernel (tile plan in the copy's launch, or in one of its own when the
-    copy takes the unaligned route; per-tile block lists, proof over the whole contraction); any other block
-    shape goes to the general engine."""
+    least half a tile go to the LDS-direct kernel (tile plan in the copy's launch, per-tile block lists, proof
+    over the whole contraction); any other block shape goes to the general engine."""
     with D.dry_run() as lib:
         heap = D.FakeHeap()
         for (N, Cc, Cout, H, W, k, pad, x, y), fast in [((128, 256, 256, 28, 28, 3, 1, 112, 576), True),
@@ -133,8 +132,8 @@ def test_block_pattern_dispatch_and_bounds():
             names = D.launches(lib)[1]
             assert ("gemm_direct_kernel" in names) == fast, (N, Cc, Cout, x, y, names)
             assert ("conv_gemm_kernel" in names) == (not fast)
-            if fast:   # the plan rides in the aligned copy, else it is a launch of its own
-                assert ("block_plan_kernel" in names) == ((H * W) % 8 != 0), (H, W, names)
+            if fast:   # the plan rides in the copy's launch
+                assert "block_plan_kernel" not in names and "to_grid_src_kernel" in names, (H, W, names)
             if fast:
                 nb, six = D.last_bounds(lib)
                 assert nb == 1 and 0 <= six[0] < six[1] <= six[2] and 0 <= six[3] < six[4] <= six[5]
