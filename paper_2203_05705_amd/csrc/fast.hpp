@@ -1157,7 +1157,9 @@ static __device__ __forceinline__ void zero_rows_body(const ZeroRowsArgs& a, con
   const int per_row = a.vec ? a.cols >> 3 : a.cols;
   const long total = (long)dropped * per_row;
   for (long e = (long)bx * 256 + threadIdx.x; e < total; e += (long)nblocks * 256) {
-    const int d = (int)(e / per_row), c = (int)(e - (long)d * per_row);
+    // (a 64-bit division costs several times a 32-bit one, and nearly every matrix stays below 2^32 pieces)
+    const int d = total < (1L << 32) ? (int)((uint32_t)e / (uint32_t)per_row) : (int)(e / per_row);
+    const int c = (int)(e - (long)d * per_row);
     // d-th dropped row: rows before `off` come first, then step - 1 per group, then the tail
     int r;
     if (d < a.off) {
