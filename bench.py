@@ -706,6 +706,32 @@ def extra_conv(ard, torch, rooflines):
     dense = min(sum(res["rate0.0"][k]["us"] for k in ("fwd", "bwd_data", "bwd_weight")),
                 res["vendor_dense_us"]["fwd"] + res["vendor_dense_us"]["bwd_data_plus_weight"])
     res["speedup_vs_dense_rate0.5"] = round(dense / ours, 3)
+    del Ag, Wg, Y
+    # the same three passes on other 3x3 layer shapes (seeded random tensors; planes of 14 x 14 and 7 x 7 positions
+    # are not whole numbers of 16-byte pieces, 7 x 7 leaves few output positions per image)
+    other = {}
+    for (n_, c_, h_, co_) in ((128, 512, 14, 512), (128, 512, 7, 512), (64, 128, 56, 128)):
+        g = torch.Generator(device="cuda").manual_seed(SEED)
+        A2 = torch.randn(n_, c_, h_, h_, device="cuda", generator=g).to(torch.bfloat16)
+        dY2 = torch.randn(n_, co_, h_, h_, device="cuda", generator=g).to(torch.bfloat16)
+        W2 = (torch.randn(co_, c_, 3, 3, device="cuda", generator=g) * 0.05).to(torch.bfloat16)
+        ws2 = torch.empty(ard.conv_workspace_bytes(ard.BF16, n_, c_, h_, h_, co_, 3, 3, 1, 1), dtype=torch.uint8, device="cuda")
+        row = {}
+        for rate in (0.0, 0.5):
+            sel = ard.conv_select(A2, rate, ws=ws2)
+            nk = int(sel["count"].item())
+            Yo = ard.conv_fwd(A2, W2, sel["keep"], nk, ws=ws2)
+            dAo = ard.conv_bwd_data(dY2, W2, sel["keep"], nk, (h_, h_), ws=ws2)
+            dWo = ard.conv_bwd_weight(dY2, A2, sel["keep"], nk, ws=ws2)
+            both = ard.CONV_REUSE_A | ard.CONV_REUSE_DY
+            row[f"rate{rate}"] = {
+                "fwd": round(event_us(torch, lambda: ard.conv_fwd(A2, W2, sel["keep"], nk, ws=ws2, out=Yo), reps=5, warm=2)["median"], 1),
+                "bwd_data": round(event_us(torch, lambda: ard.conv_bwd_data(dY2, W2, sel["keep"], nk, (h_, h_), ws=ws2, out=dAo), reps=5, warm=2)["median"], 1),
+                "bwd_weight": round(event_us(torch, lambda: ard.conv_bwd_weight(dY2, A2, sel["keep"], nk, ws=ws2, out=dWo, reuse=both), reps=5, warm=2)["median"], 1)}
+        row["speedup_rate0.5"] = round(sum(row["rate0.0"].values()) / sum(row["rate0.5"].values()), 3)
+        other[f"N{n_}_C{c_}_{h_}x{h_}_Cout{co_}_us"] = row
+        del A2, dY2, W2, ws2
+    res["other_layer_shapes"] = other
     return res
 
 
