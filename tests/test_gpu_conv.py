@@ -84,6 +84,8 @@ def _check_grid_sharing(Ad, Wd, dYd, keep, cnt, k, pad, Y, dA, dW):
     (5, 24, 130, 10, 12, 3, 1, 1, 0.75),    # more than one row tile
     (2, 8, 16, 9, 9, 3, 1, 0, 0.5),         # no padding: the output is smaller than the input
     (3, 8, 12, 8, 10, 5, 1, 1, 0.25),       # 5x5 with pad 1
+    (32, 128, 192, 14, 14, 3, 1, 1, 0.5),   # planes of 196 positions (8-byte pieces), several column tiles
+    (64, 192, 160, 7, 7, 3, 1, 1, 0.5),     # planes of 49 positions (element loads), few positions: small tiles
 ])
 def test_conv_parity(dtype, N, C, Cout, H, W, k, stride, pad, rate):
     _conv_case(dtype, N, C, Cout, H, W, k, stride, pad, rate, seed=N * 1000 + C)
