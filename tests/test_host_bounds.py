@@ -91,7 +91,10 @@ def test_lstm_and_conv_shapes():
         for N, Cc, Cout, H, W, k, pad, nk in [(128, 256, 256, 28, 28, 3, 1, 128), (128, 256, 256, 28, 28, 3, 1, 256),
                                               (2, 8, 16, 7, 7, 3, 1, 4), (3, 12, 20, 9, 6, 3, 1, 8), (2, 16, 8, 8, 8, 1, 0, 12),
                                               (2, 6, 10, 11, 10, 5, 2, 3), (5, 24, 130, 10, 12, 3, 1, 6), (7, 70, 300, 13, 17, 3, 1, 65),
-                                              (3, 16, 24, 12, 12, 3, 0, 8), (2, 8, 8, 9, 7, 5, 1, 8)]:
+                                              (3, 16, 24, 12, 12, 3, 0, 8), (2, 8, 8, 9, 7, 5, 1, 8),
+                                              # few output positions: small tiles for many output channels
+                                              (128, 512, 512, 7, 7, 3, 1, 256), (128, 512, 512, 14, 14, 3, 1, 256),
+                                              (4, 64, 300, 7, 7, 3, 1, 64), (64, 128, 128, 56, 56, 3, 1, 64)]:
             modes = (1, 2, 3, 0x101, 0x202, 0x103) + ((0x303,) if k - 1 == 2 * pad else ())   # with and without shared grids
             _ok(lib, D.conv_calls(lib, heap, D.BF16, N, Cc, Cout, H, W, k, 1, pad, nk, modes=modes), f"conv {N} {Cc} {Cout} {H}x{W} k{k} keep {nk}")
         assert n_lstm >= 10 and D.last_bounds(lib)[0] >= 10 * 3
