@@ -560,8 +560,19 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
       kb_mode = true;
       const int* lst = P.kb_list + (long)(n0 / BN) * P.kb_stride;
       const int cnt = Kn >> 6, last = kax.nphys / 64 - 1;
-      kbl0 = lane < cnt ? imin(imax(lst[lane], 0), last) : 0;
-      kbl1 = 64 + lane < cnt ? imin(imax(lst[64 + lane], 0), last) : 0;
+      // (read whatever the count says, from inside the tile's own row of the list: the loads do not wait for it)
+      const int e0 = lst[imin(lane, P.kb_stride - 1)], e1 = lst[imin(64 + lane, P.kb_stride - 1)];
+      kbl0 = lane < cnt ? imin(imax(e0, 0), last) : 0;
+      kbl1 = 64 + lane < cnt ? imin(imax(e1, 0), last) : 0;
+    }
+  }
+  // the pixels this lane's columns are stored to, looked up before the contraction instead of after it
+  int out_pix[TN];
+  if constexpr (MODE == 1) {
+#pragma unroll
+    for (int in = 0; in < TN; ++in) {
+      const int jc = n0 + wn * WTN + in * 32 + (lane & 31);
+      out_pix[in] = jc < P.cv.npix ? (P.cv.pix ? P.cv.pix[jc] : jc) : -1;
     }
   }
   auto slab = [&](int s, int& ks, int& ksb) {
@@ -867,10 +878,8 @@ __device__ __forceinline__ void direct_body(const FastParams& P, const int block
     }
 #pragma unroll
     for (int in = 0; in < TN; ++in) {
-      const int jc = n0 + wn * WTN + in * 32 + (lane & 31);
-      if (jc >= cv.npix) continue;  // npix is even whenever pair_ok, so a pair is in or out together
-      const int j = cv.pix ? cv.pix[jc] : jc;
-      if (j < 0) continue;  // padding entry of a tile
+      const int j = out_pix[in];  // (columns beyond npix hold -1; npix is even whenever pair_ok: a pair is in or out together)
+      if (j < 0) continue;        // padding entry of a tile
       const int n = j / HW;
       uint16_t* col = P.C + (long)n * cv.out_chan * HW + (j - n * HW);
 #pragma unroll
