@@ -798,9 +798,17 @@ struct PackJob {
 __device__ __forceinline__ void pack_weights_body(const PackJob& j, long idx) {
   const long total = (long)j.rows * j.taps * j.Cp;
   if (idx >= total) return;
-  const int q = (int)(idx % j.Cp);
-  const int tap = (int)((idx / j.Cp) % j.taps);
-  const int r = (int)(idx / ((long)j.Cp * j.taps));
+  int q, tap, r;
+  if (total < (1L << 31)) {  // (32-bit divisions: a fraction of the instructions of 64-bit ones)
+    const uint32_t i32 = (uint32_t)idx, a = i32 / (uint32_t)j.Cp;
+    q = (int)(i32 - a * (uint32_t)j.Cp);
+    r = (int)(a / (uint32_t)j.taps);
+    tap = (int)(a - (uint32_t)r * (uint32_t)j.taps);
+  } else {
+    q = (int)(idx % j.Cp);
+    tap = (int)((idx / j.Cp) % j.taps);
+    r = (int)(idx / ((long)j.Cp * j.taps));
+  }
   uint16_t v = 0;
   if (q < j.inner)
     v = j.flip ? j.Wt[((long)q * j.C + (j.keep ? j.keep[r] : r)) * j.taps + (j.taps - 1 - tap)]
@@ -978,9 +986,10 @@ __global__ __launch_bounds__(256) void wgrad_grid_reduce_kernel(const float* par
   if ((int)blockIdx.x < sum_blocks) {
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long)Cout * taps * n_keep) return;
-    const int r = (int)(idx % n_keep);
-    const int tap = (int)((idx / n_keep) % taps);
-    const int co = (int)(idx / ((long)n_keep * taps));
+    // (the host refuses 2^31 kept synapses or more: 32-bit divisions, a fraction of the instructions of 64-bit ones)
+    const uint32_t i32 = (uint32_t)idx, q1 = i32 / (uint32_t)n_keep;
+    const int r = (int)(i32 - q1 * (uint32_t)n_keep);
+    const int co = (int)(q1 / (uint32_t)taps), tap = (int)(q1 - (uint32_t)co * (uint32_t)taps);
     const float* p = part + (long)co * Nn + tap * Cp + r;
     const long stride = (long)Cout * Nn;
     float s = 0.0f;
@@ -1356,6 +1365,7 @@ static int32_t conv_run_grid(const ConvArgs& a, const void* A, const void* Wt, c
   st = big ? launch_direct_kernel<false, false, 256, 128, 8, 2>(F, direct_plain_grid(F.total_tiles), stream)
            : launch_direct_kernel<false, false, 128, 128, 4, 2>(F, direct_plain_grid(F.total_tiles), stream);
   if (st) return st;
+  if ((long)a.Cout * taps * Ck >= (1L << 31)) return fail(ARD_ESHAPE, "weight gradient beyond 2^31 kept synapses");
   const int sum_blocks = (int)(((long)a.Cout * taps * Ck + 255) / 256);
   const int zero_blocks = Ck < a.C && !a.kept_only ? (int)(((long)a.Cout * a.C + 255) / 256) : 0;
   ARD_LAUNCH(wgrad_grid_reduce_kernel, dim3((unsigned)(sum_blocks + zero_blocks)), dim3(256), 0, stream, (const float*)w.gpart,
