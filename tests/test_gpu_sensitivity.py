@@ -131,6 +131,19 @@ def test_forward_over_the_kept_rows_degenerate():
     assert nk == 0
 
 
+@pytest.mark.parametrize("m,n_", [(0.05, 0.2), (0.6, 0.9), (1.0, 1.0)])
+def test_forward_over_the_kept_rows_both_ways_of_zeroing(m, n_):
+    """Planes of whole 16-byte pieces: with most rows kept the dropped positions are zeroed by masked stores, with
+    few kept the whole output is zeroed as one stream before the product writes the kept rows; nothing kept: zeros."""
+    nk, tot = _rows_forward_case("bf16", 5, 24, 130, 10, 12, 3, 1, 1, 8, m, n_, seed=int(m * 100) + 7)
+    if m == 1.0:
+        assert nk == 0
+    elif m < 0.1:
+        assert nk * 10 > tot * 7, (nk, tot)       # the masked stores
+    else:
+        assert 0 < nk and nk * 10 <= tot * 7, (nk, tot)   # the stream
+
+
 def test_config5_layer_under_the_row_pattern():
     """The config-5 layer (N=128, C=Cout=256, 28x28, 3x3) under the row-based sensitivity-aware pattern: bands
     of 8 output positions, k = 30 %, threshold 0.5, t = 50 %, possibilities 0.3 / 0.7."""
