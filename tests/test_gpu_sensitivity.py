@@ -283,6 +283,27 @@ def test_block_pattern_random_shapes(seed):
     assert torch.equal(Y2, Y) and torch.equal(dA2, dA) and torch.equal(dW2, dW)
 
 
+def test_forward_under_the_block_pattern_many_tiles():
+    """More pixel tiles than the plan ranks (over 2048: they stay in band order): 1100 images of two bands each,
+    checked against the oracle on sampled images (first, middle, last)."""
+    N, C, Cout, H, W, x, y = 1100, 128, 72, 12, 12, 72, 576
+    rng = np.random.default_rng(77)
+    Av = stored(np.maximum(rng.standard_normal((N, C, H, W)), 0), "bf16")
+    Wv = stored(rng.standard_normal((Cout, C, 3, 3)) * 0.2, "bf16")
+    Ad, Wd = from_vals(Av, "bf16"), from_vals(Wv, "bf16")
+    pred = ard.sens_predict(Ad, (3, 3), 1, 1, x, y, 300, 500, 0.5, 3, 2)
+    rows, RB, CB = ard.sens_regions(Av.shape, (3, 3), 1, 1, x, y)
+    assert N * RB > 2048
+    bp = ard.sens_block_pattern(pred, 1, 0.3, 0.7, 3, 2)
+    keep = bp["keep"].cpu().numpy().reshape(N, RB, CB)
+    assert 0.2 < keep.mean() < 0.8
+    Y = ard.conv_fwd_blocks(Ad, Wd, bp["keep"], x, y)
+    torch.cuda.synchronize()
+    idx = [0, 1, 2, 548, 549, 550, 551, 1097, 1098, 1099]
+    ref = S.conv_fwd_blocks(Av[idx], Wv, keep[idx], x, y)
+    assert_parity(Y[idx], ref, "bf16", None, "conv blocks Y, sampled images")
+
+
 def test_config5_layer_under_the_block_pattern():
     """The config-5 layer under the block-based pattern: 112-by-576 blocks of the 784 x 2304 input matrices (four
     rows of output positions by one 64-channel group over all taps: the forward pass skips the dropped blocks),
