@@ -853,8 +853,10 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
   __shared__ int red4[4];
   // (workgroups beyond the copy's own pack the weights of the product that follows and zero the planes it will
   // not write: independent small jobs that would otherwise be launches of their own)
-  if ((int)blockIdx.x >= main_x) {
-    const int b = ((int)blockIdx.x - main_x) * (int)gridDim.y + (int)blockIdx.y;
+  // (they come first in the launch: started last they would be a tail of their own behind the copy)
+  const int extra_x = (int)gridDim.x - main_x;
+  if ((int)blockIdx.x < extra_x) {
+    const int b = (int)blockIdx.x * (int)gridDim.y + (int)blockIdx.y;
     if (b < pj.blocks) pack_weights_body(pj, (long)b * 256 + threadIdx.x);
     else if (b < pj.blocks + zj.blocks) zero_dropped_planes_body(zj, b - pj.blocks);
     else if (b < pj.blocks + zj.blocks + zp.blocks) zero_dropped_pixels_body(zp, b - pj.blocks - zj.blocks);
@@ -866,8 +868,8 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
   // Channel rows start at any multiple of 2 * HW bytes, so a tile's 128-byte runs straddle cache lines that the
   // neighbouring pixel tile reads too.  Workgroups are dealt to the 8 XCDs in turn: XCD x takes the x-th eighth
   // of the tiles in order, so the second read of a line finds it in that XCD's L2 (half the fetched bytes).
-  const int even = main_x / 8;
-  const int m = (int)blockIdx.x < 8 * even ? ((int)blockIdx.x & 7) * even + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+  const int even = main_x / 8, bx = (int)blockIdx.x - extra_x;
+  const int m = bx < 8 * even ? (bx & 7) * even + (bx >> 3) : bx;
   const int n = m / px_tiles, tile_j = m - n * px_tiles, p0 = tile_j * 64;
   const int c0 = blockIdx.y * 64;
   const int t = threadIdx.x;
@@ -934,7 +936,7 @@ __global__ __launch_bounds__(256) void to_grid_src_kernel(const uint16_t* src, c
     *reinterpret_cast<uint4*>(dst + ((long)n * Hg * Wg + pos) * Cp + c0 + (t & 7) * 8) = zero;
   }
   // the margin behind the last image, 32 pixels per workgroup
-  for (long g = (long)N * Hg * Wg + (long)blockIdx.x * 32 + (t >> 3); g < n_pix_total; g += (long)main_x * 32)
+  for (long g = (long)N * Hg * Wg + (long)bx * 32 + (t >> 3); g < n_pix_total; g += (long)main_x * 32)
     *reinterpret_cast<uint4*>(dst + g * Cp + c0 + (t & 7) * 8) = zero;
 }
 
