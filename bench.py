@@ -43,9 +43,9 @@ REPEATS = 5              # the block of `steps` timed iterations is repeated; me
 # kernel of the call (the product alone or grouped with the pass that zeroes dropped rows, the finishing pass
 # where the pattern needs one), as its time is; the other two: the product kernel, per launch.
 TRAFFIC = {
-    "L2.bwd_weight": (20423392, "profiles/hbm_traffic_L2_bwd_weight.txt"),
-    "C3.fwd.dp2": (151194610, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
-    "C5.fwd": (90899325, "profiles/hbm_traffic_config5_conv_fwd.txt"),
+    "L2.bwd_weight": (20423402, "profiles/hbm_traffic_L2_bwd_weight.txt"),
+    "C3.fwd.dp2": (151189085, "profiles/hbm_traffic_config3_fwd_dp2.txt"),
+    "C5.fwd": (90894338, "profiles/hbm_traffic_config5_conv_fwd.txt"),
 }
 
 

@@ -294,6 +294,8 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     need = 0;
   }
   bool self_batch = false;
+  ZeroRowsArgs zero_args{};
+  long zero_gx = 0;
   FastParams F{};
   F.A = (const uint16_t*)P.A.p;
   F.B = (const uint16_t*)P.B.p;
@@ -332,17 +334,11 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
       // is not part of a caller's batch makes one of its own for the two)
       F.scatter_rows_only = 1;
       self_batch = batch_self_begin();
-      const ZeroRowsArgs za{(uint16_t*)C.p, (int)C.ld, C.rm.nphys, C.cn.nphys, C.rm.off, C.rm.step, C.rm.n, F.scatter_vec};
+      zero_args = ZeroRowsArgs{(uint16_t*)C.p, (int)C.ld, C.rm.nphys, C.cn.nphys, C.rm.off, C.rm.step, C.rm.n, F.scatter_vec};
       const long pieces = (long)dropped_rows * (F.scatter_vec ? C.cn.nphys / 8 : C.cn.nphys);
-      long gx = (pieces + 1023) / 1024;  // four stores per thread
-      gx = gx < 1 ? 1 : (gx > 2048 ? 2048 : gx);
-      if (!batch_push_zero_rows(za, (int)gx)) ARD_LAUNCH(zero_rows_kernel, dim3((unsigned)gx), dim3(256), 0, stream, za);
-      hipError_t e = ard::launch_status();
-      if (e != hipSuccess) {
-        st = fail(ARD_EHIP, "launch of zero_rows_kernel failed: %s", hipGetErrorString(e));
-        if (self_batch) batch_self_end(false, stream);
-        return true;
-      }
+      zero_gx = (pieces + 1023) / 1024;  // four stores per thread
+      zero_gx = zero_gx < 1 ? 1 : (zero_gx > 2048 ? 2048 : zero_gx);
+      // (recorded behind the product: the product's workgroups have the longer way to go and start first)
     }
   }
   const long total = C.fill ? (long)C.rm.nphys * C.cn.nphys : (long)P.M * P.N;
@@ -356,6 +352,11 @@ static bool try_direct(int32_t dtype, bool a_kc, bool b_kc, const GemmParams& P,
     st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
   } else {
     st = launch_direct(a_kc, b_kc, F, bm, bn, stream);
+  }
+  if (zero_gx && st == ARD_OK) {
+    if (!batch_push_zero_rows(zero_args, (int)zero_gx)) ARD_LAUNCH(zero_rows_kernel, dim3((unsigned)zero_gx), dim3(256), 0, stream, zero_args);
+    const hipError_t e = ard::launch_status();
+    if (e != hipSuccess) st = fail(ARD_EHIP, "launch of zero_rows_kernel failed: %s", hipGetErrorString(e));
   }
   if (self_batch) {
     const int32_t bst = batch_self_end(st == ARD_OK, stream);
